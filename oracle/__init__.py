@@ -1,0 +1,181 @@
+"""CPU oracle for batched pipeline-schedule evaluation -- TEST INFRASTRUCTURE ONLY.
+
+Thin ctypes wrapper over ``fporacle.c`` (plain C, int64 times, single-threaded
+event loop).  Only ``tests/``, ``__graft_entry__.smoke()`` and the
+``cpu_baseline`` leg of ``bench.py`` may import this package; the product
+package never does, and this package never imports the product package.
+
+A *problem* is any object with the attributes ``n_devices, n_stages,
+n_microbatches, has_w`` (ints) and ``stage_device[S], edge_src[E], edge_dst[E],
+edge_comm[E], dur[8][S], mem_units[S], mem_cap[D]`` (array-likes of ints).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "fporacle.c")
+_LIB = os.path.join(_HERE, "libfporacle.so")
+
+FLAG_DEADLOCK = 1
+FLAG_INCOMPLETE = 2
+FLAG_OVER_CAP = 4
+INT64_MAX = np.iinfo(np.int64).max
+NKINDS = 8
+
+
+def build(force: bool = False) -> str:
+    """Compile fporacle.c with gcc (plain C, no GPU toolchain)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-o", tmp, _SRC])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+class _CProblem(ctypes.Structure):
+    _fields_ = [
+        ("n_devices", ctypes.c_int32),
+        ("n_stages", ctypes.c_int32),
+        ("n_microbatches", ctypes.c_int32),
+        ("has_w", ctypes.c_int32),
+        ("stage_device", ctypes.c_void_p),
+        ("n_edges", ctypes.c_int32),
+        ("edge_src", ctypes.c_void_p),
+        ("edge_dst", ctypes.c_void_p),
+        ("edge_comm", ctypes.c_void_p),
+        ("dur", ctypes.c_void_p),
+        ("mem_units", ctypes.c_void_p),
+        ("mem_cap", ctypes.c_void_p),
+    ]
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        _lib = ctypes.CDLL(build())
+        _lib.fporacle_eval_one.restype = ctypes.c_int
+        _lib.fporacle_evaluate.restype = ctypes.c_int
+        _lib.fporacle_topk.restype = ctypes.c_int
+    return _lib
+
+
+def _i32(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+
+
+class _Marshalled:
+    """Keeps the int32 arrays alive next to the C struct that points at them."""
+
+    def __init__(self, problem):
+        self.D = int(problem.n_devices)
+        self.S = int(problem.n_stages)
+        self.m = int(problem.n_microbatches)
+        self.arrays = dict(
+            stage_device=_i32(problem.stage_device), edge_src=_i32(problem.edge_src),
+            edge_dst=_i32(problem.edge_dst), edge_comm=_i32(problem.edge_comm),
+            dur=_i32(problem.dur).reshape(NKINDS, self.S), mem_units=_i32(problem.mem_units),
+            mem_cap=_i32(problem.mem_cap))
+        a = self.arrays
+        assert a["stage_device"].shape == (self.S,) and a["mem_cap"].shape == (self.D,)
+        self.c = _CProblem(self.D, self.S, self.m, int(problem.has_w),
+                           a["stage_device"].ctypes.data, len(a["edge_src"]),
+                           a["edge_src"].ctypes.data, a["edge_dst"].ctypes.data,
+                           a["edge_comm"].ctypes.data, a["dur"].ctypes.data,
+                           a["mem_units"].ctypes.data, a["mem_cap"].ctypes.data)
+
+
+def decode(words):
+    """(kind, chunk, micro-batch) of each op word."""
+    w = np.ascontiguousarray(np.asarray(words, dtype=np.uint16))
+    k = np.empty(w.shape, np.int32)
+    c = np.empty(w.shape, np.int32)
+    j = np.empty(w.shape, np.int32)
+    _load().fporacle_decode(ctypes.c_void_p(w.ctypes.data), ctypes.c_int64(w.size),
+                            ctypes.c_void_p(k.ctypes.data), ctypes.c_void_p(c.ctypes.data),
+                            ctypes.c_void_p(j.ctypes.data))
+    return k, c, j
+
+
+def evaluate(problem, words, threads: int = 1):
+    """Evaluate a batch ``words[C][D][stride]`` (uint16).
+
+    Returns dict(makespan int64[C], idle int64[C][D], peak int32[C][D],
+    flags uint8[C]).  ``threads`` > 1 only splits the batch over host threads;
+    every candidate is still evaluated by the same single-threaded C routine.
+    """
+    lib = _load()
+    mp = _Marshalled(problem)
+    w = np.ascontiguousarray(np.asarray(words, dtype=np.uint16))
+    assert w.ndim == 3 and w.shape[1] == mp.D, w.shape
+    C, _, stride = w.shape
+    out = dict(makespan=np.empty(C, np.int64), idle=np.empty((C, mp.D), np.int64),
+               peak=np.empty((C, mp.D), np.int32), flags=np.empty(C, np.uint8))
+
+    def run(lo, hi):
+        if hi <= lo:
+            return 0
+        return lib.fporacle_evaluate(
+            ctypes.byref(mp.c), ctypes.c_void_p(w[lo:hi].ctypes.data), ctypes.c_int64(hi - lo),
+            ctypes.c_int32(stride), ctypes.c_void_p(out["makespan"][lo:hi].ctypes.data),
+            ctypes.c_void_p(out["idle"][lo:hi].ctypes.data),
+            ctypes.c_void_p(out["peak"][lo:hi].ctypes.data),
+            ctypes.c_void_p(out["flags"][lo:hi].ctypes.data))
+
+    threads = max(1, min(int(threads), C if C else 1))
+    if threads == 1:
+        rcs = [run(0, C)]
+    else:
+        # many small slices so that uneven candidates balance over the threads
+        n_slices = min(C, threads * 8)
+        bounds = np.linspace(0, C, n_slices + 1).astype(np.int64)
+        with ThreadPoolExecutor(threads) as ex:
+            rcs = list(ex.map(lambda i: run(int(bounds[i]), int(bounds[i + 1])), range(n_slices)))
+    if any(rcs):
+        raise ValueError("fporacle: invalid problem description")
+    return out
+
+
+def evaluate_trace(problem, words_one):
+    """One candidate ``words[D][stride]``; also returns every op's start/finish."""
+    lib = _load()
+    mp = _Marshalled(problem)
+    w = np.ascontiguousarray(np.asarray(words_one, dtype=np.uint16))
+    assert w.ndim == 2 and w.shape[0] == mp.D
+    stride = w.shape[1]
+    ms = np.empty(1, np.int64)
+    idle = np.empty(mp.D, np.int64)
+    peak = np.empty(mp.D, np.int32)
+    fl = np.empty(1, np.uint8)
+    st = np.empty((mp.D, stride), np.int64)
+    fi = np.empty((mp.D, stride), np.int64)
+    rc = lib.fporacle_eval_one(ctypes.byref(mp.c), ctypes.c_void_p(w.ctypes.data),
+                               ctypes.c_int32(stride), ctypes.c_void_p(ms.ctypes.data),
+                               ctypes.c_void_p(idle.ctypes.data), ctypes.c_void_p(peak.ctypes.data),
+                               ctypes.c_void_p(fl.ctypes.data), ctypes.c_void_p(st.ctypes.data),
+                               ctypes.c_void_p(fi.ctypes.data))
+    if rc:
+        raise ValueError("fporacle: invalid problem description")
+    return dict(makespan=int(ms[0]), idle=idle, peak=peak, flags=int(fl[0]), start=st, finish=fi)
+
+
+def topk(makespan, flags, k: int):
+    """k best feasible candidates by (makespan, index).  Returns (idx[k], makespan[k], count)."""
+    lib = _load()
+    ms = np.ascontiguousarray(np.asarray(makespan, dtype=np.int64))
+    fl = np.ascontiguousarray(np.asarray(flags, dtype=np.uint8))
+    idx = np.empty(k, np.int64)
+    oms = np.empty(k, np.int64)
+    cnt = np.zeros(1, np.int32)
+    lib.fporacle_topk(ctypes.c_void_p(ms.ctypes.data), ctypes.c_void_p(fl.ctypes.data),
+                      ctypes.c_int64(ms.size), ctypes.c_int32(k), ctypes.c_void_p(idx.ctypes.data),
+                      ctypes.c_void_p(oms.ctypes.data), ctypes.c_void_p(cnt.ctypes.data))
+    return idx, oms, int(cnt[0])

@@ -1,0 +1,275 @@
+/*
+ * fporacle.c -- CPU oracle for batched pipeline-schedule evaluation.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the plain, slow, single-threaded
+ * definition that the GPU library is checked against.  Nothing in the product
+ * path may call it; it shares no code, header, table or helper with the HIP
+ * sources.  Times are int64 throughout.
+ *
+ * What is evaluated (paper, Section 3 "Overview", the auto-tuner paragraph:
+ * the offline tuner picks the most suitable schedule out of the enumerated
+ * ones; Section 7.1: it returns the alternatives with the least bubble ratio;
+ * the estimator sketch that follows Section 6: a schedule becomes an
+ * execution graph of tasks labelled with start time, end time and cost):
+ *
+ *   A schedule is, per device ("actor"), a sequence of instructions (Section 4,
+ *   "FlexPipe's Instructions"); an instruction item is (type, micro-batch,
+ *   stage) (Section 5.1, "Instruction Item").  Forward items depend on the
+ *   forward items of the predecessor stages in the stage DAG, backward items
+ *   on the backward items of the successor stages (Section 5.1, "Data
+ *   dependency").  Each device executes its list strictly in order, one item
+ *   at a time.  An item starts as soon as its device is free and all its
+ *   dependencies have finished (plus the edge's communication latency when
+ *   the two stages sit on different devices) and runs for the profiled cost
+ *   of its (type, stage).
+ *
+ * Readings of points the paper leaves open (each is repeated in the design doc):
+ *   - evaluation is time-based on integer times; all devices are free at 0;
+ *   - communication is a pure latency on cross-device DAG edges, the same
+ *     value for activations and gradients;
+ *   - same-device ordering rules are a per-(stage, micro-batch) activation
+ *     state machine:  ABSENT -F-> RES,  ABSENT -FD-> DISC,  DISC -R-> RES,
+ *     RES -O-> OFF,  OFF -L-> RES,  RES -B-> BDONE,  BDONE -W-> DONE;
+ *     an item whose (stage, micro-batch) is not in the required source state
+ *     cannot issue (and, its device being stuck behind it, never will);
+ *   - activation memory: +units at the START of F, FD, R, L; -units at the END
+ *     of FD and O; -units at the end of W (split backward) or of B (has_w=0);
+ *   - idle[d] = makespan - (sum of durations of the items on d): head, middle
+ *     and tail waiting all count (Section 2, bubbles = device idle time;
+ *     Section 7.1 breakdown, device waiting time);
+ *   - ranking key is (makespan ascending, candidate index ascending): total
+ *     work is fixed per problem, so least bubble ratio == least makespan.
+ *
+ * Parity pins (tests/, -m "not gpu"): GPipe and 1F1B closed forms, an
+ * independent longest-path + Kahn checker, brute force over all order pairs
+ * for p=2, m<=3, order-only memory scan, monotonicity, and the input
+ * generator's own list-scheduling clock.  Parity UNPINNED by the paper: the
+ * R / O / L / FD semantics and the sentinel values (the paper names neither);
+ * they are pinned only by the independent checker and the invariants.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { K_END = 0, K_F = 1, K_B = 2, K_W = 3, K_R = 4, K_O = 5, K_L = 6, K_FD = 7, NKINDS = 8 };
+enum { ST_ABSENT = 0, ST_RES = 1, ST_DISC = 2, ST_OFF = 3, ST_BDONE = 4, ST_DONE = 5 };
+enum { FLAG_DEADLOCK = 1, FLAG_INCOMPLETE = 2, FLAG_OVER_CAP = 4 };
+#define MAX_CHUNKS 4
+
+typedef struct {
+  int32_t n_devices;       /* D */
+  int32_t n_stages;        /* S */
+  int32_t n_microbatches;  /* m */
+  int32_t has_w;           /* 1: B then W, W frees; 0: B frees, W illegal */
+  const int32_t *stage_device; /* [S] */
+  int32_t n_edges;
+  const int32_t *edge_src;  /* [E] */
+  const int32_t *edge_dst;  /* [E] */
+  const int32_t *edge_comm; /* [E] */
+  const int32_t *dur;       /* [NKINDS][S] */
+  const int32_t *mem_units; /* [S] */
+  const int32_t *mem_cap;   /* [D] */
+} fporacle_problem;
+
+/* Word layout (unsigned 16 bit): kind in bits 15..13, the device-local chunk
+ * in bits 12..11, the micro-batch in bits 10..0.  The all-zero kind ends a
+ * device's list. */
+static int word_kind(uint16_t w) { return w >> 13; }
+static int word_chunk(uint16_t w) { return (w >> 11) & 3; }
+static int word_mb(uint16_t w) { return w & 0x7ff; }
+
+void fporacle_decode(const uint16_t *words, int64_t n, int32_t *kind, int32_t *chunk, int32_t *mb) {
+  for (int64_t i = 0; i < n; ++i) {
+    kind[i] = word_kind(words[i]);
+    chunk[i] = word_chunk(words[i]);
+    mb[i] = word_mb(words[i]);
+  }
+}
+
+/* chunk c of device d = the c-th of d's stages in ascending stage id. */
+static int build_local_stage(const fporacle_problem *P, int32_t *local_stage, int32_t *n_chunks) {
+  for (int d = 0; d < P->n_devices; ++d) n_chunks[d] = 0;
+  for (int s = 0; s < P->n_stages; ++s) {
+    int d = P->stage_device[s];
+    if (d < 0 || d >= P->n_devices) return -1;
+    if (n_chunks[d] >= MAX_CHUNKS) return -1;
+    local_stage[d * MAX_CHUNKS + n_chunks[d]++] = s;
+  }
+  return 0;
+}
+
+/*
+ * Evaluate one candidate.  words: [D][stride].  Outputs: makespan, idle[D],
+ * peak[D], flags; optional per-op traces op_start/op_finish [D][stride]
+ * (-1 where the op never issued or past the end of the list).
+ * Returns 0, or -1 for an invalid problem.
+ */
+int fporacle_eval_one(const fporacle_problem *P, const uint16_t *words, int32_t stride,
+                      int64_t *makespan, int64_t *idle, int32_t *peak, uint8_t *flags,
+                      int64_t *op_start, int64_t *op_finish) {
+  const int D = P->n_devices, S = P->n_stages, m = P->n_microbatches;
+  int32_t *local_stage = malloc(sizeof(int32_t) * D * MAX_CHUNKS);
+  int32_t *n_chunks = malloc(sizeof(int32_t) * D);
+  if (build_local_stage(P, local_stage, n_chunks)) { free(local_stage); free(n_chunks); return -1; }
+
+  int64_t *fin_fwd = malloc(sizeof(int64_t) * S * m);   /* finish of F/FD(s,j), -1 = not yet */
+  int64_t *fin_bwd = malloc(sizeof(int64_t) * S * m);   /* finish of B(s,j) */
+  uint8_t *state = calloc((size_t)S * m, 1);
+  int32_t *cursor = calloc(D, sizeof(int32_t));
+  int32_t *len = calloc(D, sizeof(int32_t));
+  int64_t *free_at = calloc(D, sizeof(int64_t));
+  int64_t *busy = calloc(D, sizeof(int64_t));
+  int64_t *mem = calloc(D, sizeof(int64_t));
+  int64_t *pk = calloc(D, sizeof(int64_t));
+  for (int i = 0; i < S * m; ++i) fin_fwd[i] = fin_bwd[i] = -1;
+  for (int d = 0; d < D; ++d) {
+    int n = 0;
+    while (n < stride && word_kind(words[(size_t)d * stride + n]) != K_END) ++n;
+    len[d] = n;
+  }
+  if (op_start) for (int64_t i = 0; i < (int64_t)D * stride; ++i) op_start[i] = op_finish[i] = -1;
+
+  int malformed_head = 0;
+  for (;;) {
+    int issued_any = 0;
+    malformed_head = 0;
+    for (int d = 0; d < D; ++d) {
+      if (cursor[d] >= len[d]) continue;
+      const uint16_t w = words[(size_t)d * stride + cursor[d]];
+      const int kind = word_kind(w), c = word_chunk(w), j = word_mb(w);
+      if (c >= n_chunks[d] || j >= m || (kind == K_W && !P->has_w)) { malformed_head = 1; continue; }
+      const int s = local_stage[d * MAX_CHUNKS + c];
+      uint8_t *st = &state[(size_t)s * m + j];
+
+      /* same-device rule: required source state */
+      int need;
+      switch (kind) {
+        case K_F: case K_FD: need = ST_ABSENT; break;
+        case K_R: need = ST_DISC; break;
+        case K_O: need = ST_RES; break;
+        case K_L: need = ST_OFF; break;
+        case K_B: need = ST_RES; break;
+        default:  need = ST_BDONE; break; /* K_W */
+      }
+      if (*st != need) continue;
+
+      /* cross-stage rule */
+      int64_t ready = 0;
+      int blocked = 0;
+      if (kind == K_F || kind == K_FD) {
+        for (int e = 0; e < P->n_edges && !blocked; ++e) {
+          if (P->edge_dst[e] != s) continue;
+          const int sp = P->edge_src[e];
+          const int64_t t = fin_fwd[(size_t)sp * m + j];
+          if (t < 0) { blocked = 1; break; }
+          const int64_t r = t + (P->stage_device[sp] != d ? P->edge_comm[e] : 0);
+          if (r > ready) ready = r;
+        }
+      } else if (kind == K_B) {
+        for (int e = 0; e < P->n_edges && !blocked; ++e) {
+          if (P->edge_src[e] != s) continue;
+          const int sn = P->edge_dst[e];
+          const int64_t t = fin_bwd[(size_t)sn * m + j];
+          if (t < 0) { blocked = 1; break; }
+          const int64_t r = t + (P->stage_device[sn] != d ? P->edge_comm[e] : 0);
+          if (r > ready) ready = r;
+        }
+      }
+      if (blocked) continue;
+
+      /* issue */
+      const int64_t dt = P->dur[kind * S + s];
+      const int64_t u = P->mem_units[s];
+      const int64_t start = free_at[d] > ready ? free_at[d] : ready;
+      const int64_t finish = start + dt;
+      if (kind == K_F || kind == K_FD || kind == K_R || kind == K_L) {
+        mem[d] += u;
+        if (mem[d] > pk[d]) pk[d] = mem[d];
+      }
+      if (kind == K_FD || kind == K_O) mem[d] -= u;
+      if (kind == K_W || (kind == K_B && !P->has_w)) mem[d] -= u;
+      switch (kind) {
+        case K_F:  *st = ST_RES;  fin_fwd[(size_t)s * m + j] = finish; break;
+        case K_FD: *st = ST_DISC; fin_fwd[(size_t)s * m + j] = finish; break;
+        case K_R:  *st = ST_RES; break;
+        case K_O:  *st = ST_OFF; break;
+        case K_L:  *st = ST_RES; break;
+        case K_B:  *st = ST_BDONE; fin_bwd[(size_t)s * m + j] = finish; break;
+        default:   *st = ST_DONE; break;
+      }
+      if (op_start) {
+        op_start[(size_t)d * stride + cursor[d]] = start;
+        op_finish[(size_t)d * stride + cursor[d]] = finish;
+      }
+      free_at[d] = finish;
+      busy[d] += dt;
+      cursor[d] += 1;
+      issued_any = 1;
+    }
+    if (!issued_any) break;
+  }
+
+  uint8_t fl = 0;
+  for (int d = 0; d < D; ++d) if (cursor[d] < len[d]) fl |= FLAG_DEADLOCK;
+  if (fl && malformed_head) fl |= FLAG_INCOMPLETE;
+  if (!fl) {
+    const int terminal = P->has_w ? ST_DONE : ST_BDONE;
+    for (int i = 0; i < S * m; ++i) if (state[i] != terminal) { fl |= FLAG_INCOMPLETE; break; }
+  }
+  if (fl) {
+    *makespan = INT64_MAX;
+    for (int d = 0; d < D; ++d) { idle[d] = -1; peak[d] = -1; }
+  } else {
+    int64_t ms = 0;
+    for (int d = 0; d < D; ++d) if (free_at[d] > ms) ms = free_at[d];
+    *makespan = ms;
+    for (int d = 0; d < D; ++d) {
+      idle[d] = ms - busy[d];
+      peak[d] = (int32_t)pk[d];
+      if (pk[d] > P->mem_cap[d]) fl |= FLAG_OVER_CAP;
+    }
+  }
+  *flags = fl;
+
+  free(local_stage); free(n_chunks); free(fin_fwd); free(fin_bwd); free(state);
+  free(cursor); free(len); free(free_at); free(busy); free(mem); free(pk);
+  return 0;
+}
+
+/* Evaluate candidates [0, n_cand) of a batch laid out [C][D][stride]. */
+int fporacle_evaluate(const fporacle_problem *P, const uint16_t *words, int64_t n_cand, int32_t stride,
+                      int64_t *makespan, int64_t *idle, int32_t *peak, uint8_t *flags) {
+  const int D = P->n_devices;
+  for (int64_t c = 0; c < n_cand; ++c) {
+    int rc = fporacle_eval_one(P, words + (size_t)c * D * stride, stride, &makespan[c],
+                               &idle[c * D], &peak[c * D], &flags[c], NULL, NULL);
+    if (rc) return rc;
+  }
+  return 0;
+}
+
+typedef struct { int64_t makespan, idx; } rank_key;
+static int rank_cmp(const void *a, const void *b) {
+  const rank_key *x = a, *y = b;
+  if (x->makespan != y->makespan) return x->makespan < y->makespan ? -1 : 1;
+  if (x->idx != y->idx) return x->idx < y->idx ? -1 : 1;
+  return 0;
+}
+
+/* Top-k: feasible = flags == 0; ascending (makespan, index); unused slots get
+ * idx -1 and makespan INT64_MAX; *count = min(k, #feasible). */
+int fporacle_topk(const int64_t *makespan, const uint8_t *flags, int64_t n_cand, int32_t k,
+                  int64_t *out_idx, int64_t *out_makespan, int32_t *count) {
+  rank_key *keys = malloc(sizeof(rank_key) * (n_cand > 0 ? n_cand : 1));
+  int64_t n = 0;
+  for (int64_t c = 0; c < n_cand; ++c)
+    if (flags[c] == 0) { keys[n].makespan = makespan[c]; keys[n].idx = c; ++n; }
+  qsort(keys, n, sizeof(rank_key), rank_cmp);
+  for (int32_t i = 0; i < k; ++i) {
+    if (i < n) { out_idx[i] = keys[i].idx; out_makespan[i] = keys[i].makespan; }
+    else { out_idx[i] = -1; out_makespan[i] = INT64_MAX; }
+  }
+  *count = (int32_t)(n < k ? n : k);
+  free(keys);
+  return 0;
+}

@@ -1,0 +1,86 @@
+"""Small pure-Python input builders for the CPU tests (no timing arithmetic)."""
+from __future__ import annotations
+
+import numpy as np
+
+from workloads.problem import B, F, FD, L, O, R, W, make_problem, pack_lists
+
+
+def two_tower_problem(m=4, has_w=1, comm=1, mem_cap=None):
+    """Tiny non-chain DAG: stages 0->1 and 2->3 merge into 4->5; one stage per device."""
+    edges = [(0, 1, comm), (1, 4, comm), (2, 3, comm), (3, 4, comm), (4, 5, comm)]
+    dur = {F: [3, 3, 2, 2, 4, 4], B: [6, 6, 4, 4, 8, 8], W: [3, 3, 2, 2, 4, 4],
+           FD: [3, 3, 2, 2, 4, 4], R: [3, 3, 2, 2, 4, 4], O: 5, L: 5}
+    if not has_w:
+        dur.pop(W)
+    return make_problem(6, 6, m, has_w, list(range(6)), edges, dur, mem_cap=mem_cap,
+                        name="two_tower_tiny")
+
+
+def random_valid_lists(problem, rng, p_recompute=0.0, p_offload=0.0):
+    """A random deadlock-free candidate: repeatedly append, to its device's list,
+    one op drawn uniformly from the ops whose prerequisites are already listed."""
+    S, m = problem.n_stages, problem.n_microbatches
+    dev = [int(x) for x in problem.stage_device]
+    chunk = [int(x) for x in problem.stage_chunk()]
+    preds = {s: [] for s in range(S)}
+    succs = {s: [] for s in range(S)}
+    for a, b in zip(problem.edge_src, problem.edge_dst):
+        preds[int(b)].append(int(a))
+        succs[int(a)].append(int(b))
+    recompute = rng.random((S, m)) < p_recompute
+    offload = rng.random((S, m)) < p_offload
+    # per (s, j): the remaining chain of kinds it still has to go through
+    chains = {}
+    for s in range(S):
+        for j in range(m):
+            ch = [FD, R] if recompute[s, j] else [F]
+            if offload[s, j]:
+                ch += [O, L]
+            ch.append(B)
+            if problem.has_w:
+                ch.append(W)
+            chains[(s, j)] = ch
+    fwd_done = np.zeros((S, m), bool)
+    bwd_done = np.zeros((S, m), bool)
+    lists = [[] for _ in range(problem.n_devices)]
+    remaining = sum(len(c) for c in chains.values())
+    while remaining:
+        ready = []
+        for (s, j), ch in chains.items():
+            if not ch:
+                continue
+            k = ch[0]
+            if k in (F, FD) and not all(fwd_done[sp, j] for sp in preds[s]):
+                continue
+            if k == B and not all(bwd_done[sn, j] for sn in succs[s]):
+                continue
+            ready.append((s, j))
+        s, j = ready[rng.integers(len(ready))]
+        k = chains[(s, j)].pop(0)
+        if k in (F, FD):
+            fwd_done[s, j] = True
+        if k == B:
+            bwd_done[s, j] = True
+        lists[dev[s]].append((k, chunk[s], j))
+        remaining -= 1
+    return lists
+
+
+def perturb(lists, rng, n_swaps=1):
+    """Swap random positions inside random device lists (may or may not deadlock)."""
+    out = [list(x) for x in lists]
+    for _ in range(n_swaps):
+        d = int(rng.integers(len(out)))
+        if len(out[d]) < 2:
+            continue
+        a, b = rng.integers(len(out[d]), size=2)
+        out[d][a], out[d][b] = out[d][b], out[d][a]
+    return out
+
+
+def batch_from_lists(list_of_lists, stride=None):
+    longest = max(len(x) for lists in list_of_lists for x in lists)
+    if stride is None:
+        stride = max(8, -(-(longest + 1) // 8) * 8)
+    return np.stack([pack_lists(lists, stride) for lists in list_of_lists])
