@@ -1,0 +1,161 @@
+/*
+ * fpsched.h -- C ABI of the MI355X (gfx950) batched pipeline-schedule evaluator.
+ *
+ * The library scores candidate pipeline-parallel schedules the way the paper's
+ * auto-tuner needs them scored (Section 3: the offline tuner picks the most
+ * suitable of the enumerated schedules; Section 7.1: it returns the alternatives
+ * with the least bubble ratio): for every candidate it propagates dependencies
+ * to get each op's start and finish time, then reports makespan, per-device
+ * idle (bubble) time, per-device peak activation memory and a deadlock flag,
+ * and reduces a batch to its k best candidates under the memory cap.
+ *
+ * All entry points are plain C, take plain pointers (marked HOST or DEVICE) and
+ * sizes, return 0 on success or a negative FPSCHED_E* code, and never throw or
+ * abort.  A problem with an individual candidate (deadlock, malformed words) is
+ * never a call error: it is reported in that candidate's flags.
+ */
+#ifndef FPSCHED_H
+#define FPSCHED_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FPSCHED_VERSION 100
+
+/* ---- op words ------------------------------------------------------------
+ * A schedule is, per device, a sequence of instructions (Section 4, "FlexPipe's
+ * Instructions"); an instruction item is (type, micro-batch, stage) (Section
+ * 5.1, "Instruction Item").  One item = one unsigned 16-bit word:
+ *     bits 15..13  kind        bits 12..11  device-local chunk      bits 10..0  micro-batch
+ * The stage is the chunk-th stage (ascending stage id) placed on the device
+ * whose row the word sits in.  Kinds F/B/W are the paper's FwdPass, BwdPass (or
+ * CompInputGrad when the backward is split) and CompWeightGrad (Table 1); R, O,
+ * L and FD model recomputation and offloading, which the paper only names.
+ * Kind 0 ends a device's list: the row is read up to its first END word (or
+ * the row stride); anything after it is ignored. */
+enum {
+  FPSCHED_END = 0, /* end of list / padding                                       */
+  FPSCHED_F = 1,   /* forward; activation stays resident                          */
+  FPSCHED_B = 2,   /* backward (input gradient when has_w); frees iff !has_w      */
+  FPSCHED_W = 3,   /* weight gradient; frees the activation (has_w only)          */
+  FPSCHED_R = 4,   /* recompute a discarded activation                            */
+  FPSCHED_O = 5,   /* offload a resident activation (freed at the op's end)       */
+  FPSCHED_L = 6,   /* reload an offloaded activation                              */
+  FPSCHED_FD = 7,  /* forward whose activation is discarded at the op's end       */
+  FPSCHED_NKINDS = 8
+};
+#define FPSCHED_WORD(kind, chunk, mb) ((uint16_t)(((kind) << 13) | ((chunk) << 11) | (mb)))
+#define FPSCHED_MAX_DEVICES 64
+#define FPSCHED_MAX_CHUNKS 4
+#define FPSCHED_MAX_MICROBATCHES 2048
+
+/* ---- per-candidate flags --------------------------------------------------- */
+#define FPSCHED_FLAG_DEADLOCK 1u   /* some listed op can never issue                          */
+#define FPSCHED_FLAG_INCOMPLETE 2u /* all ops issued but some (stage, micro-batch) did not
+                                      finish its backward; or, together with DEADLOCK, a
+                                      device is stuck at a malformed word                     */
+#define FPSCHED_FLAG_OVER_CAP 4u   /* evaluated fine, but peak[d] > mem_cap[d] for some d     */
+/* Candidates with DEADLOCK or INCOMPLETE get makespan = INT64_MAX, idle = -1, peak = -1. */
+
+/* ---- error codes ----------------------------------------------------------- */
+#define FPSCHED_OK 0
+#define FPSCHED_EINVAL (-1)    /* bad argument (null pointer, size out of range, bad table) */
+#define FPSCHED_ENOMEM (-2)    /* host or device allocation failed / workspace too small    */
+#define FPSCHED_EHIP (-3)      /* a HIP runtime call failed                                 */
+#define FPSCHED_EOVERFLOW (-4) /* the problem's time bound does not fit the kernel's int32  */
+#define FPSCHED_ENODEV (-5)    /* host-only handle used for a device call                   */
+#define FPSCHED_EUNSUPPORTED (-6) /* problem too large for the on-chip tables               */
+
+/* ---- problem description (Section 4.1 data model: Stage / StageSet = the DAG
+ * of stages, Actor = device; placement per Section 2.1; costs per (kind, stage)
+ * as the profiler of Section 3 delivers them; in-flight memory limit per
+ * Section 4.2).  All pointers are HOST memory, read during the call only. */
+typedef struct {
+  int32_t n_devices;       /* D, 1..64                                                   */
+  int32_t n_stages;        /* S, 1..4*D                                                  */
+  int32_t n_microbatches;  /* m, 1..2048                                                 */
+  int32_t has_w;           /* 0: B is the whole backward and frees; 1: B then W, W frees */
+  const int32_t *stage_device; /* [S] device of each stage; at most 4 stages per device  */
+  int32_t n_edges;             /* edges of the stage DAG (a chain has S-1)               */
+  const int32_t *edge_src;     /* [E]                                                    */
+  const int32_t *edge_dst;     /* [E]                                                    */
+  const int32_t *edge_comm;    /* [E] >= 0; latency added iff the two stages sit on
+                                  different devices; same for activations and gradients  */
+  const int32_t *dur;          /* [FPSCHED_NKINDS][S] >= 0; row 0 unused                 */
+  const int32_t *mem_units;    /* [S] >= 0, activation size of one (stage, micro-batch)  */
+  const int32_t *mem_cap;      /* [D] per-device cap (INT32_MAX = none)                  */
+} fpsched_problem_desc;
+
+typedef struct fpsched_problem fpsched_problem; /* opaque, library-owned */
+
+/* Validates the description (the edge list must be a DAG), precomputes the
+ * lookup tables and, unless device_id < 0, uploads them to that GPU.
+ * device_id < 0 gives a host-only handle: fpsched_encode / fpsched_validate
+ * work, device calls return FPSCHED_ENODEV.  max_stride_words bounds the row
+ * stride later passed to fpsched_evaluate (it enters the int32 time bound:
+ * FPSCHED_EOVERFLOW if D * max_stride * (max dur + max comm) >= 2^31). */
+int fpsched_problem_create(const fpsched_problem_desc *desc, int device_id, int32_t max_stride_words,
+                           fpsched_problem **out);
+void fpsched_problem_destroy(fpsched_problem *p);
+
+/* DEVICE buffers the caller owns (e.g. torch tensors); all must hold n_cand entries. */
+typedef struct {
+  int64_t *makespan; /* [C]     max finish time over all devices                          */
+  int64_t *idle;     /* [C][D]  makespan - busy time of the device (head/tail included)   */
+  int32_t *peak;     /* [C][D]  peak resident activation units                            */
+  uint8_t *flags;    /* [C]     FPSCHED_FLAG_* bits                                       */
+} fpsched_results;
+
+/* Bytes of DEVICE workspace fpsched_evaluate / fpsched_topk need for this batch. */
+size_t fpsched_workspace_bytes(const fpsched_problem *p, int64_t n_cand, int32_t k);
+
+/* Evaluate n_cand candidates.  d_ops: DEVICE, uint16 [n_cand][D][stride_words],
+ * 16-byte aligned, stride_words a multiple of 8 and <= the handle's max stride.
+ * Start rule (Section 5.1 "Data dependency" + the estimator's task graph with
+ * start/end/cost): forward items wait for the forward items of the predecessor
+ * stages, backward items for the backward items of the successor stages, each
+ * device runs its list in order;  start = max(device free, inputs' finish +
+ * cross-device latency),  finish = start + dur[kind][stage].
+ * Asynchronous: work is enqueued on hip_stream (a hipStream_t, NULL = default
+ * stream) and the call returns.  n_cand == 0 is a no-op. */
+int fpsched_evaluate(const fpsched_problem *p, const uint16_t *d_ops, int64_t n_cand,
+                     int32_t stride_words, fpsched_results out, void *d_workspace,
+                     size_t workspace_bytes, void *hip_stream);
+
+/* k best candidates with flags == 0 by (makespan ascending, index ascending)
+ * (Section 7.1: least bubble ratio; total work per problem is fixed, so this is
+ * least makespan).  d_idx, d_makespan: DEVICE [k]; unused slots get -1 and
+ * INT64_MAX.  d_count: DEVICE, min(k, #feasible).  1 <= k <= 1024.  Reads only
+ * in.makespan and in.flags.  Asynchronous on hip_stream. */
+int fpsched_topk(const fpsched_problem *p, fpsched_results in, int64_t n_cand, int32_t k,
+                 int64_t *d_idx, int64_t *d_makespan, int32_t *d_count, void *d_workspace,
+                 size_t workspace_bytes, void *hip_stream);
+
+/* HOST helper: pack n items (kind, stage, micro-batch) of one device's list into
+ * words (stage -> device-local chunk).  out_words: HOST [n].  EINVAL if an item
+ * names a stage that is not on `device`, a bad kind or micro-batch. */
+int fpsched_encode(const fpsched_problem *p, const int32_t *kind_stage_mb /* HOST [n][3] */,
+                   int32_t device, int32_t n, uint16_t *out_words);
+
+/* HOST helper: structural check of a HOST batch [n_cand][D][stride_words]: every word
+ * before a row's first END has a valid chunk for its device, micro-batch < m,
+ * and W only when has_w.  Returns the number of bad candidates (>= 0) or an error. */
+int64_t fpsched_validate(const fpsched_problem *p, const uint16_t *h_ops, int64_t n_cand,
+                         int32_t stride_words);
+
+/* Introspection (HOST): which kernel variant the handle selected and how many
+ * candidates one wavefront carries. */
+int fpsched_problem_info(const fpsched_problem *p, int32_t *lanes_per_candidate,
+                         int32_t *candidates_per_wave, int32_t *lds_bytes_per_wave);
+
+const char *fpsched_strerror(int code);
+int fpsched_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FPSCHED_H */

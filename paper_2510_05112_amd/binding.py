@@ -1,0 +1,222 @@
+"""ctypes marshalling for the C ABI declared in include/fpsched.h."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libfpsched.so")
+
+FLAG_DEADLOCK = 1
+FLAG_INCOMPLETE = 2
+FLAG_OVER_CAP = 4
+NKINDS = 8
+
+
+class FpschedError(RuntimeError):
+    def __init__(self, code, what):
+        super().__init__(f"{what}: {code} ({_strerror(code)})")
+        self.code = code
+
+
+class _Desc(ctypes.Structure):
+    _fields_ = [
+        ("n_devices", ctypes.c_int32), ("n_stages", ctypes.c_int32),
+        ("n_microbatches", ctypes.c_int32), ("has_w", ctypes.c_int32),
+        ("stage_device", ctypes.c_void_p), ("n_edges", ctypes.c_int32),
+        ("edge_src", ctypes.c_void_p), ("edge_dst", ctypes.c_void_p), ("edge_comm", ctypes.c_void_p),
+        ("dur", ctypes.c_void_p), ("mem_units", ctypes.c_void_p), ("mem_cap", ctypes.c_void_p),
+    ]
+
+
+class _Results(ctypes.Structure):
+    _fields_ = [("makespan", ctypes.c_void_p), ("idle", ctypes.c_void_p),
+                ("peak", ctypes.c_void_p), ("flags", ctypes.c_void_p)]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """dlopen libfpsched.so (built in-tree by paper_2510_05112_amd/build.py).  Fails loudly."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise FileNotFoundError(
+                f"{_LIB_PATH} is missing: build it with `python -m paper_2510_05112_amd.build`")
+        lib = ctypes.CDLL(_LIB_PATH)
+        vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+        lib.fpsched_version.restype = ctypes.c_int
+        lib.fpsched_strerror.restype = ctypes.c_char_p
+        lib.fpsched_strerror.argtypes = [ctypes.c_int]
+        lib.fpsched_problem_create.restype = ctypes.c_int
+        lib.fpsched_problem_create.argtypes = [ctypes.POINTER(_Desc), ctypes.c_int, i32, ctypes.POINTER(vp)]
+        lib.fpsched_problem_destroy.restype = None
+        lib.fpsched_problem_destroy.argtypes = [vp]
+        lib.fpsched_problem_info.restype = ctypes.c_int
+        lib.fpsched_problem_info.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i32)]
+        lib.fpsched_workspace_bytes.restype = ctypes.c_size_t
+        lib.fpsched_workspace_bytes.argtypes = [vp, i64, i32]
+        lib.fpsched_evaluate.restype = ctypes.c_int
+        lib.fpsched_evaluate.argtypes = [vp, vp, i64, i32, _Results, vp, ctypes.c_size_t, vp]
+        lib.fpsched_topk.restype = ctypes.c_int
+        lib.fpsched_topk.argtypes = [vp, _Results, i64, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.fpsched_encode.restype = ctypes.c_int
+        lib.fpsched_encode.argtypes = [vp, vp, i32, i32, vp]
+        lib.fpsched_validate.restype = ctypes.c_int64
+        lib.fpsched_validate.argtypes = [vp, vp, i64, i32]
+        _lib = lib
+    return _lib
+
+
+def _strerror(code):
+    try:
+        return load_library().fpsched_strerror(int(code)).decode()
+    except Exception:  # pragma: no cover
+        return "?"
+
+
+def version() -> int:
+    return load_library().fpsched_version()
+
+
+def _i32(a):
+    return np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+
+
+class Problem:
+    """Handle on one problem (``fpsched_problem``).
+
+    ``desc`` is any object with the fields of ``fpsched_problem_desc``
+    (n_devices, n_stages, n_microbatches, has_w, stage_device, edge_src,
+    edge_dst, edge_comm, dur[8][S], mem_units, mem_cap).  ``device`` is a CUDA/HIP
+    device index, or None for a host-only handle (encode / validate only).
+    """
+
+    def __init__(self, desc, max_stride: int, device: int | None = 0):
+        lib = load_library()
+        self.D, self.S, self.m = int(desc.n_devices), int(desc.n_stages), int(desc.n_microbatches)
+        self._keep = [_i32(desc.stage_device), _i32(desc.edge_src), _i32(desc.edge_dst),
+                      _i32(desc.edge_comm), _i32(desc.dur), _i32(desc.mem_units), _i32(desc.mem_cap)]
+        k = self._keep
+        if k[0].size != self.S or k[4].size != NKINDS * self.S or k[5].size != self.S or k[6].size != self.D:
+            raise ValueError("table sizes do not match n_stages / n_devices")
+        if not (k[1].size == k[2].size == k[3].size):
+            raise ValueError("edge arrays differ in length")
+        d = _Desc(self.D, self.S, self.m, int(desc.has_w), k[0].ctypes.data, int(k[1].size),
+                  k[1].ctypes.data, k[2].ctypes.data, k[3].ctypes.data, k[4].ctypes.data,
+                  k[5].ctypes.data, k[6].ctypes.data)
+        self.device = device
+        self.max_stride = int(max_stride)
+        self._h = ctypes.c_void_p()
+        rc = lib.fpsched_problem_create(ctypes.byref(d), -1 if device is None else int(device),
+                                        self.max_stride, ctypes.byref(self._h))
+        if rc != 0:
+            self._h = None
+            raise FpschedError(rc, "fpsched_problem_create")
+
+    def close(self):
+        if getattr(self, "_h", None):
+            load_library().fpsched_problem_destroy(self._h)
+            self._h = None
+
+    def __del__(self):  # pragma: no cover
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def info(self):
+        a, b, c = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+        load_library().fpsched_problem_info(self._h, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c))
+        return dict(lanes_per_candidate=a.value, candidates_per_wave=b.value, lds_bytes_per_wave=c.value)
+
+    # ---- host helpers -----------------------------------------------------
+    def encode(self, items, device: int) -> np.ndarray:
+        """items: [(kind, stage, micro-batch), ...] of one device's list -> uint16 words."""
+        a = _i32(items).reshape(-1, 3)
+        out = np.zeros(len(a), np.uint16)
+        rc = load_library().fpsched_encode(self._h, a.ctypes.data, int(device), len(a), out.ctypes.data)
+        if rc != 0:
+            raise FpschedError(rc, "fpsched_encode")
+        return out
+
+    def validate(self, words: np.ndarray) -> int:
+        w = np.ascontiguousarray(np.asarray(words, np.uint16))
+        assert w.ndim == 3 and w.shape[1] == self.D
+        rc = load_library().fpsched_validate(self._h, w.ctypes.data, w.shape[0], w.shape[2])
+        if rc < 0:
+            raise FpschedError(rc, "fpsched_validate")
+        return int(rc)
+
+    # ---- device calls (torch tensors in, torch tensors out) --------------------
+    def workspace_bytes(self, n_cand: int, k: int) -> int:
+        return int(load_library().fpsched_workspace_bytes(self._h, int(n_cand), int(k)))
+
+    def alloc_results(self, n_cand: int):
+        import torch
+        dev = torch.device("cuda", self.device)
+        return dict(makespan=torch.empty(n_cand, dtype=torch.int64, device=dev),
+                    idle=torch.empty((n_cand, self.D), dtype=torch.int64, device=dev),
+                    peak=torch.empty((n_cand, self.D), dtype=torch.int32, device=dev),
+                    flags=torch.empty(n_cand, dtype=torch.uint8, device=dev))
+
+    def alloc_workspace(self, n_cand: int, k: int):
+        import torch
+        return torch.empty(self.workspace_bytes(n_cand, k), dtype=torch.uint8,
+                           device=torch.device("cuda", self.device))
+
+    @staticmethod
+    def _res_struct(res):
+        return _Results(res["makespan"].data_ptr(), res["idle"].data_ptr(),
+                        res["peak"].data_ptr(), res["flags"].data_ptr())
+
+    def _stream(self, stream):
+        import torch
+        s = torch.cuda.current_stream(self.device) if stream is None else stream
+        return ctypes.c_void_p(s.cuda_stream)
+
+    def evaluate(self, ops, results=None, workspace=None, stream=None):
+        """ops: torch int16/uint16 CUDA tensor [C][D][stride] (resident in HBM).  Asynchronous."""
+        import torch
+        if self.device is None:
+            raise FpschedError(-5, "fpsched_evaluate")
+        assert ops.is_cuda and ops.is_contiguous() and ops.dim() == 3 and ops.shape[1] == self.D
+        assert ops.element_size() == 2
+        C, _, stride = ops.shape
+        if results is None:
+            results = self.alloc_results(C)
+        ws_ptr, ws_bytes = (workspace.data_ptr(), workspace.numel()) if workspace is not None else (0, 0)
+        rc = load_library().fpsched_evaluate(self._h, ops.data_ptr(), C, stride, self._res_struct(results),
+                                             ws_ptr, ws_bytes, self._stream(stream))
+        if rc != 0:
+            raise FpschedError(rc, "fpsched_evaluate")
+        return results
+
+    def topk(self, results, k: int, workspace=None, out=None, stream=None):
+        """k best feasible candidates of evaluated ``results``.  Returns dict(idx, makespan, count)
+        of CUDA tensors.  Asynchronous."""
+        import torch
+        if self.device is None:
+            raise FpschedError(-5, "fpsched_topk")
+        C = results["makespan"].numel()
+        dev = torch.device("cuda", self.device)
+        if workspace is None:
+            workspace = self.alloc_workspace(C, k)
+        if out is None:
+            out = dict(idx=torch.empty(k, dtype=torch.int64, device=dev),
+                       makespan=torch.empty(k, dtype=torch.int64, device=dev),
+                       count=torch.empty(1, dtype=torch.int32, device=dev))
+        rc = load_library().fpsched_topk(self._h, self._res_struct(results), C, int(k),
+                                         out["idx"].data_ptr(), out["makespan"].data_ptr(),
+                                         out["count"].data_ptr(), workspace.data_ptr(),
+                                         workspace.numel(), self._stream(stream))
+        if rc != 0:
+            raise FpschedError(rc, "fpsched_topk")
+        return out

@@ -1,0 +1,323 @@
+// C ABI of libfpsched: problem handles, host-side helpers and kernel launches.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+#include <vector>
+
+#include "../../include/fpsched.h"
+#include "kernels.h"
+
+using namespace fpsched;
+
+struct fpsched_problem {
+  int32_t D = 0, S = 0, m = 0, has_w = 0;
+  int device_id = -1;
+  int32_t max_stride = 0;
+  std::vector<int32_t> stage_device, stage_chunk, local_stage, n_chunks;
+  std::vector<int32_t> host_ints;  // the table image uploaded to the GPU
+  DevTables tables{};
+  int32_t* d_ints = nullptr;
+  int32_t lds_bytes = 0;           // dynamic LDS of the evaluation kernel
+  int32_t max_lds = 0;
+};
+
+namespace {
+
+int check_hip(hipError_t e) { return e == hipSuccess ? FPSCHED_OK : FPSCHED_EHIP; }
+
+struct DeviceGuard {
+  int prev = -1;
+  bool ok = false;
+  explicit DeviceGuard(int dev) {
+    if (hipGetDevice(&prev) != hipSuccess) return;
+    ok = (prev == dev) || hipSetDevice(dev) == hipSuccess;
+    if (prev == dev) prev = -1;
+  }
+  ~DeviceGuard() {
+    if (prev >= 0) (void)hipSetDevice(prev);
+  }
+};
+
+int next_pow2(int x) {
+  int p = 1;
+  while (p < x) p <<= 1;
+  return p;
+}
+
+}  // namespace
+
+extern "C" {
+
+int fpsched_version(void) { return FPSCHED_VERSION; }
+
+const char* fpsched_strerror(int code) {
+  switch (code) {
+    case FPSCHED_OK: return "ok";
+    case FPSCHED_EINVAL: return "invalid argument";
+    case FPSCHED_ENOMEM: return "out of memory or workspace too small";
+    case FPSCHED_EHIP: return "HIP runtime call failed";
+    case FPSCHED_EOVERFLOW: return "time bound does not fit int32";
+    case FPSCHED_ENODEV: return "host-only problem handle";
+    case FPSCHED_EUNSUPPORTED: return "problem too large for the on-chip tables";
+    default: return "unknown error";
+  }
+}
+
+int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int32_t max_stride_words,
+                           fpsched_problem** out) {
+  if (!desc || !out) return FPSCHED_EINVAL;
+  *out = nullptr;
+  const int D = desc->n_devices, S = desc->n_stages, m = desc->n_microbatches, E = desc->n_edges;
+  if (D < 1 || D > FPSCHED_MAX_DEVICES || S < 1 || S > D * FPSCHED_MAX_CHUNKS || m < 1 ||
+      m > FPSCHED_MAX_MICROBATCHES || E < 0 || max_stride_words < 8 || (max_stride_words & 7))
+    return FPSCHED_EINVAL;
+  if (!desc->stage_device || !desc->dur || !desc->mem_units || !desc->mem_cap) return FPSCHED_EINVAL;
+  if (E > 0 && (!desc->edge_src || !desc->edge_dst || !desc->edge_comm)) return FPSCHED_EINVAL;
+
+  fpsched_problem* p = new (std::nothrow) fpsched_problem;
+  if (!p) return FPSCHED_ENOMEM;
+  p->D = D; p->S = S; p->m = m; p->has_w = desc->has_w ? 1 : 0;
+  p->device_id = device_id < 0 ? -1 : device_id;
+  p->max_stride = max_stride_words;
+  p->stage_device.assign(desc->stage_device, desc->stage_device + S);
+  p->stage_chunk.assign(S, 0);
+  p->local_stage.assign((size_t)D * kMaxChunks, -1);
+  p->n_chunks.assign(D, 0);
+  int rc = FPSCHED_OK;
+  for (int s = 0; s < S && rc == FPSCHED_OK; ++s) {
+    const int d = p->stage_device[s];
+    if (d < 0 || d >= D || p->n_chunks[d] >= kMaxChunks) { rc = FPSCHED_EINVAL; break; }
+    p->stage_chunk[s] = p->n_chunks[d];
+    p->local_stage[(size_t)d * kMaxChunks + p->n_chunks[d]++] = s;
+  }
+  // edges: range, non-negative latency, acyclic (Kahn over stages)
+  int64_t max_dur = 0, max_comm = 0, units_total = 0;
+  if (rc == FPSCHED_OK) {
+    std::vector<int> indeg(S, 0);
+    for (int e = 0; e < E; ++e) {
+      const int a = desc->edge_src[e], b = desc->edge_dst[e];
+      if (a < 0 || a >= S || b < 0 || b >= S || a == b || desc->edge_comm[e] < 0) { rc = FPSCHED_EINVAL; break; }
+      indeg[b]++;
+      max_comm = std::max<int64_t>(max_comm, desc->edge_comm[e]);
+    }
+    if (rc == FPSCHED_OK) {
+      std::vector<int> order;
+      for (int s = 0; s < S; ++s) if (!indeg[s]) order.push_back(s);
+      for (size_t i = 0; i < order.size(); ++i)
+        for (int e = 0; e < E; ++e)
+          if (desc->edge_src[e] == order[i] && --indeg[desc->edge_dst[e]] == 0) order.push_back(desc->edge_dst[e]);
+      if ((int)order.size() != S) rc = FPSCHED_EINVAL;
+    }
+  }
+  if (rc == FPSCHED_OK) {
+    for (int i = 0; i < kNKinds * S; ++i) {
+      if (desc->dur[i] < 0) { rc = FPSCHED_EINVAL; break; }
+      max_dur = std::max<int64_t>(max_dur, desc->dur[i]);
+    }
+    for (int s = 0; s < S && rc == FPSCHED_OK; ++s) {
+      if (desc->mem_units[s] < 0) rc = FPSCHED_EINVAL;
+      units_total += (int64_t)desc->mem_units[s] * m;
+    }
+  }
+  // every finish time is at most (number of listed ops) * (largest duration + largest
+  // latency); resident memory is at most the sum of all activations
+  if (rc == FPSCHED_OK) {
+    const int64_t bound = (int64_t)D * max_stride_words * (max_dur + max_comm);
+    if (bound >= (int64_t)1 << 31 || units_total >= (int64_t)1 << 31) rc = FPSCHED_EOVERFLOW;
+  }
+  if (rc != FPSCHED_OK) { delete p; return rc; }
+
+  // table image
+  std::vector<int32_t>& I = p->host_ints;
+  DevTables& T = p->tables;
+  T.D = D; T.S = S; T.m = m; T.has_w = p->has_w;
+  auto append = [&](const int32_t* src, size_t n) { int32_t off = (int32_t)I.size(); I.insert(I.end(), src, src + n); return off; };
+  T.off_dur = append(desc->dur, (size_t)kNKinds * S);
+  T.off_mem_units = append(desc->mem_units, S);
+  std::vector<int32_t> poff(S + 1, 0), soff(S + 1, 0), pst(E), pcm(E), sst(E), scm(E);
+  for (int e = 0; e < E; ++e) { poff[desc->edge_dst[e] + 1]++; soff[desc->edge_src[e] + 1]++; }
+  for (int s = 0; s < S; ++s) { poff[s + 1] += poff[s]; soff[s + 1] += soff[s]; }
+  {
+    std::vector<int32_t> pf(S, 0), sf(S, 0);
+    for (int e = 0; e < E; ++e) {
+      const int a = desc->edge_src[e], b = desc->edge_dst[e];
+      const int32_t lat = p->stage_device[a] != p->stage_device[b] ? desc->edge_comm[e] : 0;
+      pst[poff[b] + pf[b]] = a; pcm[poff[b] + pf[b]++] = lat;
+      sst[soff[a] + sf[a]] = b; scm[soff[a] + sf[a]++] = lat;
+    }
+  }
+  T.off_pred_off = append(poff.data(), S + 1);
+  T.off_pred_stage = append(pst.data(), E);
+  T.off_pred_comm = append(pcm.data(), E);
+  T.off_succ_off = append(soff.data(), S + 1);
+  T.off_succ_stage = append(sst.data(), E);
+  T.off_succ_comm = append(scm.data(), E);
+  T.off_local_stage = append(p->local_stage.data(), (size_t)D * kMaxChunks);
+  T.off_n_chunks = append(p->n_chunks.data(), D);
+  T.off_mem_cap = append(desc->mem_cap, D);
+  T.n_table_ints = (int32_t)I.size();
+  T.lanes_per_cand = next_pow2(D);
+  T.cands_per_wave = 64 / T.lanes_per_cand;
+
+  if (p->device_id >= 0) {
+    DeviceGuard g(p->device_id);
+    if (!g.ok) { delete p; return FPSCHED_EHIP; }
+    int max_lds = 0;
+    if (hipDeviceGetAttribute(&max_lds, hipDeviceAttributeMaxSharedMemoryPerBlock, p->device_id) != hipSuccess) {
+      delete p; return FPSCHED_EHIP;
+    }
+    p->max_lds = max_lds;
+    const int64_t SM = (int64_t)S * m;
+    const int64_t per_cand = 4 * (2 * SM + ((SM + 3) >> 2));
+    const int64_t table_bytes = 4ll * T.n_table_ints;
+    int cpw = T.cands_per_wave;
+    while (cpw > 1 && table_bytes + cpw * per_cand > max_lds) cpw >>= 1;
+    if (table_bytes + cpw * per_cand > max_lds) { delete p; return FPSCHED_EUNSUPPORTED; }
+    T.cands_per_wave = cpw;
+    p->lds_bytes = (int32_t)(table_bytes + cpw * per_cand);
+    if (hipMalloc(&p->d_ints, I.size() * sizeof(int32_t)) != hipSuccess) { delete p; return FPSCHED_ENOMEM; }
+    if (hipMemcpy(p->d_ints, I.data(), I.size() * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess ||
+        hipFuncSetAttribute(reinterpret_cast<const void*>(&eval_general_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, p->lds_bytes) != hipSuccess) {
+      (void)hipFree(p->d_ints); delete p; return FPSCHED_EHIP;
+    }
+    T.ints = p->d_ints;
+  }
+  *out = p;
+  return FPSCHED_OK;
+}
+
+void fpsched_problem_destroy(fpsched_problem* p) {
+  if (!p) return;
+  if (p->d_ints) {
+    DeviceGuard g(p->device_id);
+    (void)hipFree(p->d_ints);
+  }
+  delete p;
+}
+
+int fpsched_problem_info(const fpsched_problem* p, int32_t* lanes_per_candidate,
+                         int32_t* candidates_per_wave, int32_t* lds_bytes_per_wave) {
+  if (!p) return FPSCHED_EINVAL;
+  if (lanes_per_candidate) *lanes_per_candidate = p->tables.lanes_per_cand;
+  if (candidates_per_wave) *candidates_per_wave = p->tables.cands_per_wave;
+  if (lds_bytes_per_wave) *lds_bytes_per_wave = p->lds_bytes;
+  return FPSCHED_OK;
+}
+
+static int64_t topk_level_sizes(int64_t n, int32_t k, int64_t* first, int64_t* second) {
+  // survivors after level 0 and after level 1 (the two ping-pong buffers)
+  const int64_t t0 = std::max<int64_t>(1, (n + kTile - 1) / kTile);
+  const int64_t n1 = t0 * k;
+  const int64_t t1 = std::max<int64_t>(1, (n1 + kTile - 1) / kTile);
+  *first = n1;
+  *second = t1 * k;
+  return n1 + *second;
+}
+
+size_t fpsched_workspace_bytes(const fpsched_problem* p, int64_t n_cand, int32_t k) {
+  if (!p || n_cand < 0) return 0;
+  int64_t a = 0, b = 0;
+  const int64_t keys = k > 0 ? topk_level_sizes(n_cand, std::min(k, 1024), &a, &b) : 0;
+  return (size_t)(256 + keys * (int64_t)sizeof(Key));
+}
+
+int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_cand,
+                     int32_t stride_words, fpsched_results out, void* d_workspace,
+                     size_t workspace_bytes, void* hip_stream) {
+  (void)d_workspace; (void)workspace_bytes;
+  if (!p || n_cand < 0) return FPSCHED_EINVAL;
+  if (p->device_id < 0) return FPSCHED_ENODEV;
+  if (n_cand == 0) return FPSCHED_OK;
+  if (!d_ops || !out.makespan || !out.idle || !out.peak || !out.flags) return FPSCHED_EINVAL;
+  if (stride_words < 8 || (stride_words & 7) || stride_words > p->max_stride) return FPSCHED_EINVAL;
+  if (reinterpret_cast<uintptr_t>(d_ops) & 15) return FPSCHED_EINVAL;
+  DeviceGuard g(p->device_id);
+  if (!g.ok) return FPSCHED_EHIP;
+  const int cpw = p->tables.cands_per_wave;
+  const int64_t blocks = (n_cand + cpw - 1) / cpw;
+  if (blocks > 0x7fffffffll) return FPSCHED_EINVAL;
+  hipLaunchKernelGGL(eval_general_kernel, dim3((unsigned)blocks), dim3(64), (size_t)p->lds_bytes,
+                     static_cast<hipStream_t>(hip_stream), p->tables, d_ops, (long long)n_cand,
+                     (int)stride_words, reinterpret_cast<long long*>(out.makespan),
+                     reinterpret_cast<long long*>(out.idle), out.peak, out.flags);
+  return check_hip(hipGetLastError());
+}
+
+int fpsched_topk(const fpsched_problem* p, fpsched_results in, int64_t n_cand, int32_t k,
+                 int64_t* d_idx, int64_t* d_makespan, int32_t* d_count, void* d_workspace,
+                 size_t workspace_bytes, void* hip_stream) {
+  if (!p || n_cand < 0 || k < 1 || k > 1024 || !d_idx || !d_makespan || !d_count) return FPSCHED_EINVAL;
+  if (p->device_id < 0) return FPSCHED_ENODEV;
+  if (n_cand > 0 && (!in.makespan || !in.flags)) return FPSCHED_EINVAL;
+  if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) & 15)) return FPSCHED_EINVAL;
+  if (workspace_bytes < fpsched_workspace_bytes(p, n_cand, k)) return FPSCHED_ENOMEM;
+  DeviceGuard g(p->device_id);
+  if (!g.ok) return FPSCHED_EHIP;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  int64_t cap_a = 0, cap_b = 0;
+  topk_level_sizes(n_cand, k, &cap_a, &cap_b);
+  Key* buf_a = reinterpret_cast<Key*>(static_cast<char*>(d_workspace) + 256);
+  Key* buf_b = buf_a + cap_a;
+  long long* f_idx = reinterpret_cast<long long*>(d_idx);
+  long long* f_ms = reinterpret_cast<long long*>(d_makespan);
+
+  int64_t n = n_cand;
+  const Key* src = nullptr;  // level 0 reads makespan/flags
+  Key* dst = buf_a;
+  for (;;) {
+    const int64_t tiles = std::max<int64_t>(1, (n + kTile - 1) / kTile);
+    const bool last = tiles == 1;
+    hipLaunchKernelGGL(topk_tile_kernel, dim3((unsigned)tiles), dim3(kTopkThreads), 0, st,
+                       reinterpret_cast<const long long*>(in.makespan), in.flags, src, (long long)n,
+                       (int)k, last ? nullptr : dst, last ? f_idx : nullptr, last ? f_ms : nullptr,
+                       last ? d_count : nullptr);
+    if (hipGetLastError() != hipSuccess) return FPSCHED_EHIP;
+    if (last) break;
+    n = tiles * k;
+    src = dst;
+    dst = (dst == buf_a) ? buf_b : buf_a;
+  }
+  return FPSCHED_OK;
+}
+
+int fpsched_encode(const fpsched_problem* p, const int32_t* ksm, int32_t device, int32_t n,
+                   uint16_t* out_words) {
+  if (!p || n < 0 || device < 0 || device >= p->D || (n > 0 && (!ksm || !out_words))) return FPSCHED_EINVAL;
+  for (int i = 0; i < n; ++i) {
+    const int kind = ksm[3 * i], s = ksm[3 * i + 1], j = ksm[3 * i + 2];
+    if (kind <= FPSCHED_END || kind >= FPSCHED_NKINDS || s < 0 || s >= p->S || j < 0 || j >= p->m)
+      return FPSCHED_EINVAL;
+    if (p->stage_device[s] != device) return FPSCHED_EINVAL;
+    if (kind == FPSCHED_W && !p->has_w) return FPSCHED_EINVAL;
+    out_words[i] = FPSCHED_WORD(kind, p->stage_chunk[s], j);
+  }
+  return FPSCHED_OK;
+}
+
+int64_t fpsched_validate(const fpsched_problem* p, const uint16_t* h_ops, int64_t n_cand,
+                         int32_t stride_words) {
+  if (!p || n_cand < 0 || stride_words < 1 || (n_cand > 0 && !h_ops)) return FPSCHED_EINVAL;
+  int64_t bad = 0;
+  for (int64_t c = 0; c < n_cand; ++c) {
+    bool cand_bad = false;
+    for (int d = 0; d < p->D && !cand_bad; ++d) {
+      const uint16_t* row = h_ops + ((size_t)c * p->D + d) * stride_words;
+      for (int i = 0; i < stride_words; ++i) {
+        const unsigned w = row[i];
+        const int kind = w >> 13;
+        if (kind == FPSCHED_END) break;
+        if ((int)((w >> 11) & 3) >= p->n_chunks[d] || (int)(w & 0x7ff) >= p->m ||
+            (kind == FPSCHED_W && !p->has_w)) { cand_bad = true; break; }
+      }
+    }
+    bad += cand_bad;
+  }
+  return bad;
+}
+
+}  // extern "C"

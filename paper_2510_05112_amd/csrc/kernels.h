@@ -1,0 +1,25 @@
+// Kernel declarations shared by the translation units of libfpsched.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "device_tables.h"
+
+namespace fpsched {
+
+struct Key {
+  long long makespan;
+  long long idx;
+};
+constexpr int kTile = 2048;
+constexpr int kTopkThreads = 256;
+
+__global__ void eval_general_kernel(DevTables T, const uint16_t* ops, long long n_cand, int stride,
+                                    long long* out_makespan, long long* out_idle, int* out_peak,
+                                    unsigned char* out_flags);
+
+__global__ void topk_tile_kernel(const long long* in_makespan, const unsigned char* in_flags,
+                                 const Key* in_keys, long long n, int k, Key* out_keys,
+                                 long long* final_idx, long long* final_makespan, int* final_count);
+
+}  // namespace fpsched

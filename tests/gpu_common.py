@@ -1,0 +1,45 @@
+"""Shared plumbing of the GPU parity tests: run a batch through the C ABI and fetch numpy results."""
+import numpy as np
+import torch
+
+import oracle
+import paper_2510_05112_amd as fp
+
+
+def gpu_evaluate(problem, words, k=None, max_stride=None):
+    """words: uint16 [C][D][stride] (numpy).  Returns (results dict of numpy arrays, topk tuple or None)."""
+    words = np.ascontiguousarray(words, dtype=np.uint16)
+    C, D, stride = words.shape
+    h = fp.Problem(problem, max_stride or stride, device=0)
+    ops = torch.from_numpy(words.view(np.int16)).cuda() if C else torch.empty((0, D, stride), dtype=torch.int16, device="cuda")
+    res = h.evaluate(ops)
+    top = None
+    if k is not None:
+        t = h.topk(res, k)
+        torch.cuda.synchronize()
+        top = (t["idx"].cpu().numpy(), t["makespan"].cpu().numpy(), int(t["count"].item()))
+    torch.cuda.synchronize()
+    out = {n: v.cpu().numpy() for n, v in res.items()}
+    h.close()
+    return out, top
+
+
+def assert_same(gpu, ref, what=""):
+    for name in ("flags", "makespan", "idle", "peak"):
+        a, b = gpu[name], ref[name]
+        if not np.array_equal(a, b):
+            bad = np.flatnonzero((a != b).reshape(len(a), -1).any(1))
+            raise AssertionError(f"{what}: {name} differs for {len(bad)} candidates, first {bad[:5]}: "
+                                 f"gpu {a[bad[0]]} oracle {b[bad[0]]}")
+
+
+def check_batch(problem, words, k=None, what="", threads=8):
+    gpu, top = gpu_evaluate(problem, words, k)
+    ref = oracle.evaluate(problem, words, threads=threads)
+    assert_same(gpu, ref, what)
+    if k is not None:
+        idx, ms, cnt = oracle.topk(ref["makespan"], ref["flags"], k)
+        assert top[2] == cnt, what
+        assert np.array_equal(top[0], idx), what
+        assert np.array_equal(top[1], ms), what
+    return gpu, ref

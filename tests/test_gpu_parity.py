@@ -1,0 +1,139 @@
+"""GPU parity: the HIP path, called through the C ABI, must equal the CPU oracle bit for bit."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from gpu_common import check_batch, gpu_evaluate
+from helpers import batch_from_lists, perturb, random_valid_lists, two_tower_problem
+from workloads.problem import (B, F, FD, L, O, R, W, chain_problem, gpipe_lists,
+                               one_f_one_b_lists, pack_lists, pack_word)
+
+pytestmark = pytest.mark.gpu
+
+
+def test_config1_all_candidates_and_fixed_cases():
+    spec = workloads.config(1)
+    words = workloads.generate(spec, threads=4)
+    assert len(words) == 1026
+    gpu, ref = check_batch(spec.problem, words, k=spec.top_k, what="cfg1")
+    # the appended textbook orders: GPipe 72, 1F1B 82 at comm 1
+    assert gpu["makespan"][1024] == 72 and list(gpu["idle"][1024]) == [24] * 4
+    assert gpu["makespan"][1025] == 82 and list(gpu["peak"][1025]) == [4, 3, 2, 1]
+
+
+@pytest.mark.parametrize("index,n", [(2, 3001), (3, 1027), (4, 300), (5, 2051)])
+def test_configs_reduced_batches(index, n):
+    spec = workloads.config(index, n)
+    words = workloads.generate(spec, threads=8)
+    gpu, ref = check_batch(spec.problem, words, k=spec.top_k, what=f"cfg{index}")
+    if spec.deadlock_per_mille:
+        assert (ref["flags"] & oracle.FLAG_DEADLOCK).sum() > 0
+    assert (ref["flags"] == 0).sum() > 0 and (ref["flags"] == oracle.FLAG_OVER_CAP).sum() > 0
+
+
+@pytest.mark.parametrize("p,m,v,w", [(3, 5, 1, None), (5, 4, 2, 2), (6, 3, 1, 1), (2, 6, 4, 1), (1, 7, 3, 2),
+                                     (7, 2, 1, None), (12, 3, 1, 2)])
+def test_random_orders_non_power_of_two_devices(p, m, v, w):
+    rng = np.random.default_rng(p * 1000 + m * 10 + v)
+    S = p * v
+    prob = chain_problem(p, m, v=v, f=1, b=1, w=w, comm=0)
+    prob.dur[F] = rng.integers(0, 9, S)
+    prob.dur[FD] = prob.dur[F]
+    prob.dur[R] = rng.integers(0, 9, S)
+    prob.dur[B] = rng.integers(1, 15, S)
+    prob.dur[O] = rng.integers(1, 6, S)
+    prob.dur[L] = rng.integers(1, 6, S)
+    if w is not None:
+        prob.dur[W] = rng.integers(0, 7, S)
+    prob.edge_comm[:] = rng.integers(0, 5, len(prob.edge_comm))
+    prob.mem_units[:] = rng.integers(0, 4, S)
+    prob.mem_cap[:] = rng.integers(2, 3 * m * v, p)
+    lists = []
+    for t in range(150):
+        base = random_valid_lists(prob, rng, 0.3 * (t % 2), 0.3 * ((t // 2) % 2))
+        lists.append(base)
+        lists.append(perturb(base, rng, 1 + t % 3))
+        cut = [list(x) for x in base]
+        d = int(rng.integers(p))
+        if cut[d]:
+            cut[d].pop(int(rng.integers(len(cut[d]))))
+        lists.append(cut)
+    words = batch_from_lists(lists)
+    gpu, ref = check_batch(prob, words, k=7, what=f"random p{p}")
+    assert (ref["flags"] & 1).sum() > 0 and (ref["flags"] == 0).sum() > 0
+
+
+def test_random_dag():
+    rng = np.random.default_rng(42)
+    for has_w in (0, 1):
+        prob = two_tower_problem(m=5, has_w=has_w, comm=2, mem_cap=3)
+        lists = []
+        for t in range(120):
+            base = random_valid_lists(prob, rng, 0.2, 0.3)
+            lists += [base, perturb(base, rng, 2)]
+        check_batch(prob, batch_from_lists(lists), k=33, what="dag")
+
+
+def test_edge_cases_flags_and_sentinels():
+    prob = chain_problem(2, 2, f=1, b=1, comm=0, mem_cap=1)
+    ok = gpipe_lists(2, 2)
+    cases = [
+        ok,                                                              # over cap
+        [[(B, 0, 0), (F, 0, 0), (F, 0, 1), (B, 0, 1)], ok[1]],           # same-device deadlock
+        [[(F, 0, 0), (B, 0, 0), (F, 0, 1), (B, 0, 1)], [(F, 0, 1), (F, 0, 0), (B, 0, 1), (B, 0, 0)]],  # cycle
+        [[(F, 0, 0), (F, 0, 0), (B, 0, 0), (B, 0, 1)], ok[1]],           # duplicate
+        [[(F, 0, 0), (B, 0, 0)], [(F, 0, 0), (B, 0, 0)]],                # micro-batch missing
+        [[], []],                                                        # empty
+        [[(F, 1, 0)], []],                                               # bad chunk
+        [[(F, 0, 5)], []],                                               # bad micro-batch
+        [ok[0] + [(W, 0, 0)], ok[1]],                                    # W without split backward
+        [[(B, 0, 0), (F, 1, 0)], ok[1]],                                 # malformed behind a deadlock
+        [[(F, 0, 0), (F, 0, 1), (B, 0, 0)], ok[1]],                      # one op missing
+        [[(F, 0, 0), (F, 0, 1), (B, 0, 1), (B, 0, 0)]] * 2,              # unusual but valid
+    ]
+    words = batch_from_lists(cases, stride=8)
+    words[0, 0, 5] = pack_word(F, 3, 77)   # behind the END word: ignored
+    gpu, ref = check_batch(prob, words, k=4, what="edge")
+    assert list(ref["flags"]) == [4, 1, 1, 1, 2, 2, 3, 3, 3, 1, 2, 4]
+
+
+def test_empty_batch_single_candidate_and_ragged_tail():
+    spec = workloads.config(2, 64)
+    words = workloads.generate(spec, threads=2)
+    gpu, top = gpu_evaluate(spec.problem, words[:0], k=5)
+    assert top[2] == 0 and np.all(top[0] == -1) and np.all(top[1] == oracle.INT64_MAX)
+    for n in (1, 7, 9, 63):
+        check_batch(spec.problem, words[:n], k=3, what=f"n={n}")
+
+
+def test_full_row_without_end_word_and_max_microbatches():
+    # every row exactly fills the stride (no END word): the row length bounds the list
+    p, m = 2, 4
+    prob = chain_problem(p, m, f=2, b=3, comm=1)
+    words = pack_lists(gpipe_lists(p, m), stride=8)[None]
+    assert np.all(words >> 13 != 0)
+    check_batch(prob, words, k=1, what="full row")
+    # the largest micro-batch count of the word format on a tiny pipeline
+    m = 2048
+    prob = chain_problem(2, m, f=1, b=2, comm=1)
+    lists = one_f_one_b_lists(2, m)
+    words = np.stack([pack_lists(lists, stride=4096), pack_lists(gpipe_lists(2, m), stride=4096)])
+    gpu, ref = check_batch(prob, words, k=2, what="m=2048")
+    assert gpu["makespan"][1] == (m + 1) * 3 + 2
+
+
+def test_sixty_four_devices():
+    p, m = 64, 6
+    prob = chain_problem(p, m, f=2, b=4, comm=1)
+    words = np.stack([pack_lists(gpipe_lists(p, m)), pack_lists(one_f_one_b_lists(p, m))])
+    gpu, ref = check_batch(prob, words, k=2, what="p=64")
+    assert gpu["makespan"][0] == (m + p - 1) * 6 + 2 * (p - 1)
+
+
+def test_topk_many_ties_and_large_k():
+    # config 1 has only a handful of distinct makespans: ties everywhere
+    spec = workloads.config(1, 5000)
+    words = workloads.generate(spec, threads=4)
+    for k in (1, 16, 128, 1000, 1024):
+        check_batch(spec.problem, words, k=k, what=f"ties k={k}")

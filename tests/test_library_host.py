@@ -1,0 +1,95 @@
+"""Host-side checks of libfpsched that need no GPU: the library loads, exports every symbol
+the header declares, and its host helpers (create/encode/validate/strerror) behave."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2510_05112_amd as fp
+import workloads
+from workloads.problem import B, F, FD, W, chain_problem, pack_lists, pack_word
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    lib = fp.load_library()
+    header = open(os.path.join(ROOT, "include", "fpsched.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(fpsched_[a-z_]+)\s*\(", header))
+    assert {"fpsched_evaluate", "fpsched_topk", "fpsched_problem_create", "fpsched_problem_destroy",
+            "fpsched_workspace_bytes", "fpsched_encode", "fpsched_validate", "fpsched_strerror",
+            "fpsched_version", "fpsched_problem_info"} <= names
+    for n in names:
+        assert hasattr(lib, n), n
+    assert fp.version() == 100
+    assert lib.fpsched_strerror(-4).decode().startswith("time bound")
+
+
+def test_host_only_handle_and_errors():
+    spec = workloads.config(2, 8)
+    p = fp.Problem(spec.problem, spec.stride, device=None)
+    info = p.info()
+    assert info["lanes_per_candidate"] == 8 and info["candidates_per_wave"] == 8
+    assert p.workspace_bytes(65536, 16) >= 16 * 16 * 32
+    # device calls on a host-only handle are refused, not emulated
+    lib = fp.load_library()
+    rc = lib.fpsched_evaluate(p._h, 0, 1, spec.stride, fp.binding._Results(0, 0, 0, 0), 0, 0, 0)
+    assert rc == -5
+    p.close()
+    # bad descriptions
+    bad = chain_problem(4, 8)
+    bad.stage_device[0] = 9
+    with pytest.raises(fp.FpschedError) as e:
+        fp.Problem(bad, 64, device=None)
+    assert e.value.code == -1
+    cyc = chain_problem(3, 2)
+    cyc.edge_src = np.array([0, 1, 2], np.int32)
+    cyc.edge_dst = np.array([1, 2, 0], np.int32)
+    cyc.edge_comm = np.array([0, 0, 0], np.int32)
+    with pytest.raises(fp.FpschedError):
+        fp.Problem(cyc, 64, device=None)
+    big = chain_problem(4, 8, f=1 << 28, b=1)
+    with pytest.raises(fp.FpschedError) as e:
+        fp.Problem(big, 64, device=None)
+    assert e.value.code == -4
+    with pytest.raises(fp.FpschedError):
+        fp.Problem(chain_problem(4, 8), 60, device=None)   # stride not a multiple of 8
+    five = chain_problem(1, 2, v=5)
+    with pytest.raises(fp.FpschedError):
+        fp.Problem(five, 64, device=None)                  # more than 4 stages on a device
+
+
+def test_encode_matches_hand_written_words_and_oracle_decode():
+    prob = chain_problem(4, 8, v=2, f=1, b=1, w=1)
+    p = fp.Problem(prob, 64, device=None)
+    # device 1 hosts stages 1 (chunk 0) and 5 (chunk 1)
+    words = p.encode([(F, 1, 0), (FD, 5, 7), (B, 5, 7), (W, 1, 3)], device=1)
+    assert list(words) == [0x2000, 0xE807, 0x4807, 0x6003]
+    assert list(words) == [pack_word(F, 0, 0), pack_word(FD, 1, 7), pack_word(B, 1, 7), pack_word(W, 0, 3)]
+    k, c, j = oracle.decode(words)
+    assert list(k) == [F, FD, B, W] and list(c) == [0, 1, 1, 0] and list(j) == [0, 7, 7, 3]
+    for item in [(F, 0, 0), (F, 1, 8), (9, 1, 0), (0, 1, 0), (F, 8, 0)]:
+        with pytest.raises(fp.FpschedError):
+            p.encode([item], device=1)
+    nosplit = fp.Problem(chain_problem(2, 2), 8, device=None)
+    with pytest.raises(fp.FpschedError):
+        nosplit.encode([(W, 0, 0)], device=0)
+
+
+def test_validate_counts_bad_candidates_like_the_oracle_flags_them():
+    spec = workloads.config(1, 64)
+    words = workloads.generate(spec, threads=2)
+    p = fp.Problem(spec.problem, spec.stride, device=None)
+    assert p.validate(words) == 0
+    words = words.copy()
+    words[3, 1, 4] = pack_word(F, 1, 0)     # chunk 1 does not exist (v=1)
+    words[7, 0, 0] = pack_word(B, 0, 9)     # micro-batch 9 >= m
+    words[9, 2, 2] = pack_word(W, 0, 0)     # W in a non-split problem
+    words[11, 3, 40] = pack_word(F, 3, 99)  # behind the END: ignored
+    assert p.validate(words) == 3
+    fl = oracle.evaluate(spec.problem, words)["flags"]
+    assert set(np.flatnonzero(fl & 2)) <= {3, 7, 9}

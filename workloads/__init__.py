@@ -1,0 +1,181 @@
+"""Seeded synthetic inputs: the five benchmark problems and their candidate batches.
+
+Input generation only -- no evaluation.  ``config(i)`` builds problem ``i``
+(1..5) with its seeded duration tables; ``generate(spec, ...)`` list-schedules
+candidates with the C generator ``fpgen.c`` (built with gcc on first use).
+Neither the CPU oracle nor the GPU package is imported here.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+from .problem import (B, F, FD, L, MAX_CHUNKS, NKINDS, NO_CAP, O, R, W, Problem, chain_problem,
+                      gpipe_lists, make_problem, one_f_one_b_lists, pack_lists, pack_word)
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "fpgen.c")
+_LIB = os.path.join(_HERE, "libfpgen.so")
+BASE_SEED = 0xF1E0
+
+
+def build(force: bool = False) -> str:
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-pthread", "-o", tmp, _SRC])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+class _CParams(ctypes.Structure):
+    _fields_ = [
+        ("n_devices", ctypes.c_int32), ("n_stages", ctypes.c_int32),
+        ("n_microbatches", ctypes.c_int32), ("has_w", ctypes.c_int32),
+        ("stage_device", ctypes.c_void_p), ("n_edges", ctypes.c_int32),
+        ("edge_src", ctypes.c_void_p), ("edge_dst", ctypes.c_void_p), ("edge_comm", ctypes.c_void_p),
+        ("dur", ctypes.c_void_p),
+        ("recompute", ctypes.c_int32), ("offload", ctypes.c_int32),
+        ("max_marks_per_device", ctypes.c_int32), ("cap_units", ctypes.c_int32),
+        ("seed", ctypes.c_uint64),
+        ("deadlock_per_mille", ctypes.c_int32), ("benign_per_mille", ctypes.c_int32),
+    ]
+
+
+@dataclass
+class Spec:
+    """A benchmark configuration: the problem plus the generator's knobs."""
+
+    index: int
+    problem: Problem
+    n_candidates: int
+    stride: int               # words per device row (multiple of 64)
+    top_k: int
+    recompute: int = 0
+    offload: int = 0
+    max_marks_per_device: int = 0
+    cap_units: int = 0
+    deadlock_per_mille: int = 0
+    benign_per_mille: int = 10
+    seed: int = BASE_SEED
+    fixed_cases: tuple = ()   # names of textbook orders appended after the generated ones
+
+
+def _mix64(x):
+    x = (x + 0x9E3779B97F4A7C15) & 0xFFFFFFFFFFFFFFFF
+    x = ((x ^ (x >> 30)) * 0xBF58476D1CE4E5B9) & 0xFFFFFFFFFFFFFFFF
+    x = ((x ^ (x >> 27)) * 0x94D049BB133111EB) & 0xFFFFFFFFFFFFFFFF
+    return x ^ (x >> 31)
+
+
+class _TableRng:
+    """Counter-based integers for the seeded duration tables."""
+
+    def __init__(self, seed):
+        self.key, self.ctr = _mix64(seed), 0
+
+    def uniform_int(self, lo, hi):
+        self.ctr += 1
+        return lo + _mix64(self.key ^ (self.ctr * 0x2545F4914F6CDD1D & 0xFFFFFFFFFFFFFFFF)) % (hi - lo + 1)
+
+
+def config(index: int, n_candidates: int | None = None) -> Spec:
+    """The five benchmark configurations (stage counts, durations, caps, batch sizes)."""
+    rng = _TableRng(BASE_SEED + index)
+    if index == 1:
+        prob = chain_problem(4, 8, v=1, f=2, b=4, comm=1, name="cfg1_p4_m8_FB")
+        return Spec(1, prob, n_candidates or 1024, 64, 16, cap_units=4, seed=BASE_SEED + 1,
+                    fixed_cases=("gpipe", "1f1b"))
+    if index in (2, 3, 4):
+        p, m, v = {2: (8, 32, 2), 3: (16, 64, 2), 4: (32, 128, 2)}[index]
+        S = p * v
+        if index == 2:
+            dur = {F: [rng.uniform_int(8, 12) for _ in range(S)], B: [rng.uniform_int(14, 20) for _ in range(S)],
+                   W: [rng.uniform_int(6, 10) for _ in range(S)]}
+            comm = [rng.uniform_int(1, 3) for _ in range(S - 1)]
+            cap = 3 * p // 2
+        elif index == 3:
+            def jit(base):
+                return [base + rng.uniform_int(-(base // 10), base // 10) for _ in range(S)]
+            dur = {F: jit(10), B: jit(20), W: jit(10)}
+            for k in (F, B, W):
+                dur[k][0] = (13 * dur[k][0] + 5) // 10          # embedding stage: 1.3x
+                dur[k][S - 1] = (16 * dur[k][S - 1] + 5) // 10  # LM head + loss: 1.6x
+            comm = [1] * (S - 1)
+            cap = p
+        else:
+            dur = {F: [rng.uniform_int(20, 30) for _ in range(S)], B: [rng.uniform_int(40, 60) for _ in range(S)],
+                   W: [rng.uniform_int(15, 25) for _ in range(S)]}
+            comm = [rng.uniform_int(2, 6) for _ in range(S - 1)]
+            cap = 3 * p // 4
+        dur[FD] = list(dur[F])
+        dur[R] = list(dur[F])
+        edges = [(s, s + 1, comm[s]) for s in range(S - 1)]
+        prob = make_problem(p, S, m, 1, [s % p for s in range(S)], edges, dur, mem_cap=cap,
+                            name=f"cfg{index}_p{p}_m{m}_v{v}")
+        base_len = 3 * m * v
+        if index == 4:
+            return Spec(4, prob, n_candidates or 65536, 896, 128, recompute=1, max_marks_per_device=128,
+                        cap_units=cap, seed=BASE_SEED + 4)
+        return Spec(index, prob, n_candidates or {2: 65536, 3: 262144}[index], -(-base_len // 64) * 64,
+                    {2: 16, 3: 64}[index], cap_units=cap, seed=BASE_SEED + index,
+                    deadlock_per_mille=20 if index == 2 else 0)
+    if index == 5:
+        # two towers of 6 stages (vision 0..5, text 6..11) merging into 4 fusion stages 12..15
+        m = 64
+        f = [12] * 6 + [8] * 6 + [16] * 4
+        dur = {F: f, B: [2 * x for x in f], W: list(f), FD: list(f), R: list(f), O: 5, L: 5}
+        edges = [(s, s + 1, 1) for s in range(5)] + [(5, 12, 1)]
+        edges += [(s, s + 1, 1) for s in range(6, 11)] + [(11, 12, 1)]
+        edges += [(s, s + 1, 1) for s in range(12, 15)]
+        prob = make_problem(16, 16, m, 1, list(range(16)), edges, dur, mem_cap=12, name="cfg5_two_towers")
+        return Spec(5, prob, n_candidates or 131072, 256, 64, offload=1, max_marks_per_device=32,
+                    cap_units=12, seed=BASE_SEED + 5, deadlock_per_mille=10)
+    raise ValueError("config index must be 1..5")
+
+
+def _i32(a):
+    return np.ascontiguousarray(np.asarray(a, np.int32))
+
+
+def generate(spec: Spec, n: int | None = None, first: int = 0, threads: int | None = None,
+             with_generator_clock: bool = False, out: np.ndarray | None = None):
+    """Candidates [first, first+n) of ``spec`` as uint16[n][D][stride] (+ fixed cases when the
+    range reaches the end of the batch).  ``out`` may be a preallocated (e.g. pinned) buffer."""
+    lib = ctypes.CDLL(build())
+    lib.fpgen_generate.restype = ctypes.c_int
+    p = spec.problem
+    total = spec.n_candidates
+    n = total - first if n is None else n
+    arrs = [_i32(p.stage_device), _i32(p.edge_src), _i32(p.edge_dst), _i32(p.edge_comm), _i32(p.dur)]
+    cp = _CParams(p.n_devices, p.n_stages, p.n_microbatches, p.has_w, arrs[0].ctypes.data,
+                  len(arrs[1]), arrs[1].ctypes.data, arrs[2].ctypes.data, arrs[3].ctypes.data,
+                  arrs[4].ctypes.data, spec.recompute, spec.offload, spec.max_marks_per_device,
+                  spec.cap_units, spec.seed, spec.deadlock_per_mille, spec.benign_per_mille)
+    n_fixed = len(spec.fixed_cases) if first + n >= total else 0
+    shape = (n + n_fixed, p.n_devices, spec.stride)
+    if out is None:
+        out = np.zeros(shape, np.uint16)
+    assert out.shape == shape and out.dtype == np.uint16 and out.flags.c_contiguous
+    clock = np.full(n + n_fixed, -1, np.int64)
+    threads = threads or min(16, os.cpu_count() or 1)
+    rc = lib.fpgen_generate(ctypes.byref(cp), ctypes.c_int64(first), ctypes.c_int64(n),
+                            ctypes.c_int32(spec.stride), ctypes.c_void_p(out.ctypes.data),
+                            ctypes.c_void_p(clock.ctypes.data), ctypes.c_int32(threads))
+    if rc:
+        raise RuntimeError(f"fpgen_generate failed ({rc})")
+    for i, name in enumerate(spec.fixed_cases[:n_fixed]):
+        lists = {"gpipe": gpipe_lists, "1f1b": one_f_one_b_lists}[name](p.n_devices, p.n_microbatches)
+        out[n + i] = pack_lists(lists, spec.stride)
+    return (out, clock) if with_generator_clock else out
+
+
+def count_ops(words: np.ndarray) -> int:
+    """Number of real (non-END) op words that an evaluator reads: per row, up to the first END."""
+    w = words.reshape(-1, words.shape[-1])
+    is_end = (w >> 13) == 0
+    first_end = np.where(is_end.any(1), is_end.argmax(1), w.shape[1])
+    return int(first_end.sum())
