@@ -48,7 +48,7 @@ def test_random_orders_non_power_of_two_devices(p, m, v, w):
         prob.dur[W] = rng.integers(0, 7, S)
     prob.edge_comm[:] = rng.integers(0, 5, len(prob.edge_comm))
     prob.mem_units[:] = rng.integers(0, 4, S)
-    prob.mem_cap[:] = rng.integers(2, 3 * m * v, p)
+    prob.mem_cap[:] = rng.integers(2 * m * v, 8 * m * v, p)
     lists = []
     for t in range(150):
         base = random_valid_lists(prob, rng, 0.3 * (t % 2), 0.3 * ((t // 2) % 2))
@@ -61,7 +61,7 @@ def test_random_orders_non_power_of_two_devices(p, m, v, w):
         lists.append(cut)
     words = batch_from_lists(lists)
     gpu, ref = check_batch(prob, words, k=7, what=f"random p{p}")
-    assert (ref["flags"] & 1).sum() > 0 and (ref["flags"] == 0).sum() > 0
+    assert (ref["flags"] & 1).sum() > 0 and ((ref["flags"] & 3) == 0).sum() > 0
 
 
 def test_random_dag():
