@@ -152,6 +152,16 @@ int64_t fpsched_validate(const fpsched_problem *p, const uint16_t *h_ops, int64_
 int fpsched_problem_info(const fpsched_problem *p, int32_t *lanes_per_candidate,
                          int32_t *candidates_per_wave, int32_t *lds_bytes_per_wave);
 
+/* Two evaluation kernels compute the same results.  SLOTS (default whenever its LDS
+ * footprint fits): per-micro-batch mail slots, a few KB of LDS per candidate.  GENERAL:
+ * whole finish-time tables in LDS, one wavefront per workgroup; kept for problems whose
+ * state words do not fit the slot kernel and as a cross-check.  EUNSUPPORTED if the
+ * requested kernel does not fit this problem. */
+#define FPSCHED_KERNEL_AUTO 0
+#define FPSCHED_KERNEL_GENERAL 1
+#define FPSCHED_KERNEL_SLOTS 2
+int fpsched_problem_select_kernel(fpsched_problem *p, int which);
+
 const char *fpsched_strerror(int code);
 int fpsched_version(void);
 

@@ -61,6 +61,8 @@ def load_library():
         lib.fpsched_problem_destroy.argtypes = [vp]
         lib.fpsched_problem_info.restype = ctypes.c_int
         lib.fpsched_problem_info.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i32)]
+        lib.fpsched_problem_select_kernel.restype = ctypes.c_int
+        lib.fpsched_problem_select_kernel.argtypes = [vp, ctypes.c_int]
         lib.fpsched_workspace_bytes.restype = ctypes.c_size_t
         lib.fpsched_workspace_bytes.argtypes = [vp, i64, i32]
         lib.fpsched_evaluate.restype = ctypes.c_int
@@ -136,6 +138,12 @@ class Problem:
         a, b, c = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
         load_library().fpsched_problem_info(self._h, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c))
         return dict(lanes_per_candidate=a.value, candidates_per_wave=b.value, lds_bytes_per_wave=c.value)
+
+    def select_kernel(self, which: str):
+        """'auto', 'general' or 'slots' (both kernels compute the same results)."""
+        rc = load_library().fpsched_problem_select_kernel(self._h, {"auto": 0, "general": 1, "slots": 2}[which])
+        if rc != 0:
+            raise FpschedError(rc, "fpsched_problem_select_kernel")
 
     # ---- host helpers -----------------------------------------------------
     def encode(self, items, device: int) -> np.ndarray:

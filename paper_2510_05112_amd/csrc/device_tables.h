@@ -35,6 +35,14 @@ struct DevTables {
   int32_t off_local_stage;  // [D][kMaxChunks], -1 = none
   int32_t off_n_chunks;     // [D]
   int32_t off_mem_cap;      // [D]
+  int32_t off_pred_cls;     // [E]  slot class of the edge (pred CSR order)
+  int32_t off_succ_cls;     // [E]  slot class of the edge (succ CSR order)
+  // slot kernel geometry
+  int32_t n_classes;        // slot classes (1 for a chain)
+  int32_t state_words;      // dwords of 4-bit activation states per lane
+  int32_t slot_cands_per_wave;
+  int32_t wave_ints;        // LDS dwords owned by one wavefront in the slot kernel
+  int32_t table_ints_padded;
   const int32_t* ints;      // DEVICE
 };
 

@@ -21,8 +21,12 @@ struct fpsched_problem {
   std::vector<int32_t> host_ints;  // the table image uploaded to the GPU
   DevTables tables{};
   int32_t* d_ints = nullptr;
-  int32_t lds_bytes = 0;           // dynamic LDS of the evaluation kernel
+  int32_t lds_bytes = 0;           // dynamic LDS of the general kernel (one wave per group)
   int32_t max_lds = 0;
+  bool general_ok = false, slots_ok = false;  // which kernels fit this problem in LDS
+  bool use_slots = false;          // selected kernel: slot kernel (default when it fits) or general
+  int32_t slot_v = 0;              // template bound on chunks per device
+  int32_t slot_lds_bytes = 0;      // dynamic LDS of one slot-kernel workgroup
 };
 
 namespace {
@@ -41,6 +45,12 @@ struct DeviceGuard {
     if (prev >= 0) (void)hipSetDevice(prev);
   }
 };
+
+using SlotKernel = void (*)(DevTables, const uint16_t*, long long, int, long long*, long long*, int*,
+                            unsigned char*);
+SlotKernel slot_kernel_ptr(int v) {
+  return v == 1 ? &eval_slot_kernel<1> : (v == 2 ? &eval_slot_kernel<2> : &eval_slot_kernel<4>);
+}
 
 int next_pow2(int x) {
   int p = 1;
@@ -159,7 +169,41 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
   T.off_local_stage = append(p->local_stage.data(), (size_t)D * kMaxChunks);
   T.off_n_chunks = append(p->n_chunks.data(), D);
   T.off_mem_cap = append(desc->mem_cap, D);
+  // Slot classes: chains of edges such that each edge starts at the stage the previous
+  // one ends in.  Stages are visited in topological order; an out-edge continues the
+  // class of a not yet continued in-edge of its stage, else it opens a new class.
+  std::vector<int32_t> edge_cls(E, -1);
+  int n_classes = 0;
+  {
+    std::vector<int> indeg(S, 0), order;
+    for (int e = 0; e < E; ++e) indeg[desc->edge_dst[e]]++;
+    for (int s = 0; s < S; ++s) if (!indeg[s]) order.push_back(s);
+    for (size_t i = 0; i < order.size(); ++i) {
+      const int s = order[i];
+      std::vector<int32_t> arriving;
+      for (int e = 0; e < E; ++e) if (desc->edge_dst[e] == s) arriving.push_back(edge_cls[e]);
+      size_t used = 0;
+      for (int e = 0; e < E; ++e) {
+        if (desc->edge_src[e] != s) continue;
+        edge_cls[e] = used < arriving.size() ? arriving[used++] : n_classes++;
+        if (--indeg[desc->edge_dst[e]] == 0) order.push_back(desc->edge_dst[e]);
+      }
+    }
+    if (n_classes == 0) n_classes = 1;
+  }
+  {
+    std::vector<int32_t> pcl(E), scl(E), pf(S, 0), sf(S, 0);
+    for (int e = 0; e < E; ++e) {
+      const int a = desc->edge_src[e], b = desc->edge_dst[e];
+      pcl[poff[b] + pf[b]++] = edge_cls[e];
+      scl[soff[a] + sf[a]++] = edge_cls[e];
+    }
+    T.off_pred_cls = append(pcl.data(), E);
+    T.off_succ_cls = append(scl.data(), E);
+  }
+  T.n_classes = n_classes;
   T.n_table_ints = (int32_t)I.size();
+  T.table_ints_padded = (T.n_table_ints + 3) & ~3;
   T.lanes_per_cand = next_pow2(D);
   T.cands_per_wave = 64 / T.lanes_per_cand;
 
@@ -171,20 +215,45 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
       delete p; return FPSCHED_EHIP;
     }
     p->max_lds = max_lds;
+    // general kernel geometry: finish-time tables and state bytes of whole candidates in LDS
     const int64_t SM = (int64_t)S * m;
     const int64_t per_cand = 4 * (2 * SM + ((SM + 3) >> 2));
     const int64_t table_bytes = 4ll * T.n_table_ints;
     int cpw = T.cands_per_wave;
     while (cpw > 1 && table_bytes + cpw * per_cand > max_lds) cpw >>= 1;
-    if (table_bytes + cpw * per_cand > max_lds) { delete p; return FPSCHED_EUNSUPPORTED; }
+    p->general_ok = table_bytes + cpw * per_cand <= max_lds;
     T.cands_per_wave = cpw;
     p->lds_bytes = (int32_t)(table_bytes + cpw * per_cand);
-    if (hipMalloc(&p->d_ints, I.size() * sizeof(int32_t)) != hipSuccess) { delete p; return FPSCHED_ENOMEM; }
-    if (hipMemcpy(p->d_ints, I.data(), I.size() * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess ||
-        hipFuncSetAttribute(reinterpret_cast<const void*>(&eval_general_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, p->lds_bytes) != hipSuccess) {
-      (void)hipFree(p->d_ints); delete p; return FPSCHED_EHIP;
+    // slot kernel geometry: per wave, a 16-dword op window and the 4-bit state words per
+    // lane, plus 2 * classes * m eight-byte slots per candidate
+    int max_chunks = 1;
+    for (int d = 0; d < D; ++d) max_chunks = std::max(max_chunks, p->n_chunks[d]);
+    p->slot_v = max_chunks <= 1 ? 1 : (max_chunks <= 2 ? 2 : 4);
+    T.state_words = (p->slot_v * m + 7) / 8;
+    {
+      int scpw = 64 / T.lanes_per_cand;
+      const int64_t fixed = 64ll * (16 + T.state_words);
+      const int64_t per_slot_cand = 2ll * 2 * n_classes * m;  // dwords
+      const int64_t budget_ints = (max_lds - 4ll * T.table_ints_padded) / 4 / kSlotWaves;
+      while (scpw > 1 && fixed + scpw * per_slot_cand > budget_ints) scpw >>= 1;
+      const int64_t wave_ints = fixed + scpw * per_slot_cand;
+      const int64_t block_bytes = 4ll * T.table_ints_padded + 4 * kSlotWaves * wave_ints;
+      p->slots_ok = block_bytes <= max_lds;
+      T.slot_cands_per_wave = scpw;
+      T.wave_ints = (int32_t)wave_ints;
+      p->slot_lds_bytes = (int32_t)block_bytes;
     }
+    if (!p->general_ok && !p->slots_ok) { delete p; return FPSCHED_EUNSUPPORTED; }
+    p->use_slots = p->slots_ok;
+    if (hipMalloc(&p->d_ints, I.size() * sizeof(int32_t)) != hipSuccess) { delete p; return FPSCHED_ENOMEM; }
+    bool ok = hipMemcpy(p->d_ints, I.data(), I.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess;
+    if (ok && p->general_ok)
+      ok = hipFuncSetAttribute(reinterpret_cast<const void*>(&eval_general_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, p->lds_bytes) == hipSuccess;
+    if (ok && p->slots_ok)
+      ok = hipFuncSetAttribute(reinterpret_cast<const void*>(slot_kernel_ptr(p->slot_v)),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, p->slot_lds_bytes) == hipSuccess;
+    if (!ok) { (void)hipFree(p->d_ints); delete p; return FPSCHED_EHIP; }
     T.ints = p->d_ints;
   }
   *out = p;
@@ -203,9 +272,20 @@ void fpsched_problem_destroy(fpsched_problem* p) {
 int fpsched_problem_info(const fpsched_problem* p, int32_t* lanes_per_candidate,
                          int32_t* candidates_per_wave, int32_t* lds_bytes_per_wave) {
   if (!p) return FPSCHED_EINVAL;
+  const bool slots = p->use_slots;
   if (lanes_per_candidate) *lanes_per_candidate = p->tables.lanes_per_cand;
-  if (candidates_per_wave) *candidates_per_wave = p->tables.cands_per_wave;
-  if (lds_bytes_per_wave) *lds_bytes_per_wave = p->lds_bytes;
+  if (candidates_per_wave) *candidates_per_wave = slots ? p->tables.slot_cands_per_wave : p->tables.cands_per_wave;
+  if (lds_bytes_per_wave) *lds_bytes_per_wave = slots ? p->slot_lds_bytes / kSlotWaves : p->lds_bytes;
+  return FPSCHED_OK;
+}
+
+int fpsched_problem_select_kernel(fpsched_problem* p, int which) {
+  if (!p) return FPSCHED_EINVAL;
+  if (p->device_id < 0) return FPSCHED_ENODEV;
+  if (which == FPSCHED_KERNEL_AUTO) p->use_slots = p->slots_ok;
+  else if (which == FPSCHED_KERNEL_GENERAL) { if (!p->general_ok) return FPSCHED_EUNSUPPORTED; p->use_slots = false; }
+  else if (which == FPSCHED_KERNEL_SLOTS) { if (!p->slots_ok) return FPSCHED_EUNSUPPORTED; p->use_slots = true; }
+  else return FPSCHED_EINVAL;
   return FPSCHED_OK;
 }
 
@@ -238,6 +318,16 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
   if (reinterpret_cast<uintptr_t>(d_ops) & 15) return FPSCHED_EINVAL;
   DeviceGuard g(p->device_id);
   if (!g.ok) return FPSCHED_EHIP;
+  if (p->use_slots) {
+    const int per_block = p->tables.slot_cands_per_wave * kSlotWaves;
+    const int64_t blocks = (n_cand + per_block - 1) / per_block;
+    if (blocks > 0x7fffffffll) return FPSCHED_EINVAL;
+    hipLaunchKernelGGL(slot_kernel_ptr(p->slot_v), dim3((unsigned)blocks), dim3(kSlotThreads),
+                       (size_t)p->slot_lds_bytes, static_cast<hipStream_t>(hip_stream), p->tables, d_ops,
+                       (long long)n_cand, (int)stride_words, reinterpret_cast<long long*>(out.makespan),
+                       reinterpret_cast<long long*>(out.idle), out.peak, out.flags);
+    return check_hip(hipGetLastError());
+  }
   const int cpw = p->tables.cands_per_wave;
   const int64_t blocks = (n_cand + cpw - 1) / cpw;
   if (blocks > 0x7fffffffll) return FPSCHED_EINVAL;

@@ -18,6 +18,15 @@ __global__ void eval_general_kernel(DevTables T, const uint16_t* ops, long long 
                                     long long* out_makespan, long long* out_idle, int* out_peak,
                                     unsigned char* out_flags);
 
+constexpr int kSlotWaves = 4;
+constexpr int kSlotThreads = 64 * kSlotWaves;
+
+// V = compile-time bound on the stages (chunks) per device: 1, 2 or 4.
+template <int V>
+__global__ void eval_slot_kernel(DevTables T, const uint16_t* ops, long long n_cand, int stride,
+                                 long long* out_makespan, long long* out_idle, int* out_peak,
+                                 unsigned char* out_flags);
+
 __global__ void topk_tile_kernel(const long long* in_makespan, const unsigned char* in_flags,
                                  const Key* in_keys, long long n, int k, Key* out_keys,
                                  long long* final_idx, long long* final_makespan, int* final_count);

@@ -6,11 +6,21 @@ import oracle
 import paper_2510_05112_amd as fp
 
 
-def gpu_evaluate(problem, words, k=None, max_stride=None):
+KERNELS = ("slots", "general")
+
+
+def gpu_evaluate(problem, words, k=None, max_stride=None, kernel="auto"):
     """words: uint16 [C][D][stride] (numpy).  Returns (results dict of numpy arrays, topk tuple or None)."""
     words = np.ascontiguousarray(words, dtype=np.uint16)
     C, D, stride = words.shape
     h = fp.Problem(problem, max_stride or stride, device=0)
+    try:
+        h.select_kernel(kernel)
+    except fp.FpschedError as e:
+        if e.code != -6:   # this kernel's on-chip tables do not fit the problem
+            raise
+        h.close()
+        return None, None
     ops = torch.from_numpy(words.view(np.int16)).cuda() if C else torch.empty((0, D, stride), dtype=torch.int16, device="cuda")
     res = h.evaluate(ops)
     top = None
@@ -33,13 +43,20 @@ def assert_same(gpu, ref, what=""):
                                  f"gpu {a[bad[0]]} oracle {b[bad[0]]}")
 
 
-def check_batch(problem, words, k=None, what="", threads=8):
-    gpu, top = gpu_evaluate(problem, words, k)
+def check_batch(problem, words, k=None, what="", threads=8, kernels=KERNELS):
+    """Every kernel variant of the library against the oracle, element by element."""
     ref = oracle.evaluate(problem, words, threads=threads)
-    assert_same(gpu, ref, what)
-    if k is not None:
-        idx, ms, cnt = oracle.topk(ref["makespan"], ref["flags"], k)
-        assert top[2] == cnt, what
-        assert np.array_equal(top[0], idx), what
-        assert np.array_equal(top[1], ms), what
+    gpu, ran = None, 0
+    for kernel in kernels:
+        g, top = gpu_evaluate(problem, words, k, kernel=kernel)
+        if g is None:
+            continue
+        gpu, ran = g, ran + 1
+        assert_same(gpu, ref, f"{what} [{kernel}]")
+        if k is not None:
+            idx, ms, cnt = oracle.topk(ref["makespan"], ref["flags"], k)
+            assert top[2] == cnt, what
+            assert np.array_equal(top[0], idx), what
+            assert np.array_equal(top[1], ms), what
+    assert ran > 0, f"{what}: no kernel variant supports this problem"
     return gpu, ref
