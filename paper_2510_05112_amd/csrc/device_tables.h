@@ -35,14 +35,38 @@ struct DevTables {
   int32_t off_local_stage;  // [D][kMaxChunks], -1 = none
   int32_t off_n_chunks;     // [D]
   int32_t off_mem_cap;      // [D]
-  int32_t off_pred_cls;     // [E]  slot class of the edge (pred CSR order)
-  int32_t off_succ_cls;     // [E]  slot class of the edge (succ CSR order)
-  // slot kernel geometry
+  const int32_t* ints;      // DEVICE
+};
+
+// Slot kernel tables.  `ints` = [meta][meta2][pad][dev]:
+//   meta  [kNKinds*V][lanes_per_cand] x 4 ints, one entry per (kind, chunk, device):
+//     x = dur          y = latency of the first input edge
+//     z = slot offset of the first output (16) | tag of the first input (8) << 16 | kMeta* flags
+//     w = required state (4) | next state (4) << 4 | own stage (8) << 8 | activation units (16) << 16
+//   meta2 [2*V][lanes_per_cand] x 2 ints, second input/output edge per (direction, chunk, device):
+//     x = latency of the second input edge
+//     y = slot offset of the second output (16) | tag of the second input (8) << 16 | flags
+//   dev   [lanes_per_cand] x (2 + 4V) ints: chunks on the device, memory cap, then per chunk the
+//     slot offsets of the first forward / first backward / second forward / second backward input
+// Slot offsets count 8-byte slots from the candidate's slot base: (dir * classes + class) * m.
+constexpr unsigned kMetaHasCons = 1u << 24;
+constexpr unsigned kMetaAlloc = 1u << 25;
+constexpr unsigned kMetaFree = 1u << 26;
+constexpr unsigned kMetaTerminal = 1u << 27;
+constexpr unsigned kMetaInvalid = 1u << 28;
+constexpr unsigned kMetaHasProd = 1u << 29;
+
+struct SlotTables {
+  int32_t D, m;
+  int32_t lanes_per_cand;   // power of two >= D
+  int32_t cands_per_wave;
   int32_t n_classes;        // slot classes (1 for a chain)
   int32_t state_words;      // dwords of 4-bit activation states per lane
-  int32_t slot_cands_per_wave;
-  int32_t wave_ints;        // LDS dwords owned by one wavefront in the slot kernel
-  int32_t table_ints_padded;
+  int32_t wave_ints;        // LDS dwords owned by one wavefront
+  int32_t n_shared_ints;    // meta + meta2 (+ pad), copied to LDS once per workgroup
+  int32_t off_meta2;        // in ints
+  int32_t off_dev;          // in ints
+  int32_t dev_ints;         // 2 + 4V
   const int32_t* ints;      // DEVICE
 };
 

@@ -26,7 +26,11 @@ struct fpsched_problem {
   bool general_ok = false, slots_ok = false;  // which kernels fit this problem in LDS
   bool use_slots = false;          // selected kernel: slot kernel (default when it fits) or general
   int32_t slot_v = 0;              // template bound on chunks per device
+  bool slot_deg2 = false;          // some stage has two inputs or two outputs
   int32_t slot_lds_bytes = 0;      // dynamic LDS of one slot-kernel workgroup
+  SlotTables stab{};
+  std::vector<int32_t> slot_ints;
+  int32_t* d_slot_ints = nullptr;
 };
 
 namespace {
@@ -46,10 +50,11 @@ struct DeviceGuard {
   }
 };
 
-using SlotKernel = void (*)(DevTables, const uint16_t*, long long, int, long long*, long long*, int*,
+using SlotKernel = void (*)(SlotTables, const uint16_t*, long long, int, long long*, long long*, int*,
                             unsigned char*);
-SlotKernel slot_kernel_ptr(int v) {
-  return v == 1 ? &eval_slot_kernel<1> : (v == 2 ? &eval_slot_kernel<2> : &eval_slot_kernel<4>);
+SlotKernel slot_kernel_ptr(int v, bool deg2) {
+  if (deg2) return v == 1 ? &eval_slot_kernel<1, true> : (v == 2 ? &eval_slot_kernel<2, true> : &eval_slot_kernel<4, true>);
+  return v == 1 ? &eval_slot_kernel<1, false> : (v == 2 ? &eval_slot_kernel<2, false> : &eval_slot_kernel<4, false>);
 }
 
 int next_pow2(int x) {
@@ -191,19 +196,7 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
     }
     if (n_classes == 0) n_classes = 1;
   }
-  {
-    std::vector<int32_t> pcl(E), scl(E), pf(S, 0), sf(S, 0);
-    for (int e = 0; e < E; ++e) {
-      const int a = desc->edge_src[e], b = desc->edge_dst[e];
-      pcl[poff[b] + pf[b]++] = edge_cls[e];
-      scl[soff[a] + sf[a]++] = edge_cls[e];
-    }
-    T.off_pred_cls = append(pcl.data(), E);
-    T.off_succ_cls = append(scl.data(), E);
-  }
-  T.n_classes = n_classes;
   T.n_table_ints = (int32_t)I.size();
-  T.table_ints_padded = (T.n_table_ints + 3) & ~3;
   T.lanes_per_cand = next_pow2(D);
   T.cands_per_wave = 64 / T.lanes_per_cand;
 
@@ -224,23 +217,110 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
     p->general_ok = table_bytes + cpw * per_cand <= max_lds;
     T.cands_per_wave = cpw;
     p->lds_bytes = (int32_t)(table_bytes + cpw * per_cand);
-    // slot kernel geometry: per wave, a 16-dword op window and the 4-bit state words per
-    // lane, plus 2 * classes * m eight-byte slots per candidate
-    int max_chunks = 1;
-    for (int d = 0; d < D; ++d) max_chunks = std::max(max_chunks, p->n_chunks[d]);
-    p->slot_v = max_chunks <= 1 ? 1 : (max_chunks <= 2 ? 2 : 4);
-    T.state_words = (p->slot_v * m + 7) / 8;
+    // ---- slot kernel: metadata per (kind, chunk, device), geometry, fit ----
     {
-      int scpw = 64 / T.lanes_per_cand;
-      const int64_t fixed = 64ll * (16 + T.state_words);
+      SlotTables& ST = p->stab;
+      int max_chunks = 1;
+      for (int d = 0; d < D; ++d) max_chunks = std::max(max_chunks, p->n_chunks[d]);
+      const int V = p->slot_v = max_chunks <= 1 ? 1 : (max_chunks <= 2 ? 2 : 4);
+      const int lpc = T.lanes_per_cand;
+      bool fits = 2ll * n_classes * m <= 0xffff;
+      bool deg2 = false;
+      for (int s = 0; s < S; ++s) {
+        const int nin = poff[s + 1] - poff[s], nout = soff[s + 1] - soff[s];
+        if (nin > 2 || nout > 2) fits = false;
+        if (nin > 1 || nout > 1) deg2 = true;
+        if (desc->mem_units[s] > 0xffff) fits = false;
+      }
+      p->slot_deg2 = deg2;
+      // classes of the edges in pred-CSR and succ-CSR order
+      std::vector<int32_t> pcl(E), scl(E);
+      {
+        std::vector<int32_t> pf(S, 0), sf(S, 0);
+        for (int e = 0; e < E; ++e) {
+          const int a = desc->edge_src[e], b = desc->edge_dst[e];
+          pcl[poff[b] + pf[b]++] = edge_cls[e];
+          scl[soff[a] + sf[a]++] = edge_cls[e];
+        }
+      }
+      const int n_meta = kNKinds * V * lpc * 4;
+      const int n_meta2 = deg2 ? 2 * V * lpc * 2 : 0;
+      const int dev_ints = 2 + 4 * V;
+      std::vector<int32_t>& J = p->slot_ints;
+      J.assign((size_t)n_meta + n_meta2 + (size_t)lpc * dev_ints, 0);
+      static const int need_of[kNKinds] = {15, kAbsent, kRes, kBDone, kDisc, kRes, kOff, kAbsent};
+      static const int next_of[kNKinds] = {0, kRes, kBDone, kDone, kRes, kOff, kRes, kDisc};
+      for (int kind = 0; kind < kNKinds; ++kind)
+        for (int c = 0; c < V; ++c)
+          for (int d = 0; d < lpc; ++d) {
+            int32_t* e = &J[(((size_t)kind * V + c) * lpc + d) * 4];
+            e[2] = (int32_t)kMetaInvalid;
+            e[3] = 15;
+            if (d >= D || c >= p->n_chunks[d] || kind == kEnd || (kind == kW && !p->has_w)) continue;
+            const int s = p->local_stage[(size_t)d * kMaxChunks + c];
+            unsigned z = 0;
+            int comm = 0;
+            if (kind == kF || kind == kFD || kind == kR || kind == kL) z |= kMetaAlloc;
+            if (kind == kFD || kind == kO || kind == (p->has_w ? kW : kB)) z |= kMetaFree;
+            if (kind == (p->has_w ? kW : kB)) z |= kMetaTerminal;
+            if (kind == kF || kind == kFD) {
+              if (poff[s + 1] > poff[s]) { z |= kMetaHasCons | ((unsigned)pst[poff[s]] << 16); comm = pcm[poff[s]]; }
+              if (soff[s + 1] > soff[s]) z |= kMetaHasProd | (unsigned)(scl[soff[s]] * m);
+            } else if (kind == kB) {
+              if (soff[s + 1] > soff[s]) { z |= kMetaHasCons | ((unsigned)sst[soff[s]] << 16); comm = scm[soff[s]]; }
+              if (poff[s + 1] > poff[s]) z |= kMetaHasProd | (unsigned)((n_classes + pcl[poff[s]]) * m);
+            }
+            e[0] = desc->dur[kind * S + s];
+            e[1] = comm;
+            e[2] = (int32_t)z;
+            e[3] = (int32_t)((unsigned)need_of[kind] | ((unsigned)next_of[kind] << 4) | ((unsigned)s << 8) |
+                             ((unsigned)(desc->mem_units[s] & 0xffff) << 16));
+          }
+      for (int dir = 0; dir < 2 && deg2; ++dir)
+        for (int c = 0; c < V; ++c)
+          for (int d = 0; d < D; ++d) {
+            if (c >= p->n_chunks[d]) continue;
+            const int s = p->local_stage[(size_t)d * kMaxChunks + c];
+            int32_t* e = &J[(size_t)n_meta + (((size_t)dir * V + c) * lpc + d) * 2];
+            unsigned y = 0;
+            if (dir == 0) {
+              if (poff[s + 1] - poff[s] > 1) { y |= kMetaHasCons | ((unsigned)pst[poff[s] + 1] << 16); e[0] = pcm[poff[s] + 1]; }
+              if (soff[s + 1] - soff[s] > 1) y |= kMetaHasProd | (unsigned)(scl[soff[s] + 1] * m);
+            } else {
+              if (soff[s + 1] - soff[s] > 1) { y |= kMetaHasCons | ((unsigned)sst[soff[s] + 1] << 16); e[0] = scm[soff[s] + 1]; }
+              if (poff[s + 1] - poff[s] > 1) y |= kMetaHasProd | (unsigned)((n_classes + pcl[poff[s] + 1]) * m);
+            }
+            e[1] = (int32_t)y;
+          }
+      for (int d = 0; d < D; ++d) {
+        int32_t* e = &J[(size_t)n_meta + n_meta2 + (size_t)d * dev_ints];
+        e[0] = p->n_chunks[d];
+        e[1] = desc->mem_cap[d];
+        for (int c = 0; c < p->n_chunks[d]; ++c) {
+          const int s = p->local_stage[(size_t)d * kMaxChunks + c];
+          const int nin = poff[s + 1] - poff[s], nout = soff[s + 1] - soff[s];
+          e[2 + c] = nin > 0 ? pcl[poff[s]] * m : 0;
+          e[2 + V + c] = nout > 0 ? (n_classes + scl[soff[s]]) * m : 0;
+          e[2 + 2 * V + c] = nin > 1 ? pcl[poff[s] + 1] * m : 0;
+          e[2 + 3 * V + c] = nout > 1 ? (n_classes + scl[soff[s] + 1]) * m : 0;
+        }
+      }
+      ST.D = D; ST.m = m; ST.lanes_per_cand = lpc; ST.n_classes = n_classes;
+      ST.state_words = (V * m + 7) / 8;
+      ST.n_shared_ints = n_meta + n_meta2;
+      ST.off_meta2 = n_meta;
+      ST.off_dev = n_meta + n_meta2;
+      ST.dev_ints = dev_ints;
+      int scpw = 64 / lpc;
+      const int64_t fixed = 64ll * (16 + ST.state_words);
       const int64_t per_slot_cand = 2ll * 2 * n_classes * m;  // dwords
-      const int64_t budget_ints = (max_lds - 4ll * T.table_ints_padded) / 4 / kSlotWaves;
+      const int64_t budget_ints = (max_lds / 4 - ST.n_shared_ints) / kSlotWaves;
       while (scpw > 1 && fixed + scpw * per_slot_cand > budget_ints) scpw >>= 1;
       const int64_t wave_ints = fixed + scpw * per_slot_cand;
-      const int64_t block_bytes = 4ll * T.table_ints_padded + 4 * kSlotWaves * wave_ints;
-      p->slots_ok = block_bytes <= max_lds;
-      T.slot_cands_per_wave = scpw;
-      T.wave_ints = (int32_t)wave_ints;
+      const int64_t block_bytes = 4ll * (ST.n_shared_ints + kSlotWaves * wave_ints);
+      p->slots_ok = fits && block_bytes <= max_lds;
+      ST.cands_per_wave = scpw;
+      ST.wave_ints = (int32_t)wave_ints;
       p->slot_lds_bytes = (int32_t)block_bytes;
     }
     if (!p->general_ok && !p->slots_ok) { delete p; return FPSCHED_EUNSUPPORTED; }
@@ -250,10 +330,20 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
     if (ok && p->general_ok)
       ok = hipFuncSetAttribute(reinterpret_cast<const void*>(&eval_general_kernel),
                                hipFuncAttributeMaxDynamicSharedMemorySize, p->lds_bytes) == hipSuccess;
-    if (ok && p->slots_ok)
-      ok = hipFuncSetAttribute(reinterpret_cast<const void*>(slot_kernel_ptr(p->slot_v)),
+    if (ok && p->slots_ok) {
+      ok = hipMalloc(&p->d_slot_ints, p->slot_ints.size() * sizeof(int32_t)) == hipSuccess &&
+           hipMemcpy(p->d_slot_ints, p->slot_ints.data(), p->slot_ints.size() * sizeof(int32_t),
+                     hipMemcpyHostToDevice) == hipSuccess &&
+           hipFuncSetAttribute(reinterpret_cast<const void*>(slot_kernel_ptr(p->slot_v, p->slot_deg2)),
                                hipFuncAttributeMaxDynamicSharedMemorySize, p->slot_lds_bytes) == hipSuccess;
-    if (!ok) { (void)hipFree(p->d_ints); delete p; return FPSCHED_EHIP; }
+      p->stab.ints = p->d_slot_ints;
+    }
+    if (!ok) {
+      (void)hipFree(p->d_ints);
+      if (p->d_slot_ints) (void)hipFree(p->d_slot_ints);
+      delete p;
+      return FPSCHED_EHIP;
+    }
     T.ints = p->d_ints;
   }
   *out = p;
@@ -262,9 +352,10 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
 
 void fpsched_problem_destroy(fpsched_problem* p) {
   if (!p) return;
-  if (p->d_ints) {
+  if (p->d_ints || p->d_slot_ints) {
     DeviceGuard g(p->device_id);
-    (void)hipFree(p->d_ints);
+    if (p->d_ints) (void)hipFree(p->d_ints);
+    if (p->d_slot_ints) (void)hipFree(p->d_slot_ints);
   }
   delete p;
 }
@@ -274,7 +365,7 @@ int fpsched_problem_info(const fpsched_problem* p, int32_t* lanes_per_candidate,
   if (!p) return FPSCHED_EINVAL;
   const bool slots = p->use_slots;
   if (lanes_per_candidate) *lanes_per_candidate = p->tables.lanes_per_cand;
-  if (candidates_per_wave) *candidates_per_wave = slots ? p->tables.slot_cands_per_wave : p->tables.cands_per_wave;
+  if (candidates_per_wave) *candidates_per_wave = slots ? p->stab.cands_per_wave : p->tables.cands_per_wave;
   if (lds_bytes_per_wave) *lds_bytes_per_wave = slots ? p->slot_lds_bytes / kSlotWaves : p->lds_bytes;
   return FPSCHED_OK;
 }
@@ -319,11 +410,11 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
   DeviceGuard g(p->device_id);
   if (!g.ok) return FPSCHED_EHIP;
   if (p->use_slots) {
-    const int per_block = p->tables.slot_cands_per_wave * kSlotWaves;
+    const int per_block = p->stab.cands_per_wave * kSlotWaves;
     const int64_t blocks = (n_cand + per_block - 1) / per_block;
     if (blocks > 0x7fffffffll) return FPSCHED_EINVAL;
-    hipLaunchKernelGGL(slot_kernel_ptr(p->slot_v), dim3((unsigned)blocks), dim3(kSlotThreads),
-                       (size_t)p->slot_lds_bytes, static_cast<hipStream_t>(hip_stream), p->tables, d_ops,
+    hipLaunchKernelGGL(slot_kernel_ptr(p->slot_v, p->slot_deg2), dim3((unsigned)blocks), dim3(kSlotThreads),
+                       (size_t)p->slot_lds_bytes, static_cast<hipStream_t>(hip_stream), p->stab, d_ops,
                        (long long)n_cand, (int)stride_words, reinterpret_cast<long long*>(out.makespan),
                        reinterpret_cast<long long*>(out.idle), out.peak, out.flags);
     return check_hip(hipGetLastError());

@@ -21,9 +21,10 @@ __global__ void eval_general_kernel(DevTables T, const uint16_t* ops, long long 
 constexpr int kSlotWaves = 4;
 constexpr int kSlotThreads = 64 * kSlotWaves;
 
-// V = compile-time bound on the stages (chunks) per device: 1, 2 or 4.
-template <int V>
-__global__ void eval_slot_kernel(DevTables T, const uint16_t* ops, long long n_cand, int stride,
+// V = compile-time bound on the stages (chunks) per device: 1, 2 or 4.  DEG2 = some stage
+// has two inputs or two outputs in the stage DAG.
+template <int V, bool DEG2>
+__global__ void eval_slot_kernel(SlotTables T, const uint16_t* ops, long long n_cand, int stride,
                                  long long* out_makespan, long long* out_idle, int* out_peak,
                                  unsigned char* out_flags);
 
