@@ -39,16 +39,20 @@ struct DevTables {
 };
 
 // Slot kernel tables.  `ints` = [meta][meta2][pad][dev]:
-//   meta  [kNKinds*V][lanes_per_cand] x 4 ints, one entry per (kind, chunk, device):
+//   meta  [kNKinds * 4][lanes_per_cand] x 4 ints, indexed by the top five bits of the op word
+//     (kind * 4 + chunk) and the device:
 //     x = dur          y = latency of the first input edge
-//     z = slot offset of the first output (16) | tag of the first input (8) << 16 | kMeta* flags
+//     z = slot offset of the first output, or of the dump slot (16) | tag of the first input (8) << 16
+//         | kMeta* flags
 //     w = required state (4) | next state (4) << 4 | own stage (8) << 8 | activation units (16) << 16
-//   meta2 [2*V][lanes_per_cand] x 2 ints, second input/output edge per (direction, chunk, device):
+//   meta2 [2 * 4][lanes_per_cand] x 2 ints, second input/output edge per (direction, chunk, device):
 //     x = latency of the second input edge
 //     y = slot offset of the second output (16) | tag of the second input (8) << 16 | flags
 //   dev   [lanes_per_cand] x (2 + 4V) ints: chunks on the device, memory cap, then per chunk the
 //     slot offsets of the first forward / first backward / second forward / second backward input
-// Slot offsets count 8-byte slots from the candidate's slot base: (dir * classes + class) * m.
+// A slot is one dword, finish << 8 | producer stage; offsets count slots from the candidate's
+// slot base: (dir * classes + class) * m; the dump slot (written by ops without an output edge,
+// never read) sits at 2 * classes * m.
 constexpr unsigned kMetaHasCons = 1u << 24;
 constexpr unsigned kMetaAlloc = 1u << 25;
 constexpr unsigned kMetaFree = 1u << 26;
@@ -61,6 +65,7 @@ struct SlotTables {
   int32_t lanes_per_cand;   // power of two >= D
   int32_t cands_per_wave;
   int32_t n_classes;        // slot classes (1 for a chain)
+  int32_t slots_per_cand;   // 2 * classes * m + 1
   int32_t state_words;      // dwords of 4-bit activation states per lane
   int32_t wave_ints;        // LDS dwords owned by one wavefront
   int32_t n_shared_ints;    // meta + meta2 (+ pad), copied to LDS once per workgroup

@@ -1,11 +1,14 @@
 // Slot evaluation kernel: the main path.  Any per-device op order, any stage DAG with
 // at most two inputs and two outputs per stage, a few KB of LDS per candidate.
 //
-// Mapping: one wavefront owns `slot_cands_per_wave` candidates, lane = device inside a
-// candidate; four independent wavefronts share a workgroup (and one LDS copy of the
-// op-metadata table).  Each lane walks its device's list with a cursor in registers; a
-// lane whose next op cannot issue yet waits for a later round, and a round in which no
-// lane of a candidate moves ends that candidate (lists exhausted, or deadlock).
+// Mapping: a wavefront carries `cands_per_wave` candidate segments, lane = device inside
+// a segment; the wavefronts of a workgroup are independent and only share one LDS copy
+// of the op-metadata table.  The grid is persistent: segment g evaluates candidates g,
+// g + G, g + 2G, ... (G = segments in the grid), restarting on its next candidate while
+// the other segments of the wavefront keep going.  Each lane walks its device's list
+// with a cursor in registers; a lane whose next op cannot issue yet waits for a later
+// round, and a round in which no lane of a segment moves ends that candidate (lists
+// exhausted, or deadlock).
 //
 // Cross-stage finish times travel through per-micro-batch mail slots.  The edges of
 // the stage DAG are split on the host into classes (chains of edges in which each edge
@@ -13,9 +16,10 @@
 // one micro-batch at most one edge of a class carries a live value at a time -- the
 // value of F(a,j) on edge a->b is dead once F(b,j) has issued, and only then can the
 // next edge of the class be produced -- so a class needs ONE slot per micro-batch and
-// direction, tagged with the stage that produced it: slot[dir][class][j] = (finish,
-// producer stage).  A consumer finds its input iff the tag names its upstream stage.
-// No order of micro-batches is assumed and a producer never has to wait for room.
+// direction, tagged with the stage that produced it: slot[dir][class][j] =
+// finish << 8 | producer stage.  A consumer finds its input iff the tag names its
+// upstream stage.  No order of micro-batches is assumed and a producer never has to
+// wait for room.
 //
 // Same-device ordering rules are the activation state machine of one (stage,
 // micro-batch), 4 bits per entry, in lane-private LDS words.  Op words are staged
@@ -47,42 +51,44 @@ __device__ __forceinline__ int pick(const int (&a)[V], int c) {
   return r;
 }
 
+constexpr unsigned kEmptySlot = 0xffffffffu;  // tag 0xff names no stage
+
 }  // namespace
 
 template <int V, bool DEG2>
-__global__ __launch_bounds__(kSlotThreads) void eval_slot_kernel(
+__global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     SlotTables T, const uint16_t* __restrict__ ops, long long n_cand, int stride,
     long long* __restrict__ out_makespan, long long* __restrict__ out_idle,
     int* __restrict__ out_peak, unsigned char* __restrict__ out_flags) {
   extern __shared__ int32_t lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n_waves = blockDim.x >> 6;
   const int m = T.m;
   const int cpw = T.cands_per_wave;
   const int lpc = T.lanes_per_cand;
   const int lpc_shift = __ffs(lpc) - 1;
 
   // shared: op metadata (+ second-edge metadata); per wave: window, state words, slots
-  for (int i = tid; i < T.n_shared_ints; i += kSlotThreads) lds[i] = T.ints[i];
+  for (int i = tid; i < T.n_shared_ints; i += blockDim.x) lds[i] = T.ints[i];
   const int4* meta = reinterpret_cast<const int4*>(lds);
   const int2* meta2 = reinterpret_cast<const int2*>(lds + T.off_meta2);
   uint32_t* win = reinterpret_cast<uint32_t*>(lds + T.n_shared_ints + wave * T.wave_ints);
   uint32_t* stt = win + 16 * 64;
-  int2* slots = reinterpret_cast<int2*>(stt + T.state_words * 64);
-  const int slots_per_cand = 2 * T.n_classes * m;
-  for (int i = lane; i < T.state_words * 64; i += 64) stt[i] = 0u;
-  for (int i = lane; i < cpw * slots_per_cand; i += 64) slots[i] = make_int2(0, -1);
+  uint32_t* slots = stt + T.state_words * 64;
+  const int slots_per_cand = T.slots_per_cand;  // 2 * classes * m, + 1 write-only dump slot
   __syncthreads();
 
   const int seg = lane >> lpc_shift;
   const int d = lane & (lpc - 1);
-  const long long cand = ((long long)blockIdx.x * kSlotWaves + wave) * cpw + seg;
-  const bool active = (seg < cpw) && (d < T.D) && (cand < n_cand);
-  int2* my_slots = slots + (seg < cpw ? seg : 0) * slots_per_cand;
+  const bool lane_ok = (seg < cpw) && (d < T.D);
+  uint32_t* my_slots = slots + (seg < cpw ? seg : 0) * slots_per_cand;
+  const long long n_segments = (long long)gridDim.x * n_waves * cpw;
+  long long cand = ((long long)blockIdx.x * n_waves + wave) * cpw + seg;
 
   // per-device constants: chunk count, cap, slot offsets of the inputs of each chunk
-  const int32_t* dev = T.ints + T.off_dev + d * T.dev_ints;
-  const int nch = dev[0];
-  const int cap = dev[1];
+  const int32_t* dev = T.ints + T.off_dev + (d < T.D ? d : 0) * T.dev_ints;
+  int nch = dev[0];
+  int cap = dev[1];
   int cons_f[V], cons_b[V], cons_f2[V], cons_b2[V];
 #pragma unroll
   for (int c = 0; c < V; ++c) {
@@ -90,33 +96,62 @@ __global__ __launch_bounds__(kSlotThreads) void eval_slot_kernel(
     cons_b[c] = dev[2 + V + c];
     cons_f2[c] = DEG2 ? dev[2 + 2 * V + c] : 0;
     cons_b2[c] = DEG2 ? dev[2 + 3 * V + c] : 0;
+    // have the constants in registers before the loop: a wait for them inside the loop would
+    // also wait for the op-window prefetch
+    asm volatile("" : "+v"(cons_f[c]), "+v"(cons_b[c]), "+v"(cons_f2[c]), "+v"(cons_b2[c]));
   }
-  const int dd = active ? d : 0;
-  const uint16_t* row = ops + ((size_t)(active ? cand : 0) * T.D + dd) * (size_t)stride;
+  asm volatile("" : "+v"(nch), "+v"(cap));
   const unsigned long long seg_mask =
       (lpc == 64 ? ~0ull : ((1ull << lpc) - 1ull)) << (seg * lpc);
 
-  // prime the op window with the first 16 words of the row
+  // per-candidate registers
+  const uint16_t* row = ops;
   int loaded = 0;  // words of this row already in the window ring
-#pragma unroll
-  for (int q = 0; q < 2; ++q) {
-    if (active && loaded < stride) {
-      const uint4 v = *reinterpret_cast<const uint4*>(row + loaded);
-      win[(q * 4 + 0) * 64 + lane] = v.x;
-      win[(q * 4 + 1) * 64 + lane] = v.y;
-      win[(q * 4 + 2) * 64 + lane] = v.z;
-      win[(q * 4 + 3) * 64 + lane] = v.w;
-      loaded += 8;
-    }
-  }
   uint4 pend = make_uint4(0, 0, 0, 0);
   bool has_pend = false;
-
   int cursor = 0, free_at = 0, busy = 0, mem = 0, pk = 0, n_term = 0;
-  bool done = !active, bad = false, seg_live = true;
-  unsigned w = (active && stride > 0) ? (win[lane] & 0xffffu) : 0u;
+  bool done = true, bad = false;
+  bool running = false;  // this lane's segment is evaluating a candidate
+  bool retired = true;   // this lane takes no part (no device, or its segment ran out of work)
+  bool fresh = true;     // (re)start the segment on `cand` at the top of the next round
+  unsigned w = 0u;
 
   for (unsigned round = 0;; ++round) {
+    // ---- (re)start segments on their next candidate
+    if (__ballot(fresh) != 0ull) {
+      if (fresh) {
+        fresh = false;
+        const bool seg_has_work = (seg < cpw) && (cand < n_cand);
+        running = seg_has_work;
+        retired = !(lane_ok && seg_has_work);
+        done = retired;
+        bad = false;
+        cursor = 0; free_at = 0; busy = 0; mem = 0; pk = 0; n_term = 0;
+        has_pend = false;
+        loaded = 0;
+        w = 0u;
+        if (seg_has_work) {
+          for (int i = d; i < slots_per_cand; i += lpc) my_slots[i] = kEmptySlot;
+        }
+        if (!retired) {
+          for (int i = 0; i < T.state_words; ++i) stt[i * 64 + lane] = 0u;
+          row = ops + ((size_t)cand * T.D + d) * (size_t)stride;
+#pragma unroll
+          for (int q = 0; q < 3; ++q) {
+            if (loaded < stride) {
+              const uint4 v = *reinterpret_cast<const uint4*>(row + loaded);
+              win[(q * 4 + 0) * 64 + lane] = v.x;
+              win[(q * 4 + 1) * 64 + lane] = v.y;
+              win[(q * 4 + 2) * 64 + lane] = v.z;
+              win[(q * 4 + 3) * 64 + lane] = v.w;
+              if (q == 0) w = v.x & 0xffffu;
+              loaded += 8;
+            }
+          }
+        }
+      }
+      if (__ballot(running) == 0ull) break;  // every segment of the wave is out of work
+    }
     if ((round & 7u) == 0u) {
       // wave-wide top-up: land the chunk requested eight rounds ago, request the next
       if (has_pend) {
@@ -139,87 +174,98 @@ __global__ __launch_bounds__(kSlotThreads) void eval_slot_kernel(
     const int j = w & 0x7ff;
     const bool is_b = kind == kB;
     const int nxt = cursor + 1;
-    const unsigned nx = win[((nxt >> 1) & 15) * 64 + lane];
-    const int cc = c < V ? c : 0;
-    const int4 M = meta[(kind * V + cc) * lpc + d];
-    const int jj = j < m ? j : 0;
-    const int idx = cc * m + jj;
+    unsigned nx = win[((nxt >> 1) & 15) * 64 + lane];
+    int4 M = meta[((w >> 11) << lpc_shift) + d];
+    const int jj = min(j, m - 1);
+    const int idx = (int)__umul24((unsigned)(c & (V - 1)), (unsigned)m) + jj;
     const int sw = (idx >> 3) * 64 + lane;
     const int sh = (idx & 7) * 4;
-    const unsigned sx = stt[sw];
+    unsigned sx = stt[sw];
     const int coff = is_b ? pick<V>(cons_b, c) : pick<V>(cons_f, c);
-    const int2 in1 = my_slots[coff + jj];
-    int2 M2 = make_int2(0, 0), in2 = make_int2(0, 0);
+    unsigned in1 = my_slots[coff + jj];
+    int2 M2 = make_int2(0, 0);
+    unsigned in2 = 0u;
     if (DEG2) {
-      M2 = meta2[((is_b ? V : 0) + cc) * lpc + d];
+      M2 = meta2[(((is_b ? 4 : 0) + c) << lpc_shift) + d];
       const int coff2 = is_b ? pick<V>(cons_b2, c) : pick<V>(cons_f2, c);
       in2 = my_slots[coff2 + jj];
+      asm volatile("" : "+v"(M2.x), "+v"(M2.y), "+v"(in2));
     }
+    // keep every load of the round in front of the decision (one LDS round trip per round)
+    asm volatile("" : "+v"(nx), "+v"(M.x), "+v"(M.y), "+v"(M.z), "+v"(M.w), "+v"(sx), "+v"(in1));
     // ---- decide
     const unsigned fl = (unsigned)M.z;
-    const bool live = !done && seg_live;
     const bool is_end = kind == kEnd;
-    const bool wellformed = !(fl & kMetaInvalid) && j < m && c < nch;
+    const bool wellformed = !(fl & kMetaInvalid) && j < m;
     const unsigned st = (sx >> sh) & 15u;
-    bool ok = live && !is_end && wellformed && st == ((unsigned)M.w & 15u);
+    bool ok = !done && !is_end && wellformed && st == ((unsigned)M.w & 15u);
     int ready = 0;
     if (fl & kMetaHasCons) {
-      ok = ok && in1.y == (int)((fl >> 16) & 0xffu);
-      ready = in1.x + M.y;
+      ok = ok && (in1 & 0xffu) == ((fl >> 16) & 0xffu);
+      ready = (int)(in1 >> 8) + M.y;
     }
     if (DEG2) {
       if ((unsigned)M2.y & kMetaHasCons) {
-        ok = ok && in2.y == (int)(((unsigned)M2.y >> 16) & 0xffu);
-        ready = max(ready, in2.x + M2.x);
+        ok = ok && (in2 & 0xffu) == (((unsigned)M2.y >> 16) & 0xffu);
+        ready = max(ready, (int)(in2 >> 8) + M2.x);
       }
     }
-    const bool newly_done = live && is_end;
+    const bool newly_done = !done && is_end;
+    bad = bad || (!done && !is_end && !wellformed);
     done = done || newly_done;
-    bad = bad || (live && !is_end && !wellformed);
     // ---- issue
+    const int dt = M.x;
+    const int u = (int)((unsigned)M.w >> 16);
+    const unsigned self = ((unsigned)M.w >> 8) & 0xffu;
+    const int fin = max(free_at, ready) + dt;
+    const unsigned w_next = nxt < stride ? ((nxt & 1) ? (nx >> 16) : (nx & 0xffffu)) : 0u;
     if (ok) {
-      const int dt = M.x;
-      const int u = (int)((unsigned)M.w >> 16);
-      const int self = (int)(((unsigned)M.w >> 8) & 0xffu);
-      const int fin = max(free_at, ready) + dt;
       mem += (fl & kMetaAlloc) ? u : 0;
       pk = max(pk, mem);
       mem -= (fl & kMetaFree) ? u : 0;
       stt[sw] = sx ^ ((st ^ (((unsigned)M.w >> 4) & 15u)) << sh);
-      if (fl & kMetaHasProd) my_slots[(fl & 0xffffu) + j] = make_int2(fin, self);
+      // ops without an output edge write to the candidate's dump slot
+      my_slots[(fl & 0xffffu) + ((fl & kMetaHasProd) ? j : 0)] = ((unsigned)fin << 8) | self;
       if (DEG2) {
-        if ((unsigned)M2.y & kMetaHasProd) my_slots[((unsigned)M2.y & 0xffffu) + j] = make_int2(fin, self);
+        if ((unsigned)M2.y & kMetaHasProd) my_slots[((unsigned)M2.y & 0xffffu) + j] = ((unsigned)fin << 8) | self;
       }
-      n_term += (fl & kMetaTerminal) ? 1 : 0;
+      n_term += (int)((fl >> 27) & 1u);
       free_at = fin;
       busy += dt;
       cursor = nxt;
-      w = nxt < stride ? ((nxt & 1) ? (nx >> 16) : (nx & 0xffffu)) : 0u;
+      w = w_next;
     }
     __builtin_amdgcn_wave_barrier();
     const unsigned long long moved = __ballot(ok || newly_done);
-    if ((moved & seg_mask) == 0ull) seg_live = false;
-    if (moved == 0ull) break;
-  }
-
-  const unsigned long long stuck = __ballot(active && !done) & seg_mask;
-  const unsigned long long stuck_bad = __ballot(active && !done && bad) & seg_mask;
-  const unsigned long long unfinished = __ballot(active && n_term != nch * m) & seg_mask;
-  const unsigned long long over = __ballot(active && pk > cap) & seg_mask;
-  int ms = active ? free_at : 0;
-  for (int off = 1; off < lpc; off <<= 1) ms = max(ms, __shfl_xor(ms, off, 64));
-
-  unsigned flg = 0;
-  if (stuck) flg = kDeadlock | (stuck_bad ? kIncomplete : 0);
-  else if (unfinished) flg = kIncomplete;
-  else if (over) flg = kOverCap;
-  if (active) {
-    const bool failed = (flg & (kDeadlock | kIncomplete)) != 0;
-    out_idle[cand * T.D + d] = failed ? -1ll : (long long)(ms - busy);
-    out_peak[cand * T.D + d] = failed ? -1 : pk;
-    if (d == 0) {
-      out_makespan[cand] = failed ? 0x7fffffffffffffffll : (long long)ms;
-      out_flags[cand] = (unsigned char)flg;
+    const bool seg_ended = running && (moved & seg_mask) == 0ull;
+    if (__ballot(seg_ended) != 0ull) {
+      // ---- per-candidate reductions over the segment's lanes, outputs, next candidate
+      const unsigned long long stuck = __ballot(!retired && !done) & seg_mask;
+      const unsigned long long stuck_bad = __ballot(!retired && !done && bad) & seg_mask;
+      const unsigned long long unfinished = __ballot(!retired && n_term != nch * m) & seg_mask;
+      const unsigned long long over = __ballot(!retired && pk > cap) & seg_mask;
+      int ms = retired ? 0 : free_at;
+      for (int off = 1; off < lpc; off <<= 1) ms = max(ms, __shfl_xor(ms, off, 64));
+      if (seg_ended) {
+        unsigned flg = 0;
+        if (stuck) flg = kDeadlock | (stuck_bad ? kIncomplete : 0);
+        else if (unfinished) flg = kIncomplete;
+        else if (over) flg = kOverCap;
+        if (!retired) {
+          const bool failed = (flg & (kDeadlock | kIncomplete)) != 0;
+          out_idle[cand * T.D + d] = failed ? -1ll : (long long)(ms - busy);
+          out_peak[cand * T.D + d] = failed ? -1 : pk;
+          if (d == 0) {
+            out_makespan[cand] = failed ? 0x7fffffffffffffffll : (long long)ms;
+            out_flags[cand] = (unsigned char)flg;
+          }
+        }
+        cand += n_segments;
+        running = false;
+        retired = true;
+        done = true;
+        fresh = true;
+      }
     }
   }
 }

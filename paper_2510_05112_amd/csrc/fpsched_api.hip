@@ -28,6 +28,8 @@ struct fpsched_problem {
   int32_t slot_v = 0;              // template bound on chunks per device
   bool slot_deg2 = false;          // some stage has two inputs or two outputs
   int32_t slot_lds_bytes = 0;      // dynamic LDS of one slot-kernel workgroup
+  int32_t slot_waves = 0;          // wavefronts per slot-kernel workgroup
+  int32_t slot_grid = 0;           // resident workgroups: the persistent grid
   SlotTables stab{};
   std::vector<int32_t> slot_ints;
   int32_t* d_slot_ints = nullptr;
@@ -224,7 +226,9 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
       for (int d = 0; d < D; ++d) max_chunks = std::max(max_chunks, p->n_chunks[d]);
       const int V = p->slot_v = max_chunks <= 1 ? 1 : (max_chunks <= 2 ? 2 : 4);
       const int lpc = T.lanes_per_cand;
-      bool fits = 2ll * n_classes * m <= 0xffff;
+      // slot offsets are 16-bit, tags 8-bit (0xff = empty), finish times 24-bit
+      bool fits = 2ll * n_classes * m + 1 <= 0xffff && S <= 255 &&
+                  (int64_t)D * max_stride_words * (max_dur + max_comm) < (1ll << 24);
       bool deg2 = false;
       for (int s = 0; s < S; ++s) {
         const int nin = poff[s + 1] - poff[s], nout = soff[s + 1] - soff[s];
@@ -243,17 +247,18 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
           scl[soff[a] + sf[a]++] = edge_cls[e];
         }
       }
-      const int n_meta = kNKinds * V * lpc * 4;
-      const int n_meta2 = deg2 ? 2 * V * lpc * 2 : 0;
+      const int n_meta = kNKinds * kMaxChunks * lpc * 4;
+      const int n_meta2 = deg2 ? 2 * kMaxChunks * lpc * 2 : 0;
+      const unsigned dump_slot = (unsigned)(2 * n_classes * m);
       const int dev_ints = 2 + 4 * V;
       std::vector<int32_t>& J = p->slot_ints;
       J.assign((size_t)n_meta + n_meta2 + (size_t)lpc * dev_ints, 0);
       static const int need_of[kNKinds] = {15, kAbsent, kRes, kBDone, kDisc, kRes, kOff, kAbsent};
       static const int next_of[kNKinds] = {0, kRes, kBDone, kDone, kRes, kOff, kRes, kDisc};
       for (int kind = 0; kind < kNKinds; ++kind)
-        for (int c = 0; c < V; ++c)
+        for (int c = 0; c < kMaxChunks; ++c)
           for (int d = 0; d < lpc; ++d) {
-            int32_t* e = &J[(((size_t)kind * V + c) * lpc + d) * 4];
+            int32_t* e = &J[(((size_t)kind * kMaxChunks + c) * lpc + d) * 4];
             e[2] = (int32_t)kMetaInvalid;
             e[3] = 15;
             if (d >= D || c >= p->n_chunks[d] || kind == kEnd || (kind == kW && !p->has_w)) continue;
@@ -263,13 +268,15 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
             if (kind == kF || kind == kFD || kind == kR || kind == kL) z |= kMetaAlloc;
             if (kind == kFD || kind == kO || kind == (p->has_w ? kW : kB)) z |= kMetaFree;
             if (kind == (p->has_w ? kW : kB)) z |= kMetaTerminal;
+            unsigned prod = dump_slot;
             if (kind == kF || kind == kFD) {
               if (poff[s + 1] > poff[s]) { z |= kMetaHasCons | ((unsigned)pst[poff[s]] << 16); comm = pcm[poff[s]]; }
-              if (soff[s + 1] > soff[s]) z |= kMetaHasProd | (unsigned)(scl[soff[s]] * m);
+              if (soff[s + 1] > soff[s]) { z |= kMetaHasProd; prod = (unsigned)(scl[soff[s]] * m); }
             } else if (kind == kB) {
               if (soff[s + 1] > soff[s]) { z |= kMetaHasCons | ((unsigned)sst[soff[s]] << 16); comm = scm[soff[s]]; }
-              if (poff[s + 1] > poff[s]) z |= kMetaHasProd | (unsigned)((n_classes + pcl[poff[s]]) * m);
+              if (poff[s + 1] > poff[s]) { z |= kMetaHasProd; prod = (unsigned)((n_classes + pcl[poff[s]]) * m); }
             }
+            z |= prod;
             e[0] = desc->dur[kind * S + s];
             e[1] = comm;
             e[2] = (int32_t)z;
@@ -277,11 +284,11 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
                              ((unsigned)(desc->mem_units[s] & 0xffff) << 16));
           }
       for (int dir = 0; dir < 2 && deg2; ++dir)
-        for (int c = 0; c < V; ++c)
+        for (int c = 0; c < kMaxChunks; ++c)
           for (int d = 0; d < D; ++d) {
             if (c >= p->n_chunks[d]) continue;
             const int s = p->local_stage[(size_t)d * kMaxChunks + c];
-            int32_t* e = &J[(size_t)n_meta + (((size_t)dir * V + c) * lpc + d) * 2];
+            int32_t* e = &J[(size_t)n_meta + (((size_t)dir * kMaxChunks + c) * lpc + d) * 2];
             unsigned y = 0;
             if (dir == 0) {
               if (poff[s + 1] - poff[s] > 1) { y |= kMetaHasCons | ((unsigned)pst[poff[s] + 1] << 16); e[0] = pcm[poff[s] + 1]; }
@@ -306,22 +313,36 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
         }
       }
       ST.D = D; ST.m = m; ST.lanes_per_cand = lpc; ST.n_classes = n_classes;
+      ST.slots_per_cand = 2 * n_classes * m + 1;
       ST.state_words = (V * m + 7) / 8;
       ST.n_shared_ints = n_meta + n_meta2;
       ST.off_meta2 = n_meta;
       ST.off_dev = n_meta + n_meta2;
       ST.dev_ints = dev_ints;
+      // geometry: candidates per wave, then the workgroup shape that keeps the most
+      // wavefronts resident on a compute unit (LDS is the only limiter: ~50 VGPRs)
       int scpw = 64 / lpc;
       const int64_t fixed = 64ll * (16 + ST.state_words);
-      const int64_t per_slot_cand = 2ll * 2 * n_classes * m;  // dwords
-      const int64_t budget_ints = (max_lds / 4 - ST.n_shared_ints) / kSlotWaves;
-      while (scpw > 1 && fixed + scpw * per_slot_cand > budget_ints) scpw >>= 1;
-      const int64_t wave_ints = fixed + scpw * per_slot_cand;
-      const int64_t block_bytes = 4ll * (ST.n_shared_ints + kSlotWaves * wave_ints);
-      p->slots_ok = fits && block_bytes <= max_lds;
+      const int64_t lds_ints = max_lds / 4;
+      while (scpw > 1 && ST.n_shared_ints + fixed + (int64_t)scpw * ST.slots_per_cand > lds_ints) scpw >>= 1;
+      const int64_t wave_ints = fixed + (int64_t)scpw * ST.slots_per_cand;
+      int best_waves = 0, best_groups = 0, best_total = 0;
+      for (int groups = 1; groups <= 8; ++groups) {
+        const int64_t per_group = lds_ints / groups - ST.n_shared_ints - 64;  // allocation slack
+        int wv = per_group > 0 ? (int)std::min<int64_t>(per_group / wave_ints, kSlotMaxWaves) : 0;
+        wv = std::min(wv, 32 / groups);  // 8 wavefronts per SIMD, 4 SIMDs per compute unit
+        if (wv * groups > best_total) { best_total = wv * groups; best_waves = wv; best_groups = groups; }
+      }
+      p->slots_ok = fits && best_waves >= 1;
       ST.cands_per_wave = scpw;
       ST.wave_ints = (int32_t)wave_ints;
-      p->slot_lds_bytes = (int32_t)block_bytes;
+      p->slot_waves = best_waves;
+      p->slot_lds_bytes = (int32_t)(4ll * (ST.n_shared_ints + (int64_t)best_waves * wave_ints));
+      int n_cu = 0;
+      if (hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, p->device_id) != hipSuccess || n_cu < 1) {
+        delete p; return FPSCHED_EHIP;
+      }
+      p->slot_grid = n_cu * std::max(best_groups, 1);
     }
     if (!p->general_ok && !p->slots_ok) { delete p; return FPSCHED_EUNSUPPORTED; }
     p->use_slots = p->slots_ok;
@@ -366,7 +387,7 @@ int fpsched_problem_info(const fpsched_problem* p, int32_t* lanes_per_candidate,
   const bool slots = p->use_slots;
   if (lanes_per_candidate) *lanes_per_candidate = p->tables.lanes_per_cand;
   if (candidates_per_wave) *candidates_per_wave = slots ? p->stab.cands_per_wave : p->tables.cands_per_wave;
-  if (lds_bytes_per_wave) *lds_bytes_per_wave = slots ? p->slot_lds_bytes / kSlotWaves : p->lds_bytes;
+  if (lds_bytes_per_wave) *lds_bytes_per_wave = slots ? p->slot_lds_bytes / std::max(p->slot_waves, 1) : p->lds_bytes;
   return FPSCHED_OK;
 }
 
@@ -410,10 +431,9 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
   DeviceGuard g(p->device_id);
   if (!g.ok) return FPSCHED_EHIP;
   if (p->use_slots) {
-    const int per_block = p->stab.cands_per_wave * kSlotWaves;
-    const int64_t blocks = (n_cand + per_block - 1) / per_block;
-    if (blocks > 0x7fffffffll) return FPSCHED_EINVAL;
-    hipLaunchKernelGGL(slot_kernel_ptr(p->slot_v, p->slot_deg2), dim3((unsigned)blocks), dim3(kSlotThreads),
+    const int per_block = p->stab.cands_per_wave * p->slot_waves;
+    const int64_t blocks = std::min<int64_t>((n_cand + per_block - 1) / per_block, p->slot_grid);
+    hipLaunchKernelGGL(slot_kernel_ptr(p->slot_v, p->slot_deg2), dim3((unsigned)blocks), dim3(64 * p->slot_waves),
                        (size_t)p->slot_lds_bytes, static_cast<hipStream_t>(hip_stream), p->stab, d_ops,
                        (long long)n_cand, (int)stride_words, reinterpret_cast<long long*>(out.makespan),
                        reinterpret_cast<long long*>(out.idle), out.peak, out.flags);

@@ -18,8 +18,8 @@ __global__ void eval_general_kernel(DevTables T, const uint16_t* ops, long long 
                                     long long* out_makespan, long long* out_idle, int* out_peak,
                                     unsigned char* out_flags);
 
-constexpr int kSlotWaves = 4;
-constexpr int kSlotThreads = 64 * kSlotWaves;
+constexpr int kSlotMaxWaves = 16;
+constexpr int kSlotMaxThreads = 64 * kSlotMaxWaves;
 
 // V = compile-time bound on the stages (chunks) per device: 1, 2 or 4.  DEG2 = some stage
 // has two inputs or two outputs in the stage DAG.
