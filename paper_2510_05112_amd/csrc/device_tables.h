@@ -38,40 +38,44 @@ struct DevTables {
   const int32_t* ints;      // DEVICE
 };
 
-// Slot kernel tables.  `ints` = [meta][meta2][pad][dev]:
-//   meta  [kNKinds * 4][lanes_per_cand] x 4 ints, indexed by the top five bits of the op word
-//     (kind * 4 + chunk) and the device:
-//     x = dur          y = latency of the first input edge
-//     z = slot offset of the first output, or of the dump slot (16) | tag of the first input (8) << 16
-//         | kMeta* flags
-//     w = required state (4) | next state (4) << 4 | own stage (8) << 8 | activation units (16) << 16
+// Slot kernel tables.  `ints` = [meta][meta2][dev][expect]:
+//   meta  [kNKinds * 4][lanes_per_cand] x 4 ints, one 16-byte row per (top five bits of the op
+//     word = kind * 4 + chunk, device):
+//     x = dur
+//     y = latency of the first input edge (20) | state transition need ^ next (4) << 20
+//         | tag expected on the first input (8) << 24
+//     z = slot offset of the first output, or of the dump region (16) | own stage (8) << 16
+//         | required state (4) << 24 | kMeta* flags
+//     w = units allocated at the op's start (16) | units freed at its end (16) << 16
+//     Rows of words that may not appear on the device (no such chunk, kind 0, W without split
+//     backward) carry kMetaInvalid and require state 15, which no activation is ever in.
 //   meta2 [2 * 4][lanes_per_cand] x 2 ints, second input/output edge per (direction, chunk, device):
 //     x = latency of the second input edge
 //     y = slot offset of the second output (16) | tag of the second input (8) << 16 | flags
 //   dev   [lanes_per_cand] x (2 + 4V) ints: chunks on the device, memory cap, then per chunk the
 //     slot offsets of the first forward / first backward / second forward / second backward input
+//   expect [lanes_per_cand][state_words]: the device's state words when every activation is done
 // A slot is one dword, finish << 8 | producer stage; offsets count slots from the candidate's
-// slot base: (dir * classes + class) * m; the dump slot (written by ops without an output edge,
-// never read) sits at 2 * classes * m.
-constexpr unsigned kMetaHasCons = 1u << 24;
-constexpr unsigned kMetaAlloc = 1u << 25;
-constexpr unsigned kMetaFree = 1u << 26;
-constexpr unsigned kMetaTerminal = 1u << 27;
-constexpr unsigned kMetaInvalid = 1u << 28;
-constexpr unsigned kMetaHasProd = 1u << 29;
+// slot base: (dir * classes + class) * m; the dump region (written by ops without an output
+// edge, never read) starts at 2 * classes * m.
+constexpr unsigned kMetaHasCons = 1u << 28;
+constexpr unsigned kMetaInvalid = 1u << 30;
+constexpr unsigned kMetaHasProd = 1u << 31;
+constexpr unsigned kEmptySlot = 0x000000ffu;  // finish 0, tag 0xff = no stage
 
 struct SlotTables {
   int32_t D, m;
   int32_t lanes_per_cand;   // power of two >= D
   int32_t cands_per_wave;
   int32_t n_classes;        // slot classes (1 for a chain)
-  int32_t slots_per_cand;   // 2 * classes * m + 1
+  int32_t slots_per_cand;   // (2 * classes + 1) * m
   int32_t state_words;      // dwords of 4-bit activation states per lane
   int32_t wave_ints;        // LDS dwords owned by one wavefront
   int32_t n_shared_ints;    // meta + meta2 (+ pad), copied to LDS once per workgroup
   int32_t off_meta2;        // in ints
   int32_t off_dev;          // in ints
   int32_t dev_ints;         // 2 + 4V
+  int32_t off_expect;       // in ints
   const int32_t* ints;      // DEVICE
 };
 

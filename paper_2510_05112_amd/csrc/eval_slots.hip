@@ -29,7 +29,11 @@
 //
 // A round is straight-line code: the LDS reads of a round (next op word, op metadata,
 // state word, input slots) depend only on registers and are issued together, so a
-// round costs one LDS round trip.
+// round costs one LDS round trip.  Everything a round needs to know about an op --
+// duration, latency, expected input tag, state transition, memory deltas, output slot --
+// comes from one 16-byte metadata row addressed by the top five bits of the op word
+// and the device.  Whether a candidate completed (every activation consumed) and
+// whether a stuck device sits on a malformed word are decided once, when it ends.
 //
 // Start rule (paper Section 5.1 "Data dependency"; estimator sketch after Section 6):
 // start = max(device free, finish of each cross-stage input + latency if the input ran
@@ -51,11 +55,9 @@ __device__ __forceinline__ int pick(const int (&a)[V], int c) {
   return r;
 }
 
-constexpr unsigned kEmptySlot = 0xffffffffu;  // tag 0xff names no stage
-
 }  // namespace
 
-template <int V, bool DEG2>
+template <int V, bool DEG2, bool ONE_CLASS>
 __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     SlotTables T, const uint16_t* __restrict__ ops, long long n_cand, int stride,
     long long* __restrict__ out_makespan, long long* __restrict__ out_idle,
@@ -70,12 +72,13 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
 
   // shared: op metadata (+ second-edge metadata); per wave: window, state words, slots
   for (int i = tid; i < T.n_shared_ints; i += blockDim.x) lds[i] = T.ints[i];
-  const int4* meta = reinterpret_cast<const int4*>(lds);
+  const char* lds_bytes = reinterpret_cast<const char*>(lds);
   const int2* meta2 = reinterpret_cast<const int2*>(lds + T.off_meta2);
-  uint32_t* win = reinterpret_cast<uint32_t*>(lds + T.n_shared_ints + wave * T.wave_ints);
-  uint32_t* stt = win + 16 * 64;
+  // window: 32 sixteen-bit words per lane, laid out [word][lane]
+  uint16_t* win = reinterpret_cast<uint16_t*>(lds + T.n_shared_ints + wave * T.wave_ints);
+  uint32_t* stt = reinterpret_cast<uint32_t*>(win) + 16 * 64;   // [state word][lane]
   uint32_t* slots = stt + T.state_words * 64;
-  const int slots_per_cand = T.slots_per_cand;  // 2 * classes * m, + 1 write-only dump slot
+  const int slots_per_cand = T.slots_per_cand;  // (2 * classes + 1) * m: forward, backward, dump
   __syncthreads();
 
   const int seg = lane >> lpc_shift;
@@ -85,9 +88,10 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   const long long n_segments = (long long)gridDim.x * n_waves * cpw;
   long long cand = ((long long)blockIdx.x * n_waves + wave) * cpw + seg;
 
-  // per-device constants: chunk count, cap, slot offsets of the inputs of each chunk
-  const int32_t* dev = T.ints + T.off_dev + (d < T.D ? d : 0) * T.dev_ints;
-  int nch = dev[0];
+  // per-device constants: memory cap, slot offsets of the inputs of each chunk
+  const int dd = d < T.D ? d : 0;
+  const int32_t* dev = T.ints + T.off_dev + dd * T.dev_ints;
+  const int32_t* expect = T.ints + T.off_expect + dd * T.state_words;
   int cap = dev[1];
   int cons_f[V], cons_b[V], cons_f2[V], cons_b2[V];
 #pragma unroll
@@ -100,54 +104,66 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     // also wait for the op-window prefetch
     asm volatile("" : "+v"(cons_f[c]), "+v"(cons_b[c]), "+v"(cons_f2[c]), "+v"(cons_b2[c]));
   }
-  asm volatile("" : "+v"(nch), "+v"(cap));
+  asm volatile("" : "+v"(cap));
   const unsigned long long seg_mask =
       (lpc == 64 ? ~0ull : ((1ull << lpc) - 1ull)) << (seg * lpc);
+  const int meta_shift = 7 - lpc_shift;                 // op word >> this = row offset in bytes
+  const unsigned meta_mask = 0xF800u >> meta_shift;     // (kind, chunk) bits of that offset
+  const unsigned meta_lane = (unsigned)d << 4;
+  const int words_per_chunk = (m + 7) >> 3;
 
   // per-candidate registers
   const uint16_t* row = ops;
   int loaded = 0;  // words of this row already in the window ring
   uint4 pend = make_uint4(0, 0, 0, 0);
   bool has_pend = false;
-  int cursor = 0, free_at = 0, busy = 0, mem = 0, pk = 0, n_term = 0;
-  bool done = true, bad = false;
+  int cursor = 0, free_at = 0, busy = 0, mem = 0, pk = 0;
   bool running = false;  // this lane's segment is evaluating a candidate
-  bool retired = true;   // this lane takes no part (no device, or its segment ran out of work)
+  bool live = false;     // ... and this lane carries one of its devices
   bool fresh = true;     // (re)start the segment on `cand` at the top of the next round
-  unsigned w = 0u;
+  unsigned w = 0u;       // current op word; 0 = list exhausted (or lane idle)
 
-  for (unsigned round = 0;; ++round) {
+  // Every candidate ends after at most D * stride + 2 rounds (each round but its last issues at
+  // least one of its at most D * stride ops), so the bound below is never reached; it only makes
+  // sure the wavefront leaves the loop whatever happens.
+  const unsigned long long per_cand_rounds = (unsigned long long)T.D * (unsigned)stride + 8ull;
+  const unsigned long long my_cands = (unsigned long long)((n_cand + n_segments - 1) / n_segments) + 1ull;
+  const unsigned long long bound = per_cand_rounds * my_cands;
+  const unsigned max_rounds = bound > 0xfffffff0ull ? 0xfffffff0u : (unsigned)bound;
+  for (unsigned round = 0; round < max_rounds; ++round) {
     // ---- (re)start segments on their next candidate
     if (__ballot(fresh) != 0ull) {
       if (fresh) {
         fresh = false;
-        const bool seg_has_work = (seg < cpw) && (cand < n_cand);
-        running = seg_has_work;
-        retired = !(lane_ok && seg_has_work);
-        done = retired;
-        bad = false;
-        cursor = 0; free_at = 0; busy = 0; mem = 0; pk = 0; n_term = 0;
+        running = (seg < cpw) && (cand < n_cand);
+        live = running && lane_ok;
+        cursor = 0; free_at = 0; busy = 0; mem = 0; pk = 0;
         has_pend = false;
         loaded = 0;
         w = 0u;
-        if (seg_has_work) {
+        if (running) {
           for (int i = d; i < slots_per_cand; i += lpc) my_slots[i] = kEmptySlot;
         }
-        if (!retired) {
+        if (live) {
           for (int i = 0; i < T.state_words; ++i) stt[i * 64 + lane] = 0u;
           row = ops + ((size_t)cand * T.D + d) * (size_t)stride;
 #pragma unroll
           for (int q = 0; q < 3; ++q) {
             if (loaded < stride) {
               const uint4 v = *reinterpret_cast<const uint4*>(row + loaded);
-              win[(q * 4 + 0) * 64 + lane] = v.x;
-              win[(q * 4 + 1) * 64 + lane] = v.y;
-              win[(q * 4 + 2) * 64 + lane] = v.z;
-              win[(q * 4 + 3) * 64 + lane] = v.w;
+              uint32_t* dst = reinterpret_cast<uint32_t*>(win);
+              // [word][lane] with 16-bit elements: word k of lane l at k * 64 + l
+              win[(q * 8 + 0) * 64 + lane] = (uint16_t)v.x; win[(q * 8 + 1) * 64 + lane] = (uint16_t)(v.x >> 16);
+              win[(q * 8 + 2) * 64 + lane] = (uint16_t)v.y; win[(q * 8 + 3) * 64 + lane] = (uint16_t)(v.y >> 16);
+              win[(q * 8 + 4) * 64 + lane] = (uint16_t)v.z; win[(q * 8 + 5) * 64 + lane] = (uint16_t)(v.z >> 16);
+              win[(q * 8 + 6) * 64 + lane] = (uint16_t)v.w; win[(q * 8 + 7) * 64 + lane] = (uint16_t)(v.w >> 16);
+              (void)dst;
               if (q == 0) w = v.x & 0xffffu;
               loaded += 8;
             }
           }
+          // a row that fills its stride has no END word: plant one behind it
+          if (loaded >= stride) win[(stride & 31) * 64 + lane] = 0;
         }
       }
       if (__ballot(running) == 0ull) break;  // every segment of the wave is out of work
@@ -155,33 +171,32 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     if ((round & 7u) == 0u) {
       // wave-wide top-up: land the chunk requested eight rounds ago, request the next
       if (has_pend) {
-        const int q = (loaded >> 3) & 3;
-        win[(q * 4 + 0) * 64 + lane] = pend.x;
-        win[(q * 4 + 1) * 64 + lane] = pend.y;
-        win[(q * 4 + 2) * 64 + lane] = pend.z;
-        win[(q * 4 + 3) * 64 + lane] = pend.w;
+        const int q = loaded & 31;
+        win[(q + 0) * 64 + lane] = (uint16_t)pend.x; win[(q + 1) * 64 + lane] = (uint16_t)(pend.x >> 16);
+        win[(q + 2) * 64 + lane] = (uint16_t)pend.y; win[(q + 3) * 64 + lane] = (uint16_t)(pend.y >> 16);
+        win[(q + 4) * 64 + lane] = (uint16_t)pend.z; win[(q + 5) * 64 + lane] = (uint16_t)(pend.z >> 16);
+        win[(q + 6) * 64 + lane] = (uint16_t)pend.w; win[(q + 7) * 64 + lane] = (uint16_t)(pend.w >> 16);
         loaded += 8;
         has_pend = false;
+        if (loaded >= stride) win[(stride & 31) * 64 + lane] = 0;
       }
-      if (!done && loaded - cursor <= 17 && loaded < stride) {
+      if (w != 0u && loaded - cursor <= 17 && loaded < stride) {
         pend = *reinterpret_cast<const uint4*>(row + loaded);
         has_pend = true;
       }
     }
     // ---- decode the current word (already in a register) and issue this round's reads
-    const int kind = w >> 13;
     const int c = (w >> 11) & 3;
     const int j = w & 0x7ff;
-    const bool is_b = kind == kB;
+    const bool is_b = (w >> 13) == (unsigned)kB;
     const int nxt = cursor + 1;
-    unsigned nx = win[((nxt >> 1) & 15) * 64 + lane];
-    int4 M = meta[((w >> 11) << lpc_shift) + d];
+    unsigned w_next = win[(nxt & 31) * 64 + lane];
+    int4 M = *reinterpret_cast<const int4*>(lds_bytes + (((w >> meta_shift) & meta_mask) | meta_lane));
     const int jj = min(j, m - 1);
-    const int idx = (int)__umul24((unsigned)(c & (V - 1)), (unsigned)m) + jj;
-    const int sw = (idx >> 3) * 64 + lane;
-    const int sh = (idx & 7) * 4;
+    const int sw = ((int)__umul24((unsigned)(c & (V - 1)), (unsigned)words_per_chunk) + (jj >> 3)) * 64 + lane;
+    const int sh = (jj & 7) * 4;
     unsigned sx = stt[sw];
-    const int coff = is_b ? pick<V>(cons_b, c) : pick<V>(cons_f, c);
+    const int coff = ONE_CLASS ? (is_b ? m : 0) : (is_b ? pick<V>(cons_b, c) : pick<V>(cons_f, c));
     unsigned in1 = my_slots[coff + jj];
     int2 M2 = make_int2(0, 0);
     unsigned in2 = 0u;
@@ -192,17 +207,17 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       asm volatile("" : "+v"(M2.x), "+v"(M2.y), "+v"(in2));
     }
     // keep every load of the round in front of the decision (one LDS round trip per round)
-    asm volatile("" : "+v"(nx), "+v"(M.x), "+v"(M.y), "+v"(M.z), "+v"(M.w), "+v"(sx), "+v"(in1));
-    // ---- decide
-    const unsigned fl = (unsigned)M.z;
-    const bool is_end = kind == kEnd;
-    const bool wellformed = !(fl & kMetaInvalid) && j < m;
+    asm volatile("" : "+v"(w_next), "+v"(M.x), "+v"(M.y), "+v"(M.z), "+v"(M.w), "+v"(sx), "+v"(in1));
+    // ---- decide.  An exhausted lane has w == 0, whose metadata row is invalid; invalid rows
+    // require state 15, which no activation is ever in.  Lanes without a device (and idle
+    // segments) never initialise their LDS words, so they are masked off explicitly.
+    const unsigned my = (unsigned)M.y, mz = (unsigned)M.z;
     const unsigned st = (sx >> sh) & 15u;
-    bool ok = !done && !is_end && wellformed && st == ((unsigned)M.w & 15u);
+    bool ok = live && (st == ((mz >> 24) & 15u)) && j < m;
     int ready = 0;
-    if (fl & kMetaHasCons) {
-      ok = ok && (in1 & 0xffu) == ((fl >> 16) & 0xffu);
-      ready = (int)(in1 >> 8) + M.y;
+    if (mz & kMetaHasCons) {
+      ok = ok && (in1 & 0xffu) == (my >> 24);
+      ready = (int)(in1 >> 8) + (int)(my & 0xfffffu);
     }
     if (DEG2) {
       if ((unsigned)M2.y & kMetaHasCons) {
@@ -210,48 +225,49 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
         ready = max(ready, (int)(in2 >> 8) + M2.x);
       }
     }
-    const bool newly_done = !done && is_end;
-    bad = bad || (!done && !is_end && !wellformed);
-    done = done || newly_done;
     // ---- issue
-    const int dt = M.x;
-    const int u = (int)((unsigned)M.w >> 16);
-    const unsigned self = ((unsigned)M.w >> 8) & 0xffu;
-    const int fin = max(free_at, ready) + dt;
-    const unsigned w_next = nxt < stride ? ((nxt & 1) ? (nx >> 16) : (nx & 0xffffu)) : 0u;
     if (ok) {
-      mem += (fl & kMetaAlloc) ? u : 0;
+      const int dt = M.x;
+      const int fin = max(free_at, ready) + dt;
+      mem += (int)((unsigned)M.w & 0xffffu);
       pk = max(pk, mem);
-      mem -= (fl & kMetaFree) ? u : 0;
-      stt[sw] = sx ^ ((st ^ (((unsigned)M.w >> 4) & 15u)) << sh);
-      // ops without an output edge write to the candidate's dump slot
-      my_slots[(fl & 0xffffu) + ((fl & kMetaHasProd) ? j : 0)] = ((unsigned)fin << 8) | self;
+      mem -= (int)((unsigned)M.w >> 16);
+      stt[sw] = sx ^ (((my >> 20) & 15u) << sh);
+      const unsigned val = ((unsigned)fin << 8) | ((mz >> 16) & 0xffu);
+      my_slots[(mz & 0xffffu) + j] = val;   // ops without an output edge write the dump region
       if (DEG2) {
-        if ((unsigned)M2.y & kMetaHasProd) my_slots[((unsigned)M2.y & 0xffffu) + j] = ((unsigned)fin << 8) | self;
+        if ((unsigned)M2.y & kMetaHasProd) my_slots[((unsigned)M2.y & 0xffffu) + j] = val;
       }
-      n_term += (int)((fl >> 27) & 1u);
       free_at = fin;
       busy += dt;
       cursor = nxt;
       w = w_next;
     }
     __builtin_amdgcn_wave_barrier();
-    const unsigned long long moved = __ballot(ok || newly_done);
+    const unsigned long long moved = __ballot(ok);
     const bool seg_ended = running && (moved & seg_mask) == 0ull;
     if (__ballot(seg_ended) != 0ull) {
-      // ---- per-candidate reductions over the segment's lanes, outputs, next candidate
-      const unsigned long long stuck = __ballot(!retired && !done) & seg_mask;
-      const unsigned long long stuck_bad = __ballot(!retired && !done && bad) & seg_mask;
-      const unsigned long long unfinished = __ballot(!retired && n_term != nch * m) & seg_mask;
-      const unsigned long long over = __ballot(!retired && pk > cap) & seg_mask;
-      int ms = retired ? 0 : free_at;
+      // ---- the candidate is over: lists exhausted or nothing can move any more
+      bool bad_head = false, incomplete = false;
+      if (seg_ended && lane_ok) {
+        // a stuck device sits on a malformed word?
+        const int4 Mh = *reinterpret_cast<const int4*>(lds_bytes + (((w >> meta_shift) & meta_mask) | meta_lane));
+        bad_head = w != 0u && (((unsigned)Mh.z & kMetaInvalid) || (int)(w & 0x7ff) >= m);
+        // every activation of this device consumed?
+        for (int i = 0; i < T.state_words; ++i) incomplete = incomplete || (stt[i * 64 + lane] != (unsigned)expect[i]);
+      }
+      const unsigned long long stuck = __ballot(lane_ok && w != 0u) & seg_mask;
+      const unsigned long long stuck_bad = __ballot(bad_head) & seg_mask;
+      const unsigned long long unfinished = __ballot(incomplete) & seg_mask;
+      const unsigned long long over = __ballot(lane_ok && pk > cap) & seg_mask;
+      int ms = lane_ok ? free_at : 0;
       for (int off = 1; off < lpc; off <<= 1) ms = max(ms, __shfl_xor(ms, off, 64));
       if (seg_ended) {
         unsigned flg = 0;
         if (stuck) flg = kDeadlock | (stuck_bad ? kIncomplete : 0);
         else if (unfinished) flg = kIncomplete;
         else if (over) flg = kOverCap;
-        if (!retired) {
+        if (lane_ok) {
           const bool failed = (flg & (kDeadlock | kIncomplete)) != 0;
           out_idle[cand * T.D + d] = failed ? -1ll : (long long)(ms - busy);
           out_peak[cand * T.D + d] = failed ? -1 : pk;
@@ -262,23 +278,26 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
         }
         cand += n_segments;
         running = false;
-        retired = true;
-        done = true;
+        live = false;
+        w = 0u;
         fresh = true;
       }
     }
   }
 }
 
-#define FPSCHED_INSTANTIATE(V, G)                                                               \
-  template __global__ void eval_slot_kernel<V, G>(SlotTables, const uint16_t*, long long, int,  \
-                                                  long long*, long long*, int*, unsigned char*);
-FPSCHED_INSTANTIATE(1, false)
-FPSCHED_INSTANTIATE(2, false)
-FPSCHED_INSTANTIATE(4, false)
-FPSCHED_INSTANTIATE(1, true)
-FPSCHED_INSTANTIATE(2, true)
-FPSCHED_INSTANTIATE(4, true)
+#define FPSCHED_INSTANTIATE(V, G, O)                                                               \
+  template __global__ void eval_slot_kernel<V, G, O>(SlotTables, const uint16_t*, long long, int,  \
+                                                     long long*, long long*, int*, unsigned char*);
+FPSCHED_INSTANTIATE(1, false, true)
+FPSCHED_INSTANTIATE(2, false, true)
+FPSCHED_INSTANTIATE(4, false, true)
+FPSCHED_INSTANTIATE(1, false, false)
+FPSCHED_INSTANTIATE(2, false, false)
+FPSCHED_INSTANTIATE(4, false, false)
+FPSCHED_INSTANTIATE(1, true, false)
+FPSCHED_INSTANTIATE(2, true, false)
+FPSCHED_INSTANTIATE(4, true, false)
 #undef FPSCHED_INSTANTIATE
 
 }  // namespace fpsched

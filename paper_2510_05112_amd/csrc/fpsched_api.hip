@@ -54,9 +54,15 @@ struct DeviceGuard {
 
 using SlotKernel = void (*)(SlotTables, const uint16_t*, long long, int, long long*, long long*, int*,
                             unsigned char*);
-SlotKernel slot_kernel_ptr(int v, bool deg2) {
-  if (deg2) return v == 1 ? &eval_slot_kernel<1, true> : (v == 2 ? &eval_slot_kernel<2, true> : &eval_slot_kernel<4, true>);
-  return v == 1 ? &eval_slot_kernel<1, false> : (v == 2 ? &eval_slot_kernel<2, false> : &eval_slot_kernel<4, false>);
+SlotKernel slot_kernel_ptr(int v, bool deg2, bool one_class) {
+  if (deg2)
+    return v == 1 ? &eval_slot_kernel<1, true, false>
+                  : (v == 2 ? &eval_slot_kernel<2, true, false> : &eval_slot_kernel<4, true, false>);
+  if (one_class)
+    return v == 1 ? &eval_slot_kernel<1, false, true>
+                  : (v == 2 ? &eval_slot_kernel<2, false, true> : &eval_slot_kernel<4, false, true>);
+  return v == 1 ? &eval_slot_kernel<1, false, false>
+                : (v == 2 ? &eval_slot_kernel<2, false, false> : &eval_slot_kernel<4, false, false>);
 }
 
 int next_pow2(int x) {
@@ -227,7 +233,7 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
       const int V = p->slot_v = max_chunks <= 1 ? 1 : (max_chunks <= 2 ? 2 : 4);
       const int lpc = T.lanes_per_cand;
       // slot offsets are 16-bit, tags 8-bit (0xff = empty), finish times 24-bit
-      bool fits = 2ll * n_classes * m + 1 <= 0xffff && S <= 255 &&
+      bool fits = (2ll * n_classes + 1) * m <= 0xffff && S <= 255 && max_comm < (1ll << 20) &&
                   (int64_t)D * max_stride_words * (max_dur + max_comm) < (1ll << 24);
       bool deg2 = false;
       for (int s = 0; s < S; ++s) {
@@ -251,37 +257,35 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
       const int n_meta2 = deg2 ? 2 * kMaxChunks * lpc * 2 : 0;
       const unsigned dump_slot = (unsigned)(2 * n_classes * m);
       const int dev_ints = 2 + 4 * V;
+      const int words_per_chunk = (m + 7) / 8;
+      const int state_words = V * words_per_chunk;
       std::vector<int32_t>& J = p->slot_ints;
-      J.assign((size_t)n_meta + n_meta2 + (size_t)lpc * dev_ints, 0);
+      J.assign((size_t)n_meta + n_meta2 + (size_t)lpc * dev_ints + (size_t)lpc * state_words, 0);
       static const int need_of[kNKinds] = {15, kAbsent, kRes, kBDone, kDisc, kRes, kOff, kAbsent};
       static const int next_of[kNKinds] = {0, kRes, kBDone, kDone, kRes, kOff, kRes, kDisc};
       for (int kind = 0; kind < kNKinds; ++kind)
         for (int c = 0; c < kMaxChunks; ++c)
           for (int d = 0; d < lpc; ++d) {
             int32_t* e = &J[(((size_t)kind * kMaxChunks + c) * lpc + d) * 4];
-            e[2] = (int32_t)kMetaInvalid;
-            e[3] = 15;
+            e[2] = (int32_t)(kMetaInvalid | (15u << 24) | dump_slot);
             if (d >= D || c >= p->n_chunks[d] || kind == kEnd || (kind == kW && !p->has_w)) continue;
             const int s = p->local_stage[(size_t)d * kMaxChunks + c];
-            unsigned z = 0;
+            const unsigned units = (unsigned)desc->mem_units[s];
+            const bool allocs = kind == kF || kind == kFD || kind == kR || kind == kL;
+            const bool frees = kind == kFD || kind == kO || kind == (p->has_w ? kW : kB);
+            unsigned flags = 0, tag = 0, prod = dump_slot;
             int comm = 0;
-            if (kind == kF || kind == kFD || kind == kR || kind == kL) z |= kMetaAlloc;
-            if (kind == kFD || kind == kO || kind == (p->has_w ? kW : kB)) z |= kMetaFree;
-            if (kind == (p->has_w ? kW : kB)) z |= kMetaTerminal;
-            unsigned prod = dump_slot;
             if (kind == kF || kind == kFD) {
-              if (poff[s + 1] > poff[s]) { z |= kMetaHasCons | ((unsigned)pst[poff[s]] << 16); comm = pcm[poff[s]]; }
-              if (soff[s + 1] > soff[s]) { z |= kMetaHasProd; prod = (unsigned)(scl[soff[s]] * m); }
+              if (poff[s + 1] > poff[s]) { flags |= kMetaHasCons; tag = (unsigned)pst[poff[s]]; comm = pcm[poff[s]]; }
+              if (soff[s + 1] > soff[s]) prod = (unsigned)(scl[soff[s]] * m);
             } else if (kind == kB) {
-              if (soff[s + 1] > soff[s]) { z |= kMetaHasCons | ((unsigned)sst[soff[s]] << 16); comm = scm[soff[s]]; }
-              if (poff[s + 1] > poff[s]) { z |= kMetaHasProd; prod = (unsigned)((n_classes + pcl[poff[s]]) * m); }
+              if (soff[s + 1] > soff[s]) { flags |= kMetaHasCons; tag = (unsigned)sst[soff[s]]; comm = scm[soff[s]]; }
+              if (poff[s + 1] > poff[s]) prod = (unsigned)((n_classes + pcl[poff[s]]) * m);
             }
-            z |= prod;
             e[0] = desc->dur[kind * S + s];
-            e[1] = comm;
-            e[2] = (int32_t)z;
-            e[3] = (int32_t)((unsigned)need_of[kind] | ((unsigned)next_of[kind] << 4) | ((unsigned)s << 8) |
-                             ((unsigned)(desc->mem_units[s] & 0xffff) << 16));
+            e[1] = (int32_t)((unsigned)comm | ((unsigned)(need_of[kind] ^ next_of[kind]) << 20) | (tag << 24));
+            e[2] = (int32_t)(prod | ((unsigned)s << 16) | ((unsigned)need_of[kind] << 24) | flags);
+            e[3] = (int32_t)((allocs ? units : 0u) | ((frees ? units : 0u) << 16));
           }
       for (int dir = 0; dir < 2 && deg2; ++dir)
         for (int c = 0; c < kMaxChunks; ++c)
@@ -300,6 +304,14 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
             e[1] = (int32_t)y;
           }
       for (int d = 0; d < D; ++d) {
+        // state words of device d once every activation placed on it is consumed
+        int32_t* x = &J[(size_t)n_meta + n_meta2 + (size_t)lpc * dev_ints + (size_t)d * state_words];
+        const unsigned terminal = p->has_w ? kDone : kBDone;
+        for (int c = 0; c < p->n_chunks[d]; ++c)
+          for (int j = 0; j < m; ++j)
+            x[c * words_per_chunk + (j >> 3)] |= (int32_t)(terminal << ((j & 7) * 4));
+      }
+      for (int d = 0; d < D; ++d) {
         int32_t* e = &J[(size_t)n_meta + n_meta2 + (size_t)d * dev_ints];
         e[0] = p->n_chunks[d];
         e[1] = desc->mem_cap[d];
@@ -313,8 +325,9 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
         }
       }
       ST.D = D; ST.m = m; ST.lanes_per_cand = lpc; ST.n_classes = n_classes;
-      ST.slots_per_cand = 2 * n_classes * m + 1;
-      ST.state_words = (V * m + 7) / 8;
+      ST.slots_per_cand = (2 * n_classes + 1) * m;
+      ST.state_words = state_words;
+      ST.off_expect = n_meta + n_meta2 + lpc * dev_ints;
       ST.n_shared_ints = n_meta + n_meta2;
       ST.off_meta2 = n_meta;
       ST.off_dev = n_meta + n_meta2;
@@ -355,7 +368,7 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
       ok = hipMalloc(&p->d_slot_ints, p->slot_ints.size() * sizeof(int32_t)) == hipSuccess &&
            hipMemcpy(p->d_slot_ints, p->slot_ints.data(), p->slot_ints.size() * sizeof(int32_t),
                      hipMemcpyHostToDevice) == hipSuccess &&
-           hipFuncSetAttribute(reinterpret_cast<const void*>(slot_kernel_ptr(p->slot_v, p->slot_deg2)),
+           hipFuncSetAttribute(reinterpret_cast<const void*>(slot_kernel_ptr(p->slot_v, p->slot_deg2, p->stab.n_classes == 1)),
                                hipFuncAttributeMaxDynamicSharedMemorySize, p->slot_lds_bytes) == hipSuccess;
       p->stab.ints = p->d_slot_ints;
     }
@@ -433,7 +446,7 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
   if (p->use_slots) {
     const int per_block = p->stab.cands_per_wave * p->slot_waves;
     const int64_t blocks = std::min<int64_t>((n_cand + per_block - 1) / per_block, p->slot_grid);
-    hipLaunchKernelGGL(slot_kernel_ptr(p->slot_v, p->slot_deg2), dim3((unsigned)blocks), dim3(64 * p->slot_waves),
+    hipLaunchKernelGGL(slot_kernel_ptr(p->slot_v, p->slot_deg2, p->stab.n_classes == 1), dim3((unsigned)blocks), dim3(64 * p->slot_waves),
                        (size_t)p->slot_lds_bytes, static_cast<hipStream_t>(hip_stream), p->stab, d_ops,
                        (long long)n_cand, (int)stride_words, reinterpret_cast<long long*>(out.makespan),
                        reinterpret_cast<long long*>(out.idle), out.peak, out.flags);

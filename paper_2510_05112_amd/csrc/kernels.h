@@ -22,8 +22,8 @@ constexpr int kSlotMaxWaves = 16;
 constexpr int kSlotMaxThreads = 64 * kSlotMaxWaves;
 
 // V = compile-time bound on the stages (chunks) per device: 1, 2 or 4.  DEG2 = some stage
-// has two inputs or two outputs in the stage DAG.
-template <int V, bool DEG2>
+// has two inputs or two outputs in the stage DAG.  ONE_CLASS = the DAG is a single chain.
+template <int V, bool DEG2, bool ONE_CLASS>
 __global__ void eval_slot_kernel(SlotTables T, const uint16_t* ops, long long n_cand, int stride,
                                  long long* out_makespan, long long* out_idle, int* out_peak,
                                  unsigned char* out_flags);
