@@ -110,7 +110,10 @@ typedef struct {
   uint8_t *flags;    /* [C]     FPSCHED_FLAG_* bits                                       */
 } fpsched_results;
 
-/* Bytes of DEVICE workspace fpsched_evaluate / fpsched_topk need for this batch. */
+/* Bytes of DEVICE workspace fpsched_evaluate / fpsched_topk need for this batch (>= 256;
+ * k may be 0 when only fpsched_evaluate is called).  The workspace must be 16-byte aligned;
+ * the library keeps no other device scratch.  Two calls may share a workspace only if they
+ * run one after the other on the same stream. */
 size_t fpsched_workspace_bytes(const fpsched_problem *p, int64_t n_cand, int32_t k);
 
 /* Evaluate n_cand candidates.  d_ops: DEVICE, uint16 [n_cand][D][stride_words],

@@ -200,7 +200,9 @@ class Problem:
         C, _, stride = ops.shape
         if results is None:
             results = self.alloc_results(C)
-        ws_ptr, ws_bytes = (workspace.data_ptr(), workspace.numel()) if workspace is not None else (0, 0)
+        if workspace is None:
+            workspace = self.alloc_workspace(C, 0)
+        ws_ptr, ws_bytes = workspace.data_ptr(), workspace.numel()
         rc = load_library().fpsched_evaluate(self._h, ops.data_ptr(), C, stride, self._res_struct(results),
                                              ws_ptr, ws_bytes, self._stream(stream))
         if rc != 0:

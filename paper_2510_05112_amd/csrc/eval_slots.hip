@@ -3,9 +3,10 @@
 //
 // Mapping: a wavefront carries `cands_per_wave` candidate segments, lane = device inside
 // a segment; the wavefronts of a workgroup are independent and only share one LDS copy
-// of the op-metadata table.  The grid is persistent: segment g evaluates candidates g,
-// g + G, g + 2G, ... (G = segments in the grid), restarting on its next candidate while
-// the other segments of the wavefront keep going.  Each lane walks its device's list
+// of the op-metadata table.  The grid is persistent: whenever a segment finishes a
+// candidate it draws the next unevaluated one from a global counter and restarts while
+// the other segments of the wavefront keep going, so fast and slow candidates (and
+// unevenly loaded SIMDs) balance out.  Each lane walks its device's list
 // with a cursor in registers; a lane whose next op cannot issue yet waits for a later
 // round, and a round in which no lane of a segment moves ends that candidate (lists
 // exhausted, or deadlock).
@@ -57,14 +58,18 @@ __device__ __forceinline__ int pick(const int (&a)[V], int c) {
 
 }  // namespace
 
+__global__ void reset_counter_kernel(unsigned long long* counter) {
+  if (threadIdx.x == 0) *counter = 0ull;
+}
+
 template <int V, bool DEG2, bool ONE_CLASS>
 __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     SlotTables T, const uint16_t* __restrict__ ops, long long n_cand, int stride,
     long long* __restrict__ out_makespan, long long* __restrict__ out_idle,
-    int* __restrict__ out_peak, unsigned char* __restrict__ out_flags) {
+    int* __restrict__ out_peak, unsigned char* __restrict__ out_flags,
+    unsigned long long* __restrict__ next_candidate) {
   extern __shared__ int32_t lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int n_waves = blockDim.x >> 6;
   const int m = T.m;
   const int cpw = T.cands_per_wave;
   const int lpc = T.lanes_per_cand;
@@ -85,8 +90,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   const int d = lane & (lpc - 1);
   const bool lane_ok = (seg < cpw) && (d < T.D);
   uint32_t* my_slots = slots + (seg < cpw ? seg : 0) * slots_per_cand;
-  const long long n_segments = (long long)gridDim.x * n_waves * cpw;
-  long long cand = ((long long)blockIdx.x * n_waves + wave) * cpw + seg;
+  long long cand = 0;
 
   // per-device constants: memory cap, slot offsets of the inputs of each chunk
   const int dd = d < T.D ? d : 0;
@@ -127,7 +131,8 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   // least one of its at most D * stride ops), so the bound below is never reached; it only makes
   // sure the wavefront leaves the loop whatever happens.
   const unsigned long long per_cand_rounds = (unsigned long long)T.D * (unsigned)stride + 8ull;
-  const unsigned long long my_cands = (unsigned long long)((n_cand + n_segments - 1) / n_segments) + 1ull;
+  // (a segment cannot draw more than all candidates; fast segments draw more than their share)
+  const unsigned long long my_cands = (unsigned long long)n_cand + 1ull;
   const unsigned long long bound = per_cand_rounds * my_cands;
   const unsigned max_rounds = bound > 0xfffffff0ull ? 0xfffffff0u : (unsigned)bound;
   for (unsigned round = 0; round < max_rounds; ++round) {
@@ -135,6 +140,10 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     if (__ballot(fresh) != 0ull) {
       if (fresh) {
         fresh = false;
+        // the segment's first lane draws the next unevaluated candidate for the whole segment
+        unsigned long long drawn = 0ull;
+        if (d == 0 && seg < cpw) drawn = atomicAdd(next_candidate, 1ull);
+        cand = (long long)__shfl(drawn, seg << lpc_shift, 64);
         running = (seg < cpw) && (cand < n_cand);
         live = running && lane_ok;
         cursor = 0; free_at = 0; busy = 0; mem = 0; pk = 0;
@@ -276,7 +285,6 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
             out_flags[cand] = (unsigned char)flg;
           }
         }
-        cand += n_segments;
         running = false;
         live = false;
         w = 0u;
@@ -288,7 +296,8 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
 
 #define FPSCHED_INSTANTIATE(V, G, O)                                                               \
   template __global__ void eval_slot_kernel<V, G, O>(SlotTables, const uint16_t*, long long, int,  \
-                                                     long long*, long long*, int*, unsigned char*);
+                                                     long long*, long long*, int*, unsigned char*, \
+                                                     unsigned long long*);
 FPSCHED_INSTANTIATE(1, false, true)
 FPSCHED_INSTANTIATE(2, false, true)
 FPSCHED_INSTANTIATE(4, false, true)

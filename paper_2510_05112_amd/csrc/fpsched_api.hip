@@ -53,7 +53,7 @@ struct DeviceGuard {
 };
 
 using SlotKernel = void (*)(SlotTables, const uint16_t*, long long, int, long long*, long long*, int*,
-                            unsigned char*);
+                            unsigned char*, unsigned long long*);
 SlotKernel slot_kernel_ptr(int v, bool deg2, bool one_class) {
   if (deg2)
     return v == 1 ? &eval_slot_kernel<1, true, false>
@@ -346,6 +346,11 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
         wv = std::min(wv, 32 / groups);  // 8 wavefronts per SIMD, 4 SIMDs per compute unit
         if (wv * groups > best_total) { best_total = wv * groups; best_waves = wv; best_groups = groups; }
       }
+      // tuning knob: FPSCHED_SLOT_WAVES=n caps the wavefronts per workgroup (one workgroup per CU)
+      if (const char* env = getenv("FPSCHED_SLOT_WAVES")) {
+        const int cap_waves = atoi(env);
+        if (cap_waves >= 1 && cap_waves < best_waves * best_groups) { best_waves = std::min(cap_waves, best_waves); best_groups = 1; }
+      }
       p->slots_ok = fits && best_waves >= 1;
       ST.cands_per_wave = scpw;
       ST.wave_ints = (int32_t)wave_ints;
@@ -434,7 +439,6 @@ size_t fpsched_workspace_bytes(const fpsched_problem* p, int64_t n_cand, int32_t
 int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_cand,
                      int32_t stride_words, fpsched_results out, void* d_workspace,
                      size_t workspace_bytes, void* hip_stream) {
-  (void)d_workspace; (void)workspace_bytes;
   if (!p || n_cand < 0) return FPSCHED_EINVAL;
   if (p->device_id < 0) return FPSCHED_ENODEV;
   if (n_cand == 0) return FPSCHED_OK;
@@ -444,12 +448,17 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
   DeviceGuard g(p->device_id);
   if (!g.ok) return FPSCHED_EHIP;
   if (p->use_slots) {
+    // the first 8 bytes of the workspace hold the counter the segments draw candidates from
+    if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) & 15)) return FPSCHED_EINVAL;
+    if (workspace_bytes < 256) return FPSCHED_ENOMEM;
+    unsigned long long* counter = static_cast<unsigned long long*>(d_workspace);
+    hipLaunchKernelGGL(reset_counter_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(hip_stream), counter);
     const int per_block = p->stab.cands_per_wave * p->slot_waves;
     const int64_t blocks = std::min<int64_t>((n_cand + per_block - 1) / per_block, p->slot_grid);
     hipLaunchKernelGGL(slot_kernel_ptr(p->slot_v, p->slot_deg2, p->stab.n_classes == 1), dim3((unsigned)blocks), dim3(64 * p->slot_waves),
                        (size_t)p->slot_lds_bytes, static_cast<hipStream_t>(hip_stream), p->stab, d_ops,
                        (long long)n_cand, (int)stride_words, reinterpret_cast<long long*>(out.makespan),
-                       reinterpret_cast<long long*>(out.idle), out.peak, out.flags);
+                       reinterpret_cast<long long*>(out.idle), out.peak, out.flags, counter);
     return check_hip(hipGetLastError());
   }
   const int cpw = p->tables.cands_per_wave;
