@@ -24,8 +24,8 @@
 //
 // Same-device ordering rules are the activation state machine of one (stage,
 // micro-batch), 4 bits per entry, in lane-private LDS words.  Op words are staged
-// through a lane-private 32-word LDS ring that the whole wavefront tops up with
-// 16-byte global loads every eighth round; the load issued at one top-up is only
+// through a lane-private 16-word LDS ring that the whole wavefront tops up with
+// 8-byte global loads every fourth round; the load issued at one top-up is only
 // written to LDS at the next, so its latency is off the critical path.
 //
 // A round is straight-line code: the LDS reads of a round (next op word, op metadata,
@@ -56,6 +56,16 @@ __device__ __forceinline__ int pick(const int (&a)[V], int c) {
   return r;
 }
 
+// Op window: kRing words per lane, refilled kChunk words at a time every kSyncRounds rounds.
+// A lane asks for its next chunk when at most kRefillAt words are left unread; with these
+// values a lane that issues one op per round always finds the word after its cursor in the
+// ring (at least 5 unread words after every top-up, at most 12 <= kRing).
+constexpr int kRing = 16;
+constexpr int kChunk = 4;
+constexpr unsigned kSyncRounds = 4;
+constexpr int kRefillAt = 8;
+constexpr int kPrimeChunks = 3;
+
 }  // namespace
 
 __global__ void reset_counter_kernel(unsigned long long* counter) {
@@ -79,11 +89,11 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   for (int i = tid; i < T.n_shared_ints; i += blockDim.x) lds[i] = T.ints[i];
   const char* lds_bytes = reinterpret_cast<const char*>(lds);
   const int2* meta2 = reinterpret_cast<const int2*>(lds + T.off_meta2);
-  // window: 32 sixteen-bit words per lane, laid out [word][lane]
+  // window: kRing sixteen-bit words per lane, laid out [word][lane]
   uint16_t* win = reinterpret_cast<uint16_t*>(lds + T.n_shared_ints + wave * T.wave_ints);
-  uint32_t* stt = reinterpret_cast<uint32_t*>(win) + 16 * 64;   // [state word][lane]
+  uint32_t* stt = reinterpret_cast<uint32_t*>(win) + (kRing / 2) * 64;   // [state word][lane]
   uint32_t* slots = stt + T.state_words * 64;
-  const int slots_per_cand = T.slots_per_cand;  // (2 * classes + 1) * m: forward, backward, dump
+  const int slots_per_cand = T.slots_per_cand;  // 2 * classes * m: forward, backward; + 1 dump slot
   __syncthreads();
 
   const int seg = lane >> lpc_shift;
@@ -119,7 +129,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   // per-candidate registers
   const uint16_t* row = ops;
   int loaded = 0;  // words of this row already in the window ring
-  uint4 pend = make_uint4(0, 0, 0, 0);
+  uint2 pend = make_uint2(0, 0);
   bool has_pend = false;
   int cursor = 0, free_at = 0, busy = 0, mem = 0, pk = 0;
   bool running = false;  // this lane's segment is evaluating a candidate
@@ -157,40 +167,34 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
           for (int i = 0; i < T.state_words; ++i) stt[i * 64 + lane] = 0u;
           row = ops + ((size_t)cand * T.D + d) * (size_t)stride;
 #pragma unroll
-          for (int q = 0; q < 3; ++q) {
+          for (int q = 0; q < kPrimeChunks; ++q) {
             if (loaded < stride) {
-              const uint4 v = *reinterpret_cast<const uint4*>(row + loaded);
-              uint32_t* dst = reinterpret_cast<uint32_t*>(win);
+              const uint2 v = *reinterpret_cast<const uint2*>(row + loaded);
               // [word][lane] with 16-bit elements: word k of lane l at k * 64 + l
-              win[(q * 8 + 0) * 64 + lane] = (uint16_t)v.x; win[(q * 8 + 1) * 64 + lane] = (uint16_t)(v.x >> 16);
-              win[(q * 8 + 2) * 64 + lane] = (uint16_t)v.y; win[(q * 8 + 3) * 64 + lane] = (uint16_t)(v.y >> 16);
-              win[(q * 8 + 4) * 64 + lane] = (uint16_t)v.z; win[(q * 8 + 5) * 64 + lane] = (uint16_t)(v.z >> 16);
-              win[(q * 8 + 6) * 64 + lane] = (uint16_t)v.w; win[(q * 8 + 7) * 64 + lane] = (uint16_t)(v.w >> 16);
-              (void)dst;
+              win[(q * 4 + 0) * 64 + lane] = (uint16_t)v.x; win[(q * 4 + 1) * 64 + lane] = (uint16_t)(v.x >> 16);
+              win[(q * 4 + 2) * 64 + lane] = (uint16_t)v.y; win[(q * 4 + 3) * 64 + lane] = (uint16_t)(v.y >> 16);
               if (q == 0) w = v.x & 0xffffu;
-              loaded += 8;
+              loaded += kChunk;
             }
           }
           // a row that fills its stride has no END word: plant one behind it
-          if (loaded >= stride) win[(stride & 31) * 64 + lane] = 0;
+          if (loaded >= stride) win[(stride & (kRing - 1)) * 64 + lane] = 0;
         }
       }
       if (__ballot(running) == 0ull) break;  // every segment of the wave is out of work
     }
-    if ((round & 7u) == 0u) {
-      // wave-wide top-up: land the chunk requested eight rounds ago, request the next
+    if ((round & (kSyncRounds - 1)) == 0u) {
+      // wave-wide top-up: land the chunk requested at the previous top-up, request the next
       if (has_pend) {
-        const int q = loaded & 31;
+        const int q = loaded & (kRing - 1);
         win[(q + 0) * 64 + lane] = (uint16_t)pend.x; win[(q + 1) * 64 + lane] = (uint16_t)(pend.x >> 16);
         win[(q + 2) * 64 + lane] = (uint16_t)pend.y; win[(q + 3) * 64 + lane] = (uint16_t)(pend.y >> 16);
-        win[(q + 4) * 64 + lane] = (uint16_t)pend.z; win[(q + 5) * 64 + lane] = (uint16_t)(pend.z >> 16);
-        win[(q + 6) * 64 + lane] = (uint16_t)pend.w; win[(q + 7) * 64 + lane] = (uint16_t)(pend.w >> 16);
-        loaded += 8;
+        loaded += kChunk;
         has_pend = false;
-        if (loaded >= stride) win[(stride & 31) * 64 + lane] = 0;
+        if (loaded >= stride) win[(stride & (kRing - 1)) * 64 + lane] = 0;
       }
-      if (w != 0u && loaded - cursor <= 17 && loaded < stride) {
-        pend = *reinterpret_cast<const uint4*>(row + loaded);
+      if (w != 0u && loaded - cursor <= kRefillAt && loaded < stride) {
+        pend = *reinterpret_cast<const uint2*>(row + loaded);
         has_pend = true;
       }
     }
@@ -199,7 +203,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     const int j = w & 0x7ff;
     const bool is_b = (w >> 13) == (unsigned)kB;
     const int nxt = cursor + 1;
-    unsigned w_next = win[(nxt & 31) * 64 + lane];
+    unsigned w_next = win[(nxt & (kRing - 1)) * 64 + lane];
     int4 M = *reinterpret_cast<const int4*>(lds_bytes + (((w >> meta_shift) & meta_mask) | meta_lane));
     const int jj = min(j, m - 1);
     const int sw = ((int)__umul24((unsigned)(c & (V - 1)), (unsigned)words_per_chunk) + (jj >> 3)) * 64 + lane;
@@ -243,7 +247,8 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       mem -= (int)((unsigned)M.w >> 16);
       stt[sw] = sx ^ (((my >> 20) & 15u) << sh);
       const unsigned val = ((unsigned)fin << 8) | ((mz >> 16) & 0xffu);
-      my_slots[(mz & 0xffffu) + j] = val;   // ops without an output edge write the dump region
+      // ops without an output edge write the candidate's dump slot
+      my_slots[(mz & 0xffffu) + (j & (unsigned)((int)mz >> 31))] = val;
       if (DEG2) {
         if ((unsigned)M2.y & kMetaHasProd) my_slots[((unsigned)M2.y & 0xffffu) + j] = val;
       }

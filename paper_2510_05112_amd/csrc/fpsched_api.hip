@@ -233,7 +233,7 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
       const int V = p->slot_v = max_chunks <= 1 ? 1 : (max_chunks <= 2 ? 2 : 4);
       const int lpc = T.lanes_per_cand;
       // slot offsets are 16-bit, tags 8-bit (0xff = empty), finish times 24-bit
-      bool fits = (2ll * n_classes + 1) * m <= 0xffff && S <= 255 && max_comm < (1ll << 20) &&
+      bool fits = 2ll * n_classes * m + 1 <= 0xffff && S <= 255 && max_comm < (1ll << 20) &&
                   (int64_t)D * max_stride_words * (max_dur + max_comm) < (1ll << 24);
       bool deg2 = false;
       for (int s = 0; s < S; ++s) {
@@ -277,10 +277,10 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
             int comm = 0;
             if (kind == kF || kind == kFD) {
               if (poff[s + 1] > poff[s]) { flags |= kMetaHasCons; tag = (unsigned)pst[poff[s]]; comm = pcm[poff[s]]; }
-              if (soff[s + 1] > soff[s]) prod = (unsigned)(scl[soff[s]] * m);
+              if (soff[s + 1] > soff[s]) { flags |= kMetaHasProd; prod = (unsigned)(scl[soff[s]] * m); }
             } else if (kind == kB) {
               if (soff[s + 1] > soff[s]) { flags |= kMetaHasCons; tag = (unsigned)sst[soff[s]]; comm = scm[soff[s]]; }
-              if (poff[s + 1] > poff[s]) prod = (unsigned)((n_classes + pcl[poff[s]]) * m);
+              if (poff[s + 1] > poff[s]) { flags |= kMetaHasProd; prod = (unsigned)((n_classes + pcl[poff[s]]) * m); }
             }
             e[0] = desc->dur[kind * S + s];
             e[1] = (int32_t)((unsigned)comm | ((unsigned)(need_of[kind] ^ next_of[kind]) << 20) | (tag << 24));
@@ -325,7 +325,7 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
         }
       }
       ST.D = D; ST.m = m; ST.lanes_per_cand = lpc; ST.n_classes = n_classes;
-      ST.slots_per_cand = (2 * n_classes + 1) * m;
+      ST.slots_per_cand = 2 * n_classes * m + 1;
       ST.state_words = state_words;
       ST.off_expect = n_meta + n_meta2 + lpc * dev_ints;
       ST.n_shared_ints = n_meta + n_meta2;
@@ -335,7 +335,7 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
       // geometry: candidates per wave, then the workgroup shape that keeps the most
       // wavefronts resident on a compute unit (LDS is the only limiter: ~50 VGPRs)
       int scpw = 64 / lpc;
-      const int64_t fixed = 64ll * (16 + ST.state_words);
+      const int64_t fixed = 64ll * (8 + ST.state_words);  // 16 op words + state words per lane
       const int64_t lds_ints = max_lds / 4;
       while (scpw > 1 && ST.n_shared_ints + fixed + (int64_t)scpw * ST.slots_per_cand > lds_ints) scpw >>= 1;
       const int64_t wave_ints = fixed + (int64_t)scpw * ST.slots_per_cand;
