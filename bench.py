@@ -22,6 +22,12 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+# vector-ALU issue peak: 256 CUs x 4 SIMDs, 2.4 GHz, one wave64 instruction per SIMD every 4 cycles
+VALU_PEAK_WAVE_INSTR_PER_S = 256 * 4 * 2.4e9 / 4
+# HBM bytes of ONE evaluation launch on the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE
+# scaled by a copy kernel of known size, and its VALU wave-instruction count (SQ_INSTS_VALU):
+# profiles/eval_slot_kernel_cfg4_counters.md.  Other workloads report null.
+MEASURED = {("cfg4", 65536): {"traffic_bytes": 4.613e9, "valu_wave_instructions": 3.977e9}}
 
 
 def main() -> int:
@@ -34,6 +40,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=None, help="candidates timed on the CPU oracle")
     ap.add_argument("--check", type=int, default=512, help="sampled candidates compared with the oracle")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain elementwise copy of the op batch (a kernel of known HBM "
+                         "traffic, used to calibrate rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (candidates are independent; sharding them over "
@@ -82,6 +91,13 @@ def main() -> int:
         handle.evaluate(ops, res, ws)
         handle.topk(res, k, ws, top)
 
+    if args.copy_probe:
+        probe = torch.empty_like(ops)
+        torch.add(ops, 0, out=probe)   # reads and writes ops.numel() * 2 bytes each
+        torch.cuda.synchronize()
+        print(f"[bench] copy probe: {ops.numel() * 2} bytes read, {ops.numel() * 2} bytes written",
+              file=sys.stderr, flush=True)
+        del probe
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -106,6 +122,7 @@ def main() -> int:
     alg_bytes = 2 * n_ops + C * (8 + 8 * D + 4 * D + 1)
     achieved = alg_bytes / (eval_ms * 1e-3) / 1e9
 
+    measured = MEASURED.get((f"cfg{spec.index}", C), {})
     flags = res["flags"].cpu().numpy()
     makespan = res["makespan"].cpu().numpy()
     out = {
@@ -124,8 +141,17 @@ def main() -> int:
         "op_evals_per_s": n_ops / (ms_per_step * 1e-3),
         "eval_kernel_ms": eval_ms, "topk_ms": topk_ms,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "fpsched evaluation kernel", "algorithmic_bytes_per_launch": alg_bytes},
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured.get("traffic_bytes"),
+                     "kernel": "fpsched evaluation kernel (eval_slot_kernel)",
+                     "algorithmic_bytes_per_launch": alg_bytes,
+                     "note": "the kernel is bound by vector-ALU issue, not HBM: see alu_ceiling"},
+        "alu_ceiling": None if not measured else {
+            "bound": "alu", "unit": "VALU wave-instructions/s",
+            "achieved": measured["valu_wave_instructions"] / (eval_ms * 1e-3),
+            "peak": VALU_PEAK_WAVE_INSTR_PER_S,
+            "frac": measured["valu_wave_instructions"] / (eval_ms * 1e-3) / VALU_PEAK_WAVE_INSTR_PER_S,
+            "valu_wave_instructions_per_op_eval": measured["valu_wave_instructions"] / n_ops,
+            "source": "rocprofv3 SQ_INSTS_VALU, profiles/eval_slot_kernel_cfg4_counters.md"},
         "fractions": {"feasible_under_cap": float((flags == 0).mean()),
                       "over_cap": float((flags == 4).mean()),
                       "deadlock": float(((flags & 1) != 0).mean())},

@@ -1,0 +1,54 @@
+"""GPU parity at the benchmark's full batch sizes, in the launch configuration bench.py times:
+sampled candidates against the oracle one by one, plus properties that hold at any size."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2510_05112_amd as fp
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("index", [2, 5, 4, 3])
+def test_full_batch_sampled_against_oracle(index):
+    spec = workloads.config(index)
+    prob = spec.problem
+    words = workloads.generate(spec, threads=16)
+    C, D, stride = words.shape
+    print(f"cfg{index}: {C} candidates, {words.nbytes / 1e9:.2f} GB", flush=True)
+    h = fp.Problem(prob, stride, device=0)
+    ops = torch.empty((C, D, stride), dtype=torch.int16, device="cuda")
+    step = max(1, (256 << 20) // (D * stride * 2))
+    for lo in range(0, C, step):
+        ops[lo:lo + step].copy_(torch.from_numpy(words[lo:lo + step].view(np.int16)))
+    ws = h.alloc_workspace(C, spec.top_k)
+    res = h.evaluate(ops, workspace=ws)
+    top = h.topk(res, spec.top_k, workspace=ws)
+    torch.cuda.synchronize()
+    g = {k: v.cpu().numpy() for k, v in res.items()}
+    # sampled candidates, one by one
+    rng = np.random.default_rng(index)
+    pick = np.sort(np.concatenate([rng.choice(C, 1500, replace=False), [0, C - 1]]))
+    ref = oracle.evaluate(prob, words[pick], threads=16)
+    for name in ("flags", "makespan", "idle", "peak"):
+        assert np.array_equal(g[name][pick], ref[name]), name
+    # properties at full size
+    fl, ms = g["flags"], g["makespan"]
+    assert np.all(np.isin(fl, [0, 1, 3, 2, 4]))
+    good = (fl & 3) == 0
+    assert np.all(ms[~good] == oracle.INT64_MAX) and np.all(g["idle"][~good] == -1) and np.all(g["peak"][~good] == -1)
+    assert np.all(g["idle"][good] >= 0)
+    assert np.all(g["idle"][good].max(1) <= ms[good])
+    over = (g["peak"] > np.asarray(prob.mem_cap)[None, :]).any(1)
+    assert np.array_equal(fl[good] == 4, over[good])
+    # every row's busy time is order-independent for configs without optional ops; in all configs
+    # idle + busy = makespan means idle differences between devices are makespan-independent
+    # top-k: exactly the stable sort of the feasible candidates of the GPU's own results
+    feas = np.flatnonzero(fl == 0)
+    order = feas[np.argsort(ms[feas], kind="stable")][: spec.top_k]
+    assert int(top["count"].item()) == len(order)
+    assert np.array_equal(top["idx"].cpu().numpy()[: len(order)], order)
+    assert np.array_equal(top["makespan"].cpu().numpy()[: len(order)], ms[order])
+    h.close()
