@@ -44,8 +44,8 @@ struct DevTables {
 //     x = dur
 //     y = latency of the first input edge (20) | state transition need ^ next (4) << 20
 //         | tag expected on the first input (8) << 24
-//     z = slot offset of the first output, or of the dump slot (16) | own stage (8) << 16
-//         | required state (4) << 24 | kMeta* flags
+//     z = required state (4) | slot offset of the first output, or of the dump slot (16) << 4
+//         | own stage (8) << 20 | kMeta* flags
 //     w = units allocated at the op's start (16) | units freed at its end (16) << 16
 //     Rows of words that may not appear on the device (no such chunk, kind 0, W without split
 //     backward) carry kMetaInvalid and require state 15, which no activation is ever in.
@@ -58,9 +58,9 @@ struct DevTables {
 // A slot is one dword, finish << 8 | producer stage; offsets count slots from the candidate's
 // slot base: (dir * classes + class) * m; the dump slot (written by ops without an output
 // edge, never read) sits at 2 * classes * m.
-constexpr unsigned kMetaHasCons = 1u << 28;
-constexpr unsigned kMetaInvalid = 1u << 30;
-constexpr unsigned kMetaHasProd = 1u << 31;
+constexpr unsigned kMetaInvalid = 1u << 28;
+constexpr unsigned kMetaHasProd = 1u << 30;
+constexpr unsigned kMetaHasCons = 1u << 31;
 constexpr unsigned kEmptySlot = 0x000000ffu;  // finish 0, tag 0xff = no stage
 
 struct SlotTables {

@@ -123,8 +123,19 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       (lpc == 64 ? ~0ull : ((1ull << lpc) - 1ull)) << (seg * lpc);
   const int meta_shift = 7 - lpc_shift;                 // op word >> this = row offset in bytes
   const unsigned meta_mask = 0xF800u >> meta_shift;     // (kind, chunk) bits of that offset
-  const unsigned meta_lane = (unsigned)d << 4;
+  const char* meta_lane = lds_bytes + (d << 4);         // this device's column of the metadata rows
   const int words_per_chunk = (m + 7) >> 3;
+  const char* win_lane = reinterpret_cast<const char*>(win) + lane * 2;
+  char* stt_lane = reinterpret_cast<char*>(stt) + lane * 4;
+  char* slot_base = reinterpret_cast<char*>(my_slots);
+  // segment bookkeeping on the scalar unit: bit (seg * lpc) stands for segment seg
+  unsigned long long base_bits = 0ull;
+  for (int sgm = 0; sgm < cpw; ++sgm) base_bits |= 1ull << (sgm * lpc);
+  int fold_shift[6];   // shifts 1, 2, 4, ... below the segment width, then 0 (no-ops)
+#pragma unroll
+  for (int i = 0; i < 6; ++i) fold_shift[i] = (1 << i) < lpc ? (1 << i) : 0;
+  unsigned long long run_bases = 0ull;   // base bits of the segments that are evaluating a candidate
+  bool any_fresh = true;                 // wave-uniform: some segment wants its next candidate
 
   // per-candidate registers
   const uint16_t* row = ops;
@@ -147,7 +158,8 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   const unsigned max_rounds = bound > 0xfffffff0ull ? 0xfffffff0u : (unsigned)bound;
   for (unsigned round = 0; round < max_rounds; ++round) {
     // ---- (re)start segments on their next candidate
-    if (__ballot(fresh) != 0ull) {
+    if (any_fresh) {
+      any_fresh = false;
       if (fresh) {
         fresh = false;
         // the segment's first lane draws the next unevaluated candidate for the whole segment
@@ -181,7 +193,8 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
           if (loaded >= stride) win[(stride & (kRing - 1)) * 64 + lane] = 0;
         }
       }
-      if (__ballot(running) == 0ull) break;  // every segment of the wave is out of work
+      run_bases = __ballot(running) & base_bits;
+      if (run_bases == 0ull) break;  // every segment of the wave is out of work
     }
     if ((round & (kSyncRounds - 1)) == 0u) {
       // wave-wide top-up: land the chunk requested at the previous top-up, request the next
@@ -199,18 +212,21 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       }
     }
     // ---- decode the current word (already in a register) and issue this round's reads
-    const int c = (w >> 11) & 3;
     const int j = w & 0x7ff;
-    const bool is_b = (w >> 13) == (unsigned)kB;
     const int nxt = cursor + 1;
-    unsigned w_next = win[(nxt & (kRing - 1)) * 64 + lane];
-    int4 M = *reinterpret_cast<const int4*>(lds_bytes + (((w >> meta_shift) & meta_mask) | meta_lane));
+    unsigned w_next = *reinterpret_cast<const uint16_t*>(win_lane + ((nxt & (kRing - 1)) << 7));
+    int4 M = *reinterpret_cast<const int4*>(meta_lane + ((w >> meta_shift) & meta_mask));
     const int jj = min(j, m - 1);
-    const int sw = ((int)__umul24((unsigned)(c & (V - 1)), (unsigned)words_per_chunk) + (jj >> 3)) * 64 + lane;
-    const int sh = (jj & 7) * 4;
-    unsigned sx = stt[sw];
-    const int coff = ONE_CLASS ? (is_b ? m : 0) : (is_b ? pick<V>(cons_b, c) : pick<V>(cons_f, c));
-    unsigned in1 = my_slots[coff + jj];
+    const unsigned sh = (unsigned)jj << 2;   // shift counts use their low five bits: (jj & 7) * 4
+    char* state_ptr = stt_lane + __umul24((w >> 11) & (V - 1), (unsigned)words_per_chunk << 8) + ((jj & ~7) << 5);
+    unsigned sx = *reinterpret_cast<uint32_t*>(state_ptr);
+    const int c = (w >> 11) & 3;
+    const bool is_b = (w >> 13) == (unsigned)kB;
+    // one class: forward inputs at slot j, backward inputs at slot m + j; bit 13 of the word is set
+    // for F and FD and clear for B (other kinds have no input, whatever they read is ignored)
+    const int in_off = ONE_CLASS ? (m << 2) - (int)__umul24((w >> 13) & 1u, (unsigned)m << 2)
+                                 : (is_b ? pick<V>(cons_b, c) : pick<V>(cons_f, c)) << 2;
+    unsigned in1 = *reinterpret_cast<const uint32_t*>(slot_base + in_off + (jj << 2));
     int2 M2 = make_int2(0, 0);
     unsigned in2 = 0u;
     if (DEG2) {
@@ -225,10 +241,9 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     // require state 15, which no activation is ever in.  Lanes without a device (and idle
     // segments) never initialise their LDS words, so they are masked off explicitly.
     const unsigned my = (unsigned)M.y, mz = (unsigned)M.z;
-    const unsigned st = (sx >> sh) & 15u;
-    bool ok = live && (st == ((mz >> 24) & 15u)) && j < m;
+    bool ok = live && (((sx >> (sh & 31u)) ^ mz) & 15u) == 0u && j < m;
     int ready = 0;
-    if (mz & kMetaHasCons) {
+    if ((int)mz < 0) {   // kMetaHasCons is the sign bit
       ok = ok && (in1 & 0xffu) == (my >> 24);
       ready = (int)(in1 >> 8) + (int)(my & 0xfffffu);
     }
@@ -245,10 +260,11 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       mem += (int)((unsigned)M.w & 0xffffu);
       pk = max(pk, mem);
       mem -= (int)((unsigned)M.w >> 16);
-      stt[sw] = sx ^ (((my >> 20) & 15u) << sh);
-      const unsigned val = ((unsigned)fin << 8) | ((mz >> 16) & 0xffu);
-      // ops without an output edge write the candidate's dump slot
-      my_slots[(mz & 0xffffu) + (j & (unsigned)((int)mz >> 31))] = val;
+      *reinterpret_cast<uint32_t*>(state_ptr) = sx ^ (((my >> 20) & 15u) << (sh & 31u));
+      const unsigned val = ((unsigned)fin << 8) | ((mz >> 20) & 0xffu);
+      // ops without an output edge write the candidate's dump slot (byte offset in bits 4..19)
+      const unsigned out_j = ((unsigned)j << 2) & (unsigned)((int)(mz << 1) >> 31);
+      *reinterpret_cast<uint32_t*>(slot_base + ((mz >> 4) & 0xffffu) * 4u + out_j) = val;
       if (DEG2) {
         if ((unsigned)M2.y & kMetaHasProd) my_slots[((unsigned)M2.y & 0xffffu) + j] = val;
       }
@@ -258,14 +274,19 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       w = w_next;
     }
     __builtin_amdgcn_wave_barrier();
-    const unsigned long long moved = __ballot(ok);
-    const bool seg_ended = running && (moved & seg_mask) == 0ull;
-    if (__ballot(seg_ended) != 0ull) {
+    // a segment none of whose lanes issued is finished: fold the issue mask onto the segments'
+    // base bits (scalar unit)
+    unsigned long long any_moved = __ballot(ok);
+#pragma unroll
+    for (int i = 0; i < 6; ++i) any_moved |= any_moved >> fold_shift[i];
+    const unsigned long long ended = ~any_moved & run_bases;
+    if (ended != 0ull) {
+      const bool seg_ended = ((ended >> (seg << lpc_shift)) & 1ull) != 0ull;
       // ---- the candidate is over: lists exhausted or nothing can move any more
       bool bad_head = false, incomplete = false;
       if (seg_ended && lane_ok) {
         // a stuck device sits on a malformed word?
-        const int4 Mh = *reinterpret_cast<const int4*>(lds_bytes + (((w >> meta_shift) & meta_mask) | meta_lane));
+        const int4 Mh = *reinterpret_cast<const int4*>(meta_lane + ((w >> meta_shift) & meta_mask));
         bad_head = w != 0u && (((unsigned)Mh.z & kMetaInvalid) || (int)(w & 0x7ff) >= m);
         // every activation of this device consumed?
         for (int i = 0; i < T.state_words; ++i) incomplete = incomplete || (stt[i * 64 + lane] != (unsigned)expect[i]);
@@ -295,6 +316,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
         w = 0u;
         fresh = true;
       }
+      any_fresh = true;
     }
   }
 }

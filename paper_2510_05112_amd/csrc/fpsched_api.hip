@@ -267,7 +267,7 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
         for (int c = 0; c < kMaxChunks; ++c)
           for (int d = 0; d < lpc; ++d) {
             int32_t* e = &J[(((size_t)kind * kMaxChunks + c) * lpc + d) * 4];
-            e[2] = (int32_t)(kMetaInvalid | (15u << 24) | dump_slot);
+            e[2] = (int32_t)(kMetaInvalid | 15u | (dump_slot << 4));
             if (d >= D || c >= p->n_chunks[d] || kind == kEnd || (kind == kW && !p->has_w)) continue;
             const int s = p->local_stage[(size_t)d * kMaxChunks + c];
             const unsigned units = (unsigned)desc->mem_units[s];
@@ -284,7 +284,7 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
             }
             e[0] = desc->dur[kind * S + s];
             e[1] = (int32_t)((unsigned)comm | ((unsigned)(need_of[kind] ^ next_of[kind]) << 20) | (tag << 24));
-            e[2] = (int32_t)(prod | ((unsigned)s << 16) | ((unsigned)need_of[kind] << 24) | flags);
+            e[2] = (int32_t)((unsigned)need_of[kind] | (prod << 4) | ((unsigned)s << 20) | flags);
             e[3] = (int32_t)((allocs ? units : 0u) | ((frees ? units : 0u) << 16));
           }
       for (int dir = 0; dir < 2 && deg2; ++dir)
