@@ -134,7 +134,9 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   int fold_shift[6];   // shifts 1, 2, 4, ... below the segment width, then 0 (no-ops)
 #pragma unroll
   for (int i = 0; i < 6; ++i) fold_shift[i] = (1 << i) < lpc ? (1 << i) : 0;
+  const unsigned long long high_bits = base_bits << (lpc - 1);
   unsigned long long run_bases = 0ull;   // base bits of the segments that are evaluating a candidate
+  unsigned long long idle_fields = ~0ull;  // all lanes of the segments that are not
   bool any_fresh = true;                 // wave-uniform: some segment wants its next candidate
 
   // per-candidate registers
@@ -145,6 +147,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   int cursor = 0, free_at = 0, busy = 0, mem = 0, pk = 0;
   bool running = false;  // this lane's segment is evaluating a candidate
   bool live = false;     // ... and this lane carries one of its devices
+  unsigned dead = ~0u;   // 0 while `live`, all ones otherwise (folded into the issue test)
   bool fresh = true;     // (re)start the segment on `cand` at the top of the next round
   unsigned w = 0u;       // current op word; 0 = list exhausted (or lane idle)
 
@@ -168,6 +171,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
         cand = (long long)__shfl(drawn, seg << lpc_shift, 64);
         running = (seg < cpw) && (cand < n_cand);
         live = running && lane_ok;
+        dead = live ? 0u : ~0u;
         cursor = 0; free_at = 0; busy = 0; mem = 0; pk = 0;
         has_pend = false;
         loaded = 0;
@@ -193,7 +197,9 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
           if (loaded >= stride) win[(stride & (kRing - 1)) * 64 + lane] = 0;
         }
       }
-      run_bases = __ballot(running) & base_bits;
+      const unsigned long long run_lanes = __ballot(running);
+      run_bases = run_lanes & base_bits;
+      idle_fields = ~run_lanes;
       if (run_bases == 0ull) break;  // every segment of the wave is out of work
     }
     if ((round & (kSyncRounds - 1)) == 0u) {
@@ -241,18 +247,19 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     // require state 15, which no activation is ever in.  Lanes without a device (and idle
     // segments) never initialise their LDS words, so they are masked off explicitly.
     const unsigned my = (unsigned)M.y, mz = (unsigned)M.z;
-    bool ok = live && (((sx >> (sh & 31u)) ^ mz) & 15u) == 0u && j < m;
-    int ready = 0;
-    if ((int)mz < 0) {   // kMetaHasCons is the sign bit
-      ok = ok && (in1 & 0xffu) == (my >> 24);
-      ready = (int)(in1 >> 8) + (int)(my & 0xfffffu);
-    }
+    // Everything that can forbid the issue is OR-ed into one word, so that the decision is a
+    // single vector compare: wrong activation state, micro-batch out of range (j != jj), lane
+    // not live, input slot not tagged with the upstream stage (only if the op has an input).
+    const unsigned has_in = (unsigned)((int)mz >> 31);   // kMetaHasCons is the sign bit
+    unsigned veto = (((sx >> (sh & 31u)) ^ mz) & 15u) | (unsigned)(j - jj) | dead |
+                    (((in1 ^ (my >> 24)) & 0xffu) & has_in);
+    int ready = (int)(((in1 >> 8) + (my & 0xfffffu)) & has_in);
     if (DEG2) {
-      if ((unsigned)M2.y & kMetaHasCons) {
-        ok = ok && (in2 & 0xffu) == (((unsigned)M2.y >> 16) & 0xffu);
-        ready = max(ready, (int)(in2 >> 8) + M2.x);
-      }
+      const unsigned has_in2 = (unsigned)((int)M2.y >> 31);
+      veto |= ((in2 ^ ((unsigned)M2.y >> 16)) & 0xffu) & has_in2;
+      ready = max(ready, (int)(((in2 >> 8) + (unsigned)M2.x) & has_in2));
     }
+    const bool ok = veto == 0u;
     // ---- issue
     if (ok) {
       const int dt = M.x;
@@ -274,13 +281,17 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       w = w_next;
     }
     __builtin_amdgcn_wave_barrier();
-    // a segment none of whose lanes issued is finished: fold the issue mask onto the segments'
-    // base bits (scalar unit)
-    unsigned long long any_moved = __ballot(ok);
+    // A segment none of whose lanes issued is finished.  Cheap scalar pre-test: does the issue
+    // mask, with the fields of idle segments filled, contain an all-zero field of lpc bits?
+    // (x - lows) & ~x & highs is non-zero iff some field of x is zero.
+    const unsigned long long moved = __ballot(ok);
+    const unsigned long long x = moved | idle_fields;
+    if ((((x - base_bits) & ~x) & high_bits) != 0ull) {
+      // fold the issue mask onto the segments' base bits to find which segments ended
+      unsigned long long any_moved = moved;
 #pragma unroll
-    for (int i = 0; i < 6; ++i) any_moved |= any_moved >> fold_shift[i];
-    const unsigned long long ended = ~any_moved & run_bases;
-    if (ended != 0ull) {
+      for (int i = 0; i < 6; ++i) any_moved |= any_moved >> fold_shift[i];
+      const unsigned long long ended = ~any_moved & run_bases;
       const bool seg_ended = ((ended >> (seg << lpc_shift)) & 1ull) != 0ull;
       // ---- the candidate is over: lists exhausted or nothing can move any more
       bool bad_head = false, incomplete = false;
@@ -313,6 +324,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
         }
         running = false;
         live = false;
+        dead = ~0u;
         w = 0u;
         fresh = true;
       }
