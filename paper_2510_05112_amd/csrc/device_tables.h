@@ -44,7 +44,7 @@ struct DevTables {
 //     x = dur
 //     y = latency of the first input edge (20) | state transition need ^ next (4) << 20
 //         | tag expected on the first input (8) << 24
-//     z = required state (4) | slot offset of the first output, or of the dump slot (16) << 4
+//     z = required state (4) | slot offset of the first output, or of the dump region (16) << 4
 //         | own stage (8) << 20 | kMeta* flags
 //     w = units allocated at the op's start (16) | units freed at its end (16) << 16
 //     Rows of words that may not appear on the device (no such chunk, kind 0, W without split
@@ -56,8 +56,8 @@ struct DevTables {
 //     slot offsets of the first forward / first backward / second forward / second backward input
 //   expect [lanes_per_cand][state_words]: the device's state words when every activation is done
 // A slot is one dword, finish << 8 | producer stage; offsets count slots from the candidate's
-// slot base: (dir * classes + class) * m; the dump slot (written by ops without an output
-// edge, never read) sits at 2 * classes * m.
+// slot base: (dir * classes + class) * m; the dump region (m slots written by ops without an
+// output edge, never read) starts at 2 * classes * m.
 constexpr unsigned kMetaInvalid = 1u << 28;
 constexpr unsigned kMetaHasProd = 1u << 30;
 constexpr unsigned kMetaHasCons = 1u << 31;
@@ -68,7 +68,7 @@ struct SlotTables {
   int32_t lanes_per_cand;   // power of two >= D
   int32_t cands_per_wave;
   int32_t n_classes;        // slot classes (1 for a chain)
-  int32_t slots_per_cand;   // 2 * classes * m + 1
+  int32_t slots_per_cand;   // (2 * classes + 1) * m
   int32_t state_words;      // dwords of 4-bit activation states per lane
   int32_t wave_ints;        // LDS dwords owned by one wavefront
   int32_t n_shared_ints;    // meta + meta2 (+ pad), copied to LDS once per workgroup

@@ -93,7 +93,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   uint16_t* win = reinterpret_cast<uint16_t*>(lds + T.n_shared_ints + wave * T.wave_ints);
   uint32_t* stt = reinterpret_cast<uint32_t*>(win) + (kRing / 2) * 64;   // [state word][lane]
   uint32_t* slots = stt + T.state_words * 64;
-  const int slots_per_cand = T.slots_per_cand;  // 2 * classes * m: forward, backward; + 1 dump slot
+  const int slots_per_cand = T.slots_per_cand;  // (2 * classes + 1) * m: forward, backward, dump
   __syncthreads();
 
   const int seg = lane >> lpc_shift;
@@ -260,6 +260,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       ready = max(ready, (int)(((in2 >> 8) + (unsigned)M2.x) & has_in2));
     }
     const bool ok = veto == 0u;
+    const unsigned long long moved = __builtin_amdgcn_ballot_w64(veto == 0u);
     // ---- issue
     if (ok) {
       const int dt = M.x;
@@ -267,11 +268,11 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       mem += (int)((unsigned)M.w & 0xffffu);
       pk = max(pk, mem);
       mem -= (int)((unsigned)M.w >> 16);
-      *reinterpret_cast<uint32_t*>(state_ptr) = sx ^ (((my >> 20) & 15u) << (sh & 31u));
+      *reinterpret_cast<uint32_t*>(state_ptr) = sx ^ __builtin_amdgcn_ubfe(my, 20, 4) << (sh & 31u);
       const unsigned val = ((unsigned)fin << 8) | ((mz >> 20) & 0xffu);
-      // ops without an output edge write the candidate's dump slot (byte offset in bits 4..19)
-      const unsigned out_j = ((unsigned)j << 2) & (unsigned)((int)(mz << 1) >> 31);
-      *reinterpret_cast<uint32_t*>(slot_base + ((mz >> 4) & 0xffffu) * 4u + out_j) = val;
+      // slot offset of the output in bits 4..19; ops without an output edge write the
+      // candidate's dump region, which nobody reads
+      *reinterpret_cast<uint32_t*>(slot_base + ((mz >> 4) & 0xffffu) * 4u + ((unsigned)j << 2)) = val;
       if (DEG2) {
         if ((unsigned)M2.y & kMetaHasProd) my_slots[((unsigned)M2.y & 0xffffu) + j] = val;
       }
@@ -284,7 +285,6 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     // A segment none of whose lanes issued is finished.  Cheap scalar pre-test: does the issue
     // mask, with the fields of idle segments filled, contain an all-zero field of lpc bits?
     // (x - lows) & ~x & highs is non-zero iff some field of x is zero.
-    const unsigned long long moved = __ballot(ok);
     const unsigned long long x = moved | idle_fields;
     if ((((x - base_bits) & ~x) & high_bits) != 0ull) {
       // fold the issue mask onto the segments' base bits to find which segments ended

@@ -233,7 +233,7 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
       const int V = p->slot_v = max_chunks <= 1 ? 1 : (max_chunks <= 2 ? 2 : 4);
       const int lpc = T.lanes_per_cand;
       // slot offsets are 16-bit, tags 8-bit (0xff = empty), finish times 24-bit
-      bool fits = 2ll * n_classes * m + 1 <= 0xffff && S <= 255 && max_comm < (1ll << 20) &&
+      bool fits = (2ll * n_classes + 1) * m <= 0xffff && S <= 255 && max_comm < (1ll << 20) &&
                   (int64_t)D * max_stride_words * (max_dur + max_comm) < (1ll << 24);
       bool deg2 = false;
       for (int s = 0; s < S; ++s) {
@@ -325,7 +325,7 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
         }
       }
       ST.D = D; ST.m = m; ST.lanes_per_cand = lpc; ST.n_classes = n_classes;
-      ST.slots_per_cand = 2 * n_classes * m + 1;
+      ST.slots_per_cand = (2 * n_classes + 1) * m;
       ST.state_words = state_words;
       ST.off_expect = n_meta + n_meta2 + lpc * dev_ints;
       ST.n_shared_ints = n_meta + n_meta2;
