@@ -159,7 +159,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   const unsigned long long my_cands = (unsigned long long)n_cand + 1ull;
   const unsigned long long bound = per_cand_rounds * my_cands;
   const unsigned max_rounds = bound > 0xfffffff0ull ? 0xfffffff0u : (unsigned)bound;
-  for (unsigned round = 0; round < max_rounds; ++round) {
+  for (unsigned round = 0; round < max_rounds; round += kSyncRounds) {
     // ---- (re)start segments on their next candidate
     if (any_fresh) {
       any_fresh = false;
@@ -202,7 +202,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       idle_fields = ~run_lanes;
       if (run_bases == 0ull) break;  // every segment of the wave is out of work
     }
-    if ((round & (kSyncRounds - 1)) == 0u) {
+    {
       // wave-wide top-up: land the chunk requested at the previous top-up, request the next
       if (has_pend) {
         const int q = loaded & (kRing - 1);
@@ -217,6 +217,10 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
         has_pend = true;
       }
     }
+    // kSyncRounds rounds between two top-ups; a segment that finishes in between idles until
+    // the next top-up, where it is restarted
+#pragma unroll
+    for (unsigned sub = 0; sub < kSyncRounds; ++sub) {
     // ---- decode the current word (already in a register) and issue this round's reads
     const int j = w & 0x7ff;
     const int nxt = cursor + 1;
@@ -328,8 +332,13 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
         w = 0u;
         fresh = true;
       }
+      // the finished segments stop counting as running at once
+      const unsigned long long run_lanes = __ballot(running);
+      run_bases = run_lanes & base_bits;
+      idle_fields = ~run_lanes;
       any_fresh = true;
     }
+    }  // sub-rounds
   }
 }
 
