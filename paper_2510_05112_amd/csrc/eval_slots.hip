@@ -68,8 +68,8 @@ constexpr int kPrimeChunks = 3;
 
 }  // namespace
 
-__global__ void reset_counter_kernel(unsigned long long* counter) {
-  if (threadIdx.x == 0) *counter = 0ull;
+__global__ void reset_counter_kernel(unsigned long long* counter, unsigned long long value) {
+  if (threadIdx.x == 0) *counter = value;
 }
 
 template <int V, bool DEG2, bool ONE_CLASS>
@@ -146,8 +146,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   bool has_pend = false;
   int cursor = 0, free_at = 0, busy = 0, mem = 0, pk = 0;
   bool running = false;  // this lane's segment is evaluating a candidate
-  bool live = false;     // ... and this lane carries one of its devices
-  unsigned dead = ~0u;   // 0 while `live`, all ones otherwise (folded into the issue test)
+  unsigned dead = ~0u;   // 0 while this lane carries a device of a running candidate, else all ones
   bool fresh = true;     // (re)start the segment on `cand` at the top of the next round
   unsigned w = 0u;       // current op word; 0 = list exhausted (or lane idle)
 
@@ -159,51 +158,41 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   const unsigned long long my_cands = (unsigned long long)n_cand + 1ull;
   const unsigned long long bound = per_cand_rounds * my_cands;
   const unsigned max_rounds = bound > 0xfffffff0ull ? 0xfffffff0u : (unsigned)bound;
+  // The first candidate of a segment is its global index; later ones are drawn from the counter
+  // (which the host presets to the number of segments) at the moment they are needed, so that the
+  // last candidates of a batch go to whichever segment is free.
+  bool first_draw = true;
+  uint2 prime0 = make_uint2(0, 0), prime1 = make_uint2(0, 0), prime2 = make_uint2(0, 0);
+  bool priming = false;      // the segment has requested the head of its rows and waits for the top-up
+  bool any_priming = false;  // wave-uniform
+  const int prime_words = stride < kPrimeChunks * kChunk ? stride : kPrimeChunks * kChunk;
   for (unsigned round = 0; round < max_rounds; round += kSyncRounds) {
-    // ---- (re)start segments on their next candidate
-    if (any_fresh) {
-      any_fresh = false;
-      if (fresh) {
-        fresh = false;
-        // the segment's first lane draws the next unevaluated candidate for the whole segment
-        unsigned long long drawn = 0ull;
-        if (d == 0 && seg < cpw) drawn = atomicAdd(next_candidate, 1ull);
-        cand = (long long)__shfl(drawn, seg << lpc_shift, 64);
-        running = (seg < cpw) && (cand < n_cand);
-        live = running && lane_ok;
-        dead = live ? 0u : ~0u;
-        cursor = 0; free_at = 0; busy = 0; mem = 0; pk = 0;
-        has_pend = false;
-        loaded = 0;
-        w = 0u;
-        if (running) {
-          for (int i = d; i < slots_per_cand; i += lpc) my_slots[i] = kEmptySlot;
-        }
-        if (live) {
-          for (int i = 0; i < T.state_words; ++i) stt[i * 64 + lane] = 0u;
-          row = ops + ((size_t)cand * T.D + d) * (size_t)stride;
-#pragma unroll
-          for (int q = 0; q < kPrimeChunks; ++q) {
-            if (loaded < stride) {
-              const uint2 v = *reinterpret_cast<const uint2*>(row + loaded);
-              // [word][lane] with 16-bit elements: word k of lane l at k * 64 + l
-              win[(q * 4 + 0) * 64 + lane] = (uint16_t)v.x; win[(q * 4 + 1) * 64 + lane] = (uint16_t)(v.x >> 16);
-              win[(q * 4 + 2) * 64 + lane] = (uint16_t)v.y; win[(q * 4 + 3) * 64 + lane] = (uint16_t)(v.y >> 16);
-              if (q == 0) w = v.x & 0xffffu;
-              loaded += kChunk;
-            }
+    {
+      // ---- wave-wide top-up of the op windows.  Loads requested at the previous top-up (or at a
+      // restart since then) are landed now, four rounds later, so nobody waits for HBM.
+      if (any_priming) {
+        any_priming = false;
+        if (priming && lane_ok) {
+          // [word][lane] with 16-bit elements: word k of lane l at k * 64 + l
+          win[0 * 64 + lane] = (uint16_t)prime0.x; win[1 * 64 + lane] = (uint16_t)(prime0.x >> 16);
+          win[2 * 64 + lane] = (uint16_t)prime0.y; win[3 * 64 + lane] = (uint16_t)(prime0.y >> 16);
+          win[4 * 64 + lane] = (uint16_t)prime1.x; win[5 * 64 + lane] = (uint16_t)(prime1.x >> 16);
+          win[6 * 64 + lane] = (uint16_t)prime1.y; win[7 * 64 + lane] = (uint16_t)(prime1.y >> 16);
+          if (prime_words > 8) {
+            win[8 * 64 + lane] = (uint16_t)prime2.x; win[9 * 64 + lane] = (uint16_t)(prime2.x >> 16);
+            win[10 * 64 + lane] = (uint16_t)prime2.y; win[11 * 64 + lane] = (uint16_t)(prime2.y >> 16);
           }
+          loaded = prime_words;
           // a row that fills its stride has no END word: plant one behind it
           if (loaded >= stride) win[(stride & (kRing - 1)) * 64 + lane] = 0;
+          w = prime0.x & 0xffffu;
+          dead = 0u;
         }
+        priming = false;
+        const unsigned long long run_lanes = __ballot(running);
+        run_bases = run_lanes & base_bits;
+        idle_fields = ~run_lanes;
       }
-      const unsigned long long run_lanes = __ballot(running);
-      run_bases = run_lanes & base_bits;
-      idle_fields = ~run_lanes;
-      if (run_bases == 0ull) break;  // every segment of the wave is out of work
-    }
-    {
-      // wave-wide top-up: land the chunk requested at the previous top-up, request the next
       if (has_pend) {
         const int q = loaded & (kRing - 1);
         win[(q + 0) * 64 + lane] = (uint16_t)pend.x; win[(q + 1) * 64 + lane] = (uint16_t)(pend.x >> 16);
@@ -216,6 +205,45 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
         pend = *reinterpret_cast<const uint2*>(row + loaded);
         has_pend = true;
       }
+    }
+    // ---- (re)start segments on their next candidate: reset their LDS, request the head of
+    // their rows; they join in at the next top-up
+    if (any_fresh) {
+      any_fresh = false;
+      if (fresh) {
+        fresh = false;
+        unsigned long long drawn = ((unsigned long long)blockIdx.x * (blockDim.x >> 6) + wave) * cpw + seg;
+        if (!first_draw) {
+          if (d == 0 && seg < cpw) drawn = atomicAdd(next_candidate, 1ull);
+          drawn = __shfl(drawn, seg << lpc_shift, 64);
+        }
+        first_draw = false;
+        cand = (long long)drawn;
+        running = (seg < cpw) && (cand < n_cand);
+        priming = running;
+        dead = ~0u;
+        cursor = 0; free_at = 0; busy = 0; mem = 0; pk = 0;
+        has_pend = false;
+        loaded = 0;
+        w = 0u;
+        if (running) {
+          for (int i = d; i < slots_per_cand; i += lpc) my_slots[i] = kEmptySlot;
+        }
+        if (running && lane_ok) {
+          for (int i = 0; i < T.state_words; ++i) stt[i * 64 + lane] = 0u;
+          row = ops + ((size_t)cand * T.D + d) * (size_t)stride;
+          prime0 = *reinterpret_cast<const uint2*>(row);
+          prime1 = *reinterpret_cast<const uint2*>(row + kChunk);
+          if (prime_words > 8) prime2 = *reinterpret_cast<const uint2*>(row + 2 * kChunk);
+        }
+      }
+      any_priming = true;
+      // segments that are priming do not count as running yet (nothing can move in them)
+      const unsigned long long all_running = __ballot(running);
+      const unsigned long long run_lanes = __ballot(running && !priming);
+      run_bases = run_lanes & base_bits;
+      idle_fields = ~run_lanes;
+      if (all_running == 0ull) break;  // every segment of the wave is out of work
     }
     // kSyncRounds rounds between two top-ups; a segment that finishes in between idles until
     // the next top-up, where it is restarted
@@ -327,13 +355,12 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
           }
         }
         running = false;
-        live = false;
         dead = ~0u;
         w = 0u;
         fresh = true;
       }
       // the finished segments stop counting as running at once
-      const unsigned long long run_lanes = __ballot(running);
+      const unsigned long long run_lanes = __ballot(running && !priming);
       run_bases = run_lanes & base_bits;
       idle_fields = ~run_lanes;
       any_fresh = true;

@@ -452,9 +452,11 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
     if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) & 15)) return FPSCHED_EINVAL;
     if (workspace_bytes < 256) return FPSCHED_ENOMEM;
     unsigned long long* counter = static_cast<unsigned long long*>(d_workspace);
-    hipLaunchKernelGGL(reset_counter_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(hip_stream), counter);
     const int per_block = p->stab.cands_per_wave * p->slot_waves;
     const int64_t blocks = std::min<int64_t>((n_cand + per_block - 1) / per_block, p->slot_grid);
+    // segment g starts on candidate g; the counter hands out the candidates after those
+    hipLaunchKernelGGL(reset_counter_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(hip_stream), counter,
+                       (unsigned long long)(blocks * per_block));
     hipLaunchKernelGGL(slot_kernel_ptr(p->slot_v, p->slot_deg2, p->stab.n_classes == 1), dim3((unsigned)blocks), dim3(64 * p->slot_waves),
                        (size_t)p->slot_lds_bytes, static_cast<hipStream_t>(hip_stream), p->stab, d_ops,
                        (long long)n_cand, (int)stride_words, reinterpret_cast<long long*>(out.makespan),
