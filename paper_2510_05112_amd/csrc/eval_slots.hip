@@ -268,10 +268,14 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     int2 M2 = make_int2(0, 0);
     unsigned in2 = 0u;
     if (DEG2) {
+      // second-edge rows are per direction, not per kind: only F, FD and B have cross-stage edges
+      const unsigned kind = w >> 13;
+      const bool has_edges = is_b || kind == (unsigned)kF || kind == (unsigned)kFD;
       M2 = meta2[(((is_b ? 4 : 0) + c) << lpc_shift) + d];
       const int coff2 = is_b ? pick<V>(cons_b2, c) : pick<V>(cons_f2, c);
       in2 = my_slots[coff2 + jj];
       asm volatile("" : "+v"(M2.x), "+v"(M2.y), "+v"(in2));
+      M2.y = has_edges ? M2.y : 0;
     }
     // keep every load of the round in front of the decision (one LDS round trip per round)
     asm volatile("" : "+v"(w_next), "+v"(M.x), "+v"(M.y), "+v"(M.z), "+v"(M.w), "+v"(sx), "+v"(in1));

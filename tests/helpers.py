@@ -17,6 +17,20 @@ def two_tower_problem(m=4, has_w=1, comm=1, mem_cap=None):
                         name="two_tower_tiny")
 
 
+def dag_problem(edges, n_stages, stage_device, n_devices, m=4, has_w=1, mem_cap=None, seed=0):
+    """Any stage DAG with seeded heterogeneous durations / latencies."""
+    rng = np.random.default_rng(seed)
+    S = n_stages
+    f = rng.integers(1, 9, S)
+    dur = {F: f, FD: f, R: rng.integers(1, 9, S), B: rng.integers(1, 15, S), O: rng.integers(1, 6, S),
+           L: rng.integers(1, 6, S)}
+    if has_w:
+        dur[W] = rng.integers(0, 7, S)
+    e = [(a, b, int(rng.integers(0, 5))) for a, b in edges]
+    return make_problem(n_devices, S, m, has_w, stage_device, e, dur, mem_units=rng.integers(1, 4, S),
+                        mem_cap=mem_cap, name="dag")
+
+
 def random_valid_lists(problem, rng, p_recompute=0.0, p_offload=0.0):
     """A random deadlock-free candidate: repeatedly append, to its device's list,
     one op drawn uniformly from the ops whose prerequisites are already listed."""

@@ -5,7 +5,7 @@ import pytest
 import oracle
 import workloads
 from gpu_common import check_batch, gpu_evaluate
-from helpers import batch_from_lists, perturb, random_valid_lists, two_tower_problem
+from helpers import batch_from_lists, dag_problem, perturb, random_valid_lists, two_tower_problem
 from workloads.problem import (B, F, FD, L, O, R, W, chain_problem, gpipe_lists,
                                one_f_one_b_lists, pack_lists, pack_word)
 
@@ -73,6 +73,35 @@ def test_random_dag():
             base = random_valid_lists(prob, rng, 0.2, 0.3)
             lists += [base, perturb(base, rng, 2)]
         check_batch(prob, batch_from_lists(lists), k=33, what="dag")
+
+
+DAGS = {
+    # diamond: one stage feeds two, which merge again (two outputs and two inputs)
+    "diamond": dict(edges=[(0, 1), (0, 2), (1, 3), (2, 3), (3, 4)], S=5, dev=[0, 1, 2, 3, 4], D=5),
+    # diamond with two stages sharing a device and a chain in front
+    "diamond_shared": dict(edges=[(0, 1), (1, 2), (1, 3), (2, 4), (3, 4)], S=5, dev=[0, 1, 2, 2, 0], D=3),
+    # two independent pipelines on interleaved devices (two sources, two sinks)
+    "two_chains": dict(edges=[(0, 1), (1, 2), (3, 4), (4, 5)], S=6, dev=[0, 1, 2, 2, 1, 0], D=3),
+    # three towers into one stage: more inputs than the slot kernel takes -> table kernel only
+    "three_towers": dict(edges=[(0, 3), (1, 3), (2, 3), (3, 4)], S=5, dev=[0, 1, 2, 3, 4], D=5),
+    # a single stage, no edges
+    "single": dict(edges=[], S=1, dev=[0], D=1),
+}
+
+
+@pytest.mark.parametrize("name", sorted(DAGS))
+@pytest.mark.parametrize("has_w", [0, 1])
+def test_stage_dags(name, has_w):
+    g = DAGS[name]
+    rng = np.random.default_rng(len(name) * 7 + has_w)
+    prob = dag_problem(g["edges"], g["S"], g["dev"], g["D"], m=5, has_w=has_w,
+                       mem_cap=rng.integers(4, 30, g["D"]), seed=len(name))
+    lists = []
+    for t in range(100):
+        base = random_valid_lists(prob, rng, 0.25 * (t % 2), 0.25 * ((t // 2) % 2))
+        lists += [base, perturb(base, rng, 1 + t % 2)]
+    gpu, ref = check_batch(prob, batch_from_lists(lists), k=9, what=name)
+    assert ((ref["flags"] & 3) == 0).sum() >= 100
 
 
 def test_edge_cases_flags_and_sentinels():
