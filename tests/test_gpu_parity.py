@@ -166,3 +166,51 @@ def test_topk_many_ties_and_large_k():
     words = workloads.generate(spec, threads=4)
     for k in (1, 16, 128, 1000, 1024):
         check_batch(spec.problem, words, k=k, what=f"ties k={k}")
+
+
+def test_call_errors_streams_and_workspace_reuse():
+    import torch
+
+    import paper_2510_05112_amd as fp
+    spec = workloads.config(2, 700)
+    words = workloads.generate(spec, threads=4)
+    ref = oracle.evaluate(spec.problem, words, threads=4)
+    h = fp.Problem(spec.problem, spec.stride, device=0)
+    ops = torch.from_numpy(words.view(np.int16)).cuda()
+    res = h.alloc_results(len(words))
+    ws = h.alloc_workspace(len(words), 16)
+    lib = fp.load_library()
+    R = fp.binding._Results(res["makespan"].data_ptr(), res["idle"].data_ptr(), res["peak"].data_ptr(),
+                            res["flags"].data_ptr())
+    ev = lambda ops_ptr, n, stride, ws_ptr, ws_bytes: lib.fpsched_evaluate(  # noqa: E731
+        h._h, ops_ptr, n, stride, R, ws_ptr, ws_bytes, 0)
+    assert ev(ops.data_ptr(), len(words), spec.stride, ws.data_ptr(), 8) == -2          # workspace too small
+    assert ev(ops.data_ptr(), len(words), spec.stride, 0, 0) == -1                      # no workspace
+    assert ev(ops.data_ptr() + 2, len(words), spec.stride, ws.data_ptr(), ws.numel()) == -1   # misaligned ops
+    assert ev(ops.data_ptr(), len(words), spec.stride + 8, ws.data_ptr(), ws.numel()) == -1   # stride > max
+    assert ev(ops.data_ptr(), len(words), 12, ws.data_ptr(), ws.numel()) == -1          # stride not a multiple of 8
+    assert ev(0, len(words), spec.stride, ws.data_ptr(), ws.numel()) == -1              # null ops
+    assert ev(ops.data_ptr(), -1, spec.stride, ws.data_ptr(), ws.numel()) == -1
+    out = dict(idx=torch.empty(16, dtype=torch.int64, device="cuda"),
+               makespan=torch.empty(16, dtype=torch.int64, device="cuda"),
+               count=torch.empty(1, dtype=torch.int32, device="cuda"))
+    tk = lambda k, ws_bytes: lib.fpsched_topk(h._h, R, len(words), k, out["idx"].data_ptr(),  # noqa: E731
+                                              out["makespan"].data_ptr(), out["count"].data_ptr(),
+                                              ws.data_ptr(), ws_bytes, 0)
+    assert tk(0, ws.numel()) == -1 and tk(1025, ws.numel()) == -1 and tk(16, 64) == -2
+    # a side stream, the same workspace for evaluate and top-k, several times in a row
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    idx, ms, cnt = oracle.topk(ref["makespan"], ref["flags"], 16)
+    for rep in range(3):
+        for t in res.values():
+            t.zero_()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            h.evaluate(ops, res, ws, stream=side)
+            top = h.topk(res, 16, ws, out, stream=side)
+        side.synchronize()
+        for name in ("makespan", "idle", "peak", "flags"):
+            assert np.array_equal(res[name].cpu().numpy(), ref[name]), (rep, name)
+        assert int(top["count"].item()) == cnt and np.array_equal(top["idx"].cpu().numpy(), idx)
+    h.close()
