@@ -42,10 +42,10 @@ struct DevTables {
 //   meta  [kNKinds * 4][lanes_per_cand] x 4 ints, one 16-byte row per (top five bits of the op
 //     word = kind * 4 + chunk, device):
 //     x = dur
-//     y = latency of the first input edge (20) | state transition need ^ next (4) << 20
-//         | tag expected on the first input (8) << 24
-//     z = required state (4) | slot offset of the first output, or of the dump region (16) << 4
-//         | own stage (8) << 20 | kMeta* flags
+//     y = required state (4) | latency of the first input edge (16) << 4
+//         | state transition need ^ next (4) << 20 | tag expected on the first input (8) << 24
+//     z = slot offset of the first output, or of the dump region (16) | own stage (8) << 16
+//         | kMeta* flags
 //     w = units allocated at the op's start (16) | units freed at its end (16) << 16
 //     Rows of words that may not appear on the device (no such chunk, kind 0, W without split
 //     backward) carry kMetaInvalid and require state 15, which no activation is ever in.
@@ -56,8 +56,8 @@ struct DevTables {
 //     slot offsets of the first forward / first backward / second forward / second backward input
 //   expect [lanes_per_cand][state_words]: the device's state words when every activation is done
 // A slot is one dword, finish << 8 | producer stage; offsets count slots from the candidate's
-// slot base: (dir * classes + class) * m; the dump region (m slots written by ops without an
-// output edge, never read) starts at 2 * classes * m.
+// slot base: class * m for backward values, (classes + class) * m for forward values; the dump
+// region (m slots written by ops without an output edge, never read) starts at 2 * classes * m.
 constexpr unsigned kMetaInvalid = 1u << 28;
 constexpr unsigned kMetaHasProd = 1u << 30;
 constexpr unsigned kMetaHasCons = 1u << 31;

@@ -260,9 +260,9 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     unsigned sx = *reinterpret_cast<uint32_t*>(state_ptr);
     const int c = (w >> 11) & 3;
     const bool is_b = (w >> 13) == (unsigned)kB;
-    // one class: forward inputs at slot j, backward inputs at slot m + j; bit 13 of the word is set
+    // one class: backward inputs at slot j, forward inputs at slot m + j; bit 13 of the word is set
     // for F and FD and clear for B (other kinds have no input, whatever they read is ignored)
-    const int in_off = ONE_CLASS ? (m << 2) - (int)__umul24((w >> 13) & 1u, (unsigned)m << 2)
+    const int in_off = ONE_CLASS ? (int)(((unsigned)((int)(w << 18) >> 31)) & ((unsigned)m << 2))
                                  : (is_b ? pick<V>(cons_b, c) : pick<V>(cons_f, c)) << 2;
     unsigned in1 = *reinterpret_cast<const uint32_t*>(slot_base + in_off + (jj << 2));
     int2 M2 = make_int2(0, 0);
@@ -287,9 +287,9 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     // single vector compare: wrong activation state, micro-batch out of range (j != jj), lane
     // not live, input slot not tagged with the upstream stage (only if the op has an input).
     const unsigned has_in = (unsigned)((int)mz >> 31);   // kMetaHasCons is the sign bit
-    unsigned veto = (((sx >> (sh & 31u)) ^ mz) & 15u) | (unsigned)(j - jj) | dead |
+    unsigned veto = (((sx >> (sh & 31u)) ^ my) & 15u) | (unsigned)(j - jj) | dead |
                     (((in1 ^ (my >> 24)) & 0xffu) & has_in);
-    int ready = (int)(((in1 >> 8) + (my & 0xfffffu)) & has_in);
+    int ready = (int)(((in1 >> 8) + __builtin_amdgcn_ubfe(my, 4, 16)) & has_in);
     if (DEG2) {
       const unsigned has_in2 = (unsigned)((int)M2.y >> 31);
       veto |= ((in2 ^ ((unsigned)M2.y >> 16)) & 0xffu) & has_in2;
@@ -305,10 +305,10 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       pk = max(pk, mem);
       mem -= (int)((unsigned)M.w >> 16);
       *reinterpret_cast<uint32_t*>(state_ptr) = sx ^ __builtin_amdgcn_ubfe(my, 20, 4) << (sh & 31u);
-      const unsigned val = ((unsigned)fin << 8) | ((mz >> 20) & 0xffu);
-      // slot offset of the output in bits 4..19; ops without an output edge write the
+      const unsigned val = ((unsigned)fin << 8) | ((mz >> 16) & 0xffu);
+      // slot offset of the output in the low half; ops without an output edge write the
       // candidate's dump region, which nobody reads
-      *reinterpret_cast<uint32_t*>(slot_base + ((mz >> 4) & 0xffffu) * 4u + ((unsigned)j << 2)) = val;
+      *reinterpret_cast<uint32_t*>(slot_base + ((mz & 0xffffu) << 2) + ((unsigned)j << 2)) = val;
       if (DEG2) {
         if ((unsigned)M2.y & kMetaHasProd) my_slots[((unsigned)M2.y & 0xffffu) + j] = val;
       }

@@ -233,7 +233,7 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
       const int V = p->slot_v = max_chunks <= 1 ? 1 : (max_chunks <= 2 ? 2 : 4);
       const int lpc = T.lanes_per_cand;
       // slot offsets are 16-bit, tags 8-bit (0xff = empty), finish times 24-bit
-      bool fits = (2ll * n_classes + 1) * m <= 0xffff && S <= 255 && max_comm < (1ll << 20) &&
+      bool fits = (2ll * n_classes + 1) * m <= 0xffff && S <= 255 && max_comm < (1ll << 16) &&
                   (int64_t)D * max_stride_words * (max_dur + max_comm) < (1ll << 24);
       bool deg2 = false;
       for (int s = 0; s < S; ++s) {
@@ -267,7 +267,8 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
         for (int c = 0; c < kMaxChunks; ++c)
           for (int d = 0; d < lpc; ++d) {
             int32_t* e = &J[(((size_t)kind * kMaxChunks + c) * lpc + d) * 4];
-            e[2] = (int32_t)(kMetaInvalid | 15u | (dump_slot << 4));
+            e[1] = 15;
+            e[2] = (int32_t)(kMetaInvalid | dump_slot);
             if (d >= D || c >= p->n_chunks[d] || kind == kEnd || (kind == kW && !p->has_w)) continue;
             const int s = p->local_stage[(size_t)d * kMaxChunks + c];
             const unsigned units = (unsigned)desc->mem_units[s];
@@ -277,14 +278,15 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
             int comm = 0;
             if (kind == kF || kind == kFD) {
               if (poff[s + 1] > poff[s]) { flags |= kMetaHasCons; tag = (unsigned)pst[poff[s]]; comm = pcm[poff[s]]; }
-              if (soff[s + 1] > soff[s]) { flags |= kMetaHasProd; prod = (unsigned)(scl[soff[s]] * m); }
+              if (soff[s + 1] > soff[s]) { flags |= kMetaHasProd; prod = (unsigned)((n_classes + scl[soff[s]]) * m); }
             } else if (kind == kB) {
               if (soff[s + 1] > soff[s]) { flags |= kMetaHasCons; tag = (unsigned)sst[soff[s]]; comm = scm[soff[s]]; }
-              if (poff[s + 1] > poff[s]) { flags |= kMetaHasProd; prod = (unsigned)((n_classes + pcl[poff[s]]) * m); }
+              if (poff[s + 1] > poff[s]) { flags |= kMetaHasProd; prod = (unsigned)(pcl[poff[s]] * m); }
             }
             e[0] = desc->dur[kind * S + s];
-            e[1] = (int32_t)((unsigned)comm | ((unsigned)(need_of[kind] ^ next_of[kind]) << 20) | (tag << 24));
-            e[2] = (int32_t)((unsigned)need_of[kind] | (prod << 4) | ((unsigned)s << 20) | flags);
+            e[1] = (int32_t)((unsigned)need_of[kind] | ((unsigned)comm << 4) |
+                             ((unsigned)(need_of[kind] ^ next_of[kind]) << 20) | (tag << 24));
+            e[2] = (int32_t)(prod | ((unsigned)s << 16) | flags);
             e[3] = (int32_t)((allocs ? units : 0u) | ((frees ? units : 0u) << 16));
           }
       for (int dir = 0; dir < 2 && deg2; ++dir)
@@ -296,10 +298,10 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
             unsigned y = 0;
             if (dir == 0) {
               if (poff[s + 1] - poff[s] > 1) { y |= kMetaHasCons | ((unsigned)pst[poff[s] + 1] << 16); e[0] = pcm[poff[s] + 1]; }
-              if (soff[s + 1] - soff[s] > 1) y |= kMetaHasProd | (unsigned)(scl[soff[s] + 1] * m);
+              if (soff[s + 1] - soff[s] > 1) y |= kMetaHasProd | (unsigned)((n_classes + scl[soff[s] + 1]) * m);
             } else {
               if (soff[s + 1] - soff[s] > 1) { y |= kMetaHasCons | ((unsigned)sst[soff[s] + 1] << 16); e[0] = scm[soff[s] + 1]; }
-              if (poff[s + 1] - poff[s] > 1) y |= kMetaHasProd | (unsigned)((n_classes + pcl[poff[s] + 1]) * m);
+              if (poff[s + 1] - poff[s] > 1) y |= kMetaHasProd | (unsigned)(pcl[poff[s] + 1] * m);
             }
             e[1] = (int32_t)y;
           }
@@ -318,10 +320,10 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
         for (int c = 0; c < p->n_chunks[d]; ++c) {
           const int s = p->local_stage[(size_t)d * kMaxChunks + c];
           const int nin = poff[s + 1] - poff[s], nout = soff[s + 1] - soff[s];
-          e[2 + c] = nin > 0 ? pcl[poff[s]] * m : 0;
-          e[2 + V + c] = nout > 0 ? (n_classes + scl[soff[s]]) * m : 0;
-          e[2 + 2 * V + c] = nin > 1 ? pcl[poff[s] + 1] * m : 0;
-          e[2 + 3 * V + c] = nout > 1 ? (n_classes + scl[soff[s] + 1]) * m : 0;
+          e[2 + c] = nin > 0 ? (n_classes + pcl[poff[s]]) * m : 0;
+          e[2 + V + c] = nout > 0 ? scl[soff[s]] * m : 0;
+          e[2 + 2 * V + c] = nin > 1 ? (n_classes + pcl[poff[s] + 1]) * m : 0;
+          e[2 + 3 * V + c] = nout > 1 ? scl[soff[s] + 1] * m : 0;
         }
       }
       ST.D = D; ST.m = m; ST.lanes_per_cand = lpc; ST.n_classes = n_classes;
