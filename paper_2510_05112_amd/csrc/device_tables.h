@@ -38,27 +38,28 @@ struct DevTables {
   const int32_t* ints;      // DEVICE
 };
 
-// Slot kernel tables.  `ints` = [meta][meta2][dev][expect]:
+// Slot kernel tables.  `ints` = [meta][meta2][pad to 512 ints][dev][expect]:
 //   meta  [kNKinds * 4][lanes_per_cand] x 4 ints, one 16-byte row per (top five bits of the op
 //     word = kind * 4 + chunk, device):
-//     x = dur
-//     y = required state (4) | latency of the first input edge (16) << 4
-//         | state transition need ^ next (4) << 20 | tag expected on the first input (8) << 24
-//     z = slot offset of the first output, or of the dump region (16) | own stage (8) << 16
-//         | kMeta* flags
-//     w = units allocated at the op's start (16) | units freed at its end (16) << 16
+//     x = dur << 8
+//     y = (latency of the first input edge << 8) - tag expected on the first input
+//     z = required state (low nibble of byte 0) | state transition need ^ next (byte 1)
+//         | byte offset of the first output slot, or of the dump region (16) << 16
+//     w = units allocated at the op's start (byte 0) | units freed at its end (byte 1)
+//         | own stage (byte 2) | 0xff if the op has a first input edge, else 0 (byte 3)
 //     Rows of words that may not appear on the device (no such chunk, kind 0, W without split
-//     backward) carry kMetaInvalid and require state 15, which no activation is ever in.
+//     backward) require state 15, which no activation is ever in.
 //   meta2 [2 * 4][lanes_per_cand] x 2 ints, second input/output edge per (direction, chunk, device):
-//     x = latency of the second input edge
-//     y = slot offset of the second output (16) | tag of the second input (8) << 16 | flags
-//   dev   [lanes_per_cand] x (2 + 4V) ints: chunks on the device, memory cap, then per chunk the
-//     slot offsets of the first forward / first backward / second forward / second backward input
+//     x = (latency of the second input edge << 8) - its tag
+//     y = byte offset of the second output slot (16) | kMetaHasProd | kMetaHasCons
+//   dev   [lanes_per_cand] x (2 + 4V) ints: chunks on the device, memory cap / unit_scale, then per
+//     chunk the slot offsets of the first forward / first backward / second forward / second
+//     backward input
 //   expect [lanes_per_cand][state_words]: the device's state words when every activation is done
-// A slot is one dword, finish << 8 | producer stage; offsets count slots from the candidate's
-// slot base: class * m for backward values, (classes + class) * m for forward values; the dump
+// A slot is one dword, finish << 8 | producer stage; offsets count from the candidate's slot
+// base: class * m slots for backward values, (classes + class) * m for forward values; the dump
 // region (m slots written by ops without an output edge, never read) starts at 2 * classes * m.
-constexpr unsigned kMetaInvalid = 1u << 28;
+// Memory units are divided by their greatest common divisor (unit_scale) and must then fit a byte.
 constexpr unsigned kMetaHasProd = 1u << 30;
 constexpr unsigned kMetaHasCons = 1u << 31;
 constexpr unsigned kEmptySlot = 0x000000ffu;  // finish 0, tag 0xff = no stage
@@ -68,10 +69,11 @@ struct SlotTables {
   int32_t lanes_per_cand;   // power of two >= D
   int32_t cands_per_wave;
   int32_t n_classes;        // slot classes (1 for a chain)
-  int32_t slots_per_cand;   // (2 * classes + 1) * m
+  int32_t slots_per_cand;   // (2 * classes + 1) * m, rounded up to a multiple of 8
+  int32_t unit_scale;       // common divisor of the memory units
   int32_t state_words;      // dwords of 4-bit activation states per lane
-  int32_t wave_ints;        // LDS dwords owned by one wavefront
-  int32_t n_shared_ints;    // meta + meta2 (+ pad), copied to LDS once per workgroup
+  int32_t wave_ints;        // LDS dwords owned by one wavefront (512 of them its op window)
+  int32_t n_shared_ints;    // meta + meta2 + pad to a multiple of 512, copied to LDS once per workgroup
   int32_t off_meta2;        // in ints
   int32_t off_dev;          // in ints
   int32_t dev_ints;         // 2 + 4V

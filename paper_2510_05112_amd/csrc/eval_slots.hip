@@ -33,7 +33,10 @@
 // round costs one LDS round trip.  Everything a round needs to know about an op --
 // duration, latency, expected input tag, state transition, memory deltas, output slot --
 // comes from one 16-byte metadata row addressed by the top five bits of the op word
-// and the device.  Whether a candidate completed (every activation consumed) and
+// and the device.  Times are kept shifted left by eight bits, the way a slot holds them
+// (finish << 8 | producer stage): adding the row's (latency << 8) - expected tag to a slot
+// value yields the ready time with a low byte that is zero iff the slot carries the expected
+// tag, so one addition serves the dependency test and the start rule.  Whether a candidate completed (every activation consumed) and
 // whether a stuck device sits on a malformed word are decided once, when it ends.
 //
 // Start rule (paper Section 5.1 "Data dependency"; estimator sketch after Section 6):
@@ -47,6 +50,30 @@
 namespace fpsched {
 
 namespace {
+
+// LDS accesses by 32-bit LDS address (the per-lane addresses are kept as integers so that ring
+// positions and table offsets can be OR-ed / multiplied into them)
+#define FPSCHED_LDS __attribute__((address_space(3)))
+template <class T>
+__device__ __forceinline__ T lds_read(unsigned a) {
+  return *reinterpret_cast<const FPSCHED_LDS T*>(a);
+}
+typedef int lds_int4 __attribute__((ext_vector_type(4)));
+typedef int lds_int2 __attribute__((ext_vector_type(2)));
+template <>
+__device__ __forceinline__ int4 lds_read<int4>(unsigned a) {
+  const lds_int4 v = *reinterpret_cast<const FPSCHED_LDS lds_int4*>(a);
+  return make_int4(v.x, v.y, v.z, v.w);
+}
+template <>
+__device__ __forceinline__ int2 lds_read<int2>(unsigned a) {
+  const lds_int2 v = *reinterpret_cast<const FPSCHED_LDS lds_int2*>(a);
+  return make_int2(v.x, v.y);
+}
+template <class T>
+__device__ __forceinline__ void lds_write(unsigned a, T v) {
+  *reinterpret_cast<FPSCHED_LDS T*>(a) = v;
+}
 
 template <int V>
 __device__ __forceinline__ int pick(const int (&a)[V], int c) {
@@ -85,15 +112,19 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   const int lpc = T.lanes_per_cand;
   const int lpc_shift = __ffs(lpc) - 1;
 
-  // shared: op metadata (+ second-edge metadata); per wave: window, state words, slots
+  // LDS: [metadata, padded to 2 KB][one 2 KB op window per wave][per wave: state words, slots].
+  // A window is 2 KB-aligned so that a ring position can be OR-ed into its address.
   for (int i = tid; i < T.n_shared_ints; i += blockDim.x) lds[i] = T.ints[i];
-  const char* lds_bytes = reinterpret_cast<const char*>(lds);
-  const int2* meta2 = reinterpret_cast<const int2*>(lds + T.off_meta2);
+  char* const L = reinterpret_cast<char*>(lds);
+  const unsigned lds0 = (unsigned)(size_t)(FPSCHED_LDS char*)lds;   // LDS address of the array
+  const unsigned shared_bytes = (unsigned)T.n_shared_ints * 4u;
+  const unsigned rest_ints = (unsigned)T.wave_ints - (kRing / 2) * 64u;
+  const unsigned rest_off = shared_bytes + (blockDim.x >> 6) * (kRing * 128u) + wave * rest_ints * 4u;
   // window: kRing sixteen-bit words per lane, laid out [word][lane]
-  uint16_t* win = reinterpret_cast<uint16_t*>(lds + T.n_shared_ints + wave * T.wave_ints);
-  uint32_t* stt = reinterpret_cast<uint32_t*>(win) + (kRing / 2) * 64;   // [state word][lane]
+  uint16_t* win = reinterpret_cast<uint16_t*>(L + shared_bytes + wave * (kRing * 128u));
+  uint32_t* stt = reinterpret_cast<uint32_t*>(L + rest_off);              // [state word][lane]
   uint32_t* slots = stt + T.state_words * 64;
-  const int slots_per_cand = T.slots_per_cand;  // (2 * classes + 1) * m: forward, backward, dump
+  const int slots_per_cand = T.slots_per_cand;  // backward, forward, dump; a multiple of 8
   __syncthreads();
 
   const int seg = lane >> lpc_shift;
@@ -102,7 +133,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   uint32_t* my_slots = slots + (seg < cpw ? seg : 0) * slots_per_cand;
   long long cand = 0;
 
-  // per-device constants: memory cap, slot offsets of the inputs of each chunk
+  // per-device constants: memory cap, byte offsets of the input slots of each chunk
   const int dd = d < T.D ? d : 0;
   const int32_t* dev = T.ints + T.off_dev + dd * T.dev_ints;
   const int32_t* expect = T.ints + T.off_expect + dd * T.state_words;
@@ -110,10 +141,10 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   int cons_f[V], cons_b[V], cons_f2[V], cons_b2[V];
 #pragma unroll
   for (int c = 0; c < V; ++c) {
-    cons_f[c] = dev[2 + c];
-    cons_b[c] = dev[2 + V + c];
-    cons_f2[c] = DEG2 ? dev[2 + 2 * V + c] : 0;
-    cons_b2[c] = DEG2 ? dev[2 + 3 * V + c] : 0;
+    cons_f[c] = dev[2 + c] << 2;
+    cons_b[c] = dev[2 + V + c] << 2;
+    cons_f2[c] = DEG2 ? dev[2 + 2 * V + c] << 2 : 0;
+    cons_b2[c] = DEG2 ? dev[2 + 3 * V + c] << 2 : 0;
     // have the constants in registers before the loop: a wait for them inside the loop would
     // also wait for the op-window prefetch
     asm volatile("" : "+v"(cons_f[c]), "+v"(cons_b[c]), "+v"(cons_f2[c]), "+v"(cons_b2[c]));
@@ -121,13 +152,21 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   asm volatile("" : "+v"(cap));
   const unsigned long long seg_mask =
       (lpc == 64 ? ~0ull : ((1ull << lpc) - 1ull)) << (seg * lpc);
-  const int meta_shift = 7 - lpc_shift;                 // op word >> this = row offset in bytes
-  const unsigned meta_mask = 0xF800u >> meta_shift;     // (kind, chunk) bits of that offset
-  const char* meta_lane = lds_bytes + (d << 4);         // this device's column of the metadata rows
-  const int words_per_chunk = (m + 7) >> 3;
-  const char* win_lane = reinterpret_cast<const char*>(win) + lane * 2;
-  char* stt_lane = reinterpret_cast<char*>(stt) + lane * 4;
-  char* slot_base = reinterpret_cast<char*>(my_slots);
+  // LDS byte offsets of this lane's columns
+  const unsigned row_bytes = (unsigned)lpc << 4;          // one metadata row: 16 bytes per device
+  const unsigned meta_off = lds0 + ((unsigned)d << 4);
+  const unsigned meta2_off = lds0 + (unsigned)T.off_meta2 * 4u + ((unsigned)d << 3);
+  const unsigned words_per_chunk = (unsigned)(m + 7) >> 3;
+  const unsigned win_off = lds0 + shared_bytes + wave * (kRing * 128u) + lane * 2u;   // word k at + k * 128
+  const unsigned stt_off = lds0 + rest_off + lane * 4u;                               // word i at + i * 256
+  // slots of this lane's candidate; the offset is a multiple of 32, so that the low five bits of
+  // (slot_base + 4 j) are the position of micro-batch j's nibble in its state word
+  const unsigned slot_base_ = lds0 + rest_off + (unsigned)T.state_words * 256u +
+                             (unsigned)(seg < cpw ? seg : 0) * (unsigned)slots_per_cand * 4u;
+  const unsigned m4 = (unsigned)m << 2;
+  const unsigned chunk_bytes = words_per_chunk << 8;   // state words of one chunk, all lanes
+  unsigned slot_base = slot_base_;
+  asm volatile("" : "+v"(slot_base));   // one register, not a sum to be re-associated every round
   // segment bookkeeping on the scalar unit: bit (seg * lpc) stands for segment seg
   unsigned long long base_bits = 0ull;
   for (int sgm = 0; sgm < cpw; ++sgm) base_bits |= 1ull << (sgm * lpc);
@@ -144,7 +183,9 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   int loaded = 0;  // words of this row already in the window ring
   uint2 pend = make_uint2(0, 0);
   bool has_pend = false;
-  int cursor = 0, free_at = 0, busy = 0, mem = 0, pk = 0;
+  unsigned cpos = 0;                 // list position << 7 (the byte stride of the window ring)
+  unsigned free_at8 = 0, busy8 = 0;  // device free time and busy time, << 8
+  int mem = 0, pk = 0;               // in units of the problem's common unit divisor
   bool running = false;  // this lane's segment is evaluating a candidate
   unsigned dead = ~0u;   // 0 while this lane carries a device of a running candidate, else all ones
   bool fresh = true;     // (re)start the segment on `cand` at the top of the next round
@@ -201,7 +242,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
         has_pend = false;
         if (loaded >= stride) win[(stride & (kRing - 1)) * 64 + lane] = 0;
       }
-      if (w != 0u && loaded - cursor <= kRefillAt && loaded < stride) {
+      if (w != 0u && loaded - (int)(cpos >> 7) <= kRefillAt && loaded < stride) {
         pend = *reinterpret_cast<const uint2*>(row + loaded);
         has_pend = true;
       }
@@ -222,7 +263,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
         running = (seg < cpw) && (cand < n_cand);
         priming = running;
         dead = ~0u;
-        cursor = 0; free_at = 0; busy = 0; mem = 0; pk = 0;
+        cpos = 0; free_at8 = 0; busy8 = 0; mem = 0; pk = 0;
         has_pend = false;
         loaded = 0;
         w = 0u;
@@ -250,71 +291,84 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
 #pragma unroll
     for (unsigned sub = 0; sub < kSyncRounds; ++sub) {
     // ---- decode the current word (already in a register) and issue this round's reads
-    const int j = w & 0x7ff;
-    const int nxt = cursor + 1;
-    unsigned w_next = *reinterpret_cast<const uint16_t*>(win_lane + ((nxt & (kRing - 1)) << 7));
-    int4 M = *reinterpret_cast<const int4*>(meta_lane + ((w >> meta_shift) & meta_mask));
-    const int jj = min(j, m - 1);
-    const unsigned sh = (unsigned)jj << 2;   // shift counts use their low five bits: (jj & 7) * 4
-    char* state_ptr = stt_lane + __umul24((w >> 11) & (V - 1), (unsigned)words_per_chunk << 8) + ((jj & ~7) << 5);
-    unsigned sx = *reinterpret_cast<uint32_t*>(state_ptr);
-    const int c = (w >> 11) & 3;
+    const unsigned j = w & 0x7ffu;
+    const unsigned nxt = cpos + 128u;
+    unsigned w_next = lds_read<uint16_t>((nxt & ((kRing - 1) << 7)) | win_off);
+    const unsigned c5 = w >> 11;
+    int4 M = lds_read<int4>(__umul24(c5, row_bytes) + meta_off);
+    const unsigned jc = min(j, (unsigned)m - 1u);
+    const bool in_range = j == jc;
+    unsigned c = c5 & (unsigned)(V - 1);
+    unsigned fwd = (w >> 13) & 1u;
+    // (opaque to the optimiser, which would otherwise turn the multiplications by these small
+    // values into longer compare-and-select sequences)
+    unsigned jw = jc >> 3;   // state word of the micro-batch inside its chunk
+    asm("" : "+v"(c), "+v"(fwd), "+v"(jw));
+    unsigned state_at = (jw << 8) + (__umul24(c, chunk_bytes) + stt_off);
+    asm("" : "+v"(state_at));   // read and write address: keep it instead of recomputing it
+    unsigned sx = lds_read<uint32_t>(state_at);
+    const unsigned bj = (jc << 2) + slot_base;   // slot j of the first class; low five bits = 4 (j & 7)
     const bool is_b = (w >> 13) == (unsigned)kB;
     // one class: backward inputs at slot j, forward inputs at slot m + j; bit 13 of the word is set
     // for F and FD and clear for B (other kinds have no input, whatever they read is ignored)
-    const int in_off = ONE_CLASS ? (int)(((unsigned)((int)(w << 18) >> 31)) & ((unsigned)m << 2))
-                                 : (is_b ? pick<V>(cons_b, c) : pick<V>(cons_f, c)) << 2;
-    unsigned in1 = *reinterpret_cast<const uint32_t*>(slot_base + in_off + (jj << 2));
+    const unsigned in_at = ONE_CLASS ? __umul24(fwd, m4) + bj
+                                     : bj + (unsigned)(is_b ? pick<V>(cons_b, c) : pick<V>(cons_f, c));
+    unsigned in1 = lds_read<uint32_t>(in_at);
     int2 M2 = make_int2(0, 0);
     unsigned in2 = 0u;
     if (DEG2) {
       // second-edge rows are per direction, not per kind: only F, FD and B have cross-stage edges
       const unsigned kind = w >> 13;
       const bool has_edges = is_b || kind == (unsigned)kF || kind == (unsigned)kFD;
-      M2 = meta2[(((is_b ? 4 : 0) + c) << lpc_shift) + d];
-      const int coff2 = is_b ? pick<V>(cons_b2, c) : pick<V>(cons_f2, c);
-      in2 = my_slots[coff2 + jj];
+      M2 = lds_read<int2>(((((is_b ? 4u : 0u) + c) << lpc_shift) << 3) + meta2_off);
+      in2 = lds_read<uint32_t>(bj + (unsigned)(is_b ? pick<V>(cons_b2, c) : pick<V>(cons_f2, c)));
       asm volatile("" : "+v"(M2.x), "+v"(M2.y), "+v"(in2));
       M2.y = has_edges ? M2.y : 0;
     }
     // keep every load of the round in front of the decision (one LDS round trip per round)
-    asm volatile("" : "+v"(w_next), "+v"(M.x), "+v"(M.y), "+v"(M.z), "+v"(M.w), "+v"(sx), "+v"(in1));
-    // ---- decide.  An exhausted lane has w == 0, whose metadata row is invalid; invalid rows
-    // require state 15, which no activation is ever in.  Lanes without a device (and idle
+    asm volatile("" : "+v"(w_next), "+v"(sx), "+v"(in1));
+    // ---- decide.  An exhausted lane sits on a word of kind 0, whose metadata row is invalid; invalid
+    // rows require state 15, which no activation is ever in.  Lanes without a device (and idle
     // segments) never initialise their LDS words, so they are masked off explicitly.
-    const unsigned my = (unsigned)M.y, mz = (unsigned)M.z;
-    // Everything that can forbid the issue is OR-ed into one word, so that the decision is a
-    // single vector compare: wrong activation state, micro-batch out of range (j != jj), lane
-    // not live, input slot not tagged with the upstream stage (only if the op has an input).
-    const unsigned has_in = (unsigned)((int)mz >> 31);   // kMetaHasCons is the sign bit
-    unsigned veto = (((sx >> (sh & 31u)) ^ my) & 15u) | (unsigned)(j - jj) | dead |
-                    (((in1 ^ (my >> 24)) & 0xffu) & has_in);
-    int ready = (int)(((in1 >> 8) + __builtin_amdgcn_ubfe(my, 4, 16)) & has_in);
+    const unsigned dur8 = (unsigned)M.x, lat_tag = (unsigned)M.y, mx_ = (unsigned)M.z, my_ = (unsigned)M.w;
+    // Everything that can forbid the issue is OR-ed into the low byte of one word: wrong activation
+    // state; input slot not tagged with the upstream stage (only if the op has an input: the top
+    // byte of the last metadata dword is 0xff then, else 0).  A live lane has dead == 0, any other
+    // lane all ones, which the word never equals.
+    const unsigned state = __builtin_amdgcn_ubfe(sx, bj, 4);
+    unsigned ready8 = (in1 + lat_tag) & (unsigned)((int)my_ >> 24);
+    unsigned veto = (state ^ (mx_ & 0xffu)) | (ready8 & 0xffu);
     if (DEG2) {
-      const unsigned has_in2 = (unsigned)((int)M2.y >> 31);
-      veto |= ((in2 ^ ((unsigned)M2.y >> 16)) & 0xffu) & has_in2;
-      ready = max(ready, (int)(((in2 >> 8) + (unsigned)M2.x) & has_in2));
+      const unsigned ready2 = (in2 + (unsigned)M2.x) & (unsigned)(M2.y >> 31);
+      veto |= ready2 & 0xffu;
+      ready8 = max(ready8, ready2);
     }
-    const bool ok = veto == 0u;
-    const unsigned long long moved = __builtin_amdgcn_ballot_w64(veto == 0u);
+    // micro-batch in range (the addresses above used the clamped one) and nothing vetoes
+    const unsigned long long moved =
+        __builtin_amdgcn_ballot_w64(veto == dead) & __builtin_amdgcn_ballot_w64(in_range);
+    const bool ok = (veto == dead) && in_range;
     // ---- issue
     if (ok) {
-      const int dt = M.x;
-      const int fin = max(free_at, ready) + dt;
-      mem += (int)((unsigned)M.w & 0xffffu);
+      const unsigned fin8 = max(free_at8, ready8) + dur8;
+      mem += (int)(my_ & 0xffu);
       pk = max(pk, mem);
-      mem -= (int)((unsigned)M.w >> 16);
-      *reinterpret_cast<uint32_t*>(state_ptr) = sx ^ __builtin_amdgcn_ubfe(my, 20, 4) << (sh & 31u);
-      const unsigned val = ((unsigned)fin << 8) | ((mz >> 16) & 0xffu);
-      // slot offset of the output in the low half; ops without an output edge write the
+      mem -= (int)((my_ >> 8) & 0xffu);
+      // state ^= (need ^ next) << nibble position; the shift takes the low five bits of bj
+      unsigned flip;
+      asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1"
+          : "=v"(flip) : "v"(bj), "v"(mx_));
+      lds_write<uint32_t>(state_at, sx ^ flip);
+      // finish << 8 | own stage (byte 2 of the last metadata dword; the low byte of fin8 is zero)
+      const unsigned val = __builtin_amdgcn_perm(fin8, my_, 0x07060502u);
+      // byte offset of the output slot in the high half; ops without an output edge write the
       // candidate's dump region, which nobody reads
-      *reinterpret_cast<uint32_t*>(slot_base + ((mz & 0xffffu) << 2) + ((unsigned)j << 2)) = val;
+      lds_write<uint32_t>(bj + (mx_ >> 16), val);
       if (DEG2) {
-        if ((unsigned)M2.y & kMetaHasProd) my_slots[((unsigned)M2.y & 0xffffu) + j] = val;
+        if ((unsigned)M2.y & kMetaHasProd) lds_write<uint32_t>(bj + ((unsigned)M2.y & 0xffffu), val);
       }
-      free_at = fin;
-      busy += dt;
-      cursor = nxt;
+      free_at8 = fin8;
+      busy8 += dur8;
+      cpos = nxt;
       w = w_next;
     }
     __builtin_amdgcn_wave_barrier();
@@ -333,16 +387,17 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       bool bad_head = false, incomplete = false;
       if (seg_ended && lane_ok) {
         // a stuck device sits on a malformed word?
-        const int4 Mh = *reinterpret_cast<const int4*>(meta_lane + ((w >> meta_shift) & meta_mask));
-        bad_head = w != 0u && (((unsigned)Mh.z & kMetaInvalid) || (int)(w & 0x7ff) >= m);
+        const int4 Mh = lds_read<int4>(__umul24(w >> 11, row_bytes) + meta_off);
+        bad_head = (w >> 13) != 0u && (((unsigned)Mh.z & 15u) == 15u || (int)(w & 0x7ff) >= m);
         // every activation of this device consumed?
         for (int i = 0; i < T.state_words; ++i) incomplete = incomplete || (stt[i * 64 + lane] != (unsigned)expect[i]);
       }
-      const unsigned long long stuck = __ballot(lane_ok && w != 0u) & seg_mask;
+      // (kind 0 ends a list whatever its low bits are)
+      const unsigned long long stuck = __ballot(lane_ok && (w >> 13) != 0u) & seg_mask;
       const unsigned long long stuck_bad = __ballot(bad_head) & seg_mask;
       const unsigned long long unfinished = __ballot(incomplete) & seg_mask;
       const unsigned long long over = __ballot(lane_ok && pk > cap) & seg_mask;
-      int ms = lane_ok ? free_at : 0;
+      int ms = lane_ok ? (int)(free_at8 >> 8) : 0;
       for (int off = 1; off < lpc; off <<= 1) ms = max(ms, __shfl_xor(ms, off, 64));
       if (seg_ended) {
         unsigned flg = 0;
@@ -351,8 +406,8 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
         else if (over) flg = kOverCap;
         if (lane_ok) {
           const bool failed = (flg & (kDeadlock | kIncomplete)) != 0;
-          out_idle[cand * T.D + d] = failed ? -1ll : (long long)(ms - busy);
-          out_peak[cand * T.D + d] = failed ? -1 : pk;
+          out_idle[cand * T.D + d] = failed ? -1ll : (long long)(ms - (int)(busy8 >> 8));
+          out_peak[cand * T.D + d] = failed ? -1 : pk * T.unit_scale;
           if (d == 0) {
             out_makespan[cand] = failed ? 0x7fffffffffffffffll : (long long)ms;
             out_flags[cand] = (unsigned char)flg;

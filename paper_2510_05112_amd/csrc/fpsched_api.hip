@@ -6,6 +6,7 @@
 
 #include <algorithm>
 #include <new>
+#include <numeric>
 #include <vector>
 
 #include "../../include/fpsched.h"
@@ -232,15 +233,20 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
       for (int d = 0; d < D; ++d) max_chunks = std::max(max_chunks, p->n_chunks[d]);
       const int V = p->slot_v = max_chunks <= 1 ? 1 : (max_chunks <= 2 ? 2 : 4);
       const int lpc = T.lanes_per_cand;
-      // slot offsets are 16-bit, tags 8-bit (0xff = empty), finish times 24-bit
-      bool fits = (2ll * n_classes + 1) * m <= 0xffff && S <= 255 && max_comm < (1ll << 16) &&
+      // memory units are carried in bytes: divide them (and the caps) by their common divisor
+      int64_t unit_scale = 0;
+      for (int s = 0; s < S; ++s) unit_scale = std::gcd<int64_t, int64_t>(unit_scale, desc->mem_units[s]);
+      if (unit_scale < 1) unit_scale = 1;
+      const int slot_stride = ((2 * n_classes + 1) * m + 7) & ~7;   // slots of one candidate
+      // slot byte offsets are 16-bit, tags 8-bit (0xff = empty), finish times 24-bit
+      bool fits = 4ll * slot_stride <= 0xffff && S <= 255 && max_comm < (1ll << 16) &&
                   (int64_t)D * max_stride_words * (max_dur + max_comm) < (1ll << 24);
       bool deg2 = false;
       for (int s = 0; s < S; ++s) {
         const int nin = poff[s + 1] - poff[s], nout = soff[s + 1] - soff[s];
         if (nin > 2 || nout > 2) fits = false;
         if (nin > 1 || nout > 1) deg2 = true;
-        if (desc->mem_units[s] > 0xffff) fits = false;
+        if (desc->mem_units[s] / unit_scale > 0xff) fits = false;
       }
       p->slot_deg2 = deg2;
       // classes of the edges in pred-CSR and succ-CSR order
@@ -255,39 +261,38 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
       }
       const int n_meta = kNKinds * kMaxChunks * lpc * 4;
       const int n_meta2 = deg2 ? 2 * kMaxChunks * lpc * 2 : 0;
-      const unsigned dump_slot = (unsigned)(2 * n_classes * m);
+      const int n_shared = (n_meta + n_meta2 + 511) & ~511;   // the op windows behind it are 2 KB-aligned
+      const unsigned dump_bytes = (unsigned)(2 * n_classes * m) * 4u;
       const int dev_ints = 2 + 4 * V;
       const int words_per_chunk = (m + 7) / 8;
       const int state_words = V * words_per_chunk;
       std::vector<int32_t>& J = p->slot_ints;
-      J.assign((size_t)n_meta + n_meta2 + (size_t)lpc * dev_ints + (size_t)lpc * state_words, 0);
+      J.assign((size_t)n_shared + (size_t)lpc * dev_ints + (size_t)lpc * state_words, 0);
       static const int need_of[kNKinds] = {15, kAbsent, kRes, kBDone, kDisc, kRes, kOff, kAbsent};
       static const int next_of[kNKinds] = {0, kRes, kBDone, kDone, kRes, kOff, kRes, kDisc};
       for (int kind = 0; kind < kNKinds; ++kind)
         for (int c = 0; c < kMaxChunks; ++c)
           for (int d = 0; d < lpc; ++d) {
             int32_t* e = &J[(((size_t)kind * kMaxChunks + c) * lpc + d) * 4];
-            e[1] = 15;
-            e[2] = (int32_t)(kMetaInvalid | dump_slot);
+            e[2] = (int32_t)(15u | (dump_bytes << 16));
             if (d >= D || c >= p->n_chunks[d] || kind == kEnd || (kind == kW && !p->has_w)) continue;
             const int s = p->local_stage[(size_t)d * kMaxChunks + c];
-            const unsigned units = (unsigned)desc->mem_units[s];
+            const unsigned units = (unsigned)(desc->mem_units[s] / unit_scale);
             const bool allocs = kind == kF || kind == kFD || kind == kR || kind == kL;
             const bool frees = kind == kFD || kind == kO || kind == (p->has_w ? kW : kB);
-            unsigned flags = 0, tag = 0, prod = dump_slot;
-            int comm = 0;
+            unsigned has_in = 0, tag = 0, prod = dump_bytes;
+            unsigned comm = 0;
             if (kind == kF || kind == kFD) {
-              if (poff[s + 1] > poff[s]) { flags |= kMetaHasCons; tag = (unsigned)pst[poff[s]]; comm = pcm[poff[s]]; }
-              if (soff[s + 1] > soff[s]) { flags |= kMetaHasProd; prod = (unsigned)((n_classes + scl[soff[s]]) * m); }
+              if (poff[s + 1] > poff[s]) { has_in = 0xffu; tag = (unsigned)pst[poff[s]]; comm = (unsigned)pcm[poff[s]]; }
+              if (soff[s + 1] > soff[s]) prod = (unsigned)((n_classes + scl[soff[s]]) * m) * 4u;
             } else if (kind == kB) {
-              if (soff[s + 1] > soff[s]) { flags |= kMetaHasCons; tag = (unsigned)sst[soff[s]]; comm = scm[soff[s]]; }
-              if (poff[s + 1] > poff[s]) { flags |= kMetaHasProd; prod = (unsigned)(pcl[poff[s]] * m); }
+              if (soff[s + 1] > soff[s]) { has_in = 0xffu; tag = (unsigned)sst[soff[s]]; comm = (unsigned)scm[soff[s]]; }
+              if (poff[s + 1] > poff[s]) prod = (unsigned)(pcl[poff[s]] * m) * 4u;
             }
-            e[0] = desc->dur[kind * S + s];
-            e[1] = (int32_t)((unsigned)need_of[kind] | ((unsigned)comm << 4) |
-                             ((unsigned)(need_of[kind] ^ next_of[kind]) << 20) | (tag << 24));
-            e[2] = (int32_t)(prod | ((unsigned)s << 16) | flags);
-            e[3] = (int32_t)((allocs ? units : 0u) | ((frees ? units : 0u) << 16));
+            e[0] = (int32_t)((unsigned)desc->dur[kind * S + s] << 8);
+            e[1] = (int32_t)((comm << 8) - tag);
+            e[2] = (int32_t)((unsigned)need_of[kind] | ((unsigned)(need_of[kind] ^ next_of[kind]) << 8) | (prod << 16));
+            e[3] = (int32_t)((allocs ? units : 0u) | ((frees ? units : 0u) << 8) | ((unsigned)s << 16) | (has_in << 24));
           }
       for (int dir = 0; dir < 2 && deg2; ++dir)
         for (int c = 0; c < kMaxChunks; ++c)
@@ -297,26 +302,26 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
             int32_t* e = &J[(size_t)n_meta + (((size_t)dir * kMaxChunks + c) * lpc + d) * 2];
             unsigned y = 0;
             if (dir == 0) {
-              if (poff[s + 1] - poff[s] > 1) { y |= kMetaHasCons | ((unsigned)pst[poff[s] + 1] << 16); e[0] = pcm[poff[s] + 1]; }
-              if (soff[s + 1] - soff[s] > 1) y |= kMetaHasProd | (unsigned)((n_classes + scl[soff[s] + 1]) * m);
+              if (poff[s + 1] - poff[s] > 1) { y |= kMetaHasCons; e[0] = (int32_t)(((unsigned)pcm[poff[s] + 1] << 8) - (unsigned)pst[poff[s] + 1]); }
+              if (soff[s + 1] - soff[s] > 1) y |= kMetaHasProd | ((unsigned)((n_classes + scl[soff[s] + 1]) * m) * 4u);
             } else {
-              if (soff[s + 1] - soff[s] > 1) { y |= kMetaHasCons | ((unsigned)sst[soff[s] + 1] << 16); e[0] = scm[soff[s] + 1]; }
-              if (poff[s + 1] - poff[s] > 1) y |= kMetaHasProd | (unsigned)(pcl[poff[s] + 1] * m);
+              if (soff[s + 1] - soff[s] > 1) { y |= kMetaHasCons; e[0] = (int32_t)(((unsigned)scm[soff[s] + 1] << 8) - (unsigned)sst[soff[s] + 1]); }
+              if (poff[s + 1] - poff[s] > 1) y |= kMetaHasProd | ((unsigned)(pcl[poff[s] + 1] * m) * 4u);
             }
             e[1] = (int32_t)y;
           }
       for (int d = 0; d < D; ++d) {
         // state words of device d once every activation placed on it is consumed
-        int32_t* x = &J[(size_t)n_meta + n_meta2 + (size_t)lpc * dev_ints + (size_t)d * state_words];
+        int32_t* x = &J[(size_t)n_shared + (size_t)lpc * dev_ints + (size_t)d * state_words];
         const unsigned terminal = p->has_w ? kDone : kBDone;
         for (int c = 0; c < p->n_chunks[d]; ++c)
           for (int j = 0; j < m; ++j)
             x[c * words_per_chunk + (j >> 3)] |= (int32_t)(terminal << ((j & 7) * 4));
       }
       for (int d = 0; d < D; ++d) {
-        int32_t* e = &J[(size_t)n_meta + n_meta2 + (size_t)d * dev_ints];
+        int32_t* e = &J[(size_t)n_shared + (size_t)d * dev_ints];
         e[0] = p->n_chunks[d];
-        e[1] = desc->mem_cap[d];
+        e[1] = (int32_t)(desc->mem_cap[d] / unit_scale);   // peak > cap  <=>  peak / scale > floor(cap / scale)
         for (int c = 0; c < p->n_chunks[d]; ++c) {
           const int s = p->local_stage[(size_t)d * kMaxChunks + c];
           const int nin = poff[s + 1] - poff[s], nout = soff[s + 1] - soff[s];
@@ -327,12 +332,13 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
         }
       }
       ST.D = D; ST.m = m; ST.lanes_per_cand = lpc; ST.n_classes = n_classes;
-      ST.slots_per_cand = (2 * n_classes + 1) * m;
+      ST.slots_per_cand = slot_stride;
+      ST.unit_scale = (int32_t)unit_scale;
       ST.state_words = state_words;
-      ST.off_expect = n_meta + n_meta2 + lpc * dev_ints;
-      ST.n_shared_ints = n_meta + n_meta2;
+      ST.off_expect = n_shared + lpc * dev_ints;
+      ST.n_shared_ints = n_shared;
       ST.off_meta2 = n_meta;
-      ST.off_dev = n_meta + n_meta2;
+      ST.off_dev = n_shared;
       ST.dev_ints = dev_ints;
       // geometry: candidates per wave, then the workgroup shape that keeps the most
       // wavefronts resident on a compute unit (LDS is the only limiter: ~50 VGPRs)

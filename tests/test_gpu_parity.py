@@ -127,6 +127,20 @@ def test_edge_cases_flags_and_sentinels():
     assert list(ref["flags"]) == [4, 1, 1, 1, 2, 2, 3, 3, 3, 1, 2, 4]
 
 
+def test_end_words_with_low_bits_set():
+    # kind 0 ends a list whatever its chunk and micro-batch bits say
+    p, m = 3, 5
+    prob = chain_problem(p, m, f=2, b=3, comm=1)
+    base = batch_from_lists([gpipe_lists(p, m), one_f_one_b_lists(p, m)], stride=24)
+    words = np.concatenate([base, base, base])
+    words[2:4][words[2:4] == 0] = 0x0005          # terminators and padding of kind 0, mb 5
+    words[4:6][words[4:6] == 0] = 0x1fff          # kind 0 with every other bit set
+    words[5, 1, 3] = 0x0802                       # cuts device 1 short: incomplete, not a deadlock
+    gpu, ref = check_batch(prob, words, k=4, what="end words")
+    assert list(ref["flags"][:5]) == [0] * 5 and ref["flags"][5] != 0
+    assert np.array_equal(ref["makespan"][:2], ref["makespan"][2:4])
+
+
 def test_empty_batch_single_candidate_and_ragged_tail():
     spec = workloads.config(2, 64)
     words = workloads.generate(spec, threads=2)
