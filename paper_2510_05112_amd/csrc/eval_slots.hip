@@ -371,12 +371,13 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       cpos = nxt;
       w = w_next;
     }
-    __builtin_amdgcn_wave_barrier();
-    // A segment none of whose lanes issued is finished.  Cheap scalar pre-test: does the issue
-    // mask, with the fields of idle segments filled, contain an all-zero field of lpc bits?
-    // (x - lows) & ~x & highs is non-zero iff some field of x is zero.
+    // A segment none of whose lanes issued is finished, and stays so: nothing it reads changes any
+    // more.  It could only be restarted at the next top-up anyway, so only the last round before
+    // the top-up looks.  Cheap scalar pre-test: does the issue mask, with the fields of idle
+    // segments filled, contain an all-zero field of lpc bits?  (x - lows) & ~x & highs is non-zero
+    // iff some field of x is zero.
     const unsigned long long x = moved | idle_fields;
-    if ((((x - base_bits) & ~x) & high_bits) != 0ull) {
+    if (sub == kSyncRounds - 1 && (((x - base_bits) & ~x) & high_bits) != 0ull) {
       // fold the issue mask onto the segments' base bits to find which segments ended
       unsigned long long any_moved = moved;
 #pragma unroll
