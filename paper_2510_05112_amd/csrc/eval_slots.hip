@@ -191,6 +191,36 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   bool fresh = true;     // (re)start the segment on `cand` at the top of the next round
   unsigned w = 0u;       // current op word; 0 = list exhausted (or lane idle)
 
+  // LDS addresses of everything a round reads for the current word.  They only change when the
+  // lane issues, so they are worked out there, once per op, and a round starts with its reads.
+  unsigned at_meta = meta_off, at_state = stt_off, at_slot = slot_base, at_in = slot_base, at_in2 = slot_base;
+  unsigned at_meta2 = meta2_off, at_next = win_off;
+  auto decode = [&](unsigned word, unsigned pos) {
+    const unsigned j = word & 0x7ffu;
+    const unsigned jc = min(j, (unsigned)m - 1u);
+    const unsigned c5 = word >> 11;
+    // a micro-batch out of range reads row 0 (kind 0), which is invalid and never issues
+    at_meta = j == jc ? __umul24(c5, row_bytes) + meta_off : meta_off;
+    unsigned c = c5 & (unsigned)(V - 1);
+    unsigned fwd = (word >> 13) & 1u;
+    unsigned jw = jc >> 3;   // state word of the micro-batch inside its chunk
+    // (opaque to the optimiser, which would otherwise turn the multiplications by these small
+    // values into longer compare-and-select sequences)
+    asm("" : "+v"(c), "+v"(fwd), "+v"(jw));
+    at_state = (jw << 8) + (__umul24(c, chunk_bytes) + stt_off);
+    at_slot = (jc << 2) + slot_base;   // slot j of the first class; low five bits = 4 (j & 7)
+    const bool is_b = (word >> 13) == (unsigned)kB;
+    // one class: backward inputs at slot j, forward inputs at slot m + j; bit 13 of the word is set
+    // for F and FD and clear for B (other kinds have no input, whatever they read is ignored)
+    at_in = ONE_CLASS ? __umul24(fwd, m4) + at_slot
+                      : at_slot + (unsigned)(is_b ? pick<V>(cons_b, c) : pick<V>(cons_f, c));
+    if (DEG2) {
+      at_meta2 = ((((is_b ? 4u : 0u) + c) << lpc_shift) << 3) + meta2_off;
+      at_in2 = at_slot + (unsigned)(is_b ? pick<V>(cons_b2, c) : pick<V>(cons_f2, c));
+    }
+    at_next = ((pos + 128u) & ((kRing - 1) << 7)) | win_off;   // the word behind this one
+  };
+
   // Every candidate ends after at most D * stride + 2 rounds (each round but its last issues at
   // least one of its at most D * stride ops), so the bound below is never reached; it only makes
   // sure the wavefront leaves the loop whatever happens.
@@ -227,6 +257,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
           // a row that fills its stride has no END word: plant one behind it
           if (loaded >= stride) win[(stride & (kRing - 1)) * 64 + lane] = 0;
           w = prime0.x & 0xffffu;
+          decode(w, 0u);
           dead = 0u;
         }
         priming = false;
@@ -290,38 +321,20 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     // the next top-up, where it is restarted
 #pragma unroll
     for (unsigned sub = 0; sub < kSyncRounds; ++sub) {
-    // ---- decode the current word (already in a register) and issue this round's reads
-    const unsigned j = w & 0x7ffu;
-    const unsigned nxt = cpos + 128u;
-    unsigned w_next = lds_read<uint16_t>((nxt & ((kRing - 1) << 7)) | win_off);
-    const unsigned c5 = w >> 11;
-    int4 M = lds_read<int4>(__umul24(c5, row_bytes) + meta_off);
-    const unsigned jc = min(j, (unsigned)m - 1u);
-    const bool in_range = j == jc;
-    unsigned c = c5 & (unsigned)(V - 1);
-    unsigned fwd = (w >> 13) & 1u;
-    // (opaque to the optimiser, which would otherwise turn the multiplications by these small
-    // values into longer compare-and-select sequences)
-    unsigned jw = jc >> 3;   // state word of the micro-batch inside its chunk
-    asm("" : "+v"(c), "+v"(fwd), "+v"(jw));
-    unsigned state_at = (jw << 8) + (__umul24(c, chunk_bytes) + stt_off);
-    asm("" : "+v"(state_at));   // read and write address: keep it instead of recomputing it
-    unsigned sx = lds_read<uint32_t>(state_at);
-    const unsigned bj = (jc << 2) + slot_base;   // slot j of the first class; low five bits = 4 (j & 7)
-    const bool is_b = (w >> 13) == (unsigned)kB;
-    // one class: backward inputs at slot j, forward inputs at slot m + j; bit 13 of the word is set
-    // for F and FD and clear for B (other kinds have no input, whatever they read is ignored)
-    const unsigned in_at = ONE_CLASS ? __umul24(fwd, m4) + bj
-                                     : bj + (unsigned)(is_b ? pick<V>(cons_b, c) : pick<V>(cons_f, c));
-    unsigned in1 = lds_read<uint32_t>(in_at);
+    // ---- this round's reads
+    unsigned w_next = lds_read<uint16_t>(at_next);
+    int4 M = lds_read<int4>(at_meta);
+    unsigned sx = lds_read<uint32_t>(at_state);
+    unsigned in1 = lds_read<uint32_t>(at_in);
+    const unsigned bj = at_slot;
     int2 M2 = make_int2(0, 0);
     unsigned in2 = 0u;
     if (DEG2) {
       // second-edge rows are per direction, not per kind: only F, FD and B have cross-stage edges
       const unsigned kind = w >> 13;
-      const bool has_edges = is_b || kind == (unsigned)kF || kind == (unsigned)kFD;
-      M2 = lds_read<int2>(((((is_b ? 4u : 0u) + c) << lpc_shift) << 3) + meta2_off);
-      in2 = lds_read<uint32_t>(bj + (unsigned)(is_b ? pick<V>(cons_b2, c) : pick<V>(cons_f2, c)));
+      const bool has_edges = kind == (unsigned)kB || kind == (unsigned)kF || kind == (unsigned)kFD;
+      M2 = lds_read<int2>(at_meta2);
+      in2 = lds_read<uint32_t>(at_in2);
       asm volatile("" : "+v"(M2.x), "+v"(M2.y), "+v"(in2));
       M2.y = has_edges ? M2.y : 0;
     }
@@ -343,10 +356,8 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       veto |= ready2 & 0xffu;
       ready8 = max(ready8, ready2);
     }
-    // micro-batch in range (the addresses above used the clamped one) and nothing vetoes
-    const unsigned long long moved =
-        __builtin_amdgcn_ballot_w64(veto == dead) & __builtin_amdgcn_ballot_w64(in_range);
-    const bool ok = (veto == dead) && in_range;
+    const unsigned long long moved = __builtin_amdgcn_ballot_w64(veto == dead);
+    const bool ok = veto == dead;
     // ---- issue
     if (ok) {
       const unsigned fin8 = max(free_at8, ready8) + dur8;
@@ -357,7 +368,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       unsigned flip;
       asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1"
           : "=v"(flip) : "v"(bj), "v"(mx_));
-      lds_write<uint32_t>(state_at, sx ^ flip);
+      lds_write<uint32_t>(at_state, sx ^ flip);
       // finish << 8 | own stage (byte 2 of the last metadata dword; the low byte of fin8 is zero)
       const unsigned val = __builtin_amdgcn_perm(fin8, my_, 0x07060502u);
       // byte offset of the output slot in the high half; ops without an output edge write the
@@ -368,8 +379,9 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       }
       free_at8 = fin8;
       busy8 += dur8;
-      cpos = nxt;
+      cpos += 128u;
       w = w_next;
+      decode(w, cpos);
     }
     // A segment none of whose lanes issued is finished, and stays so: nothing it reads changes any
     // more.  It could only be restarted at the next top-up anyway, so only the last round before
