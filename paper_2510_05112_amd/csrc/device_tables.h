@@ -49,7 +49,8 @@ struct DevTables {
 //         | own stage (byte 2) | 0xff if the op has a first input edge, else 0 (byte 3)
 //     Rows of words that may not appear on the device (no such chunk, kind 0, W without split
 //     backward) require state 15, which no activation is ever in.
-//   meta2 [2 * 4][lanes_per_cand] x 2 ints, second input/output edge per (direction, chunk, device):
+//   meta2 [2 * 4 + 1][lanes_per_cand] x 2 ints, second input/output edge per (direction, chunk,
+//     device); the last row is all zero (read by kinds without cross-stage edges):
 //     x = (latency of the second input edge << 8) - its tag
 //     y = byte offset of the second output slot (16) | kMetaHasProd | kMetaHasCons
 //   dev   [lanes_per_cand] x (2 + 4V) ints: chunks on the device, memory cap / unit_scale, then per

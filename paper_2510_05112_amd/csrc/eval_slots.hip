@@ -183,31 +183,32 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   int loaded = 0;  // words of this row already in the window ring
   uint2 pend = make_uint2(0, 0);
   bool has_pend = false;
-  unsigned cpos = 0;                 // list position << 7 (the byte stride of the window ring)
+  unsigned npos = 128u;              // (list position + 1) << 7 (the byte stride of the window ring)
   unsigned free_at8 = 0, busy8 = 0;  // device free time and busy time, << 8
   int mem = 0, pk = 0;               // in units of the problem's common unit divisor
   bool running = false;  // this lane's segment is evaluating a candidate
   unsigned dead = ~0u;   // 0 while this lane carries a device of a running candidate, else all ones
   bool fresh = true;     // (re)start the segment on `cand` at the top of the next round
-  unsigned w = 0u;       // current op word; 0 = list exhausted (or lane idle)
 
   // LDS addresses of everything a round reads for the current word.  They only change when the
   // lane issues, so they are worked out there, once per op, and a round starts with its reads.
   unsigned at_meta = meta_off, at_state = stt_off, at_slot = slot_base, at_in = slot_base, at_in2 = slot_base;
   unsigned at_meta2 = meta2_off, at_next = win_off;
-  auto decode = [&](unsigned word, unsigned pos) {
+  auto decode = [&](unsigned word, unsigned next_pos) {
     const unsigned j = word & 0x7ffu;
     const unsigned jc = min(j, (unsigned)m - 1u);
     const unsigned c5 = word >> 11;
     // a micro-batch out of range reads row 0 (kind 0), which is invalid and never issues
-    at_meta = j == jc ? __umul24(c5, row_bytes) + meta_off : meta_off;
+    at_meta = __umul24(j == jc ? c5 : 0u, row_bytes) + meta_off;
     unsigned c = c5 & (unsigned)(V - 1);
     unsigned fwd = (word >> 13) & 1u;
     unsigned jw = jc >> 3;   // state word of the micro-batch inside its chunk
     // (opaque to the optimiser, which would otherwise turn the multiplications by these small
     // values into longer compare-and-select sequences)
     asm("" : "+v"(c), "+v"(fwd), "+v"(jw));
-    at_state = (jw << 8) + (__umul24(c, chunk_bytes) + stt_off);
+    unsigned chunk_at = __umul24(c, chunk_bytes) + stt_off;
+    asm("" : "+v"(chunk_at));
+    at_state = (jw << 8) + chunk_at;
     at_slot = (jc << 2) + slot_base;   // slot j of the first class; low five bits = 4 (j & 7)
     const bool is_b = (word >> 13) == (unsigned)kB;
     // one class: backward inputs at slot j, forward inputs at slot m + j; bit 13 of the word is set
@@ -215,10 +216,14 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     at_in = ONE_CLASS ? __umul24(fwd, m4) + at_slot
                       : at_slot + (unsigned)(is_b ? pick<V>(cons_b, c) : pick<V>(cons_f, c));
     if (DEG2) {
-      at_meta2 = ((((is_b ? 4u : 0u) + c) << lpc_shift) << 3) + meta2_off;
+      // second-edge rows are per direction, not per kind: only F, FD and B have cross-stage
+      // edges, every other kind reads the all-zero ninth row
+      const unsigned kind = word >> 13;
+      const bool has_edges = is_b || kind == (unsigned)kF || kind == (unsigned)kFD;
+      at_meta2 = (((has_edges ? (is_b ? 4u : 0u) + c : 8u) << lpc_shift) << 3) + meta2_off;
       at_in2 = at_slot + (unsigned)(is_b ? pick<V>(cons_b2, c) : pick<V>(cons_f2, c));
     }
-    at_next = ((pos + 128u) & ((kRing - 1) << 7)) | win_off;   // the word behind this one
+    at_next = (next_pos & ((kRing - 1) << 7)) | win_off;   // the word behind this one
   };
 
   // Every candidate ends after at most D * stride + 2 rounds (each round but its last issues at
@@ -256,8 +261,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
           loaded = prime_words;
           // a row that fills its stride has no END word: plant one behind it
           if (loaded >= stride) win[(stride & (kRing - 1)) * 64 + lane] = 0;
-          w = prime0.x & 0xffffu;
-          decode(w, 0u);
+          decode(prime0.x & 0xffffu, 128u);
           dead = 0u;
         }
         priming = false;
@@ -273,7 +277,9 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
         has_pend = false;
         if (loaded >= stride) win[(stride & (kRing - 1)) * 64 + lane] = 0;
       }
-      if (w != 0u && loaded - (int)(cpos >> 7) <= kRefillAt && loaded < stride) {
+      // (a lane that has reached its END word still tops up until its ring is full: harmless, the
+      // words are inside its row)
+      if (dead == 0u && loaded + 1 - (int)(npos >> 7) <= kRefillAt && loaded < stride) {
         pend = *reinterpret_cast<const uint2*>(row + loaded);
         has_pend = true;
       }
@@ -294,10 +300,9 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
         running = (seg < cpw) && (cand < n_cand);
         priming = running;
         dead = ~0u;
-        cpos = 0; free_at8 = 0; busy8 = 0; mem = 0; pk = 0;
+        npos = 128u; free_at8 = 0; busy8 = 0; mem = 0; pk = 0;
         has_pend = false;
         loaded = 0;
-        w = 0u;
         if (running) {
           for (int i = d; i < slots_per_cand; i += lpc) my_slots[i] = kEmptySlot;
         }
@@ -330,13 +335,9 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     int2 M2 = make_int2(0, 0);
     unsigned in2 = 0u;
     if (DEG2) {
-      // second-edge rows are per direction, not per kind: only F, FD and B have cross-stage edges
-      const unsigned kind = w >> 13;
-      const bool has_edges = kind == (unsigned)kB || kind == (unsigned)kF || kind == (unsigned)kFD;
       M2 = lds_read<int2>(at_meta2);
       in2 = lds_read<uint32_t>(at_in2);
       asm volatile("" : "+v"(M2.x), "+v"(M2.y), "+v"(in2));
-      M2.y = has_edges ? M2.y : 0;
     }
     // keep every load of the round in front of the decision (one LDS round trip per round)
     asm volatile("" : "+v"(w_next), "+v"(sx), "+v"(in1));
@@ -379,9 +380,8 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       }
       free_at8 = fin8;
       busy8 += dur8;
-      cpos += 128u;
-      w = w_next;
-      decode(w, cpos);
+      decode(w_next, npos + 128u);
+      npos += 128u;
     }
     // A segment none of whose lanes issued is finished, and stays so: nothing it reads changes any
     // more.  It could only be restarted at the next top-up anyway, so only the last round before
@@ -398,6 +398,8 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       const bool seg_ended = ((ended >> (seg << lpc_shift)) & 1ull) != 0ull;
       // ---- the candidate is over: lists exhausted or nothing can move any more
       bool bad_head = false, incomplete = false;
+      // the word the lane stopped at is still in its ring (kind 0 if its list is exhausted)
+      const unsigned w = lds_read<uint16_t>(((npos - 128u) & ((kRing - 1) << 7)) | win_off);
       if (seg_ended && lane_ok) {
         // a stuck device sits on a malformed word?
         const int4 Mh = lds_read<int4>(__umul24(w >> 11, row_bytes) + meta_off);
@@ -428,7 +430,6 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
         }
         running = false;
         dead = ~0u;
-        w = 0u;
         fresh = true;
       }
       // the finished segments stop counting as running at once

@@ -260,7 +260,7 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
         }
       }
       const int n_meta = kNKinds * kMaxChunks * lpc * 4;
-      const int n_meta2 = deg2 ? 2 * kMaxChunks * lpc * 2 : 0;
+      const int n_meta2 = deg2 ? (2 * kMaxChunks + 1) * lpc * 2 : 0;   // + one all-zero row
       const int n_shared = (n_meta + n_meta2 + 511) & ~511;   // the op windows behind it are 2 KB-aligned
       const unsigned dump_bytes = (unsigned)(2 * n_classes * m) * 4u;
       const int dev_ints = 2 + 4 * V;
