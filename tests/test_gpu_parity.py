@@ -6,7 +6,7 @@ import oracle
 import workloads
 from gpu_common import check_batch, gpu_evaluate
 from helpers import batch_from_lists, dag_problem, perturb, random_valid_lists, two_tower_problem
-from workloads.problem import (B, F, FD, L, O, R, W, chain_problem, gpipe_lists,
+from workloads.problem import (B, F, FD, L, O, R, W, chain_problem, gpipe_lists, make_problem,
                                one_f_one_b_lists, pack_lists, pack_word)
 
 pytestmark = pytest.mark.gpu
@@ -139,6 +139,29 @@ def test_end_words_with_low_bits_set():
     gpu, ref = check_batch(prob, words, k=4, what="end words")
     assert list(ref["flags"][:5]) == [0] * 5 and ref["flags"][5] != 0
     assert np.array_equal(ref["makespan"][:2], ref["makespan"][2:4])
+
+
+@pytest.mark.parametrize("units,slots_fit", [
+    ([1000, 3000, 2000], True),      # common divisor 1000
+    ([768, 1536, 1536], True),
+    ([7, 300, 5], False),            # no common divisor and a unit beyond a byte
+    ([255, 1, 17], True),
+])
+def test_large_memory_units(units, slots_fit):
+    # the slot kernel carries units / gcd in a byte; anything else falls to the general kernel
+    p, m = 3, 6
+    edges = [(s, s + 1, 2) for s in range(p - 1)]
+    dur = {F: [2, 3, 2], FD: [2, 3, 2], R: [2, 3, 2], B: [4, 5, 3], W: [1, 2, 1], O: 2, L: 2}
+    cap = [int(u * 5.5) for u in units]   # not a multiple of the divisor: the cap rounds down
+    prob = make_problem(p, p, m, 1, list(range(p)), edges, dur, mem_units=units, mem_cap=cap, name="units")
+    rng = np.random.default_rng(5)
+    lists = [random_valid_lists(prob, rng, 0.3 * (t % 2), 0.3 * ((t // 2) % 2)) for t in range(64)]
+    words = batch_from_lists(lists)
+    g, _ = gpu_evaluate(prob, words, kernel="slots")
+    assert (g is not None) == slots_fit
+    gpu, ref = check_batch(prob, words, k=5, what=f"units {units}")
+    assert (ref["flags"] == 4).any() and (ref["flags"] == 0).any()
+    assert ref["peak"].max() > 255
 
 
 def test_empty_batch_single_candidate_and_ragged_tail():
