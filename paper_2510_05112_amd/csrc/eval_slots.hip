@@ -85,12 +85,13 @@ __device__ __forceinline__ int pick(const int (&a)[V], int c) {
 
 // Op window: kRing words per lane, refilled kChunk words at a time every kSyncRounds rounds.
 // A lane asks for its next chunk when at most kRefillAt words are left unread; with these
-// values a lane that issues one op per round always finds the word after its cursor in the
-// ring (at least 5 unread words after every top-up, at most 12 <= kRing).
+// values a lane that issues one op per round always finds the second word after its cursor in
+// the ring (at least 6 unread words after every top-up, at most 13 <= kRing), and the word at
+// its cursor is never overwritten.
 constexpr int kRing = 16;
 constexpr int kChunk = 4;
 constexpr unsigned kSyncRounds = 4;
-constexpr int kRefillAt = 8;
+constexpr int kRefillAt = 9;
 constexpr int kPrimeChunks = 3;
 
 }  // namespace
@@ -192,14 +193,18 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
 
   // LDS addresses of everything a round reads for the current word.  They only change when the
   // lane issues, so they are worked out there, once per op, and a round starts with its reads.
-  unsigned at_meta = meta_off, at_state = stt_off, at_slot = slot_base, at_in = slot_base, at_in2 = slot_base;
-  unsigned at_meta2 = meta2_off, at_next = win_off;
-  auto decode = [&](unsigned word, unsigned next_pos) {
+  // The word's metadata row is fetched there as well and kept in registers, and so is the op
+  // word behind it (a lane that issues the op at position k reads the word at k + 2).
+  unsigned at_state = stt_off, at_slot = slot_base, at_in = slot_base, at_in2 = slot_base;
+  int4 M = make_int4(0, 0, 15, 0);   // metadata row of the current word (an invalid row to begin with)
+  int2 M2 = make_int2(0, 0);         // its second-edge row
+  unsigned w_next = 0u;              // the word behind the current one
+  auto decode = [&](unsigned word) {
     const unsigned j = word & 0x7ffu;
     const unsigned jc = min(j, (unsigned)m - 1u);
     const unsigned c5 = word >> 11;
     // a micro-batch out of range reads row 0 (kind 0), which is invalid and never issues
-    at_meta = __umul24(j == jc ? c5 : 0u, row_bytes) + meta_off;
+    M = lds_read<int4>(__umul24(j == jc ? c5 : 0u, row_bytes) + meta_off);
     unsigned c = c5 & (unsigned)(V - 1);
     unsigned fwd = (word >> 13) & 1u;
     unsigned jw = jc >> 3;   // state word of the micro-batch inside its chunk
@@ -220,10 +225,9 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       // edges, every other kind reads the all-zero ninth row
       const unsigned kind = word >> 13;
       const bool has_edges = is_b || kind == (unsigned)kF || kind == (unsigned)kFD;
-      at_meta2 = (((has_edges ? (is_b ? 4u : 0u) + c : 8u) << lpc_shift) << 3) + meta2_off;
+      M2 = lds_read<int2>((((has_edges ? (is_b ? 4u : 0u) + c : 8u) << lpc_shift) << 3) + meta2_off);
       at_in2 = at_slot + (unsigned)(is_b ? pick<V>(cons_b2, c) : pick<V>(cons_f2, c));
     }
-    at_next = (next_pos & ((kRing - 1) << 7)) | win_off;   // the word behind this one
   };
 
   // Every candidate ends after at most D * stride + 2 rounds (each round but its last issues at
@@ -261,7 +265,8 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
           loaded = prime_words;
           // a row that fills its stride has no END word: plant one behind it
           if (loaded >= stride) win[(stride & (kRing - 1)) * 64 + lane] = 0;
-          decode(prime0.x & 0xffffu, 128u);
+          decode(prime0.x & 0xffffu);
+          w_next = prime0.x >> 16;
           dead = 0u;
         }
         priming = false;
@@ -327,20 +332,17 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
 #pragma unroll
     for (unsigned sub = 0; sub < kSyncRounds; ++sub) {
     // ---- this round's reads
-    unsigned w_next = lds_read<uint16_t>(at_next);
-    int4 M = lds_read<int4>(at_meta);
     unsigned sx = lds_read<uint32_t>(at_state);
     unsigned in1 = lds_read<uint32_t>(at_in);
     const unsigned bj = at_slot;
-    int2 M2 = make_int2(0, 0);
     unsigned in2 = 0u;
     if (DEG2) {
-      M2 = lds_read<int2>(at_meta2);
       in2 = lds_read<uint32_t>(at_in2);
-      asm volatile("" : "+v"(M2.x), "+v"(M2.y), "+v"(in2));
+      asm volatile("" : "+v"(in2), "+v"(M2.x), "+v"(M2.y));
     }
     // keep every load of the round in front of the decision (one LDS round trip per round)
-    asm volatile("" : "+v"(w_next), "+v"(sx), "+v"(in1));
+    // (the metadata row was requested when the lane last issued; nothing may wait for it earlier)
+    asm volatile("" : "+v"(sx), "+v"(in1), "+v"(M.x), "+v"(M.y), "+v"(M.z), "+v"(M.w));
     // ---- decide.  An exhausted lane sits on a word of kind 0, whose metadata row is invalid; invalid
     // rows require state 15, which no activation is ever in.  Lanes without a device (and idle
     // segments) never initialise their LDS words, so they are masked off explicitly.
@@ -380,8 +382,9 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       }
       free_at8 = fin8;
       busy8 += dur8;
-      decode(w_next, npos + 128u);
+      decode(w_next);
       npos += 128u;
+      w_next = lds_read<uint16_t>((npos & ((kRing - 1) << 7)) | win_off);
     }
     // A segment none of whose lanes issued is finished, and stays so: nothing it reads changes any
     // more.  It could only be restarted at the next top-up anyway, so only the last round before
