@@ -177,7 +177,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   const unsigned long long high_bits = base_bits << (lpc - 1);
   unsigned long long run_bases = 0ull;   // base bits of the segments that are evaluating a candidate
   unsigned long long idle_fields = ~0ull;  // all lanes of the segments that are not
-  bool any_fresh = true;                 // wave-uniform: some segment wants its next candidate
+  bool any_special = true;               // wave-uniform: some segment starts, or has just started, a candidate
 
   // per-candidate registers
   const uint16_t* row = ops;
@@ -244,55 +244,47 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   bool first_draw = true;
   uint2 prime0 = make_uint2(0, 0), prime1 = make_uint2(0, 0), prime2 = make_uint2(0, 0);
   bool priming = false;      // the segment has requested the head of its rows and waits for the top-up
-  bool any_priming = false;  // wave-uniform
   const int prime_words = stride < kPrimeChunks * kChunk ? stride : kPrimeChunks * kChunk;
   for (unsigned round = 0; round < max_rounds; round += kSyncRounds) {
-    {
-      // ---- wave-wide top-up of the op windows.  Loads requested at the previous top-up (or at a
-      // restart since then) are landed now, four rounds later, so nobody waits for HBM.
-      if (any_priming) {
-        any_priming = false;
-        if (priming && lane_ok) {
-          // [word][lane] with 16-bit elements: word k of lane l at k * 64 + l
-          win[0 * 64 + lane] = (uint16_t)prime0.x; win[1 * 64 + lane] = (uint16_t)(prime0.x >> 16);
-          win[2 * 64 + lane] = (uint16_t)prime0.y; win[3 * 64 + lane] = (uint16_t)(prime0.y >> 16);
-          win[4 * 64 + lane] = (uint16_t)prime1.x; win[5 * 64 + lane] = (uint16_t)(prime1.x >> 16);
-          win[6 * 64 + lane] = (uint16_t)prime1.y; win[7 * 64 + lane] = (uint16_t)(prime1.y >> 16);
-          if (prime_words > 8) {
-            win[8 * 64 + lane] = (uint16_t)prime2.x; win[9 * 64 + lane] = (uint16_t)(prime2.x >> 16);
-            win[10 * 64 + lane] = (uint16_t)prime2.y; win[11 * 64 + lane] = (uint16_t)(prime2.y >> 16);
-          }
-          loaded = prime_words;
-          // a row that fills its stride has no END word: plant one behind it
-          if (loaded >= stride) win[(stride & (kRing - 1)) * 64 + lane] = 0;
-          decode(prime0.x & 0xffffu);
-          w_next = prime0.x >> 16;
-          dead = 0u;
-        }
-        priming = false;
-        const unsigned long long run_lanes = __ballot(running);
-        run_bases = run_lanes & base_bits;
-        idle_fields = ~run_lanes;
-      }
-      if (has_pend) {
-        const int q = loaded & (kRing - 1);
-        win[(q + 0) * 64 + lane] = (uint16_t)pend.x; win[(q + 1) * 64 + lane] = (uint16_t)(pend.x >> 16);
-        win[(q + 2) * 64 + lane] = (uint16_t)pend.y; win[(q + 3) * 64 + lane] = (uint16_t)(pend.y >> 16);
-        loaded += kChunk;
-        has_pend = false;
-        if (loaded >= stride) win[(stride & (kRing - 1)) * 64 + lane] = 0;
-      }
-      // (a lane that has reached its END word still tops up until its ring is full: harmless, the
-      // words are inside its row)
-      if (dead == 0u && loaded + 1 - (int)(npos >> 7) <= kRefillAt && loaded < stride) {
-        pend = *reinterpret_cast<const uint2*>(row + loaded);
-        has_pend = true;
-      }
+    // ---- wave-wide top-up of the op windows.  Loads requested at the previous top-up are landed
+    // now, four rounds later, so nobody waits for HBM.
+    if (has_pend) {
+      const int q = loaded & (kRing - 1);
+      // [word][lane] with 16-bit elements: word k of lane l at k * 64 + l
+      win[(q + 0) * 64 + lane] = (uint16_t)pend.x; win[(q + 1) * 64 + lane] = (uint16_t)(pend.x >> 16);
+      win[(q + 2) * 64 + lane] = (uint16_t)pend.y; win[(q + 3) * 64 + lane] = (uint16_t)(pend.y >> 16);
+      loaded += kChunk;
+      has_pend = false;
+      // a row that fills its stride has no END word: plant one behind it
+      if (loaded >= stride) win[(stride & (kRing - 1)) * 64 + lane] = 0;
     }
-    // ---- (re)start segments on their next candidate: reset their LDS, request the head of
-    // their rows; they join in at the next top-up
-    if (any_fresh) {
-      any_fresh = false;
+    // (a lane that has reached its END word still tops up until its ring is full: harmless, the
+    // words are inside its row)
+    if (dead == 0u && loaded + 1 - (int)(npos >> 7) <= kRefillAt && loaded < stride) {
+      pend = *reinterpret_cast<const uint2*>(row + loaded);
+      has_pend = true;
+    }
+    // ---- the rare part, only when some segment starts or has just started a candidate
+    if (any_special) {
+      // segments restarted at the previous top-up: their row heads have arrived, they join in
+      if (priming && lane_ok) {
+        win[0 * 64 + lane] = (uint16_t)prime0.x; win[1 * 64 + lane] = (uint16_t)(prime0.x >> 16);
+        win[2 * 64 + lane] = (uint16_t)prime0.y; win[3 * 64 + lane] = (uint16_t)(prime0.y >> 16);
+        win[4 * 64 + lane] = (uint16_t)prime1.x; win[5 * 64 + lane] = (uint16_t)(prime1.x >> 16);
+        win[6 * 64 + lane] = (uint16_t)prime1.y; win[7 * 64 + lane] = (uint16_t)(prime1.y >> 16);
+        if (prime_words > 8) {
+          win[8 * 64 + lane] = (uint16_t)prime2.x; win[9 * 64 + lane] = (uint16_t)(prime2.x >> 16);
+          win[10 * 64 + lane] = (uint16_t)prime2.y; win[11 * 64 + lane] = (uint16_t)(prime2.y >> 16);
+        }
+        loaded = prime_words;
+        if (loaded >= stride) win[(stride & (kRing - 1)) * 64 + lane] = 0;
+        decode(prime0.x & 0xffffu);
+        w_next = prime0.x >> 16;
+        dead = 0u;
+      }
+      priming = false;
+      // (re)start segments on their next candidate: reset their LDS, request the head of their
+      // rows; they join in at the next top-up
       if (fresh) {
         fresh = false;
         unsigned long long drawn = ((unsigned long long)blockIdx.x * (blockDim.x >> 6) + wave) * cpw + seg;
@@ -319,12 +311,13 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
           if (prime_words > 8) prime2 = *reinterpret_cast<const uint2*>(row + 2 * kChunk);
         }
       }
-      any_priming = true;
       // segments that are priming do not count as running yet (nothing can move in them)
       const unsigned long long all_running = __ballot(running);
-      const unsigned long long run_lanes = __ballot(running && !priming);
+      const unsigned long long primers = __ballot(priming);
+      const unsigned long long run_lanes = all_running & ~primers;
       run_bases = run_lanes & base_bits;
       idle_fields = ~run_lanes;
+      any_special = primers != 0ull;
       if (all_running == 0ull) break;  // every segment of the wave is out of work
     }
     // kSyncRounds rounds between two top-ups; a segment that finishes in between idles until
@@ -439,7 +432,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       const unsigned long long run_lanes = __ballot(running && !priming);
       run_bases = run_lanes & base_bits;
       idle_fields = ~run_lanes;
-      any_fresh = true;
+      any_special = true;
     }
     }  // sub-rounds
   }
