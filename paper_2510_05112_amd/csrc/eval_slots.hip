@@ -346,14 +346,19 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     // lane all ones, which the word never equals.
     const unsigned state = __builtin_amdgcn_ubfe(sx, bj, 4);
     unsigned ready8 = (in1 + lat_tag) & (unsigned)((int)my_ >> 24);
-    unsigned veto = (state ^ (mx_ & 0xffu)) | (ready8 & 0xffu);
+    // (only the low byte counts: the state nibble is clean, byte 0 of the third metadata dword
+    // holds nothing but the required state, and the ready time sits above its tag byte)
+    unsigned veto = __builtin_amdgcn_bitop3_b32(state, mx_, ready8, 0xbe);   // (state ^ mx_) | ready8
     if (DEG2) {
       const unsigned ready2 = (in2 + (unsigned)M2.x) & (unsigned)(M2.y >> 31);
-      veto |= ready2 & 0xffu;
+      veto |= ready2;
       ready8 = max(ready8, ready2);
     }
-    const unsigned long long moved = __builtin_amdgcn_ballot_w64(veto == dead);
-    const bool ok = veto == dead;
+    // one compare of the low byte against `dead` yields the issue mask
+    unsigned long long moved;
+    asm volatile("v_cmp_eq_u32_sdwa %0, %1, %2 src0_sel:BYTE_0 src1_sel:DWORD"
+                 : "=s"(moved) : "v"(veto), "v"(dead));
+    const bool ok = __builtin_amdgcn_inverse_ballot_w64(moved);
     // ---- issue
     if (ok) {
       const unsigned fin8 = max(free_at8, ready8) + dur8;
