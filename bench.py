@@ -27,7 +27,7 @@ VALU_PEAK_WAVE_INSTR_PER_S = 256 * 4 * 2.4e9 / 4
 # HBM bytes of ONE evaluation launch on the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE
 # scaled by a copy kernel of known size, and its VALU wave-instruction count (SQ_INSTS_VALU):
 # profiles/eval_slot_kernel_cfg4_counters.md.  Other workloads report null.
-MEASURED = {("cfg4", 65536): {"traffic_bytes": 4.613e9, "valu_wave_instructions": 3.977e9}}
+MEASURED = {("cfg4", 65536): {"traffic_bytes": 4.514e9, "valu_wave_instructions": 2.088e9}}
 
 
 def main() -> int:
