@@ -21,6 +21,8 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "fporacle.c")
 _LIB = os.path.join(_HERE, "libfporacle.so")
+_GEN_SRC = os.path.join(_HERE, "fpgenoracle.c")
+_GEN_LIB = os.path.join(_HERE, "libfpgenoracle.so")
 
 FLAG_DEADLOCK = 1
 FLAG_INCOMPLETE = 2
@@ -29,13 +31,18 @@ INT64_MAX = np.iinfo(np.int64).max
 NKINDS = 8
 
 
+def _compile(src: str, lib: str, force: bool) -> str:
+    if force or not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(src):
+        tmp = lib + ".tmp.%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-o", tmp, src])
+        os.replace(tmp, lib)
+    return lib
+
+
 def build(force: bool = False) -> str:
-    """Compile fporacle.c with gcc (plain C, no GPU toolchain)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        tmp = _LIB + ".tmp.%d" % os.getpid()
-        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-o", tmp, _SRC])
-        os.replace(tmp, _LIB)
-    return _LIB
+    """Compile the oracle's C files with gcc (plain C, no GPU toolchain)."""
+    _compile(_GEN_SRC, _GEN_LIB, force)
+    return _compile(_SRC, _LIB, force)
 
 
 class _CProblem(ctypes.Structure):
@@ -179,3 +186,85 @@ def topk(makespan, flags, k: int):
                       ctypes.c_int64(ms.size), ctypes.c_int32(k), ctypes.c_void_p(idx.ctypes.data),
                       ctypes.c_void_p(oms.ctypes.data), ctypes.c_void_p(cnt.ctypes.data))
     return idx, oms, int(cnt[0])
+
+
+# ---------------------------------------------------------------------------------------------
+# schedule generator oracle (fpgenoracle.c)
+
+POLICY_INTS = 8
+CTTP_BWD_FIRST, CTTP_FWD_FIRST, CTTP_INTERLEAVED = 0, 1, 2
+DIR_BREADTH, DIR_DEPTH = 0, 1
+GEN_STUCK = 1
+GEN_OVERFLOW = 2
+
+
+class _CGenProblem(ctypes.Structure):
+    _fields_ = [
+        ("n_devices", ctypes.c_int32),
+        ("n_stages", ctypes.c_int32),
+        ("n_microbatches", ctypes.c_int32),
+        ("has_w", ctypes.c_int32),
+        ("stage_device", ctypes.c_void_p),
+        ("n_edges", ctypes.c_int32),
+        ("edge_src", ctypes.c_void_p),
+        ("edge_dst", ctypes.c_void_p),
+    ]
+
+
+_gen_lib = None
+
+
+def _load_gen():
+    global _gen_lib
+    if _gen_lib is None:
+        build()
+        _gen_lib = ctypes.CDLL(_GEN_LIB)
+        _gen_lib.fpgen_oracle_one.restype = ctypes.c_int
+        _gen_lib.fpgen_oracle_generate.restype = ctypes.c_int
+    return _gen_lib
+
+
+def generate(problem, policy, inflight, stride: int, threads: int = 1, diagnostics: bool = False):
+    """Run the scheduler on n parameter sets.
+
+    policy int32 [n][D][8] = (cttp, unit1, unit2, forward direction, forward interval or 0,
+    backward direction, backward interval or 0, 0) per actor; inflight int32 [n][S].
+    Returns dict(words uint16 [n][D][stride], steps int32 [n], status uint8 [n]) and, with
+    ``diagnostics``, prefix_violations int32 [n] (see fpgenoracle.c).
+    """
+    lib = _load_gen()
+    D, S = int(problem.n_devices), int(problem.n_stages)
+    arrays = (_i32(problem.stage_device), _i32(problem.edge_src), _i32(problem.edge_dst))
+    cp = _CGenProblem(D, S, int(problem.n_microbatches), int(problem.has_w), arrays[0].ctypes.data,
+                      len(arrays[1]), arrays[1].ctypes.data, arrays[2].ctypes.data)
+    pol = _i32(policy)
+    inf = _i32(inflight)
+    assert pol.ndim == 3 and pol.shape[1:] == (D, POLICY_INTS), pol.shape
+    n = pol.shape[0]
+    assert inf.shape == (n, S), inf.shape
+    out = dict(words=np.zeros((n, D, stride), np.uint16), steps=np.zeros(n, np.int32),
+               status=np.zeros(n, np.uint8))
+    viol = np.zeros(n, np.int32)
+
+    def run(lo, hi):
+        rc = 0
+        for i in range(lo, hi):
+            rc |= lib.fpgen_oracle_one(
+                ctypes.byref(cp), ctypes.c_void_p(pol[i].ctypes.data), ctypes.c_void_p(inf[i].ctypes.data),
+                ctypes.c_int32(stride), ctypes.c_void_p(out["words"][i].ctypes.data),
+                ctypes.c_void_p(out["steps"][i:].ctypes.data), ctypes.c_void_p(out["status"][i:].ctypes.data),
+                ctypes.c_void_p(viol[i:].ctypes.data))
+        return rc
+
+    threads = max(1, min(int(threads), n if n else 1))
+    if threads == 1:
+        rcs = [run(0, n)]
+    else:
+        bounds = np.linspace(0, n, min(n, threads * 8) + 1).astype(np.int64)
+        with ThreadPoolExecutor(threads) as ex:
+            rcs = list(ex.map(lambda i: run(int(bounds[i]), int(bounds[i + 1])), range(len(bounds) - 1)))
+    if any(rcs):
+        raise ValueError("fpgenoracle: invalid problem or policy")
+    if diagnostics:
+        out["prefix_violations"] = viol
+    return out

@@ -1,0 +1,188 @@
+"""Pins of the schedule-generator oracle (CPU only).
+
+The oracle restates the paper's scheduler (Section 5: instruction pool, reorder queues, step function
+of Algorithm 1, Steps 1-5) item by item.  It is pinned by: the two schedules whose order is known in
+closed form (1F1B and GPipe, and their 2(m + p - 1) unit steps), an independent counter-based model on
+random policies, properties every generated schedule must have, and hand-worked small cases.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from gen_checker import simulate
+from helpers import two_tower_problem
+from workloads.problem import chain_problem, gpipe_lists, one_f_one_b_lists, pack_lists
+
+NO_LIMIT = 2**31 - 1
+
+
+def uniform_policy(n, D, cttp, u1=1, u2=1, fdir=0, fint=0, bdir=0, bint=0):
+    pol = np.zeros((n, D, 8), np.int32)
+    pol[..., 0], pol[..., 1], pol[..., 2] = cttp, u1, u2
+    pol[..., 3], pol[..., 4], pol[..., 5], pol[..., 6] = fdir, fint, bdir, bint
+    return pol
+
+
+def stride_for(problem):
+    per_dev = np.bincount(problem.stage_device, minlength=problem.n_devices).max()
+    n = per_dev * problem.n_microbatches * (3 if problem.has_w else 2)
+    return int(-(-(n + 1) // 8) * 8)
+
+
+@pytest.mark.parametrize("p,m", [(2, 1), (2, 5), (4, 8), (4, 3), (8, 16), (5, 7)])
+def test_bwd_first_with_inflight_p_minus_d_is_1f1b_and_fwd_first_is_gpipe(p, m):
+    # Section 2.1 / Table of built-in priorities: 1F1B = backward passes first, at most p - d
+    # micro-batches in flight on stage d; GPipe = forward passes first, no limit.
+    prob = chain_problem(p, m, f=1, b=1, comm=0)
+    st = stride_for(prob)
+    pol = np.concatenate([uniform_policy(1, p, oracle.CTTP_BWD_FIRST), uniform_policy(1, p, oracle.CTTP_FWD_FIRST)])
+    inf = np.full((2, p), NO_LIMIT, np.int32)
+    inf[0] = [p - d for d in range(p)]
+    out = oracle.generate(prob, pol, inf, st, diagnostics=True)
+    assert np.array_equal(out["words"][0], pack_lists(one_f_one_b_lists(p, m), st))
+    assert np.array_equal(out["words"][1], pack_lists(gpipe_lists(p, m), st))
+    # unit steps = unit-time makespan of both schedules
+    assert list(out["steps"]) == [2 * (m + p - 1)] * 2
+    assert not out["status"].any() and not out["prefix_violations"].any()
+    ev = oracle.evaluate(prob, out["words"])
+    assert list(ev["makespan"]) == [2 * (m + p - 1)] * 2 and not ev["flags"].any()
+
+
+def random_policies(rng, n, problem, per_actor):
+    D, S, m = problem.n_devices, problem.n_stages, problem.n_microbatches
+    pol = np.zeros((n, D, 8), np.int32)
+    for i in range(n):
+        rows = D if per_actor[i] else 1
+        r = np.zeros((rows, 8), np.int32)
+        r[:, 0] = rng.integers(0, 3, rows)
+        inter = r[:, 0] == 2
+        r[:, 1] = np.where(inter, rng.integers(1, 4, rows), 1)
+        r[:, 2] = np.where(inter, rng.integers(1, 4, rows), 1)
+        r[:, 3] = rng.integers(0, 2, rows)
+        r[:, 4] = np.where(rng.random(rows) < 0.5, rng.integers(1, 6, rows), 0)
+        r[:, 5] = rng.integers(0, 2, rows)
+        r[:, 6] = np.where(rng.random(rows) < 0.5, rng.integers(1, 6, rows), 0)
+        pol[i] = r
+    inf = np.where(rng.random((n, S)) < 0.3, NO_LIMIT, rng.integers(1, max(2, m), (n, S))).astype(np.int32)
+    return pol, inf
+
+
+PROBLEMS = {
+    "chain_v1": lambda: chain_problem(4, 6, f=1, b=1, comm=0),
+    "chain_v2_w": lambda: chain_problem(3, 7, v=2, f=1, b=1, w=1, comm=0),
+    "chain_v4": lambda: chain_problem(2, 5, v=4, f=1, b=1, comm=0),
+    "two_tower_w": lambda: two_tower_problem(m=5, has_w=1),
+    "two_tower": lambda: two_tower_problem(m=4, has_w=0),
+}
+
+
+@pytest.mark.parametrize("name", sorted(PROBLEMS))
+def test_oracle_equals_the_counter_model_on_random_policies(name):
+    prob = PROBLEMS[name]()
+    rng = np.random.default_rng(11)
+    n = 60
+    pol, inf = random_policies(rng, n, prob, rng.random(n) < 0.5)
+    st = stride_for(prob)
+    out = oracle.generate(prob, pol, inf, st, diagnostics=True)
+    assert not out["prefix_violations"].any()
+    n_stuck = 0
+    for i in range(n):
+        lists, steps, stuck = simulate(prob, pol[i].tolist(), inf[i].tolist())
+        assert np.array_equal(out["words"][i], pack_lists(lists, st)), (name, i)
+        assert out["steps"][i] == steps and bool(out["status"][i] & 1) == stuck, (name, i)
+        n_stuck += stuck
+    assert n_stuck < n    # the comparison covers complete schedules too
+
+
+@pytest.mark.parametrize("name", sorted(PROBLEMS))
+def test_generated_schedules_are_valid_and_respect_the_limits(name):
+    prob = PROBLEMS[name]()
+    rng = np.random.default_rng(5)
+    n = 80
+    pol, inf = random_policies(rng, n, prob, rng.random(n) < 0.5)
+    st = stride_for(prob)
+    out = oracle.generate(prob, pol, inf, st)
+    ev = oracle.evaluate(prob, out["words"])
+    kind, chunk, mb = oracle.decode(out["words"])
+    stages = [[s for s in range(prob.n_stages) if prob.stage_device[s] == d] for d in range(prob.n_devices)]
+    ntypes = 3 if prob.has_w else 2
+    for i in range(n):
+        complete = out["status"][i] == 0
+        # a finished process has scheduled every item once, and the evaluator accepts the schedule
+        assert (ev["flags"][i] & 3 == 0) == complete, (name, i, ev["flags"][i])
+        n_ops = int((kind[i] != 0).sum())
+        assert (n_ops == ntypes * prob.n_stages * prob.n_microbatches) == complete
+        # no schedule can take fewer steps than the longest list, nor more than one item per step
+        assert out["steps"][i] >= (kind[i] != 0).sum(1).max() and out["steps"][i] <= max(n_ops, 1)
+        for d in range(prob.n_devices):
+            seen = {}
+            live = {s: 0 for s in stages[d]}
+            for k, c, j in zip(kind[i, d], chunk[i, d], mb[i, d]):
+                if k == 0:
+                    break
+                s = stages[d][c]
+                assert seen.get((k, s), 0) == j      # ascending micro-batches, each once
+                seen[(k, s)] = j + 1
+                if k == 1:
+                    live[s] += 1
+                    assert live[s] <= inf[i, s]       # the in-flight rule on every prefix
+                if k == 2:
+                    live[s] -= 1
+
+
+def test_hand_worked_interval_traversal():
+    # Section 5.2 "Stage Traversal Priority", worked by hand: 2 actors, circular placement of 4 stages
+    # (actor 0: stages 0 and 2; actor 1: stages 1 and 3), 2 micro-batches, forward passes first,
+    # forward traversal breadth-first with interval 2, backward traversal depth-first, no interval.
+    # Fsj / Bsj = stage s, micro-batch j; an item scheduled in step t resolves its successors for t+1.
+    #  step:   1    2    3    4    5    6    7    8    9    10
+    #  a0:     F00  F01  F20  F21  .    .    B20  B21  B00  B01
+    #  a1:     .    F10  F11  F30  F31  B30  B31  B10  B11  .
+    # step 3, a0: `stepped` = 2 = interval, so the position moves from stage 0 to stage 2 (F20 was
+    # resolved by F10 in step 2); step 4, a1: same move from stage 1 to stage 3 (F30 resolved by F20);
+    # steps 5-6, a0: no forward item left and B20 waits for B30 (step 6): two bubbles; step 8, a1:
+    # depth-first looks at stage 3 first (exhausted), then stage 1: B10 (resolved by B20 in step 7).
+    prob = chain_problem(2, 2, v=2, f=1, b=1, comm=0)
+    pol = uniform_policy(1, 2, oracle.CTTP_FWD_FIRST, fdir=0, fint=2, bdir=1, bint=0)
+    inf = np.full((1, 4), NO_LIMIT, np.int32)
+    out = oracle.generate(prob, pol, inf, 16)
+    k, c, j = oracle.decode(out["words"][0])
+    seq = [[(int(a), int(b), int(x)) for a, b, x in zip(k[d], c[d], j[d]) if a] for d in range(2)]
+    assert seq[0] == [(1, 0, 0), (1, 0, 1), (1, 1, 0), (1, 1, 1), (2, 1, 0), (2, 1, 1), (2, 0, 0), (2, 0, 1)]
+    assert seq[1] == [(1, 0, 0), (1, 0, 1), (1, 1, 0), (1, 1, 1), (2, 1, 0), (2, 1, 1), (2, 0, 0), (2, 0, 1)]
+    assert out["steps"][0] == 10 and out["status"][0] == 0
+
+
+def test_strict_interval_with_a_tight_inflight_limit_gets_stuck():
+    # actor 0 holds stages 0 and 2; with interval 2 it may not leave stage 0 before two forward passes,
+    # the limit of one in-flight micro-batch forbids the second, and the backward pass that would free
+    # it needs the forward pass of stage 2: nothing can move (reading G8: status 1)
+    prob = chain_problem(2, 4, v=2, f=1, b=1, comm=0)
+    pol = uniform_policy(1, 2, oracle.CTTP_BWD_FIRST, fdir=0, fint=2)
+    inf = np.full((1, 4), NO_LIMIT, np.int32)
+    inf[0, 0] = 1
+    out = oracle.generate(prob, pol, inf, 24)
+    assert out["status"][0] == oracle.GEN_STUCK
+    k, _, _ = oracle.decode(out["words"][0])
+    assert (k != 0).sum() < 2 * 4 * 4
+
+
+def test_interleaved_units_alternate_runs_of_forward_and_backward():
+    # one actor, one stage: interleaved(2, 1) must give F F B F F B ... as far as dependencies allow
+    prob = chain_problem(1, 6, f=1, b=1, comm=0)
+    pol = uniform_policy(1, 1, oracle.CTTP_INTERLEAVED, u1=2, u2=1)
+    out = oracle.generate(prob, pol, np.full((1, 1), NO_LIMIT, np.int32), 16)
+    k, _, j = oracle.decode(out["words"][0])
+    assert [int(x) for x in k[0][:12]] == [1, 1, 2, 1, 1, 2, 1, 1, 2, 2, 2, 2]
+    assert out["steps"][0] == 12
+
+
+def test_invalid_policies_are_rejected():
+    prob = chain_problem(2, 2)
+    inf = np.full((1, 2), NO_LIMIT, np.int32)
+    for bad in (uniform_policy(1, 2, 3), uniform_policy(1, 2, 0, u1=2), uniform_policy(1, 2, 2, u1=0),
+                uniform_policy(1, 2, 0, fdir=2)):
+        with pytest.raises(ValueError):
+            oracle.generate(prob, bad, inf, 8)
+    with pytest.raises(ValueError):
+        oracle.generate(prob, uniform_policy(1, 2, 0), np.zeros((1, 2), np.int32), 8)
