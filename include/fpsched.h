@@ -165,6 +165,58 @@ int fpsched_problem_info(const fpsched_problem *p, int32_t *lanes_per_candidate,
 #define FPSCHED_KERNEL_SLOTS 2
 int fpsched_problem_select_kernel(fpsched_problem *p, int which);
 
+/* ---- schedule generator: the actor-aware schedule of Section 5 -------------------------
+ * One actor's scheduling priorities (Section 5.2; table of built-in values): the
+ * computation type traversal priority with its scheduling units, and the stage traversal
+ * priority (direction and optional interval) for forward and for backward items. */
+#define FPSCHED_CTTP_BWD_FIRST 0
+#define FPSCHED_CTTP_FWD_FIRST 1
+#define FPSCHED_CTTP_INTERLEAVED 2
+#define FPSCHED_STP_BREADTH_FIRST 0 /* ascending stage id  */
+#define FPSCHED_STP_DEPTH_FIRST 1   /* descending stage id */
+typedef struct {
+  int32_t cttp;       /* FPSCHED_CTTP_*                                                    */
+  int32_t unit_f;     /* unit1: forward items per turn (interleaved only, else 1)          */
+  int32_t unit_b;     /* unit2: backward items per turn (interleaved only, else 1)         */
+  int32_t f_dir;      /* FPSCHED_STP_* for forward items                                   */
+  int32_t f_interval; /* 0 = not set                                                       */
+  int32_t b_dir;      /* FPSCHED_STP_* for backward items                                  */
+  int32_t b_interval; /* 0 = not set                                                       */
+  int32_t reserved;   /* 0                                                                 */
+} fpsched_actor_policy;
+
+#define FPSCHED_GEN_STUCK 1      /* items remained and no actor could schedule any          */
+#define FPSCHED_GEN_BAD_POLICY 4 /* a value outside its domain: nothing generated           */
+
+/* Generate one schedule per parameter set (Section 5.2, Steps 1-5, with the step function
+ * of Algorithm 1): in every scheduling step all actors look at the state the previous
+ * step left and each schedules at most one instruction item -- forward (F), backward (B)
+ * and, iff the problem splits the backward pass, weight-gradient (W) items; durations
+ * play no part.  Dependencies: F(s,j) after F of every DAG predecessor of s, B(s,j) after
+ * F(s,j) and B of every DAG successor, W(s,j) after B(s,j); within a type and stage,
+ * micro-batches ascend.  Type order: bwdpass-first = B, F; fwdpass-first = F, B;
+ * interleaved = the type whose turn it is, then the other (a turn ends after unit_f
+ * forward / unit_b backward items of the turn's own type; the first turn is forward); W is
+ * tried last, stages ascending.  Stage traversal without an interval: the actor's stages
+ * in the traversal direction, first eligible wins; with an interval n: the actor stays on
+ * one stage until it has scheduled n items of the type there (or the stage has no
+ * eligible item), then moves on in the direction, cyclically, to the next stage that has
+ * one; a type none of whose items is eligible is skipped, and a bubble only comes up
+ * when no type has an eligible item.  An F item of
+ * stage s is eligible only while (#F - #B scheduled on s) < d_inflight[s] (Section 4.2,
+ * the in-flight micro-batch limit; INT32_MAX = none, values < 1 are a bad policy).
+ *
+ * d_policy: DEVICE fpsched_actor_policy [n_sets][D]; d_inflight: DEVICE int32 [n_sets][S].
+ * d_ops: DEVICE out, uint16 [n_sets][D][stride_words], 16-byte aligned, every row written
+ * in full (END-padded); stride_words a multiple of 8 and >= (most stages on one device)
+ * x m x (3 if has_w else 2).  d_steps: DEVICE out int32 [n_sets], scheduling steps taken
+ * (the unit-time length of the schedule, bubbles included); d_status: DEVICE out uint8
+ * [n_sets], 0 or FPSCHED_GEN_*.  Asynchronous on hip_stream; no workspace.  EUNSUPPORTED
+ * if the problem's tables do not fit LDS. */
+int fpsched_generate(const fpsched_problem *p, const fpsched_actor_policy *d_policy,
+                     const int32_t *d_inflight, int64_t n_sets, int32_t stride_words,
+                     uint16_t *d_ops, int32_t *d_steps, uint8_t *d_status, void *hip_stream);
+
 const char *fpsched_strerror(int code);
 int fpsched_version(void);
 

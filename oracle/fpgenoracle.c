@@ -36,19 +36,23 @@
  *     the smallest micro-batch in the reorder queue for that stage.  Without
  *     an interval the actor's stages are scanned in the traversal direction
  *     (breadth-first = ascending stage id, depth-first = descending) and the
- *     first stage with an eligible candidate wins.  With an interval n the
- *     actor keeps (position, stepped) per type: when `stepped` has reached n,
- *     or the stage at the position has no unscheduled item of the type left,
- *     the position moves on in the traversal direction (cyclically) to the
- *     next stage that still has unscheduled items and `stepped` restarts; then
- *     only the stage at the position is looked at.  If it has no eligible
- *     candidate the next instruction type is tried.
+ *     first stage with an eligible candidate (in the queue and passing the
+ *     check function) wins.  With an interval n the actor keeps (position,
+ *     stepped) per type: when `stepped` has reached n, or the stage at the
+ *     position has no eligible candidate, the position moves on in the
+ *     traversal direction (cyclically) to the next stage that has one and
+ *     `stepped` restarts; the candidate of the stage at the position is
+ *     scheduled.  If no stage has an eligible candidate the next instruction
+ *     type is tried: a bubble only comes up when there is no schedulable
+ *     alternative at all (Section 5.2, Step 2).
  *  G7 the check function is the in-flight rule: an F item of stage s is
  *     eligible only while (#F scheduled on s) - (#B scheduled on s) is below
  *     the stage's in-flight limit.
  *  G8 a step in which no actor schedules anything although items remain ends
  *     the process with status 1 (stuck); the sequences produced so far are
- *     kept.
+ *     kept.  (With limits >= 1 and an acyclic stage graph this cannot happen:
+ *     the oldest unfinished micro-batch can always move.  The status is kept
+ *     as a guard.)
  *
  * Pinned by tests (tests/test_genoracle_*.py): exact 1F1B and GPipe orders and
  * their 2(m+p-1) steps, an independent counter-based simulator on random
@@ -113,12 +117,6 @@ static void try_queue(gen_state *g, int t, int s, int j) {
   if (!g->scheduled[i] && !g->queued[i] && deps_resolved(g, t, s, j)) g->queued[i] = 1;
 }
 
-static int unscheduled_left(const gen_state *g, int t, int s) {
-  int n = 0;
-  for (int j = 0; j < g->m; ++j) n += !g->scheduled[item(g, t, s, j)];
-  return n;
-}
-
 static int count_scheduled(const gen_state *g, int t, int s) {
   int n = 0;
   for (int j = 0; j < g->m; ++j) n += g->scheduled[item(g, t, s, j)];
@@ -136,6 +134,10 @@ static int candidate(const gen_state *g, int t, int s) {
 static int passes_check(const gen_state *g, int t, int s, const int32_t *inflight) {
   if (t != T_F) return 1;
   return (int64_t)count_scheduled(g, T_F, s) - count_scheduled(g, T_B, s) < (int64_t)inflight[s];
+}
+
+static int eligible(const gen_state *g, int t, int s, const int32_t *inflight) {
+  return candidate(g, t, s) >= 0 && passes_check(g, t, s, inflight);
 }
 
 typedef struct {
@@ -163,22 +165,22 @@ static int step_function(const gen_state *g, int a, const int32_t *pol, const in
     const int interval = t == T_F ? pol[4] : (t == T_B ? pol[6] : 0);
     if (interval > 0) {
       int p = st->pos[t];
-      if (st->stepped[t] == interval || unscheduled_left(g, t, g->stages_of[a][p]) == 0) {
-        /* move on to the next stage, in the traversal direction, that still has items */
+      int any_eligible = 0;
+      for (int c = 0; c < nst; ++c) any_eligible |= eligible(g, t, g->stages_of[a][c], inflight);
+      if (!any_eligible) continue;
+      if (st->stepped[t] == interval || !eligible(g, t, g->stages_of[a][p], inflight)) {
+        /* move on, in the traversal direction, to the next stage with an eligible candidate */
         for (int k = 0; k < nst; ++k) {
           p = dir == DIR_BREADTH ? (p + 1) % nst : (p + nst - 1) % nst;
-          if (unscheduled_left(g, t, g->stages_of[a][p]) > 0) break;
+          if (eligible(g, t, g->stages_of[a][p], inflight)) break;
         }
         st->pos[t] = p;
         st->stepped[t] = 0;
       }
       const int s = g->stages_of[a][p];
-      const int j = candidate(g, t, s);
-      if (j >= 0 && passes_check(g, t, s, inflight)) {
-        st->stepped[t] += 1;
-        *out_t = t; *out_s = s; *out_j = j;
-        return 1;
-      }
+      st->stepped[t] += 1;
+      *out_t = t; *out_s = s; *out_j = candidate(g, t, s);
+      return 1;
     } else {
       for (int k = 0; k < nst; ++k) {
         const int c = dir == DIR_BREADTH ? k : nst - 1 - k;

@@ -481,6 +481,38 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
   return check_hip(hipGetLastError());
 }
 
+int fpsched_generate(const fpsched_problem* p, const fpsched_actor_policy* d_policy, const int32_t* d_inflight,
+                     int64_t n_sets, int32_t stride_words, uint16_t* d_ops, int32_t* d_steps, uint8_t* d_status,
+                     void* hip_stream) {
+  if (!p || n_sets < 0) return FPSCHED_EINVAL;
+  if (p->device_id < 0) return FPSCHED_ENODEV;
+  if (n_sets == 0) return FPSCHED_OK;
+  if (!d_policy || !d_inflight || !d_ops || !d_steps || !d_status) return FPSCHED_EINVAL;
+  int max_chunks = 0;
+  for (int d = 0; d < p->D; ++d) max_chunks = std::max(max_chunks, p->n_chunks[d]);
+  const int64_t longest = (int64_t)max_chunks * p->m * (p->has_w ? 3 : 2);
+  if (stride_words < 8 || (stride_words & 7) || stride_words < longest) return FPSCHED_EINVAL;
+  if (reinterpret_cast<uintptr_t>(d_ops) & 15) return FPSCHED_EINVAL;
+  const int lpc = p->tables.lanes_per_cand;
+  const int cpw = 64 / lpc;
+  const int64_t lds_bytes = 4ll * (p->tables.n_table_ints + (int64_t)cpw * 3 * p->S);
+  if (lds_bytes > p->max_lds) return FPSCHED_EUNSUPPORTED;
+  const int64_t blocks = (n_sets + cpw - 1) / cpw;
+  if (blocks > 0x7fffffffll) return FPSCHED_EINVAL;
+  DeviceGuard g(p->device_id);
+  if (!g.ok) return FPSCHED_EHIP;
+  const int V = max_chunks <= 1 ? 1 : (max_chunks <= 2 ? 2 : 4);
+  auto kernel = V == 1 ? &generate_kernel<1> : (V == 2 ? &generate_kernel<2> : &generate_kernel<4>);
+  if (lds_bytes > 64 * 1024 &&
+      hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          (int)lds_bytes) != hipSuccess)
+    return FPSCHED_EHIP;
+  hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(64), (size_t)lds_bytes,
+                     static_cast<hipStream_t>(hip_stream), p->tables, reinterpret_cast<const int32_t*>(d_policy),
+                     d_inflight, (long long)n_sets, (int)stride_words, d_ops, d_steps, d_status);
+  return check_hip(hipGetLastError());
+}
+
 int fpsched_topk(const fpsched_problem* p, fpsched_results in, int64_t n_cand, int32_t k,
                  int64_t* d_idx, int64_t* d_makespan, int32_t* d_count, void* d_workspace,
                  size_t workspace_bytes, void* hip_stream) {

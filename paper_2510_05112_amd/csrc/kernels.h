@@ -32,6 +32,11 @@ __global__ void eval_slot_kernel(SlotTables T, const uint16_t* ops, long long n_
 
 __global__ void reset_counter_kernel(unsigned long long* counter, unsigned long long value);
 
+// V as above.  One wavefront per workgroup, 64 / lanes_per_cand parameter sets per wavefront.
+template <int V>
+__global__ void generate_kernel(DevTables T, const int32_t* policy, const int32_t* inflight, long long n_sets,
+                                int stride, uint16_t* ops, int32_t* out_steps, unsigned char* out_status);
+
 __global__ void topk_tile_kernel(const long long* in_makespan, const unsigned char* in_flags,
                                  const Key* in_keys, long long n, int k, Key* out_keys,
                                  long long* final_idx, long long* final_makespan, int* final_count);

@@ -61,16 +61,16 @@ def simulate(problem, policy, inflight):
                 n = len(stages[d])
                 if interval > 0:
                     p = pos[d][t]
-                    if stepped[d][t] == interval or snap[t][stages[d][p]] == m:
+                    if not any(ok.values()):
+                        continue
+                    if stepped[d][t] == interval or not ok[stages[d][p]]:
                         for _ in range(n):
                             p = (p + 1) % n if direction == 0 else (p - 1) % n
-                            if snap[t][stages[d][p]] < m:
+                            if ok[stages[d][p]]:
                                 break
                         pos[d][t], stepped[d][t] = p, 0
-                    s = stages[d][p]
-                    if ok[s]:
-                        stepped[d][t] += 1
-                        pick = (t, s)
+                    stepped[d][t] += 1
+                    pick = (t, stages[d][p])
                 else:
                     seq = stages[d] if direction == 0 else stages[d][::-1]
                     for s in seq:

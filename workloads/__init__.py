@@ -179,3 +179,61 @@ def count_ops(words: np.ndarray) -> int:
     is_end = (w >> 13) == 0
     first_end = np.where(is_end.any(1), is_end.argmax(1), w.shape[1])
     return int(first_end.sum())
+
+
+# ---------------------------------------------------------------------------------------------
+# parameter sets for the schedule generator (inputs only: the scheduler itself is not here)
+
+POLICY_INTS = 8
+NO_LIMIT = 2**31 - 1
+
+
+def policy_sets(problem: Problem, n: int, seed: int = BASE_SEED + 100):
+    """n seeded parameter sets for the scheduler: (policy int32 [n][D][8], inflight int32 [n][S]).
+
+    The mix follows the tuner's grid (schedule types = computation type traversal priority x stage
+    traversal priorities, per placement) widened by per-actor settings and in-flight limits:
+    * half of the sets use one policy for all actors, the others one per actor;
+    * computation type priority: backward-first 50 %, interleaved 40 % (units 1, sometimes 2-3),
+      forward-first 10 %;
+    * stage traversal: direction uniform; interval not set 40 %, else one of p/2, p, 2p or 1..4
+      (p = number of devices);
+    * in-flight limit per stage (v = stages per device): none 5 %; 1F1B-like
+      ceil((p - d) / v) + slack for a per-set slack in [0, p/4] 50 %; one uniform limit in [2, p/2]
+      for all stages 45 %.
+    """
+    rng = np.random.default_rng(seed)
+    D, S = problem.n_devices, problem.n_stages
+    per_actor = rng.random(n) < 0.5
+    pol = np.zeros((n, D, POLICY_INTS), np.int32)
+    shape = (n, D)
+    cttp = rng.choice(3, size=shape, p=[0.5, 0.1, 0.4]).astype(np.int32)
+    big_unit = rng.random(shape) < 0.25
+    unit_f = np.where((cttp == 2) & big_unit, rng.integers(2, 4, shape), 1)
+    unit_b = np.where((cttp == 2) & big_unit, rng.integers(1, 4, shape), 1)
+    choices = np.array([max(1, D // 2), D, 2 * D, 1, 2, 3, 4], np.int32)
+
+    def interval():
+        v = choices[rng.integers(0, len(choices), shape)]
+        return np.where(rng.random(shape) < 0.4, 0, v)
+
+    fields = [cttp, unit_f, unit_b, rng.integers(0, 2, shape), interval(), rng.integers(0, 2, shape), interval()]
+    for i, f in enumerate(fields):
+        f = np.asarray(f, np.int32)
+        pol[:, :, i] = np.where(per_actor[:, None], f, f[:, :1])
+    kind = rng.random(n)
+    dev = np.asarray(problem.stage_device, np.int64)
+    v = max(1, int(np.bincount(dev, minlength=D).max()))
+    slack = rng.integers(0, D // 4 + 1, n)
+    flat = rng.integers(2, max(3, D // 2 + 1), n)
+    like_1f1b = -(-(D - dev) // v)[None, :] + slack[:, None]
+    inflight = np.where(kind[:, None] < 0.05, NO_LIMIT,
+                        np.where(kind[:, None] < 0.55, like_1f1b, flat[:, None])).astype(np.int32)
+    return pol, np.broadcast_to(inflight, (n, S)).copy()
+
+
+def generator_stride(problem: Problem) -> int:
+    """Row stride (words, multiple of 8) that holds the longest list the scheduler can emit."""
+    per_dev = int(np.bincount(problem.stage_device, minlength=problem.n_devices).max())
+    longest = per_dev * problem.n_microbatches * (3 if problem.has_w else 2)
+    return max(8, -(-longest // 8) * 8)
