@@ -30,6 +30,94 @@ VALU_PEAK_WAVE_INSTR_PER_S = 256 * 4 * 2.4e9 / 4
 MEASURED = {("cfg4", 65536): {"traffic_bytes": 4.514e9, "valu_wave_instructions": 2.088e9}}
 
 
+def bench_generate(args, spec, threads) -> int:
+    """The schedule generator (the paper's scheduler, Section 5) on seeded parameter sets of the
+    configuration's problem: one step = one fpsched_generate launch over all sets."""
+    import numpy as np
+    import torch
+
+    import paper_2510_05112_amd as fp
+    import workloads
+
+    dev = torch.device("cuda", 0)
+    prob = spec.problem
+    n = spec.n_candidates
+    stride = workloads.generator_stride(prob)
+    t0 = time.perf_counter()
+    pol, inf = workloads.policy_sets(prob, n)
+    prep_s = time.perf_counter() - t0
+    handle = fp.Problem(prob, stride, device=0)
+    d_pol, d_inf = torch.from_numpy(pol).to(dev), torch.from_numpy(inf).to(dev)
+    out = dict(ops=torch.empty((n, prob.n_devices, stride), dtype=torch.int16, device=dev),
+               steps=torch.empty(n, dtype=torch.int32, device=dev),
+               status=torch.empty(n, dtype=torch.uint8, device=dev))
+    print(f"[bench] generate cfg{spec.index}: {n} parameter sets, {prob.n_devices} actors, stride {stride} "
+          f"({out['ops'].numel() * 2 / 1e9:.2f} GB of schedules)", file=sys.stderr, flush=True)
+    for _ in range(args.warmup):
+        handle.generate(d_pol, d_inf, stride, out=out)
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ev[i][0].record()
+        handle.generate(d_pol, d_inf, stride, out=out)
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    gen_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+    ms_per_step = wall * 1e3 / args.steps
+    words = out["ops"].cpu().numpy().view(np.uint16)
+    steps = out["steps"].cpu().numpy()
+    n_ops = int(np.count_nonzero(words >> 13))
+    # algorithmic bytes of one launch: the parameter sets in, every row of op words out (the rows are
+    # written in full, END padding included: the evaluator reads them as they are), steps and status
+    alg_bytes = pol.nbytes + inf.nbytes + words.nbytes + 5 * n
+    achieved = alg_bytes / (gen_ms * 1e-3) / 1e9
+    res = {
+        "metric": "schedules generated/sec", "value": n / (ms_per_step * 1e-3), "unit": "schedules/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
+        "config": {"workload": f"generator on cfg{spec.index}: {prob.name}, {n} seeded parameter sets",
+                   "parameter_sets": n, "devices": prob.n_devices, "stages": prob.n_stages,
+                   "microbatches": prob.n_microbatches, "ops_per_schedule": n_ops / n, "stride_words": stride},
+        "items_scheduled_per_s": n_ops / (ms_per_step * 1e-3),
+        "generate_kernel_ms": gen_ms,
+        "scheduling_steps": {"mean": float(steps.mean()), "max": int(steps.max())},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "fpsched generator kernel (generate_kernel)",
+                     "algorithmic_bytes_per_launch": alg_bytes,
+                     "note": "step-synchronous process: bound by the latency of a scheduling step, not by HBM"},
+        "fractions": {"complete": float((out["status"].cpu().numpy() == 0).mean())},
+        "host": {"parameter_sets_s": prep_s},
+    }
+    if args.check or not args.no_cpu_baseline:
+        import oracle  # test infrastructure: parity sample and the reported CPU baseline only
+        if args.check:
+            rng = np.random.default_rng(0)
+            pick = np.sort(rng.choice(n, min(args.check, n), replace=False))
+            ref = oracle.generate(prob, pol[pick], inf[pick], stride, threads=threads)
+            ok = (np.array_equal(words[pick], ref["words"]) and np.array_equal(steps[pick], ref["steps"]))
+            res["parity_sample"] = {"parameter_sets": int(len(pick)), "bit_exact": bool(ok)}
+            if not ok:
+                print("[bench] PARITY FAILURE against the generator oracle on the sample", file=sys.stderr)
+        if not args.no_cpu_baseline:
+            n1 = min(n, args.cpu_sample or 96)
+            t0 = time.perf_counter()
+            oracle.generate(prob, pol[:n1], inf[:n1], stride, threads=1)
+            t1 = time.perf_counter() - t0
+            nn = min(n, n1 * min(threads, 8))
+            t0 = time.perf_counter()
+            oracle.generate(prob, pol[:nn], inf[:nn], stride, threads=threads)
+            tn = time.perf_counter() - t0
+            res["cpu_baseline"] = {
+                "value": nn / tn, "unit": "schedules/s", "cores": threads, "kind": "oracle",
+                "sample": f"first {nn} parameter sets on {threads} host threads; single thread: first {n1}",
+                "single_thread_value": n1 / t1}
+    print(json.dumps(res))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -40,6 +128,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=None, help="candidates timed on the CPU oracle")
     ap.add_argument("--check", type=int, default=512, help="sampled candidates compared with the oracle")
+    ap.add_argument("--mode", choices=["evaluate", "generate"], default="evaluate",
+                    help="evaluate: the hot path (evaluation + top-k) on a resident batch (default, the "
+                         "headline metric); generate: the schedule generator on seeded parameter sets")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain elementwise copy of the op batch (a kernel of known HBM "
                          "traffic, used to calibrate rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -62,6 +153,8 @@ def main() -> int:
     spec = workloads.config(args.config, args.n)
     prob = spec.problem
     threads = min(16, os.cpu_count() or 1)
+    if args.mode == "generate":
+        return bench_generate(args, spec, threads)
 
     t0 = time.perf_counter()
     words = workloads.generate(spec, threads=threads)

@@ -24,6 +24,7 @@ struct fpsched_problem {
   int32_t* d_ints = nullptr;
   int32_t lds_bytes = 0;           // dynamic LDS of the general kernel (one wave per group)
   int32_t max_lds = 0;
+  int32_t max_degree = 0;          // largest in- or out-degree of a stage in the DAG
   bool general_ok = false, slots_ok = false;  // which kernels fit this problem in LDS
   bool use_slots = false;          // selected kernel: slot kernel (default when it fits) or general
   int32_t slot_v = 0;              // template bound on chunks per device
@@ -180,6 +181,8 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
   T.off_succ_off = append(soff.data(), S + 1);
   T.off_succ_stage = append(sst.data(), E);
   T.off_succ_comm = append(scm.data(), E);
+  for (int s = 0; s < S; ++s)
+    p->max_degree = std::max({p->max_degree, poff[s + 1] - poff[s], soff[s + 1] - soff[s]});
   T.off_local_stage = append(p->local_stage.data(), (size_t)D * kMaxChunks);
   T.off_n_chunks = append(p->n_chunks.data(), D);
   T.off_mem_cap = append(desc->mem_cap, D);
@@ -495,14 +498,21 @@ int fpsched_generate(const fpsched_problem* p, const fpsched_actor_policy* d_pol
   if (reinterpret_cast<uintptr_t>(d_ops) & 15) return FPSCHED_EINVAL;
   const int lpc = p->tables.lanes_per_cand;
   const int cpw = 64 / lpc;
-  const int64_t lds_bytes = 4ll * (p->tables.n_table_ints + (int64_t)cpw * 3 * p->S);
+  const int deg = p->max_degree <= 1 ? 1 : (p->max_degree == 2 ? 2 : 0);
+  const int64_t lds_bytes = 4ll * ((deg == 0 ? p->tables.n_table_ints : 0) + (int64_t)cpw * 3 * p->S + 1);
   if (lds_bytes > p->max_lds) return FPSCHED_EUNSUPPORTED;
   const int64_t blocks = (n_sets + cpw - 1) / cpw;
   if (blocks > 0x7fffffffll) return FPSCHED_EINVAL;
   DeviceGuard g(p->device_id);
   if (!g.ok) return FPSCHED_EHIP;
   const int V = max_chunks <= 1 ? 1 : (max_chunks <= 2 ? 2 : 4);
-  auto kernel = V == 1 ? &generate_kernel<1> : (V == 2 ? &generate_kernel<2> : &generate_kernel<4>);
+  using GenKernel = void (*)(DevTables, const int32_t*, const int32_t*, long long, int, uint16_t*, int32_t*,
+                             unsigned char*);
+  static const GenKernel table[3][3] = {
+      {&generate_kernel<1, 0>, &generate_kernel<1, 1>, &generate_kernel<1, 2>},
+      {&generate_kernel<2, 0>, &generate_kernel<2, 1>, &generate_kernel<2, 2>},
+      {&generate_kernel<4, 0>, &generate_kernel<4, 1>, &generate_kernel<4, 2>}};
+  const GenKernel kernel = table[V == 1 ? 0 : (V == 2 ? 1 : 2)][deg];
   if (lds_bytes > 64 * 1024 &&
       hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                           (int)lds_bytes) != hipSuccess)

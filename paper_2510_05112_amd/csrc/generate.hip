@@ -40,7 +40,10 @@ __device__ __forceinline__ int high_bit(unsigned x) { return 31 - __clz(x); }
 
 }  // namespace
 
-template <int V>
+// V = bound on the stages per device (1, 2, 4).  DEG = bound on the DAG in- and out-degree of a
+// stage (1 or 2): the LDS addresses of the neighbours' counters are then kept in registers;
+// DEG = 0 walks the edge lists in LDS instead (any degree).
+template <int V, int DEG>
 __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t* __restrict__ policy,
                                                       const int32_t* __restrict__ inflight, long long n_sets,
                                                       int stride, uint16_t* __restrict__ ops,
@@ -52,30 +55,42 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
   const int lpc = T.lanes_per_cand;
   const int lpc_shift = __ffs(lpc) - 1;
   const int cpw = 64 >> lpc_shift;
-  const int ntypes = T.has_w ? 3 : 2;
-  // LDS: [problem tables][sets of the wavefront: counters [3][S]]
-  for (int i = lane; i < T.n_table_ints; i += 64) lds[i] = T.ints[i];
-  int32_t* counts = lds + T.n_table_ints;
+  const bool has_w = T.has_w != 0;
+  // LDS: [edge lists, only if DEG == 0][sets of the wavefront: counters [3][S]][one word holding m]
+  const int n_tab = DEG == 0 ? T.n_table_ints : 0;
+  if (DEG == 0)
+    for (int i = lane; i < n_tab; i += 64) lds[i] = T.ints[i];
+  int32_t* counts = lds + n_tab;
   for (int i = lane; i < cpw * 3 * S; i += 64) counts[i] = 0;
+  const int at_m = cpw * 3 * S;   // a counter that is always "done": stands in for a missing neighbour
+  if (lane == 0) counts[at_m] = m;
   __syncthreads();
-  const int32_t* pred_off = lds + T.off_pred_off;
-  const int32_t* pred_stage = lds + T.off_pred_stage;
-  const int32_t* succ_off = lds + T.off_succ_off;
-  const int32_t* succ_stage = lds + T.off_succ_stage;
 
   const int seg = lane >> lpc_shift;
   const int d = lane & (lpc - 1);
   const long long set = (long long)blockIdx.x * cpw + seg;
   const bool has_row = set < n_sets && d < D;
   const unsigned long long seg_mask = (lpc == 64 ? ~0ull : ((1ull << lpc) - 1ull)) << (seg * lpc);
-  int32_t* cnt = counts + seg * 3 * S;   // cnt[type * S + stage]
+  const int base = seg * 3 * S;   // this set's counters: counts[base + type * S + stage]
 
-  const int nch = has_row ? lds[T.off_n_chunks + d] : 0;
+  const int nch = has_row ? T.ints[T.off_n_chunks + d] : 0;
   int stage[V], limit[V];
+  int pred_at[V][DEG > 0 ? DEG : 1], succ_at[V][DEG > 0 ? DEG : 1];
 #pragma unroll
   for (int c = 0; c < V; ++c) {
-    stage[c] = c < nch ? lds[T.off_local_stage + d * kMaxChunks + c] : 0;
+    stage[c] = c < nch ? T.ints[T.off_local_stage + d * kMaxChunks + c] : 0;
     limit[c] = c < nch ? inflight[set * S + stage[c]] : 1;
+#pragma unroll
+    for (int k = 0; k < (DEG > 0 ? DEG : 1); ++k) {
+      pred_at[c][k] = at_m;
+      succ_at[c][k] = at_m;
+      if (DEG > 0 && c < nch) {
+        const int s = stage[c];
+        const int pe = T.ints[T.off_pred_off + s] + k, se = T.ints[T.off_succ_off + s] + k;
+        if (pe < T.ints[T.off_pred_off + s + 1]) pred_at[c][k] = base + T.ints[T.off_pred_stage + pe];
+        if (se < T.ints[T.off_succ_off + s + 1]) succ_at[c][k] = base + S + T.ints[T.off_succ_stage + se];
+      }
+    }
   }
   int cttp = 0, unit_f = 1, unit_b = 1, f_dir = 0, f_int = 0, b_dir = 0, b_int = 0;
   if (has_row) {
@@ -90,83 +105,91 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
   for (int c = 0; c < V; ++c) bad = bad || limit[c] < 1;
   const bool set_bad = (__ballot(bad && has_row) & seg_mask) != 0ull;
 
+  // scheduled micro-batches of this actor's own (type, stage): in registers, mirrored to LDS for
+  // the neighbours; a chunk the actor does not have counts as finished
+  int nf[V], nb[V], nw[V];
+#pragma unroll
+  for (int c = 0; c < V; ++c) nf[c] = nb[c] = nw[c] = (c < nch && !set_bad) ? 0 : m;
   int turn_type = kGenF, turn_run = 0;
   int pos_f = f_dir == 0 ? 0 : (nch > 0 ? nch - 1 : 0), pos_b = b_dir == 0 ? 0 : (nch > 0 ? nch - 1 : 0);
   int stepped_f = 0, stepped_b = 0;
-  int left = set_bad ? 0 : nch * m * ntypes;   // items this actor still has to schedule
+  int left = set_bad ? 0 : nch * m * (has_w ? 3 : 2);   // items this actor still has to schedule
   bool live = (__ballot(left > 0) & seg_mask) != 0ull;   // the set's process is still running
   int steps = 0, status = set_bad ? 4 : 0;
   int len = 0;
   unsigned buf0 = 0u, buf1 = 0u;   // up to four op words waiting for their 8-byte store
   uint16_t* row = ops + (size_t)(has_row ? set * D + d : 0) * (size_t)stride;
 
-  // every step but the last of a set schedules at least one of its 3 S m items
+  // Every step but the last of a set schedules at least one of its 3 S m items.  A workgroup is one
+  // wavefront: its LDS instructions execute in program order, so the reads of a step see the counters
+  // as the previous step left them and no barrier is needed between the phases.
   const long long max_steps = 3ll * S * m + 2;
   for (long long step = 0; step < max_steps; ++step) {
     if (__ballot(live) == 0ull) break;
-    // ---- read phase: which of this actor's (type, stage) have their next item in the reorder
-    // queue, and which of those pass the check function
-    unsigned ready[3] = {0u, 0u, 0u}, ok_f = 0u;
-    int own[3][V];
+    // ---- read phase: for which of this actor's stages is the next item of each type eligible
+    // (dependencies resolved, and for forward items the in-flight rule)
+    unsigned ok_f = 0u, ok_b = 0u, ok_w = 0u;
 #pragma unroll
     for (int c = 0; c < V; ++c) {
-      own[0][c] = own[1][c] = own[2][c] = 0;
-      if (c < nch && live) {
-        const int s = stage[c];
-        const int nf = cnt[s], nb = cnt[S + s], nw = cnt[2 * S + s];
-        own[0][c] = nf; own[1][c] = nb; own[2][c] = nw;
-        int f_ahead = m;
-        for (int e = pred_off[s]; e < pred_off[s + 1]; ++e) f_ahead = min(f_ahead, cnt[pred_stage[e]]);
-        int b_ahead = nf;
-        for (int e = succ_off[s]; e < succ_off[s + 1]; ++e) b_ahead = min(b_ahead, cnt[S + succ_stage[e]]);
-        const unsigned bit = 1u << c;
-        if (f_ahead > nf) { ready[0] |= bit; if (nf - nb < limit[c]) ok_f |= bit; }
-        if (b_ahead > nb) ready[1] |= bit;
-        if (ntypes == 3 && nb > nw) ready[2] |= bit;
-      }
-    }
-    // ---- the step function: instruction types in priority order, stages in traversal order
-    int pick_t = -1, pick_c = 0;
-    const int first = cttp == 0 ? kGenB : (cttp == 1 ? kGenF : turn_type);
+      int f_ahead = m, b_ahead = nf[c];
+      if (DEG > 0) {
 #pragma unroll
-    for (int oi = 0; oi < 3; ++oi) {
-      const int t = oi == 0 ? first : (oi == 1 ? (first == kGenF ? kGenB : kGenF) : kGenW);
-      if (pick_t >= 0 || (oi == 2 && ntypes < 3)) continue;
-      const unsigned rdy = t == kGenF ? ready[0] : (t == kGenB ? ready[1] : ready[2]);
-      if (rdy == 0u) continue;   // this reorder queue is empty
-      const unsigned ok = t == kGenF ? ok_f : rdy;
-      const int dir = t == kGenF ? f_dir : (t == kGenB ? b_dir : 0);
-      const int interval = t == kGenF ? f_int : (t == kGenB ? b_int : 0);
-      if (ok == 0u) continue;    // nothing eligible of this type: try the next one
+        for (int k = 0; k < (DEG > 0 ? DEG : 1); ++k) {
+          f_ahead = min(f_ahead, counts[pred_at[c][k]]);
+          b_ahead = min(b_ahead, counts[succ_at[c][k]]);
+        }
+      } else if (c < nch) {
+        const int32_t* pred_off = lds + T.off_pred_off;
+        const int32_t* succ_off = lds + T.off_succ_off;
+        const int s = stage[c];
+        for (int e = pred_off[s]; e < pred_off[s + 1]; ++e) f_ahead = min(f_ahead, counts[base + lds[T.off_pred_stage + e]]);
+        for (int e = succ_off[s]; e < succ_off[s + 1]; ++e) b_ahead = min(b_ahead, counts[base + S + lds[T.off_succ_stage + e]]);
+      }
+      const unsigned bit = 1u << c;
+      if (f_ahead > nf[c] && nf[c] - nb[c] < limit[c]) ok_f |= bit;
+      if (b_ahead > nb[c]) ok_b |= bit;
+      if (has_w && nb[c] > nw[c]) ok_w |= bit;
+    }
+    if (!live) { ok_f = 0u; ok_b = 0u; ok_w = 0u; }
+    // ---- the step function: the first instruction type, in priority order, with an eligible item;
+    // then the stage, in traversal order
+    const int first = cttp == 0 ? kGenB : (cttp == 1 ? kGenF : turn_type);
+    const unsigned ok_first = first == kGenF ? ok_f : ok_b, ok_second = first == kGenF ? ok_b : ok_f;
+    const int pick_t = ok_first ? first : (ok_second ? (first ^ 1) : (ok_w ? kGenW : -1));
+    int pick_c = 0;
+    if (pick_t >= 0) {
+      const unsigned ok = pick_t == kGenF ? ok_f : (pick_t == kGenB ? ok_b : ok_w);
+      const int dir = pick_t == kGenF ? f_dir : (pick_t == kGenB ? b_dir : 0);
+      const int interval = pick_t == kGenF ? f_int : (pick_t == kGenB ? b_int : 0);
       if (interval > 0) {
-        int p = t == kGenF ? pos_f : pos_b;
-        int stepped = t == kGenF ? stepped_f : stepped_b;
+        int p = pick_t == kGenF ? pos_f : pos_b;
+        int stepped = pick_t == kGenF ? stepped_f : stepped_b;
         if (stepped == interval || !((ok >> p) & 1u)) {
           // move on, in the traversal direction, to the next stage with an eligible item
+#pragma unroll
           for (int k = 0; k < V; ++k) {
-            if (k >= nch) break;
-            p = dir == 0 ? (p + 1 == nch ? 0 : p + 1) : (p == 0 ? nch - 1 : p - 1);
-            if ((ok >> p) & 1u) break;
+            if (k < nch && !(k > 0 && ((ok >> p) & 1u))) p = dir == 0 ? (p + 1 == nch ? 0 : p + 1) : (p == 0 ? nch - 1 : p - 1);
           }
           stepped = 0;
         }
-        pick_t = t; pick_c = p; stepped += 1;
-        if (t == kGenF) { pos_f = p; stepped_f = stepped; } else { pos_b = p; stepped_b = stepped; }
+        pick_c = p;
+        stepped += 1;
+        if (pick_t == kGenF) { pos_f = p; stepped_f = stepped; } else { pos_b = p; stepped_b = stepped; }
       } else {
-        pick_t = t;
         pick_c = dir == 0 ? low_bit(ok) : high_bit(ok);
       }
-    }
-    __syncthreads();   // every lane has read the counters of this step
-    // ---- write phase: the choice becomes visible for the next step
-    if (pick_t >= 0) {
-      int s = stage[0], j = own[0][0];
+      // ---- write phase: the choice becomes visible for the next step
+      int s = stage[0], j = 0;
 #pragma unroll
       for (int c = 0; c < V; ++c)
-#pragma unroll
-        for (int t = 0; t < 3; ++t)
-          if (pick_c == c && pick_t == t) { s = stage[c]; j = own[t][c]; }
-      cnt[pick_t * S + s] = j + 1;
+        if (pick_c == c) {
+          s = stage[c];
+          j = pick_t == kGenF ? nf[c] : (pick_t == kGenB ? nb[c] : nw[c]);
+          nf[c] += pick_t == kGenF;
+          nb[c] += pick_t == kGenB;
+          nw[c] += pick_t == kGenW;
+        }
+      counts[base + pick_t * S + s] = j + 1;
       left -= 1;
       const unsigned word = ((unsigned)(pick_t + 1) << 13) | ((unsigned)pick_c << 11) | (unsigned)j;
       const int q = len & 3;
@@ -183,13 +206,13 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
         if (++turn_run >= (pick_t == kGenF ? unit_f : unit_b)) { turn_type = pick_t == kGenF ? kGenB : kGenF; turn_run = 0; }
       }
     }
+    __builtin_amdgcn_wave_barrier();
     const bool any_pick = (__ballot(pick_t >= 0) & seg_mask) != 0ull;
     const bool any_left = (__ballot(left > 0) & seg_mask) != 0ull;
     if (live) {
       if (!any_pick) { status = 1; live = false; }   // items remain and nothing can move
       else { steps += 1; live = any_left; }
     }
-    __syncthreads();   // the counters written in this step are in place
   }
   // ---- rows are END-padded to the stride; words still waiting go out with the padding
   if (has_row) {
@@ -206,11 +229,18 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
   }
 }
 
-template __global__ void generate_kernel<1>(DevTables, const int32_t*, const int32_t*, long long, int, uint16_t*,
-                                            int32_t*, unsigned char*);
-template __global__ void generate_kernel<2>(DevTables, const int32_t*, const int32_t*, long long, int, uint16_t*,
-                                            int32_t*, unsigned char*);
-template __global__ void generate_kernel<4>(DevTables, const int32_t*, const int32_t*, long long, int, uint16_t*,
-                                            int32_t*, unsigned char*);
+#define FPSCHED_INSTANTIATE(V, G)                                                                             \
+  template __global__ void generate_kernel<V, G>(DevTables, const int32_t*, const int32_t*, long long, int, \
+                                                 uint16_t*, int32_t*, unsigned char*);
+FPSCHED_INSTANTIATE(1, 1)
+FPSCHED_INSTANTIATE(2, 1)
+FPSCHED_INSTANTIATE(4, 1)
+FPSCHED_INSTANTIATE(1, 2)
+FPSCHED_INSTANTIATE(2, 2)
+FPSCHED_INSTANTIATE(4, 2)
+FPSCHED_INSTANTIATE(1, 0)
+FPSCHED_INSTANTIATE(2, 0)
+FPSCHED_INSTANTIATE(4, 0)
+#undef FPSCHED_INSTANTIATE
 
 }  // namespace fpsched

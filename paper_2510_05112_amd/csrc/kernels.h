@@ -32,8 +32,9 @@ __global__ void eval_slot_kernel(SlotTables T, const uint16_t* ops, long long n_
 
 __global__ void reset_counter_kernel(unsigned long long* counter, unsigned long long value);
 
-// V as above.  One wavefront per workgroup, 64 / lanes_per_cand parameter sets per wavefront.
-template <int V>
+// V as above; DEG = bound on the in- and out-degree of a stage (1, 2, or 0 = any).  One wavefront per
+// workgroup, 64 / lanes_per_cand parameter sets per wavefront.
+template <int V, int DEG>
 __global__ void generate_kernel(DevTables T, const int32_t* policy, const int32_t* inflight, long long n_sets,
                                 int stride, uint16_t* ops, int32_t* out_steps, unsigned char* out_status);
 
