@@ -53,14 +53,15 @@ def bench_generate(args, spec, threads) -> int:
                status=torch.empty(n, dtype=torch.uint8, device=dev))
     print(f"[bench] generate cfg{spec.index}: {n} parameter sets, {prob.n_devices} actors, stride {stride} "
           f"({out['ops'].numel() * 2 / 1e9:.2f} GB of schedules)", file=sys.stderr, flush=True)
+    ws = handle.alloc_workspace(n, 0)
     for _ in range(args.warmup):
-        handle.generate(d_pol, d_inf, stride, out=out)
+        handle.generate(d_pol, d_inf, stride, out=out, workspace=ws)
     torch.cuda.synchronize()
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
     t0 = time.perf_counter()
     for i in range(args.steps):
         ev[i][0].record()
-        handle.generate(d_pol, d_inf, stride, out=out)
+        handle.generate(d_pol, d_inf, stride, out=out, workspace=ws)
         ev[i][1].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0

@@ -211,11 +211,13 @@ typedef struct {
  * in full (END-padded); stride_words a multiple of 8 and >= (most stages on one device)
  * x m x (3 if has_w else 2).  d_steps: DEVICE out int32 [n_sets], scheduling steps taken
  * (the unit-time length of the schedule, bubbles included); d_status: DEVICE out uint8
- * [n_sets], 0 or FPSCHED_GEN_*.  Asynchronous on hip_stream; no workspace.  EUNSUPPORTED
- * if the problem's tables do not fit LDS. */
+ * [n_sets], 0 or FPSCHED_GEN_*.  d_workspace: DEVICE, 16-byte aligned, >= 256 bytes (a work
+ * counter; the same rules as for fpsched_evaluate).  Asynchronous on hip_stream.
+ * EUNSUPPORTED if the problem's tables do not fit LDS. */
 int fpsched_generate(const fpsched_problem *p, const fpsched_actor_policy *d_policy,
                      const int32_t *d_inflight, int64_t n_sets, int32_t stride_words,
-                     uint16_t *d_ops, int32_t *d_steps, uint8_t *d_status, void *hip_stream);
+                     uint16_t *d_ops, int32_t *d_steps, uint8_t *d_status, void *d_workspace,
+                     size_t workspace_bytes, void *hip_stream);
 
 const char *fpsched_strerror(int code);
 int fpsched_version(void);

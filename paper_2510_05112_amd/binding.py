@@ -70,7 +70,7 @@ def load_library():
         lib.fpsched_topk.restype = ctypes.c_int
         lib.fpsched_topk.argtypes = [vp, _Results, i64, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.fpsched_generate.restype = ctypes.c_int
-        lib.fpsched_generate.argtypes = [vp, vp, vp, i64, i32, vp, vp, vp, vp]
+        lib.fpsched_generate.argtypes = [vp, vp, vp, i64, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.fpsched_encode.restype = ctypes.c_int
         lib.fpsched_encode.argtypes = [vp, vp, i32, i32, vp]
         lib.fpsched_validate.restype = ctypes.c_int64
@@ -233,7 +233,7 @@ class Problem:
             raise FpschedError(rc, "fpsched_topk")
         return out
 
-    def generate(self, policy, inflight, stride: int, out=None, stream=None):
+    def generate(self, policy, inflight, stride: int, out=None, workspace=None, stream=None):
         """Run the scheduler on n parameter sets.  policy: torch int32 CUDA tensor [n][D][8]
         (fpsched_actor_policy per actor), inflight: torch int32 CUDA tensor [n][S].  Returns
         dict(ops int16 [n][D][stride], steps int32 [n], status uint8 [n]) of CUDA tensors.
@@ -250,9 +250,12 @@ class Problem:
             out = dict(ops=torch.empty((n, self.D, int(stride)), dtype=torch.int16, device=dev),
                        steps=torch.empty(n, dtype=torch.int32, device=dev),
                        status=torch.empty(n, dtype=torch.uint8, device=dev))
+        if workspace is None:
+            workspace = self.alloc_workspace(n, 0)
         rc = load_library().fpsched_generate(self._h, policy.data_ptr(), inflight.data_ptr(), n, int(stride),
                                              out["ops"].data_ptr(), out["steps"].data_ptr(),
-                                             out["status"].data_ptr(), self._stream(stream))
+                                             out["status"].data_ptr(), workspace.data_ptr(), workspace.numel(),
+                                             self._stream(stream))
         if rc != 0:
             raise FpschedError(rc, "fpsched_generate")
         return out

@@ -25,6 +25,7 @@ struct fpsched_problem {
   int32_t lds_bytes = 0;           // dynamic LDS of the general kernel (one wave per group)
   int32_t max_lds = 0;
   int32_t max_degree = 0;          // largest in- or out-degree of a stage in the DAG
+  int32_t n_cu = 0;                // compute units of the device
   bool general_ok = false, slots_ok = false;  // which kernels fit this problem in LDS
   bool use_slots = false;          // selected kernel: slot kernel (default when it fits) or general
   int32_t slot_v = 0;              // template bound on chunks per device
@@ -372,6 +373,7 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
         delete p; return FPSCHED_EHIP;
       }
       p->slot_grid = n_cu * std::max(best_groups, 1);
+      p->n_cu = n_cu;
     }
     if (!p->general_ok && !p->slots_ok) { delete p; return FPSCHED_EUNSUPPORTED; }
     p->use_slots = p->slots_ok;
@@ -486,7 +488,7 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
 
 int fpsched_generate(const fpsched_problem* p, const fpsched_actor_policy* d_policy, const int32_t* d_inflight,
                      int64_t n_sets, int32_t stride_words, uint16_t* d_ops, int32_t* d_steps, uint8_t* d_status,
-                     void* hip_stream) {
+                     void* d_workspace, size_t workspace_bytes, void* hip_stream) {
   if (!p || n_sets < 0) return FPSCHED_EINVAL;
   if (p->device_id < 0) return FPSCHED_ENODEV;
   if (n_sets == 0) return FPSCHED_OK;
@@ -496,18 +498,27 @@ int fpsched_generate(const fpsched_problem* p, const fpsched_actor_policy* d_pol
   const int64_t longest = (int64_t)max_chunks * p->m * (p->has_w ? 3 : 2);
   if (stride_words < 8 || (stride_words & 7) || stride_words < longest) return FPSCHED_EINVAL;
   if (reinterpret_cast<uintptr_t>(d_ops) & 15) return FPSCHED_EINVAL;
+  // the first 8 bytes of the workspace hold the counter the segments draw parameter sets from
+  if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) & 15)) return FPSCHED_EINVAL;
+  if (workspace_bytes < 256) return FPSCHED_ENOMEM;
   const int lpc = p->tables.lanes_per_cand;
   const int cpw = 64 / lpc;
   const int deg = p->max_degree <= 1 ? 1 : (p->max_degree == 2 ? 2 : 0);
   const int64_t lds_bytes = 4ll * ((deg == 0 ? p->tables.n_table_ints : 0) + (int64_t)cpw * 3 * p->S + 1);
   if (lds_bytes > p->max_lds) return FPSCHED_EUNSUPPORTED;
-  const int64_t blocks = (n_sets + cpw - 1) / cpw;
-  if (blocks > 0x7fffffffll) return FPSCHED_EINVAL;
+  // persistent grid: as many single-wavefront workgroups as stay resident (tuning knob:
+  // FPSCHED_GEN_WAVES = wavefronts per compute unit)
+  int waves_per_cu = 16;
+  if (const char* env = getenv("FPSCHED_GEN_WAVES")) {
+    const int v = atoi(env);
+    if (v >= 1 && v <= 32) waves_per_cu = v;
+  }
+  const int64_t blocks = std::min<int64_t>((n_sets + cpw - 1) / cpw, (int64_t)p->n_cu * waves_per_cu);
   DeviceGuard g(p->device_id);
   if (!g.ok) return FPSCHED_EHIP;
   const int V = max_chunks <= 1 ? 1 : (max_chunks <= 2 ? 2 : 4);
   using GenKernel = void (*)(DevTables, const int32_t*, const int32_t*, long long, int, uint16_t*, int32_t*,
-                             unsigned char*);
+                             unsigned char*, unsigned long long*);
   static const GenKernel table[3][3] = {
       {&generate_kernel<1, 0>, &generate_kernel<1, 1>, &generate_kernel<1, 2>},
       {&generate_kernel<2, 0>, &generate_kernel<2, 1>, &generate_kernel<2, 2>},
@@ -517,9 +528,13 @@ int fpsched_generate(const fpsched_problem* p, const fpsched_actor_policy* d_pol
       hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                           (int)lds_bytes) != hipSuccess)
     return FPSCHED_EHIP;
+  unsigned long long* counter = static_cast<unsigned long long*>(d_workspace);
+  // segment g starts on set g; the counter hands out the sets after those
+  hipLaunchKernelGGL(reset_counter_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(hip_stream), counter,
+                     (unsigned long long)(blocks * cpw));
   hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(64), (size_t)lds_bytes,
                      static_cast<hipStream_t>(hip_stream), p->tables, reinterpret_cast<const int32_t*>(d_policy),
-                     d_inflight, (long long)n_sets, (int)stride_words, d_ops, d_steps, d_status);
+                     d_inflight, (long long)n_sets, (int)stride_words, d_ops, d_steps, d_status, counter);
   return check_hip(hipGetLastError());
 }
 

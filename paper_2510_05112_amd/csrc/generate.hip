@@ -43,12 +43,17 @@ __device__ __forceinline__ int high_bit(unsigned x) { return 31 - __clz(x); }
 // V = bound on the stages per device (1, 2, 4).  DEG = bound on the DAG in- and out-degree of a
 // stage (1 or 2): the LDS addresses of the neighbours' counters are then kept in registers;
 // DEG = 0 walks the edge lists in LDS instead (any degree).
+//
+// The grid is persistent: a segment (the lanes of one parameter set) that finishes its schedule
+// writes it out, draws the next set from a global counter and starts over while the other segments
+// of the wavefront keep stepping, so that sets that need few and many steps balance out.
 template <int V, int DEG>
 __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t* __restrict__ policy,
                                                       const int32_t* __restrict__ inflight, long long n_sets,
                                                       int stride, uint16_t* __restrict__ ops,
                                                       int32_t* __restrict__ out_steps,
-                                                      unsigned char* __restrict__ out_status) {
+                                                      unsigned char* __restrict__ out_status,
+                                                      unsigned long long* __restrict__ next_set) {
   extern __shared__ int32_t lds[];
   const int lane = threadIdx.x;
   const int S = T.S, m = T.m, D = T.D;
@@ -61,25 +66,23 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
   if (DEG == 0)
     for (int i = lane; i < n_tab; i += 64) lds[i] = T.ints[i];
   int32_t* counts = lds + n_tab;
-  for (int i = lane; i < cpw * 3 * S; i += 64) counts[i] = 0;
   const int at_m = cpw * 3 * S;   // a counter that is always "done": stands in for a missing neighbour
   if (lane == 0) counts[at_m] = m;
   __syncthreads();
 
   const int seg = lane >> lpc_shift;
   const int d = lane & (lpc - 1);
-  const long long set = (long long)blockIdx.x * cpw + seg;
-  const bool has_row = set < n_sets && d < D;
+  const bool has_dev = d < D;
   const unsigned long long seg_mask = (lpc == 64 ? ~0ull : ((1ull << lpc) - 1ull)) << (seg * lpc);
-  const int base = seg * 3 * S;   // this set's counters: counts[base + type * S + stage]
+  const int base = seg * 3 * S;   // this segment's counters: counts[base + type * S + stage]
 
-  const int nch = has_row ? T.ints[T.off_n_chunks + d] : 0;
-  int stage[V], limit[V];
+  // what depends on the actor only
+  const int nch = has_dev ? T.ints[T.off_n_chunks + d] : 0;
+  int stage[V];
   int pred_at[V][DEG > 0 ? DEG : 1], succ_at[V][DEG > 0 ? DEG : 1];
 #pragma unroll
   for (int c = 0; c < V; ++c) {
     stage[c] = c < nch ? T.ints[T.off_local_stage + d * kMaxChunks + c] : 0;
-    limit[c] = c < nch ? inflight[set * S + stage[c]] : 1;
 #pragma unroll
     for (int k = 0; k < (DEG > 0 ? DEG : 1); ++k) {
       pred_at[c][k] = at_m;
@@ -92,40 +95,89 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
       }
     }
   }
-  int cttp = 0, unit_f = 1, unit_b = 1, f_dir = 0, f_int = 0, b_dir = 0, b_int = 0;
-  if (has_row) {
-    const int32_t* pol = policy + (set * D + d) * 8;
-    cttp = pol[0]; unit_f = pol[1]; unit_b = pol[2];
-    f_dir = pol[3]; f_int = pol[4]; b_dir = pol[5]; b_int = pol[6];
-  }
-  // a parameter set with a value outside its domain generates nothing (status 4)
-  bool bad = cttp < 0 || cttp > 2 || unit_f < 1 || unit_b < 1 || f_dir < 0 || f_dir > 1 || f_int < 0 ||
-             b_dir < 0 || b_dir > 1 || b_int < 0 || (cttp != 2 && (unit_f != 1 || unit_b != 1));
-#pragma unroll
-  for (int c = 0; c < V; ++c) bad = bad || limit[c] < 1;
-  const bool set_bad = (__ballot(bad && has_row) & seg_mask) != 0ull;
 
+  // per-set state
+  long long set = (long long)blockIdx.x * cpw + seg;   // the first set of a segment is its global index
+  bool first_draw = true;
+  bool has_set = false;   // the segment is working on a set (possibly finished and not yet written out)
+  bool fresh = true;      // the segment wants its next set
+  int limit[V];
+  int cttp = 0, unit_f = 1, unit_b = 1, f_dir = 0, f_int = 0, b_dir = 0, b_int = 0;
   // scheduled micro-batches of this actor's own (type, stage): in registers, mirrored to LDS for
   // the neighbours; a chunk the actor does not have counts as finished
   int nf[V], nb[V], nw[V];
 #pragma unroll
-  for (int c = 0; c < V; ++c) nf[c] = nb[c] = nw[c] = (c < nch && !set_bad) ? 0 : m;
-  int turn_type = kGenF, turn_run = 0;
-  int pos_f = f_dir == 0 ? 0 : (nch > 0 ? nch - 1 : 0), pos_b = b_dir == 0 ? 0 : (nch > 0 ? nch - 1 : 0);
-  int stepped_f = 0, stepped_b = 0;
-  int left = set_bad ? 0 : nch * m * (has_w ? 3 : 2);   // items this actor still has to schedule
-  bool live = (__ballot(left > 0) & seg_mask) != 0ull;   // the set's process is still running
-  int steps = 0, status = set_bad ? 4 : 0;
-  int len = 0;
+  for (int c = 0; c < V; ++c) { limit[c] = 1; nf[c] = nb[c] = nw[c] = m; }
+  int turn_type = kGenF, turn_run = 0, pos_f = 0, pos_b = 0, stepped_f = 0, stepped_b = 0;
+  int left = 0;        // items this actor still has to schedule
+  bool live = false;   // the set's process is still running
+  int steps = 0, status = 0, len = 0;
   unsigned buf0 = 0u, buf1 = 0u;   // up to four op words waiting for their 8-byte store
-  uint16_t* row = ops + (size_t)(has_row ? set * D + d : 0) * (size_t)stride;
+  uint16_t* row = ops;
 
-  // Every step but the last of a set schedules at least one of its 3 S m items.  A workgroup is one
-  // wavefront: its LDS instructions execute in program order, so the reads of a step see the counters
-  // as the previous step left them and no barrier is needed between the phases.
-  const long long max_steps = 3ll * S * m + 2;
-  for (long long step = 0; step < max_steps; ++step) {
-    if (__ballot(live) == 0ull) break;
+  // Every step but the last of a set schedules at least one of its 3 S m items, and a segment
+  // cannot draw more than all sets: the bound below is never reached, it only makes sure that the
+  // wavefront leaves the loop whatever happens.  A workgroup is one wavefront: its LDS instructions
+  // execute in program order, so the reads of a step see the counters as the previous step left them
+  // and no barrier is needed between the phases.
+  const unsigned long long per_set = 3ull * (unsigned)S * (unsigned)m + 4ull;
+  const unsigned long long bound = per_set * ((unsigned long long)n_sets + 1ull);
+  for (unsigned long long step = 0; step < bound; ++step) {
+    if (__ballot(fresh) != 0ull) {
+      // ---- segments that finished write their schedule out and start on the next set
+      if (fresh) {
+        fresh = false;
+        if (has_set && has_dev) {
+          // rows are END-padded to the stride; words still waiting go out with the padding
+          int at = len & ~3;
+          if (len & 3) {
+            if (at < stride) *reinterpret_cast<uint2*>(row + at) = make_uint2(buf0, buf1);
+            at += 4;
+          }
+          for (; at < stride; at += 4) *reinterpret_cast<uint2*>(row + at) = make_uint2(0u, 0u);
+          if (d == 0) {
+            out_steps[set] = steps;
+            out_status[set] = (unsigned char)status;
+          }
+        }
+        if (!first_draw) {
+          unsigned long long drawn = 0ull;
+          if (d == 0 && seg < cpw) drawn = atomicAdd(next_set, 1ull);
+          set = (long long)__shfl(drawn, seg << lpc_shift, 64);
+        }
+        first_draw = false;
+        has_set = seg < cpw && set < n_sets;
+        const bool has_row = has_set && has_dev;
+        if (has_set)
+          for (int i = d; i < 3 * S; i += lpc) counts[base + i] = 0;
+        cttp = 0; unit_f = 1; unit_b = 1; f_dir = 0; f_int = 0; b_dir = 0; b_int = 0;
+        if (has_row) {
+          const int32_t* pol = policy + (set * D + d) * 8;
+          cttp = pol[0]; unit_f = pol[1]; unit_b = pol[2];
+          f_dir = pol[3]; f_int = pol[4]; b_dir = pol[5]; b_int = pol[6];
+        }
+#pragma unroll
+        for (int c = 0; c < V; ++c) limit[c] = (has_row && c < nch) ? inflight[set * S + stage[c]] : 1;
+        // a parameter set with a value outside its domain generates nothing (status 4)
+        bool bad = cttp < 0 || cttp > 2 || unit_f < 1 || unit_b < 1 || f_dir < 0 || f_dir > 1 || f_int < 0 ||
+                   b_dir < 0 || b_dir > 1 || b_int < 0 || (cttp != 2 && (unit_f != 1 || unit_b != 1));
+#pragma unroll
+        for (int c = 0; c < V; ++c) bad = bad || limit[c] < 1;
+        const bool set_bad = (__ballot(bad && has_row) & seg_mask) != 0ull;
+#pragma unroll
+        for (int c = 0; c < V; ++c) nf[c] = nb[c] = nw[c] = (has_row && c < nch && !set_bad) ? 0 : m;
+        turn_type = kGenF; turn_run = 0;
+        pos_f = f_dir == 0 ? 0 : (nch > 0 ? nch - 1 : 0);
+        pos_b = b_dir == 0 ? 0 : (nch > 0 ? nch - 1 : 0);
+        stepped_f = 0; stepped_b = 0;
+        left = (has_row && !set_bad) ? nch * m * (has_w ? 3 : 2) : 0;
+        live = (__ballot(left > 0) & seg_mask) != 0ull;
+        steps = 0; status = set_bad ? 4 : 0; len = 0; buf0 = 0u; buf1 = 0u;
+        row = ops + (size_t)(has_row ? set * D + d : 0) * (size_t)stride;
+        fresh = has_set && !live;   // nothing to schedule (a bad set, no stages): written out next time round
+      }
+      if (__ballot(has_set) == 0ull) break;   // every segment of the wavefront is out of work
+    }
     // ---- read phase: for which of this actor's stages is the next item of each type eligible
     // (dependencies resolved, and for forward items the in-flight rule)
     unsigned ok_f = 0u, ok_b = 0u, ok_w = 0u;
@@ -212,26 +264,14 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
     if (live) {
       if (!any_pick) { status = 1; live = false; }   // items remain and nothing can move
       else { steps += 1; live = any_left; }
-    }
-  }
-  // ---- rows are END-padded to the stride; words still waiting go out with the padding
-  if (has_row) {
-    int at = len & ~3;
-    if (len & 3) {
-      if (at < stride) *reinterpret_cast<uint2*>(row + at) = make_uint2(buf0, buf1);
-      at += 4;
-    }
-    for (; at < stride; at += 4) *reinterpret_cast<uint2*>(row + at) = make_uint2(0u, 0u);
-    if (d == 0) {
-      out_steps[set] = steps;
-      out_status[set] = (unsigned char)status;
+      fresh = !live;
     }
   }
 }
 
 #define FPSCHED_INSTANTIATE(V, G)                                                                             \
   template __global__ void generate_kernel<V, G>(DevTables, const int32_t*, const int32_t*, long long, int, \
-                                                 uint16_t*, int32_t*, unsigned char*);
+                                                 uint16_t*, int32_t*, unsigned char*, unsigned long long*);
 FPSCHED_INSTANTIATE(1, 1)
 FPSCHED_INSTANTIATE(2, 1)
 FPSCHED_INSTANTIATE(4, 1)

@@ -33,10 +33,12 @@ __global__ void eval_slot_kernel(SlotTables T, const uint16_t* ops, long long n_
 __global__ void reset_counter_kernel(unsigned long long* counter, unsigned long long value);
 
 // V as above; DEG = bound on the in- and out-degree of a stage (1, 2, or 0 = any).  One wavefront per
-// workgroup, 64 / lanes_per_cand parameter sets per wavefront.
+// workgroup, 64 / lanes_per_cand parameter sets per wavefront at a time; next_set: a counter in
+// device memory, preset to the number of segments in the grid, from which segments draw their sets.
 template <int V, int DEG>
 __global__ void generate_kernel(DevTables T, const int32_t* policy, const int32_t* inflight, long long n_sets,
-                                int stride, uint16_t* ops, int32_t* out_steps, unsigned char* out_status);
+                                int stride, uint16_t* ops, int32_t* out_steps, unsigned char* out_status,
+                                unsigned long long* next_set);
 
 __global__ void topk_tile_kernel(const long long* in_makespan, const unsigned char* in_flags,
                                  const Key* in_keys, long long n, int k, Key* out_keys,
