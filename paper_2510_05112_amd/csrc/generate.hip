@@ -14,8 +14,8 @@
 // pool and the reorder queues of Section 5.1 reduce to one counter per (type, stage): the number
 // of micro-batches scheduled so far.  The next item of (type, stage) is in its reorder queue iff
 // every counter it depends on is ahead of its own.  The counters of a parameter set live in LDS;
-// a lane reads those of its stages' neighbours in the read phase and bumps at most one of its
-// own in the write phase.
+// a lane reads its own and those of its stages' neighbours in the read phase and bumps at most one
+// of its own in the write phase (the old value is the item's micro-batch).
 //
 // Priorities (Section 5.2; Table of built-in values): computation type traversal priority
 // bwdpass-first / fwdpass-first / interleaved(unit1, unit2); stage traversal priority
@@ -79,10 +79,12 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
   // what depends on the actor only
   const int nch = has_dev ? T.ints[T.off_n_chunks + d] : 0;
   int stage[V];
+  int own_at[V];   // LDS index of this actor's forward counter of chunk c (backward at + S, W at + 2 S)
   int pred_at[V][DEG > 0 ? DEG : 1], succ_at[V][DEG > 0 ? DEG : 1];
 #pragma unroll
   for (int c = 0; c < V; ++c) {
     stage[c] = c < nch ? T.ints[T.off_local_stage + d * kMaxChunks + c] : 0;
+    own_at[c] = base + stage[c];
 #pragma unroll
     for (int k = 0; k < (DEG > 0 ? DEG : 1); ++k) {
       pred_at[c][k] = at_m;
@@ -103,16 +105,13 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
   bool fresh = true;      // the segment wants its next set
   int limit[V];
   int cttp = 0, unit_f = 1, unit_b = 1, f_dir = 0, f_int = 0, b_dir = 0, b_int = 0;
-  // scheduled micro-batches of this actor's own (type, stage): in registers, mirrored to LDS for
-  // the neighbours; a chunk the actor does not have counts as finished
-  int nf[V], nb[V], nw[V];
 #pragma unroll
-  for (int c = 0; c < V; ++c) { limit[c] = 1; nf[c] = nb[c] = nw[c] = m; }
+  for (int c = 0; c < V; ++c) limit[c] = 1;
   int turn_type = kGenF, turn_run = 0, pos_f = 0, pos_b = 0, stepped_f = 0, stepped_b = 0;
   int left = 0;        // items this actor still has to schedule
   bool live = false;   // the set's process is still running
   int steps = 0, status = 0, len = 0;
-  unsigned buf0 = 0u, buf1 = 0u;   // up to four op words waiting for their 8-byte store
+  unsigned buf0 = 0u, buf1 = 0u;   // up to four op words waiting for their 8-byte store (a shift register)
   uint16_t* row = ops;
 
   // Every step but the last of a set schedules at least one of its 3 S m items, and a segment
@@ -131,7 +130,9 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
           // rows are END-padded to the stride; words still waiting go out with the padding
           int at = len & ~3;
           if (len & 3) {
-            if (at < stride) *reinterpret_cast<uint2*>(row + at) = make_uint2(buf0, buf1);
+            // the shift register holds the last (len & 3) words in its upper part
+            const unsigned long long both = (((unsigned long long)buf1 << 32) | buf0) >> (16 * (4 - (len & 3)));
+            if (at < stride) *reinterpret_cast<uint2*>(row + at) = make_uint2((unsigned)both, (unsigned)(both >> 32));
             at += 4;
           }
           for (; at < stride; at += 4) *reinterpret_cast<uint2*>(row + at) = make_uint2(0u, 0u);
@@ -164,8 +165,6 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
 #pragma unroll
         for (int c = 0; c < V; ++c) bad = bad || limit[c] < 1;
         const bool set_bad = (__ballot(bad && has_row) & seg_mask) != 0ull;
-#pragma unroll
-        for (int c = 0; c < V; ++c) nf[c] = nb[c] = nw[c] = (has_row && c < nch && !set_bad) ? 0 : m;
         turn_type = kGenF; turn_run = 0;
         pos_f = f_dir == 0 ? 0 : (nch > 0 ? nch - 1 : 0);
         pos_b = b_dir == 0 ? 0 : (nch > 0 ? nch - 1 : 0);
@@ -178,12 +177,14 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
       }
       if (__ballot(has_set) == 0ull) break;   // every segment of the wavefront is out of work
     }
-    // ---- read phase: for which of this actor's stages is the next item of each type eligible
-    // (dependencies resolved, and for forward items the in-flight rule)
+    // ---- read phase: the counters of this actor's own (type, stage) and of the neighbouring stages;
+    // then for which stages the next item of each type is eligible (dependencies resolved, and for
+    // forward items the in-flight rule).  A chunk the actor does not have is never eligible.
     unsigned ok_f = 0u, ok_b = 0u, ok_w = 0u;
 #pragma unroll
     for (int c = 0; c < V; ++c) {
-      int f_ahead = m, b_ahead = nf[c];
+      const int nf = counts[own_at[c]], nb = counts[own_at[c] + S], nw = counts[own_at[c] + 2 * S];
+      int f_ahead = m, b_ahead = nf;
       if (DEG > 0) {
 #pragma unroll
         for (int k = 0; k < (DEG > 0 ? DEG : 1); ++k) {
@@ -197,65 +198,55 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
         for (int e = pred_off[s]; e < pred_off[s + 1]; ++e) f_ahead = min(f_ahead, counts[base + lds[T.off_pred_stage + e]]);
         for (int e = succ_off[s]; e < succ_off[s + 1]; ++e) b_ahead = min(b_ahead, counts[base + S + lds[T.off_succ_stage + e]]);
       }
-      const unsigned bit = 1u << c;
-      if (f_ahead > nf[c] && nf[c] - nb[c] < limit[c]) ok_f |= bit;
-      if (b_ahead > nb[c]) ok_b |= bit;
-      if (has_w && nb[c] > nw[c]) ok_w |= bit;
+      const bool mine = c < nch;
+      ok_f |= (unsigned)(mine && f_ahead > nf && nf - nb < limit[c]) << c;
+      ok_b |= (unsigned)(mine && b_ahead > nb) << c;
+      ok_w |= (unsigned)(mine && has_w && nb > nw) << c;
     }
     if (!live) { ok_f = 0u; ok_b = 0u; ok_w = 0u; }
-    // ---- the step function: the first instruction type, in priority order, with an eligible item;
-    // then the stage, in traversal order
+    // ---- the step function, without branches: the first instruction type, in priority order, with an
+    // eligible item; then the stage, in traversal order
     const int first = cttp == 0 ? kGenB : (cttp == 1 ? kGenF : turn_type);
     const unsigned ok_first = first == kGenF ? ok_f : ok_b, ok_second = first == kGenF ? ok_b : ok_f;
     const int pick_t = ok_first ? first : (ok_second ? (first ^ 1) : (ok_w ? kGenW : -1));
-    int pick_c = 0;
+    const unsigned ok = ok_first ? ok_first : (ok_second ? ok_second : ok_w);
+    const bool is_f = pick_t == kGenF, is_b = pick_t == kGenB;
+    const int dir = is_f ? f_dir : (is_b ? b_dir : 0);
+    const int interval = is_f ? f_int : (is_b ? b_int : 0);
+    const int p0 = is_f ? pos_f : pos_b;
+    const int stepped0 = is_f ? stepped_f : stepped_b;
+    // the next stage after p0, in the traversal direction and cyclically, that has an eligible item:
+    // lay the mask out twice, shift it so that the stage after p0 is at bit 0, take the lowest bit
+    // (depth-first: the same on the mirrored mask)
+    const unsigned mirrored = __brev(ok) >> (32 - nch);   // (nch = 0: ok is 0 and nothing is picked)
+    const unsigned walk = dir == 0 ? ok : mirrored;
+    const int q0 = dir == 0 ? p0 : nch - 1 - p0;
+    const unsigned twice = walk | (walk << nch);
+    int q1 = q0 + 1 + low_bit(twice >> (q0 + 1));
+    q1 = q1 >= nch ? q1 - nch : q1;
+    const int moved_to = dir == 0 ? q1 : nch - 1 - q1;
+    const bool move = stepped0 == interval || !((ok >> p0) & 1u);
+    const int p1 = move ? moved_to : p0;
+    const int stepped1 = (move ? 0 : stepped0) + 1;
+    const int pick_c = interval > 0 ? p1 : (dir == 0 ? low_bit(ok) : high_bit(ok));
+    if (interval > 0 && is_f) { pos_f = p1; stepped_f = stepped1; }
+    if (interval > 0 && is_b) { pos_b = p1; stepped_b = stepped1; }
     if (pick_t >= 0) {
-      const unsigned ok = pick_t == kGenF ? ok_f : (pick_t == kGenB ? ok_b : ok_w);
-      const int dir = pick_t == kGenF ? f_dir : (pick_t == kGenB ? b_dir : 0);
-      const int interval = pick_t == kGenF ? f_int : (pick_t == kGenB ? b_int : 0);
-      if (interval > 0) {
-        int p = pick_t == kGenF ? pos_f : pos_b;
-        int stepped = pick_t == kGenF ? stepped_f : stepped_b;
-        if (stepped == interval || !((ok >> p) & 1u)) {
-          // move on, in the traversal direction, to the next stage with an eligible item
+      // ---- write phase: the choice becomes visible for the next step; the counter's old value is
+      // the micro-batch of the item
+      int at = own_at[0];
 #pragma unroll
-          for (int k = 0; k < V; ++k) {
-            if (k < nch && !(k > 0 && ((ok >> p) & 1u))) p = dir == 0 ? (p + 1 == nch ? 0 : p + 1) : (p == 0 ? nch - 1 : p - 1);
-          }
-          stepped = 0;
-        }
-        pick_c = p;
-        stepped += 1;
-        if (pick_t == kGenF) { pos_f = p; stepped_f = stepped; } else { pos_b = p; stepped_b = stepped; }
-      } else {
-        pick_c = dir == 0 ? low_bit(ok) : high_bit(ok);
-      }
-      // ---- write phase: the choice becomes visible for the next step
-      int s = stage[0], j = 0;
-#pragma unroll
-      for (int c = 0; c < V; ++c)
-        if (pick_c == c) {
-          s = stage[c];
-          j = pick_t == kGenF ? nf[c] : (pick_t == kGenB ? nb[c] : nw[c]);
-          nf[c] += pick_t == kGenF;
-          nb[c] += pick_t == kGenB;
-          nw[c] += pick_t == kGenW;
-        }
-      counts[base + pick_t * S + s] = j + 1;
+      for (int c = 1; c < V; ++c) at = pick_c == c ? own_at[c] : at;
+      const int j = atomicAdd(&counts[at + pick_t * S], 1);
       left -= 1;
       const unsigned word = ((unsigned)(pick_t + 1) << 13) | ((unsigned)pick_c << 11) | (unsigned)j;
-      const int q = len & 3;
-      if (q == 0) buf0 = word;
-      else if (q == 1) buf0 |= word << 16;
-      else if (q == 2) buf1 = word;
-      else {
-        buf1 |= word << 16;
-        *reinterpret_cast<uint2*>(row + (len - 3)) = make_uint2(buf0, buf1);
-        buf0 = 0u; buf1 = 0u;
-      }
+      // four op words are collected in a 64-bit shift register and stored together
+      buf0 = (buf0 >> 16) | (buf1 << 16);
+      buf1 = (buf1 >> 16) | (word << 16);
+      if ((len & 3) == 3) *reinterpret_cast<uint2*>(row + (len - 3)) = make_uint2(buf0, buf1);
       len += 1;
       if (cttp == 2 && pick_t == turn_type) {
-        if (++turn_run >= (pick_t == kGenF ? unit_f : unit_b)) { turn_type = pick_t == kGenF ? kGenB : kGenF; turn_run = 0; }
+        if (++turn_run >= (is_f ? unit_f : unit_b)) { turn_type = is_f ? kGenB : kGenF; turn_run = 0; }
       }
     }
     __builtin_amdgcn_wave_barrier();
