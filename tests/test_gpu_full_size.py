@@ -52,3 +52,34 @@ def test_full_batch_sampled_against_oracle(index):
     assert np.array_equal(top["idx"].cpu().numpy()[: len(order)], order)
     assert np.array_equal(top["makespan"].cpu().numpy()[: len(order)], ms[order])
     h.close()
+
+
+def test_generator_full_batch_sampled_against_oracle():
+    # the generator at the size and launch configuration of `bench.py --mode generate`
+    spec = workloads.config(4)
+    prob = spec.problem
+    n = spec.n_candidates
+    pol, inf = workloads.policy_sets(prob, n)
+    stride = workloads.generator_stride(prob)
+    h = fp.Problem(prob, stride, device=0)
+    out = h.generate(torch.from_numpy(pol).cuda(), torch.from_numpy(inf).cuda(), stride)
+    torch.cuda.synchronize()
+    steps = out["steps"].cpu().numpy()
+    status = out["status"].cpu().numpy()
+    rng = np.random.default_rng(4)
+    pick = np.sort(np.concatenate([rng.choice(n, 254, replace=False), [0, n - 1]]))
+    ref = oracle.generate(prob, pol[pick], inf[pick], stride, threads=16)
+    sel = torch.from_numpy(pick).cuda()
+    assert np.array_equal(out["ops"][sel].cpu().numpy().view(np.uint16), ref["words"])
+    assert np.array_equal(steps[pick], ref["steps"]) and np.array_equal(status[pick], ref["status"])
+    # properties at full size: every process completes, every actor schedules each of its items once
+    assert not status.any()
+    per_dev = 2 * prob.n_microbatches * 3
+    assert steps.min() >= per_dev and steps.max() <= 3 * prob.n_stages * prob.n_microbatches
+    kinds = (out["ops"].view(torch.int16).to(torch.int32) & 0xffff) >> 13
+    assert bool((kinds != 0).sum(dim=2).eq(per_dev).all())
+    # and the evaluator accepts all of them
+    res = h.evaluate(out["ops"])
+    torch.cuda.synchronize()
+    assert not bool((res["flags"] & 3).any())
+    h.close()

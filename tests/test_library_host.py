@@ -22,7 +22,8 @@ def test_library_loads_and_exports_every_declared_symbol():
     names = set(re.findall(r"\b(fpsched_[a-z_]+)\s*\(", header))
     assert {"fpsched_evaluate", "fpsched_topk", "fpsched_problem_create", "fpsched_problem_destroy",
             "fpsched_workspace_bytes", "fpsched_encode", "fpsched_validate", "fpsched_strerror",
-            "fpsched_version", "fpsched_problem_info"} <= names
+            "fpsched_version", "fpsched_problem_info", "fpsched_generate",
+            "fpsched_problem_select_kernel"} <= names
     for n in names:
         assert hasattr(lib, n), n
     assert fp.version() == 100
@@ -39,6 +40,7 @@ def test_host_only_handle_and_errors():
     lib = fp.load_library()
     rc = lib.fpsched_evaluate(p._h, 0, 1, spec.stride, fp.binding._Results(0, 0, 0, 0), 0, 0, 0)
     assert rc == -5
+    assert lib.fpsched_generate(p._h, 0, 0, 1, 1024, 0, 0, 0, 0, 0, 0) == -5
     p.close()
     # bad descriptions
     bad = chain_problem(4, 8)
