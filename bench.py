@@ -53,16 +53,31 @@ def bench_generate(args, spec, threads) -> int:
                status=torch.empty(n, dtype=torch.uint8, device=dev))
     print(f"[bench] generate cfg{spec.index}: {n} parameter sets, {prob.n_devices} actors, stride {stride} "
           f"({out['ops'].numel() * 2 / 1e9:.2f} GB of schedules)", file=sys.stderr, flush=True)
-    ws = handle.alloc_workspace(n, 0)
-    for _ in range(args.warmup):
+    search = args.mode == "search"
+    k = spec.top_k
+    ws = handle.alloc_workspace(n, k)
+    res = handle.alloc_results(n) if search else None
+    top = dict(idx=torch.empty(k, dtype=torch.int64, device=dev),
+               makespan=torch.empty(k, dtype=torch.int64, device=dev),
+               count=torch.empty(1, dtype=torch.int32, device=dev))
+
+    def step(e=None):
+        if e:
+            e[0].record()
         handle.generate(d_pol, d_inf, stride, out=out, workspace=ws)
+        if e:
+            e[1].record()
+        if search:
+            handle.evaluate(out["ops"], res, ws)
+            handle.topk(res, k, ws, top)
+
+    for _ in range(args.warmup):
+        step()
     torch.cuda.synchronize()
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
     t0 = time.perf_counter()
     for i in range(args.steps):
-        ev[i][0].record()
-        handle.generate(d_pol, d_inf, stride, out=out, workspace=ws)
-        ev[i][1].record()
+        step(ev[i])
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     gen_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
@@ -74,11 +89,13 @@ def bench_generate(args, spec, threads) -> int:
     # written in full, END padding included: the evaluator reads them as they are), steps and status
     alg_bytes = pol.nbytes + inf.nbytes + words.nbytes + 5 * n
     achieved = alg_bytes / (gen_ms * 1e-3) / 1e9
-    res = {
-        "metric": "schedules generated/sec", "value": n / (ms_per_step * 1e-3), "unit": "schedules/s",
+    json_res = {
+        "metric": "schedules generated, evaluated and ranked/sec" if search else "schedules generated/sec",
+        "value": n / (ms_per_step * 1e-3), "unit": "schedules/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
-        "config": {"workload": f"generator on cfg{spec.index}: {prob.name}, {n} seeded parameter sets",
+        "config": {"workload": f"{'search loop' if search else 'generator'} on cfg{spec.index}: {prob.name}, "
+                               f"{n} seeded parameter sets" + (f", top-{k}" if search else ""),
                    "parameter_sets": n, "devices": prob.n_devices, "stages": prob.n_stages,
                    "microbatches": prob.n_microbatches, "ops_per_schedule": n_ops / n, "stride_words": stride},
         "items_scheduled_per_s": n_ops / (ms_per_step * 1e-3),
@@ -92,6 +109,11 @@ def bench_generate(args, spec, threads) -> int:
         "fractions": {"complete": float((out["status"].cpu().numpy() == 0).mean())},
         "host": {"parameter_sets_s": prep_s},
     }
+    if search:
+        fl = res["flags"].cpu().numpy()
+        res_out = {"feasible_under_cap": float((fl == 0).mean()), "over_cap": float((fl == 4).mean()),
+                   "best_makespan": int(top["makespan"][0].item()) if int(top["count"].item()) else None}
+        json_res["search"] = res_out
     if args.check or not args.no_cpu_baseline:
         import oracle  # test infrastructure: parity sample and the reported CPU baseline only
         if args.check:
@@ -99,7 +121,7 @@ def bench_generate(args, spec, threads) -> int:
             pick = np.sort(rng.choice(n, min(args.check, n), replace=False))
             ref = oracle.generate(prob, pol[pick], inf[pick], stride, threads=threads)
             ok = (np.array_equal(words[pick], ref["words"]) and np.array_equal(steps[pick], ref["steps"]))
-            res["parity_sample"] = {"parameter_sets": int(len(pick)), "bit_exact": bool(ok)}
+            json_res["parity_sample"] = {"parameter_sets": int(len(pick)), "bit_exact": bool(ok)}
             if not ok:
                 print("[bench] PARITY FAILURE against the generator oracle on the sample", file=sys.stderr)
         if not args.no_cpu_baseline:
@@ -111,11 +133,11 @@ def bench_generate(args, spec, threads) -> int:
             t0 = time.perf_counter()
             oracle.generate(prob, pol[:nn], inf[:nn], stride, threads=threads)
             tn = time.perf_counter() - t0
-            res["cpu_baseline"] = {
+            json_res["cpu_baseline"] = {
                 "value": nn / tn, "unit": "schedules/s", "cores": threads, "kind": "oracle",
                 "sample": f"first {nn} parameter sets on {threads} host threads; single thread: first {n1}",
                 "single_thread_value": n1 / t1}
-    print(json.dumps(res))
+    print(json.dumps(json_res))
     return 0
 
 
@@ -129,9 +151,10 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=None, help="candidates timed on the CPU oracle")
     ap.add_argument("--check", type=int, default=512, help="sampled candidates compared with the oracle")
-    ap.add_argument("--mode", choices=["evaluate", "generate"], default="evaluate",
+    ap.add_argument("--mode", choices=["evaluate", "generate", "search"], default="evaluate",
                     help="evaluate: the hot path (evaluation + top-k) on a resident batch (default, the "
-                         "headline metric); generate: the schedule generator on seeded parameter sets")
+                         "headline metric); generate: the schedule generator on seeded parameter sets; "
+                         "search: generate + evaluate + top-k per step, schedules never leave HBM")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain elementwise copy of the op batch (a kernel of known HBM "
                          "traffic, used to calibrate rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -154,7 +177,7 @@ def main() -> int:
     spec = workloads.config(args.config, args.n)
     prob = spec.problem
     threads = min(16, os.cpu_count() or 1)
-    if args.mode == "generate":
+    if args.mode in ("generate", "search"):
         return bench_generate(args, spec, threads)
 
     t0 = time.perf_counter()

@@ -26,18 +26,21 @@
 // micro-batch), 4 bits per entry, in lane-private LDS words.  Op words are staged
 // through a lane-private 16-word LDS ring that the whole wavefront tops up with
 // 8-byte global loads every fourth round; the load issued at one top-up is only
-// written to LDS at the next, so its latency is off the critical path.
+// written to LDS at the next, so its latency is off the critical path.  Between two
+// top-ups run four unrolled rounds; only the last of them looks for finished segments.
 //
-// A round is straight-line code: the LDS reads of a round (next op word, op metadata,
-// state word, input slots) depend only on registers and are issued together, so a
-// round costs one LDS round trip.  Everything a round needs to know about an op --
-// duration, latency, expected input tag, state transition, memory deltas, output slot --
-// comes from one 16-byte metadata row addressed by the top five bits of the op word
-// and the device.  Times are kept shifted left by eight bits, the way a slot holds them
-// (finish << 8 | producer stage): adding the row's (latency << 8) - expected tag to a slot
-// value yields the ready time with a low byte that is zero iff the slot carries the expected
-// tag, so one addition serves the dependency test and the start rule.  Whether a candidate completed (every activation consumed) and
-// whether a stuck device sits on a malformed word are decided once, when it ends.
+// A round is straight-line code.  Everything that depends only on the op word -- the LDS
+// addresses of its state word and input slot, its 16-byte metadata row (duration, latency,
+// expected input tag, state transition, memory deltas, output slot; addressed by the top five
+// bits of the word and the device) and the word behind it -- is worked out and fetched when the
+// lane issues the previous op and kept in registers, so a blocked lane repeats no decoding; a
+// round reads the state word and the input slot (one LDS round trip), decides with one byte
+// compare, and on success updates the lane's registers, the state word and the output slot.
+// Times are kept shifted left by eight bits, the way a slot holds them (finish << 8 | producer
+// stage): adding the row's (latency << 8) - expected tag to a slot value yields the ready time
+// with a low byte that is zero iff the slot carries the expected tag, so one addition serves
+// the dependency test and the start rule.  Whether a candidate completed (every activation
+// consumed) and whether a stuck device sits on a malformed word are decided once, when it ends.
 //
 // Start rule (paper Section 5.1 "Data dependency"; estimator sketch after Section 6):
 // start = max(device free, finish of each cross-stage input + latency if the input ran
