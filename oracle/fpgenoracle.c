@@ -57,7 +57,8 @@
  * Pinned by tests (tests/test_genoracle_*.py): exact 1F1B and GPipe orders and
  * their 2(m+p-1) steps, an independent counter-based simulator on random
  * policies, validity of every generated schedule under the evaluation oracle,
- * in-flight limits on every prefix, hand-worked small cases.
+ * in-flight limits on every prefix, steps == unit-time makespan of the
+ * generated order under the evaluation oracle, hand-worked small cases.
  * Parity unpinned: nothing printed in the paper gives a generated schedule
  * item by item (its figures are images), so no pin compares against a value
  * of the paper; the interleaved schedule is only pinned by properties.

@@ -130,6 +130,38 @@ def test_generated_schedules_are_valid_and_respect_the_limits(name):
                     live[s] -= 1
 
 
+def unit_time(problem):
+    """The same problem with every duration 1 and no latency: the scheduler's own clock."""
+    S = problem.n_stages
+    dur = {1: 1, 2: 1, 3: 1, 4: 1, 5: 1, 6: 1, 7: 1}
+    edges = [(int(a), int(b), 0) for a, b in zip(problem.edge_src, problem.edge_dst)]
+    from workloads.problem import make_problem
+    return make_problem(problem.n_devices, S, problem.n_microbatches, problem.has_w,
+                        problem.stage_device, edges, dur)
+
+
+@pytest.mark.parametrize("name", sorted(PROBLEMS))
+def test_steps_equal_the_unit_time_makespan_of_the_generated_order(name):
+    # Two oracles, one fact.  The scheduler is work-conserving: an actor with an eligible item never
+    # idles.  An item is eligible as soon as its dependencies are scheduled (a forward pass held back by
+    # the in-flight rule waits for a backward pass of its own actor, which precedes it in that actor's
+    # list), so the step in which the scheduler placed an item is the earliest start the evaluator
+    # finds for the same per-actor order with unit durations and no latency: steps == makespan.
+    prob = PROBLEMS[name]()
+    unit = unit_time(prob)
+    rng = np.random.default_rng(21)
+    n = 60
+    pol, inf = random_policies(rng, n, prob, rng.random(n) < 0.5)
+    st = stride_for(prob)
+    free = oracle.generate(prob, pol, np.full_like(inf, NO_LIMIT), st)
+    ev = oracle.evaluate(unit, free["words"])
+    assert not ev["flags"].any() and np.array_equal(ev["makespan"], free["steps"])
+    tight = oracle.generate(prob, pol, inf, st)
+    ev = oracle.evaluate(unit, tight["words"])
+    assert not ev["flags"].any() and np.array_equal(ev["makespan"], tight["steps"])
+    assert np.any(tight["steps"] > free["steps"])     # the limits do stretch some schedules
+
+
 def test_hand_worked_interval_traversal():
     # Section 5.2 "Stage Traversal Priority", worked by hand: 2 actors, circular placement of 4 stages
     # (actor 0: stages 0 and 2; actor 1: stages 1 and 3), 2 micro-batches, forward passes first,
