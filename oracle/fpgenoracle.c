@@ -54,14 +54,16 @@
  *     the oldest unfinished micro-batch can always move.  The status is kept
  *     as a guard.)
  *
- * Pinned by tests (tests/test_genoracle_*.py): exact 1F1B and GPipe orders and
- * their 2(m+p-1) steps, an independent counter-based simulator on random
+ * Pinned by tests (tests/test_genoracle.py): exact 1F1B and GPipe orders and
+ * their 2(m+p-1) steps, the interleaved-1F1B length 2vm+2(p-1) for the paper's
+ * interleaved setting, an independent counter-based simulator on random
  * policies, validity of every generated schedule under the evaluation oracle,
  * in-flight limits on every prefix, steps == unit-time makespan of the
  * generated order under the evaluation oracle, hand-worked small cases.
  * Parity unpinned: nothing printed in the paper gives a generated schedule
  * item by item (its figures are images), so no pin compares against a value
- * of the paper; the interleaved schedule is only pinned by properties.
+ * of the paper; the interleaved schedule is pinned by its length and by
+ * properties, not item by item.
  */
 #include <stdint.h>
 #include <stdlib.h>

@@ -48,6 +48,25 @@ def test_bwd_first_with_inflight_p_minus_d_is_1f1b_and_fwd_first_is_gpipe(p, m):
     assert list(ev["makespan"]) == [2 * (m + p - 1)] * 2 and not ev["flags"].any()
 
 
+@pytest.mark.parametrize("p,v,m", [(4, 2, 8), (4, 2, 16), (2, 2, 4), (4, 4, 8), (8, 2, 16), (3, 2, 6), (4, 3, 12)])
+def test_the_papers_interleaved_setting_reaches_the_interleaved_1f1b_length(p, v, m):
+    # The setting the paper gives for its circular-placement example (caption of the figure of the
+    # automated scheduling process, Section 5): cttp = interleaved, forward stage traversal
+    # (breadth-first, p), backward stage traversal (depth-first, p).  With unit forward and backward
+    # times per chunk, interleaved 1F1B over p devices x v chunks (Section 2.1) has the closed-form
+    # length 2 v m + 2 (p - 1): all the work of one device plus the (p - 1)-step ramps of one chunk.
+    prob = chain_problem(p, m, v=v, f=1, b=1, comm=0)
+    st = stride_for(prob)
+    pol = uniform_policy(1, p, oracle.CTTP_INTERLEAVED, fdir=0, fint=p, bdir=1, bint=p)
+    out = oracle.generate(prob, pol, np.full((1, p * v), NO_LIMIT, np.int32), st)
+    assert out["status"][0] == 0 and out["steps"][0] == 2 * v * m + 2 * (p - 1)
+    ev = oracle.evaluate(prob, out["words"])
+    assert ev["flags"][0] == 0 and ev["makespan"][0] == 2 * v * m + 2 * (p - 1)
+    # and it holds fewer activations than running all forward passes first
+    gp = oracle.generate(prob, uniform_policy(1, p, oracle.CTTP_FWD_FIRST), np.full((1, p * v), NO_LIMIT, np.int32), st)
+    assert ev["peak"][0].max() < oracle.evaluate(prob, gp["words"])["peak"][0].max()
+
+
 def random_policies(rng, n, problem, per_actor):
     D, S, m = problem.n_devices, problem.n_stages, problem.n_microbatches
     pol = np.zeros((n, D, 8), np.int32)
