@@ -291,7 +291,7 @@ def main() -> int:
             if not ok:
                 print("[bench] PARITY FAILURE against the oracle on the sample", file=sys.stderr)
         if not args.no_cpu_baseline:
-            n1 = min(C, args.cpu_sample or max(64, int(40e6 // max(1, n_ops // C))))
+            n1 = min(C, args.cpu_sample or max(64, int(120e6 // max(1, n_ops // C))))
             t0 = time.perf_counter()
             oracle.evaluate(prob, words[:n1], threads=1)
             t1 = time.perf_counter() - t0
