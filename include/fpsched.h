@@ -138,6 +138,27 @@ int fpsched_topk(const fpsched_problem *p, fpsched_results in, int64_t n_cand, i
                  int64_t *d_idx, int64_t *d_makespan, int32_t *d_count, void *d_workspace,
                  size_t workspace_bytes, void *hip_stream);
 
+/* Richer ranking of evaluated candidates: the k best by a two-part key, ties by index.
+ * The paper ranks by bubble ratio (Section 7.1) and treats the memory footprint as the
+ * second property of a schedule (Section 2); the modes make both usable as sort keys:
+ *   FPSCHED_RANK_MAKESPAN        (makespan)                 -- the same order as fpsched_topk
+ *   FPSCHED_RANK_MAKESPAN_PEAK   (makespan, largest peak[d])
+ *   FPSCHED_RANK_PEAK_MAKESPAN   (largest peak[d], makespan)
+ *   FPSCHED_RANK_IDLE            (sum of idle[d])
+ * Candidates with DEADLOCK or INCOMPLETE never rank; OVER_CAP ones only if include_over_cap
+ * is non-zero (ranking by memory instead of cutting at the cap).  d_key: DEVICE [k], the
+ * key of each winner: primary << 32 | secondary for the two-part modes, the value itself
+ * otherwise; unused slots idx -1, key INT64_MAX.  Workspace: fpsched_rank_workspace_bytes.
+ * Reads every field of `in`.  1 <= k <= 1024.  Asynchronous on hip_stream. */
+#define FPSCHED_RANK_MAKESPAN 0
+#define FPSCHED_RANK_MAKESPAN_PEAK 1
+#define FPSCHED_RANK_PEAK_MAKESPAN 2
+#define FPSCHED_RANK_IDLE 3
+size_t fpsched_rank_workspace_bytes(const fpsched_problem *p, int64_t n_cand, int32_t k);
+int fpsched_rank(const fpsched_problem *p, fpsched_results in, int64_t n_cand, int32_t k,
+                 int32_t mode, int32_t include_over_cap, int64_t *d_idx, int64_t *d_key,
+                 int32_t *d_count, void *d_workspace, size_t workspace_bytes, void *hip_stream);
+
 /* HOST helper: pack n items (kind, stage, micro-batch) of one device's list into
  * words (stage -> device-local chunk).  out_words: HOST [n].  EINVAL if an item
  * names a stage that is not on `device`, a bad kind or micro-batch. */

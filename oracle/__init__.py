@@ -72,6 +72,7 @@ def _load():
         _lib.fporacle_eval_one.restype = ctypes.c_int
         _lib.fporacle_evaluate.restype = ctypes.c_int
         _lib.fporacle_topk.restype = ctypes.c_int
+        _lib.fporacle_rank.restype = ctypes.c_int
     return _lib
 
 
@@ -186,6 +187,31 @@ def topk(makespan, flags, k: int):
                       ctypes.c_int64(ms.size), ctypes.c_int32(k), ctypes.c_void_p(idx.ctypes.data),
                       ctypes.c_void_p(oms.ctypes.data), ctypes.c_void_p(cnt.ctypes.data))
     return idx, oms, int(cnt[0])
+
+
+RANK_MODES = {"makespan": 0, "makespan_peak": 1, "peak_makespan": 2, "idle": 3}
+
+
+def rank(results, k: int, mode: str = "makespan_peak", include_over_cap: bool = False):
+    """k best candidates of evaluated ``results`` (dict as returned by ``evaluate``) by a two-part
+    key.  Returns (idx[k], k1[k], k2[k], count)."""
+    lib = _load()
+    ms = np.ascontiguousarray(results["makespan"], dtype=np.int64)
+    idle = np.ascontiguousarray(results["idle"], dtype=np.int64)
+    peak = np.ascontiguousarray(results["peak"], dtype=np.int32)
+    fl = np.ascontiguousarray(results["flags"], dtype=np.uint8)
+    n, D = idle.shape if idle.ndim == 2 else (0, 1)
+    idx, k1, k2 = np.empty(k, np.int64), np.empty(k, np.int64), np.empty(k, np.int64)
+    cnt = np.zeros(1, np.int32)
+    rc = lib.fporacle_rank(ctypes.c_void_p(ms.ctypes.data), ctypes.c_void_p(idle.ctypes.data),
+                           ctypes.c_void_p(peak.ctypes.data), ctypes.c_void_p(fl.ctypes.data),
+                           ctypes.c_int64(n), ctypes.c_int32(D), ctypes.c_int32(k),
+                           ctypes.c_int32(RANK_MODES[mode]), ctypes.c_int32(int(include_over_cap)),
+                           ctypes.c_void_p(idx.ctypes.data), ctypes.c_void_p(k1.ctypes.data),
+                           ctypes.c_void_p(k2.ctypes.data), ctypes.c_void_p(cnt.ctypes.data))
+    if rc:
+        raise ValueError("fporacle_rank: bad mode")
+    return idx, k1, k2, int(cnt[0])
 
 
 # ---------------------------------------------------------------------------------------------

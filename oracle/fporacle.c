@@ -273,3 +273,46 @@ int fporacle_topk(const int64_t *makespan, const uint8_t *flags, int64_t n_cand,
   free(keys);
   return 0;
 }
+
+/* Ranking by a two-part key (an extension of the paper's ranking by bubble ratio, Section 7.1,
+ * by the memory footprint, Section 2): mode 0 (makespan), 1 (makespan, largest peak), 2 (largest
+ * peak, makespan), 3 (sum of idle).  Failed candidates never rank; over-cap ones only if
+ * include_over_cap.  Ties by candidate index.  out_k1/out_k2: the key parts of the winners
+ * (k2 = 0 where the mode has one part); unused slots idx -1, parts INT64_MAX. */
+typedef struct { int64_t k1, k2, idx; } rank3_key;
+static int rank3_cmp(const void *a, const void *b) {
+  const rank3_key *x = a, *y = b;
+  if (x->k1 != y->k1) return x->k1 < y->k1 ? -1 : 1;
+  if (x->k2 != y->k2) return x->k2 < y->k2 ? -1 : 1;
+  if (x->idx != y->idx) return x->idx < y->idx ? -1 : 1;
+  return 0;
+}
+
+int fporacle_rank(const int64_t *makespan, const int64_t *idle, const int32_t *peak, const uint8_t *flags,
+                  int64_t n_cand, int32_t n_devices, int32_t k, int32_t mode, int32_t include_over_cap,
+                  int64_t *out_idx, int64_t *out_k1, int64_t *out_k2, int32_t *count) {
+  if (mode < 0 || mode > 3) return -1;
+  rank3_key *keys = malloc(sizeof(rank3_key) * (n_cand > 0 ? n_cand : 1));
+  int64_t n = 0;
+  for (int64_t c = 0; c < n_cand; ++c) {
+    if (flags[c] & (FLAG_DEADLOCK | FLAG_INCOMPLETE)) continue;
+    if ((flags[c] & FLAG_OVER_CAP) && !include_over_cap) continue;
+    int64_t max_peak = 0, sum_idle = 0;
+    for (int d = 0; d < n_devices; ++d) {
+      if (peak[c * n_devices + d] > max_peak) max_peak = peak[c * n_devices + d];
+      sum_idle += idle[c * n_devices + d];
+    }
+    keys[n].idx = c;
+    keys[n].k1 = mode == 0 || mode == 1 ? makespan[c] : (mode == 2 ? max_peak : sum_idle);
+    keys[n].k2 = mode == 1 ? max_peak : (mode == 2 ? makespan[c] : 0);
+    ++n;
+  }
+  qsort(keys, n, sizeof(rank3_key), rank3_cmp);
+  for (int32_t i = 0; i < k; ++i) {
+    if (i < n) { out_idx[i] = keys[i].idx; out_k1[i] = keys[i].k1; out_k2[i] = keys[i].k2; }
+    else { out_idx[i] = -1; out_k1[i] = INT64_MAX; out_k2[i] = INT64_MAX; }
+  }
+  *count = (int32_t)(n < k ? n : k);
+  free(keys);
+  return 0;
+}

@@ -69,6 +69,10 @@ def load_library():
         lib.fpsched_evaluate.argtypes = [vp, vp, i64, i32, _Results, vp, ctypes.c_size_t, vp]
         lib.fpsched_topk.restype = ctypes.c_int
         lib.fpsched_topk.argtypes = [vp, _Results, i64, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.fpsched_rank_workspace_bytes.restype = ctypes.c_size_t
+        lib.fpsched_rank_workspace_bytes.argtypes = [vp, i64, i32]
+        lib.fpsched_rank.restype = ctypes.c_int
+        lib.fpsched_rank.argtypes = [vp, _Results, i64, i32, i32, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.fpsched_generate.restype = ctypes.c_int
         lib.fpsched_generate.argtypes = [vp, vp, vp, i64, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.fpsched_encode.restype = ctypes.c_int
@@ -258,4 +262,27 @@ class Problem:
                                              self._stream(stream))
         if rc != 0:
             raise FpschedError(rc, "fpsched_generate")
+        return out
+
+    RANK_MODES = {"makespan": 0, "makespan_peak": 1, "peak_makespan": 2, "idle": 3}
+
+    def rank(self, results, k: int, mode: str = "makespan_peak", include_over_cap: bool = False, stream=None):
+        """k best evaluated candidates by a two-part key (see fpsched_rank).  Returns dict(idx, key,
+        count) of CUDA tensors.  Asynchronous."""
+        import torch
+        if self.device is None:
+            raise FpschedError(-5, "fpsched_rank")
+        C = results["makespan"].numel()
+        dev = torch.device("cuda", self.device)
+        nbytes = int(load_library().fpsched_rank_workspace_bytes(self._h, C, int(k)))
+        workspace = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+        out = dict(idx=torch.empty(k, dtype=torch.int64, device=dev),
+                   key=torch.empty(k, dtype=torch.int64, device=dev),
+                   count=torch.empty(1, dtype=torch.int32, device=dev))
+        rc = load_library().fpsched_rank(self._h, self._res_struct(results), C, int(k), self.RANK_MODES[mode],
+                                         int(bool(include_over_cap)), out["idx"].data_ptr(), out["key"].data_ptr(),
+                                         out["count"].data_ptr(), workspace.data_ptr(), workspace.numel(),
+                                         self._stream(stream))
+        if rc != 0:
+            raise FpschedError(rc, "fpsched_rank")
         return out

@@ -538,6 +538,34 @@ int fpsched_generate(const fpsched_problem* p, const fpsched_actor_policy* d_pol
   return check_hip(hipGetLastError());
 }
 
+// k smallest (key, index) among the entries whose flag byte is 0: tile sort, then a tree of merges
+static int run_topk(const long long* keys, const unsigned char* flags, int64_t n_cand, int32_t k, int64_t* d_idx,
+                    int64_t* d_key, int32_t* d_count, char* key_buffers, hipStream_t st) {
+  int64_t cap_a = 0, cap_b = 0;
+  topk_level_sizes(n_cand, k, &cap_a, &cap_b);
+  Key* buf_a = reinterpret_cast<Key*>(key_buffers);
+  Key* buf_b = buf_a + cap_a;
+  long long* f_idx = reinterpret_cast<long long*>(d_idx);
+  long long* f_ms = reinterpret_cast<long long*>(d_key);
+
+  int64_t n = n_cand;
+  const Key* src = nullptr;  // level 0 reads keys / flags
+  Key* dst = buf_a;
+  for (;;) {
+    const int64_t tiles = std::max<int64_t>(1, (n + kTile - 1) / kTile);
+    const bool last = tiles == 1;
+    hipLaunchKernelGGL(topk_tile_kernel, dim3((unsigned)tiles), dim3(kTopkThreads), 0, st, keys, flags, src,
+                       (long long)n, (int)k, last ? nullptr : dst, last ? f_idx : nullptr, last ? f_ms : nullptr,
+                       last ? d_count : nullptr);
+    if (hipGetLastError() != hipSuccess) return FPSCHED_EHIP;
+    if (last) break;
+    n = tiles * k;
+    src = dst;
+    dst = (dst == buf_a) ? buf_b : buf_a;
+  }
+  return FPSCHED_OK;
+}
+
 int fpsched_topk(const fpsched_problem* p, fpsched_results in, int64_t n_cand, int32_t k,
                  int64_t* d_idx, int64_t* d_makespan, int32_t* d_count, void* d_workspace,
                  size_t workspace_bytes, void* hip_stream) {
@@ -548,31 +576,41 @@ int fpsched_topk(const fpsched_problem* p, fpsched_results in, int64_t n_cand, i
   if (workspace_bytes < fpsched_workspace_bytes(p, n_cand, k)) return FPSCHED_ENOMEM;
   DeviceGuard g(p->device_id);
   if (!g.ok) return FPSCHED_EHIP;
-  hipStream_t st = static_cast<hipStream_t>(hip_stream);
-  int64_t cap_a = 0, cap_b = 0;
-  topk_level_sizes(n_cand, k, &cap_a, &cap_b);
-  Key* buf_a = reinterpret_cast<Key*>(static_cast<char*>(d_workspace) + 256);
-  Key* buf_b = buf_a + cap_a;
-  long long* f_idx = reinterpret_cast<long long*>(d_idx);
-  long long* f_ms = reinterpret_cast<long long*>(d_makespan);
+  return run_topk(reinterpret_cast<const long long*>(in.makespan), in.flags, n_cand, k, d_idx, d_makespan, d_count,
+                  static_cast<char*>(d_workspace) + 256, static_cast<hipStream_t>(hip_stream));
+}
 
-  int64_t n = n_cand;
-  const Key* src = nullptr;  // level 0 reads makespan/flags
-  Key* dst = buf_a;
-  for (;;) {
-    const int64_t tiles = std::max<int64_t>(1, (n + kTile - 1) / kTile);
-    const bool last = tiles == 1;
-    hipLaunchKernelGGL(topk_tile_kernel, dim3((unsigned)tiles), dim3(kTopkThreads), 0, st,
-                       reinterpret_cast<const long long*>(in.makespan), in.flags, src, (long long)n,
-                       (int)k, last ? nullptr : dst, last ? f_idx : nullptr, last ? f_ms : nullptr,
-                       last ? d_count : nullptr);
+size_t fpsched_rank_workspace_bytes(const fpsched_problem* p, int64_t n_cand, int32_t k) {
+  if (!p || n_cand < 0) return 0;
+  const size_t base = (fpsched_workspace_bytes(p, n_cand, k) + 15) & ~(size_t)15;
+  return base + (size_t)n_cand * 8 + (((size_t)n_cand + 15) & ~(size_t)15);
+}
+
+int fpsched_rank(const fpsched_problem* p, fpsched_results in, int64_t n_cand, int32_t k, int32_t mode,
+                 int32_t include_over_cap, int64_t* d_idx, int64_t* d_key, int32_t* d_count, void* d_workspace,
+                 size_t workspace_bytes, void* hip_stream) {
+  if (!p || n_cand < 0 || k < 1 || k > 1024 || !d_idx || !d_key || !d_count) return FPSCHED_EINVAL;
+  if (mode < FPSCHED_RANK_MAKESPAN || mode > FPSCHED_RANK_IDLE) return FPSCHED_EINVAL;
+  if (p->device_id < 0) return FPSCHED_ENODEV;
+  if (n_cand > 0 && (!in.makespan || !in.idle || !in.peak || !in.flags)) return FPSCHED_EINVAL;
+  if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) & 15)) return FPSCHED_EINVAL;
+  if (workspace_bytes < fpsched_rank_workspace_bytes(p, n_cand, k)) return FPSCHED_ENOMEM;
+  DeviceGuard g(p->device_id);
+  if (!g.ok) return FPSCHED_EHIP;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const size_t base = (fpsched_workspace_bytes(p, n_cand, k) + 15) & ~(size_t)15;
+  long long* keys = reinterpret_cast<long long*>(static_cast<char*>(d_workspace) + base);
+  unsigned char* excluded = reinterpret_cast<unsigned char*>(keys + n_cand);
+  if (n_cand > 0) {
+    const int64_t blocks = (n_cand + 255) / 256;
+    if (blocks > 0x7fffffffll) return FPSCHED_EINVAL;
+    hipLaunchKernelGGL(rank_keys_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
+                       reinterpret_cast<const long long*>(in.makespan), reinterpret_cast<const long long*>(in.idle),
+                       in.peak, in.flags, (long long)n_cand, (int)p->D, (int)mode, (int)(include_over_cap != 0), keys,
+                       excluded);
     if (hipGetLastError() != hipSuccess) return FPSCHED_EHIP;
-    if (last) break;
-    n = tiles * k;
-    src = dst;
-    dst = (dst == buf_a) ? buf_b : buf_a;
   }
-  return FPSCHED_OK;
+  return run_topk(keys, excluded, n_cand, k, d_idx, d_key, d_count, static_cast<char*>(d_workspace) + 256, st);
 }
 
 int fpsched_encode(const fpsched_problem* p, const int32_t* ksm, int32_t device, int32_t n,

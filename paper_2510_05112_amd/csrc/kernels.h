@@ -44,4 +44,8 @@ __global__ void topk_tile_kernel(const long long* in_makespan, const unsigned ch
                                  const Key* in_keys, long long n, int k, Key* out_keys,
                                  long long* final_idx, long long* final_makespan, int* final_count);
 
+__global__ void rank_keys_kernel(const long long* makespan, const long long* idle, const int* peak,
+                                 const unsigned char* flags, long long n, int D, int mode, int include_over_cap,
+                                 long long* key_out, unsigned char* excluded_out);
+
 }  // namespace fpsched

@@ -84,4 +84,32 @@ __global__ __launch_bounds__(kTopkThreads) void topk_tile_kernel(
   }
 }
 
+// Ranking keys of evaluated candidates (one thread per candidate): the quantities the tuner can
+// rank by besides the makespan -- the largest peak memory over the devices and the summed bubble
+// time (Section 7.1: bubble ratio; Section 2: memory footprint as the second axis of a schedule).
+// Two-part keys are packed primary << 32 | secondary (both below 2^31), so that the top-k kernel,
+// which orders by (key, index), orders lexicographically.
+__global__ void rank_keys_kernel(const long long* makespan, const long long* idle, const int* peak,
+                                 const unsigned char* flags, long long n, int D, int mode, int include_over_cap,
+                                 long long* key_out, unsigned char* excluded_out) {
+  const long long c = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= n) return;
+  const unsigned fl = flags[c];
+  const bool out = (fl & (kDeadlock | kIncomplete)) != 0 || (!include_over_cap && (fl & kOverCap) != 0);
+  long long key = 0;
+  if (!out) {
+    int max_peak = 0;
+    long long sum_idle = 0;
+    for (int d = 0; d < D; ++d) {
+      max_peak = max(max_peak, peak[c * D + d]);
+      sum_idle += idle[c * D + d];
+    }
+    const long long ms = makespan[c];
+    key = mode == 0 ? ms : (mode == 1 ? ((ms << 32) | (long long)max_peak)
+                                      : (mode == 2 ? (((long long)max_peak << 32) | ms) : sum_idle));
+  }
+  key_out[c] = key;
+  excluded_out[c] = out ? 1 : 0;
+}
+
 }  // namespace fpsched
