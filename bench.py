@@ -28,6 +28,9 @@ VALU_PEAK_WAVE_INSTR_PER_S = 256 * 4 * 2.4e9 / 4
 # scaled by a copy kernel of known size, and its VALU wave-instruction count (SQ_INSTS_VALU):
 # profiles/eval_slot_kernel_cfg4_counters.md.  Other workloads report null.
 MEASURED = {("cfg4", 65536): {"traffic_bytes": 4.514e9, "valu_wave_instructions": 2.088e9}}
+# the same for one generator launch (--mode generate): WRITE_SIZE x 1024 plus the parameter sets read;
+# profiles/generate_kernel_cfg4.md
+MEASURED_GENERATE = {("cfg4", 65536): {"traffic_bytes": 1.234e10, "valu_wave_instructions": 1.206e10}}
 
 
 def bench_generate(args, spec, threads) -> int:
@@ -102,7 +105,8 @@ def bench_generate(args, spec, threads) -> int:
         "generate_kernel_ms": gen_ms,
         "scheduling_steps": {"mean": float(steps.mean()), "max": int(steps.max())},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_GENERATE.get((f"cfg{spec.index}", n), {}).get("traffic_bytes"),
                      "kernel": "fpsched generator kernel (generate_kernel)",
                      "algorithmic_bytes_per_launch": alg_bytes,
                      "note": "step-synchronous process: bound by the latency of a scheduling step, not by HBM"},
