@@ -62,12 +62,16 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
   const int cpw = 64 >> lpc_shift;
   const bool has_w = T.has_w != 0;
   // LDS: [edge lists, only if DEG == 0][sets of the wavefront: counters [3][S]][one word holding m]
+  // [row staging: 16 op words per lane, as 8 dwords laid out [dword][lane]]
   const int n_tab = DEG == 0 ? T.n_table_ints : 0;
   if (DEG == 0)
     for (int i = lane; i < n_tab; i += 64) lds[i] = T.ints[i];
   int32_t* counts = lds + n_tab;
   const int at_m = cpw * 3 * S;   // a counter that is always "done": stands in for a missing neighbour
   if (lane == 0) counts[at_m] = m;
+  // a lane collects 16 op words (32 bytes) of its row before it stores them: HBM is written in
+  // 32-byte pieces, not a quarter of that
+  uint32_t* staging = reinterpret_cast<uint32_t*>(counts + at_m + 1) + lane;   // dword i at + i * 64
   __syncthreads();
 
   const int seg = lane >> lpc_shift;
@@ -111,7 +115,6 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
   int left = 0;        // items this actor still has to schedule
   bool live = false;   // the set's process is still running
   int steps = 0, status = 0, len = 0;
-  unsigned buf0 = 0u, buf1 = 0u;   // up to four op words waiting for their 8-byte store (a shift register)
   uint16_t* row = ops;
 
   // Every step but the last of a set schedules at least one of its 3 S m items, and a segment
@@ -127,15 +130,17 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
       if (fresh) {
         fresh = false;
         if (has_set && has_dev) {
-          // rows are END-padded to the stride; words still waiting go out with the padding
-          int at = len & ~3;
-          if (len & 3) {
-            // the shift register holds the last (len & 3) words in its upper part
-            const unsigned long long both = (((unsigned long long)buf1 << 32) | buf0) >> (16 * (4 - (len & 3)));
-            if (at < stride) *reinterpret_cast<uint2*>(row + at) = make_uint2((unsigned)both, (unsigned)(both >> 32));
-            at += 4;
+          // rows are END-padded to the stride; words still staged go out with the padding
+          int at = len & ~15;
+          if (len & 15) {
+            for (int i = len & 15; i < 16; ++i) reinterpret_cast<uint16_t*>(staging + (i >> 1) * 64)[i & 1] = 0;
+            if (at < stride)
+              *reinterpret_cast<uint4*>(row + at) = make_uint4(staging[0], staging[64], staging[128], staging[192]);
+            if (at + 8 < stride)
+              *reinterpret_cast<uint4*>(row + at + 8) = make_uint4(staging[256], staging[320], staging[384], staging[448]);
+            at += 16;
           }
-          for (; at < stride; at += 4) *reinterpret_cast<uint2*>(row + at) = make_uint2(0u, 0u);
+          for (; at < stride; at += 8) *reinterpret_cast<uint4*>(row + at) = make_uint4(0u, 0u, 0u, 0u);
           if (d == 0) {
             out_steps[set] = steps;
             out_status[set] = (unsigned char)status;
@@ -171,7 +176,7 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
         stepped_f = 0; stepped_b = 0;
         left = (has_row && !set_bad) ? nch * m * (has_w ? 3 : 2) : 0;
         live = (__ballot(left > 0) & seg_mask) != 0ull;
-        steps = 0; status = set_bad ? 4 : 0; len = 0; buf0 = 0u; buf1 = 0u;
+        steps = 0; status = set_bad ? 4 : 0; len = 0;
         row = ops + (size_t)(has_row ? set * D + d : 0) * (size_t)stride;
         fresh = has_set && !live;   // nothing to schedule (a bad set, no stages): written out next time round
       }
@@ -240,10 +245,13 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
       const int j = atomicAdd(&counts[at + pick_t * S], 1);
       left -= 1;
       const unsigned word = ((unsigned)(pick_t + 1) << 13) | ((unsigned)pick_c << 11) | (unsigned)j;
-      // four op words are collected in a 64-bit shift register and stored together
-      buf0 = (buf0 >> 16) | (buf1 << 16);
-      buf1 = (buf1 >> 16) | (word << 16);
-      if ((len & 3) == 3) *reinterpret_cast<uint2*>(row + (len - 3)) = make_uint2(buf0, buf1);
+      // sixteen op words are collected in the lane's staging dwords and stored together
+      reinterpret_cast<uint16_t*>(staging + ((len >> 1) & 7) * 64)[len & 1] = (uint16_t)word;
+      if ((len & 15) == 15) {
+        uint4* dst = reinterpret_cast<uint4*>(row + (len - 15));
+        dst[0] = make_uint4(staging[0], staging[64], staging[128], staging[192]);
+        dst[1] = make_uint4(staging[256], staging[320], staging[384], staging[448]);
+      }
       len += 1;
       if (cttp == 2 && pick_t == turn_type) {
         if (++turn_run >= (is_f ? unit_f : unit_b)) { turn_type = is_f ? kGenB : kGenF; turn_run = 0; }
