@@ -1,0 +1,111 @@
+"""The tuner's grid (paper Section 6) as parameter sets for ``Problem.generate``.
+
+Host-side glue only: it enumerates schedule types -- (stage placement strategy, forward and
+backward stage traversal priority, computation type traversal priority) -- under the rules the
+paper states for its grid search, and hands them to the library, whose kernels generate, time
+and rank the schedules.  No scheduling or timing arithmetic happens here.
+
+Rules taken from Section 6: the parameter values come from the table of built-in values; the
+interval is not set unless the circular placement is applied; the computation type priority is
+not forward-first unless the user asks for it; unit1 = unit2 = 1.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import numpy as np
+
+CTTP_BWD_FIRST, CTTP_FWD_FIRST, CTTP_INTERLEAVED = 0, 1, 2
+BREADTH_FIRST, DEPTH_FIRST = 0, 1
+NO_LIMIT = 2**31 - 1
+_CTTP_NAMES = {CTTP_BWD_FIRST: "bwdpass-first", CTTP_FWD_FIRST: "fwdpass-first", CTTP_INTERLEAVED: "interleaved"}
+_DIR_NAMES = {BREADTH_FIRST: "breadth-first", DEPTH_FIRST: "depth-first"}
+
+
+def placement(strategy: str, n_devices: int, n_stages: int) -> list[int]:
+    """Stage -> device for the built-in placement strategies of a chain of stages (Section 4.1,
+    Section 2.1): one-to-one, circular (stage s on device s mod p), V-shape (the second half of
+    the stages walks the devices back).  The bidirectional strategy shares stages between actors
+    and is not expressible as one stage -> device map."""
+    p, S = n_devices, n_stages
+    if strategy == "one-to-one":
+        if S != p:
+            raise ValueError("one-to-one needs as many stages as devices")
+        return list(range(p))
+    if strategy == "circular":
+        return [s % p for s in range(S)]
+    if strategy == "v-shape":
+        return [(s % p) if (s // p) % 2 == 0 else (p - 1 - s % p) for s in range(S)]
+    raise ValueError(f"unknown placement strategy {strategy!r}")
+
+
+@dataclass
+class ScheduleType:
+    cttp: int
+    f_dir: int
+    f_interval: int
+    b_dir: int
+    b_interval: int
+
+    def label(self) -> str:
+        def stp(d, n):
+            return _DIR_NAMES[d] if not n else f"({_DIR_NAMES[d]}, {n})"
+        return f"cttp={_CTTP_NAMES[self.cttp]} fstp={stp(self.f_dir, self.f_interval)} bstp={stp(self.b_dir, self.b_interval)}"
+
+    def policy_row(self) -> list[int]:
+        return [self.cttp, 1, 1, self.f_dir, self.f_interval, self.b_dir, self.b_interval, 0]
+
+
+def schedule_types(n_devices: int, circular: bool, forward_first: bool = False) -> list[ScheduleType]:
+    """The schedule types of the grid for one placement.  `circular`: the placement puts several
+    stages on an actor in circular order, the only case in which an interval (= the number of
+    devices, the group size of the interleaved schedules) is tried."""
+    cttps = [CTTP_BWD_FIRST, CTTP_INTERLEAVED] + ([CTTP_FWD_FIRST] if forward_first else [])
+    intervals = [0, n_devices] if circular else [0]
+    return [ScheduleType(c, fd, fi, bd, bi)
+            for c in cttps for fd in (BREADTH_FIRST, DEPTH_FIRST) for fi in intervals
+            for bd in (BREADTH_FIRST, DEPTH_FIRST) for bi in intervals]
+
+
+def grid(problem, circular: bool, inflight_options=None, forward_first: bool = False):
+    """Parameter sets of the grid for one problem (= one placement): every schedule type, the same
+    for all actors, times every in-flight option.  inflight_options: list of int32 [S] arrays
+    (default: no limit, and the 1F1B-like limit ceil((p - d) / v) per stage).
+    Returns (labels, policy int32 [n][D][8], inflight int32 [n][S])."""
+    D, S = int(problem.n_devices), int(problem.n_stages)
+    dev = np.asarray(problem.stage_device, np.int64)
+    if inflight_options is None:
+        v = max(1, int(np.bincount(dev, minlength=D).max()))
+        inflight_options = [np.full(S, NO_LIMIT, np.int32), (-(-(D - dev) // v)).astype(np.int32)]
+    types = schedule_types(D, circular, forward_first)
+    labels, pol, inf = [], [], []
+    for t in types:
+        for i, limit in enumerate(inflight_options):
+            labels.append(f"{t.label()} inflight#{i}")
+            pol.append([t.policy_row()] * D)
+            inf.append(np.asarray(limit, np.int32))
+    return labels, np.asarray(pol, np.int32), np.stack(inf).astype(np.int32)
+
+
+def tune(handle, problem, circular: bool, k: int = 8, inflight_options=None, forward_first: bool = False):
+    """Generate, time and rank the grid of one problem on the GPU.  handle: a ``Problem`` created
+    with a stride of at least ``stride_for(problem)``.  Returns the k best feasible schedule types as
+    a list of dicts (label, makespan, index into the grid)."""
+    import torch
+
+    labels, pol, inf = grid(problem, circular, inflight_options, forward_first)
+    stride = stride_for(problem)
+    out = handle.generate(torch.from_numpy(pol).cuda(), torch.from_numpy(inf).cuda(), stride)
+    res = handle.evaluate(out["ops"])
+    top = handle.topk(res, min(k, 1024))
+    torch.cuda.synchronize()
+    n = int(top["count"].item())
+    idx, ms = top["idx"].cpu().numpy()[:n], top["makespan"].cpu().numpy()[:n]
+    return [dict(label=labels[int(i)], makespan=int(t), index=int(i)) for i, t in zip(idx, ms)]
+
+
+def stride_for(problem) -> int:
+    """Row stride (words, multiple of 8) that holds the longest list the generator can emit."""
+    per_dev = int(np.bincount(np.asarray(problem.stage_device), minlength=int(problem.n_devices)).max())
+    longest = per_dev * int(problem.n_microbatches) * (3 if problem.has_w else 2)
+    return max(8, -(-longest // 8) * 8)

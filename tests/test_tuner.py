@@ -1,0 +1,58 @@
+"""The tuner's grid (Section 6): rules of the enumeration (CPU) and the GPU search against the oracles."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2510_05112_amd import tuner
+from workloads.problem import make_problem, F, B, W, FD, R
+
+
+def chain(p, v, m, strategy, has_w=1, seed=0):
+    S = p * v
+    rng = np.random.default_rng(seed)
+    f = rng.integers(8, 13, S)
+    dur = {F: f, FD: f, R: f, B: rng.integers(14, 21, S)}
+    if has_w:
+        dur[W] = rng.integers(6, 11, S)
+    edges = [(s, s + 1, int(rng.integers(1, 4))) for s in range(S - 1)]
+    return make_problem(p, S, m, has_w, tuner.placement(strategy, p, S), edges, dur, mem_cap=3 * m, name=strategy)
+
+
+def test_placements():
+    assert tuner.placement("one-to-one", 4, 4) == [0, 1, 2, 3]
+    assert tuner.placement("circular", 4, 8) == [0, 1, 2, 3, 0, 1, 2, 3]
+    assert tuner.placement("v-shape", 4, 8) == [0, 1, 2, 3, 3, 2, 1, 0]
+    with pytest.raises(ValueError):
+        tuner.placement("one-to-one", 4, 8)
+
+
+def test_grid_follows_the_papers_rules():
+    # Section 6: no interval unless circular; no forward-first unless asked; units 1
+    flat = tuner.schedule_types(4, circular=False)
+    assert len(flat) == 2 * 2 * 2 and all(t.f_interval == 0 and t.b_interval == 0 for t in flat)
+    assert all(t.cttp != tuner.CTTP_FWD_FIRST for t in flat)
+    circ = tuner.schedule_types(4, circular=True, forward_first=True)
+    assert len(circ) == 3 * 2 * 2 * 2 * 2 and {t.f_interval for t in circ} == {0, 4}
+    prob = chain(4, 2, 8, "circular")
+    labels, pol, inf = tuner.grid(prob, circular=True)
+    assert pol.shape == (len(labels), 4, 8) and inf.shape == (len(labels), 8) and len(set(labels)) == len(labels)
+    assert np.all(pol[:, :, 1:3] == 1) and np.all(pol == pol[:, :1])      # units 1, one policy for all actors
+    assert np.all(inf >= 1)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("strategy,p,v", [("circular", 4, 2), ("v-shape", 4, 2), ("one-to-one", 6, 1)])
+def test_gpu_search_over_the_grid_matches_the_oracles(strategy, p, v):
+    import paper_2510_05112_amd as fp
+    prob = chain(p, v, 12, strategy)
+    circular = strategy == "circular"
+    st = tuner.stride_for(prob)
+    h = fp.Problem(prob, st, device=0)
+    best = tuner.tune(h, prob, circular, k=5)
+    labels, pol, inf = tuner.grid(prob, circular)
+    words = oracle.generate(prob, pol, inf, st)["words"]
+    ref = oracle.evaluate(prob, words)
+    idx, ms, cnt = oracle.topk(ref["makespan"], ref["flags"], 5)
+    assert [b["index"] for b in best] == list(idx[:cnt]) and [b["makespan"] for b in best] == list(ms[:cnt])
+    assert cnt > 0 and best[0]["label"] == labels[idx[0]]
+    h.close()
