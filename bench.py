@@ -165,7 +165,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (candidates are independent; sharding them over "
-              "GPUs is described in DESIGN.md but not built). Use --gpus 1.", file=sys.stderr)
+              "GPUs is a design note, not built). Use --gpus 1.", file=sys.stderr)
         return 2
 
     import numpy as np

@@ -16,7 +16,7 @@
  * This file does it item by item with explicit pool / queue flags and linear
  * scans, in the order of the paper's steps.  No counters, no shortcuts.
  *
- * Readings of the paper taken here (each is also listed in the design notes):
+ * Readings of the paper taken here:
  *  G1 instruction types: FwdPass (F), BwdPass (B), and the weight-gradient
  *     computation (W) iff the problem splits the backward pass.
  *  G3 dependencies: F(s,j) after F(p,j) for every DAG predecessor p of s;

@@ -23,7 +23,7 @@
  *   the two stages sit on different devices) and runs for the profiled cost
  *   of its (type, stage).
  *
- * Readings of points the paper leaves open (each is repeated in the design doc):
+ * Readings of points the paper leaves open:
  *   - evaluation is time-based on integer times; all devices are free at 0;
  *   - communication is a pure latency on cross-device DAG edges, the same
  *     value for activations and gradients;
