@@ -251,3 +251,39 @@ def test_call_errors_streams_and_workspace_reuse():
             assert np.array_equal(res[name].cpu().numpy(), ref[name]), (rep, name)
         assert int(top["count"].item()) == cnt and np.array_equal(top["idx"].cpu().numpy(), idx)
     h.close()
+
+
+def test_evaluate_and_topk_replayed_from_a_hip_graph():
+    # the calls enqueue kernels only (the work counter is reset by a kernel, not a memset), so they can
+    # be captured once and replayed on new inputs; every replay is checked against the oracle
+    import torch
+
+    import paper_2510_05112_amd as fp
+    spec = workloads.config(2, 300)
+    prob, k = spec.problem, 9
+    batches = [workloads.generate(spec, n=300, first=300 * i, threads=2) for i in range(3)]
+    h = fp.Problem(prob, spec.stride, device=0)
+    ops = torch.from_numpy(batches[0].view(np.int16)).cuda()
+    res, ws = h.alloc_results(300), h.alloc_workspace(300, k)
+    top = dict(idx=torch.empty(k, dtype=torch.int64, device="cuda"),
+               makespan=torch.empty(k, dtype=torch.int64, device="cuda"),
+               count=torch.empty(1, dtype=torch.int32, device="cuda"))
+    h.evaluate(ops, res, ws)          # eager once (warm-up outside the capture)
+    h.topk(res, k, ws, top)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        h.evaluate(ops, res, ws)
+        h.topk(res, k, ws, top)
+    for words in batches[::-1] + batches:
+        ops.copy_(torch.from_numpy(words.view(np.int16)))
+        res["flags"].fill_(255)       # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        ref = oracle.evaluate(prob, words, threads=2)
+        for name in ("makespan", "idle", "peak", "flags"):
+            assert np.array_equal(res[name].cpu().numpy(), ref[name]), name
+        idx, ms, cnt = oracle.topk(ref["makespan"], ref["flags"], k)
+        assert int(top["count"].item()) == cnt and np.array_equal(top["idx"].cpu().numpy(), idx)
+    h.close()
