@@ -287,3 +287,19 @@ def test_evaluate_and_topk_replayed_from_a_hip_graph():
         idx, ms, cnt = oracle.topk(ref["makespan"], ref["flags"], k)
         assert int(top["count"].item()) == cnt and np.array_equal(top["idx"].cpu().numpy(), idx)
     h.close()
+
+
+def test_largest_stage_counts():
+    # 252 stages (tags up to 251 in the slot kernel) and 256 stages (beyond its 8-bit tags: the
+    # general kernel takes over)
+    for p, v in ((63, 4), (64, 4)):
+        prob = chain_problem(p, 3, v=v, f=2, b=3, w=1, comm=1)
+        rng = np.random.default_rng(p)
+        lists = []
+        for t in range(6):
+            base = random_valid_lists(prob, rng)
+            lists += [base, perturb(base, rng, 2)]
+        words = batch_from_lists(lists)
+        g, _ = gpu_evaluate(prob, words, kernel="slots")
+        assert (g is not None) == (p * v <= 255)
+        check_batch(prob, words, k=3, what=f"S={p * v}")
