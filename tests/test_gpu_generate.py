@@ -65,7 +65,8 @@ def test_benchmark_problems(index, n):
     assert not ref["status"].any()
 
 
-@pytest.mark.parametrize("p,m,v,w", [(3, 5, 1, None), (5, 9, 2, 1), (7, 4, 3, 1), (33, 3, 1, None), (64, 2, 1, 1)])
+@pytest.mark.parametrize("p,m,v,w", [(3, 5, 1, None), (5, 9, 2, 1), (7, 4, 3, 1), (33, 3, 1, None), (64, 2, 1, 1),
+                                      (64, 3, 4, 1)])
 def test_odd_shapes(p, m, v, w):
     prob = chain_problem(p, m, v=v, f=1, b=1, w=w, comm=0)
     rng = np.random.default_rng(p * 100 + m)
