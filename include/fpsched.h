@@ -7,7 +7,9 @@
  * with the least bubble ratio): for every candidate it propagates dependencies
  * to get each op's start and finish time, then reports makespan, per-device
  * idle (bubble) time, per-device peak activation memory and a deadlock flag,
- * and reduces a batch to its k best candidates under the memory cap.
+ * and reduces a batch to its k best candidates under the memory cap.  It also
+ * runs the paper's scheduler itself (Section 5: step function, reorder queues,
+ * in-flight limits) as a generator of candidates: fpsched_generate.
  *
  * All entry points are plain C, take plain pointers (marked HOST or DEVICE) and
  * sizes, return 0 on success or a negative FPSCHED_E* code, and never throw or
