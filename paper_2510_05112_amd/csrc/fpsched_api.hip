@@ -504,8 +504,8 @@ int fpsched_generate(const fpsched_problem* p, const fpsched_actor_policy* d_pol
   const int lpc = p->tables.lanes_per_cand;
   const int cpw = 64 / lpc;
   const int deg = p->max_degree <= 1 ? 1 : (p->max_degree == 2 ? 2 : 0);
-  // tables (if walked), counters, one constant word, 8 staging dwords per lane
-  const int64_t lds_bytes = 4ll * ((deg == 0 ? p->tables.n_table_ints : 0) + (int64_t)cpw * 3 * p->S + 1 + 8 * 64);
+  // tables (if walked), counters, the constant words, 8 staging dwords per lane
+  const int64_t lds_bytes = 4ll * ((deg == 0 ? p->tables.n_table_ints : 0) + (int64_t)cpw * 3 * p->S + 2 * p->S + 1 + 8 * 64);
   if (lds_bytes > p->max_lds) return FPSCHED_EUNSUPPORTED;
   // persistent grid: as many single-wavefront workgroups as stay resident (tuning knob:
   // FPSCHED_GEN_WAVES = wavefronts per compute unit)

@@ -67,11 +67,13 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
   if (DEG == 0)
     for (int i = lane; i < n_tab; i += 64) lds[i] = T.ints[i];
   int32_t* counts = lds + n_tab;
-  const int at_m = cpw * 3 * S;   // a counter that is always "done": stands in for a missing neighbour
-  if (lane == 0) counts[at_m] = m;
+  // counters that are always "done" (value m): at_m stands in for a missing neighbour, and at_m,
+  // at_m + S, at_m + 2 S for the three counters of a chunk the actor does not have
+  const int at_m = cpw * 3 * S;
+  if (lane < 3) counts[at_m + lane * S] = m;
   // a lane collects 16 op words (32 bytes) of its row before it stores them: HBM is written in
   // 32-byte pieces, not a quarter of that
-  uint32_t* staging = reinterpret_cast<uint32_t*>(counts + at_m + 1) + lane;   // dword i at + i * 64
+  uint32_t* staging = reinterpret_cast<uint32_t*>(counts + at_m + 2 * S + 1) + lane;   // dword i at + i * 64
   __syncthreads();
 
   const int seg = lane >> lpc_shift;
@@ -88,7 +90,7 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
 #pragma unroll
   for (int c = 0; c < V; ++c) {
     stage[c] = c < nch ? T.ints[T.off_local_stage + d * kMaxChunks + c] : 0;
-    own_at[c] = base + stage[c];
+    own_at[c] = c < nch ? base + stage[c] : at_m;
 #pragma unroll
     for (int k = 0; k < (DEG > 0 ? DEG : 1); ++k) {
       pred_at[c][k] = at_m;
@@ -203,10 +205,9 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
         for (int e = pred_off[s]; e < pred_off[s + 1]; ++e) f_ahead = min(f_ahead, counts[base + lds[T.off_pred_stage + e]]);
         for (int e = succ_off[s]; e < succ_off[s + 1]; ++e) b_ahead = min(b_ahead, counts[base + S + lds[T.off_succ_stage + e]]);
       }
-      const bool mine = c < nch;
-      ok_f |= (unsigned)(mine && f_ahead > nf && nf - nb < limit[c]) << c;
-      ok_b |= (unsigned)(mine && b_ahead > nb) << c;
-      ok_w |= (unsigned)(mine && has_w && nb > nw) << c;
+      ok_f |= (unsigned)(f_ahead > nf && nf - nb < limit[c]) << c;
+      ok_b |= (unsigned)(b_ahead > nb) << c;
+      ok_w |= (unsigned)(has_w && nb > nw) << c;
     }
     if (!live) { ok_f = 0u; ok_b = 0u; ok_w = 0u; }
     // ---- the step function, without branches: the first instruction type, in priority order, with an
@@ -233,7 +234,8 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
     const bool move = stepped0 == interval || !((ok >> p0) & 1u);
     const int p1 = move ? moved_to : p0;
     const int stepped1 = (move ? 0 : stepped0) + 1;
-    const int pick_c = interval > 0 ? p1 : (dir == 0 ? low_bit(ok) : high_bit(ok));
+    const int first_c = low_bit(ok), last_c = high_bit(ok);
+    const int pick_c = interval > 0 ? p1 : (dir == 0 ? first_c : last_c);
     if (interval > 0 && is_f) { pos_f = p1; stepped_f = stepped1; }
     if (interval > 0 && is_b) { pos_b = p1; stepped_b = stepped1; }
     if (pick_t >= 0) {
@@ -242,7 +244,7 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
       int at = own_at[0];
 #pragma unroll
       for (int c = 1; c < V; ++c) at = pick_c == c ? own_at[c] : at;
-      const int j = atomicAdd(&counts[at + pick_t * S], 1);
+      const int j = atomicAdd(&counts[at + (int)__umul24((unsigned)pick_t, (unsigned)S)], 1);
       left -= 1;
       const unsigned word = ((unsigned)(pick_t + 1) << 13) | ((unsigned)pick_c << 11) | (unsigned)j;
       // sixteen op words are collected in the lane's staging dwords and stored together
