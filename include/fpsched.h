@@ -3,8 +3,8 @@
  *
  * The library scores candidate pipeline-parallel schedules the way the paper's
  * auto-tuner needs them scored (Section 3: the offline tuner picks the most
- * suitable of the enumerated schedules; Section 7.1: it returns the alternatives
- * with the least bubble ratio): for every candidate it propagates dependencies
+ * suitable of the enumerated schedules; Section 7.1: the winners are those whose
+ * bubble ratio is lowest): for every candidate it propagates dependencies
  * to get each op's start and finish time, then reports makespan, per-device
  * idle (bubble) time, per-device peak activation memory and a deadlock flag,
  * and reduces a batch to its k best candidates under the memory cap.  It also
@@ -224,8 +224,8 @@ typedef struct {
  * in the traversal direction, first eligible wins; with an interval n: the actor stays on
  * one stage until it has scheduled n items of the type there (or the stage has no
  * eligible item), then moves on in the direction, cyclically, to the next stage that has
- * one; a type none of whose items is eligible is skipped, and a bubble only comes up
- * when no type has an eligible item.  An F item of
+ * one; a type none of whose items is eligible is skipped, and the actor idles in a step
+ * only when no type has an eligible item.  An F item of
  * stage s is eligible only while (#F - #B scheduled on s) < d_inflight[s] (Section 4.2,
  * the in-flight micro-batch limit; INT32_MAX = none, values < 1 are a bad policy).
  *

@@ -43,8 +43,8 @@
  *     traversal direction (cyclically) to the next stage that has one and
  *     `stepped` restarts; the candidate of the stage at the position is
  *     scheduled.  If no stage has an eligible candidate the next instruction
- *     type is tried: a bubble only comes up when there is no schedulable
- *     alternative at all (Section 5.2, Step 2).
+ *     type is tried: the actor idles in a step only if none of its items
+ *     can be scheduled (Section 5.2, Step 2).
  *  G7 the check function is the in-flight rule: an F item of stage s is
  *     eligible only while (#F scheduled on s) - (#B scheduled on s) is below
  *     the stage's in-flight limit.

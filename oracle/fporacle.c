@@ -8,7 +8,7 @@
  *
  * What is evaluated (paper, Section 3 "Overview", the auto-tuner paragraph:
  * the offline tuner picks the most suitable schedule out of the enumerated
- * ones; Section 7.1: it returns the alternatives with the least bubble ratio;
+ * ones; Section 7.1: the winners are the schedules whose bubble ratio is lowest;
  * the estimator sketch that follows Section 6: a schedule becomes an
  * execution graph of tasks labelled with start time, end time and cost):
  *

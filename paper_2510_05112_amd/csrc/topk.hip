@@ -1,6 +1,6 @@
 // Top-k under the memory cap: the k feasible candidates (flags == 0) with the
-// smallest (makespan, index), ascending (paper Section 7.1: the tuner returns the
-// alternatives with the least bubble ratio; with fixed total work that is the
+// smallest (makespan, index), ascending (paper Section 7.1: the tuner keeps the
+// schedules whose bubble ratio is lowest; with fixed total work that is the
 // least makespan).
 //
 // Tile sort + tree merge, all in LDS: every workgroup loads one tile of

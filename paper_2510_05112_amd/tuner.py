@@ -5,9 +5,9 @@ backward stage traversal priority, computation type traversal priority) -- under
 paper states for its grid search, and hands them to the library, whose kernels generate, time
 and rank the schedules.  No scheduling or timing arithmetic happens here.
 
-Rules taken from Section 6: the parameter values come from the table of built-in values; the
-interval is not set unless the circular placement is applied; the computation type priority is
-not forward-first unless the user asks for it; unit1 = unit2 = 1.
+Rules taken from Section 6: the parameter values come from the table of built-in values; an
+interval is tried only together with the circular placement; forward-first type priority is
+left out unless the user asks for it; unit1 = unit2 = 1.
 """
 from __future__ import annotations
 

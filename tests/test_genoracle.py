@@ -207,7 +207,7 @@ def test_hand_worked_interval_traversal():
 def test_an_interval_never_holds_an_actor_on_a_blocked_stage():
     # actor 0 holds stages 0 and 2; with interval 2 it would stay on stage 0 for two forward passes,
     # but the limit of one in-flight micro-batch forbids the second: the traversal moves on to stage 2
-    # (Section 5.2, Step 2: a bubble only comes up when there is no schedulable alternative), and the
+    # (Section 5.2, Step 2: an actor idles only when none of its items can be scheduled), and the
     # process completes.  With limits >= 1 nothing ever gets stuck (reading G8).
     prob = chain_problem(2, 4, v=2, f=1, b=1, comm=0)
     pol = uniform_policy(1, 2, oracle.CTTP_BWD_FIRST, fdir=0, fint=2)
