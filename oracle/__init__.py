@@ -214,6 +214,38 @@ def rank(results, k: int, mode: str = "makespan_peak", include_over_cap: bool = 
     return idx, k1, k2, int(cnt[0])
 
 
+def pareto(results, kmax: int):
+    """Pareto front of (makespan, largest peak) over the completed candidates of ``results``.
+    Returns (idx[kmax], makespan[kmax], peak[kmax], count), ascending makespan."""
+    lib = _load()
+    ms = np.ascontiguousarray(results["makespan"], dtype=np.int64)
+    peak = np.ascontiguousarray(results["peak"], dtype=np.int32)
+    fl = np.ascontiguousarray(results["flags"], dtype=np.uint8)
+    n, D = peak.shape if peak.ndim == 2 else (0, 1)
+    idx, oms, opk = np.empty(kmax, np.int64), np.empty(kmax, np.int64), np.empty(kmax, np.int32)
+    cnt = np.zeros(1, np.int32)
+    lib.fporacle_pareto(ctypes.c_void_p(ms.ctypes.data), ctypes.c_void_p(peak.ctypes.data),
+                        ctypes.c_void_p(fl.ctypes.data), ctypes.c_int64(n), ctypes.c_int32(D),
+                        ctypes.c_int32(kmax), ctypes.c_void_p(idx.ctypes.data), ctypes.c_void_p(oms.ctypes.data),
+                        ctypes.c_void_p(opk.ctypes.data), ctypes.c_void_p(cnt.ctypes.data))
+    return idx, oms, opk, int(cnt[0])
+
+
+def apply_caps(results, caps):
+    """Flags of ``results`` with OVER_CAP recomputed against ``caps`` ([D] or [n][D])."""
+    lib = _load()
+    peak = np.ascontiguousarray(results["peak"], dtype=np.int32)
+    fl = np.array(results["flags"], dtype=np.uint8, copy=True)
+    caps = np.ascontiguousarray(caps, dtype=np.int32)
+    n, D = peak.shape if peak.ndim == 2 else (0, 1)
+    per = 1 if caps.ndim == 2 else 0
+    assert caps.shape == ((n, D) if per else (D,))
+    lib.fporacle_apply_caps(ctypes.c_void_p(peak.ctypes.data), ctypes.c_void_p(caps.ctypes.data),
+                            ctypes.c_int32(per), ctypes.c_int64(n), ctypes.c_int32(D),
+                            ctypes.c_void_p(fl.ctypes.data))
+    return fl
+
+
 # ---------------------------------------------------------------------------------------------
 # schedule generator oracle (fpgenoracle.c)
 

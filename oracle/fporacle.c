@@ -316,3 +316,68 @@ int fporacle_rank(const int64_t *makespan, const int64_t *idle, const int32_t *p
   free(keys);
   return 0;
 }
+
+/* Pareto front of (makespan, largest peak[d]) over the candidates that completed (neither
+ * DEADLOCK nor INCOMPLETE; the cap plays no part: the front replaces a hard cap by the whole
+ * trade-off between the two properties a schedule has in the paper, bubble ratio (Section 7.1)
+ * and memory footprint (Section 2)).  Written as the definition: candidate c is on the front
+ * iff no other completed candidate is at most as large in both values and smaller in one, and
+ * no completed candidate with a smaller index has the same pair.  Quadratic on purpose.
+ * The front is returned by ascending makespan (hence descending peak), at most kmax entries;
+ * *count = number of entries written; unused slots idx -1, makespan INT64_MAX, peak -1. */
+typedef struct { int64_t ms, pk, idx; } front_pt;
+static int front_cmp(const void *a, const void *b) {
+  const front_pt *x = a, *y = b;
+  if (x->ms != y->ms) return x->ms < y->ms ? -1 : 1;
+  return 0;
+}
+
+int fporacle_pareto(const int64_t *makespan, const int32_t *peak, const uint8_t *flags, int64_t n_cand,
+                    int32_t n_devices, int32_t kmax, int64_t *out_idx, int64_t *out_makespan,
+                    int32_t *out_peak, int32_t *count) {
+  int64_t *mp = malloc(sizeof(int64_t) * (n_cand > 0 ? n_cand : 1));
+  front_pt *front = malloc(sizeof(front_pt) * (n_cand > 0 ? n_cand : 1));
+  for (int64_t c = 0; c < n_cand; ++c) {
+    mp[c] = 0;
+    for (int d = 0; d < n_devices; ++d)
+      if (peak[c * n_devices + d] > mp[c]) mp[c] = peak[c * n_devices + d];
+  }
+  int64_t nf = 0;
+  for (int64_t c = 0; c < n_cand; ++c) {
+    if (flags[c] & (FLAG_DEADLOCK | FLAG_INCOMPLETE)) continue;
+    int on_front = 1;
+    for (int64_t o = 0; o < n_cand && on_front; ++o) {
+      if (o == c || (flags[o] & (FLAG_DEADLOCK | FLAG_INCOMPLETE))) continue;
+      const int no_worse = makespan[o] <= makespan[c] && mp[o] <= mp[c];
+      const int better = makespan[o] < makespan[c] || mp[o] < mp[c];
+      if (no_worse && (better || o < c)) on_front = 0;
+    }
+    if (on_front) { front[nf].ms = makespan[c]; front[nf].pk = mp[c]; front[nf].idx = c; ++nf; }
+  }
+  qsort(front, nf, sizeof(front_pt), front_cmp);   /* makespans on the front are distinct */
+  for (int32_t i = 0; i < kmax; ++i) {
+    if (i < nf) { out_idx[i] = front[i].idx; out_makespan[i] = front[i].ms; out_peak[i] = (int32_t)front[i].pk; }
+    else { out_idx[i] = -1; out_makespan[i] = INT64_MAX; out_peak[i] = -1; }
+  }
+  *count = (int32_t)(nf < kmax ? nf : kmax);
+  free(mp);
+  free(front);
+  return 0;
+}
+
+/* OVER_CAP recomputed from the peaks for other memory caps than the problem's (the same
+ * schedules judged for devices with less or more memory: Section 2, memory footprint against
+ * device capacity).  caps: [n_devices] when per_candidate == 0, else [n_cand][n_devices].
+ * The other flag bits are kept; a failed candidate (DEADLOCK or INCOMPLETE: no peaks) never gets OVER_CAP. */
+int fporacle_apply_caps(const int32_t *peak, const int32_t *caps, int32_t per_candidate, int64_t n_cand,
+                        int32_t n_devices, uint8_t *flags) {
+  for (int64_t c = 0; c < n_cand; ++c) {
+    int over = 0;
+    for (int d = 0; d < n_devices; ++d) {
+      const int32_t cap = per_candidate ? caps[c * n_devices + d] : caps[d];
+      if (peak[c * n_devices + d] > cap) over = 1;
+    }
+    flags[c] = (uint8_t)((flags[c] & ~FLAG_OVER_CAP) | (over && !(flags[c] & (FLAG_DEADLOCK | FLAG_INCOMPLETE)) ? FLAG_OVER_CAP : 0));
+  }
+  return 0;
+}
