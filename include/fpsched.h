@@ -161,6 +161,31 @@ int fpsched_rank(const fpsched_problem *p, fpsched_results in, int64_t n_cand, i
                  int32_t mode, int32_t include_over_cap, int64_t *d_idx, int64_t *d_key,
                  int32_t *d_count, void *d_workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Pareto front of (makespan, largest peak[d]) over the candidates that completed (neither
+ * DEADLOCK nor INCOMPLETE; OVER_CAP is ignored: the front takes the place of a fixed cap).
+ * The paper gives a schedule two properties, bubble ratio (Section 7.1) and memory footprint
+ * (Section 2), and lets the tuner return several alternatives; the front is every candidate
+ * that no other one matches or beats in both values (of candidates with the same pair the
+ * one with the smallest index stands for all).  Output by ascending makespan, hence strictly
+ * descending peak: d_idx, d_makespan (int64), d_peak (int32): DEVICE [kmax]; d_count: DEVICE,
+ * min(kmax, size of the front) -- a count equal to kmax may mean that the tail was cut off;
+ * unused slots idx -1, makespan INT64_MAX, peak -1.  1 <= kmax <= 1024; n_cand <= 2^24,
+ * else FPSCHED_EINVAL.  Workspace: fpsched_pareto_workspace_bytes, 16-byte aligned.  Reads
+ * in.makespan, in.peak, in.flags.  Asynchronous on hip_stream. */
+size_t fpsched_pareto_workspace_bytes(const fpsched_problem *p, int64_t n_cand);
+int fpsched_pareto(const fpsched_problem *p, fpsched_results in, int64_t n_cand, int32_t kmax,
+                   int64_t *d_idx, int64_t *d_makespan, int32_t *d_peak, int32_t *d_count,
+                   void *d_workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Judge evaluated candidates against other memory caps than the problem's, without timing
+ * them again (Section 2: the footprint of a schedule against the memory of the devices it
+ * is to run on): rewrites the OVER_CAP bit of d_flags (DEVICE uint8 [n_cand], in place) from
+ * d_peak (DEVICE int32 [n_cand][D]); the other bits stay, failed candidates never get the
+ * bit.  d_caps: DEVICE int32 [D] (per_candidate == 0) or [n_cand][D] (per_candidate != 0),
+ * in the units of the problem's mem_units.  Asynchronous on hip_stream. */
+int fpsched_apply_caps(const fpsched_problem *p, const int32_t *d_peak, const int32_t *d_caps,
+                       int32_t per_candidate, int64_t n_cand, uint8_t *d_flags, void *hip_stream);
+
 /* HOST helper: pack n items (kind, stage, micro-batch) of one device's list into
  * words (stage -> device-local chunk).  out_words: HOST [n].  EINVAL if an item
  * names a stage that is not on `device`, a bad kind or micro-batch. */

@@ -73,6 +73,12 @@ def load_library():
         lib.fpsched_rank_workspace_bytes.argtypes = [vp, i64, i32]
         lib.fpsched_rank.restype = ctypes.c_int
         lib.fpsched_rank.argtypes = [vp, _Results, i64, i32, i32, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.fpsched_pareto_workspace_bytes.restype = ctypes.c_size_t
+        lib.fpsched_pareto_workspace_bytes.argtypes = [vp, i64]
+        lib.fpsched_pareto.restype = ctypes.c_int
+        lib.fpsched_pareto.argtypes = [vp, _Results, i64, i32, vp, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.fpsched_apply_caps.restype = ctypes.c_int
+        lib.fpsched_apply_caps.argtypes = [vp, vp, vp, i32, i64, vp, vp]
         lib.fpsched_generate.restype = ctypes.c_int
         lib.fpsched_generate.argtypes = [vp, vp, vp, i64, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.fpsched_encode.restype = ctypes.c_int
@@ -286,3 +292,42 @@ class Problem:
         if rc != 0:
             raise FpschedError(rc, "fpsched_rank")
         return out
+
+    def pareto(self, results, kmax: int, stream=None):
+        """Pareto front of (makespan, largest peak) over the completed candidates (see fpsched_pareto).
+        Returns dict(idx, makespan, peak, count) of CUDA tensors.  Asynchronous."""
+        import torch
+        if self.device is None:
+            raise FpschedError(-5, "fpsched_pareto")
+        C = results["makespan"].numel()
+        dev = torch.device("cuda", self.device)
+        nbytes = int(load_library().fpsched_pareto_workspace_bytes(self._h, C))
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
+        out = dict(idx=torch.empty(kmax, dtype=torch.int64, device=dev),
+                   makespan=torch.empty(kmax, dtype=torch.int64, device=dev),
+                   peak=torch.empty(kmax, dtype=torch.int32, device=dev),
+                   count=torch.empty(1, dtype=torch.int32, device=dev))
+        rc = load_library().fpsched_pareto(self._h, self._res_struct(results), C, int(kmax), out["idx"].data_ptr(),
+                                           out["makespan"].data_ptr(), out["peak"].data_ptr(),
+                                           out["count"].data_ptr(), workspace.data_ptr(), workspace.numel(),
+                                           self._stream(stream))
+        if rc != 0:
+            raise FpschedError(rc, "fpsched_pareto")
+        return out
+
+    def apply_caps(self, results, caps, stream=None):
+        """Rewrite the OVER_CAP bit of results["flags"] in place for other caps: an int32 CUDA tensor
+        [D] (one cap per device) or [n][D] (caps per candidate).  Asynchronous."""
+        import torch
+        if self.device is None:
+            raise FpschedError(-5, "fpsched_apply_caps")
+        C = results["flags"].numel()
+        per = caps.dim() == 2
+        if caps.dtype != torch.int32 or not caps.is_cuda or not caps.is_contiguous() or \
+                tuple(caps.shape) != ((C, self.D) if per else (self.D,)):
+            raise ValueError("caps: contiguous int32 CUDA tensor [D] or [n][D]")
+        rc = load_library().fpsched_apply_caps(self._h, results["peak"].data_ptr(), caps.data_ptr(), int(per), C,
+                                               results["flags"].data_ptr(), self._stream(stream))
+        if rc != 0:
+            raise FpschedError(rc, "fpsched_apply_caps")
+        return results

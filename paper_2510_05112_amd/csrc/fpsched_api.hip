@@ -614,6 +614,61 @@ int fpsched_rank(const fpsched_problem* p, fpsched_results in, int64_t n_cand, i
   return run_topk(keys, excluded, n_cand, k, d_idx, d_key, d_count, static_cast<char*>(d_workspace) + 256, st);
 }
 
+static int64_t pareto_tiles(int64_t n_cand) { return (n_cand + kTile - 1) / kTile; }
+
+size_t fpsched_pareto_workspace_bytes(const fpsched_problem* p, int64_t n_cand) {
+  if (!p || n_cand < 0) return 0;
+  const size_t tiles = (size_t)pareto_tiles(n_cand);
+  // [256 reserved][tile fronts: Key, then peak, kTile entries per tile][entries per tile front]
+  return 256 + tiles * kTile * (sizeof(Key) + sizeof(int32_t)) + ((tiles * sizeof(int32_t) + 15) & ~(size_t)15);
+}
+
+int fpsched_pareto(const fpsched_problem* p, fpsched_results in, int64_t n_cand, int32_t kmax, int64_t* d_idx,
+                   int64_t* d_makespan, int32_t* d_peak, int32_t* d_count, void* d_workspace,
+                   size_t workspace_bytes, void* hip_stream) {
+  if (!p || n_cand < 0 || kmax < 1 || kmax > 1024 || !d_idx || !d_makespan || !d_peak || !d_count)
+    return FPSCHED_EINVAL;
+  if (pareto_tiles(n_cand) > kParetoMaxTiles) return FPSCHED_EINVAL;
+  if (p->device_id < 0) return FPSCHED_ENODEV;
+  if (n_cand > 0 && (!in.makespan || !in.peak || !in.flags)) return FPSCHED_EINVAL;
+  if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) & 15)) return FPSCHED_EINVAL;
+  if (workspace_bytes < fpsched_pareto_workspace_bytes(p, n_cand)) return FPSCHED_ENOMEM;
+  DeviceGuard g(p->device_id);
+  if (!g.ok) return FPSCHED_EHIP;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  const int64_t tiles = pareto_tiles(n_cand);
+  Key* front_keys = reinterpret_cast<Key*>(static_cast<char*>(d_workspace) + 256);
+  int* front_peak = reinterpret_cast<int*>(front_keys + tiles * kTile);
+  int* tile_count = front_peak + tiles * kTile;
+  if (tiles > 0) {
+    hipLaunchKernelGGL(pareto_tile_kernel, dim3((unsigned)tiles), dim3(kTopkThreads), 0, st,
+                       reinterpret_cast<const long long*>(in.makespan), in.peak, in.flags, (long long)n_cand,
+                       (int)p->D, front_keys, front_peak, tile_count);
+    if (hipGetLastError() != hipSuccess) return FPSCHED_EHIP;
+  }
+  hipLaunchKernelGGL(pareto_merge_kernel, dim3(1), dim3(kParetoMergeThreads), 0, st, front_keys, front_peak,
+                     tile_count, (int)tiles, (int)kmax, reinterpret_cast<long long*>(d_idx),
+                     reinterpret_cast<long long*>(d_makespan), d_peak, d_count);
+  if (hipGetLastError() != hipSuccess) return FPSCHED_EHIP;
+  return FPSCHED_OK;
+}
+
+int fpsched_apply_caps(const fpsched_problem* p, const int32_t* d_peak, const int32_t* d_caps,
+                       int32_t per_candidate, int64_t n_cand, uint8_t* d_flags, void* hip_stream) {
+  if (!p || n_cand < 0 || !d_caps) return FPSCHED_EINVAL;
+  if (p->device_id < 0) return FPSCHED_ENODEV;
+  if (n_cand == 0) return FPSCHED_OK;
+  if (!d_peak || !d_flags) return FPSCHED_EINVAL;
+  const int64_t blocks = (n_cand + 255) / 256;
+  if (blocks > 0x7fffffffll) return FPSCHED_EINVAL;
+  DeviceGuard g(p->device_id);
+  if (!g.ok) return FPSCHED_EHIP;
+  hipLaunchKernelGGL(apply_caps_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                     d_peak, d_caps, (int)(per_candidate != 0), (long long)n_cand, (int)p->D, d_flags);
+  if (hipGetLastError() != hipSuccess) return FPSCHED_EHIP;
+  return FPSCHED_OK;
+}
+
 int fpsched_encode(const fpsched_problem* p, const int32_t* ksm, int32_t device, int32_t n,
                    uint16_t* out_words) {
   if (!p || n < 0 || device < 0 || device >= p->D || (n > 0 && (!ksm || !out_words))) return FPSCHED_EINVAL;

@@ -48,4 +48,18 @@ __global__ void rank_keys_kernel(const long long* makespan, const long long* idl
                                  const unsigned char* flags, long long n, int D, int mode, int include_over_cap,
                                  long long* key_out, unsigned char* excluded_out);
 
+// Pareto front: at most kParetoMaxTiles tiles of kTile candidates (one cursor per tile in LDS).
+constexpr int kParetoMergeThreads = 1024;
+constexpr int kParetoMaxTiles = 8192;
+
+__global__ void pareto_tile_kernel(const long long* makespan, const int* peak, const unsigned char* flags,
+                                   long long n, int D, Key* front_keys, int* front_peak, int* tile_count);
+
+__global__ void pareto_merge_kernel(const Key* front_keys, const int* front_peak, const int* tile_count, int tiles,
+                                    int kmax, long long* out_idx, long long* out_makespan, int* out_peak,
+                                    int* out_count);
+
+__global__ void apply_caps_kernel(const int* peak, const int* caps, int per_candidate, long long n, int D,
+                                  unsigned char* flags);
+
 }  // namespace fpsched

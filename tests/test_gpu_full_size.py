@@ -51,6 +51,21 @@ def test_full_batch_sampled_against_oracle(index):
     assert int(top["count"].item()) == len(order)
     assert np.array_equal(top["idx"].cpu().numpy()[: len(order)], order)
     assert np.array_equal(top["makespan"].cpu().numpy()[: len(order)], ms[order])
+    # Pareto front of (makespan, largest peak): the staircase of the GPU's own results
+    front = h.pareto(res, 1024)
+    torch.cuda.synchronize()
+    done = np.flatnonzero(good)
+    mp = g["peak"][done].max(1).astype(np.int64)
+    expect, best = [], np.iinfo(np.int64).max
+    for i in np.lexsort((done, mp, ms[done])):
+        if mp[i] < best:
+            best = mp[i]
+            expect.append((done[i], ms[done[i]], mp[i]))
+    cnt = int(front["count"].item())
+    assert cnt == min(1024, len(expect)) and cnt >= 1
+    got = list(zip(front["idx"].cpu().numpy()[:cnt], front["makespan"].cpu().numpy()[:cnt],
+                   front["peak"].cpu().numpy()[:cnt]))
+    assert [tuple(int(x) for x in e) for e in got] == [tuple(int(x) for x in e) for e in expect[:cnt]]
     h.close()
 
 

@@ -23,7 +23,8 @@ def test_library_loads_and_exports_every_declared_symbol():
     assert {"fpsched_evaluate", "fpsched_topk", "fpsched_problem_create", "fpsched_problem_destroy",
             "fpsched_workspace_bytes", "fpsched_encode", "fpsched_validate", "fpsched_strerror",
             "fpsched_version", "fpsched_problem_info", "fpsched_generate",
-            "fpsched_problem_select_kernel", "fpsched_rank", "fpsched_rank_workspace_bytes"} <= names
+            "fpsched_problem_select_kernel", "fpsched_rank", "fpsched_rank_workspace_bytes",
+            "fpsched_pareto", "fpsched_pareto_workspace_bytes", "fpsched_apply_caps"} <= names
     for n in names:
         assert hasattr(lib, n), n
     assert fp.version() == 100

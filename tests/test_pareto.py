@@ -135,3 +135,103 @@ def test_apply_caps_reproduces_the_evaluator_and_moves_with_the_cap():
     assert np.array_equal(fl & 3, res["flags"] & 3)
     # no cap at all
     assert not np.any(oracle.apply_caps(res, np.full(D, 2**31 - 1, np.int32)) & 4)
+
+
+def to_cuda(res):
+    import torch
+    return {k: torch.from_numpy(np.ascontiguousarray(v)).cuda() for k, v in res.items()}
+
+
+def gpu_front(h, res_gpu, kmax):
+    import torch
+    out = h.pareto(res_gpu, kmax)
+    torch.cuda.synchronize()
+    return (out["idx"].cpu().numpy(), out["makespan"].cpu().numpy(), out["peak"].cpu().numpy(),
+            int(out["count"].item()))
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("index,n", [(2, 5000), (5, 3000), (1, 200)])
+def test_gpu_front_of_evaluated_schedules_matches_the_oracle(index, n):
+    import torch
+
+    import paper_2510_05112_amd as fp
+    spec, words, ref = evaluated_batch(index, n)
+    h = fp.Problem(spec.problem, spec.stride, device=0)
+    res = h.evaluate(torch.from_numpy(words.view(np.int16)).cuda())
+    for kmax in (1, 7, 1024):
+        got = gpu_front(h, res, kmax)
+        exp = oracle.pareto(ref, kmax)
+        assert got[3] == exp[3], kmax
+        for g, e in zip(got[:3], exp[:3]):
+            assert np.array_equal(g, e), kmax
+    h.close()
+
+
+@pytest.mark.gpu
+def test_gpu_front_with_ties_long_fronts_and_ragged_tiles():
+    import paper_2510_05112_amd as fp
+    spec = workloads.config(1, 8)
+    h = fp.Problem(spec.problem, spec.stride, device=0)
+    D = int(spec.problem.n_devices)
+    cases = [
+        synthetic_results(3000, D, 1, (10, 60), (1, 8)),            # few values, many equal pairs, two tiles
+        synthetic_results(2048, D, 2, (0, 10**6), (1, 10**6)),      # exactly one tile, wide values
+        synthetic_results(2049, D, 3, (0, 10**12), (1, 2**31 - 1)),  # one candidate in the second tile
+        synthetic_results(4500, D, 4, (5, 6), (3, 4)),              # every pair the same: lowest index wins
+        synthetic_results(1, D, 5, (5, 6), (3, 4), fail=0.0),
+        synthetic_results(700, D, 6, (0, 50), (0, 50), fail=1.0),   # nothing completed
+    ]
+    # a front longer than kmax and longer than a tile: makespan rises while the peak falls
+    n = 5000
+    stair = dict(makespan=np.arange(n, dtype=np.int64) * 3, idle=np.zeros((n, D), np.int64),
+                 peak=np.repeat((n - np.arange(n, dtype=np.int32))[:, None], D, 1), flags=np.zeros(n, np.uint8))
+    # the same staircase in a scrambled order
+    perm = np.random.default_rng(9).permutation(n)
+    shuffled = {k: v[perm] for k, v in stair.items()}
+    for ci, res in enumerate(cases + [stair, shuffled]):
+        gres = to_cuda(res)
+        for kmax in (1, 5, 1024):
+            got = gpu_front(h, gres, kmax)
+            check_front(res, kmax, *got)
+            if res["makespan"].size <= 3000:
+                exp = oracle.pareto(res, kmax)
+                assert got[3] == exp[3] and all(np.array_equal(g, e) for g, e in zip(got[:3], exp[:3])), (ci, kmax)
+    # the empty batch, and argument errors
+    empty = to_cuda({k: v[:0] for k, v in stair.items()})
+    got = gpu_front(h, empty, 4)
+    assert got[3] == 0 and np.all(got[0] == -1) and np.all(got[2] == -1)
+    with pytest.raises(fp.FpschedError):
+        h.pareto(empty, 0)
+    with pytest.raises(fp.FpschedError):
+        h.pareto(empty, 1025)
+    h.close()
+
+
+@pytest.mark.gpu
+def test_gpu_apply_caps_matches_the_oracle():
+    import torch
+
+    import paper_2510_05112_amd as fp
+    spec, words, ref = evaluated_batch(2, 3000)
+    h = fp.Problem(spec.problem, spec.stride, device=0)
+    res = h.evaluate(torch.from_numpy(words.view(np.int16)).cuda())
+    torch.cuda.synchronize()
+    assert np.array_equal(res["flags"].cpu().numpy(), ref["flags"])
+    n, D = ref["peak"].shape
+    cap = np.asarray(spec.problem.mem_cap, np.int32)
+    rng = np.random.default_rng(3)
+    per_cand = rng.integers(0, int(ref["peak"].max()) + 2, (n, D)).astype(np.int32)
+    for caps in (cap - 2, cap + 1, np.zeros(D, np.int32), np.full(D, 2**31 - 1, np.int32), per_cand, cap):
+        h.apply_caps(res, torch.from_numpy(caps).cuda())
+        torch.cuda.synchronize()
+        assert np.array_equal(res["flags"].cpu().numpy(), oracle.apply_caps(ref, caps))
+    # top-k under the new cap is the oracle's top-k under that cap
+    h.apply_caps(res, torch.from_numpy(cap - 2).cuda())
+    top = h.topk(res, 32)
+    torch.cuda.synchronize()
+    e_idx, e_ms, e_cnt = oracle.topk(ref["makespan"], oracle.apply_caps(ref, cap - 2), 32)
+    assert int(top["count"].item()) == e_cnt and np.array_equal(top["idx"].cpu().numpy(), e_idx)
+    with pytest.raises(ValueError):
+        h.apply_caps(res, torch.zeros(D + 1, dtype=torch.int32, device="cuda"))
+    h.close()
