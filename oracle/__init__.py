@@ -23,6 +23,8 @@ _SRC = os.path.join(_HERE, "fporacle.c")
 _LIB = os.path.join(_HERE, "libfporacle.so")
 _GEN_SRC = os.path.join(_HERE, "fpgenoracle.c")
 _GEN_LIB = os.path.join(_HERE, "libfpgenoracle.so")
+_SLIDE_SRC = os.path.join(_HERE, "fpslideoracle.c")
+_SLIDE_LIB = os.path.join(_HERE, "libfpslideoracle.so")
 
 FLAG_DEADLOCK = 1
 FLAG_INCOMPLETE = 2
@@ -42,6 +44,7 @@ def _compile(src: str, lib: str, force: bool) -> str:
 def build(force: bool = False) -> str:
     """Compile the oracle's C files with gcc (plain C, no GPU toolchain)."""
     _compile(_GEN_SRC, _GEN_LIB, force)
+    _compile(_SLIDE_SRC, _SLIDE_LIB, force)
     return _compile(_SRC, _LIB, force)
 
 
@@ -244,6 +247,45 @@ def apply_caps(results, caps):
                             ctypes.c_int32(per), ctypes.c_int64(n), ctypes.c_int32(D),
                             ctypes.c_void_p(fl.ctypes.data))
     return fl
+
+
+# ---------------------------------------------------------------------------------------------
+# weight-gradient sliding oracle (fpslideoracle.c)
+
+_slide_lib = None
+
+
+def wslide(problem, words, stride_out: int, threads: int = 1):
+    """Slide the weight-gradient items of a batch ``words[C][D][stride]`` into idle time.
+    Returns dict(ops uint16[C][D][stride_out], makespan, idle, peak, flags) of the new lists."""
+    global _slide_lib
+    if _slide_lib is None:
+        _slide_lib = ctypes.CDLL(_compile(_SLIDE_SRC, _SLIDE_LIB, False))
+        _slide_lib.fpslide_oracle_batch.restype = ctypes.c_int
+    mp = _Marshalled(problem)   # the same field layout as fpslide_problem
+    w = np.ascontiguousarray(np.asarray(words, dtype=np.uint16))
+    assert w.ndim == 3 and w.shape[1] == mp.D, w.shape
+    C, _, stride = w.shape
+    out = dict(ops=np.zeros((C, mp.D, stride_out), np.uint16), makespan=np.empty(C, np.int64),
+               idle=np.empty((C, mp.D), np.int64), peak=np.empty((C, mp.D), np.int32),
+               flags=np.empty(C, np.uint8))
+
+    def run(lo, hi):
+        if hi <= lo:
+            return 0
+        return _slide_lib.fpslide_oracle_batch(
+            ctypes.byref(mp.c), ctypes.c_void_p(w[lo:hi].ctypes.data), ctypes.c_int64(hi - lo),
+            ctypes.c_int32(stride), ctypes.c_void_p(out["ops"][lo:hi].ctypes.data), ctypes.c_int32(stride_out),
+            ctypes.c_void_p(out["makespan"][lo:hi].ctypes.data), ctypes.c_void_p(out["idle"][lo:hi].ctypes.data),
+            ctypes.c_void_p(out["peak"][lo:hi].ctypes.data), ctypes.c_void_p(out["flags"][lo:hi].ctypes.data))
+
+    threads = max(1, min(int(threads), C if C else 1))
+    bounds = np.linspace(0, C, min(C, threads * 8) + 1).astype(np.int64) if C else np.zeros(1, np.int64)
+    with ThreadPoolExecutor(threads) as ex:
+        rcs = list(ex.map(lambda i: run(int(bounds[i]), int(bounds[i + 1])), range(len(bounds) - 1)))
+    if any(rcs):
+        raise ValueError("fpslideoracle: needs a problem with split backward and at most 4 stages per device")
+    return out
 
 
 # ---------------------------------------------------------------------------------------------
