@@ -161,6 +161,31 @@ int fpsched_rank(const fpsched_problem *p, fpsched_results in, int64_t n_cand, i
                  int32_t mode, int32_t include_over_cap, int64_t *d_idx, int64_t *d_key,
                  int32_t *d_count, void *d_workspace, size_t workspace_bytes, void *hip_stream);
 
+/* Weight-gradient sliding (Section 5.2, "Bubble optimizations": the weight-gradient part of a
+ * backward pass is stashed and run in a later bubble of the same actor, so that the items
+ * other actors wait for run first).  The paper shows the idea on a figure and states no rule
+ * for which bubble takes which stashed item; this call applies the following one to every
+ * candidate of a batch, for problems with split backward (has_w; else FPSCHED_EINVAL):
+ *   - the W words of the input lists are dropped, the other items keep their order;
+ *   - every device walks its list under the start rule of fpsched_evaluate; a B item that
+ *     issues puts its W item at the back of the device's stash (first in, first out);
+ *   - in front of the next item of the list, which starts at time t, the oldest stashed
+ *     item runs at the time the device is free if it ends by t (free + dur[W][stage] <= t),
+ *     then the next oldest, and so on; the item of the list is never delayed;
+ *   - when the list ends, what is still stashed runs back to back.
+ * d_ops_out: DEVICE uint16 [n_cand][D][stride_out_words], 16-byte aligned, stride_out_words
+ * a multiple of 8 and <= the handle's max stride: the new lists (the order in which the
+ * items issued), END-padded.  `out`: the evaluation of the new lists, as fpsched_evaluate
+ * would report it for them.  An item for which a new row has no room left halts its device
+ * like a malformed word (DEADLOCK | INCOMPLETE); rows of failed candidates hold the items
+ * that did issue.  The makespan may grow: an item that moves up can open idle time that the
+ * stashed items do not fit into; evaluate both lists and rank.  Needs the slot tables (at
+ * most two inputs and outputs per stage, see fpsched_problem_info), else FPSCHED_EUNSUPPORTED.
+ * No workspace.  Asynchronous on hip_stream. */
+int fpsched_wslide(const fpsched_problem *p, const uint16_t *d_ops, int64_t n_cand,
+                   int32_t stride_words, uint16_t *d_ops_out, int32_t stride_out_words,
+                   fpsched_results out, void *hip_stream);
+
 /* Pareto front of (makespan, largest peak[d]) over the candidates that completed (neither
  * DEADLOCK nor INCOMPLETE; OVER_CAP is ignored: the front takes the place of a fixed cap).
  * The paper gives a schedule two properties, bubble ratio (Section 7.1) and memory footprint

@@ -33,6 +33,8 @@ struct fpsched_problem {
   int32_t slot_lds_bytes = 0;      // dynamic LDS of one slot-kernel workgroup
   int32_t slot_waves = 0;          // wavefronts per slot-kernel workgroup
   int32_t slot_grid = 0;           // resident workgroups: the persistent grid
+  int32_t slide_waves = 0;         // wavefronts per workgroup of the sliding kernel (0: not available)
+  int32_t slide_lds_bytes = 0;
   SlotTables stab{};
   std::vector<int32_t> slot_ints;
   int32_t* d_slot_ints = nullptr;
@@ -66,6 +68,13 @@ SlotKernel slot_kernel_ptr(int v, bool deg2, bool one_class) {
                   : (v == 2 ? &eval_slot_kernel<2, false, true> : &eval_slot_kernel<4, false, true>);
   return v == 1 ? &eval_slot_kernel<1, false, false>
                 : (v == 2 ? &eval_slot_kernel<2, false, false> : &eval_slot_kernel<4, false, false>);
+}
+
+using SlideKernel = void (*)(SlotTables, const uint16_t*, long long, int, uint16_t*, int, long long*, long long*,
+                             int*, unsigned char*);
+SlideKernel slide_kernel_ptr(int v, bool deg2) {
+  if (deg2) return v == 1 ? &wslide_kernel<1, true> : (v == 2 ? &wslide_kernel<2, true> : &wslide_kernel<4, true>);
+  return v == 1 ? &wslide_kernel<1, false> : (v == 2 ? &wslide_kernel<2, false> : &wslide_kernel<4, false>);
 }
 
 int next_pow2(int x) {
@@ -389,6 +398,21 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
            hipFuncSetAttribute(reinterpret_cast<const void*>(slot_kernel_ptr(p->slot_v, p->slot_deg2, p->stab.n_classes == 1)),
                                hipFuncAttributeMaxDynamicSharedMemorySize, p->slot_lds_bytes) == hipSuccess;
       p->stab.ints = p->d_slot_ints;
+      // the sliding kernel: metadata once per workgroup; per wavefront the state words, the slots of
+      // its candidates and 8 staging dwords per lane
+      if (ok && p->has_w) {
+        const int64_t wave_ints = 64ll * p->stab.state_words + (int64_t)p->stab.cands_per_wave * p->stab.slots_per_cand + 8 * 64;
+        const int64_t room = p->max_lds / 4 - p->stab.n_shared_ints - 64;
+        const int waves = (int)std::min<int64_t>(room > 0 ? room / wave_ints : 0, kSlotMaxWaves);
+        if (waves >= 1) {
+          p->slide_lds_bytes = (int32_t)(4ll * (p->stab.n_shared_ints + waves * wave_ints));
+          if (hipFuncSetAttribute(reinterpret_cast<const void*>(slide_kernel_ptr(p->slot_v, p->slot_deg2)),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, p->slide_lds_bytes) == hipSuccess)
+            p->slide_waves = waves;
+          else
+            (void)hipGetLastError();
+        }
+      }
     }
     if (!ok) {
       (void)hipFree(p->d_ints);
@@ -612,6 +636,30 @@ int fpsched_rank(const fpsched_problem* p, fpsched_results in, int64_t n_cand, i
     if (hipGetLastError() != hipSuccess) return FPSCHED_EHIP;
   }
   return run_topk(keys, excluded, n_cand, k, d_idx, d_key, d_count, static_cast<char*>(d_workspace) + 256, st);
+}
+
+int fpsched_wslide(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_cand, int32_t stride_words,
+                   uint16_t* d_ops_out, int32_t stride_out_words, fpsched_results out, void* hip_stream) {
+  if (!p || n_cand < 0) return FPSCHED_EINVAL;
+  if (p->device_id < 0) return FPSCHED_ENODEV;
+  if (!p->has_w) return FPSCHED_EINVAL;
+  if (!p->slots_ok || p->slide_waves < 1) return FPSCHED_EUNSUPPORTED;
+  if (n_cand == 0) return FPSCHED_OK;
+  if (!d_ops || !d_ops_out || !out.makespan || !out.idle || !out.peak || !out.flags) return FPSCHED_EINVAL;
+  if (stride_words < 8 || (stride_words & 7) || stride_words > p->max_stride) return FPSCHED_EINVAL;
+  if (stride_out_words < 8 || (stride_out_words & 7) || stride_out_words > p->max_stride) return FPSCHED_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(d_ops) & 15) || (reinterpret_cast<uintptr_t>(d_ops_out) & 15)) return FPSCHED_EINVAL;
+  const int64_t per_block = (int64_t)p->stab.cands_per_wave * p->slide_waves;
+  const int64_t blocks = (n_cand + per_block - 1) / per_block;
+  if (blocks > 0x7fffffffll) return FPSCHED_EINVAL;
+  DeviceGuard g(p->device_id);
+  if (!g.ok) return FPSCHED_EHIP;
+  hipLaunchKernelGGL(slide_kernel_ptr(p->slot_v, p->slot_deg2), dim3((unsigned)blocks), dim3(64 * p->slide_waves),
+                     (size_t)p->slide_lds_bytes, static_cast<hipStream_t>(hip_stream), p->stab, d_ops,
+                     (long long)n_cand, (int)stride_words, d_ops_out, (int)stride_out_words,
+                     reinterpret_cast<long long*>(out.makespan), reinterpret_cast<long long*>(out.idle), out.peak,
+                     out.flags);
+  return check_hip(hipGetLastError());
 }
 
 static int64_t pareto_tiles(int64_t n_cand) { return (n_cand + kTile - 1) / kTile; }

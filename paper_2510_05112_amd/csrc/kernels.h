@@ -48,6 +48,13 @@ __global__ void rank_keys_kernel(const long long* makespan, const long long* idl
                                  const unsigned char* flags, long long n, int D, int mode, int include_over_cap,
                                  long long* key_out, unsigned char* excluded_out);
 
+// Weight-gradient sliding on the slot tables; V and DEG2 as for eval_slot_kernel.  Candidates are
+// assigned statically: wavefront w of workgroup b owns candidates (b * waves + w) * cands_per_wave ...
+template <int V, bool DEG2>
+__global__ void wslide_kernel(SlotTables T, const uint16_t* ops, long long n_cand, int stride, uint16_t* ops_out,
+                              int stride_out, long long* out_makespan, long long* out_idle, int* out_peak,
+                              unsigned char* out_flags);
+
 // Pareto front: at most kParetoMaxTiles tiles of kTile candidates (one cursor per tile in LDS).
 constexpr int kParetoMergeThreads = 1024;
 constexpr int kParetoMaxTiles = 8192;

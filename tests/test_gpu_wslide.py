@@ -1,0 +1,115 @@
+"""GPU parity of fpsched_wslide (weight-gradient sliding) against oracle/fpslideoracle.c, through the C ABI."""
+import copy
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2510_05112_amd as fp
+import workloads
+from workloads.problem import B, F, chain_problem, pack_lists
+
+pytestmark = pytest.mark.gpu
+
+NAMES = ("ops", "makespan", "idle", "peak", "flags")
+
+
+def to_gpu(words):
+    return torch.from_numpy(np.ascontiguousarray(words).view(np.int16)).cuda()
+
+
+def run_gpu(h, words, stride_out):
+    out = h.wslide(to_gpu(words), stride_out)
+    torch.cuda.synchronize()
+    got = {k: v.cpu().numpy() for k, v in out.items()}
+    got["ops"] = got["ops"].view(np.uint16)
+    return out, got
+
+
+def assert_same(got, ref, what=""):
+    for name in NAMES:
+        assert np.array_equal(got[name], ref[name]), (what, name)
+
+
+@pytest.mark.parametrize("index,n", [(2, 3001), (3, 700), (5, 2000), (4, 130)])
+def test_matches_the_oracle_on_the_configurations(index, n):
+    spec = workloads.config(index, n)
+    words = workloads.generate(spec, threads=16)
+    print(f"cfg{index}: {n} candidates", flush=True)
+    h = fp.Problem(spec.problem, spec.stride, device=0)
+    out, got = run_gpu(h, words, spec.stride)
+    ref = oracle.wslide(spec.problem, words, spec.stride, threads=16)
+    assert_same(got, ref, f"cfg{index}")
+    assert ((ref["flags"] & 3) == 0).sum() > n // 2
+    # the new lists, evaluated by the evaluation kernel, give the results the pass reported
+    again = h.evaluate(out["ops"])
+    torch.cuda.synchronize()
+    ok = (ref["flags"] & 3) == 0
+    for name in NAMES[1:]:
+        assert np.array_equal(again[name].cpu().numpy()[ok], ref[name][ok]), name
+    h.close()
+
+
+def test_lists_without_w_words_short_rows_and_free_items():
+    spec = workloads.config(2, 1500)
+    prob = spec.problem
+    words = workloads.generate(spec, threads=16)
+    kinds = words >> 13
+    # the same lists with their W words taken out, in a narrower row
+    longest = int(((kinds != 0) & (kinds != 3)).sum(2).max())
+    stride_in = -(-longest // 8) * 8
+    stripped = np.zeros((words.shape[0], words.shape[1], stride_in), np.uint16)
+    for c in range(words.shape[0]):
+        for d in range(words.shape[1]):
+            row = words[c, d]
+            keep = row[((row >> 13) != 0) & ((row >> 13) != 3)]
+            stripped[c, d, :len(keep)] = keep
+    h = fp.Problem(prob, spec.stride, device=0)
+    _, got = run_gpu(h, stripped, spec.stride)
+    assert_same(got, oracle.wslide(prob, stripped, spec.stride, threads=16), "stripped")
+    assert_same(got, oracle.wslide(prob, words, spec.stride, threads=16), "stripped == with W")
+    # new rows too short for some candidates: those devices halt
+    short = spec.stride - 16
+    _, got = run_gpu(h, words, short)
+    ref = oracle.wslide(prob, words, short, threads=16)
+    assert_same(got, ref, "short rows")
+    assert (ref["flags"] == 3).sum() > 0
+    h.close()
+    # weight-gradient items that cost nothing, and ones longer than any idle time
+    for w_cost in (0, 5000):
+        p2 = copy.deepcopy(prob)
+        p2.dur[3] = w_cost
+        h = fp.Problem(p2, spec.stride, device=0)
+        _, got = run_gpu(h, words[:600], spec.stride)
+        assert_same(got, oracle.wslide(p2, words[:600], spec.stride, threads=16), f"W cost {w_cost}")
+        h.close()
+
+
+def test_small_cases_and_errors():
+    prob = chain_problem(2, 2, v=1, f=2, b=2, w=1, comm=1)
+    prob.dur[3] = [1, 3]
+    lists = [[(F, 0, 0), (F, 0, 1), (B, 0, 0), (B, 0, 1)], [(F, 0, 0), (B, 0, 0), (F, 0, 1), (B, 0, 1)]]
+    deadlock = [[(F, 0, 0), (B, 0, 0), (F, 0, 1), (B, 0, 1)], [(F, 0, 1), (B, 0, 1), (F, 0, 0), (B, 0, 0)]]
+    malformed = [[(F, 0, 0), (F, 1, 0)], [(F, 0, 0), (B, 0, 0)]]
+    early_end = [[(F, 0, 0)], [(F, 0, 0)]]
+    words = np.stack([pack_lists(x, stride=8) for x in (lists, deadlock, malformed, early_end)])
+    h = fp.Problem(prob, 8, device=0)
+    _, got = run_gpu(h, words, 8)
+    ref = oracle.wslide(prob, words, 8)
+    assert_same(got, ref, "small")
+    assert list(ref["flags"]) == [0, 1, 3, 2] and ref["makespan"][0] == 17
+    # the empty batch is a no-op
+    out = h.wslide(to_gpu(words[:0]), 8)
+    torch.cuda.synchronize()
+    assert out["makespan"].numel() == 0
+    # a row stride that is not a multiple of 8 words
+    with pytest.raises(fp.FpschedError):
+        h.wslide(to_gpu(words), 12)
+    h.close()
+    # a problem without split backward has no weight-gradient items
+    spec = workloads.config(1, 16)
+    h = fp.Problem(spec.problem, spec.stride, device=0)
+    with pytest.raises(fp.FpschedError):
+        h.wslide(to_gpu(workloads.generate(spec)), spec.stride)
+    h.close()
