@@ -33,6 +33,10 @@ MEASURED = {("cfg4", 65536): {"traffic_bytes": 4.514e9, "valu_wave_instructions"
 MEASURED_GENERATE = {("cfg4", 65536): {"traffic_bytes": 4.81e9, "valu_wave_instructions": 1.231e10}}
 
 
+# the sliding kernel (--mode wslide): profiles/wslide_kernel_cfg4.md
+MEASURED_WSLIDE = {("cfg4", 65536): {"traffic_bytes": 1.595e10, "valu_wave_instructions": 1.2854e10}}
+
+
 def bench_generate(args, spec, threads) -> int:
     """The schedule generator (the paper's scheduler, Section 5) on seeded parameter sets of the
     configuration's problem: one step = one fpsched_generate launch over all sets."""
@@ -145,6 +149,112 @@ def bench_generate(args, spec, threads) -> int:
     return 0
 
 
+def bench_wslide(args, spec, threads) -> int:
+    """The weight-gradient sliding pass (Section 5.2, bubble optimizations) on the configuration's
+    resident batch: one step = one fpsched_wslide launch (new lists + their evaluation), then top-k."""
+    import numpy as np
+    import torch
+
+    import paper_2510_05112_amd as fp
+    import workloads
+
+    dev = torch.device("cuda", 0)
+    prob = spec.problem
+    words = workloads.generate(spec, threads=threads)
+    C, D, stride = words.shape
+    n_ops = workloads.count_ops(words)
+    handle = fp.Problem(prob, stride, device=0)
+    ops = torch.empty((C, D, stride), dtype=torch.int16, device=dev)
+    chunk = max(1, (256 << 20) // (D * stride * 2))
+    for lo in range(0, C, chunk):
+        ops[lo:lo + chunk].copy_(torch.from_numpy(words[lo:lo + chunk].view(np.int16)))
+    k = spec.top_k
+    ws = handle.alloc_workspace(C, k)
+    before = handle.evaluate(ops, workspace=ws)
+    torch.cuda.synchronize()
+    print(f"[bench] wslide cfg{spec.index}: {C} candidates x {D} devices x stride {stride} "
+          f"({words.nbytes / 1e9:.2f} GB in, the same out)", file=sys.stderr, flush=True)
+    if args.copy_probe:
+        probe = torch.empty_like(ops)
+        torch.add(ops, 0, out=probe)   # reads and writes ops.numel() * 2 bytes each
+        torch.cuda.synchronize()
+        print(f"[bench] copy probe: {ops.numel() * 2} bytes read, {ops.numel() * 2} bytes written",
+              file=sys.stderr, flush=True)
+        del probe
+    out = handle.wslide(ops, stride)
+    for _ in range(args.warmup):
+        out = handle.wslide(ops, stride)
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ev[i][0].record()
+        out = handle.wslide(ops, stride)
+        ev[i][1].record()
+        top = handle.topk(out, k, ws)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kernel_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+    ms_per_step = wall * 1e3 / args.steps
+    # algorithmic bytes of one launch: the op words read, the new rows written in full (END padding
+    # included: the evaluator reads them as they are), the per-candidate results
+    alg_bytes = 2 * n_ops + words.nbytes + C * (8 + 8 * D + 4 * D + 1)
+    achieved = alg_bytes / (kernel_ms * 1e-3) / 1e9
+    fl0, fl1 = before["flags"].cpu().numpy(), out["flags"].cpu().numpy()
+    ms0, ms1 = before["makespan"].cpu().numpy(), out["makespan"].cpu().numpy()
+    both = ((fl0 & 3) == 0) & ((fl1 & 3) == 0)
+    json_res = {
+        "metric": "candidate schedules slid and re-evaluated/sec", "value": C / (ms_per_step * 1e-3),
+        "unit": "schedules/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int32", "data": "synthetic",
+        "config": {"workload": f"weight-gradient sliding on cfg{spec.index}: {prob.name}, {C} candidates, top-{k}",
+                   "candidates": C, "devices": D, "stages": prob.n_stages, "microbatches": prob.n_microbatches,
+                   "ops_per_candidate": n_ops / C, "stride_words": stride},
+        "wslide_kernel_ms": kernel_ms,
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_WSLIDE.get((f"cfg{spec.index}", C), {}).get("traffic_bytes"),
+                     "kernel": "fpsched sliding kernel (wslide_kernel)", "algorithmic_bytes_per_launch": alg_bytes,
+                     "note": "round-synchronous like the evaluation kernel, with branches: bound by the latency "
+                             "of a round at 9 wavefronts per compute unit, not by HBM"},
+        "effect": {"mean_makespan_ratio": float((ms1[both] / ms0[both]).mean()) if both.any() else None,
+                   "shorter": float((ms1[both] < ms0[both]).mean()) if both.any() else None,
+                   "longer": float((ms1[both] > ms0[both]).mean()) if both.any() else None,
+                   "feasible_under_cap_before": float((fl0 == 0).mean()),
+                   "feasible_under_cap_after": float((fl1 == 0).mean()),
+                   "best_makespan_before": int(ms0[fl0 == 0].min()) if (fl0 == 0).any() else None,
+                   "best_makespan_after": int(top["makespan"][0].item()) if int(top["count"].item()) else None},
+    }
+    if args.check or not args.no_cpu_baseline:
+        import oracle  # test infrastructure: parity sample and the reported CPU baseline only
+        if args.check:
+            rng = np.random.default_rng(0)
+            pick = np.sort(rng.choice(C, min(args.check, C), replace=False))
+            ref = oracle.wslide(prob, words[pick], stride, threads=threads)
+            sel = torch.from_numpy(pick).to(dev)
+            ok = np.array_equal(out["ops"][sel].cpu().numpy().view(np.uint16), ref["ops"]) and all(
+                np.array_equal(out[n][sel].cpu().numpy(), ref[n]) for n in ("makespan", "idle", "peak", "flags"))
+            json_res["parity_sample"] = {"candidates": int(len(pick)), "bit_exact": bool(ok)}
+            if not ok:
+                print("[bench] PARITY FAILURE against the sliding oracle on the sample", file=sys.stderr)
+        if not args.no_cpu_baseline:
+            n1 = min(C, args.cpu_sample or max(64, int(60e6 // max(1, n_ops // C))))
+            t0 = time.perf_counter()
+            oracle.wslide(prob, words[:n1], stride, threads=1)
+            t1 = time.perf_counter() - t0
+            nn = min(C, n1 * min(threads, 8))
+            t0 = time.perf_counter()
+            oracle.wslide(prob, words[:nn], stride, threads=threads)
+            tn = time.perf_counter() - t0
+            json_res["cpu_baseline"] = {
+                "value": nn / tn, "unit": "schedules/s", "cores": threads, "kind": "oracle",
+                "sample": f"first {nn} candidates of the same batch on {threads} host threads; "
+                          f"single thread: first {n1}", "single_thread_value": n1 / t1}
+    print(json.dumps(json_res))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -155,10 +265,11 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=None, help="candidates timed on the CPU oracle")
     ap.add_argument("--check", type=int, default=512, help="sampled candidates compared with the oracle")
-    ap.add_argument("--mode", choices=["evaluate", "generate", "search"], default="evaluate",
+    ap.add_argument("--mode", choices=["evaluate", "generate", "search", "wslide"], default="evaluate",
                     help="evaluate: the hot path (evaluation + top-k) on a resident batch (default, the "
                          "headline metric); generate: the schedule generator on seeded parameter sets; "
-                         "search: generate + evaluate + top-k per step, schedules never leave HBM")
+                         "search: generate + evaluate + top-k per step, schedules never leave HBM; "
+                         "wslide: the weight-gradient sliding pass + top-k on the resident batch")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain elementwise copy of the op batch (a kernel of known HBM "
                          "traffic, used to calibrate rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -183,6 +294,8 @@ def main() -> int:
     threads = min(16, os.cpu_count() or 1)
     if args.mode in ("generate", "search"):
         return bench_generate(args, spec, threads)
+    if args.mode == "wslide":
+        return bench_wslide(args, spec, threads)
 
     t0 = time.perf_counter()
     words = workloads.generate(spec, threads=threads)

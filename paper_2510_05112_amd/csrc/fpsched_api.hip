@@ -399,9 +399,9 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
                                hipFuncAttributeMaxDynamicSharedMemorySize, p->slot_lds_bytes) == hipSuccess;
       p->stab.ints = p->d_slot_ints;
       // the sliding kernel: metadata once per workgroup; per wavefront the state words, the slots of
-      // its candidates and 8 staging dwords per lane
+      // its candidates, and per lane a 16-word op window and a 16-word stash ring
       if (ok && p->has_w) {
-        const int64_t wave_ints = 64ll * p->stab.state_words + (int64_t)p->stab.cands_per_wave * p->stab.slots_per_cand + 8 * 64;
+        const int64_t wave_ints = 64ll * p->stab.state_words + (int64_t)p->stab.cands_per_wave * p->stab.slots_per_cand + (16 + 16) * 32;
         const int64_t room = p->max_lds / 4 - p->stab.n_shared_ints - 64;
         const int waves = (int)std::min<int64_t>(room > 0 ? room / wave_ints : 0, kSlotMaxWaves);
         if (waves >= 1) {

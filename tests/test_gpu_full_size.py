@@ -98,3 +98,44 @@ def test_generator_full_batch_sampled_against_oracle():
     torch.cuda.synchronize()
     assert not bool((res["flags"] & 3).any())
     h.close()
+
+
+def test_wslide_full_batch_sampled_against_oracle():
+    """The sliding pass on configuration 4's full batch, in the launch configuration bench.py times."""
+    spec = workloads.config(4)
+    prob = spec.problem
+    words = workloads.generate(spec, threads=16)
+    C, D, stride = words.shape
+    print(f"wslide cfg4: {C} candidates", flush=True)
+    h = fp.Problem(prob, stride, device=0)
+    ops = torch.empty((C, D, stride), dtype=torch.int16, device="cuda")
+    step = max(1, (256 << 20) // (D * stride * 2))
+    for lo in range(0, C, step):
+        ops[lo:lo + step].copy_(torch.from_numpy(words[lo:lo + step].view(np.int16)))
+    out = h.wslide(ops, stride)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(4)
+    pick = np.sort(np.concatenate([rng.choice(C, 800, replace=False), [0, C - 1]]))
+    ref = oracle.wslide(prob, words[pick], stride, threads=16)
+    sel = torch.from_numpy(pick).cuda()
+    assert np.array_equal(out["ops"][sel].cpu().numpy().view(np.uint16), ref["ops"])
+    for name in ("makespan", "idle", "peak", "flags"):
+        assert np.array_equal(out[name][sel].cpu().numpy(), ref[name]), name
+    # at full size: the new lists, timed by the evaluation kernel, give the reported results
+    again = h.evaluate(out["ops"])
+    torch.cuda.synchronize()
+    fl = out["flags"].cpu().numpy()
+    ok = torch.from_numpy((fl & 3) == 0).cuda()
+    assert int(ok.sum()) > C // 2
+    for name in ("makespan", "idle", "peak", "flags"):
+        assert torch.equal(again[name][ok], out[name][ok]), name
+    # every new row holds the old row's items other than W in their old order
+    new = out["ops"].cpu().numpy().view(np.uint16)
+    for c in pick[:50]:
+        for d in range(D):
+            a, b = words[c, d], new[c, d]
+            keep_a = a[((a >> 13) != 0) & ((a >> 13) != 3)]
+            keep_b = b[((b >> 13) != 0) & ((b >> 13) != 3)]
+            if (fl[c] & 3) == 0:
+                assert np.array_equal(keep_a, keep_b)
+    h.close()
