@@ -39,6 +39,20 @@ def placement(strategy: str, n_devices: int, n_stages: int) -> list[int]:
     raise ValueError(f"unknown placement strategy {strategy!r}")
 
 
+def bidirectional(n_devices: int):
+    """The bidirectional placement strategy (Section 4.1's built-in strategies; Section 2.1): two
+    replicas of a chain of p stages, one laid down the devices and one up, each taking half of the
+    micro-batches, so that every device holds one early and one late stage.  In the scheduler's
+    terms that is a stage DAG of two separate chains: stages 0..p-1 on devices 0..p-1 and stages
+    p..2p-1 on devices p-1..0; micro-batch j of the problem stands for the j-th micro-batch of
+    either replica.  Returns (stage_device[2p], edges [(src, dst)], replica_stage[2p]: the model
+    stage each scheduler stage is a copy of, for the caller's cost tables)."""
+    p = n_devices
+    stage_device = list(range(p)) + list(range(p - 1, -1, -1))
+    edges = [(s, s + 1) for s in range(p - 1)] + [(p + s, p + s + 1) for s in range(p - 1)]
+    return stage_device, edges, list(range(p)) * 2
+
+
 @dataclass
 class ScheduleType:
     cttp: int
@@ -87,21 +101,29 @@ def grid(problem, circular: bool, inflight_options=None, forward_first: bool = F
     return labels, np.asarray(pol, np.int32), np.stack(inf).astype(np.int32)
 
 
-def tune(handle, problem, circular: bool, k: int = 8, inflight_options=None, forward_first: bool = False):
+def tune(handle, problem, circular: bool, k: int = 8, inflight_options=None, forward_first: bool = False,
+         slide: bool = False):
     """Generate, time and rank the grid of one problem on the GPU.  handle: a ``Problem`` created
-    with a stride of at least ``stride_for(problem)``.  Returns the k best feasible schedule types as
-    a list of dicts (label, makespan, index into the grid)."""
+    with a stride of at least ``stride_for(problem)``.  slide: for problems with split backward,
+    also rank every generated schedule after the weight-gradient sliding pass (Section 5.2, bubble
+    optimizations); such entries have ``slid`` set.  Returns the k best feasible schedules as a list
+    of dicts (label, makespan, index into the grid, slid)."""
     import torch
 
     labels, pol, inf = grid(problem, circular, inflight_options, forward_first)
+    n = len(labels)
     stride = stride_for(problem)
     out = handle.generate(torch.from_numpy(pol).cuda(), torch.from_numpy(inf).cuda(), stride)
     res = handle.evaluate(out["ops"])
+    if slide and problem.has_w:
+        slid = handle.wslide(out["ops"], stride)
+        res = {name: torch.cat([res[name], slid[name]]) for name in ("makespan", "idle", "peak", "flags")}
     top = handle.topk(res, min(k, 1024))
     torch.cuda.synchronize()
-    n = int(top["count"].item())
-    idx, ms = top["idx"].cpu().numpy()[:n], top["makespan"].cpu().numpy()[:n]
-    return [dict(label=labels[int(i)], makespan=int(t), index=int(i)) for i, t in zip(idx, ms)]
+    cnt = int(top["count"].item())
+    idx, ms = top["idx"].cpu().numpy()[:cnt], top["makespan"].cpu().numpy()[:cnt]
+    return [dict(label=labels[int(i) % n] + (" +slide" if i >= n else ""), makespan=int(t), index=int(i) % n,
+                 slid=bool(i >= n)) for i, t in zip(idx, ms)]
 
 
 def stride_for(problem) -> int:

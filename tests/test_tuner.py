@@ -24,6 +24,32 @@ def test_placements():
     assert tuner.placement("v-shape", 4, 8) == [0, 1, 2, 3, 3, 2, 1, 0]
     with pytest.raises(ValueError):
         tuner.placement("one-to-one", 4, 8)
+    dev, edges, copy_of = tuner.bidirectional(4)
+    assert dev == [0, 1, 2, 3, 3, 2, 1, 0] and copy_of == [0, 1, 2, 3, 0, 1, 2, 3]
+    assert edges == [(0, 1), (1, 2), (2, 3), (4, 5), (5, 6), (6, 7)]   # two chains, no edge between them
+
+
+def bidirectional_problem(p, m_per_replica, seed=0):
+    rng = np.random.default_rng(seed)
+    f, b, w = rng.integers(8, 13, p), rng.integers(14, 21, p), rng.integers(6, 11, p)
+    dev, edges, copy_of = tuner.bidirectional(p)
+    dur = {F: f[copy_of], FD: f[copy_of], R: f[copy_of], B: b[copy_of], W: w[copy_of]}
+    return make_problem(p, 2 * p, m_per_replica, 1, dev, [(a, c, 2) for a, c in edges], dur,
+                        mem_cap=4 * m_per_replica, name="bidirectional")
+
+
+def test_bidirectional_schedules_from_the_generator_oracle_are_valid():
+    prob = bidirectional_problem(4, 6)
+    labels, pol, inf = tuner.grid(prob, circular=False)
+    st = tuner.stride_for(prob)
+    gen = oracle.generate(prob, pol, inf, st)
+    assert np.all(gen["status"] == 0)
+    res = oracle.evaluate(prob, gen["words"])
+    assert np.all((res["flags"] & 3) == 0)
+    # both replicas run at once: the best schedule beats one replica doing all 12 micro-batches alone
+    work = int(prob.dur[F][:4].sum() + prob.dur[B][:4].sum() + prob.dur[W][:4].sum())
+    one_after_the_other = 12 * max(int(prob.dur[F][s] + prob.dur[B][s] + prob.dur[W][s]) for s in range(4))
+    assert work < res["makespan"].min() < one_after_the_other + work
 
 
 def test_grid_follows_the_papers_rules():
@@ -38,6 +64,26 @@ def test_grid_follows_the_papers_rules():
     assert pol.shape == (len(labels), 4, 8) and inf.shape == (len(labels), 8) and len(set(labels)) == len(labels)
     assert np.all(pol[:, :, 1:3] == 1) and np.all(pol == pol[:, :1])      # units 1, one policy for all actors
     assert np.all(inf >= 1)
+
+
+@pytest.mark.gpu
+def test_gpu_search_with_sliding_and_bidirectional_placement_matches_the_oracles():
+    import paper_2510_05112_amd as fp
+    for prob, circular in ((chain(4, 2, 12, "circular"), True), (bidirectional_problem(4, 6), False)):
+        st = tuner.stride_for(prob)
+        h = fp.Problem(prob, st, device=0)
+        best = tuner.tune(h, prob, circular, k=7, slide=True)
+        labels, pol, inf = tuner.grid(prob, circular)
+        words = oracle.generate(prob, pol, inf, st)["words"]
+        ref, slid = oracle.evaluate(prob, words), oracle.wslide(prob, words, st)
+        ms = np.concatenate([ref["makespan"], slid["makespan"]])
+        fl = np.concatenate([ref["flags"], slid["flags"]])
+        idx, top_ms, cnt = oracle.topk(ms, fl, 7)
+        n = len(labels)
+        assert cnt > 0 and [b["makespan"] for b in best] == list(top_ms[:cnt])
+        assert [(b["index"], b["slid"]) for b in best] == [(int(i) % n, bool(i >= n)) for i in idx[:cnt]]
+        assert all(b["label"].endswith(" +slide") == b["slid"] for b in best)
+        h.close()
 
 
 @pytest.mark.gpu
