@@ -9,7 +9,10 @@
  * idle (bubble) time, per-device peak activation memory and a deadlock flag,
  * and reduces a batch to its k best candidates under the memory cap.  It also
  * runs the paper's scheduler itself (Section 5: step function, reorder queues,
- * in-flight limits) as a generator of candidates: fpsched_generate.
+ * in-flight limits) as a generator of candidates (fpsched_generate), moves the
+ * weight-gradient items of candidate lists into idle time (fpsched_wslide;
+ * Section 5.2, bubble optimizations), and ranks evaluated candidates by other
+ * keys than the makespan (fpsched_rank, fpsched_pareto, fpsched_apply_caps).
  *
  * All entry points are plain C, take plain pointers (marked HOST or DEVICE) and
  * sizes, return 0 on success or a negative FPSCHED_E* code, and never throw or
