@@ -4,7 +4,8 @@
 // Mapping: a wavefront carries `cands_per_wave` candidate segments, lane = device inside
 // a segment; the wavefronts of a workgroup are independent and only share one LDS copy
 // of the op-metadata table.  The grid is persistent: whenever a segment finishes a
-// candidate it draws the next unevaluated one from a global counter and restarts while
+// candidate it takes the next unevaluated one (from a global counter, through a small pool per
+// wavefront so that short candidates do not pay one atomic each) and restarts while
 // the other segments of the wavefront keep going, so fast and slow candidates (and
 // unevenly loaded SIMDs) balance out.  Each lane walks its device's list
 // with a cursor in registers; a lane whose next op cannot issue yet waits for a later
@@ -108,7 +109,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     SlotTables T, const uint16_t* __restrict__ ops, long long n_cand, int stride,
     long long* __restrict__ out_makespan, long long* __restrict__ out_idle,
     int* __restrict__ out_peak, unsigned char* __restrict__ out_flags,
-    unsigned long long* __restrict__ next_candidate) {
+    unsigned long long* __restrict__ next_candidate, int draw_block) {
   extern __shared__ int32_t lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int m = T.m;
@@ -245,6 +246,11 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   // (which the host presets to the number of segments) at the moment they are needed, so that the
   // last candidates of a batch go to whichever segment is free.
   bool first_draw = true;
+  // later candidates come from the wavefront's pool [pool_next, pool_end), refilled from the global
+  // counter draw_block at a time: one atomic per refill, not one per candidate (a batch of short
+  // candidates is otherwise bound by the rate of atomics on one address; long candidates are
+  // drawn one by one, so that the last ones of a batch go to whichever segment is free)
+  unsigned long long pool_next = 0ull, pool_end = 0ull;
   uint2 prime0 = make_uint2(0, 0), prime1 = make_uint2(0, 0), prime2 = make_uint2(0, 0);
   bool priming = false;      // the segment has requested the head of its rows and waits for the top-up
   const int prime_words = stride < kPrimeChunks * kChunk ? stride : kPrimeChunks * kChunk;
@@ -288,13 +294,32 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       priming = false;
       // (re)start segments on their next candidate: reset their LDS, request the head of their
       // rows; they join in at the next top-up
+      // hand the segments that ask for one (lane 0 of each speaks for it) their next candidate
+      const unsigned long long want = __ballot(fresh && !first_draw && d == 0 && seg < cpw);
+      unsigned long long from_pool = 0ull;
+      if (want != 0ull) {
+        const int n_want = __popcll(want);
+        const int have = (int)(pool_end - pool_next);
+        unsigned long long new_base = 0ull;
+        int amount = 0;
+        if (n_want > have) {
+          amount = max(draw_block, n_want - have);
+          if (lane == 0) new_base = atomicAdd(next_candidate, (unsigned long long)amount);
+          new_base = __shfl(new_base, 0, 64);
+        }
+        const int rank = __popcll(want & ((1ull << lane) - 1ull));   // among the asking segments
+        from_pool = rank < have ? pool_next + (unsigned)rank : new_base + (unsigned)(rank - have);
+        if (n_want > have) {
+          pool_next = new_base + (unsigned)(n_want - have);
+          pool_end = new_base + (unsigned)amount;
+        } else {
+          pool_next += (unsigned)n_want;
+        }
+      }
       if (fresh) {
         fresh = false;
         unsigned long long drawn = ((unsigned long long)blockIdx.x * (blockDim.x >> 6) + wave) * cpw + seg;
-        if (!first_draw) {
-          if (d == 0 && seg < cpw) drawn = atomicAdd(next_candidate, 1ull);
-          drawn = __shfl(drawn, seg << lpc_shift, 64);
-        }
+        if (!first_draw) drawn = __shfl(from_pool, seg << lpc_shift, 64);
         first_draw = false;
         cand = (long long)drawn;
         running = (seg < cpw) && (cand < n_cand);
@@ -449,7 +474,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
 #define FPSCHED_INSTANTIATE(V, G, O)                                                               \
   template __global__ void eval_slot_kernel<V, G, O>(SlotTables, const uint16_t*, long long, int,  \
                                                      long long*, long long*, int*, unsigned char*, \
-                                                     unsigned long long*);
+                                                     unsigned long long*, int);
 FPSCHED_INSTANTIATE(1, false, true)
 FPSCHED_INSTANTIATE(2, false, true)
 FPSCHED_INSTANTIATE(4, false, true)

@@ -58,7 +58,7 @@ struct DeviceGuard {
 };
 
 using SlotKernel = void (*)(SlotTables, const uint16_t*, long long, int, long long*, long long*, int*,
-                            unsigned char*, unsigned long long*);
+                            unsigned char*, unsigned long long*, int);
 SlotKernel slot_kernel_ptr(int v, bool deg2, bool one_class) {
   if (deg2)
     return v == 1 ? &eval_slot_kernel<1, true, false>
@@ -491,13 +491,18 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
     unsigned long long* counter = static_cast<unsigned long long*>(d_workspace);
     const int per_block = p->stab.cands_per_wave * p->slot_waves;
     const int64_t blocks = std::min<int64_t>((n_cand + per_block - 1) / per_block, p->slot_grid);
+    // Candidates per atomic draw.  Atomics on one address complete at some 8e7 per second; a batch of
+    // long candidates stays far below that and is drawn one by one (best balance at the end of the
+    // batch), short rows are drawn several at a time: about one draw per 12 K op words.
+    const int64_t row_words = (int64_t)p->D * stride_words;
+    const int draw_block = (int)std::clamp<int64_t>((12288 + row_words - 1) / row_words, 1, p->stab.cands_per_wave);
     // segment g starts on candidate g; the counter hands out the candidates after those
     hipLaunchKernelGGL(reset_counter_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(hip_stream), counter,
                        (unsigned long long)(blocks * per_block));
     hipLaunchKernelGGL(slot_kernel_ptr(p->slot_v, p->slot_deg2, p->stab.n_classes == 1), dim3((unsigned)blocks), dim3(64 * p->slot_waves),
                        (size_t)p->slot_lds_bytes, static_cast<hipStream_t>(hip_stream), p->stab, d_ops,
                        (long long)n_cand, (int)stride_words, reinterpret_cast<long long*>(out.makespan),
-                       reinterpret_cast<long long*>(out.idle), out.peak, out.flags, counter);
+                       reinterpret_cast<long long*>(out.idle), out.peak, out.flags, counter, draw_block);
     return check_hip(hipGetLastError());
   }
   const int cpw = p->tables.cands_per_wave;

@@ -24,11 +24,11 @@ constexpr int kSlotMaxThreads = 64 * kSlotMaxWaves;
 // V = compile-time bound on the stages (chunks) per device: 1, 2 or 4.  DEG2 = some stage
 // has two inputs or two outputs in the stage DAG.  ONE_CLASS = the DAG is a single chain.
 // next_candidate: a counter in device memory, preset to the number of segments in the grid, from
-// which segments draw their work.
+// which wavefronts draw their work, draw_block candidates per atomic (1 <= draw_block <= 64).
 template <int V, bool DEG2, bool ONE_CLASS>
 __global__ void eval_slot_kernel(SlotTables T, const uint16_t* ops, long long n_cand, int stride,
                                  long long* out_makespan, long long* out_idle, int* out_peak,
-                                 unsigned char* out_flags, unsigned long long* next_candidate);
+                                 unsigned char* out_flags, unsigned long long* next_candidate, int draw_block);
 
 __global__ void reset_counter_kernel(unsigned long long* counter, unsigned long long value);
 
