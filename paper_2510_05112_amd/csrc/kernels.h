@@ -12,7 +12,7 @@ struct Key {
   long long idx;
 };
 constexpr int kTile = 2048;
-constexpr int kTopkThreads = 256;
+constexpr int kTopkThreads = 1024;
 
 __global__ void eval_general_kernel(DevTables T, const uint16_t* ops, long long n_cand, int stride,
                                     long long* out_makespan, long long* out_idle, int* out_peak,
