@@ -76,3 +76,41 @@ def test_random_problems_generator(seed):
         # whatever the scheduler emits, the evaluator accepts
         ev = oracle.evaluate(prob, ref["words"], threads=4)
         assert not (ev["flags"] & 3).any()
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_problems_sliding(seed):
+    """fpsched_wslide on random DAGs, placements (1 to 4 stages per device) and lists with recompute and
+    offload items, valid, perturbed and cut short; rows that are wide enough and rows that are not."""
+    import torch
+
+    import paper_2510_05112_amd as fp
+    rng = np.random.default_rng(3000 + seed)
+    done = 0
+    while done < 8:
+        prob = random_problem(rng)
+        if not prob.has_w:
+            continue
+        lists = []
+        for t in range(16):
+            base = random_valid_lists(prob, rng, 0.3 * (t % 2), 0.3 * ((t // 2) % 2))
+            lists.append(base)
+            lists.append(perturb(base, rng, 1 + t % 3))
+            if t % 5 == 0:
+                cut = [list(x) for x in base]
+                d = int(rng.integers(prob.n_devices))
+                cut[d] = cut[d][: len(cut[d]) // 2]
+                lists.append(cut)
+        words = batch_from_lists(lists)
+        stride = words.shape[2]
+        h = fp.Problem(prob, stride + 8, device=0)
+        for stride_out in (stride + 8, max(8, (stride // 2) // 8 * 8)):
+            out = h.wslide(torch.from_numpy(words.view(np.int16)).cuda(), stride_out)
+            torch.cuda.synchronize()
+            ref = oracle.wslide(prob, words, stride_out, threads=4)
+            what = f"seed {seed} problem {done} stride_out {stride_out}"
+            assert np.array_equal(out["ops"].cpu().numpy().view(np.uint16), ref["ops"]), what
+            for name in ("makespan", "idle", "peak", "flags"):
+                assert np.array_equal(out[name].cpu().numpy(), ref[name]), (what, name)
+        h.close()
+        done += 1
