@@ -39,18 +39,21 @@ def placement(strategy: str, n_devices: int, n_stages: int) -> list[int]:
     raise ValueError(f"unknown placement strategy {strategy!r}")
 
 
-def bidirectional(n_devices: int):
+def bidirectional(n_devices: int, v_shape: bool = False):
     """The bidirectional placement strategy (Section 4.1's built-in strategies; Section 2.1): two
-    replicas of a chain of p stages, one laid down the devices and one up, each taking half of the
-    micro-batches, so that every device holds one early and one late stage.  In the scheduler's
-    terms that is a stage DAG of two separate chains: stages 0..p-1 on devices 0..p-1 and stages
-    p..2p-1 on devices p-1..0; micro-batch j of the problem stands for the j-th micro-batch of
-    either replica.  Returns (stage_device[2p], edges [(src, dst)], replica_stage[2p]: the model
-    stage each scheduler stage is a copy of, for the caller's cost tables)."""
+    replicas of a chain of stages, one laid down the devices and one up, each taking half of the
+    micro-batches, so that every device holds early and late stages.  In the scheduler's terms
+    that is a stage DAG of two separate chains; micro-batch j of the problem stands for the j-th
+    micro-batch of either replica.  v_shape: every replica is itself a V-shape chain of 2p stages
+    (the combination Section 7.1 also searches), four stages per device.  Returns
+    (stage_device, edges [(src, dst)], replica_stage: the model stage each scheduler stage is a
+    copy of, for the caller's cost tables)."""
     p = n_devices
-    stage_device = list(range(p)) + list(range(p - 1, -1, -1))
-    edges = [(s, s + 1) for s in range(p - 1)] + [(p + s, p + s + 1) for s in range(p - 1)]
-    return stage_device, edges, list(range(p)) * 2
+    down = list(range(p)) + (list(range(p - 1, -1, -1)) if v_shape else [])
+    n = len(down)                                  # stages per replica
+    stage_device = down + [p - 1 - d for d in down]
+    edges = [(s, s + 1) for s in range(n - 1)] + [(n + s, n + s + 1) for s in range(n - 1)]
+    return stage_device, edges, list(range(n)) * 2
 
 
 @dataclass

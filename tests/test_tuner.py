@@ -27,15 +27,19 @@ def test_placements():
     dev, edges, copy_of = tuner.bidirectional(4)
     assert dev == [0, 1, 2, 3, 3, 2, 1, 0] and copy_of == [0, 1, 2, 3, 0, 1, 2, 3]
     assert edges == [(0, 1), (1, 2), (2, 3), (4, 5), (5, 6), (6, 7)]   # two chains, no edge between them
+    dev, edges, copy_of = tuner.bidirectional(3, v_shape=True)
+    assert dev == [0, 1, 2, 2, 1, 0, 2, 1, 0, 0, 1, 2] and copy_of == [0, 1, 2, 3, 4, 5] * 2
+    assert len(edges) == 10 and (5, 6) not in edges and all(sorted(dev).count(d) == 4 for d in range(3))
 
 
-def bidirectional_problem(p, m_per_replica, seed=0):
+def bidirectional_problem(p, m_per_replica, seed=0, v_shape=False):
     rng = np.random.default_rng(seed)
-    f, b, w = rng.integers(8, 13, p), rng.integers(14, 21, p), rng.integers(6, 11, p)
-    dev, edges, copy_of = tuner.bidirectional(p)
+    dev, edges, copy_of = tuner.bidirectional(p, v_shape)
+    n = len(dev) // 2
+    f, b, w = rng.integers(8, 13, n), rng.integers(14, 21, n), rng.integers(6, 11, n)
     dur = {F: f[copy_of], FD: f[copy_of], R: f[copy_of], B: b[copy_of], W: w[copy_of]}
-    return make_problem(p, 2 * p, m_per_replica, 1, dev, [(a, c, 2) for a, c in edges], dur,
-                        mem_cap=4 * m_per_replica, name="bidirectional")
+    return make_problem(p, 2 * n, m_per_replica, 1, dev, [(a, c, 2) for a, c in edges], dur,
+                        mem_cap=8 * m_per_replica, name="bidirectional")
 
 
 def test_bidirectional_schedules_from_the_generator_oracle_are_valid():
@@ -69,7 +73,8 @@ def test_grid_follows_the_papers_rules():
 @pytest.mark.gpu
 def test_gpu_search_with_sliding_and_bidirectional_placement_matches_the_oracles():
     import paper_2510_05112_amd as fp
-    for prob, circular in ((chain(4, 2, 12, "circular"), True), (bidirectional_problem(4, 6), False)):
+    for prob, circular in ((chain(4, 2, 12, "circular"), True), (bidirectional_problem(4, 6), False),
+                           (bidirectional_problem(3, 5, 1, v_shape=True), False)):
         st = tuner.stride_for(prob)
         h = fp.Problem(prob, st, device=0)
         best = tuner.tune(h, prob, circular, k=7, slide=True)
