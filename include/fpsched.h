@@ -179,9 +179,10 @@ int fpsched_rank(const fpsched_problem *p, fpsched_results in, int64_t n_cand, i
  * d_ops_out: DEVICE uint16 [n_cand][D][stride_out_words], 16-byte aligned, stride_out_words
  * a multiple of 8 and <= the handle's max stride: the new lists (the order in which the
  * items issued), END-padded.  `out`: the evaluation of the new lists, as fpsched_evaluate
- * would report it for them.  An item for which a new row has no room left halts its device
- * like a malformed word (DEADLOCK | INCOMPLETE); rows of failed candidates hold the items
- * that did issue.  The makespan may grow: an item that moves up can open idle time that the
+ * would report it for them.  A new row too short for all items of its device keeps the first
+ * stride_out_words of them; the other devices are not affected (where the W items go never
+ * moves an item of the list), and the candidate is reported as DEADLOCK | INCOMPLETE with
+ * the sentinels.  Rows of candidates that fail otherwise hold the items that did issue.  The makespan may grow: an item that moves up can open idle time that the
  * stashed items do not fit into; evaluate both lists and rank.  Needs the slot tables (at
  * most two inputs and outputs per stage, see fpsched_problem_info), else FPSCHED_EUNSUPPORTED.
  * No workspace.  Asynchronous on hip_stream. */

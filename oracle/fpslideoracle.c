@@ -34,9 +34,11 @@
  *
  *   Output: per device the new list (the order in which its items issued,
  *   END-padded to stride_out) and the evaluation of that list: makespan,
- *   idle, peak, flags, with the evaluator's meaning and sentinels.  An item
- *   that does not fit into stride_out words halts its device like a malformed
- *   word does (DEADLOCK | INCOMPLETE).
+ *   idle, peak, flags, with the evaluator's meaning and sentinels.  A row of
+ *   stride_out words that cannot hold all items of its device keeps the
+ *   first stride_out of them; nothing else changes for the other devices
+ *   (where the W items go never moves an item of the list), and the
+ *   candidate is reported as DEADLOCK | INCOMPLETE with the sentinels.
  *
  * Parity pins (tests/test_slideoracle.py): the output list evaluated by the
  * evaluation oracle reproduces the results; the new list is the old order of
@@ -69,14 +71,15 @@ typedef struct {
   uint16_t *out;         /* its output row */
   int32_t cap, len;      /* words the row holds, words written */
   int64_t free_at, busy, mem, peak;
-  int halted;            /* an item did not fit, or a malformed word */
+  int halted;            /* stopped at a malformed word */
+  int overflow;          /* some item found the row full */
 } device_t;
 
-/* One item issues on its device at `start`; returns 0 if the row is full. */
-static int issue(device_t *dev, int kind, int chunk, int s, int j, int64_t start, uint8_t *state) {
+/* One item issues on its device at `start`; its word joins the row while there is room. */
+static void issue(device_t *dev, int kind, int chunk, int s, int j, int64_t start, uint8_t *state) {
   const fpslide_problem *P = dev->P;
-  if (dev->len >= dev->cap) { dev->halted = 1; return 0; }
-  dev->out[dev->len++] = (uint16_t)((kind << 13) | (chunk << 11) | j);
+  if (dev->len < dev->cap) dev->out[dev->len++] = (uint16_t)((kind << 13) | (chunk << 11) | j);
+  else dev->overflow = 1;
   const int64_t dt = P->dur[kind * P->n_stages + s], u = P->mem_units[s];
   if (kind == K_F || kind == K_FD || kind == K_R || kind == K_L) {
     dev->mem += u;
@@ -94,7 +97,6 @@ static int issue(device_t *dev, int kind, int chunk, int s, int j, int64_t start
   }
   dev->free_at = start + dt;
   dev->busy += dt;
-  return 1;
 }
 
 int fpslide_oracle_one(const fpslide_problem *P, const uint16_t *words, int32_t stride, uint16_t *out_words,
@@ -131,10 +133,10 @@ int fpslide_oracle_one(const fpslide_problem *P, const uint16_t *words, int32_t 
         /* the list is over: what is still stashed runs back to back */
         while (stash_head[d] < stash_tail[d]) {
           const int c = q[2 * stash_head[d]], j = q[2 * stash_head[d] + 1], s = local_stage[d * MAX_CHUNKS + c];
-          if (!issue(&dev[d], K_W, c, s, j, dev[d].free_at, &state[(size_t)s * m + j])) break;
+          issue(&dev[d], K_W, c, s, j, dev[d].free_at, &state[(size_t)s * m + j]);
           ++stash_head[d];
         }
-        if (!dev[d].halted) finished[d] = 1;
+        finished[d] = 1;
         moved = 1;
         continue;
       }
@@ -166,11 +168,10 @@ int fpslide_oracle_one(const fpslide_problem *P, const uint16_t *words, int32_t 
       while (stash_head[d] < stash_tail[d]) {
         const int cq = q[2 * stash_head[d]], jq = q[2 * stash_head[d] + 1], sq = local_stage[d * MAX_CHUNKS + cq];
         if (dev[d].free_at + P->dur[K_W * S + sq] > start) break;
-        if (!issue(&dev[d], K_W, cq, sq, jq, dev[d].free_at, &state[(size_t)sq * m + jq])) break;
+        issue(&dev[d], K_W, cq, sq, jq, dev[d].free_at, &state[(size_t)sq * m + jq]);
         ++stash_head[d];
       }
-      if (dev[d].halted) { moved = 1; continue; }
-      if (!issue(&dev[d], kind, c, s, j, start, st)) { moved = 1; continue; }
+      issue(&dev[d], kind, c, s, j, start, st);
       if (kind == K_F || kind == K_FD) fin_fwd[(size_t)s * m + j] = dev[d].free_at;
       if (kind == K_B) {
         fin_bwd[(size_t)s * m + j] = dev[d].free_at;
@@ -184,7 +185,7 @@ int fpslide_oracle_one(const fpslide_problem *P, const uint16_t *words, int32_t 
   uint8_t fl = 0;
   for (int d = 0; d < D; ++d) {
     if (!finished[d]) fl |= FLAG_DEADLOCK;
-    if (dev[d].halted) fl |= FLAG_DEADLOCK | FLAG_INCOMPLETE;
+    if (dev[d].halted || dev[d].overflow) fl |= FLAG_DEADLOCK | FLAG_INCOMPLETE;
   }
   if (!fl)
     for (int i = 0; i < S * m; ++i) if (state[i] != ST_DONE) { fl = FLAG_INCOMPLETE; break; }

@@ -90,7 +90,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void wslide_kernel(
   int cursor = 0, out_len = 0;
   unsigned free_at8 = 0, busy8 = 0;
   int mem = 0, pk = 0;
-  bool done = !active, halted = false, seg_live = true;
+  bool done = !active, halted = false, overflow = false, seg_live = true;
   // op window: words [loaded - kWin, loaded) of the row are in the ring; the head of the row is
   // fetched before the first round
   int loaded = 0;
@@ -172,10 +172,13 @@ __global__ __launch_bounds__(kSlotMaxThreads) void wslide_kernel(
   // The item issues at start8: the word joins the new row (false: the row is full), the device's
   // clock, memory and the activation state move on, the finish time goes to the output slots.
   auto issue = [&](unsigned word, const int4& Mo, const int2& M2o, unsigned start8) -> bool {
-    if (out_len >= stride_out) return false;
-    shift_in(word);
-    if ((out_len & 7) == 7) *reinterpret_cast<uint4*>(out_row + (out_len - 7)) = make_uint4(acc0, acc1, acc2, acc3);
-    ++out_len;
+    if (out_len < stride_out) {
+      shift_in(word);
+      if ((out_len & 7) == 7) *reinterpret_cast<uint4*>(out_row + (out_len - 7)) = make_uint4(acc0, acc1, acc2, acc3);
+      ++out_len;
+    } else {
+      overflow = true;   // the row keeps its first stride_out items; the candidate is reported as failed
+    }
     const unsigned j = word & 0x7ffu, c = (word >> 11) & 3u;
     const unsigned fin8 = start8 + (unsigned)Mo.x;
     mem += (int)((unsigned)Mo.w & 0xffu);
@@ -305,8 +308,8 @@ __global__ __launch_bounds__(kSlotMaxThreads) void wslide_kernel(
   bool incomplete = false;
   if (active)
     for (int i = 0; i < T.state_words; ++i) incomplete = incomplete || (stt[i * 64 + lane] != (unsigned)expect[i]);
-  const unsigned long long stuck = __ballot(active && !done) & seg_mask;
-  const unsigned long long stuck_bad = __ballot(active && halted) & seg_mask;
+  const unsigned long long stuck = __ballot(active && (!done || overflow)) & seg_mask;
+  const unsigned long long stuck_bad = __ballot(active && (halted || overflow)) & seg_mask;
   const unsigned long long unfinished = __ballot(incomplete) & seg_mask;
   const unsigned long long over = __ballot(active && pk > cap) & seg_mask;
   int ms = active ? (int)(free_at8 >> 8) : 0;

@@ -93,6 +93,24 @@ def test_output_evaluates_to_the_reported_results_and_keeps_the_order(index, n):
         assert np.array_equal(r[name], r2[name]), name
 
 
+@pytest.mark.parametrize("index", [2, 5])
+def test_items_of_the_list_keep_the_times_of_the_list_without_w(index):
+    # a stashed item only runs where it delays nothing, so every other item starts when it would start if
+    # there were no W items at all: the traces of the evaluation oracle on the new list and on the list
+    # with its W words taken out agree item by item
+    spec, words = batch(index, 30)
+    prob = spec.problem
+    r = oracle.wslide(prob, words, spec.stride, threads=4)
+    bare = strip_w(words)
+    for c in np.flatnonzero((r["flags"] & 3) == 0)[:12]:
+        new, old = oracle.evaluate_trace(prob, r["ops"][c]), oracle.evaluate_trace(prob, bare[c])
+        for d in range(prob.n_devices):
+            keep = (r["ops"][c, d] >> 13 != 0) & (r["ops"][c, d] >> 13 != W)
+            n = int(keep.sum())
+            assert np.array_equal(new["start"][d][keep], old["start"][d][:n])
+            assert np.array_equal(new["finish"][d][keep], old["finish"][d][:n])
+
+
 def test_items_of_zero_cost_follow_their_backward_item_at_once():
     spec, words = batch(2, 150)
     prob = copy.deepcopy(spec.problem)
@@ -143,7 +161,7 @@ def test_one_f_one_b_with_unit_costs_reaches_the_known_bubble(p, m):
     assert np.all(r["idle"][0] == p - 1)
 
 
-def test_a_row_that_is_too_short_halts_its_device():
+def test_a_row_that_is_too_short_keeps_the_head_of_its_list():
     spec, words = batch(2, 40)
     prob = spec.problem
     full = oracle.wslide(prob, words, spec.stride, threads=4)
@@ -153,13 +171,14 @@ def test_a_row_that_is_too_short_halts_its_device():
     hit = 0
     for c in range(40):
         f_rows, s_rows = rows_of(full["ops"][c]), rows_of(r["ops"][c])
-        if max(len(x) for x in f_rows) > short and (full["flags"][c] & 3) == 0:
-            hit += 1
-            assert r["flags"][c] == 3 and r["makespan"][c] == oracle.INT64_MAX
         for a, b in zip(f_rows, s_rows):
-            assert a[:len(b)] == b   # what was written is the head of the full row
-        if max(len(x) for x in f_rows) <= short:
-            assert r["flags"][c] == full["flags"][c] and r["makespan"][c] == full["makespan"][c]
+            assert b == a[:short]   # every row: the first `short` items of the full row, whatever the others do
+        if max(len(x) for x in f_rows) > short:
+            hit += 1
+            assert r["flags"][c] == 3 and r["makespan"][c] == oracle.INT64_MAX and np.all(r["peak"][c] == -1)
+        else:
+            for name in ("makespan", "idle", "peak", "flags"):
+                assert np.array_equal(r[name][c], full[name][c])
     assert hit > 0
 
 
