@@ -181,15 +181,17 @@ def bench_wslide(args, spec, threads) -> int:
         print(f"[bench] copy probe: {ops.numel() * 2} bytes read, {ops.numel() * 2} bytes written",
               file=sys.stderr, flush=True)
         del probe
-    out = handle.wslide(ops, stride)
+    slide_ws = torch.empty(int(fp.load_library().fpsched_wslide_workspace_bytes(handle._h, C, stride)),
+                           dtype=torch.uint8, device=dev)
+    out = handle.wslide(ops, stride, workspace=slide_ws)
     for _ in range(args.warmup):
-        out = handle.wslide(ops, stride)
+        handle.wslide(ops, stride, out=out, workspace=slide_ws)
     torch.cuda.synchronize()
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
     t0 = time.perf_counter()
     for i in range(args.steps):
         ev[i][0].record()
-        out = handle.wslide(ops, stride)
+        handle.wslide(ops, stride, out=out, workspace=slide_ws)
         ev[i][1].record()
         top = handle.topk(out, k, ws)
     torch.cuda.synchronize()

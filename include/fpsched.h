@@ -182,13 +182,17 @@ int fpsched_rank(const fpsched_problem *p, fpsched_results in, int64_t n_cand, i
  * would report it for them.  A new row too short for all items of its device keeps the first
  * stride_out_words of them; the other devices are not affected (where the W items go never
  * moves an item of the list), and the candidate is reported as DEADLOCK | INCOMPLETE with
- * the sentinels.  Rows of candidates that fail otherwise hold the items that did issue.  The makespan may grow: an item that moves up can open idle time that the
- * stashed items do not fit into; evaluate both lists and rank.  Needs the slot tables (at
- * most two inputs and outputs per stage, see fpsched_problem_info), else FPSCHED_EUNSUPPORTED.
- * No workspace.  Asynchronous on hip_stream. */
+ * the sentinels.  Rows of candidates that fail otherwise hold the items that did issue.
+ * The makespan may grow: an item that moves up can open idle time that the stashed items do
+ * not fit into; evaluate both lists and rank.  Needs the slot tables (at most two inputs and
+ * outputs per stage, see fpsched_problem_info), else FPSCHED_EUNSUPPORTED.
+ * Workspace: fpsched_wslide_workspace_bytes (DEVICE, 16-byte aligned; it holds a start time
+ * per op word, i.e. about twice the bytes of the input lists).  Asynchronous on hip_stream. */
+size_t fpsched_wslide_workspace_bytes(const fpsched_problem *p, int64_t n_cand, int32_t stride_words);
 int fpsched_wslide(const fpsched_problem *p, const uint16_t *d_ops, int64_t n_cand,
                    int32_t stride_words, uint16_t *d_ops_out, int32_t stride_out_words,
-                   fpsched_results out, void *hip_stream);
+                   fpsched_results out, void *d_workspace, size_t workspace_bytes,
+                   void *hip_stream);
 
 /* Pareto front of (makespan, largest peak[d]) over the candidates that completed (neither
  * DEADLOCK nor INCOMPLETE; OVER_CAP is ignored: the front takes the place of a fixed cap).

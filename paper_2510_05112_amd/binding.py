@@ -73,8 +73,10 @@ def load_library():
         lib.fpsched_rank_workspace_bytes.argtypes = [vp, i64, i32]
         lib.fpsched_rank.restype = ctypes.c_int
         lib.fpsched_rank.argtypes = [vp, _Results, i64, i32, i32, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.fpsched_wslide_workspace_bytes.restype = ctypes.c_size_t
+        lib.fpsched_wslide_workspace_bytes.argtypes = [vp, i64, i32]
         lib.fpsched_wslide.restype = ctypes.c_int
-        lib.fpsched_wslide.argtypes = [vp, vp, i64, i32, vp, i32, _Results, vp]
+        lib.fpsched_wslide.argtypes = [vp, vp, i64, i32, vp, i32, _Results, vp, ctypes.c_size_t, vp]
         lib.fpsched_pareto_workspace_bytes.restype = ctypes.c_size_t
         lib.fpsched_pareto_workspace_bytes.argtypes = [vp, i64]
         lib.fpsched_pareto.restype = ctypes.c_int
@@ -295,10 +297,11 @@ class Problem:
             raise FpschedError(rc, "fpsched_rank")
         return out
 
-    def wslide(self, ops, stride_out: int | None = None, stream=None):
+    def wslide(self, ops, stride_out: int | None = None, out=None, workspace=None, stream=None):
         """Slide the weight-gradient items of ``ops`` (int16/uint16 CUDA tensor [n][D][stride]) into idle
         time (see fpsched_wslide).  Returns dict(ops, makespan, idle, peak, flags) of the new lists.
-        Asynchronous."""
+        out / workspace: reuse earlier results / a uint8 CUDA tensor of at least
+        fpsched_wslide_workspace_bytes.  Asynchronous."""
         import torch
         if self.device is None:
             raise FpschedError(-5, "fpsched_wslide")
@@ -307,13 +310,18 @@ class Problem:
         n, _, stride = ops.shape
         stride_out = int(stride if stride_out is None else stride_out)
         dev = torch.device("cuda", self.device)
-        out = dict(ops=torch.empty((n, self.D, stride_out), dtype=ops.dtype, device=dev),
-                   makespan=torch.empty(n, dtype=torch.int64, device=dev),
-                   idle=torch.empty((n, self.D), dtype=torch.int64, device=dev),
-                   peak=torch.empty((n, self.D), dtype=torch.int32, device=dev),
-                   flags=torch.empty(n, dtype=torch.uint8, device=dev))
+        if out is None:
+            out = dict(ops=torch.empty((n, self.D, stride_out), dtype=ops.dtype, device=dev),
+                       makespan=torch.empty(n, dtype=torch.int64, device=dev),
+                       idle=torch.empty((n, self.D), dtype=torch.int64, device=dev),
+                       peak=torch.empty((n, self.D), dtype=torch.int32, device=dev),
+                       flags=torch.empty(n, dtype=torch.uint8, device=dev))
+        nbytes = int(load_library().fpsched_wslide_workspace_bytes(self._h, n, int(stride)))
+        if workspace is None:
+            workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
         rc = load_library().fpsched_wslide(self._h, ops.data_ptr(), n, int(stride), out["ops"].data_ptr(), stride_out,
-                                           self._res_struct(out), self._stream(stream))
+                                           self._res_struct(out), workspace.data_ptr(), workspace.numel(),
+                                           self._stream(stream))
         if rc != 0:
             raise FpschedError(rc, "fpsched_wslide")
         return out

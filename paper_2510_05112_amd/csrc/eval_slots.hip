@@ -104,12 +104,18 @@ __global__ void reset_counter_kernel(unsigned long long* counter, unsigned long 
   if (threadIdx.x == 0) *counter = value;
 }
 
-template <int V, bool DEG2, bool ONE_CLASS>
+// TIMES = true is the first pass of the weight-gradient sliding (wslide.hip): the tables then
+// describe the lists without their W items (a W word is a no-op that always issues at once), and
+// instead of makespan, idle and peak the kernel writes, per op word, the time the op started
+// (<< 8, at the word's position in a [candidate][device][stride] array) and, per device, the
+// position at which its list stopped.
+template <int V, bool DEG2, bool ONE_CLASS, bool TIMES>
 __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     SlotTables T, const uint16_t* __restrict__ ops, long long n_cand, int stride,
     long long* __restrict__ out_makespan, long long* __restrict__ out_idle,
     int* __restrict__ out_peak, unsigned char* __restrict__ out_flags,
-    unsigned long long* __restrict__ next_candidate, int draw_block) {
+    unsigned long long* __restrict__ next_candidate, int draw_block,
+    uint32_t* __restrict__ out_start8, int32_t* __restrict__ out_stop) {
   extern __shared__ int32_t lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int m = T.m;
@@ -130,6 +136,9 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   uint32_t* stt = reinterpret_cast<uint32_t*>(L + rest_off);              // [state word][lane]
   uint32_t* slots = stt + T.state_words * 64;
   const int slots_per_cand = T.slots_per_cand;  // backward, forward, dump; a multiple of 8
+  // TIMES: one dword behind the last wavefront's region stays zero; it is the state word of W words
+  const unsigned zero_off = shared_bytes + (blockDim.x >> 6) * (kRing * 128u + rest_ints * 4u);
+  if (TIMES && tid == 0) *reinterpret_cast<uint32_t*>(L + zero_off) = 0u;
   __syncthreads();
 
   const int seg = lane >> lpc_shift;
@@ -194,6 +203,9 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   bool running = false;  // this lane's segment is evaluating a candidate
   unsigned dead = ~0u;   // 0 while this lane carries a device of a running candidate, else all ones
   bool fresh = true;     // (re)start the segment on `cand` at the top of the next round
+  // TIMES: start times of the last four ops, stored 16 bytes at a time at the ops' positions
+  unsigned st0 = 0u, st1 = 0u, st2 = 0u, st3 = 0u;
+  uint32_t* start_row = out_start8;
 
   // LDS addresses of everything a round reads for the current word.  They only change when the
   // lane issues, so they are worked out there, once per op, and a round starts with its reads.
@@ -218,6 +230,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     unsigned chunk_at = __umul24(c, chunk_bytes) + stt_off;
     asm("" : "+v"(chunk_at));
     at_state = (jw << 8) + chunk_at;
+    if (TIMES) at_state = (word >> 13) == (unsigned)kW ? lds0 + zero_off : at_state;
     at_slot = (jc << 2) + slot_base;   // slot j of the first class; low five bits = 4 (j & 7)
     const bool is_b = (word >> 13) == (unsigned)kB;
     // one class: backward inputs at slot j, forward inputs at slot m + j; bit 13 of the word is set
@@ -334,6 +347,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
         if (running && lane_ok) {
           for (int i = 0; i < T.state_words; ++i) stt[i * 64 + lane] = 0u;
           row = ops + ((size_t)cand * T.D + d) * (size_t)stride;
+          if (TIMES) start_row = out_start8 + ((size_t)cand * T.D + d) * (size_t)stride;
           prime0 = *reinterpret_cast<const uint2*>(row);
           prime1 = *reinterpret_cast<const uint2*>(row + kChunk);
           if (prime_words > 8) prime2 = *reinterpret_cast<const uint2*>(row + 2 * kChunk);
@@ -389,7 +403,13 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     const bool ok = __builtin_amdgcn_inverse_ballot_w64(moved);
     // ---- issue
     if (ok) {
-      const unsigned fin8 = max(free_at8, ready8) + dur8;
+      const unsigned start8 = max(free_at8, ready8);
+      const unsigned fin8 = start8 + dur8;
+      if (TIMES) {
+        st0 = st1; st1 = st2; st2 = st3; st3 = start8;
+        // npos = (position of this op + 1) << 7: the fourth op of a group completes it
+        if ((npos & (3u << 7)) == 0u) *reinterpret_cast<uint4*>(start_row + ((npos >> 7) - 4u)) = make_uint4(st0, st1, st2, st3);
+      }
       mem += (int)(my_ & 0xffu);
       pk = max(pk, mem);
       mem -= (int)((my_ >> 8) & 0xffu);
@@ -448,7 +468,18 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
         if (stuck) flg = kDeadlock | (stuck_bad ? kIncomplete : 0);
         else if (unfinished) flg = kIncomplete;
         else if (over) flg = kOverCap;
-        if (lane_ok) {
+        if (TIMES) {
+          if (lane_ok) {
+            // the start times of an unfinished group of four, and where the list stopped
+            const unsigned stop = (npos >> 7) - 1u;
+            if (stop & 3u) {
+              for (unsigned i = stop & 3u; i < 4u; ++i) { st0 = st1; st1 = st2; st2 = st3; st3 = 0u; }
+              *reinterpret_cast<uint4*>(start_row + (stop & ~3u)) = make_uint4(st0, st1, st2, st3);
+            }
+            out_stop[cand * T.D + d] = (int)stop;
+            if (d == 0) out_flags[cand] = (unsigned char)(flg & (kDeadlock | kIncomplete));
+          }
+        } else if (lane_ok) {
           const bool failed = (flg & (kDeadlock | kIncomplete)) != 0;
           out_idle[cand * T.D + d] = failed ? -1ll : (long long)(ms - (int)(busy8 >> 8));
           out_peak[cand * T.D + d] = failed ? -1 : pk * T.unit_scale;
@@ -471,10 +502,13 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   }
 }
 
-#define FPSCHED_INSTANTIATE(V, G, O)                                                               \
-  template __global__ void eval_slot_kernel<V, G, O>(SlotTables, const uint16_t*, long long, int,  \
-                                                     long long*, long long*, int*, unsigned char*, \
-                                                     unsigned long long*, int);
+#define FPSCHED_INSTANTIATE(V, G, O)                                                                      \
+  template __global__ void eval_slot_kernel<V, G, O, false>(                                              \
+      SlotTables, const uint16_t*, long long, int, long long*, long long*, int*, unsigned char*,          \
+      unsigned long long*, int, uint32_t*, int32_t*);                                                     \
+  template __global__ void eval_slot_kernel<V, G, O, true>(                                               \
+      SlotTables, const uint16_t*, long long, int, long long*, long long*, int*, unsigned char*,          \
+      unsigned long long*, int, uint32_t*, int32_t*);
 FPSCHED_INSTANTIATE(1, false, true)
 FPSCHED_INSTANTIATE(2, false, true)
 FPSCHED_INSTANTIATE(4, false, true)

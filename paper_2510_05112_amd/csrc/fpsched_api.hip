@@ -33,8 +33,9 @@ struct fpsched_problem {
   int32_t slot_lds_bytes = 0;      // dynamic LDS of one slot-kernel workgroup
   int32_t slot_waves = 0;          // wavefronts per slot-kernel workgroup
   int32_t slot_grid = 0;           // resident workgroups: the persistent grid
-  int32_t slide_waves = 0;         // wavefronts per workgroup of the sliding kernel (0: not available)
-  int32_t slide_lds_bytes = 0;
+  bool slide_ok = false;           // the sliding pass is available (split backward, slot tables)
+  SlotTables stab_times{};         // the slot tables of the lists without their W items
+  int32_t* d_times_ints = nullptr;
   SlotTables stab{};
   std::vector<int32_t> slot_ints;
   int32_t* d_slot_ints = nullptr;
@@ -58,24 +59,19 @@ struct DeviceGuard {
 };
 
 using SlotKernel = void (*)(SlotTables, const uint16_t*, long long, int, long long*, long long*, int*,
-                            unsigned char*, unsigned long long*, int);
-SlotKernel slot_kernel_ptr(int v, bool deg2, bool one_class) {
+                            unsigned char*, unsigned long long*, int, uint32_t*, int32_t*);
+template <bool TIMES>
+SlotKernel slot_kernel_of(int v, bool deg2, bool one_class) {
   if (deg2)
-    return v == 1 ? &eval_slot_kernel<1, true, false>
-                  : (v == 2 ? &eval_slot_kernel<2, true, false> : &eval_slot_kernel<4, true, false>);
+    return v == 1 ? &eval_slot_kernel<1, true, false, TIMES>
+                  : (v == 2 ? &eval_slot_kernel<2, true, false, TIMES> : &eval_slot_kernel<4, true, false, TIMES>);
   if (one_class)
-    return v == 1 ? &eval_slot_kernel<1, false, true>
-                  : (v == 2 ? &eval_slot_kernel<2, false, true> : &eval_slot_kernel<4, false, true>);
-  return v == 1 ? &eval_slot_kernel<1, false, false>
-                : (v == 2 ? &eval_slot_kernel<2, false, false> : &eval_slot_kernel<4, false, false>);
+    return v == 1 ? &eval_slot_kernel<1, false, true, TIMES>
+                  : (v == 2 ? &eval_slot_kernel<2, false, true, TIMES> : &eval_slot_kernel<4, false, true, TIMES>);
+  return v == 1 ? &eval_slot_kernel<1, false, false, TIMES>
+                : (v == 2 ? &eval_slot_kernel<2, false, false, TIMES> : &eval_slot_kernel<4, false, false, TIMES>);
 }
-
-using SlideKernel = void (*)(SlotTables, const uint16_t*, long long, int, uint16_t*, int, long long*, long long*,
-                             int*, unsigned char*);
-SlideKernel slide_kernel_ptr(int v, bool deg2) {
-  if (deg2) return v == 1 ? &wslide_kernel<1, true> : (v == 2 ? &wslide_kernel<2, true> : &wslide_kernel<4, true>);
-  return v == 1 ? &wslide_kernel<1, false> : (v == 2 ? &wslide_kernel<2, false> : &wslide_kernel<4, false>);
-}
+SlotKernel slot_kernel_ptr(int v, bool deg2, bool one_class) { return slot_kernel_of<false>(v, deg2, one_class); }
 
 int next_pow2(int x) {
   int p = 1;
@@ -398,25 +394,48 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
            hipFuncSetAttribute(reinterpret_cast<const void*>(slot_kernel_ptr(p->slot_v, p->slot_deg2, p->stab.n_classes == 1)),
                                hipFuncAttributeMaxDynamicSharedMemorySize, p->slot_lds_bytes) == hipSuccess;
       p->stab.ints = p->d_slot_ints;
-      // the sliding kernel: metadata once per workgroup; per wavefront the state words, the slots of
-      // its candidates, and per lane a 16-word op window and a 16-word stash ring
+      // The sliding pass times the lists without their W items with the evaluation kernel's TIMES
+      // form: the same tables, except that a W word is a no-op (any state, no cost, no memory) and a
+      // (stage, micro-batch) is finished once its B item ran.
       if (ok && p->has_w) {
-        const int64_t wave_ints = 64ll * p->stab.state_words + (int64_t)p->stab.cands_per_wave * p->stab.slots_per_cand + (16 + 16) * 32;
-        const int64_t room = p->max_lds / 4 - p->stab.n_shared_ints - 64;
-        const int waves = (int)std::min<int64_t>(room > 0 ? room / wave_ints : 0, kSlotMaxWaves);
-        if (waves >= 1) {
-          p->slide_lds_bytes = (int32_t)(4ll * (p->stab.n_shared_ints + waves * wave_ints));
-          if (hipFuncSetAttribute(reinterpret_cast<const void*>(slide_kernel_ptr(p->slot_v, p->slot_deg2)),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, p->slide_lds_bytes) == hipSuccess)
-            p->slide_waves = waves;
-          else
-            (void)hipGetLastError();
+        std::vector<int32_t> J = p->slot_ints;
+        const int lpc = p->stab.lanes_per_cand;
+        for (int c = 0; c < kMaxChunks; ++c)
+          for (int d = 0; d < D; ++d) {
+            if (c >= p->n_chunks[d]) continue;
+            int32_t* e = &J[(((size_t)kW * kMaxChunks + c) * lpc + d) * 4];
+            e[0] = 0;
+            e[1] = 0;
+            e[2] = (int32_t)((unsigned)e[2] & 0xffff0000u);   // required state 0, no transition, same output slot
+            e[3] = (int32_t)((unsigned)e[3] & 0x00ff0000u);   // own stage only
+          }
+        const int words_per_chunk = (m + 7) / 8;
+        for (int d = 0; d < D; ++d) {
+          int32_t* x = &J[(size_t)p->stab.off_expect + (size_t)d * p->stab.state_words];
+          for (int i = 0; i < p->stab.state_words; ++i) x[i] = 0;
+          for (int c = 0; c < p->n_chunks[d]; ++c)
+            for (int j = 0; j < m; ++j) x[c * words_per_chunk + (j >> 3)] |= (int32_t)((unsigned)kBDone << ((j & 7) * 4));
+        }
+        p->stab_times = p->stab;
+        const bool up = hipMalloc(&p->d_times_ints, J.size() * sizeof(int32_t)) == hipSuccess &&
+                        hipMemcpy(p->d_times_ints, J.data(), J.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess &&
+                        hipFuncSetAttribute(reinterpret_cast<const void*>(slot_kernel_of<true>(p->slot_v, p->slot_deg2, p->stab.n_classes == 1)),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, p->slot_lds_bytes + 16) == hipSuccess &&
+                        hipFuncSetAttribute(reinterpret_cast<const void*>(&wslide_place_kernel),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, kNKinds * kMaxChunks * lpc * 16) == hipSuccess;
+        if (up) {
+          p->stab_times.ints = p->d_times_ints;
+          p->slide_ok = true;
+        } else {
+          (void)hipGetLastError();
+          if (p->d_times_ints) { (void)hipFree(p->d_times_ints); p->d_times_ints = nullptr; }
         }
       }
     }
     if (!ok) {
       (void)hipFree(p->d_ints);
       if (p->d_slot_ints) (void)hipFree(p->d_slot_ints);
+      if (p->d_times_ints) (void)hipFree(p->d_times_ints);
       delete p;
       return FPSCHED_EHIP;
     }
@@ -432,6 +451,7 @@ void fpsched_problem_destroy(fpsched_problem* p) {
     DeviceGuard g(p->device_id);
     if (p->d_ints) (void)hipFree(p->d_ints);
     if (p->d_slot_ints) (void)hipFree(p->d_slot_ints);
+    if (p->d_times_ints) (void)hipFree(p->d_times_ints);
   }
   delete p;
 }
@@ -502,7 +522,8 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
     hipLaunchKernelGGL(slot_kernel_ptr(p->slot_v, p->slot_deg2, p->stab.n_classes == 1), dim3((unsigned)blocks), dim3(64 * p->slot_waves),
                        (size_t)p->slot_lds_bytes, static_cast<hipStream_t>(hip_stream), p->stab, d_ops,
                        (long long)n_cand, (int)stride_words, reinterpret_cast<long long*>(out.makespan),
-                       reinterpret_cast<long long*>(out.idle), out.peak, out.flags, counter, draw_block);
+                       reinterpret_cast<long long*>(out.idle), out.peak, out.flags, counter, draw_block,
+                       (uint32_t*)nullptr, (int32_t*)nullptr);
     return check_hip(hipGetLastError());
   }
   const int cpw = p->tables.cands_per_wave;
@@ -643,25 +664,59 @@ int fpsched_rank(const fpsched_problem* p, fpsched_results in, int64_t n_cand, i
   return run_topk(keys, excluded, n_cand, k, d_idx, d_key, d_count, static_cast<char*>(d_workspace) + 256, st);
 }
 
+// workspace of the sliding pass: [256 bytes: candidate counter][start times: uint32 per op word]
+// [stop positions: int32 per row][flags of the timing pass: one byte per candidate]
+static size_t wslide_starts_bytes(const fpsched_problem* p, int64_t n_cand, int32_t stride_words) {
+  return (size_t)n_cand * p->D * (size_t)stride_words * sizeof(uint32_t);
+}
+
+size_t fpsched_wslide_workspace_bytes(const fpsched_problem* p, int64_t n_cand, int32_t stride_words) {
+  if (!p || n_cand < 0 || stride_words < 8) return 0;
+  const size_t rows = (size_t)n_cand * p->D;
+  return 256 + wslide_starts_bytes(p, n_cand, stride_words) + ((rows * sizeof(int32_t) + 15) & ~(size_t)15) +
+         (((size_t)n_cand + 15) & ~(size_t)15);
+}
+
 int fpsched_wslide(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_cand, int32_t stride_words,
-                   uint16_t* d_ops_out, int32_t stride_out_words, fpsched_results out, void* hip_stream) {
+                   uint16_t* d_ops_out, int32_t stride_out_words, fpsched_results out, void* d_workspace,
+                   size_t workspace_bytes, void* hip_stream) {
   if (!p || n_cand < 0) return FPSCHED_EINVAL;
   if (p->device_id < 0) return FPSCHED_ENODEV;
   if (!p->has_w) return FPSCHED_EINVAL;
-  if (!p->slots_ok || p->slide_waves < 1) return FPSCHED_EUNSUPPORTED;
+  if (!p->slide_ok) return FPSCHED_EUNSUPPORTED;
   if (n_cand == 0) return FPSCHED_OK;
   if (!d_ops || !d_ops_out || !out.makespan || !out.idle || !out.peak || !out.flags) return FPSCHED_EINVAL;
   if (stride_words < 8 || (stride_words & 7) || stride_words > p->max_stride) return FPSCHED_EINVAL;
   if (stride_out_words < 8 || (stride_out_words & 7) || stride_out_words > p->max_stride) return FPSCHED_EINVAL;
   if ((reinterpret_cast<uintptr_t>(d_ops) & 15) || (reinterpret_cast<uintptr_t>(d_ops_out) & 15)) return FPSCHED_EINVAL;
-  const int64_t per_block = (int64_t)p->stab.cands_per_wave * p->slide_waves;
-  const int64_t blocks = (n_cand + per_block - 1) / per_block;
-  if (blocks > 0x7fffffffll) return FPSCHED_EINVAL;
+  if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) & 15)) return FPSCHED_EINVAL;
+  if (workspace_bytes < fpsched_wslide_workspace_bytes(p, n_cand, stride_words)) return FPSCHED_ENOMEM;
+  const int lpc = p->stab.lanes_per_cand;
+  const int64_t place_blocks = (n_cand * lpc + kSlideThreads - 1) / kSlideThreads;
+  if (place_blocks > 0x7fffffffll) return FPSCHED_EINVAL;
   DeviceGuard g(p->device_id);
   if (!g.ok) return FPSCHED_EHIP;
-  hipLaunchKernelGGL(slide_kernel_ptr(p->slot_v, p->slot_deg2), dim3((unsigned)blocks), dim3(64 * p->slide_waves),
-                     (size_t)p->slide_lds_bytes, static_cast<hipStream_t>(hip_stream), p->stab, d_ops,
-                     (long long)n_cand, (int)stride_words, d_ops_out, (int)stride_out_words,
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  char* ws = static_cast<char*>(d_workspace);
+  unsigned long long* counter = reinterpret_cast<unsigned long long*>(ws);
+  uint32_t* starts = reinterpret_cast<uint32_t*>(ws + 256);
+  int32_t* stops = reinterpret_cast<int32_t*>(ws + 256 + wslide_starts_bytes(p, n_cand, stride_words));
+  unsigned char* timed_flags = reinterpret_cast<unsigned char*>(stops) + (((size_t)n_cand * p->D * sizeof(int32_t) + 15) & ~(size_t)15);
+  // pass 1: the lists without their W items, timed by the evaluation kernel (launched as in fpsched_evaluate)
+  const int per_block = p->stab.cands_per_wave * p->slot_waves;
+  const int64_t blocks = std::min<int64_t>((n_cand + per_block - 1) / per_block, p->slot_grid);
+  const int64_t row_words = (int64_t)p->D * stride_words;
+  const int draw_block = (int)std::clamp<int64_t>((12288 + row_words - 1) / row_words, 1, p->stab.cands_per_wave);
+  hipLaunchKernelGGL(reset_counter_kernel, dim3(1), dim3(64), 0, st, counter, (unsigned long long)(blocks * per_block));
+  hipLaunchKernelGGL(slot_kernel_of<true>(p->slot_v, p->slot_deg2, p->stab.n_classes == 1), dim3((unsigned)blocks),
+                     dim3(64 * p->slot_waves), (size_t)p->slot_lds_bytes + 16, st, p->stab_times, d_ops, (long long)n_cand,
+                     (int)stride_words, (long long*)nullptr, (long long*)nullptr, (int*)nullptr, timed_flags, counter,
+                     draw_block, starts, stops);
+  if (hipGetLastError() != hipSuccess) return FPSCHED_EHIP;
+  // pass 2: every row places its W items on its own
+  hipLaunchKernelGGL(wslide_place_kernel, dim3((unsigned)place_blocks), dim3(kSlideThreads),
+                     (size_t)kNKinds * kMaxChunks * lpc * 16, st, p->stab, d_ops, (long long)n_cand, (int)stride_words,
+                     starts, stops, timed_flags, d_ops_out, (int)stride_out_words,
                      reinterpret_cast<long long*>(out.makespan), reinterpret_cast<long long*>(out.idle), out.peak,
                      out.flags);
   return check_hip(hipGetLastError());

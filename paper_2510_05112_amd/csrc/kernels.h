@@ -25,10 +25,14 @@ constexpr int kSlotMaxThreads = 64 * kSlotMaxWaves;
 // has two inputs or two outputs in the stage DAG.  ONE_CLASS = the DAG is a single chain.
 // next_candidate: a counter in device memory, preset to the number of segments in the grid, from
 // which wavefronts draw their work, draw_block candidates per atomic (1 <= draw_block <= 64).
-template <int V, bool DEG2, bool ONE_CLASS>
+// TIMES: first pass of the weight-gradient sliding; writes out_start8 [n_cand][D][stride] (start time
+// << 8 of the op at each position), out_stop [n_cand][D] (words issued per device) and out_flags
+// (DEADLOCK / INCOMPLETE only) instead of makespan, idle and peak; needs 16 bytes of LDS more.
+template <int V, bool DEG2, bool ONE_CLASS, bool TIMES>
 __global__ void eval_slot_kernel(SlotTables T, const uint16_t* ops, long long n_cand, int stride,
                                  long long* out_makespan, long long* out_idle, int* out_peak,
-                                 unsigned char* out_flags, unsigned long long* next_candidate, int draw_block);
+                                 unsigned char* out_flags, unsigned long long* next_candidate, int draw_block,
+                                 uint32_t* out_start8, int32_t* out_stop);
 
 __global__ void reset_counter_kernel(unsigned long long* counter, unsigned long long value);
 
@@ -48,12 +52,14 @@ __global__ void rank_keys_kernel(const long long* makespan, const long long* idl
                                  const unsigned char* flags, long long n, int D, int mode, int include_over_cap,
                                  long long* key_out, unsigned char* excluded_out);
 
-// Weight-gradient sliding on the slot tables; V and DEG2 as for eval_slot_kernel.  Candidates are
-// assigned statically: wavefront w of workgroup b owns candidates (b * waves + w) * cands_per_wave ...
-template <int V, bool DEG2>
-__global__ void wslide_kernel(SlotTables T, const uint16_t* ops, long long n_cand, int stride, uint16_t* ops_out,
-                              int stride_out, long long* out_makespan, long long* out_idle, int* out_peak,
-                              unsigned char* out_flags);
+// Second kernel of the weight-gradient sliding: one lane per (candidate, device) row places the W
+// items into the idle time in front of the ops timed by eval_slot_kernel<..., TIMES = true>.
+constexpr int kSlideThreads = 256;
+__global__ void wslide_place_kernel(SlotTables T, const uint16_t* ops, long long n_cand, int stride,
+                                    const uint32_t* start8, const int32_t* stop_pos,
+                                    const unsigned char* timed_flags, uint16_t* ops_out, int stride_out,
+                                    long long* out_makespan, long long* out_idle, int* out_peak,
+                                    unsigned char* out_flags);
 
 // Pareto front: at most kParetoMaxTiles tiles of kTile candidates (one cursor per tile in LDS).
 constexpr int kParetoMergeThreads = 1024;

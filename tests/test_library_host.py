@@ -24,7 +24,7 @@ def test_library_loads_and_exports_every_declared_symbol():
             "fpsched_workspace_bytes", "fpsched_encode", "fpsched_validate", "fpsched_strerror",
             "fpsched_version", "fpsched_problem_info", "fpsched_generate",
             "fpsched_problem_select_kernel", "fpsched_rank", "fpsched_rank_workspace_bytes",
-            "fpsched_pareto", "fpsched_pareto_workspace_bytes", "fpsched_apply_caps", "fpsched_wslide"} <= names
+            "fpsched_pareto", "fpsched_pareto_workspace_bytes", "fpsched_apply_caps", "fpsched_wslide", "fpsched_wslide_workspace_bytes"} <= names
     for n in names:
         assert hasattr(lib, n), n
     assert fp.version() == 100
