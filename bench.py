@@ -34,7 +34,7 @@ MEASURED_GENERATE = {("cfg4", 65536): {"traffic_bytes": 4.81e9, "valu_wave_instr
 
 
 # the sliding kernel (--mode wslide): profiles/wslide_kernel_cfg4.md
-MEASURED_WSLIDE = {("cfg4", 65536): {"traffic_bytes": 1.595e10, "valu_wave_instructions": 1.2854e10}}
+MEASURED_WSLIDE = {("cfg4", 65536): {"traffic_bytes": 1.107e11, "valu_wave_instructions": 1.041e10}}
 
 
 def bench_generate(args, spec, threads) -> int:
@@ -217,9 +217,10 @@ def bench_wslide(args, spec, threads) -> int:
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_WSLIDE.get((f"cfg{spec.index}", C), {}).get("traffic_bytes"),
-                     "kernel": "fpsched sliding kernel (wslide_kernel)", "algorithmic_bytes_per_launch": alg_bytes,
-                     "note": "round-synchronous like the evaluation kernel, with branches: bound by the latency "
-                             "of a round at 9 wavefronts per compute unit, not by HBM"},
+                     "kernel": "fpsched sliding pass: eval_slot_kernel<TIMES> + wslide_place_kernel",
+                     "algorithmic_bytes_per_launch": alg_bytes,
+                     "note": "two kernels per call; traffic is far above the algorithmic bytes: partly used cache "
+                             "lines of per-lane row streams (profiles/wslide_kernel_cfg4.md)"},
         "effect": {"mean_makespan_ratio": float((ms1[both] / ms0[both]).mean()) if both.any() else None,
                    "shorter": float((ms1[both] < ms0[both]).mean()) if both.any() else None,
                    "longer": float((ms1[both] > ms0[both]).mean()) if both.any() else None,

@@ -18,7 +18,7 @@
 //      had its W item placed), so it needs no storage.  In front of each item it places stashed
 //      items while they fit, then the item; at the end of the list it places the rest.  The new row
 //      leaves in 16-byte pieces collected in registers; memory is accounted along the new order.
-// Rows are read 8 bytes (op words) and 16 bytes (start times) at a time with the loads' latency
+// Rows are read 16 bytes (op words) and 32 bytes (start times) at a time with the loads' latency
 // exposed: there are thousands of independent wavefronts to cover it.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -29,26 +29,30 @@ namespace fpsched {
 
 namespace {
 
-// 4 op words in one 64-bit register, refilled from an 8-byte aligned row one piece ahead
+// 8 op words in four registers, refilled from a 16-byte aligned row one piece ahead
 struct WordReader {
   const uint16_t* row;
   int stride;
-  unsigned long long cur, next;
-  __device__ __forceinline__ unsigned long long piece(int at) const {
-    return at < stride ? *reinterpret_cast<const unsigned long long*>(row + at) : 0ull;
+  uint4 cur, next;
+  __device__ __forceinline__ uint4 piece(int at) const {
+    return at < stride ? *reinterpret_cast<const uint4*>(row + at) : make_uint4(0u, 0u, 0u, 0u);
   }
   __device__ __forceinline__ void start(const uint16_t* r, int s) {
     row = r; stride = s;
     cur = piece(0);
-    next = piece(4);
+    next = piece(8);
   }
   // word at position i (i only ever moves forward by one, starting at 0)
-  __device__ __forceinline__ unsigned at(int i) const { return (unsigned)(cur >> ((i & 3) * 16)) & 0xffffu; }
+  __device__ __forceinline__ unsigned at(int i) const {
+    const unsigned lo = (i & 2) ? cur.y : cur.x, hi = (i & 2) ? cur.w : cur.z;
+    const unsigned dw = (i & 4) ? hi : lo;
+    return (i & 1) ? dw >> 16 : dw & 0xffffu;
+  }
   // call after moving on to position i
   __device__ __forceinline__ void moved_to(int i) {
-    if ((i & 3) == 0) {
+    if ((i & 7) == 0) {
       cur = next;
-      next = piece(i + 4);
+      next = piece(i + 8);
     }
   }
 };
@@ -126,14 +130,18 @@ __global__ __launch_bounds__(kSlideThreads) void wslide_place_kernel(
     if (wcur < limit) stash_head(scan.at(wcur));
   };
 
-  uint4 starts = make_uint4(0u, 0u, 0u, 0u);
+  uint4 starts = make_uint4(0u, 0u, 0u, 0u), starts_hi = make_uint4(0u, 0u, 0u, 0u);
   for (int pos = 0; pos < stop; ++pos) {
-    if ((pos & 3) == 0) starts = *reinterpret_cast<const uint4*>(start_row + pos);
+    if ((pos & 7) == 0) {   // the start times of eight positions (strides are multiples of 8)
+      starts = *reinterpret_cast<const uint4*>(start_row + pos);
+      starts_hi = *reinterpret_cast<const uint4*>(start_row + pos + 4);
+    }
     const unsigned w = list.at(pos);
     const unsigned kind = w >> 13;
     if (kind != (unsigned)kW) {   // where the input put its W items is not used
       const int4 M = meta[(w >> 11) * lpc + d];
-      const unsigned s01 = (pos & 1) ? starts.y : starts.x, s23 = (pos & 1) ? starts.w : starts.z;
+      const uint4 half = (pos & 4) ? starts_hi : starts;
+      const unsigned s01 = (pos & 1) ? half.y : half.x, s23 = (pos & 1) ? half.w : half.z;
       const unsigned s8 = (pos & 2) ? s23 : s01;
       // idle time in front of the item: stashed items run while they end by its start
       while (wcur < pos && t8 + q_dur8 <= s8) place_stashed(pos);
