@@ -18,6 +18,14 @@
  * sizes, return 0 on success or a negative FPSCHED_E* code, and never throw or
  * abort.  A problem with an individual candidate (deadlock, malformed words) is
  * never a call error: it is reported in that candidate's flags.
+ *
+ * Ownership and threads.  The caller owns every buffer it passes, the workspaces
+ * included; the library owns only the opaque handle and the few KB of tables it
+ * uploads when the handle is created (it allocates nothing afterwards).  A handle
+ * is immutable after creation except for fpsched_problem_select_kernel: calls on
+ * distinct handles, and calls on one handle that use distinct workspaces and
+ * output buffers, may run from different host threads and on different streams.
+ * Device calls only enqueue kernels on the given stream and return.
  */
 #ifndef FPSCHED_H
 #define FPSCHED_H
