@@ -15,9 +15,10 @@
 //   2. this kernel places the W items: one lane per (candidate, device) row, no interaction
 //      between lanes until the final reduction.  A lane walks its row once; the stash is the B
 //      words between a second cursor and the first one (every B word before the second cursor has
-//      had its W item placed), so it needs no storage.  In front of each item it places stashed
-//      items while they fit, then the item; at the end of the list it places the rest.  The new row
-//      leaves in 16-byte pieces collected in registers; memory is accounted along the new order.
+//      had its W item placed), so it needs no storage.  One step per loop iteration, the same code
+//      for all lanes: the oldest stashed item if it fits in front of the item at the list cursor
+//      (or the list is over), else that item.  The new row leaves in 16-byte pieces collected in
+//      registers; memory is accounted along the new order.
 // Rows are read 16 bytes (op words) and 32 bytes (start times) at a time with the loads' latency
 // exposed: there are thousands of independent wavefronts to cover it.
 #include <hip/hip_runtime.h>
@@ -117,56 +118,67 @@ __global__ __launch_bounds__(kSlideThreads) void wslide_place_kernel(
       overflow = true;   // the row keeps its first stride_out items; the candidate is reported as failed
     }
   };
-  // the oldest stashed item runs now; the stash cursor moves on to the next B word before `limit`
-  auto place_stashed = [&](int limit) {
-    append(q_word);
-    t8 += q_dur8;
-    busy8 += q_dur8;
-    mem -= q_free;
-    do {
-      ++wcur;
-      scan.moved_to(wcur);
-    } while (wcur < limit && (scan.at(wcur) >> 13) != (unsigned)kB);
-    if (wcur < limit) stash_head(scan.at(wcur));
-  };
-
+  // the item at the list cursor: its word, metadata row and start time, fetched when the cursor moves
+  int pos = 0;
+  unsigned w = 0u, s8 = 0u;
+  int4 M = make_int4(0, 0, 0, 0);
   uint4 starts = make_uint4(0u, 0u, 0u, 0u), starts_hi = make_uint4(0u, 0u, 0u, 0u);
-  for (int pos = 0; pos < stop; ++pos) {
+  auto fetch = [&]() {
     if ((pos & 7) == 0) {   // the start times of eight positions (strides are multiples of 8)
       starts = *reinterpret_cast<const uint4*>(start_row + pos);
       starts_hi = *reinterpret_cast<const uint4*>(start_row + pos + 4);
     }
-    const unsigned w = list.at(pos);
+    w = list.at(pos);
+    M = meta[(w >> 11) * lpc + d];
+    const uint4 half = (pos & 4) ? starts_hi : starts;
+    const unsigned s01 = (pos & 1) ? half.y : half.x, s23 = (pos & 1) ? half.w : half.z;
+    s8 = (pos & 2) ? s23 : s01;
+  };
+  if (pos < stop) fetch();
+  // a device that reached the end of its list runs what is still stashed back to back
+  const bool at_end = active && (stop >= stride || (ops[row_index * (size_t)stride + stop] >> 13) == (unsigned)kEnd);
+
+  // One step per iteration: the oldest stashed item runs if it ends by the start of the item at the
+  // list cursor (or the list is over); else that item issues, or a W word of the input is passed over.
+  for (;;) {
+    const bool have = pos < stop;
     const unsigned kind = w >> 13;
-    if (kind != (unsigned)kW) {   // where the input put its W items is not used
-      const int4 M = meta[(w >> 11) * lpc + d];
-      const uint4 half = (pos & 4) ? starts_hi : starts;
-      const unsigned s01 = (pos & 1) ? half.y : half.x, s23 = (pos & 1) ? half.w : half.z;
-      const unsigned s8 = (pos & 2) ? s23 : s01;
-      // idle time in front of the item: stashed items run while they end by its start
-      while (wcur < pos && t8 + q_dur8 <= s8) place_stashed(pos);
-      append(w);
-      mem += (int)((unsigned)M.w & 0xffu);
+    const bool item = have && kind != (unsigned)kW;   // where the input put its W items is not used
+    const bool place = wcur < pos && (have ? (item && t8 + q_dur8 <= s8) : at_end);
+    if (!have && !place) break;
+    if (place || item) {
+      const unsigned dur8 = place ? q_dur8 : (unsigned)M.x;
+      const unsigned at8 = place ? t8 : s8;
+      append(place ? q_word : w);
+      mem += place ? 0 : (int)((unsigned)M.w & 0xffu);
       pk = max(pk, mem);
-      mem -= (int)(((unsigned)M.w >> 8) & 0xffu);
-      t8 = s8 + (unsigned)M.x;
-      busy8 += (unsigned)M.x;
+      mem -= place ? q_free : (int)(((unsigned)M.w >> 8) & 0xffu);
+      t8 = at8 + dur8;
+      busy8 += dur8;
     }
-    // the stash cursor follows the list cursor unless it rests on a B word whose W item is due
-    if (wcur == pos) {
-      if (kind == (unsigned)kB) {
-        stash_head(w);
-      } else {
+    if (place) {
+      // the stash cursor moves on to the next B word in front of the list cursor
+      do {
         ++wcur;
         scan.moved_to(wcur);
+      } while (wcur < pos && (scan.at(wcur) >> 13) != (unsigned)kB);
+      if (wcur < pos) stash_head(scan.at(wcur));
+    } else {
+      // the word at the list cursor is done with; the stash cursor follows the list cursor unless it
+      // rests on a B word whose W item is due
+      if (wcur == pos) {
+        if (kind == (unsigned)kB) {
+          stash_head(w);
+        } else {
+          ++wcur;
+          scan.moved_to(wcur);
+        }
       }
+      ++pos;
+      list.moved_to(pos);
+      if (pos < stop) fetch();
     }
-    list.moved_to(pos + 1);
   }
-  // a device that reached the end of its list runs what is still stashed back to back
-  const bool at_end = active && (stop >= stride || (list.at(stop) >> 13) == (unsigned)kEnd);
-  if (at_end)
-    while (wcur < stop) place_stashed(stop);
 
   // ---- the rest of the new row: words still in the registers, then END words up to the stride
   if (active) {
