@@ -289,6 +289,48 @@ def test_evaluate_and_topk_replayed_from_a_hip_graph():
     h.close()
 
 
+def test_generate_slide_and_topk_replayed_from_a_hip_graph():
+    # the search loop with the sliding pass, captured once and replayed on new parameter sets; every
+    # replay is checked against the three oracles
+    import torch
+
+    import paper_2510_05112_amd as fp
+    spec = workloads.config(2, 8)
+    prob, k, n = spec.problem, 5, 160
+    st = workloads.generator_stride(prob)
+    sets = [workloads.policy_sets(prob, n, seed=77 + i) for i in range(3)]
+    h = fp.Problem(prob, st, device=0)
+    d_pol, d_inf = torch.from_numpy(sets[0][0]).cuda(), torch.from_numpy(sets[0][1]).cuda()
+    gen = h.generate(d_pol, d_inf, st)                      # eager once: allocates the outputs
+    ws = h.alloc_workspace(n, k)
+    slide_ws = torch.empty(int(fp.load_library().fpsched_wslide_workspace_bytes(h._h, n, st)), dtype=torch.uint8,
+                           device="cuda")
+    slid = h.wslide(gen["ops"], st, workspace=slide_ws)
+    top = h.topk(slid, k, ws)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        h.generate(d_pol, d_inf, st, out=gen, workspace=ws)
+        h.wslide(gen["ops"], st, out=slid, workspace=slide_ws)
+        h.topk(slid, k, ws, top)
+    for pol, inf in sets[::-1] + sets:
+        d_pol.copy_(torch.from_numpy(pol))
+        d_inf.copy_(torch.from_numpy(inf))
+        slid["flags"].fill_(255)      # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        ref_gen = oracle.generate(prob, pol, inf, st, threads=2)
+        assert np.array_equal(gen["ops"].cpu().numpy().view(np.uint16), ref_gen["words"])
+        ref = oracle.wslide(prob, ref_gen["words"], st, threads=2)
+        assert np.array_equal(slid["ops"].cpu().numpy().view(np.uint16), ref["ops"])
+        for name in ("makespan", "idle", "peak", "flags"):
+            assert np.array_equal(slid[name].cpu().numpy(), ref[name]), name
+        idx, ms, cnt = oracle.topk(ref["makespan"], ref["flags"], k)
+        assert int(top["count"].item()) == cnt and np.array_equal(top["idx"].cpu().numpy(), idx)
+    h.close()
+
+
 def test_largest_stage_counts():
     # 252 stages (tags up to 251 in the slot kernel) and 256 stages (beyond its 8-bit tags: the
     # general kernel takes over)
