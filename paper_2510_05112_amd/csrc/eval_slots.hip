@@ -107,8 +107,10 @@ __global__ void reset_counter_kernel(unsigned long long* counter, unsigned long 
 // TIMES = true is the first pass of the weight-gradient sliding (wslide.hip): the tables then
 // describe the lists without their W items (a W word is a no-op that always issues at once), and
 // instead of makespan, idle and peak the kernel writes, per op word, the time the op started
-// (<< 8, at the word's position in a [candidate][device][stride] array) and, per device, the
-// position at which its list stopped.
+// (<< 8; four positions of a device are 16 bytes, and the 16-byte pieces of a candidate's devices
+// for the same four positions lie side by side, [candidate][stride / 4][lanes per candidate][4]: the
+// lanes of a candidate pass a position at about the same time, so a line fills up quickly) and,
+// per device, the position at which its list stopped.
 template <int V, bool DEG2, bool ONE_CLASS, bool TIMES>
 __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     SlotTables T, const uint16_t* __restrict__ ops, long long n_cand, int stride,
@@ -347,7 +349,8 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
         if (running && lane_ok) {
           for (int i = 0; i < T.state_words; ++i) stt[i * 64 + lane] = 0u;
           row = ops + ((size_t)cand * T.D + d) * (size_t)stride;
-          if (TIMES) start_row = out_start8 + ((size_t)cand * T.D + d) * (size_t)stride;
+          // start times: [candidate][group of four positions][lane of the candidate][4]
+          if (TIMES) start_row = out_start8 + (size_t)cand * (size_t)stride * (size_t)lpc + ((size_t)d << 2);
           prime0 = *reinterpret_cast<const uint2*>(row);
           prime1 = *reinterpret_cast<const uint2*>(row + kChunk);
           if (prime_words > 8) prime2 = *reinterpret_cast<const uint2*>(row + 2 * kChunk);
@@ -408,7 +411,8 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       if (TIMES) {
         st0 = st1; st1 = st2; st2 = st3; st3 = start8;
         // npos = (position of this op + 1) << 7: the fourth op of a group completes it
-        if ((npos & (3u << 7)) == 0u) *reinterpret_cast<uint4*>(start_row + ((npos >> 7) - 4u)) = make_uint4(st0, st1, st2, st3);
+        if ((npos & (3u << 7)) == 0u)
+          *reinterpret_cast<uint4*>(start_row + ((size_t)((npos >> 9) - 1u) << (lpc_shift + 2))) = make_uint4(st0, st1, st2, st3);
       }
       mem += (int)(my_ & 0xffu);
       pk = max(pk, mem);
@@ -474,7 +478,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
             const unsigned stop = (npos >> 7) - 1u;
             if (stop & 3u) {
               for (unsigned i = stop & 3u; i < 4u; ++i) { st0 = st1; st1 = st2; st2 = st3; st3 = 0u; }
-              *reinterpret_cast<uint4*>(start_row + (stop & ~3u)) = make_uint4(st0, st1, st2, st3);
+              *reinterpret_cast<uint4*>(start_row + ((size_t)(stop >> 2) << (lpc_shift + 2))) = make_uint4(st0, st1, st2, st3);
             }
             out_stop[cand * T.D + d] = (int)stop;
             if (d == 0) out_flags[cand] = (unsigned char)(flg & (kDeadlock | kIncomplete));

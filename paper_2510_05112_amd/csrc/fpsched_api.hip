@@ -667,7 +667,7 @@ int fpsched_rank(const fpsched_problem* p, fpsched_results in, int64_t n_cand, i
 // workspace of the sliding pass: [256 bytes: candidate counter][start times: uint32 per op word]
 // [stop positions: int32 per row][flags of the timing pass: one byte per candidate]
 static size_t wslide_starts_bytes(const fpsched_problem* p, int64_t n_cand, int32_t stride_words) {
-  return (size_t)n_cand * p->D * (size_t)stride_words * sizeof(uint32_t);
+  return (size_t)n_cand * p->tables.lanes_per_cand * (size_t)stride_words * sizeof(uint32_t);
 }
 
 size_t fpsched_wslide_workspace_bytes(const fpsched_problem* p, int64_t n_cand, int32_t stride_words) {

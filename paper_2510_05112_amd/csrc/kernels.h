@@ -25,8 +25,8 @@ constexpr int kSlotMaxThreads = 64 * kSlotMaxWaves;
 // has two inputs or two outputs in the stage DAG.  ONE_CLASS = the DAG is a single chain.
 // next_candidate: a counter in device memory, preset to the number of segments in the grid, from
 // which wavefronts draw their work, draw_block candidates per atomic (1 <= draw_block <= 64).
-// TIMES: first pass of the weight-gradient sliding; writes out_start8 [n_cand][D][stride] (start time
-// << 8 of the op at each position), out_stop [n_cand][D] (words issued per device) and out_flags
+// TIMES: first pass of the weight-gradient sliding; writes out_start8 [n_cand][stride / 4][lanes per
+// candidate][4] (start time << 8 of the op at each position), out_stop [n_cand][D] (words issued per device) and out_flags
 // (DEADLOCK / INCOMPLETE only) instead of makespan, idle and peak; needs 16 bytes of LDS more.
 template <int V, bool DEG2, bool ONE_CLASS, bool TIMES>
 __global__ void eval_slot_kernel(SlotTables T, const uint16_t* ops, long long n_cand, int stride,

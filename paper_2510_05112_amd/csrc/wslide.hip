@@ -81,7 +81,8 @@ __global__ __launch_bounds__(kSlideThreads) void wslide_place_kernel(
   const int d = (int)(t & (lpc - 1));
   const bool active = cand < n_cand && d < T.D;
   const size_t row_index = (size_t)(active ? cand : 0) * T.D + (active ? d : 0);
-  const uint32_t* start_row = start8 + row_index * (size_t)stride;
+  // start times: [candidate][group of four positions][lane of the candidate][4]
+  const uint32_t* start_row = start8 + (size_t)(active ? cand : 0) * (size_t)stride * (size_t)lpc + ((size_t)d << 2);
   uint16_t* out_row = ops_out + row_index * (size_t)stride_out;
   const int stop = active ? stop_pos[row_index] : 0;
 
@@ -125,8 +126,8 @@ __global__ __launch_bounds__(kSlideThreads) void wslide_place_kernel(
   uint4 starts = make_uint4(0u, 0u, 0u, 0u), starts_hi = make_uint4(0u, 0u, 0u, 0u);
   auto fetch = [&]() {
     if ((pos & 7) == 0) {   // the start times of eight positions (strides are multiples of 8)
-      starts = *reinterpret_cast<const uint4*>(start_row + pos);
-      starts_hi = *reinterpret_cast<const uint4*>(start_row + pos + 4);
+      starts = *reinterpret_cast<const uint4*>(start_row + ((size_t)(pos >> 2) << (lpc_shift + 2)));
+      starts_hi = *reinterpret_cast<const uint4*>(start_row + ((size_t)((pos >> 2) + 1) << (lpc_shift + 2)));
     }
     w = list.at(pos);
     M = meta[(w >> 11) * lpc + d];
