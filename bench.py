@@ -34,7 +34,7 @@ MEASURED_GENERATE = {("cfg4", 65536): {"traffic_bytes": 4.81e9, "valu_wave_instr
 
 
 # the sliding kernel (--mode wslide): profiles/wslide_kernel_cfg4.md
-MEASURED_WSLIDE = {("cfg4", 65536): {"traffic_bytes": 1.178e11, "valu_wave_instructions": 9.47e9}}
+MEASURED_WSLIDE = {("cfg4", 65536): {"traffic_bytes": 8.08e10, "valu_wave_instructions": 5.54e9}}
 
 
 def bench_generate(args, spec, threads) -> int:

@@ -422,7 +422,8 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
                         hipFuncSetAttribute(reinterpret_cast<const void*>(slot_kernel_of<true>(p->slot_v, p->slot_deg2, p->stab.n_classes == 1)),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, p->slot_lds_bytes + 16) == hipSuccess &&
                         hipFuncSetAttribute(reinterpret_cast<const void*>(&wslide_place_kernel),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, kNKinds * kMaxChunks * lpc * 16) == hipSuccess;
+                                            hipFuncAttributeMaxDynamicSharedMemorySize,
+                                            kNKinds * kMaxChunks * lpc * 16 + (kSlideThreads / 64) * kSlideWaveLdsBytes) == hipSuccess;
         if (up) {
           p->stab_times.ints = p->d_times_ints;
           p->slide_ok = true;
@@ -715,7 +716,8 @@ int fpsched_wslide(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_ca
   if (hipGetLastError() != hipSuccess) return FPSCHED_EHIP;
   // pass 2: every row places its W items on its own
   hipLaunchKernelGGL(wslide_place_kernel, dim3((unsigned)place_blocks), dim3(kSlideThreads),
-                     (size_t)kNKinds * kMaxChunks * lpc * 16, st, p->stab, d_ops, (long long)n_cand, (int)stride_words,
+                     (size_t)kNKinds * kMaxChunks * lpc * 16 + (kSlideThreads / 64) * kSlideWaveLdsBytes, st, p->stab, d_ops,
+                     (long long)n_cand, (int)stride_words,
                      starts, stops, timed_flags, d_ops_out, (int)stride_out_words,
                      reinterpret_cast<long long*>(out.makespan), reinterpret_cast<long long*>(out.idle), out.peak,
                      out.flags);

@@ -54,7 +54,9 @@ __global__ void rank_keys_kernel(const long long* makespan, const long long* idl
 
 // Second kernel of the weight-gradient sliding: one lane per (candidate, device) row places the W
 // items into the idle time in front of the ops timed by eval_slot_kernel<..., TIMES = true>.
-constexpr int kSlideThreads = 256;
+constexpr int kSlideThreads = 512;
+// dynamic LDS of a workgroup: the metadata rows, then 8 KB per wavefront (windows and stash ring)
+constexpr int kSlideWaveLdsBytes = 8192;
 __global__ void wslide_place_kernel(SlotTables T, const uint16_t* ops, long long n_cand, int stride,
                                     const uint32_t* start8, const int32_t* stop_pos,
                                     const unsigned char* timed_flags, uint16_t* ops_out, int stride_out,

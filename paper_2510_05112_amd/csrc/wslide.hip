@@ -13,14 +13,16 @@
 //      items -- the only part with dependencies between devices -- and leaves each op's start time
 //      and the position at which each list stopped;
 //   2. this kernel places the W items: one lane per (candidate, device) row, no interaction
-//      between lanes until the final reduction.  A lane walks its row once; the stash is the B
-//      words between a second cursor and the first one (every B word before the second cursor has
-//      had its W item placed), so it needs no storage.  One step per loop iteration, the same code
-//      for all lanes: the oldest stashed item if it fits in front of the item at the list cursor
-//      (or the list is over), else that item.  The new row leaves in 16-byte pieces collected in
-//      registers; memory is accounted along the new order.
-// Rows are read 16 bytes (op words) and 32 bytes (start times) at a time with the loads' latency
-// exposed: there are thousands of independent wavefronts to cover it.
+//      between lanes until the final reduction.  A lane walks its row once.  One step per loop
+//      iteration, the same code for all lanes: the oldest stashed item if it fits in front of the
+//      item at the list cursor (or the list is over), else that item.  The new row leaves in
+//      16-byte pieces collected in registers; memory is accounted along the new order.
+// No global load sits on a step's critical path: op words and start times reach a lane through a
+// 16-position LDS window that the whole wavefront tops up every fourth step, the loads requested
+// at one top-up landing at the next.  (With loads issued by each lane when it needs them the
+// wavefront waited for memory in nearly every step: among 64 lanes at 64 different positions some
+// lane always needs its next piece.)  The stash is a ring of B words in LDS; only a stash deeper
+// than the ring is read back from the device's own row, with the latency exposed.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -30,33 +32,10 @@ namespace fpsched {
 
 namespace {
 
-// 8 op words in four registers, refilled from a 16-byte aligned row one piece ahead
-struct WordReader {
-  const uint16_t* row;
-  int stride;
-  uint4 cur, next;
-  __device__ __forceinline__ uint4 piece(int at) const {
-    return at < stride ? *reinterpret_cast<const uint4*>(row + at) : make_uint4(0u, 0u, 0u, 0u);
-  }
-  __device__ __forceinline__ void start(const uint16_t* r, int s) {
-    row = r; stride = s;
-    cur = piece(0);
-    next = piece(8);
-  }
-  // word at position i (i only ever moves forward by one, starting at 0)
-  __device__ __forceinline__ unsigned at(int i) const {
-    const unsigned lo = (i & 2) ? cur.y : cur.x, hi = (i & 2) ? cur.w : cur.z;
-    const unsigned dw = (i & 4) ? hi : lo;
-    return (i & 1) ? dw >> 16 : dw & 0xffffu;
-  }
-  // call after moving on to position i
-  __device__ __forceinline__ void moved_to(int i) {
-    if ((i & 7) == 0) {
-      cur = next;
-      next = piece(i + 8);
-    }
-  }
-};
+constexpr int kWin = 16;     // window: positions per lane (op words and their start times)
+constexpr int kPiece = 4;    // positions per load: 8 bytes of op words, 16 bytes of start times
+constexpr int kRefillAt = 9; // a lane asks for its next piece when at most this many positions are unread
+constexpr int kFifo = 16;    // stash ring: B words per lane
 
 }  // namespace
 
@@ -69,11 +48,16 @@ __global__ __launch_bounds__(kSlideThreads) void wslide_place_kernel(
   extern __shared__ int32_t lds[];
   const int lpc = T.lanes_per_cand;
   const int lpc_shift = __ffs(lpc) - 1;
-  // LDS: the metadata rows, one int4 per (kind * 4 + chunk, device): x = dur << 8,
-  // w = units allocated at the start (byte 0) | units freed at the end (byte 1)
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // LDS: [the metadata rows, one int4 per (kind * 4 + chunk, device): x = dur << 8, w = units
+  // allocated at the start (byte 0) | units freed at the end (byte 1)][per wavefront: start-time
+  // window [position][lane] (dwords), op-word window [position][lane], stash ring [entry][lane]]
   const int n_meta_ints = kNKinds * kMaxChunks * lpc * 4;
   for (int i = threadIdx.x; i < n_meta_ints; i += blockDim.x) lds[i] = T.ints[i];
   const int4* meta = reinterpret_cast<const int4*>(lds);
+  uint32_t* start_win = reinterpret_cast<uint32_t*>(lds + n_meta_ints + wave * (kWin * 64 + (kWin + kFifo) * 32)) + lane;
+  uint16_t* word_win = reinterpret_cast<uint16_t*>(start_win - lane + kWin * 64) + lane;   // entry i at + i * 64
+  uint16_t* fifo = word_win + kWin * 64;
   __syncthreads();
 
   const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -81,26 +65,71 @@ __global__ __launch_bounds__(kSlideThreads) void wslide_place_kernel(
   const int d = (int)(t & (lpc - 1));
   const bool active = cand < n_cand && d < T.D;
   const size_t row_index = (size_t)(active ? cand : 0) * T.D + (active ? d : 0);
+  const uint16_t* row = ops + row_index * (size_t)stride;
   // start times: [candidate][group of four positions][lane of the candidate][4]
   const uint32_t* start_row = start8 + (size_t)(active ? cand : 0) * (size_t)stride * (size_t)lpc + ((size_t)d << 2);
   uint16_t* out_row = ops_out + row_index * (size_t)stride_out;
-  const int stop = active ? stop_pos[row_index] : 0;
+  int stop = active ? stop_pos[row_index] : 0;
+  // a device that reached the end of its list runs what is still stashed back to back
+  unsigned end_word = (active && stop < stride) ? row[stop] : 0u;
+  // have both in registers before the loop: a wait for them inside the loop would also wait for
+  // the window loads in flight
+  asm volatile("" : "+v"(stop), "+v"(end_word));
+  const bool at_end = active && (end_word >> 13) == (unsigned)kEnd;
 
-  WordReader list, scan;   // the list cursor and the stash cursor read the same row
-  list.start(ops + row_index * (size_t)stride, active ? stride : 0);
-  scan = list;
-  int wcur = 0, out_len = 0;
+  // window: positions [loaded - kWin, loaded) of the row are in the rings; the whole wavefront tops
+  // them up every fourth step, the loads requested at one top-up landing at the next
+  int loaded = 0;
+  uint2 pend_words = make_uint2(0u, 0u);
+  uint4 pend_starts = make_uint4(0u, 0u, 0u, 0u);
+  bool has_pend = false;
+  auto land = [&](uint2 wv, uint4 sv) {
+    const int q = loaded & (kWin - 1);
+    word_win[(q + 0) * 64] = (uint16_t)wv.x; word_win[(q + 1) * 64] = (uint16_t)(wv.x >> 16);
+    word_win[(q + 2) * 64] = (uint16_t)wv.y; word_win[(q + 3) * 64] = (uint16_t)(wv.y >> 16);
+    start_win[(q + 0) * 64] = sv.x; start_win[(q + 1) * 64] = sv.y;
+    start_win[(q + 2) * 64] = sv.z; start_win[(q + 3) * 64] = sv.w;
+    loaded += kPiece;
+  };
+  auto piece_words = [&](int at) { return *reinterpret_cast<const uint2*>(row + at); };
+  auto piece_starts = [&](int at) { return *reinterpret_cast<const uint4*>(start_row + ((size_t)(at >> 2) << (lpc_shift + 2))); };
+  if (active)   // the head of the row is fetched before the first step (strides are multiples of 8)
+    for (int i = 0; i < 12 && i < stride; i += kPiece) land(piece_words(i), piece_starts(i));
+
+  int pos = 0, out_len = 0;
   unsigned t8 = 0u, busy8 = 0u;   // device free time and busy time, << 8
   int mem = 0, pk = 0;
-  bool overflow = false;
-  // the oldest stashed item: the B word at the stash cursor as a W word, its cost and what it frees
-  unsigned q_word = 0u, q_dur8 = 0u;
+  bool overflow = false, done = !active;
+  // the item at the list cursor: its word, metadata row and start time, read when the cursor moves
+  unsigned w = 0u, s8 = 0u;
+  int4 M = make_int4(0, 0, 0, 0);
+  bool need_word = true;
+  auto fetch = [&]() {   // (only called with pos < stop)
+    if (pos < loaded) {
+      w = word_win[(pos & (kWin - 1)) * 64];
+      s8 = start_win[(pos & (kWin - 1)) * 64];
+      M = meta[(w >> 11) * lpc + d];
+      need_word = false;
+    }
+  };
+  // stash ring: entries [q_head, q_tail) are B words whose W item is due, oldest first; `overflowed`:
+  // B words from row position refill_pos on found no room and are still to be read back from the row
+  int q_head = 0, q_tail = 0, refill_pos = 0;
+  bool overflowed = false;
+  unsigned q_word = 0u, q_dur8 = 0u;   // the oldest stashed item as a W word, its cost and what it frees
   int q_free = 0;
   auto stash_head = [&](unsigned b_word) {
     q_word = (b_word & 0x1fffu) | ((unsigned)kW << 13);
     const int4 Mq = meta[(q_word >> 11) * lpc + d];
     q_dur8 = (unsigned)Mq.x;
     q_free = (int)(((unsigned)Mq.w >> 8) & 0xffu);
+  };
+  auto stash_push = [&](unsigned b_word) -> bool {
+    if (q_tail - q_head >= kFifo) return false;
+    fifo[(q_tail & (kFifo - 1)) * 64] = (uint16_t)b_word;
+    if (q_tail == q_head) stash_head(b_word);
+    ++q_tail;
+    return true;
   };
   // the new row leaves in 16-byte pieces: eight words shifted into four registers
   unsigned acc0 = 0u, acc1 = 0u, acc2 = 0u, acc3 = 0u;
@@ -119,66 +148,72 @@ __global__ __launch_bounds__(kSlideThreads) void wslide_place_kernel(
       overflow = true;   // the row keeps its first stride_out items; the candidate is reported as failed
     }
   };
-  // the item at the list cursor: its word, metadata row and start time, fetched when the cursor moves
-  int pos = 0;
-  unsigned w = 0u, s8 = 0u;
-  int4 M = make_int4(0, 0, 0, 0);
-  uint4 starts = make_uint4(0u, 0u, 0u, 0u), starts_hi = make_uint4(0u, 0u, 0u, 0u);
-  auto fetch = [&]() {
-    if ((pos & 7) == 0) {   // the start times of eight positions (strides are multiples of 8)
-      starts = *reinterpret_cast<const uint4*>(start_row + ((size_t)(pos >> 2) << (lpc_shift + 2)));
-      starts_hi = *reinterpret_cast<const uint4*>(start_row + ((size_t)((pos >> 2) + 1) << (lpc_shift + 2)));
-    }
-    w = list.at(pos);
-    M = meta[(w >> 11) * lpc + d];
-    const uint4 half = (pos & 4) ? starts_hi : starts;
-    const unsigned s01 = (pos & 1) ? half.y : half.x, s23 = (pos & 1) ? half.w : half.z;
-    s8 = (pos & 2) ? s23 : s01;
-  };
-  if (pos < stop) fetch();
-  // a device that reached the end of its list runs what is still stashed back to back
-  const bool at_end = active && (stop >= stride || (ops[row_index * (size_t)stride + stop] >> 13) == (unsigned)kEnd);
 
-  // One step per iteration: the oldest stashed item runs if it ends by the start of the item at the
-  // list cursor (or the list is over); else that item issues, or a W word of the input is passed over.
-  for (;;) {
-    const bool have = pos < stop;
-    const unsigned kind = w >> 13;
-    const bool item = have && kind != (unsigned)kW;   // where the input put its W items is not used
-    const bool place = wcur < pos && (have ? (item && t8 + q_dur8 <= s8) : at_end);
-    if (!have && !place) break;
-    if (place || item) {
-      const unsigned dur8 = place ? q_dur8 : (unsigned)M.x;
-      const unsigned at8 = place ? t8 : s8;
-      append(place ? q_word : w);
-      mem += place ? 0 : (int)((unsigned)M.w & 0xffu);
-      pk = max(pk, mem);
-      mem -= place ? q_free : (int)(((unsigned)M.w >> 8) & 0xffu);
-      t8 = at8 + dur8;
-      busy8 += dur8;
+  // One step per iteration and lane: the oldest stashed item runs if it ends by the start of the
+  // item at the list cursor (or the list is over); else that item issues, or a W word of the input
+  // is passed over.  A lane takes at most one position per step, so with these window sizes it
+  // finds its word in the window (a lane that does not waits for the next top-up).
+  for (unsigned step = 0;; ++step) {
+    if ((step & 3u) == 0u) {
+      if (has_pend) {
+        land(pend_words, pend_starts);
+        has_pend = false;
+      }
+      if (!done && loaded - pos <= kRefillAt && loaded < stride) {
+        pend_words = piece_words(loaded);
+        pend_starts = piece_starts(loaded);
+        has_pend = true;
+      }
     }
-    if (place) {
-      // the stash cursor moves on to the next B word in front of the list cursor
-      do {
-        ++wcur;
-        scan.moved_to(wcur);
-      } while (wcur < pos && (scan.at(wcur) >> 13) != (unsigned)kB);
-      if (wcur < pos) stash_head(scan.at(wcur));
-    } else {
-      // the word at the list cursor is done with; the stash cursor follows the list cursor unless it
-      // rests on a B word whose W item is due
-      if (wcur == pos) {
-        if (kind == (unsigned)kB) {
-          stash_head(w);
+    if (!done) {
+      const bool have = pos < stop;
+      if (have && need_word) fetch();
+      if (!(have && need_word)) {
+        const unsigned kind = w >> 13;
+        const bool item = have && kind != (unsigned)kW;   // where the input put its W items is not used
+        const bool place = q_head < q_tail && (have ? (item && t8 + q_dur8 <= s8) : at_end);
+        if (!have && !place) {
+          done = true;
         } else {
-          ++wcur;
-          scan.moved_to(wcur);
+          if (place || item) {
+            const unsigned dur8 = place ? q_dur8 : (unsigned)M.x;
+            const unsigned at8 = place ? t8 : s8;
+            append(place ? q_word : w);
+            mem += place ? 0 : (int)((unsigned)M.w & 0xffu);
+            pk = max(pk, mem);
+            mem -= place ? q_free : (int)(((unsigned)M.w >> 8) & 0xffu);
+            t8 = at8 + dur8;
+            busy8 += dur8;
+          }
+          if (place) {
+            ++q_head;
+            if (q_head == q_tail && overflowed) {
+              // the ring ran empty while B words wait in the row: read them back, up to the list cursor
+              int at = refill_pos;
+              while (at < pos && q_tail - q_head < kFifo) {
+                const unsigned b_word = row[at];
+                if ((b_word >> 13) == (unsigned)kB) stash_push(b_word);
+                ++at;
+              }
+              refill_pos = at;
+              overflowed = at < pos;
+            }
+            if (q_head < q_tail) stash_head(fifo[(q_head & (kFifo - 1)) * 64]);
+          } else {
+            // the word at the list cursor is done with; an issued B item stashes its W item (once the
+            // ring has overflowed, later ones stay in the row)
+            if (kind == (unsigned)kB && !overflowed && !stash_push(w)) {
+              overflowed = true;
+              refill_pos = pos;
+            }
+            ++pos;
+            need_word = true;
+            if (pos < stop) fetch();
+          }
         }
       }
-      ++pos;
-      list.moved_to(pos);
-      if (pos < stop) fetch();
     }
+    if (__ballot(!done) == 0ull) break;
   }
 
   // ---- the rest of the new row: words still in the registers, then END words up to the stride
