@@ -64,6 +64,11 @@ def bench_generate(args, spec, threads) -> int:
     k = spec.top_k
     ws = handle.alloc_workspace(n, k)
     res = handle.alloc_results(n) if search else None
+    slide = search and args.slide and bool(prob.has_w)
+    if slide:   # the generated schedules also go through the sliding pass (Section 5.2, bubble optimizations)
+        slide_ws = torch.empty(int(fp.load_library().fpsched_wslide_workspace_bytes(handle._h, n, stride)),
+                               dtype=torch.uint8, device=dev)
+        slid = handle.wslide(out["ops"], stride, workspace=slide_ws)
     top = dict(idx=torch.empty(k, dtype=torch.int64, device=dev),
                makespan=torch.empty(k, dtype=torch.int64, device=dev),
                count=torch.empty(1, dtype=torch.int32, device=dev))
@@ -75,8 +80,12 @@ def bench_generate(args, spec, threads) -> int:
         if e:
             e[1].record()
         if search:
-            handle.evaluate(out["ops"], res, ws)
-            handle.topk(res, k, ws, top)
+            if slide:
+                handle.wslide(out["ops"], stride, out=slid, workspace=slide_ws)
+                handle.topk(slid, k, ws, top)
+            else:
+                handle.evaluate(out["ops"], res, ws)
+                handle.topk(res, k, ws, top)
 
     for _ in range(args.warmup):
         step()
@@ -118,9 +127,10 @@ def bench_generate(args, spec, threads) -> int:
         "host": {"parameter_sets_s": prep_s},
     }
     if search:
-        fl = res["flags"].cpu().numpy()
+        fl = (slid if slide else res)["flags"].cpu().numpy()
         res_out = {"feasible_under_cap": float((fl == 0).mean()), "over_cap": float((fl == 4).mean()),
                    "best_makespan": int(top["makespan"][0].item()) if int(top["count"].item()) else None}
+        res_out["sliding_pass"] = bool(slide)
         json_res["search"] = res_out
     if args.check or not args.no_cpu_baseline:
         import oracle  # test infrastructure: parity sample and the reported CPU baseline only
@@ -273,6 +283,8 @@ def main() -> int:
                          "headline metric); generate: the schedule generator on seeded parameter sets; "
                          "search: generate + evaluate + top-k per step, schedules never leave HBM; "
                          "wslide: the weight-gradient sliding pass + top-k on the resident batch")
+    ap.add_argument("--slide", action="store_true",
+                    help="search mode: rank the generated schedules after the weight-gradient sliding pass")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain elementwise copy of the op batch (a kernel of known HBM "
                          "traffic, used to calibrate rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
