@@ -36,6 +36,7 @@ constexpr int kWin = 16;     // window: positions per lane (op words and their s
 constexpr int kPiece = 4;    // positions per load: 8 bytes of op words, 16 bytes of start times
 constexpr int kRefillAt = 9; // a lane asks for its next piece when at most this many positions are unread
 constexpr int kFifo = 16;    // stash ring: B words per lane
+static_assert((kWin * 64 + (kWin + kFifo) * 32) * 4 == kSlideWaveLdsBytes, "LDS of one wavefront");
 
 }  // namespace
 
