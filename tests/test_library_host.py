@@ -56,6 +56,7 @@ def test_host_only_handle_and_errors():
     assert lib.fpsched_wslide(None, 0, 1, 8, 0, 8, none, 0, 0, 0) == -1
     assert lib.fpsched_pareto(p._h, none, 1, 0, 1, 1, 1, 1, 0, 0, 0) == -1
     assert lib.fpsched_topk(p._h, none, 1, 2000, 1, 1, 1, 0, 0, 0) == -1
+    assert lib.fpsched_pareto(p._h, none, (1 << 24) + 1, 4, 1, 1, 1, 1, 1, 1 << 40, 0) == -1   # more tiles than cursors
     p.close()
     # bad descriptions
     bad = chain_problem(4, 8)
