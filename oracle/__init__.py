@@ -74,6 +74,8 @@ def _load():
         _lib = ctypes.CDLL(build())
         _lib.fporacle_eval_one.restype = ctypes.c_int
         _lib.fporacle_evaluate.restype = ctypes.c_int
+        _lib.fporacle_eval_one_mb.restype = ctypes.c_int
+        _lib.fporacle_evaluate_mb.restype = ctypes.c_int
         _lib.fporacle_topk.restype = ctypes.c_int
         _lib.fporacle_rank.restype = ctypes.c_int
     return _lib
@@ -116,15 +118,27 @@ def decode(words):
     return k, c, j
 
 
-def evaluate(problem, words, threads: int = 1):
+def _mb_table(mp, dur_mb):
+    """``dur_mb[8][S][m]`` as a contiguous int32 array (None stays None)."""
+    if dur_mb is None:
+        return None
+    t = np.ascontiguousarray(np.asarray(dur_mb, dtype=np.int32))
+    assert t.shape == (NKINDS, mp.S, mp.m), t.shape
+    return t
+
+
+def evaluate(problem, words, threads: int = 1, dur_mb=None):
     """Evaluate a batch ``words[C][D][stride]`` (uint16).
 
     Returns dict(makespan int64[C], idle int64[C][D], peak int32[C][D],
     flags uint8[C]).  ``threads`` > 1 only splits the batch over host threads;
     every candidate is still evaluated by the same single-threaded C routine.
+    ``dur_mb[8][S][m]``: per-micro-batch costs in place of ``problem.dur``.
     """
     lib = _load()
     mp = _Marshalled(problem)
+    table = _mb_table(mp, dur_mb)
+    table_ptr = ctypes.c_void_p(table.ctypes.data if table is not None else None)
     w = np.ascontiguousarray(np.asarray(words, dtype=np.uint16))
     assert w.ndim == 3 and w.shape[1] == mp.D, w.shape
     C, _, stride = w.shape
@@ -134,8 +148,8 @@ def evaluate(problem, words, threads: int = 1):
     def run(lo, hi):
         if hi <= lo:
             return 0
-        return lib.fporacle_evaluate(
-            ctypes.byref(mp.c), ctypes.c_void_p(w[lo:hi].ctypes.data), ctypes.c_int64(hi - lo),
+        return lib.fporacle_evaluate_mb(
+            ctypes.byref(mp.c), table_ptr, ctypes.c_void_p(w[lo:hi].ctypes.data), ctypes.c_int64(hi - lo),
             ctypes.c_int32(stride), ctypes.c_void_p(out["makespan"][lo:hi].ctypes.data),
             ctypes.c_void_p(out["idle"][lo:hi].ctypes.data),
             ctypes.c_void_p(out["peak"][lo:hi].ctypes.data),
@@ -155,10 +169,11 @@ def evaluate(problem, words, threads: int = 1):
     return out
 
 
-def evaluate_trace(problem, words_one):
+def evaluate_trace(problem, words_one, dur_mb=None):
     """One candidate ``words[D][stride]``; also returns every op's start/finish."""
     lib = _load()
     mp = _Marshalled(problem)
+    table = _mb_table(mp, dur_mb)
     w = np.ascontiguousarray(np.asarray(words_one, dtype=np.uint16))
     assert w.ndim == 2 and w.shape[0] == mp.D
     stride = w.shape[1]
@@ -168,8 +183,9 @@ def evaluate_trace(problem, words_one):
     fl = np.empty(1, np.uint8)
     st = np.empty((mp.D, stride), np.int64)
     fi = np.empty((mp.D, stride), np.int64)
-    rc = lib.fporacle_eval_one(ctypes.byref(mp.c), ctypes.c_void_p(w.ctypes.data),
-                               ctypes.c_int32(stride), ctypes.c_void_p(ms.ctypes.data),
+    rc = lib.fporacle_eval_one_mb(ctypes.byref(mp.c),
+                                  ctypes.c_void_p(table.ctypes.data if table is not None else None),
+                                  ctypes.c_void_p(w.ctypes.data), ctypes.c_int32(stride), ctypes.c_void_p(ms.ctypes.data),
                                ctypes.c_void_p(idle.ctypes.data), ctypes.c_void_p(peak.ctypes.data),
                                ctypes.c_void_p(fl.ctypes.data), ctypes.c_void_p(st.ctypes.data),
                                ctypes.c_void_p(fi.ctypes.data))

@@ -104,9 +104,9 @@ static int build_local_stage(const fporacle_problem *P, int32_t *local_stage, in
  * (-1 where the op never issued or past the end of the list).
  * Returns 0, or -1 for an invalid problem.
  */
-int fporacle_eval_one(const fporacle_problem *P, const uint16_t *words, int32_t stride,
-                      int64_t *makespan, int64_t *idle, int32_t *peak, uint8_t *flags,
-                      int64_t *op_start, int64_t *op_finish) {
+static int eval_one(const fporacle_problem *P, const int32_t *dur_mb, const uint16_t *words, int32_t stride,
+                    int64_t *makespan, int64_t *idle, int32_t *peak, uint8_t *flags,
+                    int64_t *op_start, int64_t *op_finish) {
   const int D = P->n_devices, S = P->n_stages, m = P->n_microbatches;
   int32_t *local_stage = malloc(sizeof(int32_t) * D * MAX_CHUNKS);
   int32_t *n_chunks = malloc(sizeof(int32_t) * D);
@@ -178,7 +178,8 @@ int fporacle_eval_one(const fporacle_problem *P, const uint16_t *words, int32_t 
       if (blocked) continue;
 
       /* issue */
-      const int64_t dt = P->dur[kind * S + s];
+      /* cost of the item: per (type, stage), or per (type, stage, micro-batch) if such a table is given */
+      const int64_t dt = dur_mb ? dur_mb[((size_t)kind * S + s) * m + j] : P->dur[kind * S + s];
       const int64_t u = P->mem_units[s];
       const int64_t start = free_at[d] > ready ? free_at[d] : ready;
       const int64_t finish = start + dt;
@@ -236,16 +237,43 @@ int fporacle_eval_one(const fporacle_problem *P, const uint16_t *words, int32_t 
   return 0;
 }
 
-/* Evaluate candidates [0, n_cand) of a batch laid out [C][D][stride]. */
-int fporacle_evaluate(const fporacle_problem *P, const uint16_t *words, int64_t n_cand, int32_t stride,
-                      int64_t *makespan, int64_t *idle, int32_t *peak, uint8_t *flags) {
+int fporacle_eval_one(const fporacle_problem *P, const uint16_t *words, int32_t stride,
+                      int64_t *makespan, int64_t *idle, int32_t *peak, uint8_t *flags,
+                      int64_t *op_start, int64_t *op_finish) {
+  return eval_one(P, NULL, words, stride, makespan, idle, peak, flags, op_start, op_finish);
+}
+
+/*
+ * Variant of the cost model: micro-batches of unequal size.  The paper profiles one cost per
+ * (type, stage) (estimator sketch after Section 6); its related-work section (Section 8,
+ * "Frameworks") names dynamic micro-batching, where the micro-batches of one iteration differ in
+ * length and so in cost.  dur_mb[NKINDS][S][m] then replaces dur[NKINDS][S] in the start rule
+ * (finish = start + dur_mb[type][stage][micro-batch]) and in the busy time; nothing else changes.
+ * Pins: tests/test_oracle_mbdur.py (proportionate flow shop closed form, a timeline worked by hand,
+ * the critical-path checker with per-item weights, a constant table against the plain model).
+ */
+int fporacle_eval_one_mb(const fporacle_problem *P, const int32_t *dur_mb, const uint16_t *words,
+                         int32_t stride, int64_t *makespan, int64_t *idle, int32_t *peak, uint8_t *flags,
+                         int64_t *op_start, int64_t *op_finish) {
+  return eval_one(P, dur_mb, words, stride, makespan, idle, peak, flags, op_start, op_finish);
+}
+
+/* Evaluate candidates [0, n_cand) of a batch laid out [C][D][stride]; dur_mb may be NULL. */
+int fporacle_evaluate_mb(const fporacle_problem *P, const int32_t *dur_mb, const uint16_t *words,
+                         int64_t n_cand, int32_t stride, int64_t *makespan, int64_t *idle, int32_t *peak,
+                         uint8_t *flags) {
   const int D = P->n_devices;
   for (int64_t c = 0; c < n_cand; ++c) {
-    int rc = fporacle_eval_one(P, words + (size_t)c * D * stride, stride, &makespan[c],
-                               &idle[c * D], &peak[c * D], &flags[c], NULL, NULL);
+    int rc = eval_one(P, dur_mb, words + (size_t)c * D * stride, stride, &makespan[c],
+                      &idle[c * D], &peak[c * D], &flags[c], NULL, NULL);
     if (rc) return rc;
   }
   return 0;
+}
+
+int fporacle_evaluate(const fporacle_problem *P, const uint16_t *words, int64_t n_cand, int32_t stride,
+                      int64_t *makespan, int64_t *idle, int32_t *peak, uint8_t *flags) {
+  return fporacle_evaluate_mb(P, NULL, words, n_cand, stride, makespan, idle, peak, flags);
 }
 
 typedef struct { int64_t makespan, idx; } rank_key;

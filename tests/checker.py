@@ -36,9 +36,15 @@ def decode_lists(problem, words):
     return out
 
 
-def check(problem, words):
-    """Returns dict(deadlock, incomplete, makespan, idle, peak, finish) for one candidate."""
+def check(problem, words, dur_mb=None):
+    """Returns dict(deadlock, incomplete, makespan, idle, peak, finish) for one candidate.
+
+    dur_mb[kind][stage][micro-batch], if given, is the weight of every node instead of
+    problem.dur[kind][stage]."""
     D, S, m = problem.n_devices, problem.n_stages, problem.n_microbatches
+
+    def weight(kind, s, j):
+        return int(dur_mb[kind][s][j]) if dur_mb is not None else int(problem.dur[kind][s])
     lists = decode_lists(problem, words)
     dev = [int(x) for x in problem.stage_device]
     preds = {s: [] for s in range(S)}
@@ -74,7 +80,7 @@ def check(problem, words):
                 mem -= u
             if kind == W or (kind == B and not problem.has_w):
                 mem -= u
-            busy[d] += int(problem.dur[kind][s])
+            busy[d] += weight(kind, s, j)
             n_ok += 1
         valid_len.append(n_ok)
     if stuck:
@@ -125,8 +131,8 @@ def check(problem, words):
     while q:
         n = q.popleft()
         d, i = n
-        kind, s, _j, _c = lists[d][i]
-        finish[n] = ready[n] + int(problem.dur[kind][s])
+        kind, s, j, _c = lists[d][i]
+        finish[n] = ready[n] + weight(kind, s, j)
         done += 1
         for nxt, wgt in out_edges[n]:
             ready[nxt] = max(ready[nxt], finish[n] + wgt)
