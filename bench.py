@@ -285,6 +285,9 @@ def main() -> int:
                          "wslide: the weight-gradient sliding pass + top-k on the resident batch")
     ap.add_argument("--slide", action="store_true",
                     help="search mode: rank the generated schedules after the weight-gradient sliding pass")
+    ap.add_argument("--mb-costs", action="store_true",
+                    help="evaluate mode: costs per micro-batch (seeded factors in [1/2, 3/2) on the "
+                         "configuration's costs) instead of one cost per (type, stage)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain elementwise copy of the op batch (a kernel of known HBM "
                          "traffic, used to calibrate rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -322,6 +325,10 @@ def main() -> int:
           f"on {threads} threads", file=sys.stderr, flush=True)
 
     handle = fp.Problem(prob, stride, device=0)
+    dur_mb = None
+    if args.mb_costs:
+        dur_mb = workloads.microbatch_costs(prob)
+        handle.set_microbatch_costs(dur_mb)
     t0 = time.perf_counter()
     ops = torch.empty((C, D, stride), dtype=torch.int16, device=dev)
     chunk = max(1, (256 << 20) // (D * stride * 2))
@@ -372,7 +379,7 @@ def main() -> int:
     alg_bytes = 2 * n_ops + C * (8 + 8 * D + 4 * D + 1)
     achieved = alg_bytes / (eval_ms * 1e-3) / 1e9
 
-    measured = MEASURED.get((f"cfg{spec.index}", C), {})
+    measured = {} if args.mb_costs else MEASURED.get((f"cfg{spec.index}", C), {})
     flags = res["flags"].cpu().numpy()
     makespan = res["makespan"].cpu().numpy()
     out = {
@@ -384,7 +391,8 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int32", "data": "synthetic",
         "config": {"workload": f"cfg{spec.index}: {prob.name}, {C} candidates, top-{k}, "
-                               f"cap {int(prob.mem_cap[0])} units/device",
+                               f"cap {int(prob.mem_cap[0])} units/device"
+                               + (", costs per micro-batch (factors in [1/2, 3/2))" if args.mb_costs else ""),
                    "candidates": C, "devices": D, "stages": prob.n_stages,
                    "microbatches": prob.n_microbatches, "ops_per_candidate": n_ops / C,
                    "stride_words": stride, "top_k": k},
@@ -417,7 +425,7 @@ def main() -> int:
         if args.check:
             rng = np.random.default_rng(0)
             pick = np.sort(rng.choice(C, min(args.check, C), replace=False))
-            ref = oracle.evaluate(prob, words[pick], threads=threads)
+            ref = oracle.evaluate(prob, words[pick], threads=threads, dur_mb=dur_mb)
             ok = all(np.array_equal(res[n][torch.from_numpy(pick).to(dev)].cpu().numpy(), ref[n])
                      for n in ("makespan", "idle", "peak", "flags"))
             out["parity_sample"] = {"candidates": int(len(pick)), "bit_exact": bool(ok)}
@@ -426,11 +434,11 @@ def main() -> int:
         if not args.no_cpu_baseline:
             n1 = min(C, args.cpu_sample or max(64, int(120e6 // max(1, n_ops // C))))
             t0 = time.perf_counter()
-            oracle.evaluate(prob, words[:n1], threads=1)
+            oracle.evaluate(prob, words[:n1], threads=1, dur_mb=dur_mb)
             t1 = time.perf_counter() - t0
             nn = min(C, n1 * min(threads, 8))
             t0 = time.perf_counter()
-            oracle.evaluate(prob, words[:nn], threads=threads)
+            oracle.evaluate(prob, words[:nn], threads=threads, dur_mb=dur_mb)
             tn = time.perf_counter() - t0
             out["cpu_baseline"] = {
                 "value": nn / tn, "unit": "schedules/s", "cores": threads, "kind": "oracle",

@@ -21,8 +21,9 @@
  *
  * Ownership and threads.  The caller owns every buffer it passes, the workspaces
  * included; the library owns only the opaque handle and the few KB of tables it
- * uploads when the handle is created (it allocates nothing afterwards).  A handle
- * is immutable after creation except for fpsched_problem_select_kernel: calls on
+ * uploads when the handle is created (it allocates nothing afterwards, except for the two
+ * tables of fpsched_problem_set_microbatch_costs).  A handle is immutable after creation except
+ * for fpsched_problem_select_kernel and fpsched_problem_set_microbatch_costs: calls on
  * distinct handles, and calls on one handle that use distinct workspaces and
  * output buffers, may run from different host threads and on different streams.
  * Device calls only enqueue kernels on the given stream and return.
@@ -114,6 +115,21 @@ typedef struct fpsched_problem fpsched_problem; /* opaque, library-owned */
 int fpsched_problem_create(const fpsched_problem_desc *desc, int device_id, int32_t max_stride_words,
                            fpsched_problem **out);
 void fpsched_problem_destroy(fpsched_problem *p);
+
+/* Variant of the cost model: micro-batches of unequal size.  The paper profiles one cost per
+ * (type, stage) (estimator sketch after Section 6); its related-work section (Section 8,
+ * "Frameworks") names dynamic micro-batching, where the micro-batches of an iteration differ in
+ * length and so in cost.  dur_mb: HOST, int32 [FPSCHED_NKINDS][S][m], >= 0 (row 0 unused), copied;
+ * from then on fpsched_evaluate uses  finish = start + dur_mb[kind][stage][micro-batch]  and counts
+ * those costs as the devices' busy time; nothing else changes.  NULL switches back to desc.dur.
+ * Synchronous: waits for the device's queued work (the previous table may be in use) and must
+ * not run concurrently with other calls on the handle.  The first call on a device handle
+ * allocates two tables of device memory (FPSCHED_ENOMEM), freed by fpsched_problem_destroy.
+ * FPSCHED_EINVAL for a negative value, FPSCHED_EOVERFLOW if D * max_stride * (max value + max
+ * comm) >= 2^31, FPSCHED_EUNSUPPORTED if no kernel fits these values.  While a table is set,
+ * fpsched_wslide returns FPSCHED_EUNSUPPORTED (the sliding pass knows one cost per (type, stage));
+ * fpsched_generate ignores costs anyway.  Works on a host-only handle (validation only). */
+int fpsched_problem_set_microbatch_costs(fpsched_problem *p, const int32_t *dur_mb);
 
 /* DEVICE buffers the caller owns (e.g. torch tensors); all must hold n_cand entries. */
 typedef struct {

@@ -61,6 +61,8 @@ def load_library():
         lib.fpsched_problem_destroy.argtypes = [vp]
         lib.fpsched_problem_info.restype = ctypes.c_int
         lib.fpsched_problem_info.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i32)]
+        lib.fpsched_problem_set_microbatch_costs.restype = ctypes.c_int
+        lib.fpsched_problem_set_microbatch_costs.argtypes = [vp, vp]
         lib.fpsched_problem_select_kernel.restype = ctypes.c_int
         lib.fpsched_problem_select_kernel.argtypes = [vp, ctypes.c_int]
         lib.fpsched_workspace_bytes.restype = ctypes.c_size_t
@@ -160,6 +162,19 @@ class Problem:
         rc = load_library().fpsched_problem_select_kernel(self._h, {"auto": 0, "general": 1, "slots": 2}[which])
         if rc != 0:
             raise FpschedError(rc, "fpsched_problem_select_kernel")
+
+    def set_microbatch_costs(self, dur_mb):
+        """dur_mb[8][S][m] (host array): per-micro-batch costs that replace dur[kind][stage] in evaluate;
+        None switches back (see fpsched_problem_set_microbatch_costs)."""
+        ptr = None
+        if dur_mb is not None:
+            table = np.ascontiguousarray(np.asarray(dur_mb, dtype=np.int32))
+            if table.shape != (NKINDS, self.S, self.m):
+                raise ValueError(f"dur_mb must be [{NKINDS}][{self.S}][{self.m}], got {table.shape}")
+            ptr = table.ctypes.data
+        rc = load_library().fpsched_problem_set_microbatch_costs(self._h, ptr)
+        if rc != 0:
+            raise FpschedError(rc, "fpsched_problem_set_microbatch_costs")
 
     # ---- host helpers -----------------------------------------------------
     def encode(self, items, device: int) -> np.ndarray:

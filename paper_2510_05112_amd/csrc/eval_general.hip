@@ -22,7 +22,7 @@ namespace fpsched {
 __global__ __launch_bounds__(64) void eval_general_kernel(
     DevTables T, const uint16_t* __restrict__ ops, long long n_cand, int stride,
     long long* __restrict__ out_makespan, long long* __restrict__ out_idle,
-    int* __restrict__ out_peak, unsigned char* __restrict__ out_flags) {
+    int* __restrict__ out_peak, unsigned char* __restrict__ out_flags, const int32_t* __restrict__ dur_mb) {
   extern __shared__ int32_t lds[];
   const int lane = threadIdx.x;
   const int S = T.S, m = T.m, SM = S * m;
@@ -98,7 +98,7 @@ __global__ __launch_bounds__(64) void eval_general_kernel(
               }
             }
             if (!blocked) {
-              const int dt = tab[T.off_dur + kind * S + s];
+              const int dt = dur_mb ? dur_mb[(kind * S + s) * m + j] : tab[T.off_dur + kind * S + s];
               const int u = tab[T.off_mem_units + s];
               const int fin = max(free_at, ready) + dt;
               if ((0xD2u >> kind) & 1u) {  // F, R, L, FD allocate at their start

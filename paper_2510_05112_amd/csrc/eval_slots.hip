@@ -104,20 +104,26 @@ __global__ void reset_counter_kernel(unsigned long long* counter, unsigned long 
   if (threadIdx.x == 0) *counter = value;
 }
 
-// TIMES = true is the first pass of the weight-gradient sliding (wslide.hip): the tables then
+// MODE kSlotTimes (TIMES below) is the first pass of the weight-gradient sliding (wslide.hip): the tables then
 // describe the lists without their W items (a W word is a no-op that always issues at once), and
 // instead of makespan, idle and peak the kernel writes, per op word, the time the op started
 // (<< 8; four positions of a device are 16 bytes, and the 16-byte pieces of a candidate's devices
 // for the same four positions lie side by side, [candidate][stride / 4][lanes per candidate][4]: the
 // lanes of a candidate pass a position at about the same time, so a line fills up quickly) and,
 // per device, the position at which its list stopped.
-template <int V, bool DEG2, bool ONE_CLASS, bool TIMES>
+//
+// MODE kSlotPerMicrobatch: the cost of an item depends on its micro-batch as well (micro-batches of
+// unequal size).  The duration then comes from mb_rows [32 metadata rows][lanes per candidate][m]
+// (cost << 8, zero for rows the device does not have) in device memory instead of the metadata row;
+// it is requested when the word is decoded and first needed one round later.
+template <int V, bool DEG2, bool ONE_CLASS, int MODE>
 __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     SlotTables T, const uint16_t* __restrict__ ops, long long n_cand, int stride,
     long long* __restrict__ out_makespan, long long* __restrict__ out_idle,
     int* __restrict__ out_peak, unsigned char* __restrict__ out_flags,
     unsigned long long* __restrict__ next_candidate, int draw_block,
-    uint32_t* __restrict__ out_start8, int32_t* __restrict__ out_stop) {
+    uint32_t* __restrict__ out_start8, int32_t* __restrict__ out_stop, const int32_t* __restrict__ mb_rows) {
+  constexpr bool TIMES = MODE == kSlotTimes, MBDUR = MODE == kSlotPerMicrobatch;
   extern __shared__ int32_t lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int m = T.m;
@@ -217,12 +223,17 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   int4 M = make_int4(0, 0, 15, 0);   // metadata row of the current word (an invalid row to begin with)
   int2 M2 = make_int2(0, 0);         // its second-edge row
   unsigned w_next = 0u;              // the word behind the current one
+  int dur_mb8 = 0;                   // MBDUR: cost << 8 of the current word
+  const unsigned mb_lane = (unsigned)d * (unsigned)m;   // this device's part of a row of mb_rows
+  const unsigned mb_row_ints = (unsigned)lpc * (unsigned)m;
   auto decode = [&](unsigned word) {
     const unsigned j = word & 0x7ffu;
     const unsigned jc = min(j, (unsigned)m - 1u);
     const unsigned c5 = word >> 11;
     // a micro-batch out of range reads row 0 (kind 0), which is invalid and never issues
     M = lds_read<int4>(__umul24(j == jc ? c5 : 0u, row_bytes) + meta_off);
+    // (c5 < 32, d < lanes per candidate, jc < m: inside the table whatever the word holds)
+    if (MBDUR) dur_mb8 = mb_rows[__umul24(c5, mb_row_ints) + mb_lane + jc];
     unsigned c = c5 & (unsigned)(V - 1);
     unsigned fwd = (word >> 13) & 1u;
     unsigned jw = jc >> 3;   // state word of the micro-batch inside its chunk
@@ -384,7 +395,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     // ---- decide.  An exhausted lane sits on a word of kind 0, whose metadata row is invalid; invalid
     // rows require state 15, which no activation is ever in.  Lanes without a device (and idle
     // segments) never initialise their LDS words, so they are masked off explicitly.
-    const unsigned dur8 = (unsigned)M.x, lat_tag = (unsigned)M.y, mx_ = (unsigned)M.z, my_ = (unsigned)M.w;
+    const unsigned dur8 = MBDUR ? (unsigned)dur_mb8 : (unsigned)M.x, lat_tag = (unsigned)M.y, mx_ = (unsigned)M.z, my_ = (unsigned)M.w;
     // Everything that can forbid the issue is OR-ed into the low byte of one word: wrong activation
     // state; input slot not tagged with the upstream stage (only if the op has an input: the top
     // byte of the last metadata dword is 0xff then, else 0).  A live lane has dead == 0, any other
@@ -506,13 +517,14 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   }
 }
 
-#define FPSCHED_INSTANTIATE(V, G, O)                                                                      \
-  template __global__ void eval_slot_kernel<V, G, O, false>(                                              \
+#define FPSCHED_INSTANTIATE_MODE(V, G, O, MODE)                                                           \
+  template __global__ void eval_slot_kernel<V, G, O, MODE>(                                               \
       SlotTables, const uint16_t*, long long, int, long long*, long long*, int*, unsigned char*,          \
-      unsigned long long*, int, uint32_t*, int32_t*);                                                     \
-  template __global__ void eval_slot_kernel<V, G, O, true>(                                               \
-      SlotTables, const uint16_t*, long long, int, long long*, long long*, int*, unsigned char*,          \
-      unsigned long long*, int, uint32_t*, int32_t*);
+      unsigned long long*, int, uint32_t*, int32_t*, const int32_t*);
+#define FPSCHED_INSTANTIATE(V, G, O)               \
+  FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotPlain)    \
+  FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotTimes)    \
+  FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotPerMicrobatch)
 FPSCHED_INSTANTIATE(1, false, true)
 FPSCHED_INSTANTIATE(2, false, true)
 FPSCHED_INSTANTIATE(4, false, true)
@@ -523,5 +535,6 @@ FPSCHED_INSTANTIATE(1, true, false)
 FPSCHED_INSTANTIATE(2, true, false)
 FPSCHED_INSTANTIATE(4, true, false)
 #undef FPSCHED_INSTANTIATE
+#undef FPSCHED_INSTANTIATE_MODE
 
 }  // namespace fpsched

@@ -39,6 +39,12 @@ struct fpsched_problem {
   SlotTables stab{};
   std::vector<int32_t> slot_ints;
   int32_t* d_slot_ints = nullptr;
+  // costs per micro-batch (fpsched_problem_set_microbatch_costs)
+  int64_t max_comm = 0;
+  bool mb_set = false;
+  bool mb_slots_ok = false;        // the table's values fit the slot kernel's 24-bit times
+  int32_t* d_mb_raw = nullptr;     // [kinds][S][m]
+  int32_t* d_mb_rows = nullptr;    // [32 metadata rows][lanes per candidate][m], << 8
 };
 
 namespace {
@@ -59,8 +65,8 @@ struct DeviceGuard {
 };
 
 using SlotKernel = void (*)(SlotTables, const uint16_t*, long long, int, long long*, long long*, int*,
-                            unsigned char*, unsigned long long*, int, uint32_t*, int32_t*);
-template <bool TIMES>
+                            unsigned char*, unsigned long long*, int, uint32_t*, int32_t*, const int32_t*);
+template <int TIMES>   // one of kSlotPlain, kSlotTimes, kSlotPerMicrobatch
 SlotKernel slot_kernel_of(int v, bool deg2, bool one_class) {
   if (deg2)
     return v == 1 ? &eval_slot_kernel<1, true, false, TIMES>
@@ -71,7 +77,7 @@ SlotKernel slot_kernel_of(int v, bool deg2, bool one_class) {
   return v == 1 ? &eval_slot_kernel<1, false, false, TIMES>
                 : (v == 2 ? &eval_slot_kernel<2, false, false, TIMES> : &eval_slot_kernel<4, false, false, TIMES>);
 }
-SlotKernel slot_kernel_ptr(int v, bool deg2, bool one_class) { return slot_kernel_of<false>(v, deg2, one_class); }
+SlotKernel slot_kernel_ptr(int v, bool deg2, bool one_class) { return slot_kernel_of<kSlotPlain>(v, deg2, one_class); }
 
 int next_pow2(int x) {
   int p = 1;
@@ -161,6 +167,7 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
     if (bound >= (int64_t)1 << 31 || units_total >= (int64_t)1 << 31) rc = FPSCHED_EOVERFLOW;
   }
   if (rc != FPSCHED_OK) { delete p; return rc; }
+  p->max_comm = max_comm;
 
   // table image
   std::vector<int32_t>& I = p->host_ints;
@@ -419,7 +426,7 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
         p->stab_times = p->stab;
         const bool up = hipMalloc(&p->d_times_ints, J.size() * sizeof(int32_t)) == hipSuccess &&
                         hipMemcpy(p->d_times_ints, J.data(), J.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess &&
-                        hipFuncSetAttribute(reinterpret_cast<const void*>(slot_kernel_of<true>(p->slot_v, p->slot_deg2, p->stab.n_classes == 1)),
+                        hipFuncSetAttribute(reinterpret_cast<const void*>(slot_kernel_of<kSlotTimes>(p->slot_v, p->slot_deg2, p->stab.n_classes == 1)),
                                             hipFuncAttributeMaxDynamicSharedMemorySize, p->slot_lds_bytes + 16) == hipSuccess &&
                         hipFuncSetAttribute(reinterpret_cast<const void*>(&wslide_place_kernel),
                                             hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -453,6 +460,8 @@ void fpsched_problem_destroy(fpsched_problem* p) {
     if (p->d_ints) (void)hipFree(p->d_ints);
     if (p->d_slot_ints) (void)hipFree(p->d_slot_ints);
     if (p->d_times_ints) (void)hipFree(p->d_times_ints);
+    if (p->d_mb_raw) (void)hipFree(p->d_mb_raw);
+    if (p->d_mb_rows) (void)hipFree(p->d_mb_rows);
   }
   delete p;
 }
@@ -505,7 +514,7 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
   if (reinterpret_cast<uintptr_t>(d_ops) & 15) return FPSCHED_EINVAL;
   DeviceGuard g(p->device_id);
   if (!g.ok) return FPSCHED_EHIP;
-  if (p->use_slots) {
+  if (p->use_slots && (!p->mb_set || p->mb_slots_ok)) {
     // the first 8 bytes of the workspace hold the counter the segments draw candidates from
     if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) & 15)) return FPSCHED_EINVAL;
     if (workspace_bytes < 256) return FPSCHED_ENOMEM;
@@ -520,11 +529,13 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
     // segment g starts on candidate g; the counter hands out the candidates after those
     hipLaunchKernelGGL(reset_counter_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(hip_stream), counter,
                        (unsigned long long)(blocks * per_block));
-    hipLaunchKernelGGL(slot_kernel_ptr(p->slot_v, p->slot_deg2, p->stab.n_classes == 1), dim3((unsigned)blocks), dim3(64 * p->slot_waves),
+    const SlotKernel kernel = p->mb_set ? slot_kernel_of<kSlotPerMicrobatch>(p->slot_v, p->slot_deg2, p->stab.n_classes == 1)
+                                        : slot_kernel_ptr(p->slot_v, p->slot_deg2, p->stab.n_classes == 1);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(64 * p->slot_waves),
                        (size_t)p->slot_lds_bytes, static_cast<hipStream_t>(hip_stream), p->stab, d_ops,
                        (long long)n_cand, (int)stride_words, reinterpret_cast<long long*>(out.makespan),
                        reinterpret_cast<long long*>(out.idle), out.peak, out.flags, counter, draw_block,
-                       (uint32_t*)nullptr, (int32_t*)nullptr);
+                       (uint32_t*)nullptr, (int32_t*)nullptr, (const int32_t*)(p->mb_set ? p->d_mb_rows : nullptr));
     return check_hip(hipGetLastError());
   }
   const int cpw = p->tables.cands_per_wave;
@@ -533,8 +544,61 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
   hipLaunchKernelGGL(eval_general_kernel, dim3((unsigned)blocks), dim3(64), (size_t)p->lds_bytes,
                      static_cast<hipStream_t>(hip_stream), p->tables, d_ops, (long long)n_cand,
                      (int)stride_words, reinterpret_cast<long long*>(out.makespan),
-                     reinterpret_cast<long long*>(out.idle), out.peak, out.flags);
+                     reinterpret_cast<long long*>(out.idle), out.peak, out.flags,
+                     (const int32_t*)(p->mb_set ? p->d_mb_raw : nullptr));
   return check_hip(hipGetLastError());
+}
+
+int fpsched_problem_set_microbatch_costs(fpsched_problem* p, const int32_t* dur_mb) {
+  if (!p) return FPSCHED_EINVAL;
+  if (!dur_mb) {
+    p->mb_set = false;   // the tables stay allocated for the next call
+    return FPSCHED_OK;
+  }
+  const int D = p->D, S = p->S, m = p->m;
+  const size_t n_raw = (size_t)kNKinds * S * m;
+  int64_t max_dur = 0;
+  for (size_t i = 0; i < n_raw; ++i) {
+    if (dur_mb[i] < 0) return FPSCHED_EINVAL;
+    max_dur = std::max<int64_t>(max_dur, dur_mb[i]);
+  }
+  const int64_t bound = (int64_t)D * p->max_stride * (max_dur + p->max_comm);
+  if (bound >= (int64_t)1 << 31) return FPSCHED_EOVERFLOW;
+  const bool fits_slots = bound < (1ll << 24);
+  if (p->device_id < 0) {
+    p->mb_set = true;
+    p->mb_slots_ok = fits_slots;
+    return FPSCHED_OK;
+  }
+  if (!(p->slots_ok && fits_slots) && !p->general_ok) return FPSCHED_EUNSUPPORTED;
+  const int lpc = p->tables.lanes_per_cand;
+  const size_t n_rows = (size_t)kNKinds * kMaxChunks * lpc * m;
+  std::vector<int32_t> rows(n_rows, 0);
+  for (int kind = 1; kind < kNKinds; ++kind)
+    for (int c = 0; c < kMaxChunks; ++c)
+      for (int d = 0; d < D; ++d) {
+        if (c >= p->n_chunks[d]) continue;
+        const int s = p->local_stage[(size_t)d * kMaxChunks + c];
+        for (int j = 0; j < m; ++j)
+          rows[(((size_t)kind * kMaxChunks + c) * lpc + d) * m + j] =
+              fits_slots ? (int32_t)((unsigned)dur_mb[((size_t)kind * S + s) * m + j] << 8) : 0;
+      }
+  DeviceGuard g(p->device_id);
+  if (!g.ok) return FPSCHED_EHIP;
+  // work that reads the previous table must be over before it is overwritten
+  if (hipDeviceSynchronize() != hipSuccess) return FPSCHED_EHIP;
+  if (!p->d_mb_raw && hipMalloc(&p->d_mb_raw, n_raw * sizeof(int32_t)) != hipSuccess) { p->d_mb_raw = nullptr; return FPSCHED_ENOMEM; }
+  if (!p->d_mb_rows && hipMalloc(&p->d_mb_rows, n_rows * sizeof(int32_t)) != hipSuccess) { p->d_mb_rows = nullptr; return FPSCHED_ENOMEM; }
+  if (hipMemcpy(p->d_mb_raw, dur_mb, n_raw * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess ||
+      hipMemcpy(p->d_mb_rows, rows.data(), n_rows * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess)
+    return FPSCHED_EHIP;
+  if (p->slots_ok && fits_slots &&
+      hipFuncSetAttribute(reinterpret_cast<const void*>(slot_kernel_of<kSlotPerMicrobatch>(p->slot_v, p->slot_deg2, p->stab.n_classes == 1)),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, p->slot_lds_bytes) != hipSuccess)
+    return FPSCHED_EHIP;
+  p->mb_set = true;
+  p->mb_slots_ok = p->slots_ok && fits_slots;
+  return FPSCHED_OK;
 }
 
 int fpsched_generate(const fpsched_problem* p, const fpsched_actor_policy* d_policy, const int32_t* d_inflight,
@@ -684,7 +748,7 @@ int fpsched_wslide(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_ca
   if (!p || n_cand < 0) return FPSCHED_EINVAL;
   if (p->device_id < 0) return FPSCHED_ENODEV;
   if (!p->has_w) return FPSCHED_EINVAL;
-  if (!p->slide_ok) return FPSCHED_EUNSUPPORTED;
+  if (!p->slide_ok || p->mb_set) return FPSCHED_EUNSUPPORTED;   // the pass knows one cost per (type, stage)
   if (n_cand == 0) return FPSCHED_OK;
   if (!d_ops || !d_ops_out || !out.makespan || !out.idle || !out.peak || !out.flags) return FPSCHED_EINVAL;
   if (stride_words < 8 || (stride_words & 7) || stride_words > p->max_stride) return FPSCHED_EINVAL;
@@ -709,10 +773,10 @@ int fpsched_wslide(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_ca
   const int64_t row_words = (int64_t)p->D * stride_words;
   const int draw_block = (int)std::clamp<int64_t>((12288 + row_words - 1) / row_words, 1, p->stab.cands_per_wave);
   hipLaunchKernelGGL(reset_counter_kernel, dim3(1), dim3(64), 0, st, counter, (unsigned long long)(blocks * per_block));
-  hipLaunchKernelGGL(slot_kernel_of<true>(p->slot_v, p->slot_deg2, p->stab.n_classes == 1), dim3((unsigned)blocks),
+  hipLaunchKernelGGL(slot_kernel_of<kSlotTimes>(p->slot_v, p->slot_deg2, p->stab.n_classes == 1), dim3((unsigned)blocks),
                      dim3(64 * p->slot_waves), (size_t)p->slot_lds_bytes + 16, st, p->stab_times, d_ops, (long long)n_cand,
                      (int)stride_words, (long long*)nullptr, (long long*)nullptr, (int*)nullptr, timed_flags, counter,
-                     draw_block, starts, stops);
+                     draw_block, starts, stops, (const int32_t*)nullptr);
   if (hipGetLastError() != hipSuccess) return FPSCHED_EHIP;
   // pass 2: every row places its W items on its own
   hipLaunchKernelGGL(wslide_place_kernel, dim3((unsigned)place_blocks), dim3(kSlideThreads),

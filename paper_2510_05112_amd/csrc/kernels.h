@@ -14,9 +14,10 @@ struct Key {
 constexpr int kTile = 2048;
 constexpr int kTopkThreads = 1024;
 
+// dur_mb: nullptr, or costs per micro-batch [kinds][S][m] in device memory that replace the table's.
 __global__ void eval_general_kernel(DevTables T, const uint16_t* ops, long long n_cand, int stride,
                                     long long* out_makespan, long long* out_idle, int* out_peak,
-                                    unsigned char* out_flags);
+                                    unsigned char* out_flags, const int32_t* dur_mb);
 
 constexpr int kSlotMaxWaves = 16;
 constexpr int kSlotMaxThreads = 64 * kSlotMaxWaves;
@@ -25,14 +26,17 @@ constexpr int kSlotMaxThreads = 64 * kSlotMaxWaves;
 // has two inputs or two outputs in the stage DAG.  ONE_CLASS = the DAG is a single chain.
 // next_candidate: a counter in device memory, preset to the number of segments in the grid, from
 // which wavefronts draw their work, draw_block candidates per atomic (1 <= draw_block <= 64).
-// TIMES: first pass of the weight-gradient sliding; writes out_start8 [n_cand][stride / 4][lanes per
+// MODE kSlotTimes: first pass of the weight-gradient sliding; writes out_start8 [n_cand][stride / 4][lanes per
 // candidate][4] (start time << 8 of the op at each position), out_stop [n_cand][D] (words issued per device) and out_flags
 // (DEADLOCK / INCOMPLETE only) instead of makespan, idle and peak; needs 16 bytes of LDS more.
-template <int V, bool DEG2, bool ONE_CLASS, bool TIMES>
+// MODE kSlotPerMicrobatch: durations from mb_rows [32][lanes per candidate][m] (cost << 8 per metadata
+// row, device and micro-batch) instead of the metadata rows.
+constexpr int kSlotPlain = 0, kSlotTimes = 1, kSlotPerMicrobatch = 2;
+template <int V, bool DEG2, bool ONE_CLASS, int MODE>
 __global__ void eval_slot_kernel(SlotTables T, const uint16_t* ops, long long n_cand, int stride,
                                  long long* out_makespan, long long* out_idle, int* out_peak,
                                  unsigned char* out_flags, unsigned long long* next_candidate, int draw_block,
-                                 uint32_t* out_start8, int32_t* out_stop);
+                                 uint32_t* out_start8, int32_t* out_stop, const int32_t* mb_rows);
 
 __global__ void reset_counter_kernel(unsigned long long* counter, unsigned long long value);
 

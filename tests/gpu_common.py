@@ -9,8 +9,9 @@ import paper_2510_05112_amd as fp
 KERNELS = ("slots", "general")
 
 
-def gpu_evaluate(problem, words, k=None, max_stride=None, kernel="auto"):
-    """words: uint16 [C][D][stride] (numpy).  Returns (results dict of numpy arrays, topk tuple or None)."""
+def gpu_evaluate(problem, words, k=None, max_stride=None, kernel="auto", dur_mb=None):
+    """words: uint16 [C][D][stride] (numpy).  Returns (results dict of numpy arrays, topk tuple or None).
+    dur_mb[8][S][m]: costs per micro-batch, set on the handle before the batch is evaluated."""
     words = np.ascontiguousarray(words, dtype=np.uint16)
     C, D, stride = words.shape
     h = fp.Problem(problem, max_stride or stride, device=0)
@@ -21,6 +22,8 @@ def gpu_evaluate(problem, words, k=None, max_stride=None, kernel="auto"):
             raise
         h.close()
         return None, None
+    if dur_mb is not None:
+        h.set_microbatch_costs(dur_mb)
     ops = torch.from_numpy(words.view(np.int16)).cuda() if C else torch.empty((0, D, stride), dtype=torch.int16, device="cuda")
     res = h.evaluate(ops)
     top = None
@@ -43,12 +46,12 @@ def assert_same(gpu, ref, what=""):
                                  f"gpu {a[bad[0]]} oracle {b[bad[0]]}")
 
 
-def check_batch(problem, words, k=None, what="", threads=8, kernels=KERNELS):
+def check_batch(problem, words, k=None, what="", threads=8, kernels=KERNELS, dur_mb=None):
     """Every kernel variant of the library against the oracle, element by element."""
-    ref = oracle.evaluate(problem, words, threads=threads)
+    ref = oracle.evaluate(problem, words, threads=threads, dur_mb=dur_mb)
     gpu, ran = None, 0
     for kernel in kernels:
-        g, top = gpu_evaluate(problem, words, k, kernel=kernel)
+        g, top = gpu_evaluate(problem, words, k, kernel=kernel, dur_mb=dur_mb)
         if g is None:
             continue
         gpu, ran = g, ran + 1

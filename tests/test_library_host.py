@@ -57,6 +57,19 @@ def test_host_only_handle_and_errors():
     assert lib.fpsched_pareto(p._h, none, 1, 0, 1, 1, 1, 1, 0, 0, 0) == -1
     assert lib.fpsched_topk(p._h, none, 1, 2000, 1, 1, 1, 0, 0, 0) == -1
     assert lib.fpsched_pareto(p._h, none, (1 << 24) + 1, 4, 1, 1, 1, 1, 1, 1 << 40, 0) == -1   # more tiles than cursors
+    # costs per micro-batch are validated on the host: shape, sign, the int32 time bound
+    table = workloads.microbatch_costs(spec.problem)
+    p.set_microbatch_costs(table)
+    p.set_microbatch_costs(None)
+    with pytest.raises(ValueError):
+        p.set_microbatch_costs(table[:, :, :-1])
+    for value, code in ((-1, -1), (1 << 30, -4)):
+        wrong = table.copy()
+        wrong[2, -1, -1] = value
+        with pytest.raises(fp.FpschedError) as e:
+            p.set_microbatch_costs(wrong)
+        assert e.value.code == code
+    assert lib.fpsched_problem_set_microbatch_costs(None, None) == -1
     p.close()
     # bad descriptions
     bad = chain_problem(4, 8)

@@ -232,6 +232,16 @@ def policy_sets(problem: Problem, n: int, seed: int = BASE_SEED + 100):
     return pol, np.broadcast_to(inflight, (n, S)).copy()
 
 
+def microbatch_costs(problem: Problem, seed: int = BASE_SEED + 200) -> np.ndarray:
+    """Seeded costs per micro-batch, int32 [NKINDS][S][m]: the problem's cost of every (type, stage)
+    scaled by a per-micro-batch factor drawn uniformly from [1/2, 3/2) in steps of 1/256 and rounded to
+    the nearest integer -- micro-batches that pack sequences of unequal total length."""
+    rng = np.random.default_rng(seed)
+    base = np.asarray(problem.dur, np.int64).reshape(NKINDS, problem.n_stages)[:, :, None]
+    factor = rng.integers(128, 384, problem.n_microbatches)[None, None, :]
+    return ((base * factor + 128) >> 8).astype(np.int32)
+
+
 def generator_stride(problem: Problem) -> int:
     """Row stride (words, multiple of 8) that holds the longest list the scheduler can emit."""
     per_dev = int(np.bincount(problem.stage_device, minlength=problem.n_devices).max())
