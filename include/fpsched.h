@@ -126,7 +126,8 @@ void fpsched_problem_destroy(fpsched_problem *p);
  * not run concurrently with other calls on the handle.  The first call on a device handle
  * allocates two tables of device memory (FPSCHED_ENOMEM), freed by fpsched_problem_destroy.
  * FPSCHED_EINVAL for a negative value, FPSCHED_EOVERFLOW if D * max_stride * (max value + max
- * comm) >= 2^31, FPSCHED_EUNSUPPORTED if no kernel fits these values.  While a table is set,
+ * comm) >= 2^31, FPSCHED_EUNSUPPORTED if no kernel fits these values: the handle then keeps
+ * what it had.  After FPSCHED_EHIP / FPSCHED_ENOMEM it is back on desc.dur.  While a table is set,
  * fpsched_wslide returns FPSCHED_EUNSUPPORTED (the sliding pass knows one cost per (type, stage));
  * fpsched_generate ignores costs anyway.  Works on a host-only handle (validation only). */
 int fpsched_problem_set_microbatch_costs(fpsched_problem *p, const int32_t *dur_mb);

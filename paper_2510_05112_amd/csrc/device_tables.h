@@ -38,7 +38,7 @@ struct DevTables {
   const int32_t* ints;      // DEVICE
 };
 
-// Slot kernel tables.  `ints` = [meta][meta2][pad to 512 ints][dev][expect]:
+// Slot kernel tables.  `ints` = [meta][meta2][pad to 512 ints][costs per micro-batch, if any][dev][expect]:
 //   meta  [kNKinds * 4][lanes_per_cand] x 4 ints, one 16-byte row per (top five bits of the op
 //     word = kind * 4 + chunk, device):
 //     x = dur << 8
@@ -65,6 +65,9 @@ constexpr unsigned kMetaHasProd = 1u << 30;
 constexpr unsigned kMetaHasCons = 1u << 31;
 constexpr unsigned kEmptySlot = 0x000000ffu;  // finish 0, tag 0xff = no stage
 
+// dwords of one device's row of costs per micro-batch (one or two bytes each): enough for m values, and odd
+constexpr unsigned slot_mb_row_dwords(int m, int value_bytes) { return (((unsigned)m * (unsigned)value_bytes + 3u) >> 2) | 1u; }
+
 struct SlotTables {
   int32_t D, m;
   int32_t lanes_per_cand;   // power of two >= D
@@ -79,6 +82,12 @@ struct SlotTables {
   int32_t off_dev;          // in ints
   int32_t dev_ints;         // 2 + 4V
   int32_t off_expect;       // in ints
+  int32_t off_mb;           // in ints; costs per micro-batch inside the shared part (0 = none): values of
+                            // mb_value_bytes (1 or 2) bytes, [block][chunk < V][lanes_per_cand][row of
+                            // slot_mb_row_dwords(m, bytes) dwords], padded to a multiple of 512 ints
+  int32_t mb_value_bytes;
+  uint32_t mb_kind_map;     // four bits per kind: which block of the table at off_mb holds the kind's costs
+                            // (kinds with the same costs share a block)
   const int32_t* ints;      // DEVICE
 };
 

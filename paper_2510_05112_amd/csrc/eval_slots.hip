@@ -115,7 +115,10 @@ __global__ void reset_counter_kernel(unsigned long long* counter, unsigned long 
 // MODE kSlotPerMicrobatch: the cost of an item depends on its micro-batch as well (micro-batches of
 // unequal size).  The duration then comes from mb_rows [32 metadata rows][lanes per candidate][m]
 // (cost << 8, zero for rows the device does not have) in device memory instead of the metadata row;
-// it is requested when the word is decoded and first needed one round later.
+// it is requested when the word is decoded and first needed one round later.  That wait also
+// covers the op-window load in flight, so the form is about twice as slow as the plain kernel.
+// MODE kSlotPerMicrobatchLds: the same costs as values of one or two bytes in the shared part of LDS
+// (T.off_mb), read like the metadata row; the host picks it when the table fits.
 template <int V, bool DEG2, bool ONE_CLASS, int MODE>
 __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     SlotTables T, const uint16_t* __restrict__ ops, long long n_cand, int stride,
@@ -123,7 +126,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     int* __restrict__ out_peak, unsigned char* __restrict__ out_flags,
     unsigned long long* __restrict__ next_candidate, int draw_block,
     uint32_t* __restrict__ out_start8, int32_t* __restrict__ out_stop, const int32_t* __restrict__ mb_rows) {
-  constexpr bool TIMES = MODE == kSlotTimes, MBDUR = MODE == kSlotPerMicrobatch;
+  constexpr bool TIMES = MODE == kSlotTimes, MBDUR = MODE == kSlotPerMicrobatch, MBLDS = MODE == kSlotPerMicrobatchLds;
   extern __shared__ int32_t lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int m = T.m;
@@ -226,6 +229,16 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   int dur_mb8 = 0;                   // MBDUR: cost << 8 of the current word
   const unsigned mb_lane = (unsigned)d * (unsigned)m;   // this device's part of a row of mb_rows
   const unsigned mb_row_ints = (unsigned)lpc * (unsigned)m;
+  // MBLDS: [block of the kind][chunk][device][micro-batch] costs of one or two bytes (kind 0 maps to block 0).
+  // A device's row is an odd number of dwords long, so that the lanes of a candidate, which mostly ask
+  // for the same micro-batch, fall into different banks.
+  unsigned dur_mb16 = 0;
+  const bool mb_wide = T.mb_value_bytes == 2;   // else one byte per value
+  const unsigned mb_dev_bytes = slot_mb_row_dwords(m, T.mb_value_bytes) * 4u;
+  const unsigned mb_chunk_bytes = (unsigned)lpc * mb_dev_bytes, mb_kind_bytes = mb_chunk_bytes * (unsigned)V;
+  unsigned mb_lds_lane = lds0 + (unsigned)T.off_mb * 4u + (unsigned)d * mb_dev_bytes;
+  const unsigned mb_kind_map = T.mb_kind_map;
+  if (MBLDS) asm volatile("" : "+v"(mb_lds_lane));
   auto decode = [&](unsigned word) {
     const unsigned j = word & 0x7ffu;
     const unsigned jc = min(j, (unsigned)m - 1u);
@@ -243,6 +256,12 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     unsigned chunk_at = __umul24(c, chunk_bytes) + stt_off;
     asm("" : "+v"(chunk_at));
     at_state = (jw << 8) + chunk_at;
+    if (MBLDS) {
+      const unsigned block = __builtin_amdgcn_ubfe(mb_kind_map, c5 & 0x1cu, 3);   // nibble `kind` of the map
+      const unsigned at_row = __umul24(block, mb_kind_bytes) + mb_lds_lane + __umul24(c, mb_chunk_bytes);
+      if (mb_wide) dur_mb16 = lds_read<uint16_t>(at_row + (jc << 1));
+      else dur_mb16 = lds_read<uint8_t>(at_row + jc);
+    }
     if (TIMES) at_state = (word >> 13) == (unsigned)kW ? lds0 + zero_off : at_state;
     at_slot = (jc << 2) + slot_base;   // slot j of the first class; low five bits = 4 (j & 7)
     const bool is_b = (word >> 13) == (unsigned)kB;
@@ -395,7 +414,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     // ---- decide.  An exhausted lane sits on a word of kind 0, whose metadata row is invalid; invalid
     // rows require state 15, which no activation is ever in.  Lanes without a device (and idle
     // segments) never initialise their LDS words, so they are masked off explicitly.
-    const unsigned dur8 = MBDUR ? (unsigned)dur_mb8 : (unsigned)M.x, lat_tag = (unsigned)M.y, mx_ = (unsigned)M.z, my_ = (unsigned)M.w;
+    const unsigned dur8 = MBDUR ? (unsigned)dur_mb8 : (MBLDS ? dur_mb16 << 8 : (unsigned)M.x), lat_tag = (unsigned)M.y, mx_ = (unsigned)M.z, my_ = (unsigned)M.w;
     // Everything that can forbid the issue is OR-ed into the low byte of one word: wrong activation
     // state; input slot not tagged with the upstream stage (only if the op has an input: the top
     // byte of the last metadata dword is 0xff then, else 0).  A live lane has dead == 0, any other
@@ -524,7 +543,8 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
 #define FPSCHED_INSTANTIATE(V, G, O)               \
   FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotPlain)    \
   FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotTimes)    \
-  FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotPerMicrobatch)
+  FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotPerMicrobatch) \
+  FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotPerMicrobatchLds)
 FPSCHED_INSTANTIATE(1, false, true)
 FPSCHED_INSTANTIATE(2, false, true)
 FPSCHED_INSTANTIATE(4, false, true)

@@ -1,5 +1,6 @@
 // C ABI of libfpsched: problem handles, host-side helpers and kernel launches.
 #include <hip/hip_runtime.h>
+#include <stdio.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -45,6 +46,12 @@ struct fpsched_problem {
   bool mb_slots_ok = false;        // the table's values fit the slot kernel's 24-bit times
   int32_t* d_mb_raw = nullptr;     // [kinds][S][m]
   int32_t* d_mb_rows = nullptr;    // [32 metadata rows][lanes per candidate][m], << 8
+  // ... or, when the values fit sixteen bits and the table fits LDS, inside a second table image
+  bool mb_in_lds = false;
+  SlotTables stab_mb{};
+  int32_t* d_mb_image = nullptr;
+  size_t mb_image_ints = 0;
+  int32_t mb_waves = 0, mb_grid = 0, mb_lds_bytes = 0;
 };
 
 namespace {
@@ -78,6 +85,31 @@ SlotKernel slot_kernel_of(int v, bool deg2, bool one_class) {
                 : (v == 2 ? &eval_slot_kernel<2, false, false, TIMES> : &eval_slot_kernel<4, false, false, TIMES>);
 }
 SlotKernel slot_kernel_ptr(int v, bool deg2, bool one_class) { return slot_kernel_of<kSlotPlain>(v, deg2, one_class); }
+
+// Workgroup shape of the slot kernel for a shared LDS part of n_shared_ints dwords: candidates per
+// wavefront, then the split of a compute unit's LDS into workgroups that keeps the most wavefronts
+// resident (LDS is the only limiter: ~50 VGPRs).  Returns wavefronts per workgroup (0 = does not fit).
+struct SlotGeometry { int cands_per_wave, wave_ints, waves, groups; };
+SlotGeometry slot_geometry(int64_t n_shared_ints, int lanes_per_cand, int state_words, int slots_per_cand, int max_lds) {
+  int scpw = 64 / lanes_per_cand;
+  const int64_t fixed = 64ll * (8 + state_words);  // 16 op words + state words per lane
+  const int64_t lds_ints = max_lds / 4;
+  while (scpw > 1 && n_shared_ints + fixed + (int64_t)scpw * slots_per_cand > lds_ints) scpw >>= 1;
+  const int64_t wave_ints = fixed + (int64_t)scpw * slots_per_cand;
+  int best_waves = 0, best_groups = 0, best_total = 0;
+  for (int groups = 1; groups <= 8; ++groups) {
+    const int64_t per_group = lds_ints / groups - n_shared_ints - 64;  // allocation slack
+    int wv = per_group > 0 ? (int)std::min<int64_t>(per_group / wave_ints, kSlotMaxWaves) : 0;
+    wv = std::min(wv, 32 / groups);  // 8 wavefronts per SIMD, 4 SIMDs per compute unit
+    if (wv * groups > best_total) { best_total = wv * groups; best_waves = wv; best_groups = groups; }
+  }
+  // tuning knob: FPSCHED_SLOT_WAVES=n caps the wavefronts per workgroup (one workgroup per CU)
+  if (const char* env = getenv("FPSCHED_SLOT_WAVES")) {
+    const int cap_waves = atoi(env);
+    if (cap_waves >= 1 && cap_waves < best_waves * best_groups) { best_waves = std::min(cap_waves, best_waves); best_groups = 1; }
+  }
+  return SlotGeometry{scpw, (int)wave_ints, best_waves, std::max(best_groups, 1)};
+}
 
 int next_pow2(int x) {
   int p = 1;
@@ -356,25 +388,12 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
       ST.off_meta2 = n_meta;
       ST.off_dev = n_shared;
       ST.dev_ints = dev_ints;
-      // geometry: candidates per wave, then the workgroup shape that keeps the most
-      // wavefronts resident on a compute unit (LDS is the only limiter: ~50 VGPRs)
-      int scpw = 64 / lpc;
-      const int64_t fixed = 64ll * (8 + ST.state_words);  // 16 op words + state words per lane
-      const int64_t lds_ints = max_lds / 4;
-      while (scpw > 1 && ST.n_shared_ints + fixed + (int64_t)scpw * ST.slots_per_cand > lds_ints) scpw >>= 1;
-      const int64_t wave_ints = fixed + (int64_t)scpw * ST.slots_per_cand;
-      int best_waves = 0, best_groups = 0, best_total = 0;
-      for (int groups = 1; groups <= 8; ++groups) {
-        const int64_t per_group = lds_ints / groups - ST.n_shared_ints - 64;  // allocation slack
-        int wv = per_group > 0 ? (int)std::min<int64_t>(per_group / wave_ints, kSlotMaxWaves) : 0;
-        wv = std::min(wv, 32 / groups);  // 8 wavefronts per SIMD, 4 SIMDs per compute unit
-        if (wv * groups > best_total) { best_total = wv * groups; best_waves = wv; best_groups = groups; }
-      }
-      // tuning knob: FPSCHED_SLOT_WAVES=n caps the wavefronts per workgroup (one workgroup per CU)
-      if (const char* env = getenv("FPSCHED_SLOT_WAVES")) {
-        const int cap_waves = atoi(env);
-        if (cap_waves >= 1 && cap_waves < best_waves * best_groups) { best_waves = std::min(cap_waves, best_waves); best_groups = 1; }
-      }
+      ST.off_mb = 0;
+      ST.mb_kind_map = 0;
+      ST.mb_value_bytes = 2;
+      const SlotGeometry geo = slot_geometry(ST.n_shared_ints, lpc, ST.state_words, ST.slots_per_cand, max_lds);
+      const int scpw = geo.cands_per_wave, best_waves = geo.waves, best_groups = geo.groups;
+      const int64_t wave_ints = geo.wave_ints;
       p->slots_ok = fits && best_waves >= 1;
       ST.cands_per_wave = scpw;
       ST.wave_ints = (int32_t)wave_ints;
@@ -462,6 +481,7 @@ void fpsched_problem_destroy(fpsched_problem* p) {
     if (p->d_times_ints) (void)hipFree(p->d_times_ints);
     if (p->d_mb_raw) (void)hipFree(p->d_mb_raw);
     if (p->d_mb_rows) (void)hipFree(p->d_mb_rows);
+    if (p->d_mb_image) (void)hipFree(p->d_mb_image);
   }
   delete p;
 }
@@ -519,23 +539,32 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
     if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) & 15)) return FPSCHED_EINVAL;
     if (workspace_bytes < 256) return FPSCHED_ENOMEM;
     unsigned long long* counter = static_cast<unsigned long long*>(d_workspace);
-    const int per_block = p->stab.cands_per_wave * p->slot_waves;
-    const int64_t blocks = std::min<int64_t>((n_cand + per_block - 1) / per_block, p->slot_grid);
+    // costs per micro-batch: their own table image and workgroup shape when the table sits in LDS
+    const bool mb_lds = p->mb_set && p->mb_in_lds;
+    const SlotTables& tab = mb_lds ? p->stab_mb : p->stab;
+    const int waves = mb_lds ? p->mb_waves : p->slot_waves;
+    const int grid = mb_lds ? p->mb_grid : p->slot_grid;
+    const size_t lds_bytes = (size_t)(mb_lds ? p->mb_lds_bytes : p->slot_lds_bytes);
+    const int per_block = tab.cands_per_wave * waves;
+    const int64_t blocks = std::min<int64_t>((n_cand + per_block - 1) / per_block, grid);
     // Candidates per atomic draw.  Atomics on one address complete at some 8e7 per second; a batch of
     // long candidates stays far below that and is drawn one by one (best balance at the end of the
     // batch), short rows are drawn several at a time: about one draw per 12 K op words.
     const int64_t row_words = (int64_t)p->D * stride_words;
-    const int draw_block = (int)std::clamp<int64_t>((12288 + row_words - 1) / row_words, 1, p->stab.cands_per_wave);
+    const int draw_block = (int)std::clamp<int64_t>((12288 + row_words - 1) / row_words, 1, tab.cands_per_wave);
     // segment g starts on candidate g; the counter hands out the candidates after those
     hipLaunchKernelGGL(reset_counter_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(hip_stream), counter,
                        (unsigned long long)(blocks * per_block));
-    const SlotKernel kernel = p->mb_set ? slot_kernel_of<kSlotPerMicrobatch>(p->slot_v, p->slot_deg2, p->stab.n_classes == 1)
-                                        : slot_kernel_ptr(p->slot_v, p->slot_deg2, p->stab.n_classes == 1);
-    hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(64 * p->slot_waves),
-                       (size_t)p->slot_lds_bytes, static_cast<hipStream_t>(hip_stream), p->stab, d_ops,
+    const bool one_class = p->stab.n_classes == 1;
+    const SlotKernel kernel = !p->mb_set ? slot_kernel_ptr(p->slot_v, p->slot_deg2, one_class)
+                              : (mb_lds ? slot_kernel_of<kSlotPerMicrobatchLds>(p->slot_v, p->slot_deg2, one_class)
+                                        : slot_kernel_of<kSlotPerMicrobatch>(p->slot_v, p->slot_deg2, one_class));
+    hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(64 * waves), lds_bytes,
+                       static_cast<hipStream_t>(hip_stream), tab, d_ops,
                        (long long)n_cand, (int)stride_words, reinterpret_cast<long long*>(out.makespan),
                        reinterpret_cast<long long*>(out.idle), out.peak, out.flags, counter, draw_block,
-                       (uint32_t*)nullptr, (int32_t*)nullptr, (const int32_t*)(p->mb_set ? p->d_mb_rows : nullptr));
+                       (uint32_t*)nullptr, (int32_t*)nullptr,
+                       (const int32_t*)(p->mb_set && !mb_lds ? p->d_mb_rows : nullptr));
     return check_hip(hipGetLastError());
   }
   const int cpw = p->tables.cands_per_wave;
@@ -587,6 +616,7 @@ int fpsched_problem_set_microbatch_costs(fpsched_problem* p, const int32_t* dur_
   if (!g.ok) return FPSCHED_EHIP;
   // work that reads the previous table must be over before it is overwritten
   if (hipDeviceSynchronize() != hipSuccess) return FPSCHED_EHIP;
+  p->mb_set = false;   // a failure from here on leaves the handle on the costs of its description
   if (!p->d_mb_raw && hipMalloc(&p->d_mb_raw, n_raw * sizeof(int32_t)) != hipSuccess) { p->d_mb_raw = nullptr; return FPSCHED_ENOMEM; }
   if (!p->d_mb_rows && hipMalloc(&p->d_mb_rows, n_rows * sizeof(int32_t)) != hipSuccess) { p->d_mb_rows = nullptr; return FPSCHED_ENOMEM; }
   if (hipMemcpy(p->d_mb_raw, dur_mb, n_raw * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess ||
@@ -596,6 +626,79 @@ int fpsched_problem_set_microbatch_costs(fpsched_problem* p, const int32_t* dur_
       hipFuncSetAttribute(reinterpret_cast<const void*>(slot_kernel_of<kSlotPerMicrobatch>(p->slot_v, p->slot_deg2, p->stab.n_classes == 1)),
                           hipFuncAttributeMaxDynamicSharedMemorySize, p->slot_lds_bytes) != hipSuccess)
     return FPSCHED_EHIP;
+  // Costs of one or two bytes in LDS next to the metadata, if that leaves room for at least six wavefronts
+  // per compute unit: [block][chunk < V][lanes per candidate][row of m values], padded to 2 KB.  Kinds
+  // whose costs are the same (a forward pass whether its activation is kept or dropped, a
+  // recomputation, ...) share a block.
+  bool in_lds = false;
+  if (p->slots_ok && fits_slots && max_dur < 65536 && !getenv("FPSCHED_MB_GLOBAL")) {
+    const SlotTables& ST = p->stab;
+    const int V = p->slot_v;
+    int block_of[kNKinds] = {0}, n_blocks = 0, kind_of_block[kNKinds] = {0};
+    for (int kind = 1; kind < kNKinds; ++kind) {
+      int found = -1;
+      for (int b = 0; b < n_blocks && found < 0; ++b)
+        if (std::equal(dur_mb + (size_t)kind * S * m, dur_mb + (size_t)(kind + 1) * S * m, dur_mb + (size_t)kind_of_block[b] * S * m)) found = b;
+      if (found < 0) { found = n_blocks; kind_of_block[n_blocks++] = kind; }
+      block_of[kind] = found;
+    }
+    uint32_t kind_map = 0;
+    for (int kind = 1; kind < kNKinds; ++kind) kind_map |= (uint32_t)block_of[kind] << (4 * kind);
+    const int value_bytes = max_dur < 256 ? 1 : 2;
+    const int64_t row_dwords = slot_mb_row_dwords(m, value_bytes);   // of one device
+    const int64_t table_ints = ((int64_t)n_blocks * V * lpc * row_dwords + 511) & ~511ll;
+    const int64_t shared = ST.n_shared_ints + table_ints;
+    const SlotGeometry geo = slot_geometry(shared, lpc, ST.state_words, ST.slots_per_cand, p->max_lds);
+    if (geo.waves * geo.groups >= 6 && geo.cands_per_wave == ST.cands_per_wave) {
+      std::vector<int32_t> J((size_t)shared + (p->slot_ints.size() - ST.n_shared_ints), 0);
+      std::copy(p->slot_ints.begin(), p->slot_ints.begin() + ST.n_shared_ints, J.begin());
+      std::copy(p->slot_ints.begin() + ST.n_shared_ints, p->slot_ints.end(), J.begin() + shared);
+      unsigned char* t8 = reinterpret_cast<unsigned char*>(J.data() + ST.n_shared_ints);
+      for (int b = 0; b < n_blocks; ++b)
+        for (int c = 0; c < V; ++c)
+          for (int d = 0; d < D; ++d) {
+            if (c >= p->n_chunks[d]) continue;
+            const int s = p->local_stage[(size_t)d * kMaxChunks + c];
+            unsigned char* row = t8 + (((size_t)b * V + c) * lpc + d) * row_dwords * 4;
+            for (int j = 0; j < m; ++j) {
+              const uint32_t value = (uint32_t)dur_mb[((size_t)kind_of_block[b] * S + s) * m + j];
+              if (value_bytes == 1) row[j] = (unsigned char)value;
+              else { row[2 * j] = (unsigned char)value; row[2 * j + 1] = (unsigned char)(value >> 8); }
+            }
+          }
+      if (J.size() > p->mb_image_ints) {   // tables with more distinct kinds need a larger image
+        if (p->d_mb_image) (void)hipFree(p->d_mb_image);
+        p->d_mb_image = nullptr;
+        p->mb_image_ints = 0;
+        if (hipMalloc(&p->d_mb_image, J.size() * sizeof(int32_t)) != hipSuccess) { p->d_mb_image = nullptr; return FPSCHED_ENOMEM; }
+        p->mb_image_ints = J.size();
+      }
+      if (hipMemcpy(p->d_mb_image, J.data(), J.size() * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess) return FPSCHED_EHIP;
+      p->stab_mb = ST;
+      p->stab_mb.ints = p->d_mb_image;
+      p->stab_mb.off_mb = ST.n_shared_ints;
+      p->stab_mb.mb_kind_map = kind_map;
+      p->stab_mb.mb_value_bytes = value_bytes;
+      p->stab_mb.n_shared_ints = (int32_t)shared;
+      p->stab_mb.off_dev = ST.off_dev + (int32_t)table_ints;
+      p->stab_mb.off_expect = ST.off_expect + (int32_t)table_ints;
+      p->stab_mb.cands_per_wave = geo.cands_per_wave;
+      p->stab_mb.wave_ints = geo.wave_ints;
+      p->mb_waves = geo.waves;
+      p->mb_grid = p->n_cu * geo.groups;
+      p->mb_lds_bytes = (int32_t)(4ll * (shared + (int64_t)geo.waves * geo.wave_ints));
+      if (hipFuncSetAttribute(reinterpret_cast<const void*>(slot_kernel_of<kSlotPerMicrobatchLds>(p->slot_v, p->slot_deg2, ST.n_classes == 1)),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, p->mb_lds_bytes) != hipSuccess)
+        return FPSCHED_EHIP;
+      in_lds = true;
+    }
+  }
+  p->mb_in_lds = in_lds;
+  if (getenv("FPSCHED_VERBOSE"))
+    fprintf(stderr, "[fpsched] costs per micro-batch: %s; slot kernel %d x %d wavefronts per compute unit (plain: %d x %d), LDS limit %d bytes\n",
+            !(p->slots_ok && fits_slots) ? "general kernel" : (in_lds ? "slot kernel, table in LDS" : "slot kernel, table in device memory"),
+            in_lds ? p->mb_grid / std::max(p->n_cu, 1) : p->slot_grid / std::max(p->n_cu, 1), in_lds ? p->mb_waves : p->slot_waves,
+            p->slot_grid / std::max(p->n_cu, 1), p->slot_waves, p->max_lds);
   p->mb_set = true;
   p->mb_slots_ok = p->slots_ok && fits_slots;
   return FPSCHED_OK;

@@ -30,8 +30,9 @@ constexpr int kSlotMaxThreads = 64 * kSlotMaxWaves;
 // candidate][4] (start time << 8 of the op at each position), out_stop [n_cand][D] (words issued per device) and out_flags
 // (DEADLOCK / INCOMPLETE only) instead of makespan, idle and peak; needs 16 bytes of LDS more.
 // MODE kSlotPerMicrobatch: durations from mb_rows [32][lanes per candidate][m] (cost << 8 per metadata
-// row, device and micro-batch) instead of the metadata rows.
-constexpr int kSlotPlain = 0, kSlotTimes = 1, kSlotPerMicrobatch = 2;
+// row, device and micro-batch) instead of the metadata rows.  MODE kSlotPerMicrobatchLds: from the
+// sixteen-bit table at T.off_mb, which travels to LDS with the metadata.
+constexpr int kSlotPlain = 0, kSlotTimes = 1, kSlotPerMicrobatch = 2, kSlotPerMicrobatchLds = 3;
 template <int V, bool DEG2, bool ONE_CLASS, int MODE>
 __global__ void eval_slot_kernel(SlotTables T, const uint16_t* ops, long long n_cand, int stride,
                                  long long* out_makespan, long long* out_idle, int* out_peak,

@@ -22,8 +22,13 @@ def scaled_table(prob, rng):
     return workloads.microbatch_costs(prob, seed=int(rng.integers(1 << 30)))
 
 
+@pytest.mark.parametrize("table_in", ["lds", "device memory"])
 @pytest.mark.parametrize("index,n", [(1, 64), (2, 3000), (3, 700), (4, 900), (5, 2000)])
-def test_benchmark_shapes_with_costs_per_micro_batch(index, n):
+def test_benchmark_shapes_with_costs_per_micro_batch(index, n, table_in, monkeypatch):
+    # the slot kernel reads the costs from LDS when the table fits there, else from device memory
+    # (FPSCHED_MB_GLOBAL forces the latter)
+    if table_in != "lds":
+        monkeypatch.setenv("FPSCHED_MB_GLOBAL", "1")
     spec = workloads.config(index, n)
     words = workloads.generate(spec, threads=8)
     table = scaled_table(spec.problem, np.random.default_rng(index))
@@ -35,11 +40,17 @@ def test_benchmark_shapes_with_costs_per_micro_batch(index, n):
 
 
 @pytest.mark.parametrize("seed", range(6))
-def test_random_problems_with_random_tables(seed):
+def test_random_problems_with_random_tables(seed, monkeypatch):
+    if seed % 2:
+        monkeypatch.setenv("FPSCHED_MB_GLOBAL", "1")
     rng = np.random.default_rng(7000 + seed)
     for i in range(10):
         prob = random_problem(rng)
-        table = rng.integers(0, 40, (NKINDS, prob.n_stages, prob.n_microbatches)).astype(np.int32)
+        # small values travel as bytes, larger ones as sixteen-bit values
+        table = rng.integers(0, 40 if i % 2 else 3000, (NKINDS, prob.n_stages, prob.n_microbatches)).astype(np.int32)
+        if i % 3 == 0:
+            table[[4, 7]] = table[1]   # kinds with equal costs share their part of the table
+            table[[5, 6]] = 0
         lists = []
         for t in range(20):
             base = random_valid_lists(prob, rng, 0.3 * (t % 2), 0.3 * ((t // 2) % 2))
