@@ -22,12 +22,15 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
-# vector-ALU issue peak: 256 CUs x 4 SIMDs, 2.4 GHz, one wave64 instruction per SIMD every 4 cycles
-VALU_PEAK_WAVE_INSTR_PER_S = 256 * 4 * 2.4e9 / 4
 # HBM bytes of ONE evaluation launch on the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE
 # scaled by a copy kernel of known size, and its VALU wave-instruction count (SQ_INSTS_VALU):
 # profiles/eval_slot_kernel_cfg4_counters.md.  Other workloads report null.
 MEASURED = {("cfg4", 65536): {"traffic_bytes": 4.514e9, "valu_wave_instructions": 2.088e9}}
+# with costs per micro-batch (--mb-costs): profiles/eval_slot_kernel_cfg4_microbatch_costs.md
+MEASURED_MB = {("cfg4", 65536): {"traffic_bytes": None, "valu_wave_instructions": 2.694e9}}
+# int32 vector peak: 256 CUs x 4 SIMDs x 16 lanes, one operation per lane and clock at 2.4 GHz
+# (= the published 157.3 TFLOP/s fp32 vector figure / 4: an FMA counts two, packed issue two more)
+ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 # the same for one generator launch (--mode generate): WRITE_SIZE x 1024 plus the parameter sets read;
 # profiles/generate_kernel_cfg4.md
 MEASURED_GENERATE = {("cfg4", 65536): {"traffic_bytes": 4.81e9, "valu_wave_instructions": 1.231e10}}
@@ -379,7 +382,26 @@ def main() -> int:
     alg_bytes = 2 * n_ops + C * (8 + 8 * D + 4 * D + 1)
     achieved = alg_bytes / (eval_ms * 1e-3) / 1e9
 
-    measured = {} if args.mb_costs else MEASURED.get((f"cfg{spec.index}", C), {})
+    measured = (MEASURED_MB if args.mb_costs else MEASURED).get((f"cfg{spec.index}", C), {})
+    hbm_view = {"achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                "algorithmic_bytes_per_launch": alg_bytes}
+    kernel_name = "fpsched evaluation kernel (eval_slot_kernel)"
+    if measured:
+        # the kernel is bound by vector-ALU issue: executed int32 lane operations (64 per wavefront
+        # instruction, counted by rocprofv3 for exactly this workload) over the live launch duration
+        tops = measured["valu_wave_instructions"] * 64 / (eval_ms * 1e-3) / 1e12
+        roofline = {"bound": "alu", "achieved": tops, "peak": ALU_PEAK_TOPS,
+                    "unit": "TOP/s (int32 vector lane operations)", "frac": tops / ALU_PEAK_TOPS,
+                    "traffic": measured["traffic_bytes"], "kernel": kernel_name,
+                    "vector_wave_instructions_per_launch": measured["valu_wave_instructions"],
+                    "vector_wave_instructions_per_op_eval": measured["valu_wave_instructions"] / n_ops,
+                    "source": "rocprofv3 SQ_INSTS_VALU of one launch on this workload (profiles/), executed "
+                              "instructions, waiting lanes included",
+                    "hbm": hbm_view}
+    else:
+        roofline = dict(hbm_view, bound="hbm", traffic=None, kernel=kernel_name,
+                        note="no instruction count was taken for this workload; the kernel is bound by "
+                             "vector-ALU issue, not HBM (see the default workload)")
     flags = res["flags"].cpu().numpy()
     makespan = res["makespan"].cpu().numpy()
     out = {
@@ -398,18 +420,7 @@ def main() -> int:
                    "stride_words": stride, "top_k": k},
         "op_evals_per_s": n_ops / (ms_per_step * 1e-3),
         "eval_kernel_ms": eval_ms, "eval_kernel_ms_median": float(np.median(eval_each)), "topk_ms": topk_ms,
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured.get("traffic_bytes"),
-                     "kernel": "fpsched evaluation kernel (eval_slot_kernel)",
-                     "algorithmic_bytes_per_launch": alg_bytes,
-                     "note": "the kernel is bound by vector-ALU issue, not HBM: see alu_ceiling"},
-        "alu_ceiling": None if not measured else {
-            "bound": "alu", "unit": "VALU wave-instructions/s",
-            "achieved": measured["valu_wave_instructions"] / (eval_ms * 1e-3),
-            "peak": VALU_PEAK_WAVE_INSTR_PER_S,
-            "frac": measured["valu_wave_instructions"] / (eval_ms * 1e-3) / VALU_PEAK_WAVE_INSTR_PER_S,
-            "valu_wave_instructions_per_op_eval": measured["valu_wave_instructions"] / n_ops,
-            "source": "rocprofv3 SQ_INSTS_VALU, profiles/eval_slot_kernel_cfg4_counters.md"},
+        "roofline": roofline,
         "fractions": {"feasible_under_cap": float((flags == 0).mean()),
                       "over_cap": float((flags == 4).mean()),
                       "deadlock": float(((flags & 1) != 0).mean())},
