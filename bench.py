@@ -108,6 +108,23 @@ def bench_generate(args, spec, threads) -> int:
     # written in full, END padding included: the evaluator reads them as they are), steps and status
     alg_bytes = pol.nbytes + inf.nbytes + words.nbytes + 5 * n
     achieved = alg_bytes / (gen_ms * 1e-3) / 1e9
+    counted = MEASURED_GENERATE.get((f"cfg{spec.index}", n), {})
+    hbm_view = {"achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                "algorithmic_bytes_per_launch": alg_bytes}
+    if counted:
+        # a step-synchronous process bound by vector-ALU issue: executed int32 lane operations (64 per
+        # wavefront instruction, the rocprofv3 count for this workload) over the live launch duration
+        tops = counted["valu_wave_instructions"] * 64 / (gen_ms * 1e-3) / 1e12
+        gen_roofline = {"bound": "alu", "achieved": tops, "peak": ALU_PEAK_TOPS,
+                        "unit": "TOP/s (int32 vector lane operations)", "frac": tops / ALU_PEAK_TOPS,
+                        "traffic": counted["traffic_bytes"], "kernel": "fpsched generator kernel (generate_kernel)",
+                        "vector_wave_instructions_per_launch": counted["valu_wave_instructions"],
+                        "source": "rocprofv3 SQ_INSTS_VALU of one launch on this workload (profiles/generate_kernel_cfg4.md)",
+                        "hbm": hbm_view}
+    else:
+        gen_roofline = dict(hbm_view, bound="hbm", traffic=None, kernel="fpsched generator kernel (generate_kernel)",
+                            note="no instruction count was taken for this workload; the kernel is bound by "
+                                 "vector-ALU issue, not HBM (see configuration 4)")
     json_res = {
         "metric": "schedules generated, evaluated and ranked/sec" if search else "schedules generated/sec",
         "value": n / (ms_per_step * 1e-3), "unit": "schedules/s",
@@ -120,12 +137,7 @@ def bench_generate(args, spec, threads) -> int:
         "items_scheduled_per_s": n_ops / (ms_per_step * 1e-3),
         "generate_kernel_ms": gen_ms,
         "scheduling_steps": {"mean": float(steps.mean()), "max": int(steps.max())},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_GENERATE.get((f"cfg{spec.index}", n), {}).get("traffic_bytes"),
-                     "kernel": "fpsched generator kernel (generate_kernel)",
-                     "algorithmic_bytes_per_launch": alg_bytes,
-                     "note": "step-synchronous process: bound by the latency of a scheduling step, not by HBM"},
+        "roofline": gen_roofline,
         "fractions": {"complete": float((out["status"].cpu().numpy() == 0).mean())},
         "host": {"parameter_sets_s": prep_s},
     }

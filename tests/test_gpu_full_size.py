@@ -68,6 +68,19 @@ def test_full_batch_every_candidate_against_oracle(index):
     got = list(zip(front["idx"].cpu().numpy()[:cnt], front["makespan"].cpu().numpy()[:cnt],
                    front["peak"].cpu().numpy()[:cnt]))
     assert [tuple(int(x) for x in e) for e in got] == [tuple(int(x) for x in e) for e in expect[:cnt]]
+    # the same batch with costs per micro-batch (the launch `bench.py --mb-costs` times): every candidate
+    if index in (2, 4, 5):
+        table = workloads.microbatch_costs(prob)
+        h.set_microbatch_costs(table)
+        res = h.evaluate(ops, workspace=ws)
+        top = h.topk(res, spec.top_k, workspace=ws)
+        torch.cuda.synchronize()
+        ref = oracle.evaluate(prob, words, threads=16, dur_mb=table)
+        for name in ("flags", "makespan", "idle", "peak"):
+            assert np.array_equal(res[name].cpu().numpy(), ref[name]), f"costs per micro-batch: {name}"
+        r_idx, r_ms, r_cnt = oracle.topk(ref["makespan"], ref["flags"], spec.top_k)
+        assert int(top["count"].item()) == r_cnt and np.array_equal(top["idx"].cpu().numpy(), r_idx)
+        assert np.array_equal(top["makespan"].cpu().numpy(), r_ms)
     h.close()
 
 
