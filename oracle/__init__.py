@@ -76,6 +76,8 @@ def _load():
         _lib.fporacle_evaluate.restype = ctypes.c_int
         _lib.fporacle_eval_one_mb.restype = ctypes.c_int
         _lib.fporacle_evaluate_mb.restype = ctypes.c_int
+        _lib.fporacle_eval_one_links.restype = ctypes.c_int
+        _lib.fporacle_evaluate_links.restype = ctypes.c_int
         _lib.fporacle_topk.restype = ctypes.c_int
         _lib.fporacle_rank.restype = ctypes.c_int
     return _lib
@@ -127,14 +129,16 @@ def _mb_table(mp, dur_mb):
     return t
 
 
-def evaluate(problem, words, threads: int = 1, dur_mb=None):
+def evaluate(problem, words, threads: int = 1, dur_mb=None, links: bool = False):
     """Evaluate a batch ``words[C][D][stride]`` (uint16).
 
     Returns dict(makespan int64[C], idle int64[C][D], peak int32[C][D],
     flags uint8[C]).  ``threads`` > 1 only splits the batch over host threads;
     every candidate is still evaluated by the same single-threaded C routine.
-    ``dur_mb[8][S][m]``: per-micro-batch costs in place of ``problem.dur``.
+    ``dur_mb[8][S][m]``: per-micro-batch costs in place of ``problem.dur``.  ``links``: every ordered
+    pair of devices is a link that carries one value at a time (see fporacle_evaluate_links).
     """
+    assert not (links and dur_mb is not None), "one variant of the cost model at a time"
     lib = _load()
     mp = _Marshalled(problem)
     table = _mb_table(mp, dur_mb)
@@ -148,6 +152,13 @@ def evaluate(problem, words, threads: int = 1, dur_mb=None):
     def run(lo, hi):
         if hi <= lo:
             return 0
+        if links:
+            return lib.fporacle_evaluate_links(
+                ctypes.byref(mp.c), ctypes.c_void_p(w[lo:hi].ctypes.data), ctypes.c_int64(hi - lo),
+                ctypes.c_int32(stride), ctypes.c_void_p(out["makespan"][lo:hi].ctypes.data),
+                ctypes.c_void_p(out["idle"][lo:hi].ctypes.data),
+                ctypes.c_void_p(out["peak"][lo:hi].ctypes.data),
+                ctypes.c_void_p(out["flags"][lo:hi].ctypes.data))
         return lib.fporacle_evaluate_mb(
             ctypes.byref(mp.c), table_ptr, ctypes.c_void_p(w[lo:hi].ctypes.data), ctypes.c_int64(hi - lo),
             ctypes.c_int32(stride), ctypes.c_void_p(out["makespan"][lo:hi].ctypes.data),
@@ -169,8 +180,9 @@ def evaluate(problem, words, threads: int = 1, dur_mb=None):
     return out
 
 
-def evaluate_trace(problem, words_one, dur_mb=None):
+def evaluate_trace(problem, words_one, dur_mb=None, links: bool = False):
     """One candidate ``words[D][stride]``; also returns every op's start/finish."""
+    assert not (links and dur_mb is not None), "one variant of the cost model at a time"
     lib = _load()
     mp = _Marshalled(problem)
     table = _mb_table(mp, dur_mb)
@@ -183,12 +195,14 @@ def evaluate_trace(problem, words_one, dur_mb=None):
     fl = np.empty(1, np.uint8)
     st = np.empty((mp.D, stride), np.int64)
     fi = np.empty((mp.D, stride), np.int64)
-    rc = lib.fporacle_eval_one_mb(ctypes.byref(mp.c),
-                                  ctypes.c_void_p(table.ctypes.data if table is not None else None),
-                                  ctypes.c_void_p(w.ctypes.data), ctypes.c_int32(stride), ctypes.c_void_p(ms.ctypes.data),
-                               ctypes.c_void_p(idle.ctypes.data), ctypes.c_void_p(peak.ctypes.data),
-                               ctypes.c_void_p(fl.ctypes.data), ctypes.c_void_p(st.ctypes.data),
-                               ctypes.c_void_p(fi.ctypes.data))
+    tail = (ctypes.c_void_p(w.ctypes.data), ctypes.c_int32(stride), ctypes.c_void_p(ms.ctypes.data),
+            ctypes.c_void_p(idle.ctypes.data), ctypes.c_void_p(peak.ctypes.data), ctypes.c_void_p(fl.ctypes.data),
+            ctypes.c_void_p(st.ctypes.data), ctypes.c_void_p(fi.ctypes.data))
+    if links:
+        rc = lib.fporacle_eval_one_links(ctypes.byref(mp.c), *tail)
+    else:
+        rc = lib.fporacle_eval_one_mb(ctypes.byref(mp.c),
+                                      ctypes.c_void_p(table.ctypes.data if table is not None else None), *tail)
     if rc:
         raise ValueError("fporacle: invalid problem description")
     return dict(makespan=int(ms[0]), idle=idle, peak=peak, flags=int(fl[0]), start=st, finish=fi)

@@ -104,10 +104,19 @@ static int build_local_stage(const fporacle_problem *P, int32_t *local_stage, in
  * (-1 where the op never issued or past the end of the list).
  * Returns 0, or -1 for an invalid problem.
  */
-static int eval_one(const fporacle_problem *P, const int32_t *dur_mb, const uint16_t *words, int32_t stride,
+static int eval_one(const fporacle_problem *P, const int32_t *dur_mb, int links, const uint16_t *words, int32_t stride,
                     int64_t *makespan, int64_t *idle, int32_t *peak, uint8_t *flags,
                     int64_t *op_start, int64_t *op_finish) {
-  const int D = P->n_devices, S = P->n_stages, m = P->n_microbatches;
+  const int D = P->n_devices, S = P->n_stages, m = P->n_microbatches, E = P->n_edges;
+  /* links != 0 (see fporacle_evaluate_links): when each value sent over a cross-device edge arrives,
+   * per edge and micro-batch (-1 = not sent yet), and until when each device-to-device link is busy */
+  int64_t *arr_fwd = NULL, *arr_bwd = NULL, *link_free = NULL;
+  if (links) {
+    arr_fwd = malloc(sizeof(int64_t) * (size_t)(E > 0 ? E : 1) * m);
+    arr_bwd = malloc(sizeof(int64_t) * (size_t)(E > 0 ? E : 1) * m);
+    link_free = calloc((size_t)D * D, sizeof(int64_t));
+    for (int64_t i = 0; i < (int64_t)E * m; ++i) arr_fwd[i] = arr_bwd[i] = -1;
+  }
   int32_t *local_stage = malloc(sizeof(int32_t) * D * MAX_CHUNKS);
   int32_t *n_chunks = malloc(sizeof(int32_t) * D);
   if (build_local_stage(P, local_stage, n_chunks)) { free(local_stage); free(n_chunks); return -1; }
@@ -160,18 +169,18 @@ static int eval_one(const fporacle_problem *P, const int32_t *dur_mb, const uint
         for (int e = 0; e < P->n_edges && !blocked; ++e) {
           if (P->edge_dst[e] != s) continue;
           const int sp = P->edge_src[e];
-          const int64_t t = fin_fwd[(size_t)sp * m + j];
+          const int64_t t = links ? arr_fwd[(size_t)e * m + j] : fin_fwd[(size_t)sp * m + j];
           if (t < 0) { blocked = 1; break; }
-          const int64_t r = t + (P->stage_device[sp] != d ? P->edge_comm[e] : 0);
+          const int64_t r = links ? t : t + (P->stage_device[sp] != d ? P->edge_comm[e] : 0);
           if (r > ready) ready = r;
         }
       } else if (kind == K_B) {
         for (int e = 0; e < P->n_edges && !blocked; ++e) {
           if (P->edge_src[e] != s) continue;
           const int sn = P->edge_dst[e];
-          const int64_t t = fin_bwd[(size_t)sn * m + j];
+          const int64_t t = links ? arr_bwd[(size_t)e * m + j] : fin_bwd[(size_t)sn * m + j];
           if (t < 0) { blocked = 1; break; }
-          const int64_t r = t + (P->stage_device[sn] != d ? P->edge_comm[e] : 0);
+          const int64_t r = links ? t : t + (P->stage_device[sn] != d ? P->edge_comm[e] : 0);
           if (r > ready) ready = r;
         }
       }
@@ -197,6 +206,25 @@ static int eval_one(const fporacle_problem *P, const int32_t *dur_mb, const uint
         case K_L:  *st = ST_RES; break;
         case K_B:  *st = ST_BDONE; fin_bwd[(size_t)s * m + j] = finish; break;
         default:   *st = ST_DONE; break;
+      }
+      if (links && (kind == K_F || kind == K_FD || kind == K_B)) {
+        /* send the result over every outgoing edge, in the order of the edge list: activations to the
+         * successor stages, gradients to the predecessor stages.  A transfer starts when the item has
+         * finished and the link from this device to the receiving one is free, and keeps the link busy for
+         * the edge's latency; on the same device the value is there at once. */
+        const int fwd = kind != K_B;
+        for (int e = 0; e < E; ++e) {
+          if ((fwd ? P->edge_src[e] : P->edge_dst[e]) != s) continue;
+          const int to = P->stage_device[fwd ? P->edge_dst[e] : P->edge_src[e]];
+          int64_t arrival = finish;
+          if (to != d) {
+            int64_t *busy_until = &link_free[(size_t)d * D + to];
+            const int64_t depart = finish > *busy_until ? finish : *busy_until;
+            arrival = depart + P->edge_comm[e];
+            *busy_until = arrival;
+          }
+          (fwd ? arr_fwd : arr_bwd)[(size_t)e * m + j] = arrival;
+        }
       }
       if (op_start) {
         op_start[(size_t)d * stride + cursor[d]] = start;
@@ -232,6 +260,7 @@ static int eval_one(const fporacle_problem *P, const int32_t *dur_mb, const uint
   }
   *flags = fl;
 
+  free(arr_fwd); free(arr_bwd); free(link_free);
   free(local_stage); free(n_chunks); free(fin_fwd); free(fin_bwd); free(state);
   free(cursor); free(len); free(free_at); free(busy); free(mem); free(pk);
   return 0;
@@ -240,7 +269,7 @@ static int eval_one(const fporacle_problem *P, const int32_t *dur_mb, const uint
 int fporacle_eval_one(const fporacle_problem *P, const uint16_t *words, int32_t stride,
                       int64_t *makespan, int64_t *idle, int32_t *peak, uint8_t *flags,
                       int64_t *op_start, int64_t *op_finish) {
-  return eval_one(P, NULL, words, stride, makespan, idle, peak, flags, op_start, op_finish);
+  return eval_one(P, NULL, 0, words, stride, makespan, idle, peak, flags, op_start, op_finish);
 }
 
 /*
@@ -255,7 +284,7 @@ int fporacle_eval_one(const fporacle_problem *P, const uint16_t *words, int32_t 
 int fporacle_eval_one_mb(const fporacle_problem *P, const int32_t *dur_mb, const uint16_t *words,
                          int32_t stride, int64_t *makespan, int64_t *idle, int32_t *peak, uint8_t *flags,
                          int64_t *op_start, int64_t *op_finish) {
-  return eval_one(P, dur_mb, words, stride, makespan, idle, peak, flags, op_start, op_finish);
+  return eval_one(P, dur_mb, 0, words, stride, makespan, idle, peak, flags, op_start, op_finish);
 }
 
 /* Evaluate candidates [0, n_cand) of a batch laid out [C][D][stride]; dur_mb may be NULL. */
@@ -264,7 +293,35 @@ int fporacle_evaluate_mb(const fporacle_problem *P, const int32_t *dur_mb, const
                          uint8_t *flags) {
   const int D = P->n_devices;
   for (int64_t c = 0; c < n_cand; ++c) {
-    int rc = eval_one(P, dur_mb, words + (size_t)c * D * stride, stride, &makespan[c],
+    int rc = eval_one(P, dur_mb, 0, words + (size_t)c * D * stride, stride, &makespan[c],
+                      &idle[c * D], &peak[c * D], &flags[c], NULL, NULL);
+    if (rc) return rc;
+  }
+  return 0;
+}
+
+/*
+ * Variant of the cost model: links that carry one value at a time.  The paper lists P2P send / receive
+ * among its instructions (Section 4, "FlexPipe's Instructions") and leaves out how they are overlapped
+ * (Section 5.2, end); the plain model above reads a transfer as a pure latency.  Here every ordered pair
+ * of devices (from, to) is a link of its own: a value (the activation of a forward item for a successor
+ * stage on another device, the gradient of a backward item for a predecessor stage on another device)
+ * leaves when its item has finished and the link is free, occupies the link for the edge's latency and
+ * arrives at its end.  Values of one device leave in the order its items run (several values of one item:
+ * in the order of the edge list).  A consumer is ready when all its inputs have arrived.  Everything else
+ * (order rules, memory, idle, flags) is as in the plain model; with latencies of zero the two coincide.
+ * Pins: tests/test_oracle_links.py.
+ */
+int fporacle_eval_one_links(const fporacle_problem *P, const uint16_t *words, int32_t stride, int64_t *makespan,
+                            int64_t *idle, int32_t *peak, uint8_t *flags, int64_t *op_start, int64_t *op_finish) {
+  return eval_one(P, NULL, 1, words, stride, makespan, idle, peak, flags, op_start, op_finish);
+}
+
+int fporacle_evaluate_links(const fporacle_problem *P, const uint16_t *words, int64_t n_cand, int32_t stride,
+                            int64_t *makespan, int64_t *idle, int32_t *peak, uint8_t *flags) {
+  const int D = P->n_devices;
+  for (int64_t c = 0; c < n_cand; ++c) {
+    int rc = eval_one(P, NULL, 1, words + (size_t)c * D * stride, stride, &makespan[c],
                       &idle[c * D], &peak[c * D], &flags[c], NULL, NULL);
     if (rc) return rc;
   }

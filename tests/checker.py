@@ -36,11 +36,14 @@ def decode_lists(problem, words):
     return out
 
 
-def check(problem, words, dur_mb=None):
+def check(problem, words, dur_mb=None, links=False):
     """Returns dict(deadlock, incomplete, makespan, idle, peak, finish) for one candidate.
 
     dur_mb[kind][stage][micro-batch], if given, is the weight of every node instead of
-    problem.dur[kind][stage]."""
+    problem.dur[kind][stage].  links: every value sent to another device becomes a node of its own
+    (weight = the edge's latency) between its producer and its consumer, and the transfer nodes of one
+    ordered pair of devices form a chain in the order their producers stand in the sending device's list
+    (several values of one producer: in the order of the edge list) -- a link carries one value at a time."""
     D, S, m = problem.n_devices, problem.n_stages, problem.n_microbatches
 
     def weight(kind, s, j):
@@ -99,6 +102,7 @@ def check(problem, words, dur_mb=None):
     for n in nodes:
         edges_in[n] = []
     missing_producer = False
+    transfer_weight = {}
     for d, ops in enumerate(lists):
         for i, (kind, s, j, _c) in enumerate(ops):
             if i > 0:
@@ -107,16 +111,49 @@ def check(problem, words, dur_mb=None):
                 for sp, c in preds[s]:
                     if (sp, j) not in where_fwd:
                         missing_producer = True
+                    elif links and dev[sp] != d:
+                        edges_in[(d, i)].append((("send", "f", sp, s, j), 0))
                     else:
                         edges_in[(d, i)].append((where_fwd[(sp, j)], c if dev[sp] != d else 0))
             elif kind == B:
                 for sn, c in succs[s]:
                     if (sn, j) not in where_bwd:
                         missing_producer = True
+                    elif links and dev[sn] != d:
+                        edges_in[(d, i)].append((("send", "b", sn, s, j), 0))
                     else:
                         edges_in[(d, i)].append((where_bwd[(sn, j)], c if dev[sn] != d else 0))
     if missing_producer:
         return dict(deadlock=True, incomplete=None, makespan=None, idle=None, peak=None, finish=None)
+    if links:
+        # one node per value sent to another device; per ordered device pair a chain in sending order
+        last_on_link = {}
+        edge_list = list(zip(problem.edge_src, problem.edge_dst, problem.edge_comm))
+        for d, ops in enumerate(lists):
+            for i, (kind, s, j, _c) in enumerate(ops):
+                if kind not in (F, FD, B):
+                    continue
+                for a, b, c in edge_list:   # in the order of the edge list
+                    a, b, c = int(a), int(b), int(c)
+                    if kind == B:
+                        if b != s or dev[a] == d:
+                            continue
+                        node, to = ("send", "b", s, a, j), dev[a]
+                    else:
+                        if a != s or dev[b] == d:
+                            continue
+                        node, to = ("send", "f", s, b, j), dev[b]
+                    nodes.append(node)
+                    transfer_weight[node] = c
+                    edges_in[node] = [((d, i), 0)]
+                    if (d, to) in last_on_link:
+                        edges_in[node].append((last_on_link[(d, to)], 0))
+                    last_on_link[(d, to)] = node
+        # a consumer may name a transfer whose producer never runs: then it is stuck
+        for n in list(nodes):
+            for src, _w in edges_in[n]:
+                if src not in edges_in:
+                    return dict(deadlock=True, incomplete=None, makespan=None, idle=None, peak=None, finish=None)
 
     # 3. Kahn + longest path
     indeg = {n: len(edges_in[n]) for n in nodes}
@@ -130,9 +167,12 @@ def check(problem, words, dur_mb=None):
     done = 0
     while q:
         n = q.popleft()
-        d, i = n
-        kind, s, j, _c = lists[d][i]
-        finish[n] = ready[n] + weight(kind, s, j)
+        if n in transfer_weight:
+            finish[n] = ready[n] + transfer_weight[n]
+        else:
+            d, i = n
+            kind, s, j, _c = lists[d][i]
+            finish[n] = ready[n] + weight(kind, s, j)
         done += 1
         for nxt, wgt in out_edges[n]:
             ready[nxt] = max(ready[nxt], finish[n] + wgt)
@@ -144,6 +184,7 @@ def check(problem, words, dur_mb=None):
 
     terminal = _DONE if problem.has_w else _BDONE
     incomplete = any(state.get((s, j), _ABSENT) != terminal for s in range(S) for j in range(m))
+    finish = {n: t for n, t in finish.items() if n not in transfer_weight}   # the ops' own finish times
     makespan = max(finish.values(), default=0)
     return dict(deadlock=False, incomplete=incomplete, makespan=makespan,
                 idle=[makespan - b for b in busy], peak=peak, finish=finish)
