@@ -21,9 +21,9 @@
  *
  * Ownership and threads.  The caller owns every buffer it passes, the workspaces
  * included; the library owns only the opaque handle and the few KB of tables it
- * uploads when the handle is created (it allocates nothing afterwards, except for the two
- * tables of fpsched_problem_set_microbatch_costs).  A handle is immutable after creation except
- * for fpsched_problem_select_kernel and fpsched_problem_set_microbatch_costs: calls on
+ * uploads when the handle is created (it allocates nothing afterwards, except for the tables
+ * of fpsched_problem_set_microbatch_costs and fpsched_problem_set_link_occupancy).  A handle is
+ * immutable after creation except for fpsched_problem_select_kernel and those two calls: calls on
  * distinct handles, and calls on one handle that use distinct workspaces and
  * output buffers, may run from different host threads and on different streams.
  * Device calls only enqueue kernels on the given stream and return.
@@ -131,6 +131,24 @@ void fpsched_problem_destroy(fpsched_problem *p);
  * fpsched_wslide returns FPSCHED_EUNSUPPORTED (the sliding pass knows one cost per (type, stage));
  * fpsched_generate ignores costs anyway.  Works on a host-only handle (validation only). */
 int fpsched_problem_set_microbatch_costs(fpsched_problem *p, const int32_t *dur_mb);
+
+/* Variant of the cost model: links that carry one value at a time.  The paper lists P2P send and
+ * receive among its instructions (Section 4, "FlexPipe's Instructions") and leaves out how they
+ * overlap (end of Section 5.2); fpsched_evaluate reads a transfer as a pure latency.  With on != 0
+ * every ordered pair of devices (from, to) is a link: a value (the activation of a forward item
+ * for a successor stage on another device, the gradient of a backward item for a predecessor
+ * stage on another device) leaves when its item has finished and the link is free, occupies the
+ * link for edge_comm and arrives at its end; the values of a device leave in the order its items
+ * run (two values of one item: in the order of the edge list).  A consumer is ready when all its
+ * inputs have arrived; everything else is unchanged, and with latencies of zero the two models
+ * coincide.  on == 0 switches back.  Only the slot kernel has this form: FPSCHED_EUNSUPPORTED if
+ * the problem does not fit it (more than two inputs or outputs per stage, or
+ * D * max_stride * (max dur + 2 * max comm) >= 2^24), if costs per micro-batch are set (one variant
+ * at a time; the reverse order of the two calls is refused the same way), and from
+ * fpsched_evaluate while the general kernel is selected or from fpsched_wslide while on.
+ * The first call on a device handle allocates one more table image (FPSCHED_ENOMEM); not to be
+ * called concurrently with other calls on the handle.  Works on a host-only handle (flag only). */
+int fpsched_problem_set_link_occupancy(fpsched_problem *p, int32_t on);
 
 /* DEVICE buffers the caller owns (e.g. torch tensors); all must hold n_cand entries. */
 typedef struct {

@@ -63,6 +63,8 @@ def load_library():
         lib.fpsched_problem_info.argtypes = [vp, ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(i32)]
         lib.fpsched_problem_set_microbatch_costs.restype = ctypes.c_int
         lib.fpsched_problem_set_microbatch_costs.argtypes = [vp, vp]
+        lib.fpsched_problem_set_link_occupancy.restype = ctypes.c_int
+        lib.fpsched_problem_set_link_occupancy.argtypes = [vp, i32]
         lib.fpsched_problem_select_kernel.restype = ctypes.c_int
         lib.fpsched_problem_select_kernel.argtypes = [vp, ctypes.c_int]
         lib.fpsched_workspace_bytes.restype = ctypes.c_size_t
@@ -175,6 +177,13 @@ class Problem:
         rc = load_library().fpsched_problem_set_microbatch_costs(self._h, ptr)
         if rc != 0:
             raise FpschedError(rc, "fpsched_problem_set_microbatch_costs")
+
+    def set_link_occupancy(self, on: bool = True):
+        """Every ordered pair of devices becomes a link that carries one value at a time
+        (see fpsched_problem_set_link_occupancy)."""
+        rc = load_library().fpsched_problem_set_link_occupancy(self._h, 1 if on else 0)
+        if rc != 0:
+            raise FpschedError(rc, "fpsched_problem_set_link_occupancy")
 
     # ---- host helpers -----------------------------------------------------
     def encode(self, items, device: int) -> np.ndarray:

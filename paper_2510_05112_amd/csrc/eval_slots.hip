@@ -119,6 +119,13 @@ __global__ void reset_counter_kernel(unsigned long long* counter, unsigned long 
 // covers the op-window load in flight, so the form is about twice as slow as the plain kernel.
 // MODE kSlotPerMicrobatchLds: the same costs as values of one or two bytes in the shared part of LDS
 // (T.off_mb), read like the metadata row; the host picks it when the table fits.
+//
+// MODE kSlotLinks: the link-occupancy variant of the cost model.  Every device a lane's device sends
+// to has a word behind the lane's state words: the time until which that link is busy.  An op with an
+// outgoing edge to another device writes into its output slot not its finish time but the time its
+// value leaves, max(finish, link busy until), and keeps the link busy for the edge's latency from then;
+// the consumer adds the latency as before.  The link word of the current op is read when the op is
+// decoded (only the lane itself ever writes it, in program order before that read).
 template <int V, bool DEG2, bool ONE_CLASS, int MODE>
 __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     SlotTables T, const uint16_t* __restrict__ ops, long long n_cand, int stride,
@@ -127,6 +134,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     unsigned long long* __restrict__ next_candidate, int draw_block,
     uint32_t* __restrict__ out_start8, int32_t* __restrict__ out_stop, const int32_t* __restrict__ mb_rows) {
   constexpr bool TIMES = MODE == kSlotTimes, MBDUR = MODE == kSlotPerMicrobatch, MBLDS = MODE == kSlotPerMicrobatchLds;
+  constexpr bool LINKS = MODE == kSlotLinks;
   extern __shared__ int32_t lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int m = T.m;
@@ -145,7 +153,8 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   // window: kRing sixteen-bit words per lane, laid out [word][lane]
   uint16_t* win = reinterpret_cast<uint16_t*>(L + shared_bytes + wave * (kRing * 128u));
   uint32_t* stt = reinterpret_cast<uint32_t*>(L + rest_off);              // [state word][lane]
-  uint32_t* slots = stt + T.state_words * 64;
+  const int lane_words = T.state_words + (LINKS ? T.link_words : 0);   // state words, then link words
+  uint32_t* slots = stt + lane_words * 64;
   const int slots_per_cand = T.slots_per_cand;  // backward, forward, dump; a multiple of 8
   // TIMES: one dword behind the last wavefront's region stays zero; it is the state word of W words
   const unsigned zero_off = shared_bytes + (blockDim.x >> 6) * (kRing * 128u + rest_ints * 4u);
@@ -175,6 +184,16 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     asm volatile("" : "+v"(cons_f[c]), "+v"(cons_b[c]), "+v"(cons_f2[c]), "+v"(cons_b2[c]));
   }
   asm volatile("" : "+v"(cap));
+  // LINKS: per chunk the out-edges as latency << 13 | byte offset of the link word
+  int out_f[V], out_b[V], out_f2[V], out_b2[V];
+#pragma unroll
+  for (int c = 0; c < V; ++c) {
+    out_f[c] = LINKS ? dev[2 + 4 * V + c] : 0;
+    out_b[c] = LINKS ? dev[2 + 5 * V + c] : 0;
+    out_f2[c] = LINKS && DEG2 ? dev[2 + 6 * V + c] : 0;
+    out_b2[c] = LINKS && DEG2 ? dev[2 + 7 * V + c] : 0;
+    if (LINKS) asm volatile("" : "+v"(out_f[c]), "+v"(out_b[c]), "+v"(out_f2[c]), "+v"(out_b2[c]));
+  }
   const unsigned long long seg_mask =
       (lpc == 64 ? ~0ull : ((1ull << lpc) - 1ull)) << (seg * lpc);
   // LDS byte offsets of this lane's columns
@@ -186,7 +205,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   const unsigned stt_off = lds0 + rest_off + lane * 4u;                               // word i at + i * 256
   // slots of this lane's candidate; the offset is a multiple of 32, so that the low five bits of
   // (slot_base + 4 j) are the position of micro-batch j's nibble in its state word
-  const unsigned slot_base_ = lds0 + rest_off + (unsigned)T.state_words * 256u +
+  const unsigned slot_base_ = lds0 + rest_off + (unsigned)lane_words * 256u +
                              (unsigned)(seg < cpw ? seg : 0) * (unsigned)slots_per_cand * 4u;
   const unsigned m4 = (unsigned)m << 2;
   const unsigned chunk_bytes = words_per_chunk << 8;   // state words of one chunk, all lanes
@@ -239,6 +258,11 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   unsigned mb_lds_lane = lds0 + (unsigned)T.off_mb * 4u + (unsigned)d * mb_dev_bytes;
   const unsigned mb_kind_map = T.mb_kind_map;
   if (MBLDS) asm volatile("" : "+v"(mb_lds_lane));
+  // LINKS: the current op's first out-edge (latency << 13 | link word offset), the address of its link
+  // word and that word's value; the second out-edge is looked at when the op issues
+  const unsigned link_base = stt_off + (unsigned)T.state_words * 256u;
+  const unsigned link_dummy = LINKS ? (unsigned)(T.link_words - 1) * 256u : 0u;
+  unsigned out1 = link_dummy, out2 = link_dummy, at_link1 = link_base, lf1 = 0u;
   auto decode = [&](unsigned word) {
     const unsigned j = word & 0x7ffu;
     const unsigned jc = min(j, (unsigned)m - 1u);
@@ -269,6 +293,18 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     // for F and FD and clear for B (other kinds have no input, whatever they read is ignored)
     at_in = ONE_CLASS ? __umul24(fwd, m4) + at_slot
                       : at_slot + (unsigned)(is_b ? pick<V>(cons_b, c) : pick<V>(cons_f, c));
+    if (LINKS) {
+      const unsigned kind = word >> 13;
+      const bool sends = is_b || kind == (unsigned)kF || kind == (unsigned)kFD;
+      const unsigned o1 = (unsigned)(is_b ? pick<V>(out_b, c) : pick<V>(out_f, c));
+      out1 = sends ? o1 : link_dummy;
+      at_link1 = link_base + (out1 & 0x1fffu);
+      lf1 = lds_read<uint32_t>(at_link1);
+      if (DEG2) {
+        const unsigned o2 = (unsigned)(is_b ? pick<V>(out_b2, c) : pick<V>(out_f2, c));
+        out2 = sends ? o2 : link_dummy;
+      }
+    }
     if (DEG2) {
       // second-edge rows are per direction, not per kind: only F, FD and B have cross-stage
       // edges, every other kind reads the all-zero ninth row
@@ -377,7 +413,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
           for (int i = d; i < slots_per_cand; i += lpc) my_slots[i] = kEmptySlot;
         }
         if (running && lane_ok) {
-          for (int i = 0; i < T.state_words; ++i) stt[i * 64 + lane] = 0u;
+          for (int i = 0; i < lane_words; ++i) stt[i * 64 + lane] = 0u;
           row = ops + ((size_t)cand * T.D + d) * (size_t)stride;
           // start times: [candidate][group of four positions][lane of the candidate][4]
           if (TIMES) start_row = out_start8 + (size_t)cand * (size_t)stride * (size_t)lpc + ((size_t)d << 2);
@@ -452,13 +488,31 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1"
           : "=v"(flip) : "v"(bj), "v"(mx_));
       lds_write<uint32_t>(at_state, sx ^ flip);
+      // LINKS: the value leaves when the link to its consumer's device is free, and keeps it busy for
+      // the edge's latency (an op that sends nothing off the device uses the lane's spare link word,
+      // which never holds more than an earlier finish time)
+      unsigned leave8 = fin8;
+      if (LINKS) {
+        leave8 = max(fin8, lf1);
+        lds_write<uint32_t>(at_link1, leave8 + ((out1 >> 13) << 8));
+      }
       // finish << 8 | own stage (byte 2 of the last metadata dword; the low byte of fin8 is zero)
-      const unsigned val = __builtin_amdgcn_perm(fin8, my_, 0x07060502u);
+      const unsigned val = __builtin_amdgcn_perm(leave8, my_, 0x07060502u);
       // byte offset of the output slot in the high half; ops without an output edge write the
       // candidate's dump region, which nobody reads
       lds_write<uint32_t>(bj + (mx_ >> 16), val);
       if (DEG2) {
-        if ((unsigned)M2.y & kMetaHasProd) lds_write<uint32_t>(bj + ((unsigned)M2.y & 0xffffu), val);
+        if ((unsigned)M2.y & kMetaHasProd) {
+          unsigned val2 = val;
+          if (LINKS) {
+            // (read after the write above: both edges may use the same link)
+            const unsigned at_link2 = link_base + (out2 & 0x1fffu);
+            const unsigned leave2 = max(fin8, lds_read<uint32_t>(at_link2));
+            lds_write<uint32_t>(at_link2, leave2 + ((out2 >> 13) << 8));
+            val2 = __builtin_amdgcn_perm(leave2, my_, 0x07060502u);
+          }
+          lds_write<uint32_t>(bj + ((unsigned)M2.y & 0xffffu), val2);
+        }
       }
       free_at8 = fin8;
       busy8 += dur8;
@@ -544,7 +598,8 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotPlain)    \
   FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotTimes)    \
   FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotPerMicrobatch) \
-  FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotPerMicrobatchLds)
+  FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotPerMicrobatchLds) \
+  FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotLinks)
 FPSCHED_INSTANTIATE(1, false, true)
 FPSCHED_INSTANTIATE(2, false, true)
 FPSCHED_INSTANTIATE(4, false, true)

@@ -46,6 +46,12 @@ struct fpsched_problem {
   bool mb_slots_ok = false;        // the table's values fit the slot kernel's 24-bit times
   int32_t* d_mb_raw = nullptr;     // [kinds][S][m]
   int32_t* d_mb_rows = nullptr;    // [32 metadata rows][lanes per candidate][m], << 8
+  // link occupancy (fpsched_problem_set_link_occupancy): a table image with longer dev rows
+  int64_t max_dur = 0;
+  bool links_on = false;
+  SlotTables stab_links{};
+  int32_t* d_links_image = nullptr;
+  int32_t links_waves = 0, links_grid = 0, links_lds_bytes = 0;
   // ... or, when the values fit sixteen bits and the table fits LDS, inside a second table image
   bool mb_in_lds = false;
   SlotTables stab_mb{};
@@ -200,6 +206,7 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
   }
   if (rc != FPSCHED_OK) { delete p; return rc; }
   p->max_comm = max_comm;
+  p->max_dur = max_dur;
 
   // table image
   std::vector<int32_t>& I = p->host_ints;
@@ -389,6 +396,7 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
       ST.off_dev = n_shared;
       ST.dev_ints = dev_ints;
       ST.off_mb = 0;
+      ST.link_words = 0;
       ST.mb_kind_map = 0;
       ST.mb_value_bytes = 2;
       const SlotGeometry geo = slot_geometry(ST.n_shared_ints, lpc, ST.state_words, ST.slots_per_cand, max_lds);
@@ -482,6 +490,7 @@ void fpsched_problem_destroy(fpsched_problem* p) {
     if (p->d_mb_raw) (void)hipFree(p->d_mb_raw);
     if (p->d_mb_rows) (void)hipFree(p->d_mb_rows);
     if (p->d_mb_image) (void)hipFree(p->d_mb_image);
+    if (p->d_links_image) (void)hipFree(p->d_links_image);
   }
   delete p;
 }
@@ -534,6 +543,7 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
   if (reinterpret_cast<uintptr_t>(d_ops) & 15) return FPSCHED_EINVAL;
   DeviceGuard g(p->device_id);
   if (!g.ok) return FPSCHED_EHIP;
+  if (p->links_on && !p->use_slots) return FPSCHED_EUNSUPPORTED;   // the general kernel has no link form
   if (p->use_slots && (!p->mb_set || p->mb_slots_ok)) {
     // the first 8 bytes of the workspace hold the counter the segments draw candidates from
     if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) & 15)) return FPSCHED_EINVAL;
@@ -541,10 +551,11 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
     unsigned long long* counter = static_cast<unsigned long long*>(d_workspace);
     // costs per micro-batch: their own table image and workgroup shape when the table sits in LDS
     const bool mb_lds = p->mb_set && p->mb_in_lds;
-    const SlotTables& tab = mb_lds ? p->stab_mb : p->stab;
-    const int waves = mb_lds ? p->mb_waves : p->slot_waves;
-    const int grid = mb_lds ? p->mb_grid : p->slot_grid;
-    const size_t lds_bytes = (size_t)(mb_lds ? p->mb_lds_bytes : p->slot_lds_bytes);
+    const bool links = p->links_on;   // (never together with costs per micro-batch)
+    const SlotTables& tab = links ? p->stab_links : (mb_lds ? p->stab_mb : p->stab);
+    const int waves = links ? p->links_waves : (mb_lds ? p->mb_waves : p->slot_waves);
+    const int grid = links ? p->links_grid : (mb_lds ? p->mb_grid : p->slot_grid);
+    const size_t lds_bytes = (size_t)(links ? p->links_lds_bytes : (mb_lds ? p->mb_lds_bytes : p->slot_lds_bytes));
     const int per_block = tab.cands_per_wave * waves;
     const int64_t blocks = std::min<int64_t>((n_cand + per_block - 1) / per_block, grid);
     // Candidates per atomic draw.  Atomics on one address complete at some 8e7 per second; a batch of
@@ -556,7 +567,8 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
     hipLaunchKernelGGL(reset_counter_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(hip_stream), counter,
                        (unsigned long long)(blocks * per_block));
     const bool one_class = p->stab.n_classes == 1;
-    const SlotKernel kernel = !p->mb_set ? slot_kernel_ptr(p->slot_v, p->slot_deg2, one_class)
+    const SlotKernel kernel = links ? slot_kernel_of<kSlotLinks>(p->slot_v, p->slot_deg2, one_class)
+                              : !p->mb_set ? slot_kernel_ptr(p->slot_v, p->slot_deg2, one_class)
                               : (mb_lds ? slot_kernel_of<kSlotPerMicrobatchLds>(p->slot_v, p->slot_deg2, one_class)
                                         : slot_kernel_of<kSlotPerMicrobatch>(p->slot_v, p->slot_deg2, one_class));
     hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(64 * waves), lds_bytes,
@@ -584,6 +596,7 @@ int fpsched_problem_set_microbatch_costs(fpsched_problem* p, const int32_t* dur_
     p->mb_set = false;   // the tables stay allocated for the next call
     return FPSCHED_OK;
   }
+  if (p->links_on) return FPSCHED_EUNSUPPORTED;   // one variant of the cost model at a time
   const int D = p->D, S = p->S, m = p->m;
   const size_t n_raw = (size_t)kNKinds * S * m;
   int64_t max_dur = 0;
@@ -701,6 +714,112 @@ int fpsched_problem_set_microbatch_costs(fpsched_problem* p, const int32_t* dur_
             p->slot_grid / std::max(p->n_cu, 1), p->slot_waves, p->max_lds);
   p->mb_set = true;
   p->mb_slots_ok = p->slots_ok && fits_slots;
+  return FPSCHED_OK;
+}
+
+int fpsched_problem_set_link_occupancy(fpsched_problem* p, int32_t on) {
+  if (!p) return FPSCHED_EINVAL;
+  if (!on) {
+    p->links_on = false;   // the table image stays allocated for the next call
+    return FPSCHED_OK;
+  }
+  if (p->mb_set) return FPSCHED_EUNSUPPORTED;   // one variant of the cost model at a time
+  const int D = p->D, S = p->S;
+  // every finish time is at most the sum of all costs and of all transfers (at most two per op here)
+  const int64_t bound = (int64_t)D * p->max_stride * (p->max_dur + 2 * p->max_comm);
+  if (bound >= (int64_t)1 << 31) return FPSCHED_EOVERFLOW;
+  if (p->device_id < 0) {
+    p->links_on = true;
+    return FPSCHED_OK;
+  }
+  if (!p->slots_ok || bound >= (1ll << 24)) return FPSCHED_EUNSUPPORTED;
+  if (p->d_links_image) {   // built by an earlier call
+    p->links_on = true;
+    return FPSCHED_OK;
+  }
+  // links of a device: the devices its stages send to (activations to successor stages, gradients to
+  // predecessor stages), numbered in the order they are met
+  const std::vector<int32_t>& I = p->host_ints;
+  const DevTables& T = p->tables;
+  const SlotTables& ST = p->stab;
+  const int V = p->slot_v, lpc = ST.lanes_per_cand;
+  std::vector<std::vector<int>> sends_to(D);
+  auto link_of = [&](int d, int to) {
+    for (size_t i = 0; i < sends_to[d].size(); ++i) if (sends_to[d][i] == to) return (int)i;
+    sends_to[d].push_back(to);
+    return (int)sends_to[d].size() - 1;
+  };
+  struct OutEdge { int to, comm; };
+  auto out_edge = [&](int s, bool forward, int k, OutEdge* e) {
+    const int off = forward ? T.off_succ_off : T.off_pred_off;
+    const int at = I[off + s] + k;
+    if (at >= I[off + s + 1]) return false;
+    e->to = p->stage_device[I[(forward ? T.off_succ_stage : T.off_pred_stage) + at]];
+    e->comm = I[(forward ? T.off_succ_comm : T.off_pred_comm) + at];
+    return true;
+  };
+  for (int s = 0; s < S; ++s)
+    for (int fwd = 0; fwd < 2; ++fwd)
+      for (int k = 0; k < 2; ++k) {
+        OutEdge e;
+        if (out_edge(s, fwd != 0, k, &e) && e.to != p->stage_device[s]) (void)link_of(p->stage_device[s], e.to);
+      }
+  int link_words = 1;
+  for (int d = 0; d < D; ++d) link_words = std::max(link_words, (int)sends_to[d].size() + 1);
+  if (link_words * 256 > 0x1fff) return FPSCHED_EUNSUPPORTED;
+  const uint32_t spare = (uint32_t)(link_words - 1) * 256u;   // latency 0, the word nobody waits for
+  const SlotGeometry geo = slot_geometry(ST.n_shared_ints, lpc, ST.state_words + link_words, ST.slots_per_cand, p->max_lds);
+  if (geo.waves < 1 || geo.cands_per_wave != ST.cands_per_wave) return FPSCHED_EUNSUPPORTED;
+  // the plain image with longer dev rows: [.. 2 + 4V ints as before ..][4V out-edges]
+  const int dev_ints = ST.dev_ints + 4 * V;
+  std::vector<int32_t> J((size_t)ST.n_shared_ints + (size_t)lpc * dev_ints + (size_t)lpc * ST.state_words, 0);
+  std::copy(p->slot_ints.begin(), p->slot_ints.begin() + ST.n_shared_ints, J.begin());
+  for (int d = 0; d < lpc; ++d) {
+    int32_t* row = &J[(size_t)ST.n_shared_ints + (size_t)d * dev_ints];
+    std::copy(p->slot_ints.begin() + ST.off_dev + (size_t)d * ST.dev_ints,
+              p->slot_ints.begin() + ST.off_dev + (size_t)(d + 1) * ST.dev_ints, row);
+    for (int i = 0; i < 4 * V; ++i) row[ST.dev_ints + i] = (int32_t)spare;
+    if (d >= D) continue;
+    for (int c = 0; c < p->n_chunks[d]; ++c) {
+      const int s = p->local_stage[(size_t)d * kMaxChunks + c];
+      for (int fwd = 0; fwd < 2; ++fwd)
+        for (int k = 0; k < 2; ++k) {
+          OutEdge e;
+          if (!out_edge(s, fwd != 0, k, &e) || e.to == d) continue;
+          // first forward / first backward / second forward / second backward
+          row[ST.dev_ints + (2 * k + (fwd ? 0 : 1)) * V + c] =
+              (int32_t)(((uint32_t)e.comm << 13) | (uint32_t)link_of(d, e.to) * 256u);
+        }
+    }
+  }
+  std::copy(p->slot_ints.begin() + ST.off_expect, p->slot_ints.end(),
+            J.begin() + ST.n_shared_ints + (size_t)lpc * dev_ints);
+  DeviceGuard g(p->device_id);
+  if (!g.ok) return FPSCHED_EHIP;
+  int32_t* image = nullptr;
+  if (hipMalloc(&image, J.size() * sizeof(int32_t)) != hipSuccess) return FPSCHED_ENOMEM;
+  const SlotKernel kernel = slot_kernel_of<kSlotLinks>(p->slot_v, p->slot_deg2, ST.n_classes == 1);
+  const int32_t lds_bytes = (int32_t)(4ll * (ST.n_shared_ints + (int64_t)geo.waves * geo.wave_ints));
+  if (hipMemcpy(image, J.data(), J.size() * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess ||
+      hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess) {
+    (void)hipFree(image);
+    return FPSCHED_EHIP;
+  }
+  p->d_links_image = image;
+  p->stab_links = ST;
+  p->stab_links.ints = image;
+  p->stab_links.link_words = link_words;
+  p->stab_links.dev_ints = dev_ints;
+  p->stab_links.off_expect = ST.n_shared_ints + lpc * dev_ints;
+  p->stab_links.cands_per_wave = geo.cands_per_wave;
+  p->stab_links.wave_ints = geo.wave_ints;
+  p->links_waves = geo.waves;
+  p->links_grid = p->n_cu * geo.groups;
+  p->links_lds_bytes = lds_bytes;
+  p->links_on = true;
+  if (getenv("FPSCHED_VERBOSE"))
+    fprintf(stderr, "[fpsched] link occupancy: %d link words per lane, %d x %d wavefronts per compute unit (plain: %d x %d)\n",
+            link_words, geo.groups, geo.waves, p->slot_grid / std::max(p->n_cu, 1), p->slot_waves);
   return FPSCHED_OK;
 }
 
@@ -851,7 +970,8 @@ int fpsched_wslide(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_ca
   if (!p || n_cand < 0) return FPSCHED_EINVAL;
   if (p->device_id < 0) return FPSCHED_ENODEV;
   if (!p->has_w) return FPSCHED_EINVAL;
-  if (!p->slide_ok || p->mb_set) return FPSCHED_EUNSUPPORTED;   // the pass knows one cost per (type, stage)
+  // the pass knows one cost per (type, stage) and transfers as pure latencies
+  if (!p->slide_ok || p->mb_set || p->links_on) return FPSCHED_EUNSUPPORTED;
   if (n_cand == 0) return FPSCHED_OK;
   if (!d_ops || !d_ops_out || !out.makespan || !out.idle || !out.peak || !out.flags) return FPSCHED_EINVAL;
   if (stride_words < 8 || (stride_words & 7) || stride_words > p->max_stride) return FPSCHED_EINVAL;

@@ -9,9 +9,10 @@ import paper_2510_05112_amd as fp
 KERNELS = ("slots", "general")
 
 
-def gpu_evaluate(problem, words, k=None, max_stride=None, kernel="auto", dur_mb=None):
+def gpu_evaluate(problem, words, k=None, max_stride=None, kernel="auto", dur_mb=None, links=False):
     """words: uint16 [C][D][stride] (numpy).  Returns (results dict of numpy arrays, topk tuple or None).
-    dur_mb[8][S][m]: costs per micro-batch, set on the handle before the batch is evaluated."""
+    dur_mb[8][S][m]: costs per micro-batch, set on the handle before the batch is evaluated; links: the
+    link-occupancy variant (a problem or kernel that has no such form gives (None, None))."""
     words = np.ascontiguousarray(words, dtype=np.uint16)
     C, D, stride = words.shape
     h = fp.Problem(problem, max_stride or stride, device=0)
@@ -24,6 +25,16 @@ def gpu_evaluate(problem, words, k=None, max_stride=None, kernel="auto", dur_mb=
         return None, None
     if dur_mb is not None:
         h.set_microbatch_costs(dur_mb)
+    if links:
+        try:
+            if kernel == "general":
+                raise fp.FpschedError(-6, "the general kernel has no link form")
+            h.set_link_occupancy(True)
+        except fp.FpschedError as e:
+            if e.code != -6:
+                raise
+            h.close()
+            return None, None
     ops = torch.from_numpy(words.view(np.int16)).cuda() if C else torch.empty((0, D, stride), dtype=torch.int16, device="cuda")
     res = h.evaluate(ops)
     top = None
@@ -46,12 +57,12 @@ def assert_same(gpu, ref, what=""):
                                  f"gpu {a[bad[0]]} oracle {b[bad[0]]}")
 
 
-def check_batch(problem, words, k=None, what="", threads=8, kernels=KERNELS, dur_mb=None):
+def check_batch(problem, words, k=None, what="", threads=8, kernels=KERNELS, dur_mb=None, links=False):
     """Every kernel variant of the library against the oracle, element by element."""
-    ref = oracle.evaluate(problem, words, threads=threads, dur_mb=dur_mb)
+    ref = oracle.evaluate(problem, words, threads=threads, dur_mb=dur_mb, links=links)
     gpu, ran = None, 0
     for kernel in kernels:
-        g, top = gpu_evaluate(problem, words, k, kernel=kernel, dur_mb=dur_mb)
+        g, top = gpu_evaluate(problem, words, k, kernel=kernel, dur_mb=dur_mb, links=links)
         if g is None:
             continue
         gpu, ran = g, ran + 1
