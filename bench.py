@@ -28,6 +28,8 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
 MEASURED = {("cfg4", 65536): {"traffic_bytes": 4.514e9, "valu_wave_instructions": 2.088e9}}
 # with costs per micro-batch (--mb-costs): profiles/eval_slot_kernel_cfg4_microbatch_costs.md
 MEASURED_MB = {("cfg4", 65536): {"traffic_bytes": None, "valu_wave_instructions": 2.694e9}}
+# with link occupancy (--links): profiles/eval_slot_kernel_cfg4_link_occupancy.md
+MEASURED_LINKS = {}
 # int32 vector peak: 256 CUs x 4 SIMDs x 16 lanes, one operation per lane and clock at 2.4 GHz
 # (= the published 157.3 TFLOP/s fp32 vector figure / 4: an FMA counts two, packed issue two more)
 ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
@@ -303,6 +305,9 @@ def main() -> int:
     ap.add_argument("--mb-costs", action="store_true",
                     help="evaluate mode: costs per micro-batch (seeded factors in [1/2, 3/2) on the "
                          "configuration's costs) instead of one cost per (type, stage)")
+    ap.add_argument("--links", action="store_true",
+                    help="evaluate mode: the link-occupancy variant of the cost model (every ordered pair of "
+                         "devices carries one value at a time) instead of pure latencies")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain elementwise copy of the op batch (a kernel of known HBM "
                          "traffic, used to calibrate rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -341,6 +346,11 @@ def main() -> int:
 
     handle = fp.Problem(prob, stride, device=0)
     dur_mb = None
+    if args.links and args.mb_costs:
+        print("bench.py: --links and --mb-costs are two variants of the cost model; pick one.", file=sys.stderr)
+        return 2
+    if args.links:
+        handle.set_link_occupancy(True)
     if args.mb_costs:
         dur_mb = workloads.microbatch_costs(prob)
         handle.set_microbatch_costs(dur_mb)
@@ -394,7 +404,7 @@ def main() -> int:
     alg_bytes = 2 * n_ops + C * (8 + 8 * D + 4 * D + 1)
     achieved = alg_bytes / (eval_ms * 1e-3) / 1e9
 
-    measured = (MEASURED_MB if args.mb_costs else MEASURED).get((f"cfg{spec.index}", C), {})
+    measured = (MEASURED_LINKS if args.links else MEASURED_MB if args.mb_costs else MEASURED).get((f"cfg{spec.index}", C), {})
     hbm_view = {"achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                 "algorithmic_bytes_per_launch": alg_bytes}
     kernel_name = "fpsched evaluation kernel (eval_slot_kernel)"
@@ -426,7 +436,8 @@ def main() -> int:
         "dtype": "int32", "data": "synthetic",
         "config": {"workload": f"cfg{spec.index}: {prob.name}, {C} candidates, top-{k}, "
                                f"cap {int(prob.mem_cap[0])} units/device"
-                               + (", costs per micro-batch (factors in [1/2, 3/2))" if args.mb_costs else ""),
+                               + (", costs per micro-batch (factors in [1/2, 3/2))" if args.mb_costs else "")
+                               + (", link occupancy" if args.links else ""),
                    "candidates": C, "devices": D, "stages": prob.n_stages,
                    "microbatches": prob.n_microbatches, "ops_per_candidate": n_ops / C,
                    "stride_words": stride, "top_k": k},
@@ -448,7 +459,7 @@ def main() -> int:
         if args.check:
             rng = np.random.default_rng(0)
             pick = np.sort(rng.choice(C, min(args.check, C), replace=False))
-            ref = oracle.evaluate(prob, words[pick], threads=threads, dur_mb=dur_mb)
+            ref = oracle.evaluate(prob, words[pick], threads=threads, dur_mb=dur_mb, links=args.links)
             ok = all(np.array_equal(res[n][torch.from_numpy(pick).to(dev)].cpu().numpy(), ref[n])
                      for n in ("makespan", "idle", "peak", "flags"))
             out["parity_sample"] = {"candidates": int(len(pick)), "bit_exact": bool(ok)}
@@ -457,11 +468,11 @@ def main() -> int:
         if not args.no_cpu_baseline:
             n1 = min(C, args.cpu_sample or max(64, int(120e6 // max(1, n_ops // C))))
             t0 = time.perf_counter()
-            oracle.evaluate(prob, words[:n1], threads=1, dur_mb=dur_mb)
+            oracle.evaluate(prob, words[:n1], threads=1, dur_mb=dur_mb, links=args.links)
             t1 = time.perf_counter() - t0
             nn = min(C, n1 * min(threads, 8))
             t0 = time.perf_counter()
-            oracle.evaluate(prob, words[:nn], threads=threads, dur_mb=dur_mb)
+            oracle.evaluate(prob, words[:nn], threads=threads, dur_mb=dur_mb, links=args.links)
             tn = time.perf_counter() - t0
             out["cpu_baseline"] = {
                 "value": nn / tn, "unit": "schedules/s", "cores": threads, "kind": "oracle",

@@ -87,9 +87,10 @@ struct SlotTables {
                             // slot_mb_row_dwords(m, bytes) dwords], padded to a multiple of 512 ints
   int32_t mb_value_bytes;
   int32_t link_words;       // link mode: dwords per lane behind its state words, one per device this device
-                            // sends to plus one that takes the values nobody waits for (0 = plain model);
+                            // sends to, one for values that stay on the device and, last, one that takes
+                            // what ops without an out-edge write (0 = plain model);
                             // the dev rows then have 4V more ints: per chunk the first forward / first backward /
-                            // second forward / second backward out-edge as latency << 13 | byte offset of its
+                            // second forward / second backward out-edge as latency << 16 | byte offset of its
                             // link word (link index * 256)
   uint32_t mb_kind_map;     // four bits per kind: which block of the table at off_mb holds the kind's costs
                             // (kinds with the same costs share a block)

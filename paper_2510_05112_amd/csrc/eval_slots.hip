@@ -184,7 +184,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     asm volatile("" : "+v"(cons_f[c]), "+v"(cons_b[c]), "+v"(cons_f2[c]), "+v"(cons_b2[c]));
   }
   asm volatile("" : "+v"(cap));
-  // LINKS: per chunk the out-edges as latency << 13 | byte offset of the link word
+  // LINKS: per chunk the out-edges as latency << 16 | byte offset of the link word
   int out_f[V], out_b[V], out_f2[V], out_b2[V];
 #pragma unroll
   for (int c = 0; c < V; ++c) {
@@ -262,6 +262,9 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   // word and that word's value; the second out-edge is looked at when the op issues
   const unsigned link_base = stt_off + (unsigned)T.state_words * 256u;
   const unsigned link_dummy = LINKS ? (unsigned)(T.link_words - 1) * 256u : 0u;
+  unsigned spare_at = link_base + link_dummy;
+  if (LINKS) asm volatile("" : "+v"(spare_at));
+  const unsigned dump_bytes = (unsigned)(2 * T.n_classes * m) * 4u;   // offset of the slots nobody reads
   unsigned out1 = link_dummy, out2 = link_dummy, at_link1 = link_base, lf1 = 0u;
   auto decode = [&](unsigned word) {
     const unsigned j = word & 0x7ffu;
@@ -294,16 +297,12 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     at_in = ONE_CLASS ? __umul24(fwd, m4) + at_slot
                       : at_slot + (unsigned)(is_b ? pick<V>(cons_b, c) : pick<V>(cons_f, c));
     if (LINKS) {
-      const unsigned kind = word >> 13;
-      const bool sends = is_b || kind == (unsigned)kF || kind == (unsigned)kFD;
-      const unsigned o1 = (unsigned)(is_b ? pick<V>(out_b, c) : pick<V>(out_f, c));
-      out1 = sends ? o1 : link_dummy;
-      at_link1 = link_base + (out1 & 0x1fffu);
+      // by direction and chunk only: whether the op has an out-edge at all is known when its metadata
+      // row is there, i.e. when it issues (an op without one must not touch a real link word)
+      out1 = (unsigned)(is_b ? pick<V>(out_b, c) : pick<V>(out_f, c));
+      at_link1 = link_base + (out1 & 0xffffu);
       lf1 = lds_read<uint32_t>(at_link1);
-      if (DEG2) {
-        const unsigned o2 = (unsigned)(is_b ? pick<V>(out_b2, c) : pick<V>(out_f2, c));
-        out2 = sends ? o2 : link_dummy;
-      }
+      if (DEG2) out2 = (unsigned)(is_b ? pick<V>(out_b2, c) : pick<V>(out_f2, c));
     }
     if (DEG2) {
       // second-edge rows are per direction, not per kind: only F, FD and B have cross-stage
@@ -493,8 +492,11 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       // which never holds more than an earlier finish time)
       unsigned leave8 = fin8;
       if (LINKS) {
+        // (an op without an out-edge writes the dump region and the lane's last link word: never read back
+        // by an op whose value counts)
         leave8 = max(fin8, lf1);
-        lds_write<uint32_t>(at_link1, leave8 + ((out1 >> 13) << 8));
+        const bool has_out = (mx_ >> 16) != dump_bytes;
+        lds_write<uint32_t>(has_out ? at_link1 : spare_at, leave8 + ((out1 >> 16) << 8));
       }
       // finish << 8 | own stage (byte 2 of the last metadata dword; the low byte of fin8 is zero)
       const unsigned val = __builtin_amdgcn_perm(leave8, my_, 0x07060502u);
@@ -506,9 +508,9 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
           unsigned val2 = val;
           if (LINKS) {
             // (read after the write above: both edges may use the same link)
-            const unsigned at_link2 = link_base + (out2 & 0x1fffu);
+            const unsigned at_link2 = link_base + (out2 & 0xffffu);
             const unsigned leave2 = max(fin8, lds_read<uint32_t>(at_link2));
-            lds_write<uint32_t>(at_link2, leave2 + ((out2 >> 13) << 8));
+            lds_write<uint32_t>(at_link2, leave2 + ((out2 >> 16) << 8));
             val2 = __builtin_amdgcn_perm(leave2, my_, 0x07060502u);
           }
           lds_write<uint32_t>(bj + ((unsigned)M2.y & 0xffffu), val2);

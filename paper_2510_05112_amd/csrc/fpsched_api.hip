@@ -764,10 +764,13 @@ int fpsched_problem_set_link_occupancy(fpsched_problem* p, int32_t on) {
         OutEdge e;
         if (out_edge(s, fwd != 0, k, &e) && e.to != p->stage_device[s]) (void)link_of(p->stage_device[s], e.to);
       }
-  int link_words = 1;
-  for (int d = 0; d < D; ++d) link_words = std::max(link_words, (int)sends_to[d].size() + 1);
-  if (link_words * 256 > 0x1fff) return FPSCHED_EUNSUPPORTED;
-  const uint32_t spare = (uint32_t)(link_words - 1) * 256u;   // latency 0, the word nobody waits for
+  // two more words per lane: one for values that stay on the device (latency 0; it only ever holds
+  // earlier finish times of the device, so nothing waits for it) and one that takes what ops without an
+  // out-edge write
+  int link_words = 2;
+  for (int d = 0; d < D; ++d) link_words = std::max(link_words, (int)sends_to[d].size() + 2);
+  if (link_words * 256 > 0xffff) return FPSCHED_EUNSUPPORTED;
+  const uint32_t spare = (uint32_t)(link_words - 2) * 256u;
   const SlotGeometry geo = slot_geometry(ST.n_shared_ints, lpc, ST.state_words + link_words, ST.slots_per_cand, p->max_lds);
   if (geo.waves < 1 || geo.cands_per_wave != ST.cands_per_wave) return FPSCHED_EUNSUPPORTED;
   // the plain image with longer dev rows: [.. 2 + 4V ints as before ..][4V out-edges]
@@ -788,7 +791,7 @@ int fpsched_problem_set_link_occupancy(fpsched_problem* p, int32_t on) {
           if (!out_edge(s, fwd != 0, k, &e) || e.to == d) continue;
           // first forward / first backward / second forward / second backward
           row[ST.dev_ints + (2 * k + (fwd ? 0 : 1)) * V + c] =
-              (int32_t)(((uint32_t)e.comm << 13) | (uint32_t)link_of(d, e.to) * 256u);
+              (int32_t)(((uint32_t)e.comm << 16) | (uint32_t)link_of(d, e.to) * 256u);
         }
     }
   }

@@ -81,6 +81,14 @@ def test_full_batch_every_candidate_against_oracle(index):
         r_idx, r_ms, r_cnt = oracle.topk(ref["makespan"], ref["flags"], spec.top_k)
         assert int(top["count"].item()) == r_cnt and np.array_equal(top["idx"].cpu().numpy(), r_idx)
         assert np.array_equal(top["makespan"].cpu().numpy(), r_ms)
+        h.set_microbatch_costs(None)
+        # ... and with links that carry one value at a time (the launch `bench.py --links` times)
+        h.set_link_occupancy(True)
+        res = h.evaluate(ops, workspace=ws)
+        torch.cuda.synchronize()
+        ref = oracle.evaluate(prob, words, threads=16, links=True)
+        for name in ("flags", "makespan", "idle", "peak"):
+            assert np.array_equal(res[name].cpu().numpy(), ref[name]), f"link occupancy: {name}"
     h.close()
 
 
