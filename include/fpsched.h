@@ -27,6 +27,14 @@
  * distinct handles, and calls on one handle that use distinct workspaces and
  * output buffers, may run from different host threads and on different streams.
  * Device calls only enqueue kernels on the given stream and return.
+ *
+ * Environment variables, read when the call they belong to runs; none changes a result:
+ *   FPSCHED_SLOT_WAVES=n  (fpsched_problem_create, the two cost-model setters) at most n wavefronts
+ *                         per workgroup of the main evaluation kernel, one workgroup per compute unit;
+ *   FPSCHED_GEN_WAVES=n   (fpsched_generate) n resident wavefronts per compute unit, default 16;
+ *   FPSCHED_MB_GLOBAL=1   (fpsched_problem_set_microbatch_costs) keep the cost table in device
+ *                         memory even where it would fit LDS;
+ *   FPSCHED_VERBOSE=1     the two cost-model setters print the kernel form and shape they chose.
  */
 #ifndef FPSCHED_H
 #define FPSCHED_H
