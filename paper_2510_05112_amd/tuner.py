@@ -110,7 +110,9 @@ def tune(handle, problem, circular: bool, k: int = 8, inflight_options=None, for
     with a stride of at least ``stride_for(problem)``.  slide: for problems with split backward,
     also rank every generated schedule after the weight-gradient sliding pass (Section 5.2, bubble
     optimizations); such entries have ``slid`` set.  Returns the k best feasible schedules as a list
-    of dicts (label, makespan, index into the grid, slid)."""
+    of dicts (label, makespan, index into the grid, slid).  The schedules are timed with whatever cost
+    model the handle is set to (``set_microbatch_costs``, ``set_link_occupancy``); the sliding pass
+    only knows the plain one."""
     import torch
 
     labels, pol, inf = grid(problem, circular, inflight_options, forward_first)

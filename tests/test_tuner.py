@@ -107,3 +107,31 @@ def test_gpu_search_over_the_grid_matches_the_oracles(strategy, p, v):
     assert [b["index"] for b in best] == list(idx[:cnt]) and [b["makespan"] for b in best] == list(ms[:cnt])
     assert cnt > 0 and best[0]["label"] == labels[idx[0]]
     h.close()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("variant", ["costs per micro-batch", "link occupancy"])
+def test_gpu_search_under_the_other_cost_models_matches_the_oracles(variant):
+    import paper_2510_05112_amd as fp
+    import workloads
+    prob = chain(4, 2, 12, "circular", seed=3)
+    prob.edge_comm[:] = 9   # of the order of an item's cost: a link is often busy
+    st = tuner.stride_for(prob)
+    h = fp.Problem(prob, st, device=0)
+    kwargs = {}
+    if variant == "link occupancy":
+        h.set_link_occupancy(True)
+        kwargs["links"] = True
+    else:
+        kwargs["dur_mb"] = workloads.microbatch_costs(prob)
+        h.set_microbatch_costs(kwargs["dur_mb"])
+    best = tuner.tune(h, prob, True, k=5)
+    labels, pol, inf = tuner.grid(prob, True)
+    words = oracle.generate(prob, pol, inf, st)["words"]
+    ref = oracle.evaluate(prob, words, **kwargs)
+    idx, ms, cnt = oracle.topk(ref["makespan"], ref["flags"], 5)
+    assert cnt > 0 and [b["index"] for b in best] == list(idx[:cnt]) and [b["makespan"] for b in best] == list(ms[:cnt])
+    # the model matters for the ranking's makespans
+    plain = oracle.evaluate(prob, words)
+    assert not np.array_equal(plain["makespan"], ref["makespan"])
+    h.close()
