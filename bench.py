@@ -29,7 +29,7 @@ MEASURED = {("cfg4", 65536): {"traffic_bytes": 4.514e9, "valu_wave_instructions"
 # with costs per micro-batch (--mb-costs): profiles/eval_slot_kernel_cfg4_microbatch_costs.md
 MEASURED_MB = {("cfg4", 65536): {"traffic_bytes": None, "valu_wave_instructions": 2.694e9}}
 # with link occupancy (--links): profiles/eval_slot_kernel_cfg4_link_occupancy.md
-MEASURED_LINKS = {("cfg4", 65536): {"traffic_bytes": None, "valu_wave_instructions": 2.825e9}}
+MEASURED_LINKS = {("cfg4", 65536): {"traffic_bytes": None, "valu_wave_instructions": 2.890e9}}
 # int32 vector peak: 256 CUs x 4 SIMDs x 16 lanes, one operation per lane and clock at 2.4 GHz
 # (= the published 157.3 TFLOP/s fp32 vector figure / 4: an FMA counts two, packed issue two more)
 ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12

@@ -501,8 +501,10 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       // finish << 8 | own stage (byte 2 of the last metadata dword; the low byte of fin8 is zero)
       const unsigned val = __builtin_amdgcn_perm(leave8, my_, 0x07060502u);
       // byte offset of the output slot in the high half; ops without an output edge write the
-      // candidate's dump region, which nobody reads
-      lds_write<uint32_t>(bj + (mx_ >> 16), val);
+      // candidate's dump region, which nobody reads (LINKS: the lane's last link word instead; that
+      // form's tables have no dump region, its offset only marks such ops)
+      if (LINKS) lds_write<uint32_t>((mx_ >> 16) != dump_bytes ? bj + (mx_ >> 16) : spare_at, val);
+      else lds_write<uint32_t>(bj + (mx_ >> 16), val);
       if (DEG2) {
         if ((unsigned)M2.y & kMetaHasProd) {
           unsigned val2 = val;

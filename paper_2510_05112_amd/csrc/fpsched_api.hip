@@ -771,7 +771,10 @@ int fpsched_problem_set_link_occupancy(fpsched_problem* p, int32_t on) {
   for (int d = 0; d < D; ++d) link_words = std::max(link_words, (int)sends_to[d].size() + 2);
   if (link_words * 256 > 0xffff) return FPSCHED_EUNSUPPORTED;
   const uint32_t spare = (uint32_t)(link_words - 2) * 256u;
-  const SlotGeometry geo = slot_geometry(ST.n_shared_ints, lpc, ST.state_words + link_words, ST.slots_per_cand, p->max_lds);
+  // (this form of the kernel needs no dump region behind the slots: ops without an out-edge write the
+  // lane's last link word)
+  const int slots_per_cand = (2 * ST.n_classes * p->m + 7) & ~7;
+  const SlotGeometry geo = slot_geometry(ST.n_shared_ints, lpc, ST.state_words + link_words, slots_per_cand, p->max_lds);
   if (geo.waves < 1 || geo.cands_per_wave != ST.cands_per_wave) return FPSCHED_EUNSUPPORTED;
   // the plain image with longer dev rows: [.. 2 + 4V ints as before ..][4V out-edges]
   const int dev_ints = ST.dev_ints + 4 * V;
@@ -812,6 +815,7 @@ int fpsched_problem_set_link_occupancy(fpsched_problem* p, int32_t on) {
   p->stab_links = ST;
   p->stab_links.ints = image;
   p->stab_links.link_words = link_words;
+  p->stab_links.slots_per_cand = slots_per_cand;
   p->stab_links.dev_ints = dev_ints;
   p->stab_links.off_expect = ST.n_shared_ints + lpc * dev_ints;
   p->stab_links.cands_per_wave = geo.cands_per_wave;
