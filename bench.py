@@ -244,7 +244,7 @@ def bench_wslide(args, spec, threads) -> int:
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_WSLIDE.get((f"cfg{spec.index}", C), {}).get("traffic_bytes"),
-                     "kernel": "fpsched sliding pass: eval_slot_kernel<TIMES> + wslide_place_kernel",
+                     "kernel": "fpsched sliding pass: eval_slot_kernel in its timing mode + wslide_place_kernel",
                      "algorithmic_bytes_per_launch": alg_bytes,
                      "note": "two kernels per call; traffic is far above the algorithmic bytes: partly used cache "
                              "lines of per-lane row streams (profiles/wslide_kernel_cfg4.md)"},

@@ -79,16 +79,16 @@ struct DeviceGuard {
 
 using SlotKernel = void (*)(SlotTables, const uint16_t*, long long, int, long long*, long long*, int*,
                             unsigned char*, unsigned long long*, int, uint32_t*, int32_t*, const int32_t*);
-template <int TIMES>   // one of kSlotPlain, kSlotTimes, kSlotPerMicrobatch
+template <int MODE>   // kSlotPlain, kSlotTimes, ...
 SlotKernel slot_kernel_of(int v, bool deg2, bool one_class) {
   if (deg2)
-    return v == 1 ? &eval_slot_kernel<1, true, false, TIMES>
-                  : (v == 2 ? &eval_slot_kernel<2, true, false, TIMES> : &eval_slot_kernel<4, true, false, TIMES>);
+    return v == 1 ? &eval_slot_kernel<1, true, false, MODE>
+                  : (v == 2 ? &eval_slot_kernel<2, true, false, MODE> : &eval_slot_kernel<4, true, false, MODE>);
   if (one_class)
-    return v == 1 ? &eval_slot_kernel<1, false, true, TIMES>
-                  : (v == 2 ? &eval_slot_kernel<2, false, true, TIMES> : &eval_slot_kernel<4, false, true, TIMES>);
-  return v == 1 ? &eval_slot_kernel<1, false, false, TIMES>
-                : (v == 2 ? &eval_slot_kernel<2, false, false, TIMES> : &eval_slot_kernel<4, false, false, TIMES>);
+    return v == 1 ? &eval_slot_kernel<1, false, true, MODE>
+                  : (v == 2 ? &eval_slot_kernel<2, false, true, MODE> : &eval_slot_kernel<4, false, true, MODE>);
+  return v == 1 ? &eval_slot_kernel<1, false, false, MODE>
+                : (v == 2 ? &eval_slot_kernel<2, false, false, MODE> : &eval_slot_kernel<4, false, false, MODE>);
 }
 SlotKernel slot_kernel_ptr(int v, bool deg2, bool one_class) { return slot_kernel_of<kSlotPlain>(v, deg2, one_class); }
 

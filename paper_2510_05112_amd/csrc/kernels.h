@@ -60,7 +60,7 @@ __global__ void rank_keys_kernel(const long long* makespan, const long long* idl
                                  long long* key_out, unsigned char* excluded_out);
 
 // Second kernel of the weight-gradient sliding: one lane per (candidate, device) row places the W
-// items into the idle time in front of the ops timed by eval_slot_kernel<..., TIMES = true>.
+// items into the idle time in front of the ops timed by eval_slot_kernel<..., kSlotTimes>.
 constexpr int kSlideThreads = 512;
 // dynamic LDS of a workgroup: the metadata rows, then 8 KB per wavefront (windows and stash ring)
 constexpr int kSlideWaveLdsBytes = 8192;
