@@ -774,8 +774,16 @@ int fpsched_problem_set_link_occupancy(fpsched_problem* p, int32_t on) {
   // (this form of the kernel needs no dump region behind the slots: ops without an out-edge write the
   // lane's last link word)
   const int slots_per_cand = (2 * ST.n_classes * p->m + 7) & ~7;
-  const SlotGeometry geo = slot_geometry(ST.n_shared_ints, lpc, ST.state_words + link_words, slots_per_cand, p->max_lds);
+  SlotGeometry geo = slot_geometry(ST.n_shared_ints, lpc, ST.state_words + link_words, slots_per_cand, p->max_lds);
   if (geo.waves < 1 || geo.cands_per_wave != ST.cands_per_wave) return FPSCHED_EUNSUPPORTED;
+  // never more wavefronts than the plain kernel runs with: where this form would fit more (batches of
+  // short candidates), more segments only lengthen the ragged end of a batch
+  const int plain_groups = std::max(p->slot_grid / std::max(p->n_cu, 1), 1);
+  if (geo.waves * geo.groups > p->slot_waves * plain_groups &&
+      4ll * (ST.n_shared_ints + (int64_t)p->slot_waves * geo.wave_ints) + 256 <= p->max_lds / plain_groups) {
+    geo.waves = p->slot_waves;
+    geo.groups = plain_groups;
+  }
   // the plain image with longer dev rows: [.. 2 + 4V ints as before ..][4V out-edges]
   const int dev_ints = ST.dev_ints + 4 * V;
   std::vector<int32_t> J((size_t)ST.n_shared_ints + (size_t)lpc * dev_ints + (size_t)lpc * ST.state_words, 0);
