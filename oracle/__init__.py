@@ -285,13 +285,14 @@ def apply_caps(results, caps):
 _slide_lib = None
 
 
-def wslide(problem, words, stride_out: int, threads: int = 1):
+def wslide(problem, words, stride_out: int, threads: int = 1, links: bool = False):
     """Slide the weight-gradient items of a batch ``words[C][D][stride]`` into idle time.
-    Returns dict(ops uint16[C][D][stride_out], makespan, idle, peak, flags) of the new lists."""
+    Returns dict(ops uint16[C][D][stride_out], makespan, idle, peak, flags) of the new lists.
+    links: under the link-occupancy variant of the cost model."""
     global _slide_lib
     if _slide_lib is None:
         _slide_lib = ctypes.CDLL(_compile(_SLIDE_SRC, _SLIDE_LIB, False))
-        _slide_lib.fpslide_oracle_batch.restype = ctypes.c_int
+        _slide_lib.fpslide_oracle_batch_links.restype = ctypes.c_int
     mp = _Marshalled(problem)   # the same field layout as fpslide_problem
     w = np.ascontiguousarray(np.asarray(words, dtype=np.uint16))
     assert w.ndim == 3 and w.shape[1] == mp.D, w.shape
@@ -303,8 +304,9 @@ def wslide(problem, words, stride_out: int, threads: int = 1):
     def run(lo, hi):
         if hi <= lo:
             return 0
-        return _slide_lib.fpslide_oracle_batch(
-            ctypes.byref(mp.c), ctypes.c_void_p(w[lo:hi].ctypes.data), ctypes.c_int64(hi - lo),
+        return _slide_lib.fpslide_oracle_batch_links(
+            ctypes.byref(mp.c), ctypes.c_int32(1 if links else 0), ctypes.c_void_p(w[lo:hi].ctypes.data),
+            ctypes.c_int64(hi - lo),
             ctypes.c_int32(stride), ctypes.c_void_p(out["ops"][lo:hi].ctypes.data), ctypes.c_int32(stride_out),
             ctypes.c_void_p(out["makespan"][lo:hi].ctypes.data), ctypes.c_void_p(out["idle"][lo:hi].ctypes.data),
             ctypes.c_void_p(out["peak"][lo:hi].ctypes.data), ctypes.c_void_p(out["flags"][lo:hi].ctypes.data))

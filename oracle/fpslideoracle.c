@@ -99,10 +99,23 @@ static void issue(device_t *dev, int kind, int chunk, int s, int j, int64_t star
   dev->busy += dt;
 }
 
-int fpslide_oracle_one(const fpslide_problem *P, const uint16_t *words, int32_t stride, uint16_t *out_words,
-                       int32_t stride_out, int64_t *makespan, int64_t *idle, int32_t *peak, uint8_t *flags) {
-  const int D = P->n_devices, S = P->n_stages, m = P->n_microbatches;
+/*
+ * links != 0: the pass under the link-occupancy variant of the cost model (every ordered pair of devices
+ * is a link that carries one value at a time: a value leaves when its item has finished and the link is
+ * free, keeps the link busy for the edge's latency and arrives at its end; values of a device leave in the
+ * order its items run, two values of one item in the order of the edge list).  Weight-gradient items send
+ * nothing, so the sliding rule itself is the same; only the times the list items are ready at change.
+ */
+static int slide_one(const fpslide_problem *P, int links, const uint16_t *words, int32_t stride, uint16_t *out_words,
+                     int32_t stride_out, int64_t *makespan, int64_t *idle, int32_t *peak, uint8_t *flags) {
+  const int D = P->n_devices, S = P->n_stages, m = P->n_microbatches, E = P->n_edges;
   if (!P->has_w) return -1;
+  /* links: arrival of the value sent over edge e for micro-batch j, forward and backward (-1 = not sent),
+   * and until when the link from device a to device b is busy */
+  int64_t *arr_fwd = malloc(sizeof(int64_t) * (size_t)(E > 0 ? E : 1) * m);
+  int64_t *arr_bwd = malloc(sizeof(int64_t) * (size_t)(E > 0 ? E : 1) * m);
+  int64_t *busy_until = calloc((size_t)D * D, sizeof(int64_t));
+  for (int64_t i = 0; i < (int64_t)E * m; ++i) arr_fwd[i] = arr_bwd[i] = -1;
   int32_t *local_stage = malloc(sizeof(int32_t) * D * MAX_CHUNKS), *n_chunks = calloc(D, sizeof(int32_t));
   for (int s = 0; s < S; ++s) {   /* chunk c of device d = the c-th of d's stages in ascending stage id */
     const int d = P->stage_device[s];
@@ -157,9 +170,15 @@ int fpslide_oracle_one(const fpslide_problem *P, const uint16_t *words, int32_t 
         if ((kind == K_F || kind == K_FD) && P->edge_dst[e] == s) { other = P->edge_src[e]; fin = fin_fwd; }
         else if (kind == K_B && P->edge_src[e] == s) { other = P->edge_dst[e]; fin = fin_bwd; }
         else continue;
-        const int64_t t = fin[(size_t)other * m + j];
-        if (t < 0) { blocked = 1; break; }
-        const int64_t r = t + (P->stage_device[other] != d ? P->edge_comm[e] : 0);
+        int64_t r;
+        if (links) {
+          r = (fin == fin_fwd ? arr_fwd : arr_bwd)[(size_t)e * m + j];
+          if (r < 0) { blocked = 1; break; }
+        } else {
+          const int64_t t = fin[(size_t)other * m + j];
+          if (t < 0) { blocked = 1; break; }
+          r = t + (P->stage_device[other] != d ? P->edge_comm[e] : 0);
+        }
         if (r > ready) ready = r;
       }
       if (blocked) continue;
@@ -176,6 +195,22 @@ int fpslide_oracle_one(const fpslide_problem *P, const uint16_t *words, int32_t 
       if (kind == K_B) {
         fin_bwd[(size_t)s * m + j] = dev[d].free_at;
         q[2 * stash_tail[d]] = c; q[2 * stash_tail[d] + 1] = j; ++stash_tail[d];
+      }
+      if (links && (kind == K_F || kind == K_FD || kind == K_B)) {
+        /* the result goes out over every edge to another stage: activations downstream, gradients upstream */
+        const int fwd = kind != K_B;
+        const int64_t finish = dev[d].free_at;
+        for (int e = 0; e < E; ++e) {
+          if ((fwd ? P->edge_src[e] : P->edge_dst[e]) != s) continue;
+          const int to = P->stage_device[fwd ? P->edge_dst[e] : P->edge_src[e]];
+          int64_t arrival = finish;
+          if (to != d) {
+            int64_t *link = &busy_until[(size_t)d * D + to];
+            arrival = (finish > *link ? finish : *link) + P->edge_comm[e];
+            *link = arrival;
+          }
+          (fwd ? arr_fwd : arr_bwd)[(size_t)e * m + j] = arrival;
+        }
       }
       ++cursor[d];
       moved = 1;
@@ -203,21 +238,33 @@ int fpslide_oracle_one(const fpslide_problem *P, const uint16_t *words, int32_t 
     }
   }
   *flags = fl;
+  free(arr_fwd); free(arr_bwd); free(busy_until);
   free(local_stage); free(n_chunks); free(fin_fwd); free(fin_bwd); free(state); free(dev); free(cursor);
   free(len); free(finished); free(stash); free(stash_head); free(stash_tail);
   return 0;
 }
 
-/* Candidates [0, n_cand) of a batch laid out [C][D][stride] -> [C][D][stride_out]. */
-int fpslide_oracle_batch(const fpslide_problem *P, const uint16_t *words, int64_t n_cand, int32_t stride,
-                         uint16_t *out_words, int32_t stride_out, int64_t *makespan, int64_t *idle,
-                         int32_t *peak, uint8_t *flags) {
+int fpslide_oracle_one(const fpslide_problem *P, const uint16_t *words, int32_t stride, uint16_t *out_words,
+                       int32_t stride_out, int64_t *makespan, int64_t *idle, int32_t *peak, uint8_t *flags) {
+  return slide_one(P, 0, words, stride, out_words, stride_out, makespan, idle, peak, flags);
+}
+
+/* Candidates [0, n_cand) of a batch laid out [C][D][stride] -> [C][D][stride_out]; links: see slide_one. */
+int fpslide_oracle_batch_links(const fpslide_problem *P, int32_t links, const uint16_t *words, int64_t n_cand,
+                               int32_t stride, uint16_t *out_words, int32_t stride_out, int64_t *makespan,
+                               int64_t *idle, int32_t *peak, uint8_t *flags) {
   const int D = P->n_devices;
   for (int64_t c = 0; c < n_cand; ++c) {
-    const int rc = fpslide_oracle_one(P, words + (size_t)c * D * stride, stride,
-                                      out_words + (size_t)c * D * stride_out, stride_out, &makespan[c],
-                                      &idle[c * D], &peak[c * D], &flags[c]);
+    const int rc = slide_one(P, links, words + (size_t)c * D * stride, stride,
+                             out_words + (size_t)c * D * stride_out, stride_out, &makespan[c],
+                             &idle[c * D], &peak[c * D], &flags[c]);
     if (rc) return rc;
   }
   return 0;
+}
+
+int fpslide_oracle_batch(const fpslide_problem *P, const uint16_t *words, int64_t n_cand, int32_t stride,
+                         uint16_t *out_words, int32_t stride_out, int64_t *makespan, int64_t *idle,
+                         int32_t *peak, uint8_t *flags) {
+  return fpslide_oracle_batch_links(P, 0, words, n_cand, stride, out_words, stride_out, makespan, idle, peak, flags);
 }

@@ -200,3 +200,69 @@ def test_deadlocked_order_and_malformed_words():
     # a problem without split backward is refused
     with pytest.raises(ValueError):
         oracle.wslide(chain_problem(2, 2), pack_lists(lists, stride=8)[None], 8)
+
+
+# ---- the pass under the link-occupancy variant of the cost model ------------------------------------
+
+def slow_links(prob, seed):
+    rng = np.random.default_rng(seed)
+    slow = copy.deepcopy(prob)
+    slow.edge_comm[:] = rng.integers(0, 2 * int(np.median(np.asarray(prob.dur)[F])) + 2, len(slow.edge_comm))
+    return slow
+
+
+@pytest.mark.parametrize("index,n", [(2, 300), (3, 40), (5, 200)])
+def test_links_the_output_evaluates_to_the_reported_results(index, n):
+    # the evaluation oracle (another file, another event loop) in its link form on the new lists
+    spec, words = batch(index, n)
+    prob = slow_links(spec.problem, index)
+    r = oracle.wslide(prob, words, spec.stride, threads=4, links=True)
+    again = oracle.evaluate(prob, r["ops"], threads=4, links=True)
+    ok = (r["flags"] & 3) == 0
+    assert ok.sum() > n // 2
+    for name in ("makespan", "idle", "peak", "flags"):
+        assert np.array_equal(again[name][ok], r[name][ok]), name
+    assert np.all(r["makespan"][~ok] == oracle.INT64_MAX)
+    # the links matter, and the order of the list items does not depend on the model
+    plain = oracle.wslide(prob, words, spec.stride, threads=4)
+    assert (r["makespan"][ok] > plain["makespan"][ok]).any()
+    for c in np.flatnonzero(ok)[:40]:
+        for a, b in zip(rows_of(r["ops"][c]), rows_of(plain["ops"][c])):
+            assert [o for o in a if o[0] != W] == [o for o in b if o[0] != W]
+    # without latencies the two models are one
+    free = copy.deepcopy(prob)
+    free.edge_comm[:] = 0
+    a, b = oracle.wslide(free, words, spec.stride, threads=4), oracle.wslide(free, words, spec.stride, threads=4, links=True)
+    for name in a:
+        assert np.array_equal(a[name], b[name]), name
+
+
+def test_links_items_of_the_list_keep_the_times_of_the_list_without_w():
+    spec, words = batch(2, 30)
+    prob = slow_links(spec.problem, 11)
+    r = oracle.wslide(prob, words, spec.stride, threads=4, links=True)
+    bare = strip_w(words)
+    for c in np.flatnonzero((r["flags"] & 3) == 0)[:12]:
+        new = oracle.evaluate_trace(prob, r["ops"][c], links=True)
+        old = oracle.evaluate_trace(prob, bare[c], links=True)
+        for d in range(prob.n_devices):
+            keep = (r["ops"][c, d] >> 13 != 0) & (r["ops"][c, d] >> 13 != W)
+            n = int(keep.sum())
+            assert np.array_equal(new["start"][d][keep], old["start"][d][:n])
+
+
+def test_links_hand_worked_timeline():
+    # two stages on two devices, F = B = 1, W = 1, latency 3: the links are the bottleneck (the timeline of
+    # tests/test_oracle_links.py); device 0 waits for its gradients from 3 to 9, then for 2 between them
+    # device 0: F0 F1 F2 [0,3]; B0 [9,10] B1 [12,13] B2 [15,16]; stash after B0: W0 runs [10,11] (ends before 12),
+    # W1 [13,14], W2 at the end [16,17]
+    # device 1: F0 [4,5] B0 [5,6] then F1 is ready at 7: W0 [6,7] fits; F1 [7,8] B1 [8,9] W1 [9,10] F2 [10,11]
+    # B2 [11,12] W2 [12,13]
+    prob = chain_problem(2, 3, f=1, b=1, w=1, comm=3)
+    lists = [[(F, 0, 0), (F, 0, 1), (F, 0, 2), (B, 0, 0), (B, 0, 1), (B, 0, 2)],
+             [(F, 0, 0), (B, 0, 0), (F, 0, 1), (B, 0, 1), (F, 0, 2), (B, 0, 2)]]
+    r = oracle.wslide(prob, pack_lists(lists, stride=16)[None], 16, links=True)
+    got = rows_of(r["ops"][0])
+    assert got[0] == [(F, 0, 0), (F, 0, 1), (F, 0, 2), (B, 0, 0), (W, 0, 0), (B, 0, 1), (W, 0, 1), (B, 0, 2), (W, 0, 2)]
+    assert got[1] == [(F, 0, 0), (B, 0, 0), (W, 0, 0), (F, 0, 1), (B, 0, 1), (W, 0, 1), (F, 0, 2), (B, 0, 2), (W, 0, 2)]
+    assert r["makespan"][0] == 17 and r["flags"][0] == 0
