@@ -191,6 +191,8 @@ def bench_wslide(args, spec, threads) -> int:
     C, D, stride = words.shape
     n_ops = workloads.count_ops(words)
     handle = fp.Problem(prob, stride, device=0)
+    if args.links:
+        handle.set_link_occupancy(True)
     ops = torch.empty((C, D, stride), dtype=torch.int16, device=dev)
     chunk = max(1, (256 << 20) // (D * stride * 2))
     for lo in range(0, C, chunk):
@@ -237,13 +239,14 @@ def bench_wslide(args, spec, threads) -> int:
         "unit": "schedules/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int32", "data": "synthetic",
-        "config": {"workload": f"weight-gradient sliding on cfg{spec.index}: {prob.name}, {C} candidates, top-{k}",
+        "config": {"workload": f"weight-gradient sliding on cfg{spec.index}: {prob.name}, {C} candidates, top-{k}"
+                               + (", link occupancy" if args.links else ""),
                    "candidates": C, "devices": D, "stages": prob.n_stages, "microbatches": prob.n_microbatches,
                    "ops_per_candidate": n_ops / C, "stride_words": stride},
         "wslide_kernel_ms": kernel_ms,
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_WSLIDE.get((f"cfg{spec.index}", C), {}).get("traffic_bytes"),
+                     "traffic": None if args.links else MEASURED_WSLIDE.get((f"cfg{spec.index}", C), {}).get("traffic_bytes"),
                      "kernel": "fpsched sliding pass: eval_slot_kernel in its timing mode + wslide_place_kernel",
                      "algorithmic_bytes_per_launch": alg_bytes,
                      "note": "two kernels per call; traffic is far above the algorithmic bytes: partly used cache "
@@ -261,7 +264,7 @@ def bench_wslide(args, spec, threads) -> int:
         if args.check:
             rng = np.random.default_rng(0)
             pick = np.sort(rng.choice(C, min(args.check, C), replace=False))
-            ref = oracle.wslide(prob, words[pick], stride, threads=threads)
+            ref = oracle.wslide(prob, words[pick], stride, threads=threads, links=args.links)
             sel = torch.from_numpy(pick).to(dev)
             ok = np.array_equal(out["ops"][sel].cpu().numpy().view(np.uint16), ref["ops"]) and all(
                 np.array_equal(out[n][sel].cpu().numpy(), ref[n]) for n in ("makespan", "idle", "peak", "flags"))
@@ -271,11 +274,11 @@ def bench_wslide(args, spec, threads) -> int:
         if not args.no_cpu_baseline:
             n1 = min(C, args.cpu_sample or max(64, int(60e6 // max(1, n_ops // C))))
             t0 = time.perf_counter()
-            oracle.wslide(prob, words[:n1], stride, threads=1)
+            oracle.wslide(prob, words[:n1], stride, threads=1, links=args.links)
             t1 = time.perf_counter() - t0
             nn = min(C, n1 * min(threads, 8))
             t0 = time.perf_counter()
-            oracle.wslide(prob, words[:nn], stride, threads=threads)
+            oracle.wslide(prob, words[:nn], stride, threads=threads, links=args.links)
             tn = time.perf_counter() - t0
             json_res["cpu_baseline"] = {
                 "value": nn / tn, "unit": "schedules/s", "cores": threads, "kind": "oracle",
@@ -306,7 +309,7 @@ def main() -> int:
                     help="evaluate mode: costs per micro-batch (seeded factors in [1/2, 3/2) on the "
                          "configuration's costs) instead of one cost per (type, stage)")
     ap.add_argument("--links", action="store_true",
-                    help="evaluate mode: the link-occupancy variant of the cost model (every ordered pair of "
+                    help="evaluate and wslide modes: the link-occupancy variant of the cost model (every ordered pair of "
                          "devices carries one value at a time) instead of pure latencies")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain elementwise copy of the op batch (a kernel of known HBM "

@@ -153,7 +153,9 @@ int fpsched_problem_set_microbatch_costs(fpsched_problem *p, const int32_t *dur_
  * the problem does not fit it (more than two inputs or outputs per stage, or
  * D * max_stride * (max dur + 2 * max comm) >= 2^24), if costs per micro-batch are set (one variant
  * at a time; the reverse order of the two calls is refused the same way), and from
- * fpsched_evaluate while the general kernel is selected or from fpsched_wslide while on.
+ * fpsched_evaluate while the general kernel is selected.  fpsched_wslide follows the switch (the
+ * weight-gradient items send nothing, so its rule is unchanged; the times it works with are this
+ * model's).
  * The first call on a device handle allocates one more table image (FPSCHED_ENOMEM); not to be
  * called concurrently with other calls on the handle.  Works on a host-only handle (flag only). */
 int fpsched_problem_set_link_occupancy(fpsched_problem *p, int32_t on);

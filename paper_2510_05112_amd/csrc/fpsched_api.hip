@@ -51,6 +51,10 @@ struct fpsched_problem {
   bool links_on = false;
   SlotTables stab_links{};
   int32_t* d_links_image = nullptr;
+  std::vector<int32_t> times_ints;      // host copy of the timing pass's table image
+  bool links_slide_ok = false;          // the sliding pass has a link form (its LDS fits)
+  SlotTables stab_times_links{};
+  int32_t* d_times_links_image = nullptr;
   int32_t links_waves = 0, links_grid = 0, links_lds_bytes = 0;
   // ... or, when the values fit sixteen bits and the table fits LDS, inside a second table image
   bool mb_in_lds = false;
@@ -451,6 +455,7 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
             for (int j = 0; j < m; ++j) x[c * words_per_chunk + (j >> 3)] |= (int32_t)((unsigned)kBDone << ((j & 7) * 4));
         }
         p->stab_times = p->stab;
+        p->times_ints = J;
         const bool up = hipMalloc(&p->d_times_ints, J.size() * sizeof(int32_t)) == hipSuccess &&
                         hipMemcpy(p->d_times_ints, J.data(), J.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess &&
                         hipFuncSetAttribute(reinterpret_cast<const void*>(slot_kernel_of<kSlotTimes>(p->slot_v, p->slot_deg2, p->stab.n_classes == 1)),
@@ -491,6 +496,7 @@ void fpsched_problem_destroy(fpsched_problem* p) {
     if (p->d_mb_rows) (void)hipFree(p->d_mb_rows);
     if (p->d_mb_image) (void)hipFree(p->d_mb_image);
     if (p->d_links_image) (void)hipFree(p->d_links_image);
+    if (p->d_times_links_image) (void)hipFree(p->d_times_links_image);
   }
   delete p;
 }
@@ -784,14 +790,16 @@ int fpsched_problem_set_link_occupancy(fpsched_problem* p, int32_t on) {
     geo.waves = p->slot_waves;
     geo.groups = plain_groups;
   }
-  // the plain image with longer dev rows: [.. 2 + 4V ints as before ..][4V out-edges]
+  // a table image (the plain one, or the timing pass's) with longer dev rows:
+  // [.. 2 + 4V ints as before ..][4V out-edges]
   const int dev_ints = ST.dev_ints + 4 * V;
+  auto with_links = [&](const std::vector<int32_t>& base) {
   std::vector<int32_t> J((size_t)ST.n_shared_ints + (size_t)lpc * dev_ints + (size_t)lpc * ST.state_words, 0);
-  std::copy(p->slot_ints.begin(), p->slot_ints.begin() + ST.n_shared_ints, J.begin());
+  std::copy(base.begin(), base.begin() + ST.n_shared_ints, J.begin());
   for (int d = 0; d < lpc; ++d) {
     int32_t* row = &J[(size_t)ST.n_shared_ints + (size_t)d * dev_ints];
-    std::copy(p->slot_ints.begin() + ST.off_dev + (size_t)d * ST.dev_ints,
-              p->slot_ints.begin() + ST.off_dev + (size_t)(d + 1) * ST.dev_ints, row);
+    std::copy(base.begin() + ST.off_dev + (size_t)d * ST.dev_ints,
+              base.begin() + ST.off_dev + (size_t)(d + 1) * ST.dev_ints, row);
     for (int i = 0; i < 4 * V; ++i) row[ST.dev_ints + i] = (int32_t)spare;
     if (d >= D) continue;
     for (int c = 0; c < p->n_chunks[d]; ++c) {
@@ -806,8 +814,10 @@ int fpsched_problem_set_link_occupancy(fpsched_problem* p, int32_t on) {
         }
     }
   }
-  std::copy(p->slot_ints.begin() + ST.off_expect, p->slot_ints.end(),
-            J.begin() + ST.n_shared_ints + (size_t)lpc * dev_ints);
+  std::copy(base.begin() + ST.off_expect, base.end(), J.begin() + ST.n_shared_ints + (size_t)lpc * dev_ints);
+  return J;
+  };
+  const std::vector<int32_t> J = with_links(p->slot_ints);
   DeviceGuard g(p->device_id);
   if (!g.ok) return FPSCHED_EHIP;
   int32_t* image = nullptr;
@@ -832,6 +842,24 @@ int fpsched_problem_set_link_occupancy(fpsched_problem* p, int32_t on) {
   p->links_grid = p->n_cu * geo.groups;
   p->links_lds_bytes = lds_bytes;
   p->links_on = true;
+  // the sliding pass's timing kernel under the link model: the timing image, widened the same way; it
+  // needs 16 bytes of LDS more
+  if (p->slide_ok && !p->times_ints.empty() && (int64_t)lds_bytes + 16 <= p->max_lds / geo.groups) {
+    const std::vector<int32_t> JT = with_links(p->times_ints);
+    int32_t* timg = nullptr;
+    if (hipMalloc(&timg, JT.size() * sizeof(int32_t)) == hipSuccess &&
+        hipMemcpy(timg, JT.data(), JT.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess &&
+        hipFuncSetAttribute(reinterpret_cast<const void*>(slot_kernel_of<kSlotTimesLinks>(p->slot_v, p->slot_deg2, ST.n_classes == 1)),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes + 16) == hipSuccess) {
+      p->d_times_links_image = timg;
+      p->stab_times_links = p->stab_links;
+      p->stab_times_links.ints = timg;
+      p->links_slide_ok = true;
+    } else {
+      (void)hipGetLastError();
+      if (timg) (void)hipFree(timg);
+    }
+  }
   if (getenv("FPSCHED_VERBOSE"))
     fprintf(stderr, "[fpsched] link occupancy: %d link words per lane, %d x %d wavefronts per compute unit (plain: %d x %d)\n",
             link_words, geo.groups, geo.waves, p->slot_grid / std::max(p->n_cu, 1), p->slot_waves);
@@ -985,8 +1013,8 @@ int fpsched_wslide(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_ca
   if (!p || n_cand < 0) return FPSCHED_EINVAL;
   if (p->device_id < 0) return FPSCHED_ENODEV;
   if (!p->has_w) return FPSCHED_EINVAL;
-  // the pass knows one cost per (type, stage) and transfers as pure latencies
-  if (!p->slide_ok || p->mb_set || p->links_on) return FPSCHED_EUNSUPPORTED;
+  // the pass knows one cost per (type, stage)
+  if (!p->slide_ok || p->mb_set || (p->links_on && !p->links_slide_ok)) return FPSCHED_EUNSUPPORTED;
   if (n_cand == 0) return FPSCHED_OK;
   if (!d_ops || !d_ops_out || !out.makespan || !out.idle || !out.peak || !out.flags) return FPSCHED_EINVAL;
   if (stride_words < 8 || (stride_words & 7) || stride_words > p->max_stride) return FPSCHED_EINVAL;
@@ -1006,13 +1034,22 @@ int fpsched_wslide(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_ca
   int32_t* stops = reinterpret_cast<int32_t*>(ws + 256 + wslide_starts_bytes(p, n_cand, stride_words));
   unsigned char* timed_flags = reinterpret_cast<unsigned char*>(stops) + (((size_t)n_cand * p->D * sizeof(int32_t) + 15) & ~(size_t)15);
   // pass 1: the lists without their W items, timed by the evaluation kernel (launched as in fpsched_evaluate)
-  const int per_block = p->stab.cands_per_wave * p->slot_waves;
-  const int64_t blocks = std::min<int64_t>((n_cand + per_block - 1) / per_block, p->slot_grid);
+  // (under the link model: that model's tables and workgroup shape; W items send nothing, so the second
+  // pass is the same)
+  const bool links = p->links_on;
+  const SlotTables& times_tab = links ? p->stab_times_links : p->stab_times;
+  const int waves = links ? p->links_waves : p->slot_waves;
+  const int grid = links ? p->links_grid : p->slot_grid;
+  const size_t times_lds = (size_t)(links ? p->links_lds_bytes : p->slot_lds_bytes) + 16;
+  const int per_block = times_tab.cands_per_wave * waves;
+  const int64_t blocks = std::min<int64_t>((n_cand + per_block - 1) / per_block, grid);
   const int64_t row_words = (int64_t)p->D * stride_words;
-  const int draw_block = (int)std::clamp<int64_t>((12288 + row_words - 1) / row_words, 1, p->stab.cands_per_wave);
+  const int draw_block = (int)std::clamp<int64_t>((12288 + row_words - 1) / row_words, 1, times_tab.cands_per_wave);
+  const bool one_class = p->stab.n_classes == 1;
   hipLaunchKernelGGL(reset_counter_kernel, dim3(1), dim3(64), 0, st, counter, (unsigned long long)(blocks * per_block));
-  hipLaunchKernelGGL(slot_kernel_of<kSlotTimes>(p->slot_v, p->slot_deg2, p->stab.n_classes == 1), dim3((unsigned)blocks),
-                     dim3(64 * p->slot_waves), (size_t)p->slot_lds_bytes + 16, st, p->stab_times, d_ops, (long long)n_cand,
+  hipLaunchKernelGGL(links ? slot_kernel_of<kSlotTimesLinks>(p->slot_v, p->slot_deg2, one_class)
+                           : slot_kernel_of<kSlotTimes>(p->slot_v, p->slot_deg2, one_class),
+                     dim3((unsigned)blocks), dim3(64 * waves), times_lds, st, times_tab, d_ops, (long long)n_cand,
                      (int)stride_words, (long long*)nullptr, (long long*)nullptr, (int*)nullptr, timed_flags, counter,
                      draw_block, starts, stops, (const int32_t*)nullptr);
   if (hipGetLastError() != hipSuccess) return FPSCHED_EHIP;

@@ -34,7 +34,9 @@ constexpr int kSlotMaxThreads = 64 * kSlotMaxWaves;
 // sixteen-bit table at T.off_mb, which travels to LDS with the metadata.
 // MODE kSlotLinks: every ordered pair of devices is a link that carries one value at a time; a
 // producer holds its value back until its link is free (T.link_words, the longer dev rows).
-constexpr int kSlotPlain = 0, kSlotTimes = 1, kSlotPerMicrobatch = 2, kSlotPerMicrobatchLds = 3, kSlotLinks = 4;
+// MODE kSlotTimesLinks: the timing pass of the sliding under the link model (both of the above).
+constexpr int kSlotPlain = 0, kSlotTimes = 1, kSlotPerMicrobatch = 2, kSlotPerMicrobatchLds = 3, kSlotLinks = 4,
+              kSlotTimesLinks = 5;
 template <int V, bool DEG2, bool ONE_CLASS, int MODE>
 __global__ void eval_slot_kernel(SlotTables T, const uint16_t* ops, long long n_cand, int stride,
                                  long long* out_makespan, long long* out_idle, int* out_peak,

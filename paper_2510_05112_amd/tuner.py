@@ -113,7 +113,7 @@ def tune(handle, problem, circular: bool, k: int = 8, inflight_options=None, for
     optimizations); such entries have ``slid`` set.  Returns the k best feasible schedules as a list
     of dicts (label, makespan, index into the grid, slid).  The schedules are timed with whatever cost
     model the handle is set to (``set_microbatch_costs``, ``set_link_occupancy``); the sliding pass
-    only knows the plain one."""
+    follows the link switch and refuses costs per micro-batch."""
     import torch
 
     labels, pol, inf = grid(problem, circular, inflight_options, forward_first)

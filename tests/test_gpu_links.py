@@ -84,10 +84,16 @@ def test_switching_the_variant_on_and_off_on_one_handle():
     assert_same(run(), plain, "before")
     h.set_link_occupancy(True)
     assert_same(run(), linked, "links on")
-    for refused in (lambda: h.wslide(ops), lambda: h.set_microbatch_costs(workloads.microbatch_costs(prob))):
-        with pytest.raises(fp.FpschedError) as e:
-            refused()
-        assert e.value.code == -6
+    with pytest.raises(fp.FpschedError) as e:
+        h.set_microbatch_costs(workloads.microbatch_costs(prob))
+    assert e.value.code == -6
+    # the sliding pass follows the switch
+    slid = h.wslide(ops)
+    torch.cuda.synchronize()
+    ref = oracle.wslide(prob, words, spec.stride, threads=8, links=True)
+    for name in ("ops", "makespan", "idle", "peak", "flags"):
+        got = slid[name].cpu().numpy()
+        assert np.array_equal(got.view(np.uint16) if name == "ops" else got, ref[name]), name
     h.select_kernel("general")
     with pytest.raises(fp.FpschedError) as e:
         h.evaluate(ops)
@@ -103,3 +109,56 @@ def test_switching_the_variant_on_and_off_on_one_handle():
     h.set_link_occupancy(True)
     assert_same(run(), linked, "links on again")
     h.close()
+
+
+def check_slide(prob, words, stride_out, what):
+    h = fp.Problem(prob, max(words.shape[2], stride_out), device=0)
+    h.set_link_occupancy(True)
+    out = h.wslide(torch.from_numpy(words.view(np.int16)).cuda(), stride_out)
+    torch.cuda.synchronize()
+    ref = oracle.wslide(prob, words, stride_out, threads=8, links=True)
+    for name in ("flags", "makespan", "idle", "peak", "ops"):
+        got = out[name].cpu().numpy()
+        got = got.view(np.uint16) if name == "ops" else got
+        if not np.array_equal(got, ref[name]):
+            bad = np.flatnonzero((got != ref[name]).reshape(len(got), -1).any(1))
+            raise AssertionError(f"{what}: {name} differs for {len(bad)} candidates, first {bad[:5]}")
+    h.close()
+    return ref
+
+
+@pytest.mark.parametrize("index,n", [(2, 3000), (3, 700), (4, 600), (5, 2000)])
+def test_sliding_pass_under_link_occupancy_on_the_benchmark_shapes(index, n):
+    spec = workloads.config(index, n)
+    words = workloads.generate(spec, threads=8)
+    prob = slow_links(spec.problem, 50 + index)
+    ref = check_slide(prob, words, spec.stride, f"cfg{index}")
+    plain = oracle.wslide(prob, words, spec.stride, threads=8)
+    ok = ref["flags"] & 3 == 0
+    assert ok.sum() > 0 and (ref["makespan"][ok] > plain["makespan"][ok]).any()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_sliding_pass_under_link_occupancy_on_random_problems(seed):
+    rng = np.random.default_rng(9500 + seed)
+    done = 0
+    while done < 8:
+        prob = random_problem(rng)
+        if not prob.has_w:
+            continue
+        prob.edge_comm[:] = rng.integers(0, 12, len(prob.edge_comm))
+        lists = []
+        for t in range(16):
+            base = random_valid_lists(prob, rng, 0.3 * (t % 2), 0.3 * ((t // 2) % 2))
+            lists.append(base)
+            lists.append(perturb(base, rng, 1 + t % 3))
+            if t % 5 == 0:
+                cut = [list(x) for x in base]
+                d = int(rng.integers(prob.n_devices))
+                cut[d] = cut[d][: len(cut[d]) // 2]
+                lists.append(cut)
+        words = batch_from_lists(lists)
+        stride = words.shape[2]
+        for stride_out in (stride + 8, max(8, (stride // 2) // 8 * 8)):
+            check_slide(prob, words, stride_out, f"seed {seed} problem {done} stride_out {stride_out}")
+        done += 1
