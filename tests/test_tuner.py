@@ -134,6 +134,16 @@ def test_gpu_search_under_the_other_cost_models_matches_the_oracles(variant):
     # the model matters for the ranking's makespans
     plain = oracle.evaluate(prob, words)
     assert not np.array_equal(plain["makespan"], ref["makespan"])
+    if variant == "link occupancy":
+        # the sliding pass follows the link switch: both halves of the ranking against their oracles
+        best = tuner.tune(h, prob, True, k=6, slide=True)
+        slid = oracle.wslide(prob, words, st, links=True)
+        ms = np.concatenate([ref["makespan"], slid["makespan"]])
+        fl = np.concatenate([ref["flags"], slid["flags"]])
+        idx, top_ms, cnt = oracle.topk(ms, fl, 6)
+        n = len(labels)
+        assert [(b["index"], b["slid"], b["makespan"]) for b in best] == [(int(i) % n, bool(i >= n), int(t)) for i, t in zip(idx[:cnt], top_ms[:cnt])]
+        assert any(b["slid"] for b in best)
     h.close()
 
 
