@@ -59,6 +59,8 @@ def bench_generate(args, spec, threads) -> int:
     pol, inf = workloads.policy_sets(prob, n)
     prep_s = time.perf_counter() - t0
     handle = fp.Problem(prob, stride, device=0)
+    if args.links:   # the generator ignores costs; the evaluation (and the sliding pass) of a search step follow
+        handle.set_link_occupancy(True)
     d_pol, d_inf = torch.from_numpy(pol).to(dev), torch.from_numpy(inf).to(dev)
     out = dict(ops=torch.empty((n, prob.n_devices, stride), dtype=torch.int16, device=dev),
                steps=torch.empty(n, dtype=torch.int32, device=dev),
@@ -133,7 +135,8 @@ def bench_generate(args, spec, threads) -> int:
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
         "config": {"workload": f"{'search loop' if search else 'generator'} on cfg{spec.index}: {prob.name}, "
-                               f"{n} seeded parameter sets" + (f", top-{k}" if search else ""),
+                               f"{n} seeded parameter sets" + (f", top-{k}" if search else "")
+                               + (", link occupancy" if search and args.links else ""),
                    "parameter_sets": n, "devices": prob.n_devices, "stages": prob.n_stages,
                    "microbatches": prob.n_microbatches, "ops_per_schedule": n_ops / n, "stride_words": stride},
         "items_scheduled_per_s": n_ops / (ms_per_step * 1e-3),
@@ -309,7 +312,7 @@ def main() -> int:
                     help="evaluate mode: costs per micro-batch (seeded factors in [1/2, 3/2) on the "
                          "configuration's costs) instead of one cost per (type, stage)")
     ap.add_argument("--links", action="store_true",
-                    help="evaluate and wslide modes: the link-occupancy variant of the cost model (every ordered pair of "
+                    help="evaluate, search and wslide modes: the link-occupancy variant of the cost model (every ordered pair of "
                          "devices carries one value at a time) instead of pure latencies")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain elementwise copy of the op batch (a kernel of known HBM "
