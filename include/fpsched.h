@@ -238,7 +238,9 @@ int fpsched_rank(const fpsched_problem *p, fpsched_results in, int64_t n_cand, i
  * the sentinels.  Rows of candidates that fail otherwise hold the items that did issue.
  * The makespan may grow: an item that moves up can open idle time that the stashed items do
  * not fit into; evaluate both lists and rank.  Needs the slot tables (at most two inputs and
- * outputs per stage, see fpsched_problem_info), else FPSCHED_EUNSUPPORTED.
+ * outputs per stage, see fpsched_problem_info), else FPSCHED_EUNSUPPORTED.  Cost model: the
+ * handle's latencies as pure latencies or, after fpsched_problem_set_link_occupancy, as links
+ * that carry one value at a time; FPSCHED_EUNSUPPORTED while costs per micro-batch are set.
  * Workspace: fpsched_wslide_workspace_bytes (DEVICE, 16-byte aligned; it holds a start time
  * per op word, i.e. about twice the bytes of the input lists).  Asynchronous on hip_stream. */
 size_t fpsched_wslide_workspace_bytes(const fpsched_problem *p, int64_t n_cand, int32_t stride_words);
