@@ -253,7 +253,8 @@ def test_call_errors_streams_and_workspace_reuse():
     h.close()
 
 
-def test_evaluate_and_topk_replayed_from_a_hip_graph():
+@pytest.mark.parametrize("model", ["plain", "costs per micro-batch", "link occupancy"])
+def test_evaluate_and_topk_replayed_from_a_hip_graph(model):
     # the calls enqueue kernels only (the work counter is reset by a kernel, not a memset), so they can
     # be captured once and replayed on new inputs; every replay is checked against the oracle
     import torch
@@ -263,6 +264,13 @@ def test_evaluate_and_topk_replayed_from_a_hip_graph():
     prob, k = spec.problem, 9
     batches = [workloads.generate(spec, n=300, first=300 * i, threads=2) for i in range(3)]
     h = fp.Problem(prob, spec.stride, device=0)
+    variant = {}
+    if model == "costs per micro-batch":
+        variant["dur_mb"] = workloads.microbatch_costs(prob)
+        h.set_microbatch_costs(variant["dur_mb"])
+    elif model == "link occupancy":
+        variant["links"] = True
+        h.set_link_occupancy(True)
     ops = torch.from_numpy(batches[0].view(np.int16)).cuda()
     res, ws = h.alloc_results(300), h.alloc_workspace(300, k)
     top = dict(idx=torch.empty(k, dtype=torch.int64, device="cuda"),
@@ -281,7 +289,7 @@ def test_evaluate_and_topk_replayed_from_a_hip_graph():
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
-        ref = oracle.evaluate(prob, words, threads=2)
+        ref = oracle.evaluate(prob, words, threads=2, **variant)
         for name in ("makespan", "idle", "peak", "flags"):
             assert np.array_equal(res[name].cpu().numpy(), ref[name]), name
         idx, ms, cnt = oracle.topk(ref["makespan"], ref["flags"], k)
@@ -289,7 +297,8 @@ def test_evaluate_and_topk_replayed_from_a_hip_graph():
     h.close()
 
 
-def test_generate_slide_and_topk_replayed_from_a_hip_graph():
+@pytest.mark.parametrize("links", [False, True])
+def test_generate_slide_and_topk_replayed_from_a_hip_graph(links):
     # the search loop with the sliding pass, captured once and replayed on new parameter sets; every
     # replay is checked against the three oracles
     import torch
@@ -300,6 +309,8 @@ def test_generate_slide_and_topk_replayed_from_a_hip_graph():
     st = workloads.generator_stride(prob)
     sets = [workloads.policy_sets(prob, n, seed=77 + i) for i in range(3)]
     h = fp.Problem(prob, st, device=0)
+    if links:
+        h.set_link_occupancy(True)
     d_pol, d_inf = torch.from_numpy(sets[0][0]).cuda(), torch.from_numpy(sets[0][1]).cuda()
     gen = h.generate(d_pol, d_inf, st)                      # eager once: allocates the outputs
     ws = h.alloc_workspace(n, k)
@@ -322,7 +333,7 @@ def test_generate_slide_and_topk_replayed_from_a_hip_graph():
         torch.cuda.synchronize()
         ref_gen = oracle.generate(prob, pol, inf, st, threads=2)
         assert np.array_equal(gen["ops"].cpu().numpy().view(np.uint16), ref_gen["words"])
-        ref = oracle.wslide(prob, ref_gen["words"], st, threads=2)
+        ref = oracle.wslide(prob, ref_gen["words"], st, threads=2, links=links)
         assert np.array_equal(slid["ops"].cpu().numpy().view(np.uint16), ref["ops"])
         for name in ("makespan", "idle", "peak", "flags"):
             assert np.array_equal(slid[name].cpu().numpy(), ref[name]), name
