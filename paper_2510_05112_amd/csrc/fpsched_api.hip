@@ -100,8 +100,9 @@ SlotKernel slot_kernel_ptr(int v, bool deg2, bool one_class) { return slot_kerne
 // wavefront, then the split of a compute unit's LDS into workgroups that keeps the most wavefronts
 // resident (LDS is the only limiter: ~50 VGPRs).  Returns wavefronts per workgroup (0 = does not fit).
 struct SlotGeometry { int cands_per_wave, wave_ints, waves, groups; };
-SlotGeometry slot_geometry(int64_t n_shared_ints, int lanes_per_cand, int state_words, int slots_per_cand, int max_lds) {
-  int scpw = 64 / lanes_per_cand;
+SlotGeometry slot_geometry(int64_t n_shared_ints, int lanes_per_cand, int state_words, int slots_per_cand, int max_lds,
+                           int max_cands_per_wave = 64) {
+  int scpw = std::min(64 / lanes_per_cand, max_cands_per_wave);
   const int64_t fixed = 64ll * (8 + state_words);  // 16 op words + state words per lane
   const int64_t lds_ints = max_lds / 4;
   while (scpw > 1 && n_shared_ints + fixed + (int64_t)scpw * slots_per_cand > lds_ints) scpw >>= 1;
@@ -667,7 +668,7 @@ int fpsched_problem_set_microbatch_costs(fpsched_problem* p, const int32_t* dur_
     const int64_t row_dwords = slot_mb_row_dwords(m, value_bytes);   // of one device
     const int64_t table_ints = ((int64_t)n_blocks * V * lpc * row_dwords + 511) & ~511ll;
     const int64_t shared = ST.n_shared_ints + table_ints;
-    const SlotGeometry geo = slot_geometry(shared, lpc, ST.state_words, ST.slots_per_cand, p->max_lds);
+    const SlotGeometry geo = slot_geometry(shared, lpc, ST.state_words, ST.slots_per_cand, p->max_lds, ST.cands_per_wave);
     if (geo.waves * geo.groups >= 6 && geo.cands_per_wave == ST.cands_per_wave) {
       std::vector<int32_t> J((size_t)shared + (p->slot_ints.size() - ST.n_shared_ints), 0);
       std::copy(p->slot_ints.begin(), p->slot_ints.begin() + ST.n_shared_ints, J.begin());
@@ -780,7 +781,9 @@ int fpsched_problem_set_link_occupancy(fpsched_problem* p, int32_t on) {
   // (this form of the kernel needs no dump region behind the slots: ops without an out-edge write the
   // lane's last link word)
   const int slots_per_cand = (2 * ST.n_classes * p->m + 7) & ~7;
-  SlotGeometry geo = slot_geometry(ST.n_shared_ints, lpc, ST.state_words + link_words, slots_per_cand, p->max_lds);
+  // (as many candidates per wavefront as the plain tables: the per-lane constants are shared)
+  SlotGeometry geo = slot_geometry(ST.n_shared_ints, lpc, ST.state_words + link_words, slots_per_cand, p->max_lds,
+                                   ST.cands_per_wave);
   if (geo.waves < 1 || geo.cands_per_wave != ST.cands_per_wave) return FPSCHED_EUNSUPPORTED;
   // never more wavefronts than the plain kernel runs with: where this form would fit more (batches of
   // short candidates), more segments only lengthen the ragged end of a batch

@@ -10,7 +10,7 @@ import torch
 import oracle
 import paper_2510_05112_amd as fp
 import workloads
-from gpu_common import assert_same, check_batch
+from gpu_common import assert_same, check_batch, gpu_evaluate
 from helpers import batch_from_lists, perturb, random_valid_lists
 from test_gpu_fuzz import random_problem
 from workloads.problem import chain_problem, gpipe_lists, pack_lists
@@ -162,3 +162,29 @@ def test_sliding_pass_under_link_occupancy_on_random_problems(seed):
         for stride_out in (stride + 8, max(8, (stride // 2) // 8 * 8)):
             check_slide(prob, words, stride_out, f"seed {seed} problem {done} stride_out {stride_out}")
         done += 1
+
+
+def test_largest_sizes_under_link_occupancy():
+    from workloads.problem import one_f_one_b_lists
+    # many micro-batches, a link slower than the items; with the largest count of the word format the
+    # link words no longer fit beside the state words, and the call says so
+    for m in (512, 2048):
+        prob = chain_problem(2, m, f=1, b=2, comm=3)
+        words = np.stack([pack_lists(one_f_one_b_lists(2, m), stride=2 * m), pack_lists(gpipe_lists(2, m), stride=2 * m)])
+        gpu, _ = gpu_evaluate(prob, words, kernel="slots", links=True)
+        if m == 2048 and gpu is None:
+            continue
+        assert_same(gpu, oracle.evaluate(prob, words, links=True), f"m={m}")
+        assert gpu["makespan"][1] == 2 * (1 + 2) + 2 * m * 3        # p (f + b) + 2 (m + p - 2) c
+    # 64 devices, and 252 stages on 63 devices (four per device, each sending both ways)
+    prob = chain_problem(64, 6, f=2, b=4, comm=5)
+    words = np.stack([pack_lists(gpipe_lists(64, 6)), pack_lists(one_f_one_b_lists(64, 6))])
+    gpu, _ = check_batch(prob, words, k=2, what="p=64", links=True)
+    assert gpu["makespan"][0] == 64 * 6 + 2 * (6 + 64 - 2) * 5
+    prob = chain_problem(63, 3, v=4, f=2, b=3, w=1, comm=4)
+    rng = np.random.default_rng(63)
+    lists = []
+    for t in range(6):
+        base = random_valid_lists(prob, rng)
+        lists += [base, perturb(base, rng, 2)]
+    check_batch(prob, batch_from_lists(lists), k=3, what="S=252", links=True)

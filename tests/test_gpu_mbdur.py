@@ -116,3 +116,26 @@ def test_costs_too_large_for_the_slot_kernel_go_through_the_general_kernel():
     table[2, 1, 3] += 12345
     gpu, ref = check_batch(prob, words, k=4, what="large costs", dur_mb=table, kernels=("auto",))
     assert ref["makespan"][ref["flags"] == 0].max() > 1 << 20
+
+
+def test_largest_sizes_with_costs_per_micro_batch():
+    from workloads.problem import gpipe_lists, one_f_one_b_lists, pack_lists, chain_problem
+    rng = np.random.default_rng(2048)
+    # the largest micro-batch count of the word format (a table of 2 x 2048 values per kind)
+    m = 2048
+    prob = chain_problem(2, m, f=1, b=2, comm=1)
+    table = rng.integers(0, 30, (NKINDS, 2, m)).astype(np.int32)
+    words = np.stack([pack_lists(one_f_one_b_lists(2, m), stride=4096), pack_lists(gpipe_lists(2, m), stride=4096)])
+    check_batch(prob, words, k=2, what="m=2048", dur_mb=table)
+    # 64 devices; 252 stages on 63 devices (the table does not fit LDS beside four chunks of state)
+    prob = chain_problem(64, 6, f=2, b=4, comm=1)
+    table = rng.integers(1, 300, (NKINDS, 64, 6)).astype(np.int32)
+    words = np.stack([pack_lists(gpipe_lists(64, 6)), pack_lists(one_f_one_b_lists(64, 6))])
+    check_batch(prob, words, k=2, what="p=64", dur_mb=table)
+    prob = chain_problem(63, 3, v=4, f=2, b=3, w=1, comm=1)
+    table = rng.integers(0, 20, (NKINDS, 252, 3)).astype(np.int32)
+    lists = []
+    for t in range(6):
+        base = random_valid_lists(prob, rng)
+        lists += [base, perturb(base, rng, 2)]
+    check_batch(prob, batch_from_lists(lists), k=3, what="S=252", dur_mb=table)
