@@ -139,3 +139,16 @@ def test_largest_sizes_with_costs_per_micro_batch():
         base = random_valid_lists(prob, rng)
         lists += [base, perturb(base, rng, 2)]
     check_batch(prob, batch_from_lists(lists), k=3, what="S=252", dur_mb=table)
+
+
+def test_costs_beyond_sixteen_bits_use_the_table_in_device_memory():
+    # values that fit the slot kernel's times but not the LDS table's sixteen bits
+    from workloads.problem import chain_problem, gpipe_lists, one_f_one_b_lists, pack_lists
+    prob = chain_problem(2, 4, f=1, b=1, w=1, comm=1)
+    rng = np.random.default_rng(70000)
+    table = rng.integers(60000, 90000, (NKINDS, 2, 4)).astype(np.int32)
+    lists = [one_f_one_b_lists(2, 4), gpipe_lists(2, 4)]
+    with_w = [[[op for x in row for op in ([x, (3, x[1], x[2])] if x[0] == 2 else [x])] for row in l] for l in lists]
+    words = np.stack([pack_lists(l, stride=16) for l in with_w])
+    gpu, ref = check_batch(prob, words, k=2, what="costs of 17 bits", dur_mb=table)
+    assert (ref["flags"] == 0).all() and ref["makespan"].min() > 60000 * 8
