@@ -113,3 +113,39 @@ def test_small_cases_and_errors():
     with pytest.raises(fp.FpschedError):
         h.wslide(to_gpu(workloads.generate(spec)), spec.stride)
     h.close()
+
+
+@pytest.mark.parametrize("links", [False, True])
+def test_largest_sizes_and_long_stashes(links):
+    from helpers import batch_from_lists, perturb, random_valid_lists
+    from workloads.problem import gpipe_lists, one_f_one_b_lists
+
+    def check(prob, words, stride_out, what):
+        h = fp.Problem(prob, max(words.shape[2], stride_out), device=0)
+        if links:
+            h.set_link_occupancy(True)
+        _, got = run_gpu(h, words, stride_out)
+        assert_same(got, oracle.wslide(prob, words, stride_out, threads=8, links=links), what)
+        h.close()
+        return got
+
+    # GPipe order on two devices, 1024 micro-batches: the last device runs all its backward items back to back,
+    # so its stash grows to 1024 items (far beyond the kernel's ring of 16) before anything can be placed
+    m = 1024
+    prob = chain_problem(2, m, f=1, b=2, w=1, comm=3)
+    words = np.stack([pack_lists(gpipe_lists(2, m), stride=3 * m + 8), pack_lists(one_f_one_b_lists(2, m), stride=3 * m + 8)])
+    got = check(prob, words, 3 * m + 8, "m=1024")
+    assert (got["flags"] == 0).all()
+    check(prob, words, 3 * m - 8, "m=1024, rows too short")
+    # 64 devices; 252 stages on 63 devices
+    prob = chain_problem(64, 6, f=2, b=4, w=3, comm=2)
+    words = np.stack([pack_lists(gpipe_lists(64, 6), stride=24), pack_lists(one_f_one_b_lists(64, 6), stride=24)])
+    check(prob, words, 24, "p=64")
+    prob = chain_problem(63, 3, v=4, f=2, b=3, w=1, comm=1)
+    rng = np.random.default_rng(252)
+    lists = []
+    for t in range(6):
+        base = random_valid_lists(prob, rng)
+        lists += [base, perturb(base, rng, 2)]
+    words = batch_from_lists(lists)
+    check(prob, words, words.shape[2] + 8, "S=252")
