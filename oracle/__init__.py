@@ -138,7 +138,6 @@ def evaluate(problem, words, threads: int = 1, dur_mb=None, links: bool = False)
     ``dur_mb[8][S][m]``: per-micro-batch costs in place of ``problem.dur``.  ``links``: every ordered
     pair of devices is a link that carries one value at a time (see fporacle_evaluate_links).
     """
-    assert not (links and dur_mb is not None), "one variant of the cost model at a time"
     lib = _load()
     mp = _Marshalled(problem)
     table = _mb_table(mp, dur_mb)
@@ -154,7 +153,7 @@ def evaluate(problem, words, threads: int = 1, dur_mb=None, links: bool = False)
             return 0
         if links:
             return lib.fporacle_evaluate_links(
-                ctypes.byref(mp.c), ctypes.c_void_p(w[lo:hi].ctypes.data), ctypes.c_int64(hi - lo),
+                ctypes.byref(mp.c), table_ptr, ctypes.c_void_p(w[lo:hi].ctypes.data), ctypes.c_int64(hi - lo),
                 ctypes.c_int32(stride), ctypes.c_void_p(out["makespan"][lo:hi].ctypes.data),
                 ctypes.c_void_p(out["idle"][lo:hi].ctypes.data),
                 ctypes.c_void_p(out["peak"][lo:hi].ctypes.data),
@@ -182,7 +181,6 @@ def evaluate(problem, words, threads: int = 1, dur_mb=None, links: bool = False)
 
 def evaluate_trace(problem, words_one, dur_mb=None, links: bool = False):
     """One candidate ``words[D][stride]``; also returns every op's start/finish."""
-    assert not (links and dur_mb is not None), "one variant of the cost model at a time"
     lib = _load()
     mp = _Marshalled(problem)
     table = _mb_table(mp, dur_mb)
@@ -198,11 +196,8 @@ def evaluate_trace(problem, words_one, dur_mb=None, links: bool = False):
     tail = (ctypes.c_void_p(w.ctypes.data), ctypes.c_int32(stride), ctypes.c_void_p(ms.ctypes.data),
             ctypes.c_void_p(idle.ctypes.data), ctypes.c_void_p(peak.ctypes.data), ctypes.c_void_p(fl.ctypes.data),
             ctypes.c_void_p(st.ctypes.data), ctypes.c_void_p(fi.ctypes.data))
-    if links:
-        rc = lib.fporacle_eval_one_links(ctypes.byref(mp.c), *tail)
-    else:
-        rc = lib.fporacle_eval_one_mb(ctypes.byref(mp.c),
-                                      ctypes.c_void_p(table.ctypes.data if table is not None else None), *tail)
+    table_ptr = ctypes.c_void_p(table.ctypes.data if table is not None else None)
+    rc = (lib.fporacle_eval_one_links if links else lib.fporacle_eval_one_mb)(ctypes.byref(mp.c), table_ptr, *tail)
     if rc:
         raise ValueError("fporacle: invalid problem description")
     return dict(makespan=int(ms[0]), idle=idle, peak=peak, flags=int(fl[0]), start=st, finish=fi)

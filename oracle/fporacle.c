@@ -312,16 +312,19 @@ int fporacle_evaluate_mb(const fporacle_problem *P, const int32_t *dur_mb, const
  * (order rules, memory, idle, flags) is as in the plain model; with latencies of zero the two coincide.
  * Pins: tests/test_oracle_links.py.
  */
-int fporacle_eval_one_links(const fporacle_problem *P, const uint16_t *words, int32_t stride, int64_t *makespan,
-                            int64_t *idle, int32_t *peak, uint8_t *flags, int64_t *op_start, int64_t *op_finish) {
-  return eval_one(P, NULL, 1, words, stride, makespan, idle, peak, flags, op_start, op_finish);
+int fporacle_eval_one_links(const fporacle_problem *P, const int32_t *dur_mb, const uint16_t *words, int32_t stride,
+                            int64_t *makespan, int64_t *idle, int32_t *peak, uint8_t *flags, int64_t *op_start,
+                            int64_t *op_finish) {
+  return eval_one(P, dur_mb, 1, words, stride, makespan, idle, peak, flags, op_start, op_finish);
 }
 
-int fporacle_evaluate_links(const fporacle_problem *P, const uint16_t *words, int64_t n_cand, int32_t stride,
-                            int64_t *makespan, int64_t *idle, int32_t *peak, uint8_t *flags) {
+/* dur_mb: NULL, or costs per micro-batch as in fporacle_evaluate_mb (the two variants are independent: one
+ * says what an item costs, the other when its result arrives). */
+int fporacle_evaluate_links(const fporacle_problem *P, const int32_t *dur_mb, const uint16_t *words, int64_t n_cand,
+                            int32_t stride, int64_t *makespan, int64_t *idle, int32_t *peak, uint8_t *flags) {
   const int D = P->n_devices;
   for (int64_t c = 0; c < n_cand; ++c) {
-    int rc = eval_one(P, NULL, 1, words + (size_t)c * D * stride, stride, &makespan[c],
+    int rc = eval_one(P, dur_mb, 1, words + (size_t)c * D * stride, stride, &makespan[c],
                       &idle[c * D], &peak[c * D], &flags[c], NULL, NULL);
     if (rc) return rc;
   }

@@ -155,3 +155,35 @@ def test_against_the_plain_model_on_the_benchmark_shapes(index, n):
     slow.edge_comm[:] = np.asarray(prob.edge_comm) + 3
     slower = oracle.evaluate(slow, words, threads=4, links=True)
     assert np.all(slower["makespan"][ok] >= linked["makespan"][ok])
+
+
+def test_both_variants_of_the_cost_model_together():
+    # costs per micro-batch say what an item costs, links when its result arrives: the checker with per-item
+    # weights and transfer nodes, and each variant alone as a special case of the pair
+    rng = np.random.default_rng(77)
+    prob = chain_problem(3, 5, v=2, f=1, b=1, w=2, comm=0)
+    prob.edge_comm[:] = rng.integers(0, 9, len(prob.edge_comm))
+    table = rng.integers(0, 9, (8, prob.n_stages, prob.n_microbatches)).astype(np.int32)
+    table[7] = table[1]
+    constant = np.repeat(np.asarray(prob.dur, np.int32)[:, :, None], prob.n_microbatches, axis=2)
+    for t in range(25):
+        lists = random_valid_lists(prob, rng, 0.3, 0.2)
+        for cand in (lists, perturb(lists, rng, 2)):
+            words = pack_lists(cand, stride=-(-(max(len(x) for x in cand) + 1) // 8) * 8)
+            o = oracle.evaluate_trace(prob, words, dur_mb=table, links=True)
+            c = checker.check(prob, words, dur_mb=table, links=True)
+            if c["deadlock"] or c["incomplete"]:
+                assert o["makespan"] == oracle.INT64_MAX
+                continue
+            assert o["makespan"] == c["makespan"] and list(o["idle"]) == c["idle"]
+            for (d, i), fin in c["finish"].items():
+                assert o["finish"][d][i] == fin
+            same = oracle.evaluate_trace(prob, words, dur_mb=constant, links=True)
+            alone = oracle.evaluate_trace(prob, words, links=True)
+            assert same["makespan"] == alone["makespan"] and np.array_equal(same["finish"], alone["finish"])
+    free = copy.deepcopy(prob)
+    free.edge_comm[:] = 0
+    words = pack_lists(lists, stride=-(-(max(len(x) for x in lists) + 1) // 8) * 8)
+    a = oracle.evaluate_trace(free, words, dur_mb=table, links=True)
+    b = oracle.evaluate_trace(free, words, dur_mb=table)
+    assert a["makespan"] == b["makespan"] and np.array_equal(a["finish"], b["finish"])
