@@ -135,7 +135,8 @@ void fpsched_problem_destroy(fpsched_problem *p);
  * allocates two tables of device memory (FPSCHED_ENOMEM), freed by fpsched_problem_destroy.
  * FPSCHED_EINVAL for a negative value, FPSCHED_EOVERFLOW if D * max_stride * (max value + max
  * comm) >= 2^31, FPSCHED_EUNSUPPORTED if no kernel fits these values: the handle then keeps
- * what it had.  After FPSCHED_EHIP / FPSCHED_ENOMEM it is back on desc.dur.  While a table is set,
+ * what it had.  After FPSCHED_EHIP / FPSCHED_ENOMEM, and when the table cannot be combined with
+ * link occupancy that is switched on, it is back on desc.dur.  While a table is set,
  * fpsched_wslide returns FPSCHED_EUNSUPPORTED (the sliding pass knows one cost per (type, stage));
  * fpsched_generate ignores costs anyway.  Works on a host-only handle (validation only). */
 int fpsched_problem_set_microbatch_costs(fpsched_problem *p, const int32_t *dur_mb);
@@ -151,9 +152,11 @@ int fpsched_problem_set_microbatch_costs(fpsched_problem *p, const int32_t *dur_
  * inputs have arrived; everything else is unchanged, and with latencies of zero the two models
  * coincide.  on == 0 switches back.  Only the slot kernel has this form: FPSCHED_EUNSUPPORTED if
  * the problem does not fit it (more than two inputs or outputs per stage, or
- * D * max_stride * (max dur + 2 * max comm) >= 2^24), if costs per micro-batch are set (one variant
- * at a time; the reverse order of the two calls is refused the same way), and from
- * fpsched_evaluate while the general kernel is selected.  fpsched_wslide follows the switch (the
+ * D * max_stride * (max dur + 2 * max comm) >= 2^24), and from fpsched_evaluate while the general
+ * kernel is selected.  Together with costs per micro-batch (either call may come first; the two are
+ * independent: one says what an item costs, the other when its result arrives) it needs the cost
+ * table in LDS: the call that would complete the pair answers FPSCHED_EUNSUPPORTED otherwise and
+ * the handle stays on the variant it had.  fpsched_wslide follows the switch (the
  * weight-gradient items send nothing, so its rule is unchanged; the times it works with are this
  * model's).
  * The first call on a device handle allocates one more table image (FPSCHED_ENOMEM); not to be

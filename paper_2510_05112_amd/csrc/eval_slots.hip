@@ -134,8 +134,9 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     unsigned long long* __restrict__ next_candidate, int draw_block,
     uint32_t* __restrict__ out_start8, int32_t* __restrict__ out_stop, const int32_t* __restrict__ mb_rows) {
   constexpr bool TIMES = MODE == kSlotTimes || MODE == kSlotTimesLinks;
-  constexpr bool MBDUR = MODE == kSlotPerMicrobatch, MBLDS = MODE == kSlotPerMicrobatchLds;
-  constexpr bool LINKS = MODE == kSlotLinks || MODE == kSlotTimesLinks;
+  constexpr bool MBDUR = MODE == kSlotPerMicrobatch;
+  constexpr bool MBLDS = MODE == kSlotPerMicrobatchLds || MODE == kSlotPerMicrobatchLdsLinks;
+  constexpr bool LINKS = MODE == kSlotLinks || MODE == kSlotTimesLinks || MODE == kSlotPerMicrobatchLdsLinks;
   extern __shared__ int32_t lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int m = T.m;
@@ -605,7 +606,8 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotPerMicrobatch) \
   FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotPerMicrobatchLds) \
   FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotLinks)            \
-  FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotTimesLinks)
+  FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotTimesLinks)       \
+  FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotPerMicrobatchLdsLinks)
 FPSCHED_INSTANTIATE(1, false, true)
 FPSCHED_INSTANTIATE(2, false, true)
 FPSCHED_INSTANTIATE(4, false, true)

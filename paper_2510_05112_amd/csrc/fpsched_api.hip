@@ -51,6 +51,16 @@ struct fpsched_problem {
   bool links_on = false;
   SlotTables stab_links{};
   int32_t* d_links_image = nullptr;
+  // both variants together: the cost-table image with the link form's device rows
+  std::vector<int32_t> mb_image_host;   // host copy of the image behind stab_mb
+  std::vector<int32_t> link_rows;       // [lanes per candidate][4V] out-edge entries of the link form
+  int32_t link_words = 0;
+  int64_t mb_max_dur = 0;               // largest value of the cost table that is set
+  bool combo_ok = false;
+  SlotTables stab_combo{};
+  int32_t* d_combo_image = nullptr;
+  size_t combo_image_ints = 0;
+  int32_t combo_waves = 0, combo_grid = 0, combo_lds_bytes = 0;
   std::vector<int32_t> times_ints;      // host copy of the timing pass's table image
   bool links_slide_ok = false;          // the sliding pass has a link form (its LDS fits)
   SlotTables stab_times_links{};
@@ -498,6 +508,7 @@ void fpsched_problem_destroy(fpsched_problem* p) {
     if (p->d_mb_image) (void)hipFree(p->d_mb_image);
     if (p->d_links_image) (void)hipFree(p->d_links_image);
     if (p->d_times_links_image) (void)hipFree(p->d_times_links_image);
+    if (p->d_combo_image) (void)hipFree(p->d_combo_image);
   }
   delete p;
 }
@@ -558,11 +569,13 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
     unsigned long long* counter = static_cast<unsigned long long*>(d_workspace);
     // costs per micro-batch: their own table image and workgroup shape when the table sits in LDS
     const bool mb_lds = p->mb_set && p->mb_in_lds;
-    const bool links = p->links_on;   // (never together with costs per micro-batch)
-    const SlotTables& tab = links ? p->stab_links : (mb_lds ? p->stab_mb : p->stab);
-    const int waves = links ? p->links_waves : (mb_lds ? p->mb_waves : p->slot_waves);
-    const int grid = links ? p->links_grid : (mb_lds ? p->mb_grid : p->slot_grid);
-    const size_t lds_bytes = (size_t)(links ? p->links_lds_bytes : (mb_lds ? p->mb_lds_bytes : p->slot_lds_bytes));
+    const bool combo = p->links_on && p->mb_set;   // both variants: the setters made sure the tables exist
+    if (combo && !p->combo_ok) return FPSCHED_EUNSUPPORTED;
+    const bool links = p->links_on && !combo;
+    const SlotTables& tab = combo ? p->stab_combo : links ? p->stab_links : (mb_lds ? p->stab_mb : p->stab);
+    const int waves = combo ? p->combo_waves : links ? p->links_waves : (mb_lds ? p->mb_waves : p->slot_waves);
+    const int grid = combo ? p->combo_grid : links ? p->links_grid : (mb_lds ? p->mb_grid : p->slot_grid);
+    const size_t lds_bytes = (size_t)(combo ? p->combo_lds_bytes : links ? p->links_lds_bytes : (mb_lds ? p->mb_lds_bytes : p->slot_lds_bytes));
     const int per_block = tab.cands_per_wave * waves;
     const int64_t blocks = std::min<int64_t>((n_cand + per_block - 1) / per_block, grid);
     // Candidates per atomic draw.  Atomics on one address complete at some 8e7 per second; a batch of
@@ -574,7 +587,8 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
     hipLaunchKernelGGL(reset_counter_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(hip_stream), counter,
                        (unsigned long long)(blocks * per_block));
     const bool one_class = p->stab.n_classes == 1;
-    const SlotKernel kernel = links ? slot_kernel_of<kSlotLinks>(p->slot_v, p->slot_deg2, one_class)
+    const SlotKernel kernel = combo ? slot_kernel_of<kSlotPerMicrobatchLdsLinks>(p->slot_v, p->slot_deg2, one_class)
+                              : links ? slot_kernel_of<kSlotLinks>(p->slot_v, p->slot_deg2, one_class)
                               : !p->mb_set ? slot_kernel_ptr(p->slot_v, p->slot_deg2, one_class)
                               : (mb_lds ? slot_kernel_of<kSlotPerMicrobatchLds>(p->slot_v, p->slot_deg2, one_class)
                                         : slot_kernel_of<kSlotPerMicrobatch>(p->slot_v, p->slot_deg2, one_class));
@@ -583,7 +597,7 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
                        (long long)n_cand, (int)stride_words, reinterpret_cast<long long*>(out.makespan),
                        reinterpret_cast<long long*>(out.idle), out.peak, out.flags, counter, draw_block,
                        (uint32_t*)nullptr, (int32_t*)nullptr,
-                       (const int32_t*)(p->mb_set && !mb_lds ? p->d_mb_rows : nullptr));
+                       (const int32_t*)(p->mb_set && !mb_lds && !combo ? p->d_mb_rows : nullptr));
     return check_hip(hipGetLastError());
   }
   const int cpw = p->tables.cands_per_wave;
@@ -597,13 +611,65 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
   return check_hip(hipGetLastError());
 }
 
+// Costs per micro-batch and link occupancy together: the image behind stab_mb with the link form's longer
+// device rows.  Needs both built (the cost table in LDS).  FPSCHED_EUNSUPPORTED if it does not fit.
+static int build_combined_tables(fpsched_problem* p) {
+  p->combo_ok = false;
+  if (!p->mb_in_lds || p->mb_image_host.empty() || p->link_rows.empty()) return FPSCHED_EUNSUPPORTED;
+  const SlotTables& MT = p->stab_mb;
+  const int V = p->slot_v, lpc = MT.lanes_per_cand;
+  const int dev_ints = MT.dev_ints + 4 * V;
+  const int slots_per_cand = (2 * MT.n_classes * p->m + 7) & ~7;   // no dump region in the link form
+  SlotGeometry geo = slot_geometry(MT.n_shared_ints, lpc, MT.state_words + p->link_words, slots_per_cand, p->max_lds,
+                                   MT.cands_per_wave);
+  if (geo.waves * geo.groups < 4 || geo.cands_per_wave != MT.cands_per_wave) return FPSCHED_EUNSUPPORTED;
+  const std::vector<int32_t>& B = p->mb_image_host;
+  std::vector<int32_t> J((size_t)MT.n_shared_ints + (size_t)lpc * dev_ints + (size_t)lpc * MT.state_words, 0);
+  std::copy(B.begin(), B.begin() + MT.n_shared_ints, J.begin());
+  for (int d = 0; d < lpc; ++d) {
+    int32_t* row = &J[(size_t)MT.n_shared_ints + (size_t)d * dev_ints];
+    std::copy(B.begin() + MT.off_dev + (size_t)d * MT.dev_ints, B.begin() + MT.off_dev + (size_t)(d + 1) * MT.dev_ints, row);
+    std::copy(p->link_rows.begin() + (size_t)d * 4 * V, p->link_rows.begin() + (size_t)(d + 1) * 4 * V, row + MT.dev_ints);
+  }
+  std::copy(B.begin() + MT.off_expect, B.end(), J.begin() + MT.n_shared_ints + (size_t)lpc * dev_ints);
+  DeviceGuard g(p->device_id);
+  if (!g.ok) return FPSCHED_EHIP;
+  if (hipDeviceSynchronize() != hipSuccess) return FPSCHED_EHIP;   // an earlier image may be in use
+  if (J.size() > p->combo_image_ints) {
+    if (p->d_combo_image) (void)hipFree(p->d_combo_image);
+    p->d_combo_image = nullptr;
+    p->combo_image_ints = 0;
+    if (hipMalloc(&p->d_combo_image, J.size() * sizeof(int32_t)) != hipSuccess) { p->d_combo_image = nullptr; return FPSCHED_ENOMEM; }
+    p->combo_image_ints = J.size();
+  }
+  const int32_t lds_bytes = (int32_t)(4ll * (MT.n_shared_ints + (int64_t)geo.waves * geo.wave_ints));
+  if (hipMemcpy(p->d_combo_image, J.data(), J.size() * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess ||
+      hipFuncSetAttribute(reinterpret_cast<const void*>(slot_kernel_of<kSlotPerMicrobatchLdsLinks>(p->slot_v, p->slot_deg2, MT.n_classes == 1)),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
+    return FPSCHED_EHIP;
+  p->stab_combo = MT;
+  p->stab_combo.ints = p->d_combo_image;
+  p->stab_combo.link_words = p->link_words;
+  p->stab_combo.slots_per_cand = slots_per_cand;
+  p->stab_combo.dev_ints = dev_ints;
+  p->stab_combo.off_expect = MT.n_shared_ints + lpc * dev_ints;
+  p->stab_combo.cands_per_wave = geo.cands_per_wave;
+  p->stab_combo.wave_ints = geo.wave_ints;
+  p->combo_waves = geo.waves;
+  p->combo_grid = p->n_cu * geo.groups;
+  p->combo_lds_bytes = lds_bytes;
+  p->combo_ok = true;
+  if (getenv("FPSCHED_VERBOSE"))
+    fprintf(stderr, "[fpsched] costs per micro-batch + link occupancy: %d x %d wavefronts per compute unit\n", geo.groups, geo.waves);
+  return FPSCHED_OK;
+}
+
 int fpsched_problem_set_microbatch_costs(fpsched_problem* p, const int32_t* dur_mb) {
   if (!p) return FPSCHED_EINVAL;
   if (!dur_mb) {
     p->mb_set = false;   // the tables stay allocated for the next call
     return FPSCHED_OK;
   }
-  if (p->links_on) return FPSCHED_EUNSUPPORTED;   // one variant of the cost model at a time
   const int D = p->D, S = p->S, m = p->m;
   const size_t n_raw = (size_t)kNKinds * S * m;
   int64_t max_dur = 0;
@@ -611,14 +677,17 @@ int fpsched_problem_set_microbatch_costs(fpsched_problem* p, const int32_t* dur_
     if (dur_mb[i] < 0) return FPSCHED_EINVAL;
     max_dur = std::max<int64_t>(max_dur, dur_mb[i]);
   }
-  const int64_t bound = (int64_t)D * p->max_stride * (max_dur + p->max_comm);
+  // (with links every item may add two transfers to the longest chain)
+  const int64_t bound = (int64_t)D * p->max_stride * (max_dur + (p->links_on ? 2 : 1) * p->max_comm);
   if (bound >= (int64_t)1 << 31) return FPSCHED_EOVERFLOW;
   const bool fits_slots = bound < (1ll << 24);
   if (p->device_id < 0) {
     p->mb_set = true;
     p->mb_slots_ok = fits_slots;
+    p->mb_max_dur = max_dur;
     return FPSCHED_OK;
   }
+  if (p->links_on && !(p->slots_ok && fits_slots)) return FPSCHED_EUNSUPPORTED;   // the link form is the slot kernel's
   if (!(p->slots_ok && fits_slots) && !p->general_ok) return FPSCHED_EUNSUPPORTED;
   const int lpc = p->tables.lanes_per_cand;
   const size_t n_rows = (size_t)kNKinds * kMaxChunks * lpc * m;
@@ -694,6 +763,7 @@ int fpsched_problem_set_microbatch_costs(fpsched_problem* p, const int32_t* dur_
         p->mb_image_ints = J.size();
       }
       if (hipMemcpy(p->d_mb_image, J.data(), J.size() * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess) return FPSCHED_EHIP;
+      p->mb_image_host = J;
       p->stab_mb = ST;
       p->stab_mb.ints = p->d_mb_image;
       p->stab_mb.off_mb = ST.n_shared_ints;
@@ -714,6 +784,10 @@ int fpsched_problem_set_microbatch_costs(fpsched_problem* p, const int32_t* dur_
     }
   }
   p->mb_in_lds = in_lds;
+  if (p->links_on) {   // both variants: only with the table in LDS; else the handle stays on the links alone
+    const int rc = build_combined_tables(p);
+    if (rc != FPSCHED_OK) return rc;
+  }
   if (getenv("FPSCHED_VERBOSE"))
     fprintf(stderr, "[fpsched] costs per micro-batch: %s; slot kernel %d x %d wavefronts per compute unit (plain: %d x %d), LDS limit %d bytes\n",
             !(p->slots_ok && fits_slots) ? "general kernel" : (in_lds ? "slot kernel, table in LDS" : "slot kernel, table in device memory"),
@@ -721,6 +795,7 @@ int fpsched_problem_set_microbatch_costs(fpsched_problem* p, const int32_t* dur_
             p->slot_grid / std::max(p->n_cu, 1), p->slot_waves, p->max_lds);
   p->mb_set = true;
   p->mb_slots_ok = p->slots_ok && fits_slots;
+  p->mb_max_dur = max_dur;
   return FPSCHED_OK;
 }
 
@@ -730,10 +805,9 @@ int fpsched_problem_set_link_occupancy(fpsched_problem* p, int32_t on) {
     p->links_on = false;   // the table image stays allocated for the next call
     return FPSCHED_OK;
   }
-  if (p->mb_set) return FPSCHED_EUNSUPPORTED;   // one variant of the cost model at a time
   const int D = p->D, S = p->S;
   // every finish time is at most the sum of all costs and of all transfers (at most two per op here)
-  const int64_t bound = (int64_t)D * p->max_stride * (p->max_dur + 2 * p->max_comm);
+  const int64_t bound = (int64_t)D * p->max_stride * ((p->mb_set ? p->mb_max_dur : p->max_dur) + 2 * p->max_comm);
   if (bound >= (int64_t)1 << 31) return FPSCHED_EOVERFLOW;
   if (p->device_id < 0) {
     p->links_on = true;
@@ -741,6 +815,10 @@ int fpsched_problem_set_link_occupancy(fpsched_problem* p, int32_t on) {
   }
   if (!p->slots_ok || bound >= (1ll << 24)) return FPSCHED_EUNSUPPORTED;
   if (p->d_links_image) {   // built by an earlier call
+    if (p->mb_set) {        // both variants: the cost table's image with this form's device rows
+      const int rc = build_combined_tables(p);
+      if (rc != FPSCHED_OK) return rc;
+    }
     p->links_on = true;
     return FPSCHED_OK;
   }
@@ -844,6 +922,15 @@ int fpsched_problem_set_link_occupancy(fpsched_problem* p, int32_t on) {
   p->links_waves = geo.waves;
   p->links_grid = p->n_cu * geo.groups;
   p->links_lds_bytes = lds_bytes;
+  p->link_words = link_words;
+  p->link_rows.assign((size_t)lpc * 4 * V, 0);
+  for (int d = 0; d < lpc; ++d)
+    std::copy(J.begin() + ST.n_shared_ints + (size_t)d * dev_ints + ST.dev_ints,
+              J.begin() + ST.n_shared_ints + (size_t)(d + 1) * dev_ints, p->link_rows.begin() + (size_t)d * 4 * V);
+  if (p->mb_set) {   // both variants (the link tables stay built whatever comes of it)
+    const int rc = build_combined_tables(p);
+    if (rc != FPSCHED_OK) return rc;
+  }
   p->links_on = true;
   // the sliding pass's timing kernel under the link model: the timing image, widened the same way; it
   // needs 16 bytes of LDS more

@@ -35,8 +35,9 @@ constexpr int kSlotMaxThreads = 64 * kSlotMaxWaves;
 // MODE kSlotLinks: every ordered pair of devices is a link that carries one value at a time; a
 // producer holds its value back until its link is free (T.link_words, the longer dev rows).
 // MODE kSlotTimesLinks: the timing pass of the sliding under the link model (both of the above).
+// MODE kSlotPerMicrobatchLdsLinks: costs per micro-batch from LDS and link occupancy together.
 constexpr int kSlotPlain = 0, kSlotTimes = 1, kSlotPerMicrobatch = 2, kSlotPerMicrobatchLds = 3, kSlotLinks = 4,
-              kSlotTimesLinks = 5;
+              kSlotTimesLinks = 5, kSlotPerMicrobatchLdsLinks = 6;
 template <int V, bool DEG2, bool ONE_CLASS, int MODE>
 __global__ void eval_slot_kernel(SlotTables T, const uint16_t* ops, long long n_cand, int stride,
                                  long long* out_makespan, long long* out_idle, int* out_peak,

@@ -84,9 +84,6 @@ def test_switching_the_variant_on_and_off_on_one_handle():
     assert_same(run(), plain, "before")
     h.set_link_occupancy(True)
     assert_same(run(), linked, "links on")
-    with pytest.raises(fp.FpschedError) as e:
-        h.set_microbatch_costs(workloads.microbatch_costs(prob))
-    assert e.value.code == -6
     # the sliding pass follows the switch
     slid = h.wslide(ops)
     torch.cuda.synchronize()
@@ -101,14 +98,45 @@ def test_switching_the_variant_on_and_off_on_one_handle():
     h.select_kernel("auto")
     h.set_link_occupancy(False)
     assert_same(run(), plain, "links off")
-    h.set_microbatch_costs(workloads.microbatch_costs(prob))
+    # both variants, in either order of the calls, and back to each alone
+    table = workloads.microbatch_costs(prob)
+    both = oracle.evaluate(prob, words, threads=8, dur_mb=table, links=True)
+    h.set_microbatch_costs(table)
+    h.set_link_occupancy(True)
+    assert_same(run(), both, "costs, then links")
     with pytest.raises(fp.FpschedError) as e:
-        h.set_link_occupancy(True)
+        h.wslide(ops)
     assert e.value.code == -6
     h.set_microbatch_costs(None)
-    h.set_link_occupancy(True)
-    assert_same(run(), linked, "links on again")
+    assert_same(run(), linked, "links alone again")
+    h.set_microbatch_costs(table)
+    assert_same(run(), both, "links, then costs")
+    h.set_link_occupancy(False)
+    assert_same(run(), oracle.evaluate(prob, words, threads=8, dur_mb=table), "costs alone")
     h.close()
+
+
+@pytest.mark.parametrize("index,n", [(2, 3000), (3, 700), (4, 900), (5, 2000)])
+def test_both_variants_on_the_benchmark_shapes(index, n):
+    spec = workloads.config(index, n)
+    words = workloads.generate(spec, threads=8)
+    prob = slow_links(spec.problem, 70 + index)
+    check_batch(prob, words, k=16, what=f"cfg{index}", links=True, dur_mb=workloads.microbatch_costs(prob))
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_both_variants_on_random_problems(seed):
+    rng = np.random.default_rng(9800 + seed)
+    for i in range(8):
+        prob = random_problem(rng)
+        prob.edge_comm[:] = rng.integers(0, 12, len(prob.edge_comm))
+        table = rng.integers(0, 40 if i % 2 else 2000, (8, prob.n_stages, prob.n_microbatches)).astype(np.int32)
+        lists = []
+        for t in range(16):
+            base = random_valid_lists(prob, rng, 0.3 * (t % 2), 0.3 * ((t // 2) % 2))
+            lists.append(base)
+            lists.append(perturb(base, rng, 1 + t % 3))
+        check_batch(prob, batch_from_lists(lists), k=5, what=f"seed {seed} problem {i}", links=True, dur_mb=table)
 
 
 def check_slide(prob, words, stride_out, what):
