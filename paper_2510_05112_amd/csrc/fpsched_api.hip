@@ -927,11 +927,6 @@ int fpsched_problem_set_link_occupancy(fpsched_problem* p, int32_t on) {
   for (int d = 0; d < lpc; ++d)
     std::copy(J.begin() + ST.n_shared_ints + (size_t)d * dev_ints + ST.dev_ints,
               J.begin() + ST.n_shared_ints + (size_t)(d + 1) * dev_ints, p->link_rows.begin() + (size_t)d * 4 * V);
-  if (p->mb_set) {   // both variants (the link tables stay built whatever comes of it)
-    const int rc = build_combined_tables(p);
-    if (rc != FPSCHED_OK) return rc;
-  }
-  p->links_on = true;
   // the sliding pass's timing kernel under the link model: the timing image, widened the same way; it
   // needs 16 bytes of LDS more
   if (p->slide_ok && !p->times_ints.empty() && (int64_t)lds_bytes + 16 <= p->max_lds / geo.groups) {
@@ -950,6 +945,11 @@ int fpsched_problem_set_link_occupancy(fpsched_problem* p, int32_t on) {
       if (timg) (void)hipFree(timg);
     }
   }
+  if (p->mb_set) {   // both variants (the link tables stay built whatever comes of it)
+    const int rc = build_combined_tables(p);
+    if (rc != FPSCHED_OK) return rc;
+  }
+  p->links_on = true;
   if (getenv("FPSCHED_VERBOSE"))
     fprintf(stderr, "[fpsched] link occupancy: %d link words per lane, %d x %d wavefronts per compute unit (plain: %d x %d)\n",
             link_words, geo.groups, geo.waves, p->slot_grid / std::max(p->n_cu, 1), p->slot_waves);
