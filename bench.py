@@ -22,24 +22,73 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
-# HBM bytes of ONE evaluation launch on the default workload, from rocprofv3 FETCH_SIZE / WRITE_SIZE
-# scaled by a copy kernel of known size, and its VALU wave-instruction count (SQ_INSTS_VALU):
-# profiles/eval_slot_kernel_cfg4_counters.md.  Other workloads report null.
-MEASURED = {("cfg4", 65536): {"traffic_bytes": 4.514e9, "valu_wave_instructions": 2.088e9}}
-# with costs per micro-batch (--mb-costs): profiles/eval_slot_kernel_cfg4_microbatch_costs.md
-MEASURED_MB = {("cfg4", 65536): {"traffic_bytes": None, "valu_wave_instructions": 2.694e9}}
-# with link occupancy (--links): profiles/eval_slot_kernel_cfg4_link_occupancy.md
-MEASURED_LINKS = {("cfg4", 65536): {"traffic_bytes": None, "valu_wave_instructions": 2.890e9}}
 # int32 vector peak: 256 CUs x 4 SIMDs x 16 lanes, one operation per lane and clock at 2.4 GHz
 # (= the published 157.3 TFLOP/s fp32 vector figure / 4: an FMA counts two, packed issue two more)
 ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
-# the same for one generator launch (--mode generate): WRITE_SIZE x 1024 plus the parameter sets read;
-# profiles/generate_kernel_cfg4.md
-MEASURED_GENERATE = {("cfg4", 65536): {"traffic_bytes": 4.81e9, "valu_wave_instructions": 1.231e10}}
+# Counted figures of ONE launch of each kernel on the default workload, from the rocprofv3 summaries under
+# profiles/ (HBM traffic: FETCH_SIZE / WRITE_SIZE scaled by a copy kernel of known size; vector wavefront
+# instructions: SQ_INSTS_VALU).  They belong to the kernel as it was when the profile was taken:
+# profile_kernel_ms is that run's launch duration, and a live launch that differs from it by more than
+# 10 % means the kernel has changed since -- the counted figures are then left out (null) instead of being
+# carried over.  valu_per_wave_round: vector instructions of one round of the whole wavefront (from the
+# kernel's instruction listing), which turns the instruction count into wavefront-rounds.
+MEASURED = {("cfg4", 65536): {"traffic_bytes": 4.514e9, "valu_wave_instructions": 2.088e9,
+                              "valu_per_wave_round": 33.7, "profile_kernel_ms": 4.884,
+                              "profile": "profiles/eval_slot_kernel_cfg4_counters.md"}}
+# with costs per micro-batch (--mb-costs)
+MEASURED_MB = {("cfg4", 65536): {"traffic_bytes": None, "valu_wave_instructions": 2.694e9,
+                                 "valu_per_wave_round": None, "profile_kernel_ms": 7.32,
+                                 "profile": "profiles/eval_slot_kernel_cfg4_microbatch_costs.md"}}
+# with link occupancy (--links)
+MEASURED_LINKS = {("cfg4", 65536): {"traffic_bytes": None, "valu_wave_instructions": 2.890e9,
+                                    "valu_per_wave_round": None, "profile_kernel_ms": 6.16,
+                                    "profile": "profiles/eval_slot_kernel_cfg4_link_occupancy.md"}}
+# both cost-model variants together (--links --mb-costs)
+MEASURED_BOTH = {}
+# one generator launch (--mode generate): WRITE_SIZE x 1024 plus the parameter sets read
+MEASURED_GENERATE = {("cfg4", 65536): {"traffic_bytes": 4.81e9, "valu_wave_instructions": 1.231e10,
+                                       "valu_per_wave_round": None, "profile_kernel_ms": 23.3,
+                                       "profile": "profiles/generate_kernel_cfg4.md"}}
+# the sliding pass (--mode wslide), both of its kernels
+MEASURED_WSLIDE = {("cfg4", 65536): {"traffic_bytes": 8.08e10, "valu_wave_instructions": 5.54e9,
+                                     "valu_per_wave_round": None, "profile_kernel_ms": 20.2,
+                                     "profile": "profiles/wslide_kernel_cfg4.md"}}
 
 
-# the sliding kernel (--mode wslide): profiles/wslide_kernel_cfg4.md
-MEASURED_WSLIDE = {("cfg4", 65536): {"traffic_bytes": 8.08e10, "valu_wave_instructions": 5.54e9}}
+def rooflines(alg_bytes, kernel_ms, kernel_name, counted, units=None):
+    """The roofline object of the JSON line and its sibling.  `roofline` is the HBM view the metric names:
+    algorithmic bytes of one launch / the launch duration measured in this run, against 8 TB/s; `traffic`
+    is the counted HBM bytes of a launch, or null.  `issue` is the vector-ALU view of the same launch
+    (executed wavefront instructions x 64 lanes against the int32 issue peak), with the share of lane-rounds
+    that evaluated an op where the profile allows to state it; None when no count applies to this run."""
+    achieved = alg_bytes / (kernel_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": kernel_name,
+                "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": kernel_ms}
+    if not counted:
+        roofline["note"] = "no rocprofv3 count was taken for this workload"
+        return roofline, None
+    drift = kernel_ms / counted["profile_kernel_ms"] - 1.0
+    if abs(drift) > 0.10:
+        roofline["note"] = (f"the launch took {kernel_ms:.3f} ms, the profiled kernel {counted['profile_kernel_ms']:.3f} ms "
+                            f"({counted['profile']}): the counted figures belong to another version of the "
+                            "kernel and are left out")
+        return roofline, None
+    roofline["traffic"] = counted["traffic_bytes"]
+    roofline["traffic_source"] = counted["profile"]
+    tops = counted["valu_wave_instructions"] * 64 / (kernel_ms * 1e-3) / 1e12
+    issue = {"bound": "alu", "achieved": tops, "peak": ALU_PEAK_TOPS,
+             "unit": "TOP/s (int32 vector lane slots, waiting and masked lanes included)",
+             "frac": tops / ALU_PEAK_TOPS,
+             "vector_wave_instructions_per_launch": counted["valu_wave_instructions"],
+             "source": f"rocprofv3 SQ_INSTS_VALU of one launch on this workload ({counted['profile']}); "
+                       "occupancy of the issue slots, not useful throughput"}
+    if units and counted.get("valu_per_wave_round"):
+        wave_rounds = counted["valu_wave_instructions"] / counted["valu_per_wave_round"]
+        issue["useful_lane_fraction"] = units / (64.0 * wave_rounds)
+        issue["useful_frac_of_peak"] = issue["frac"] * issue["useful_lane_fraction"]
+        issue["vector_wave_instructions_per_unit"] = counted["valu_wave_instructions"] / units
+    return roofline, issue
 
 
 def bench_generate(args, spec, threads) -> int:
@@ -111,24 +160,8 @@ def bench_generate(args, spec, threads) -> int:
     # algorithmic bytes of one launch: the parameter sets in, every row of op words out (the rows are
     # written in full, END padding included: the evaluator reads them as they are), steps and status
     alg_bytes = pol.nbytes + inf.nbytes + words.nbytes + 5 * n
-    achieved = alg_bytes / (gen_ms * 1e-3) / 1e9
-    counted = MEASURED_GENERATE.get((f"cfg{spec.index}", n), {})
-    hbm_view = {"achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                "algorithmic_bytes_per_launch": alg_bytes}
-    if counted:
-        # a step-synchronous process bound by vector-ALU issue: executed int32 lane operations (64 per
-        # wavefront instruction, the rocprofv3 count for this workload) over the live launch duration
-        tops = counted["valu_wave_instructions"] * 64 / (gen_ms * 1e-3) / 1e12
-        gen_roofline = {"bound": "alu", "achieved": tops, "peak": ALU_PEAK_TOPS,
-                        "unit": "TOP/s (int32 vector lane operations)", "frac": tops / ALU_PEAK_TOPS,
-                        "traffic": counted["traffic_bytes"], "kernel": "fpsched generator kernel (generate_kernel)",
-                        "vector_wave_instructions_per_launch": counted["valu_wave_instructions"],
-                        "source": "rocprofv3 SQ_INSTS_VALU of one launch on this workload (profiles/generate_kernel_cfg4.md)",
-                        "hbm": hbm_view}
-    else:
-        gen_roofline = dict(hbm_view, bound="hbm", traffic=None, kernel="fpsched generator kernel (generate_kernel)",
-                            note="no instruction count was taken for this workload; the kernel is bound by "
-                                 "vector-ALU issue, not HBM (see configuration 4)")
+    gen_roofline, gen_issue = rooflines(alg_bytes, gen_ms, "fpsched generator kernel (generate_kernel)",
+                                        MEASURED_GENERATE.get((f"cfg{spec.index}", n)), units=n_ops)
     json_res = {
         "metric": "schedules generated, evaluated and ranked/sec" if search else "schedules generated/sec",
         "value": n / (ms_per_step * 1e-3), "unit": "schedules/s",
@@ -142,7 +175,7 @@ def bench_generate(args, spec, threads) -> int:
         "items_scheduled_per_s": n_ops / (ms_per_step * 1e-3),
         "generate_kernel_ms": gen_ms,
         "scheduling_steps": {"mean": float(steps.mean()), "max": int(steps.max())},
-        "roofline": gen_roofline,
+        "roofline": gen_roofline, "issue": gen_issue,
         "fractions": {"complete": float((out["status"].cpu().numpy() == 0).mean())},
         "host": {"parameter_sets_s": prep_s},
     }
@@ -176,7 +209,7 @@ def bench_generate(args, spec, threads) -> int:
                 "sample": f"first {nn} parameter sets on {threads} host threads; single thread: first {n1}",
                 "single_thread_value": n1 / t1}
     print(json.dumps(json_res))
-    return 0
+    return 0 if json_res.get("parity_sample", {}).get("bit_exact", True) else 1
 
 
 def bench_wslide(args, spec, threads) -> int:
@@ -233,7 +266,9 @@ def bench_wslide(args, spec, threads) -> int:
     # algorithmic bytes of one launch: the op words read, the new rows written in full (END padding
     # included: the evaluator reads them as they are), the per-candidate results
     alg_bytes = 2 * n_ops + words.nbytes + C * (8 + 8 * D + 4 * D + 1)
-    achieved = alg_bytes / (kernel_ms * 1e-3) / 1e9
+    ws_roofline, ws_issue = rooflines(
+        alg_bytes, kernel_ms, "fpsched sliding pass: eval_slot_kernel in its timing mode + wslide_place_kernel",
+        None if args.links else MEASURED_WSLIDE.get((f"cfg{spec.index}", C)))
     fl0, fl1 = before["flags"].cpu().numpy(), out["flags"].cpu().numpy()
     ms0, ms1 = before["makespan"].cpu().numpy(), out["makespan"].cpu().numpy()
     both = ((fl0 & 3) == 0) & ((fl1 & 3) == 0)
@@ -247,13 +282,7 @@ def bench_wslide(args, spec, threads) -> int:
                    "candidates": C, "devices": D, "stages": prob.n_stages, "microbatches": prob.n_microbatches,
                    "ops_per_candidate": n_ops / C, "stride_words": stride},
         "wslide_kernel_ms": kernel_ms,
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": None if args.links else MEASURED_WSLIDE.get((f"cfg{spec.index}", C), {}).get("traffic_bytes"),
-                     "kernel": "fpsched sliding pass: eval_slot_kernel in its timing mode + wslide_place_kernel",
-                     "algorithmic_bytes_per_launch": alg_bytes,
-                     "note": "two kernels per call; traffic is far above the algorithmic bytes: partly used cache "
-                             "lines of per-lane row streams (profiles/wslide_kernel_cfg4.md)"},
+        "roofline": ws_roofline, "issue": ws_issue,
         "effect": {"mean_makespan_ratio": float((ms1[both] / ms0[both]).mean()) if both.any() else None,
                    "shorter": float((ms1[both] < ms0[both]).mean()) if both.any() else None,
                    "longer": float((ms1[both] > ms0[both]).mean()) if both.any() else None,
@@ -288,7 +317,7 @@ def bench_wslide(args, spec, threads) -> int:
                 "sample": f"first {nn} candidates of the same batch on {threads} host threads; "
                           f"single thread: first {n1}", "single_thread_value": n1 / t1}
     print(json.dumps(json_res))
-    return 0
+    return 0 if json_res.get("parity_sample", {}).get("bit_exact", True) else 1
 
 
 def main() -> int:
@@ -405,29 +434,9 @@ def main() -> int:
     # algorithmic bytes of one evaluation launch: 2 B per op word actually needed, plus the
     # per-candidate outputs (makespan 8 + idle 8D + peak 4D + flags 1)
     alg_bytes = 2 * n_ops + C * (8 + 8 * D + 4 * D + 1)
-    achieved = alg_bytes / (eval_ms * 1e-3) / 1e9
-
-    counted = {} if args.links and args.mb_costs else MEASURED_LINKS if args.links else MEASURED_MB if args.mb_costs else MEASURED
-    measured = counted.get((f"cfg{spec.index}", C), {})
-    hbm_view = {"achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                "algorithmic_bytes_per_launch": alg_bytes}
-    kernel_name = "fpsched evaluation kernel (eval_slot_kernel)"
-    if measured:
-        # the kernel is bound by vector-ALU issue: executed int32 lane operations (64 per wavefront
-        # instruction, counted by rocprofv3 for exactly this workload) over the live launch duration
-        tops = measured["valu_wave_instructions"] * 64 / (eval_ms * 1e-3) / 1e12
-        roofline = {"bound": "alu", "achieved": tops, "peak": ALU_PEAK_TOPS,
-                    "unit": "TOP/s (int32 vector lane operations)", "frac": tops / ALU_PEAK_TOPS,
-                    "traffic": measured["traffic_bytes"], "kernel": kernel_name,
-                    "vector_wave_instructions_per_launch": measured["valu_wave_instructions"],
-                    "vector_wave_instructions_per_op_eval": measured["valu_wave_instructions"] / n_ops,
-                    "source": "rocprofv3 SQ_INSTS_VALU of one launch on this workload (profiles/), executed "
-                              "instructions, waiting lanes included",
-                    "hbm": hbm_view}
-    else:
-        roofline = dict(hbm_view, bound="hbm", traffic=None, kernel=kernel_name,
-                        note="no instruction count was taken for this workload; the kernel is bound by "
-                             "vector-ALU issue, not HBM (see the default workload)")
+    counted = MEASURED_BOTH if args.links and args.mb_costs else MEASURED_LINKS if args.links else MEASURED_MB if args.mb_costs else MEASURED
+    roofline, issue = rooflines(alg_bytes, eval_ms, "fpsched evaluation kernel (eval_slot_kernel)",
+                                counted.get((f"cfg{spec.index}", C)), units=n_ops)
     flags = res["flags"].cpu().numpy()
     makespan = res["makespan"].cpu().numpy()
     out = {
@@ -447,7 +456,7 @@ def main() -> int:
                    "stride_words": stride, "top_k": k},
         "op_evals_per_s": n_ops / (ms_per_step * 1e-3),
         "eval_kernel_ms": eval_ms, "eval_kernel_ms_median": float(np.median(eval_each)), "topk_ms": topk_ms,
-        "roofline": roofline,
+        "roofline": roofline, "issue": issue,
         "fractions": {"feasible_under_cap": float((flags == 0).mean()),
                       "over_cap": float((flags == 4).mean()),
                       "deadlock": float(((flags & 1) != 0).mean())},
@@ -485,7 +494,8 @@ def main() -> int:
                 "single_thread_value": n1 / t1,
                 "op_evals_per_s": nn / tn * (n_ops / C)}
     print(json.dumps(out))
-    return 0
+    # a mismatch against the oracle on the sample is a failed run, whatever the throughput
+    return 0 if out.get("parity_sample", {}).get("bit_exact", True) else 1
 
 
 if __name__ == "__main__":

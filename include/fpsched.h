@@ -109,7 +109,7 @@ typedef struct {
                                   different devices; same for activations and gradients  */
   const int32_t *dur;          /* [FPSCHED_NKINDS][S] >= 0; row 0 unused                 */
   const int32_t *mem_units;    /* [S] >= 0, activation size of one (stage, micro-batch)  */
-  const int32_t *mem_cap;      /* [D] per-device cap (INT32_MAX = none)                  */
+  const int32_t *mem_cap;      /* [D] >= 0, per-device cap (INT32_MAX = none)            */
 } fpsched_problem_desc;
 
 typedef struct fpsched_problem fpsched_problem; /* opaque, library-owned */

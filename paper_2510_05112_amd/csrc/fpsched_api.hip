@@ -212,6 +212,9 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
       if (desc->mem_units[s] < 0) rc = FPSCHED_EINVAL;
       units_total += (int64_t)desc->mem_units[s] * m;
     }
+    // (a negative cap would round towards zero when divided by the units' common divisor)
+    for (int d = 0; d < D && rc == FPSCHED_OK; ++d)
+      if (desc->mem_cap[d] < 0) rc = FPSCHED_EINVAL;
   }
   // every finish time is at most (number of listed ops) * (largest duration + largest
   // latency); resident memory is at most the sum of all activations
@@ -287,6 +290,8 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
       delete p; return FPSCHED_EHIP;
     }
     p->max_lds = max_lds;
+    // (The dynamic-LDS limit of a kernel is one value per process, not per handle: it is always raised
+    // to the device's maximum, so that handles with different needs never undo each other's setting.)
     // general kernel geometry: finish-time tables and state bytes of whole candidates in LDS
     const int64_t SM = (int64_t)S * m;
     const int64_t per_cand = 4 * (2 * SM + ((SM + 3) >> 2));
@@ -435,13 +440,13 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
     bool ok = hipMemcpy(p->d_ints, I.data(), I.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess;
     if (ok && p->general_ok)
       ok = hipFuncSetAttribute(reinterpret_cast<const void*>(&eval_general_kernel),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, p->lds_bytes) == hipSuccess;
+                               hipFuncAttributeMaxDynamicSharedMemorySize, p->max_lds) == hipSuccess;
     if (ok && p->slots_ok) {
       ok = hipMalloc(&p->d_slot_ints, p->slot_ints.size() * sizeof(int32_t)) == hipSuccess &&
            hipMemcpy(p->d_slot_ints, p->slot_ints.data(), p->slot_ints.size() * sizeof(int32_t),
                      hipMemcpyHostToDevice) == hipSuccess &&
            hipFuncSetAttribute(reinterpret_cast<const void*>(slot_kernel_ptr(p->slot_v, p->slot_deg2, p->stab.n_classes == 1)),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, p->slot_lds_bytes) == hipSuccess;
+                               hipFuncAttributeMaxDynamicSharedMemorySize, p->max_lds) == hipSuccess;
       p->stab.ints = p->d_slot_ints;
       // The sliding pass times the lists without their W items with the evaluation kernel's TIMES
       // form: the same tables, except that a W word is a no-op (any state, no cost, no memory) and a
@@ -470,10 +475,9 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
         const bool up = hipMalloc(&p->d_times_ints, J.size() * sizeof(int32_t)) == hipSuccess &&
                         hipMemcpy(p->d_times_ints, J.data(), J.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess &&
                         hipFuncSetAttribute(reinterpret_cast<const void*>(slot_kernel_of<kSlotTimes>(p->slot_v, p->slot_deg2, p->stab.n_classes == 1)),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, p->slot_lds_bytes + 16) == hipSuccess &&
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, p->max_lds) == hipSuccess &&
                         hipFuncSetAttribute(reinterpret_cast<const void*>(&wslide_place_kernel),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize,
-                                            kNKinds * kMaxChunks * lpc * 16 + (kSlideThreads / 64) * kSlideWaveLdsBytes) == hipSuccess;
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, p->max_lds) == hipSuccess;
         if (up) {
           p->stab_times.ints = p->d_times_ints;
           p->slide_ok = true;
@@ -645,7 +649,7 @@ static int build_combined_tables(fpsched_problem* p) {
   const int32_t lds_bytes = (int32_t)(4ll * (MT.n_shared_ints + (int64_t)geo.waves * geo.wave_ints));
   if (hipMemcpy(p->d_combo_image, J.data(), J.size() * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess ||
       hipFuncSetAttribute(reinterpret_cast<const void*>(slot_kernel_of<kSlotPerMicrobatchLdsLinks>(p->slot_v, p->slot_deg2, MT.n_classes == 1)),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess)
+                          hipFuncAttributeMaxDynamicSharedMemorySize, p->max_lds) != hipSuccess)
     return FPSCHED_EHIP;
   p->stab_combo = MT;
   p->stab_combo.ints = p->d_combo_image;
@@ -713,7 +717,7 @@ int fpsched_problem_set_microbatch_costs(fpsched_problem* p, const int32_t* dur_
     return FPSCHED_EHIP;
   if (p->slots_ok && fits_slots &&
       hipFuncSetAttribute(reinterpret_cast<const void*>(slot_kernel_of<kSlotPerMicrobatch>(p->slot_v, p->slot_deg2, p->stab.n_classes == 1)),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, p->slot_lds_bytes) != hipSuccess)
+                          hipFuncAttributeMaxDynamicSharedMemorySize, p->max_lds) != hipSuccess)
     return FPSCHED_EHIP;
   // Costs of one or two bytes in LDS next to the metadata, if that leaves room for at least six wavefronts
   // per compute unit: [block][chunk < V][lanes per candidate][row of m values], padded to 2 KB.  Kinds
@@ -778,7 +782,7 @@ int fpsched_problem_set_microbatch_costs(fpsched_problem* p, const int32_t* dur_
       p->mb_grid = p->n_cu * geo.groups;
       p->mb_lds_bytes = (int32_t)(4ll * (shared + (int64_t)geo.waves * geo.wave_ints));
       if (hipFuncSetAttribute(reinterpret_cast<const void*>(slot_kernel_of<kSlotPerMicrobatchLds>(p->slot_v, p->slot_deg2, ST.n_classes == 1)),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, p->mb_lds_bytes) != hipSuccess)
+                              hipFuncAttributeMaxDynamicSharedMemorySize, p->max_lds) != hipSuccess)
         return FPSCHED_EHIP;
       in_lds = true;
     }
@@ -906,7 +910,7 @@ int fpsched_problem_set_link_occupancy(fpsched_problem* p, int32_t on) {
   const SlotKernel kernel = slot_kernel_of<kSlotLinks>(p->slot_v, p->slot_deg2, ST.n_classes == 1);
   const int32_t lds_bytes = (int32_t)(4ll * (ST.n_shared_ints + (int64_t)geo.waves * geo.wave_ints));
   if (hipMemcpy(image, J.data(), J.size() * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess ||
-      hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes) != hipSuccess) {
+      hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, p->max_lds) != hipSuccess) {
     (void)hipFree(image);
     return FPSCHED_EHIP;
   }
@@ -935,7 +939,7 @@ int fpsched_problem_set_link_occupancy(fpsched_problem* p, int32_t on) {
     if (hipMalloc(&timg, JT.size() * sizeof(int32_t)) == hipSuccess &&
         hipMemcpy(timg, JT.data(), JT.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess &&
         hipFuncSetAttribute(reinterpret_cast<const void*>(slot_kernel_of<kSlotTimesLinks>(p->slot_v, p->slot_deg2, ST.n_classes == 1)),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes + 16) == hipSuccess) {
+                            hipFuncAttributeMaxDynamicSharedMemorySize, p->max_lds) == hipSuccess) {
       p->d_times_links_image = timg;
       p->stab_times_links = p->stab_links;
       p->stab_times_links.ints = timg;
@@ -997,7 +1001,7 @@ int fpsched_generate(const fpsched_problem* p, const fpsched_actor_policy* d_pol
   const GenKernel kernel = table[V == 1 ? 0 : (V == 2 ? 1 : 2)][deg];
   if (lds_bytes > 64 * 1024 &&
       hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                          (int)lds_bytes) != hipSuccess)
+                          p->max_lds) != hipSuccess)
     return FPSCHED_EHIP;
   unsigned long long* counter = static_cast<unsigned long long*>(d_workspace);
   // segment g starts on set g; the counter hands out the sets after those

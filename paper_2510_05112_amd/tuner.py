@@ -1,5 +1,4 @@
-"""The tuner's grid (paper Section 6) as parameter sets for ``Problem.generate``, and the outer loop
-over pipeline depth, data-parallel width and micro-batch size around it (``tune_parallel``).
+"""The tuner's grid of schedule types (paper Section 6) as parameter sets for ``Problem.generate``.
 
 Host-side glue only: it enumerates schedule types -- (stage placement strategy, forward and
 backward stage traversal priority, computation type traversal priority) -- under the rules the
@@ -130,102 +129,6 @@ def tune(handle, problem, circular: bool, k: int = 8, inflight_options=None, for
     idx, ms = top["idx"].cpu().numpy()[:cnt], top["makespan"].cpu().numpy()[:cnt]
     return [dict(label=labels[int(i) % n] + (" +slide" if i >= n else ""), makespan=int(t), index=int(i) % n,
                  slid=bool(i >= n)) for i, t in zip(idx, ms)]
-
-
-# ---- the outer dimensions of the grid: pipeline depth, data-parallel width, micro-batch size ----------
-
-@dataclass
-class ProblemDesc:
-    """The fields of ``fpsched_problem_desc`` (what ``Problem`` takes)."""
-    n_devices: int
-    n_stages: int
-    n_microbatches: int
-    has_w: int
-    stage_device: np.ndarray
-    edge_src: np.ndarray
-    edge_dst: np.ndarray
-    edge_comm: np.ndarray
-    dur: np.ndarray          # int32 [8][S]
-    mem_units: np.ndarray
-    mem_cap: np.ndarray
-    name: str = ""
-
-
-def parallel_grid(n_gpus: int, n_layers: int, global_batch: int, pp_options=None, mbs_options=None,
-                  max_microbatches: int = 2048):
-    """The (pp, dp, mbs) part of the tuner's parameter space (Section 6): every pipeline depth pp that
-    divides the number of GPUs and does not exceed the number of layers, dp = n_gpus / pp, and every
-    micro-batch size mbs that divides the per-replica batch global_batch / dp; the number of
-    micro-batches of an iteration is then m = global_batch / (dp mbs).  Returns [(pp, dp, mbs, m)]."""
-    out = []
-    for pp in (pp_options or range(1, n_gpus + 1)):
-        if n_gpus % pp or pp > n_layers:
-            continue
-        dp = n_gpus // pp
-        if global_batch % dp:
-            continue
-        per_replica = global_batch // dp
-        for mbs in (mbs_options or range(1, per_replica + 1)):
-            if per_replica % mbs == 0 and per_replica // mbs <= max_microbatches:
-                out.append((pp, dp, mbs, per_replica // mbs))
-    return out
-
-
-def split_layers(n_layers: int, n_stages: int) -> list[int]:
-    """Layers per stage of an even split; the first n_layers mod n_stages stages take one more."""
-    base, extra = divmod(n_layers, n_stages)
-    return [base + (1 if s < extra else 0) for s in range(n_stages)]
-
-
-def chain_problem_from_layers(pp: int, stages_per_device: int, m: int, strategy: str, layer_cost, mbs: int,
-                              comm: int, layer_mem_units: int, mem_cap: int, n_layers: int, has_w: bool = True):
-    """One problem of the outer grid: a chain of pp * stages_per_device stages placed by `strategy`.
-    The cost of a stage is the sum of the costs of its layers (the estimator sketched after Section 6);
-    layer_cost(mbs) -> (forward, backward, weight-gradient) integer cost of ONE layer for a micro-batch of
-    mbs samples (with has_w false the backward cost stands for both parts).  A stage holds
-    layer_mem_units * mbs activation units per layer and micro-batch."""
-    S = pp * stages_per_device
-    layers = np.asarray(split_layers(n_layers, S), np.int64)
-    f, b, w = (int(x) for x in layer_cost(mbs))
-    dur = np.zeros((8, S), np.int32)
-    dur[1] = dur[7] = dur[4] = layers * f      # forward, discarding forward, recomputation
-    dur[2] = layers * b
-    if has_w:
-        dur[3] = layers * w
-    src = np.arange(S - 1, dtype=np.int32)
-    return ProblemDesc(pp, S, m, int(has_w), np.asarray(placement(strategy, pp, S), np.int32), src, src + 1,
-                       np.full(S - 1, comm, np.int32), dur, (layers * layer_mem_units * mbs).astype(np.int32),
-                       np.full(pp, mem_cap, np.int32), name=f"{strategy} pp={pp} mbs={mbs}")
-
-
-def tune_parallel(n_gpus: int, n_layers: int, global_batch: int, layer_cost, comm: int = 1, layer_mem_units: int = 1,
-                  mem_cap: int = NO_LIMIT, strategies=("one-to-one", "circular"), stages_per_device: int = 2,
-                  has_w: bool = True, k: int = 1, device: int = 0, pp_options=None, mbs_options=None,
-                  slide: bool = False):
-    """The whole grid search of Section 6 on the GPU: for every (pp, dp, mbs) of `parallel_grid` and every
-    placement strategy, build the problem (`chain_problem_from_layers`; one-to-one has one stage per
-    device, the others `stages_per_device`), generate and time its schedule types (`tune`) and keep the k
-    best of each; the result is sorted by makespan, which is the time of one iteration of a replica in
-    the units of layer_cost.  Configurations whose every schedule exceeds the memory cap give no entry.
-    Returns a list of dicts (pp, dp, mbs, microbatches, placement, label, makespan, slid)."""
-    from .binding import Problem
-    found = []
-    for pp, dp, mbs, m in parallel_grid(n_gpus, n_layers, global_batch, pp_options, mbs_options):
-        for strategy in strategies:
-            v = 1 if strategy == "one-to-one" else stages_per_device
-            if pp * v > n_layers or (strategy != "one-to-one" and (v < 2 or pp < 2)):
-                continue
-            prob = chain_problem_from_layers(pp, v, m, strategy, layer_cost, mbs, comm, layer_mem_units, mem_cap,
-                                             n_layers, has_w)
-            handle = Problem(prob, stride_for(prob), device=device)
-            try:
-                for best in tune(handle, prob, strategy == "circular", k=k, slide=slide):
-                    found.append(dict(pp=pp, dp=dp, mbs=mbs, microbatches=m, placement=strategy, label=best["label"],
-                                      makespan=best["makespan"], slid=best["slid"]))
-            finally:
-                handle.close()
-    found.sort(key=lambda e: e["makespan"])   # stable: ties keep the order of the enumeration
-    return found
 
 
 def stride_for(problem) -> int:

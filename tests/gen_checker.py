@@ -13,8 +13,19 @@ F, B, W = 0, 1, 2
 KIND = {F: 1, B: 2, W: 3}
 
 
-def simulate(problem, policy, inflight):
-    """policy[D][8], inflight[S] -> (lists[d] = [(kind, chunk, mb)], steps, stuck)."""
+def simulate(problem, policy, inflight, reading="no-idle"):
+    """policy[D][8], inflight[S] -> (lists[d] = [(kind, chunk, mb)], steps, stuck).
+
+    reading: how an interval position behaves when the stage it stands on has nothing eligible.
+      "no-idle"  (the oracle's): the position moves on, in the traversal direction, to the next stage
+                 with an eligible item; the type is skipped only if no stage has one.
+      "strict":  the position moves only after `interval` items (or when every item of the type on that
+                 stage is scheduled); while the stage has nothing eligible the type yields nothing and
+                 the next type is tried.
+      "literal": Algorithm 1 as printed: the position moves only after `interval` items, and whatever
+                 the fetch at the position yields is returned -- a type whose reorder queue is not empty
+                 ends the step function, with an item or without, and later types are not tried.
+    The last two exist to show what they lead to (tests/test_genoracle.py); nothing else uses them."""
     D, S, m = problem.n_devices, problem.n_stages, problem.n_microbatches
     dev = [int(x) for x in problem.stage_device]
     preds = {s: [] for s in range(S)}
@@ -59,7 +70,21 @@ def simulate(problem, policy, inflight):
                 direction = policy[d][3] if t == F else policy[d][5] if t == B else 0
                 interval = policy[d][4] if t == F else policy[d][6] if t == B else 0
                 n = len(stages[d])
-                if interval > 0:
+                if interval > 0 and reading != "no-idle":
+                    p = pos[d][t]
+                    step = 1 if direction == 0 else -1
+                    if stepped[d][t] == interval or (reading == "strict" and snap[t][stages[d][p]] == m):
+                        for _ in range(n):   # on to the next stage that still has items of the type
+                            p = (p + step) % n
+                            if snap[t][stages[d][p]] < m:
+                                break
+                        pos[d][t], stepped[d][t] = p, 0
+                    if ok[stages[d][p]]:
+                        stepped[d][t] += 1
+                        pick = (t, stages[d][p])
+                    elif reading == "literal":
+                        break                 # return whatever the fetch gave: a nop
+                elif interval > 0:
                     p = pos[d][t]
                     if not any(ok.values()):
                         continue

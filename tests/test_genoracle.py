@@ -11,7 +11,7 @@ import pytest
 import oracle
 from gen_checker import simulate
 from helpers import two_tower_problem
-from workloads.problem import chain_problem, gpipe_lists, one_f_one_b_lists, pack_lists
+from workloads.problem import chain_problem, gpipe_lists, interleaved_1f1b_lists, one_f_one_b_lists, pack_lists
 
 NO_LIMIT = 2**31 - 1
 
@@ -65,6 +65,89 @@ def test_the_papers_interleaved_setting_reaches_the_interleaved_1f1b_length(p, v
     # and it holds fewer activations than running all forward passes first
     gp = oracle.generate(prob, uniform_policy(1, p, oracle.CTTP_FWD_FIRST), np.full((1, p * v), NO_LIMIT, np.int32), st)
     assert ev["peak"][0].max() < oracle.evaluate(prob, gp["words"])["peak"][0].max()
+
+
+PAPER_INTERLEAVED = dict(cttp=oracle.CTTP_INTERLEAVED, fdir=0, bdir=1)   # intervals = p, set per shape
+
+
+@pytest.mark.parametrize("p", [2, 3, 4, 5, 6, 8])
+@pytest.mark.parametrize("v", [2, 3, 4])
+def test_the_papers_interleaved_setting_reproduces_the_published_interleaved_1f1b_order(p, v):
+    # An external pin of the interval traversal (Section 5.2, "Stage Traversal Priority") and of the
+    # interleaved type priority: on the circular placement the setting of the paper's example --
+    # interleaved, forward (breadth-first, p), backward (depth-first, p) -- must give interleaved 1F1B
+    # (Section 2.1), whose order is written out from its published definition in
+    # workloads.problem.interleaved_1f1b_lists (and is itself pinned below).  One round of p
+    # micro-batches: item by item the same op words on every device.
+    m = p
+    prob = chain_problem(p, m, v=v, f=1, b=1, comm=0)
+    st = stride_for(prob)
+    pol = uniform_policy(1, p, fint=p, bint=p, **PAPER_INTERLEAVED)
+    out = oracle.generate(prob, pol, np.full((1, p * v), NO_LIMIT, np.int32), st)
+    assert np.array_equal(out["words"][0], pack_lists(interleaved_1f1b_lists(p, v, m), st))
+    assert out["steps"][0] == 2 * v * m + 2 * (p - 1) and out["status"][0] == 0
+
+
+@pytest.mark.parametrize("p,v,m", [(4, 2, 4), (4, 2, 8), (4, 2, 16), (3, 2, 9), (8, 2, 16), (4, 4, 8), (5, 3, 10)])
+def test_the_published_interleaved_order_and_where_the_scheduler_leaves_it(p, v, m):
+    # The published order, timed by the evaluation oracle with unit costs, has the closed-form length
+    # 2 v m + 2 (p - 1) and holds at most its warm-up depth in activations (this pins the order builder).
+    prob = chain_problem(p, m, v=v, f=1, b=1, comm=0)
+    st = stride_for(prob)
+    lists = interleaved_1f1b_lists(p, v, m)
+    ev = oracle.evaluate(prob, pack_lists(lists, st)[None])
+    assert ev["flags"][0] == 0 and ev["makespan"][0] == 2 * v * m + 2 * (p - 1)
+    assert list(ev["peak"][0]) == [min(2 * (p - d - 1) + (v - 1) * p + 1, m * v) for d in range(p)]
+    # With more than one round of micro-batches the fixed order lets a device wait for a forward item
+    # of its next chunk where the paper's scheduler, which idles only when nothing at all can be
+    # scheduled (Section 5.2, Step 2), takes another item: the orders then differ, the lengths do not.
+    pol = uniform_policy(1, p, fint=p, bint=p, **PAPER_INTERLEAVED)
+    out = oracle.generate(prob, pol, np.full((1, p * v), NO_LIMIT, np.int32), st)
+    assert out["steps"][0] == ev["makespan"][0]
+    assert np.array_equal(out["words"][0], pack_lists(lists, st)) == (m == p)
+
+
+def test_what_the_other_readings_of_the_interval_rule_lead_to():
+    # Algorithm 1 as printed moves the position only when `interval` items were scheduled and returns
+    # whatever the fetch at the position gives; read a little more kindly, a position whose stage has
+    # nothing to offer lets the next type try.  Both readings (modelled in gen_checker.simulate) keep an
+    # actor on a stage that cannot move, so a valid problem stops dead:
+    prob = chain_problem(2, 2, v=2, f=1, b=1, comm=0)
+    none = [NO_LIMIT] * 4
+    # (a) a setting of the tuner's own grid (Section 6): forward traversal (depth-first, interval) on the
+    # circular placement.  The position starts on the actor's last stage, whose forward items wait for
+    # the first stage's: no item is ever scheduled.
+    pol = uniform_policy(1, 2, oracle.CTTP_BWD_FIRST, fdir=1, fint=2)[0].tolist()
+    for reading in ("strict", "literal"):
+        lists, steps, stuck = simulate(prob, pol, none, reading)
+        assert stuck and steps == 0 and not any(lists)
+    lists, steps, stuck = simulate(prob, pol, none)
+    assert not stuck and sum(len(x) for x in lists) == 2 * 4 * 2
+    out = oracle.generate(prob, uniform_policy(1, 2, oracle.CTTP_BWD_FIRST, fdir=1, fint=2),
+                          np.full((1, 4), NO_LIMIT, np.int32), 16)
+    assert out["status"][0] == 0 and np.array_equal(out["words"][0], pack_lists(lists, 16))
+    # (b) an interval of two with one micro-batch in flight on the first stage (the case of the next
+    # test): after F(0, 0) the position waits on stage 0 for a second item that the limit forbids until
+    # the first has come back, which needs the actor's other stage.
+    prob = chain_problem(2, 4, v=2, f=1, b=1, comm=0)
+    pol = uniform_policy(1, 2, oracle.CTTP_BWD_FIRST, fdir=0, fint=2)[0].tolist()
+    for reading in ("strict", "literal"):
+        lists, steps, stuck = simulate(prob, pol, [1, NO_LIMIT, NO_LIMIT, NO_LIMIT], reading)
+        assert stuck and steps == 2 and [len(x) for x in lists] == [1, 1]
+    # (c) on random interval policies without any limit more than half of the processes get stuck
+    rng = np.random.default_rng(3)
+    pol, inf = random_policies(rng, 60, prob, rng.random(60) < 0.5)
+    with_interval = [i for i in range(60) if pol[i][:, 4].any() or pol[i][:, 6].any()]
+    stuck = {r: sum(simulate(prob, pol[i].tolist(), [NO_LIMIT] * 4, r)[2] for i in with_interval)
+             for r in ("no-idle", "strict", "literal")}
+    assert stuck["no-idle"] == 0 and stuck["strict"] > len(with_interval) // 3 and stuck["literal"] >= stuck["strict"]
+    # (d) where the paper's example setting is concerned the three readings cannot be told apart: one
+    # round of micro-batches gives the published order under each of them
+    prob = chain_problem(4, 4, v=2, f=1, b=1, comm=0)
+    pol = uniform_policy(1, 4, fint=4, bint=4, **PAPER_INTERLEAVED)[0].tolist()
+    for reading in ("no-idle", "strict", "literal"):
+        lists, steps, stuck = simulate(prob, pol, [NO_LIMIT] * 8, reading)
+        assert not stuck and lists == interleaved_1f1b_lists(4, 2, 4)
 
 
 def random_policies(rng, n, problem, per_actor):

@@ -1,6 +1,7 @@
 """GPU parity at the benchmark's full batch sizes, in the launch configuration bench.py times:
-every candidate of every configuration against the oracle, plus properties that hold at any size
-(the generator and the sliding pass: sampled candidates, their oracles being slower)."""
+every candidate of every configuration against the oracle under each cost model, every candidate of
+the sliding pass, 8,192 parameter sets of the generator (its oracle does some 300 per second), plus
+properties that hold at any size."""
 import numpy as np
 import pytest
 import torch
@@ -68,31 +69,28 @@ def test_full_batch_every_candidate_against_oracle(index):
     got = list(zip(front["idx"].cpu().numpy()[:cnt], front["makespan"].cpu().numpy()[:cnt],
                    front["peak"].cpu().numpy()[:cnt]))
     assert [tuple(int(x) for x in e) for e in got] == [tuple(int(x) for x in e) for e in expect[:cnt]]
-    # the same batch with costs per micro-batch (the launch `bench.py --mb-costs` times): every candidate
-    if index in (2, 4, 5):
+    # the same batch under the other cost models (the launches `bench.py --mb-costs`, `--links` and both
+    # together time): every candidate
+    if index != 1:
         table = workloads.microbatch_costs(prob)
-        h.set_microbatch_costs(table)
-        res = h.evaluate(ops, workspace=ws)
-        top = h.topk(res, spec.top_k, workspace=ws)
-        torch.cuda.synchronize()
-        ref = oracle.evaluate(prob, words, threads=16, dur_mb=table)
-        for name in ("flags", "makespan", "idle", "peak"):
-            assert np.array_equal(res[name].cpu().numpy(), ref[name]), f"costs per micro-batch: {name}"
-        r_idx, r_ms, r_cnt = oracle.topk(ref["makespan"], ref["flags"], spec.top_k)
-        assert int(top["count"].item()) == r_cnt and np.array_equal(top["idx"].cpu().numpy(), r_idx)
-        assert np.array_equal(top["makespan"].cpu().numpy(), r_ms)
-        h.set_microbatch_costs(None)
-        # ... and with links that carry one value at a time (the launch `bench.py --links` times)
-        h.set_link_occupancy(True)
-        res = h.evaluate(ops, workspace=ws)
-        torch.cuda.synchronize()
-        ref = oracle.evaluate(prob, words, threads=16, links=True)
-        for name in ("flags", "makespan", "idle", "peak"):
-            assert np.array_equal(res[name].cpu().numpy(), ref[name]), f"link occupancy: {name}"
+        for dur_mb, links, what in ((table, False, "costs per micro-batch"), (None, True, "link occupancy"),
+                                    (table, True, "both variants")):
+            h.set_microbatch_costs(dur_mb)
+            h.set_link_occupancy(links)
+            res = h.evaluate(ops, workspace=ws)
+            top = h.topk(res, spec.top_k, workspace=ws)
+            torch.cuda.synchronize()
+            ref = oracle.evaluate(prob, words, threads=16, dur_mb=dur_mb, links=links)
+            for name in ("flags", "makespan", "idle", "peak"):
+                assert np.array_equal(res[name].cpu().numpy(), ref[name]), f"{what}: {name}"
+            r_idx, r_ms, r_cnt = oracle.topk(ref["makespan"], ref["flags"], spec.top_k)
+            assert int(top["count"].item()) == r_cnt and np.array_equal(top["idx"].cpu().numpy(), r_idx), what
+            assert np.array_equal(top["makespan"].cpu().numpy(), r_ms), what
+            print(f"cfg{index}: {what} ok", flush=True)
     h.close()
 
 
-def test_generator_full_batch_sampled_against_oracle():
+def test_generator_full_batch_8192_sets_against_oracle():
     # the generator at the size and launch configuration of `bench.py --mode generate`
     spec = workloads.config(4)
     prob = spec.problem
@@ -105,11 +103,14 @@ def test_generator_full_batch_sampled_against_oracle():
     steps = out["steps"].cpu().numpy()
     status = out["status"].cpu().numpy()
     rng = np.random.default_rng(4)
-    pick = np.sort(np.concatenate([rng.choice(n, 254, replace=False), [0, n - 1]]))
-    ref = oracle.generate(prob, pol[pick], inf[pick], stride, threads=16)
-    sel = torch.from_numpy(pick).cuda()
-    assert np.array_equal(out["ops"][sel].cpu().numpy().view(np.uint16), ref["words"])
-    assert np.array_equal(steps[pick], ref["steps"]) and np.array_equal(status[pick], ref["status"])
+    pick = np.unique(np.concatenate([rng.choice(n, 8190, replace=False), [0, n - 1]]))
+    for lo in range(0, len(pick), 2048):   # in pieces: the run prints its progress
+        part = pick[lo:lo + 2048]
+        ref = oracle.generate(prob, pol[part], inf[part], stride, threads=16)
+        sel = torch.from_numpy(part).cuda()
+        assert np.array_equal(out["ops"][sel].cpu().numpy().view(np.uint16), ref["words"])
+        assert np.array_equal(steps[part], ref["steps"]) and np.array_equal(status[part], ref["status"])
+        print(f"generator: {lo + len(part)} of {len(pick)} sets ok", flush=True)
     # properties at full size: every process completes, every actor schedules each of its items once
     assert not status.any()
     per_dev = 2 * prob.n_microbatches * 3
@@ -123,27 +124,31 @@ def test_generator_full_batch_sampled_against_oracle():
     h.close()
 
 
-def test_wslide_full_batch_sampled_against_oracle():
-    """The sliding pass on configuration 4's full batch, in the launch configuration bench.py times."""
+@pytest.mark.parametrize("links", [False, True])
+def test_wslide_full_batch_every_candidate_against_oracle(links):
+    """The sliding pass on configuration 4's full batch, in the launch configuration bench.py times, under
+    both readings of a transfer (pure latency; links that carry one value at a time)."""
     spec = workloads.config(4)
     prob = spec.problem
     words = workloads.generate(spec, threads=16)
     C, D, stride = words.shape
     print(f"wslide cfg4: {C} candidates", flush=True)
     h = fp.Problem(prob, stride, device=0)
+    h.set_link_occupancy(links)
     ops = torch.empty((C, D, stride), dtype=torch.int16, device="cuda")
     step = max(1, (256 << 20) // (D * stride * 2))
     for lo in range(0, C, step):
         ops[lo:lo + step].copy_(torch.from_numpy(words[lo:lo + step].view(np.int16)))
     out = h.wslide(ops, stride)
     torch.cuda.synchronize()
-    rng = np.random.default_rng(4)
-    pick = np.sort(np.concatenate([rng.choice(C, 800, replace=False), [0, C - 1]]))
-    ref = oracle.wslide(prob, words[pick], stride, threads=16)
-    sel = torch.from_numpy(pick).cuda()
-    assert np.array_equal(out["ops"][sel].cpu().numpy().view(np.uint16), ref["ops"])
-    for name in ("makespan", "idle", "peak", "flags"):
-        assert np.array_equal(out[name][sel].cpu().numpy(), ref[name]), name
+    # every candidate against the oracle, 8,192 at a time (new lists and their evaluation)
+    for lo in range(0, C, 8192):
+        ref = oracle.wslide(prob, words[lo:lo + 8192], stride, threads=16, links=links)
+        assert np.array_equal(out["ops"][lo:lo + 8192].cpu().numpy().view(np.uint16), ref["ops"]), lo
+        for name in ("makespan", "idle", "peak", "flags"):
+            assert np.array_equal(out[name][lo:lo + 8192].cpu().numpy(), ref[name]), (name, lo)
+        print(f"wslide links={links}: {min(C, lo + 8192)} of {C} candidates ok", flush=True)
+    pick = np.arange(0, C, 1311)
     # at full size: the new lists, timed by the evaluation kernel, give the reported results
     again = h.evaluate(out["ops"])
     torch.cuda.synchronize()

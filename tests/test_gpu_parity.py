@@ -4,7 +4,9 @@ import pytest
 
 import oracle
 import workloads
-from gpu_common import check_batch, gpu_evaluate
+import paper_2510_05112_amd as fp
+import torch
+from gpu_common import assert_same, check_batch, gpu_evaluate
 from helpers import batch_from_lists, dag_problem, perturb, random_valid_lists, two_tower_problem
 from workloads.problem import (B, F, FD, L, O, R, W, chain_problem, gpipe_lists, make_problem,
                                one_f_one_b_lists, pack_lists, pack_word)
@@ -340,6 +342,29 @@ def test_generate_slide_and_topk_replayed_from_a_hip_graph(links):
         idx, ms, cnt = oracle.topk(ref["makespan"], ref["flags"], k)
         assert int(top["count"].item()) == cnt and np.array_equal(top["idx"].cpu().numpy(), idx)
     h.close()
+
+
+def test_two_live_handles_with_different_lds_needs():
+    # The dynamic-LDS limit of a kernel is one value per process: a handle created later with a smaller
+    # need must not take the room of an earlier one (both problems run the same kernel instantiation).
+    big, small = workloads.config(4, 64), workloads.config(2, 64)
+    w_big, w_small = workloads.generate(big, threads=4), workloads.generate(small, threads=4)
+    h_big = fp.Problem(big.problem, big.stride, device=0)
+    h_small = fp.Problem(small.problem, small.stride, device=0)       # created second, needs less LDS
+    assert h_big.info()["lds_bytes_per_wave"] > h_small.info()["lds_bytes_per_wave"]
+    for h, spec, words in ((h_big, big, w_big), (h_small, small, w_small), (h_big, big, w_big)):
+        for links in (False, True):
+            h.set_link_occupancy(links)
+            res = h.evaluate(torch.from_numpy(words.view(np.int16)).cuda())
+            torch.cuda.synchronize()
+            ref = oracle.evaluate(spec.problem, words, threads=4, links=links)
+            assert_same({n: v.cpu().numpy() for n, v in res.items()}, ref, f"{spec.problem.name} links={links}")
+    out = h_big.wslide(torch.from_numpy(w_big.view(np.int16)).cuda(), big.stride)   # links still on
+    torch.cuda.synchronize()
+    ref = oracle.wslide(big.problem, w_big, big.stride, threads=4, links=True)
+    assert np.array_equal(out["ops"].cpu().numpy().view(np.uint16), ref["ops"])
+    h_big.close()
+    h_small.close()
 
 
 def test_largest_stage_counts():

@@ -97,6 +97,12 @@ def test_host_only_handle_and_errors():
     assert e.value.code == -4
     with pytest.raises(fp.FpschedError):
         fp.Problem(chain_problem(4, 8), 60, device=None)   # stride not a multiple of 8
+    neg = chain_problem(4, 8)
+    neg.mem_cap = np.asarray(neg.mem_cap).copy()
+    neg.mem_cap[2] = -1
+    with pytest.raises(fp.FpschedError) as e:
+        fp.Problem(neg, 64, device=None)                   # a negative memory cap
+    assert e.value.code == -1
     five = chain_problem(1, 2, v=5)
     with pytest.raises(fp.FpschedError):
         fp.Problem(five, 64, device=None)                  # more than 4 stages on a device

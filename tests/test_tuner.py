@@ -145,45 +145,3 @@ def test_gpu_search_under_the_other_cost_models_matches_the_oracles(variant):
         assert [(b["index"], b["slid"], b["makespan"]) for b in best] == [(int(i) % n, bool(i >= n), int(t)) for i, t in zip(idx[:cnt], top_ms[:cnt])]
         assert any(b["slid"] for b in best)
     h.close()
-
-
-def layer_cost(mbs):
-    return 2 * mbs + 1, 4 * mbs + 1, 2 * mbs
-
-
-def test_outer_grid_and_stage_costs():
-    g = tuner.parallel_grid(8, 16, 32)
-    # every pp that divides the GPUs, dp = GPUs / pp, every mbs that divides the per-replica batch
-    assert sorted({(pp, dp) for pp, dp, _, _ in g}) == [(1, 8), (2, 4), (4, 2), (8, 1)]
-    assert all(pp * dp == 8 and dp * mbs * m == 32 for pp, dp, mbs, m in g) and len(g) == 3 + 4 + 5 + 6
-    assert tuner.parallel_grid(8, 3, 32, mbs_options=[2]) == [(1, 8, 2, 2), (2, 4, 2, 4)]   # pp <= layers
-    # a data-parallel width that does not divide the batch is left out (6 GPUs, batch 32: dp 6 and 3)
-    assert sorted({dp for _, dp, _, _ in tuner.parallel_grid(6, 16, 32)}) == [1, 2]
-    assert tuner.split_layers(16, 6) == [3, 3, 3, 3, 2, 2] and sum(tuner.split_layers(61, 8)) == 61
-    prob = tuner.chain_problem_from_layers(4, 2, 8, "circular", layer_cost, 2, 3, 5, 100, 18)
-    layers = np.asarray(tuner.split_layers(18, 8))
-    assert prob.n_stages == 8 and prob.n_devices == 4 and prob.n_microbatches == 8
-    assert np.array_equal(prob.dur[F], layers * 5) and np.array_equal(prob.dur[B], layers * 9)   # sums over a stage's layers
-    assert np.array_equal(prob.dur[W], layers * 4) and np.array_equal(prob.dur[FD], prob.dur[F])
-    assert np.array_equal(prob.mem_units, layers * 5 * 2) and list(prob.stage_device) == [0, 1, 2, 3, 0, 1, 2, 3]
-    assert np.array_equal(prob.edge_comm, np.full(7, 3))
-
-
-@pytest.mark.gpu
-def test_gpu_search_over_pipeline_depth_and_micro_batch_size_matches_the_oracles():
-    found = tuner.tune_parallel(8, 16, 16, layer_cost, comm=2, mem_cap=40, pp_options=[2, 4, 8], mbs_options=[1, 2, 4])
-    assert found and all(a["makespan"] <= b["makespan"] for a, b in zip(found, found[1:]))
-    expect = []
-    for pp, dp, mbs, m in tuner.parallel_grid(8, 16, 16, [2, 4, 8], [1, 2, 4]):
-        for strategy in ("one-to-one", "circular"):
-            v = 1 if strategy == "one-to-one" else 2
-            prob = tuner.chain_problem_from_layers(pp, v, m, strategy, layer_cost, mbs, 2, 1, 40, 16)
-            labels, pol, inf = tuner.grid(prob, strategy == "circular")
-            words = oracle.generate(prob, pol, inf, tuner.stride_for(prob))["words"]
-            ref = oracle.evaluate(prob, words)
-            idx, ms, cnt = oracle.topk(ref["makespan"], ref["flags"], 1)
-            if cnt:
-                expect.append((int(ms[0]), pp, dp, mbs, strategy, labels[idx[0]]))
-    assert len(expect) > 6
-    got = [(e["makespan"], e["pp"], e["dp"], e["mbs"], e["placement"], e["label"]) for e in found]
-    assert sorted(got) == sorted(expect) and got[0][0] == min(e[0] for e in expect)

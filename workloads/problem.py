@@ -135,3 +135,29 @@ def one_f_one_b_lists(p, m):
             nb += 1
         out.append(ops)
     return out
+
+
+def interleaved_1f1b_lists(p, v, m):
+    """Interleaved 1F1B (paper Section 2.1: the circular placement, stage s on device s mod p), as the
+    schedule is defined where it was published (Narayanan et al., SC'21): the m * v forward items of a
+    device are numbered k = 0, 1, ... in groups of p micro-batches per chunk, chunks ascending (item k =
+    chunk (k div p) mod v, micro-batch (k div pv) p + k mod p); the backward items likewise with the
+    chunks descending; device d runs 2 (p - d - 1) + (v - 1) p forward items to warm up, then
+    alternates one forward and one backward item, then drains the backward items.  m must be a
+    multiple of p.  Items are (kind, chunk, micro-batch)."""
+    assert m % p == 0 and v >= 1
+    total = m * v
+
+    def item(k, forward):
+        c = (k // p) % v
+        return (F if forward else B, c if forward else v - 1 - c, (k // (p * v)) * p + k % p)
+
+    out = []
+    for d in range(p):
+        warm = min(2 * (p - d - 1) + (v - 1) * p, total)
+        ops = [item(k, True) for k in range(warm)]
+        for i in range(total - warm):
+            ops += [item(warm + i, True), item(i, False)]
+        ops += [item(i, False) for i in range(total - warm, total)]
+        out.append(ops)
+    return out
