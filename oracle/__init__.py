@@ -25,6 +25,8 @@ _GEN_SRC = os.path.join(_HERE, "fpgenoracle.c")
 _GEN_LIB = os.path.join(_HERE, "libfpgenoracle.so")
 _SLIDE_SRC = os.path.join(_HERE, "fpslideoracle.c")
 _SLIDE_LIB = os.path.join(_HERE, "libfpslideoracle.so")
+_SYNC_SRC = os.path.join(_HERE, "fpsyncoracle.c")
+_SYNC_LIB = os.path.join(_HERE, "libfpsyncoracle.so")
 
 FLAG_DEADLOCK = 1
 FLAG_INCOMPLETE = 2
@@ -45,6 +47,7 @@ def build(force: bool = False) -> str:
     """Compile the oracle's C files with gcc (plain C, no GPU toolchain)."""
     _compile(_GEN_SRC, _GEN_LIB, force)
     _compile(_SLIDE_SRC, _SLIDE_LIB, force)
+    _compile(_SYNC_SRC, _SYNC_LIB, force)
     return _compile(_SRC, _LIB, force)
 
 
@@ -395,3 +398,89 @@ def generate(problem, policy, inflight, stride: int, threads: int = 1, diagnosti
     if diagnostics:
         out["prefix_violations"] = viol
     return out
+
+
+# ---- synchronisation stages and dependency pairs (fpsyncoracle.c) ---------------------------------
+
+class _CSyncProblem(ctypes.Structure):
+    _fields_ = _CProblem._fields_ + [("group", ctypes.c_void_p), ("n_pairs", ctypes.c_int32),
+                                      ("pairs", ctypes.c_void_p)]
+
+
+_sync_lib = None
+
+
+def _load_sync():
+    global _sync_lib
+    if _sync_lib is None:
+        build()
+        _sync_lib = ctypes.CDLL(_SYNC_LIB)
+        _sync_lib.fpsync_eval_one.restype = ctypes.c_int
+        _sync_lib.fpsync_evaluate.restype = ctypes.c_int
+    return _sync_lib
+
+
+def _sync_problem(problem, group, pairs):
+    mp = _Marshalled(problem)
+    grp = _i32(np.ones(mp.S, np.int32) if group is None else group)
+    prs = _i32(np.zeros((0, 5), np.int32) if pairs is None else pairs).reshape(-1, 5)
+    assert grp.shape == (mp.S,)
+    a = mp.arrays
+    c = _CSyncProblem(mp.D, mp.S, mp.m, int(problem.has_w), a["stage_device"].ctypes.data, len(a["edge_src"]),
+                      a["edge_src"].ctypes.data, a["edge_dst"].ctypes.data, a["edge_comm"].ctypes.data,
+                      a["dur"].ctypes.data, a["mem_units"].ctypes.data, a["mem_cap"].ctypes.data,
+                      grp.ctypes.data, len(prs), prs.ctypes.data)
+    return mp, c, (grp, prs)
+
+
+def evaluate_sync(problem, words, group=None, pairs=None, threads: int = 1):
+    """Evaluate ``words[C][D][stride]`` under the model with synchronisation stages and dependency pairs
+    (fpsyncoracle.c): ``group[S]`` micro-batches per item of each stage (None = 1 everywhere), ``pairs``
+    rows (kind_from, stage_from, kind_to, stage_to, latency).  Returns the dict of ``evaluate``."""
+    lib = _load_sync()
+    mp, c, keep = _sync_problem(problem, group, pairs)
+    w = np.ascontiguousarray(np.asarray(words, dtype=np.uint16))
+    assert w.ndim == 3 and w.shape[1] == mp.D, w.shape
+    C, _, stride = w.shape
+    out = dict(makespan=np.empty(C, np.int64), idle=np.empty((C, mp.D), np.int64),
+               peak=np.empty((C, mp.D), np.int32), flags=np.empty(C, np.uint8))
+
+    def run(lo, hi):
+        if hi <= lo:
+            return 0
+        return lib.fpsync_evaluate(ctypes.byref(c), ctypes.c_void_p(w[lo:hi].ctypes.data), ctypes.c_int64(hi - lo),
+                                   ctypes.c_int32(stride), ctypes.c_void_p(out["makespan"][lo:hi].ctypes.data),
+                                   ctypes.c_void_p(out["idle"][lo:hi].ctypes.data),
+                                   ctypes.c_void_p(out["peak"][lo:hi].ctypes.data),
+                                   ctypes.c_void_p(out["flags"][lo:hi].ctypes.data))
+
+    threads = max(1, min(int(threads), C if C else 1))
+    if threads == 1:
+        rcs = [run(0, C)]
+    else:
+        n_slices = min(C, threads * 8)
+        bounds = np.linspace(0, C, n_slices + 1).astype(np.int64)
+        with ThreadPoolExecutor(threads) as ex:
+            rcs = list(ex.map(lambda i: run(int(bounds[i]), int(bounds[i + 1])), range(n_slices)))
+    if any(rcs):
+        raise ValueError("fpsyncoracle: invalid problem description")
+    return out
+
+
+def evaluate_sync_trace(problem, words_one, group=None, pairs=None):
+    """One candidate ``words[D][stride]`` under the same model; also every op's start and finish."""
+    lib = _load_sync()
+    mp, c, keep = _sync_problem(problem, group, pairs)
+    w = np.ascontiguousarray(np.asarray(words_one, dtype=np.uint16))
+    assert w.ndim == 2 and w.shape[0] == mp.D
+    stride = w.shape[1]
+    ms, fl = np.empty(1, np.int64), np.empty(1, np.uint8)
+    idle, peak = np.empty(mp.D, np.int64), np.empty(mp.D, np.int32)
+    st, fi = np.empty((mp.D, stride), np.int64), np.empty((mp.D, stride), np.int64)
+    rc = lib.fpsync_eval_one(ctypes.byref(c), ctypes.c_void_p(w.ctypes.data), ctypes.c_int32(stride),
+                             ctypes.c_void_p(ms.ctypes.data), ctypes.c_void_p(idle.ctypes.data),
+                             ctypes.c_void_p(peak.ctypes.data), ctypes.c_void_p(fl.ctypes.data),
+                             ctypes.c_void_p(st.ctypes.data), ctypes.c_void_p(fi.ctypes.data))
+    if rc:
+        raise ValueError("fpsyncoracle: invalid problem description")
+    return dict(makespan=int(ms[0]), idle=idle, peak=peak, flags=int(fl[0]), start=st, finish=fi)

@@ -98,3 +98,55 @@ def batch_from_lists(list_of_lists, stride=None):
     if stride is None:
         stride = max(8, -(-(longest + 1) // 8) * 8)
     return np.stack([pack_lists(lists, stride) for lists in list_of_lists])
+
+
+def random_sync_lists(problem, group, pairs, rng, p_recompute=0.0, p_offload=0.0):
+    """A random deadlock-free candidate of a problem with synchronisation stages (``group[S]``
+    micro-batches per item) and dependency pairs: one op at a time, drawn from the ops all of whose
+    prerequisites (stage DAG and pairs, over the overlapping items) are already listed.  Returns None
+    if the pairs leave nothing to draw before everything is listed (a cyclic set of pairs)."""
+    S, m = problem.n_stages, problem.n_microbatches
+    group = [int(x) for x in group]
+    n_items = [-(-m // n) for n in group]
+    dev = [int(x) for x in problem.stage_device]
+    chunk = [int(x) for x in problem.stage_chunk()]
+    cls = {F: "f", FD: "f", B: "b", W: "w"}
+    waits = {}
+    for a, b in zip(problem.edge_src, problem.edge_dst):
+        for kind in (F, FD):
+            waits.setdefault((kind, int(b)), []).append(("f", int(a)))
+        waits.setdefault((B, int(a)), []).append(("b", int(b)))
+    for k1, s1, k2, s2, _lat in pairs:
+        for kind in ((F, FD) if int(k2) == F else (int(k2),)):
+            waits.setdefault((kind, int(s2)), []).append((cls[int(k1)], int(s1)))
+    chains = {}
+    for s in range(S):
+        for g in range(n_items[s]):
+            ch = [FD, R] if rng.random() < p_recompute else [F]
+            if rng.random() < p_offload:
+                ch += [O, L]
+            ch.append(B)
+            if problem.has_w:
+                ch.append(W)
+            chains[(s, g)] = ch
+    listed = set()
+    lists = [[] for _ in range(problem.n_devices)]
+    remaining = sum(len(c) for c in chains.values())
+    while remaining:
+        ready = []
+        for (s, g), ch in chains.items():
+            if not ch:
+                continue
+            lo, hi = g * group[s], min(m, (g + 1) * group[s]) - 1
+            if all((c, a, ga) in listed for c, a in waits.get((ch[0], s), [])
+                   for ga in range(lo // group[a], hi // group[a] + 1)):
+                ready.append((s, g))
+        if not ready:
+            return None
+        s, g = ready[rng.integers(len(ready))]
+        k = chains[(s, g)].pop(0)
+        if k in cls:
+            listed.add((cls[k], s, g))
+        lists[dev[s]].append((k, chunk[s], g))
+        remaining -= 1
+    return lists
