@@ -91,6 +91,8 @@ enum {
 #define FPSCHED_EOVERFLOW (-4) /* the problem's time bound does not fit the kernel's int32  */
 #define FPSCHED_ENODEV (-5)    /* host-only handle used for a device call                   */
 #define FPSCHED_EUNSUPPORTED (-6) /* problem too large for the on-chip tables               */
+#define FPSCHED_ESCRATCH (-7)  /* batch too large for the static scratch of
+                                  fpsched_evaluate_topk_static                              */
 
 /* ---- problem description (Section 4.1 data model: Stage / StageSet = the DAG
  * of stages, Actor = device; placement per Section 2.1; costs per (kind, stage)
@@ -198,6 +200,26 @@ int fpsched_evaluate(const fpsched_problem *p, const uint16_t *d_ops, int64_t n_
 int fpsched_topk(const fpsched_problem *p, fpsched_results in, int64_t n_cand, int32_t k,
                  int64_t *d_idx, int64_t *d_makespan, int32_t *d_count, void *d_workspace,
                  size_t workspace_bytes, void *hip_stream);
+
+/* For callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  fpsched_evaluate followed by
+ * fpsched_topk on the same results, with the work counter and the top-k key buffers in a
+ * static array of FPSCHED_STATIC_SCRATCH_BYTES that every GPU the library runs on holds from
+ * the first fpsched_problem_create on that GPU until the process ends; the call itself
+ * allocates nothing, on the host or on the device.  Arguments, results and error codes are
+ * those of the two calls; in addition FPSCHED_ESCRATCH if fpsched_workspace_bytes(p, n_cand, k)
+ * exceeds the array (2 MiB: room for 172,032 candidates at k = 1024, 1.4 million at k = 128,
+ * 16 million at k <= 16), in which case nothing is enqueued.  All calls on one GPU share that GPU's array:
+ * two calls that overlap in time on one GPU (different streams, or different host threads
+ * without ordering between their streams) race; calls on one stream, or ordered by events,
+ * are safe, and so are calls on different GPUs.  Nothing of an earlier call's contents is read.
+ * Asynchronous on hip_stream. */
+#define FPSCHED_STATIC_SCRATCH_BYTES (2u << 20)
+size_t fpsched_static_scratch_bytes(void);
+int fpsched_evaluate_topk_static(const fpsched_problem *p, const uint16_t *d_ops, int64_t n_cand,
+                                 int32_t stride_words, fpsched_results out, int32_t k,
+                                 int64_t *d_idx, int64_t *d_makespan, int32_t *d_count,
+                                 void *hip_stream);
 
 /* Richer ranking of evaluated candidates: the k best by a two-part key, ties by index.
  * The paper ranks by bubble ratio (Section 7.1) and treats the memory footprint as the

@@ -73,6 +73,10 @@ def load_library():
         lib.fpsched_evaluate.argtypes = [vp, vp, i64, i32, _Results, vp, ctypes.c_size_t, vp]
         lib.fpsched_topk.restype = ctypes.c_int
         lib.fpsched_topk.argtypes = [vp, _Results, i64, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.fpsched_static_scratch_bytes.restype = ctypes.c_size_t
+        lib.fpsched_static_scratch_bytes.argtypes = []
+        lib.fpsched_evaluate_topk_static.restype = ctypes.c_int
+        lib.fpsched_evaluate_topk_static.argtypes = [vp, vp, i64, i32, _Results, i32, vp, vp, vp, vp]
         lib.fpsched_rank_workspace_bytes.restype = ctypes.c_size_t
         lib.fpsched_rank_workspace_bytes.argtypes = [vp, i64, i32]
         lib.fpsched_rank.restype = ctypes.c_int
@@ -269,6 +273,22 @@ class Problem:
                                          workspace.numel(), self._stream(stream))
         if rc != 0:
             raise FpschedError(rc, "fpsched_topk")
+        return out
+
+    def evaluate_topk_static(self, ops, k: int, results, out, stream=None):
+        """fpsched_evaluate_topk_static: evaluate + top-k with the library's static scratch memory instead
+        of a workspace.  ``results`` (alloc_results) and ``out`` (dict idx, makespan, count) are the
+        caller's; nothing is allocated here or in the library.  Asynchronous."""
+        if self.device is None:
+            raise FpschedError(-5, "fpsched_evaluate_topk_static")
+        assert ops.is_cuda and ops.is_contiguous() and ops.dim() == 3 and ops.shape[1] == self.D
+        assert ops.element_size() == 2
+        C, _, stride = ops.shape
+        rc = load_library().fpsched_evaluate_topk_static(
+            self._h, ops.data_ptr(), C, stride, self._res_struct(results), int(k), out["idx"].data_ptr(),
+            out["makespan"].data_ptr(), out["count"].data_ptr(), self._stream(stream))
+        if rc != 0:
+            raise FpschedError(rc, "fpsched_evaluate_topk_static")
         return out
 
     def generate(self, policy, inflight, stride: int, out=None, workspace=None, stream=None):

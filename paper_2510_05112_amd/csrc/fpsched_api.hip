@@ -6,6 +6,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 #include <numeric>
 #include <vector>
@@ -27,6 +28,7 @@ struct fpsched_problem {
   int32_t max_lds = 0;
   int32_t max_degree = 0;          // largest in- or out-degree of a stage in the DAG
   int32_t n_cu = 0;                // compute units of the device
+  void* d_static_scratch = nullptr; // this device's copy of the library's static scratch array
   bool general_ok = false, slots_ok = false;  // which kernels fit this problem in LDS
   bool use_slots = false;          // selected kernel: slot kernel (default when it fits) or general
   int32_t slot_v = 0;              // template bound on chunks per device
@@ -77,6 +79,34 @@ struct fpsched_problem {
 namespace {
 
 int check_hip(hipError_t e) { return e == hipSuccess ? FPSCHED_OK : FPSCHED_EHIP; }
+
+// Device memory of fpsched_evaluate_topk_static, the entry point for callers that cannot allocate: the
+// work counter and the top-k key buffers that the other entry points take from the caller's workspace.
+// Every GPU the library runs on holds its own copy of the array until the process ends.  In host code the
+// array's name is only a stand-in: the address on a device comes from hipGetSymbolAddress, asked once per
+// device with that device current, and only that pointer is ever handed to a kernel.
+constexpr size_t kStaticScratchBytes = FPSCHED_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxGpus = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxGpus] = {nullptr};
+
+// The device must be current.  FPSCHED_EHIP if the runtime does not give the address.
+int static_scratch_of(int device_id, void** out) {
+  *out = nullptr;
+  if (device_id < 0 || device_id >= kMaxGpus) return FPSCHED_EINVAL;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[device_id]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      return FPSCHED_EHIP;
+    }
+    g_scratch_ptr[device_id] = ptr;
+  }
+  *out = g_scratch_ptr[device_id];
+  return FPSCHED_OK;
+}
 
 struct DeviceGuard {
   int prev = -1;
@@ -153,6 +183,7 @@ const char* fpsched_strerror(int code) {
     case FPSCHED_EOVERFLOW: return "time bound does not fit int32";
     case FPSCHED_ENODEV: return "host-only problem handle";
     case FPSCHED_EUNSUPPORTED: return "problem too large for the on-chip tables";
+    case FPSCHED_ESCRATCH: return "batch too large for the library's static scratch memory";
     default: return "unknown error";
   }
 }
@@ -290,6 +321,7 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
       delete p; return FPSCHED_EHIP;
     }
     p->max_lds = max_lds;
+    if (static_scratch_of(p->device_id, &p->d_static_scratch) != FPSCHED_OK) { delete p; return FPSCHED_EHIP; }
     // (The dynamic-LDS limit of a kernel is one value per process, not per handle: it is always raised
     // to the device's maximum, so that handles with different needs never undo each other's setting.)
     // general kernel geometry: finish-time tables and state bytes of whole candidates in LDS
@@ -1053,6 +1085,25 @@ int fpsched_topk(const fpsched_problem* p, fpsched_results in, int64_t n_cand, i
   if (!g.ok) return FPSCHED_EHIP;
   return run_topk(reinterpret_cast<const long long*>(in.makespan), in.flags, n_cand, k, d_idx, d_makespan, d_count,
                   static_cast<char*>(d_workspace) + 256, static_cast<hipStream_t>(hip_stream));
+}
+
+size_t fpsched_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int fpsched_evaluate_topk_static(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_cand,
+                                 int32_t stride_words, fpsched_results out, int32_t k, int64_t* d_idx,
+                                 int64_t* d_makespan, int32_t* d_count, void* hip_stream) {
+  if (!p || n_cand < 0 || k < 1 || k > 1024) return FPSCHED_EINVAL;
+  if (p->device_id < 0) return FPSCHED_ENODEV;
+  if (!p->d_static_scratch) return FPSCHED_EHIP;
+  // the same layout as a caller's workspace: [256 bytes: work counter][top-k key buffers]
+  if (fpsched_workspace_bytes(p, n_cand, k) > kStaticScratchBytes) return FPSCHED_ESCRATCH;
+  // (the counter is preset by a kernel and every key that is read was written by the level before: nothing
+  // of an earlier call's contents is ever looked at)
+  const int rc = fpsched_evaluate(p, d_ops, n_cand, stride_words, out, p->d_static_scratch, kStaticScratchBytes,
+                                  hip_stream);
+  if (rc != FPSCHED_OK) return rc;
+  return fpsched_topk(p, out, n_cand, k, d_idx, d_makespan, d_count, p->d_static_scratch, kStaticScratchBytes,
+                      hip_stream);
 }
 
 size_t fpsched_rank_workspace_bytes(const fpsched_problem* p, int64_t n_cand, int32_t k) {
