@@ -45,6 +45,8 @@ MEASURED_LINKS = {("cfg4", 65536): {"traffic_bytes": None, "valu_wave_instructio
                                     "profile": "profiles/eval_slot_kernel_cfg4_link_occupancy.md"}}
 # both cost-model variants together (--links --mb-costs)
 MEASURED_BOTH = {}
+# the evaluation with synchronisation stages (--mode sync)
+MEASURED_SYNC = {}
 # one generator launch (--mode generate): WRITE_SIZE x 1024 plus the parameter sets read
 MEASURED_GENERATE = {("cfg4", 65536): {"traffic_bytes": 4.81e9, "valu_wave_instructions": 1.231e10,
                                        "valu_per_wave_round": None, "profile_kernel_ms": 23.3,
@@ -320,6 +322,92 @@ def bench_wslide(args, spec, threads) -> int:
     return 0 if json_res.get("parity_sample", {}).get("bit_exact", True) else 1
 
 
+def bench_sync(args, threads) -> int:
+    """Evaluation + top-k under the model with synchronisation stages and dependency pairs
+    (fpsched_problem_set_sync), on the multimodal workload with a registered synchronisation every four
+    micro-batches (workloads.sync_config): one step = fpsched_evaluate + fpsched_topk on the resident batch."""
+    import numpy as np
+    import torch
+
+    import paper_2510_05112_amd as fp
+    import workloads
+
+    dev = torch.device("cuda", 0)
+    spec = workloads.sync_config(args.n)
+    prob = spec.problem
+    t0 = time.perf_counter()
+    words = workloads.generate_sync(spec, threads=threads)
+    gen_s = time.perf_counter() - t0
+    C, D, stride = words.shape
+    n_ops = workloads.count_ops(words)
+    handle = fp.Problem(prob, stride, device=0)
+    handle.set_sync(spec.group, spec.pairs)
+    ops = torch.from_numpy(words.view(np.int16)).to(dev)
+    res, k = handle.alloc_results(C), spec.top_k
+    ws = handle.alloc_workspace(C, k)
+    top = dict(idx=torch.empty(k, dtype=torch.int64, device=dev), makespan=torch.empty(k, dtype=torch.int64, device=dev),
+               count=torch.empty(1, dtype=torch.int32, device=dev))
+    print(f"[bench] sync: {C} candidates x {D} devices x stride {stride} ({words.nbytes / 1e9:.2f} GB), "
+          f"{n_ops / C:.0f} ops/candidate, generated in {gen_s:.1f}s", file=sys.stderr, flush=True)
+    for _ in range(args.warmup):
+        handle.evaluate(ops, res, ws)
+        handle.topk(res, k, ws, top)
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        ev[i][0].record()
+        handle.evaluate(ops, res, ws)
+        ev[i][1].record()
+        handle.topk(res, k, ws, top)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    eval_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+    ms_per_step = wall * 1e3 / args.steps
+    alg_bytes = 2 * n_ops + C * (8 + 8 * D + 4 * D + 1)
+    roofline, issue = rooflines(alg_bytes, eval_ms, "fpsched evaluation kernel for synchronisation stages (eval_sync_kernel)",
+                                MEASURED_SYNC.get(("sync4", C)), units=n_ops)
+    flags = res["flags"].cpu().numpy()
+    out = {
+        "metric": "candidate schedules evaluated/sec", "value": C / (ms_per_step * 1e-3), "unit": "schedules/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
+        "config": {"workload": f"{prob.name}: two towers of 6 stages + a synchronisation stage, {C} candidates, "
+                               f"top-{k}, cap {int(prob.mem_cap[0])} units/device, one dependency pair",
+                   "candidates": C, "devices": D, "stages": prob.n_stages, "microbatches": prob.n_microbatches,
+                   "ops_per_candidate": n_ops / C, "stride_words": stride, "top_k": k},
+        "op_evals_per_s": n_ops / (ms_per_step * 1e-3), "eval_kernel_ms": eval_ms,
+        "roofline": roofline, "issue": issue,
+        "fractions": {"feasible_under_cap": float((flags == 0).mean()), "over_cap": float((flags == 4).mean()),
+                      "deadlock": float(((flags & 1) != 0).mean())},
+        "best_makespan": int(top["makespan"][0].item()) if int(top["count"].item()) else None,
+    }
+    if args.check or not args.no_cpu_baseline:
+        import oracle  # test infrastructure: parity sample and the reported CPU baseline only
+        if args.check:
+            pick = np.sort(np.random.default_rng(0).choice(C, min(args.check, C), replace=False))
+            ref = oracle.evaluate_sync(prob, words[pick], spec.group, spec.pairs, threads=threads)
+            ok = all(np.array_equal(res[n][torch.from_numpy(pick).to(dev)].cpu().numpy(), ref[n])
+                     for n in ("makespan", "idle", "peak", "flags"))
+            out["parity_sample"] = {"candidates": int(len(pick)), "bit_exact": bool(ok)}
+            if not ok:
+                print("[bench] PARITY FAILURE against the oracle on the sample", file=sys.stderr)
+        if not args.no_cpu_baseline:
+            n1 = min(C, args.cpu_sample or 16384)
+            t0 = time.perf_counter()
+            oracle.evaluate_sync(prob, words[:n1], spec.group, spec.pairs, threads=1)
+            t1 = time.perf_counter() - t0
+            nn = min(C, n1 * min(threads, 8))
+            t0 = time.perf_counter()
+            oracle.evaluate_sync(prob, words[:nn], spec.group, spec.pairs, threads=threads)
+            tn = time.perf_counter() - t0
+            out["cpu_baseline"] = {"value": nn / tn, "unit": "schedules/s", "cores": threads, "kind": "oracle",
+                                   "sample": f"first {nn} candidates of the same batch on {threads} host threads; "
+                                             f"single thread: first {n1}", "single_thread_value": n1 / t1}
+    print(json.dumps(out))
+    return 0 if out.get("parity_sample", {}).get("bit_exact", True) else 1
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -330,11 +418,13 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=None, help="candidates timed on the CPU oracle")
     ap.add_argument("--check", type=int, default=512, help="sampled candidates compared with the oracle")
-    ap.add_argument("--mode", choices=["evaluate", "generate", "search", "wslide"], default="evaluate",
+    ap.add_argument("--mode", choices=["evaluate", "generate", "search", "wslide", "sync"], default="evaluate",
                     help="evaluate: the hot path (evaluation + top-k) on a resident batch (default, the "
                          "headline metric); generate: the schedule generator on seeded parameter sets; "
                          "search: generate + evaluate + top-k per step, schedules never leave HBM; "
-                         "wslide: the weight-gradient sliding pass + top-k on the resident batch")
+                         "wslide: the weight-gradient sliding pass + top-k on the resident batch; "
+                         "sync: evaluation + top-k on the multimodal workload with a registered "
+                         "synchronisation every four micro-batches and a dependency pair")
     ap.add_argument("--slide", action="store_true",
                     help="search mode: rank the generated schedules after the weight-gradient sliding pass")
     ap.add_argument("--mb-costs", action="store_true",
@@ -362,9 +452,11 @@ def main() -> int:
         print("bench.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
         return 3
     dev = torch.device("cuda", 0)
+    threads = min(16, os.cpu_count() or 1)
+    if args.mode == "sync":
+        return bench_sync(args, threads)
     spec = workloads.config(args.config, args.n)
     prob = spec.problem
-    threads = min(16, os.cpu_count() or 1)
     if args.mode in ("generate", "search"):
         return bench_generate(args, spec, threads)
     if args.mode == "wslide":

@@ -165,6 +165,43 @@ int fpsched_problem_set_microbatch_costs(fpsched_problem *p, const int32_t *dur_
  * called concurrently with other calls on the handle.  Works on a host-only handle (flag only). */
 int fpsched_problem_set_link_occupancy(fpsched_problem *p, int32_t on);
 
+/* Synchronisation stages and dependency pairs.  The paper lets a user register a new instruction --
+ * its example is the synchronisation that exchanges the output states of the submodules of a
+ * multimodal model (SyncWithGather, Section 7.2) -- attached to a stage registered for it, state how
+ * many of the instructions it depends on must have been scheduled before it (the comparison system
+ * synchronises once every few micro-batches, Section 2.2), and add data dependencies as pairs
+ * ((type1, stage_i), (type2, stage_j)): type1 of stage_i before type2 of stage_j (Section 4.2,
+ * "Registration of new instructions"; Section 5.1, "Data dependency").  In this library:
+ *   - group: HOST int32 [S], >= 1, or NULL (all 1).  A stage with group n has ceil(m / n) items per
+ *     kind; item g stands for the micro-batches g n .. min(m, (g + 1) n) - 1, and the micro-batch
+ *     field of its op words holds g (a larger value is a malformed word).  A synchronisation every n
+ *     micro-batches is a stage of the DAG with group n: its forward item is the synchronisation, its
+ *     backward (and weight-gradient) item what the backward pass has to do there, possibly at cost 0.
+ *   - along a DAG edge or a pair, an item waits for EVERY item of the other stage whose micro-batches
+ *     overlap its own.
+ *   - pairs: HOST [n_pairs].  An item of kind_to on stage_to starts no earlier than the finish of the
+ *     items of kind_from on stage_from, plus `latency` if the two stages sit on different devices.
+ *     kind_from: FPSCHED_F (stands for F and FD, whichever ran), FPSCHED_B or FPSCHED_W; kind_to: any
+ *     kind (FPSCHED_F also constrains FD).  Pairs that close a cycle make candidates deadlock, which
+ *     their flags report.
+ * From then on fpsched_evaluate (and fpsched_evaluate_topk_static) time the candidates under this
+ * model, with a kernel that keeps whole finish-time tables in LDS; fpsched_encode and
+ * fpsched_validate check micro-batch fields against the item counts.  (NULL, 0, NULL) switches back.
+ * Copied; synchronous (waits for the device's queued work); allocates one table of device memory
+ * (FPSCHED_ENOMEM), freed by fpsched_problem_destroy.  FPSCHED_EINVAL for a group < 1, a stage or
+ * kind out of range, a negative latency, W without split backward, or a pair from an item to
+ * itself; FPSCHED_EOVERFLOW if D * max_stride * (max dur + max latency) >= 2^31; FPSCHED_EUNSUPPORTED
+ * if the tables do not fit LDS, or while costs per micro-batch or link occupancy are set (and those
+ * two setters, fpsched_wslide and fpsched_generate answer FPSCHED_EUNSUPPORTED while this is set): the
+ * handle then keeps what it had.  Works on a host-only handle (validation, encode, validate). */
+typedef struct {
+  int32_t kind_from, stage_from; /* the item waited for  */
+  int32_t kind_to, stage_to;     /* the item that waits  */
+  int32_t latency;               /* >= 0, added iff the two stages sit on different devices */
+} fpsched_dependency;
+int fpsched_problem_set_sync(fpsched_problem *p, const int32_t *group, int32_t n_pairs,
+                             const fpsched_dependency *pairs);
+
 /* DEVICE buffers the caller owns (e.g. torch tensors); all must hold n_cand entries. */
 typedef struct {
   int64_t *makespan; /* [C]     max finish time over all devices                          */

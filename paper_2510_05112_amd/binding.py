@@ -65,6 +65,8 @@ def load_library():
         lib.fpsched_problem_set_microbatch_costs.argtypes = [vp, vp]
         lib.fpsched_problem_set_link_occupancy.restype = ctypes.c_int
         lib.fpsched_problem_set_link_occupancy.argtypes = [vp, i32]
+        lib.fpsched_problem_set_sync.restype = ctypes.c_int
+        lib.fpsched_problem_set_sync.argtypes = [vp, vp, i32, vp]
         lib.fpsched_problem_select_kernel.restype = ctypes.c_int
         lib.fpsched_problem_select_kernel.argtypes = [vp, ctypes.c_int]
         lib.fpsched_workspace_bytes.restype = ctypes.c_size_t
@@ -188,6 +190,19 @@ class Problem:
         rc = load_library().fpsched_problem_set_link_occupancy(self._h, 1 if on else 0)
         if rc != 0:
             raise FpschedError(rc, "fpsched_problem_set_link_occupancy")
+
+    def set_sync(self, group=None, pairs=None):
+        """Synchronisation stages and dependency pairs (see fpsched_problem_set_sync): group[S]
+        micro-batches per item of each stage (None = 1), pairs = rows (kind_from, stage_from, kind_to,
+        stage_to, latency).  set_sync() switches back to the plain model."""
+        grp = None if group is None else _i32(group)
+        if grp is not None and grp.shape != (self.S,):
+            raise ValueError(f"group must have {self.S} entries")
+        prs = _i32(np.zeros((0, 5), np.int32) if pairs is None else pairs).reshape(-1, 5)
+        rc = load_library().fpsched_problem_set_sync(self._h, None if grp is None else grp.ctypes.data, len(prs),
+                                                     prs.ctypes.data if len(prs) else None)
+        if rc != 0:
+            raise FpschedError(rc, "fpsched_problem_set_sync")
 
     # ---- host helpers -----------------------------------------------------
     def encode(self, items, device: int) -> np.ndarray:

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libfpsched.so")
-SOURCES = ["fpsched_api.hip", "eval_general.hip", "eval_slots.hip", "generate.hip", "topk.hip", "pareto.hip", "wslide.hip"]
+SOURCES = ["fpsched_api.hip", "eval_general.hip", "eval_sync.hip", "eval_slots.hip", "generate.hip", "topk.hip", "pareto.hip", "wslide.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-command-line-argument"]

@@ -97,4 +97,27 @@ struct SlotTables {
   const int32_t* ints;      // DEVICE
 };
 
+// Tables of the evaluation with synchronisation stages and dependency pairs (eval_sync.hip).  Every
+// dependency of an item -- the edges of the stage DAG and the user's pairs alike -- is one entry of a list
+// per (kind, stage): which finish-time table it looks into (0 forward, 1 backward, 2 weight gradient), the
+// producing stage, and the latency (already 0 when both stages sit on one device).
+struct SyncTables {
+  int32_t D, S, m, has_w;
+  int32_t lanes_per_cand;   // power of two >= D
+  int32_t cands_per_wave;   // limited by LDS
+  int32_t n_fin_tables;     // 2, or 3 if some pair waits for a weight-gradient item
+  int32_t n_table_ints;     // length of `ints`
+  // offsets (in int32 units) into `ints`
+  int32_t off_dur;          // [kNKinds][S]
+  int32_t off_mem_units;    // [S]
+  int32_t off_group;        // [S] micro-batches per item of the stage
+  int32_t off_items;        // [S] items per kind: ceil(m / group)
+  int32_t off_dep_off;      // [kNKinds * S + 1] first entry of (kind, stage) in the dependency list
+  int32_t off_dep;          // [entries][3]: table, producing stage, latency
+  int32_t off_local_stage;  // [D][kMaxChunks], -1 = none
+  int32_t off_n_chunks;     // [D]
+  int32_t off_mem_cap;      // [D]
+  const int32_t* ints;      // DEVICE
+};
+
 }  // namespace fpsched

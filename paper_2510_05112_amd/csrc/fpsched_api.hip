@@ -68,6 +68,13 @@ struct fpsched_problem {
   SlotTables stab_times_links{};
   int32_t* d_times_links_image = nullptr;
   int32_t links_waves = 0, links_grid = 0, links_lds_bytes = 0;
+  // synchronisation stages and dependency pairs (fpsched_problem_set_sync)
+  bool sync_on = false;
+  std::vector<int32_t> sync_items;      // [S] items per kind of each stage (m while the model is off)
+  SyncTables sync_tab{};
+  int32_t* d_sync_ints = nullptr;
+  size_t sync_ints_capacity = 0;
+  int32_t sync_lds_bytes = 0;
   // ... or, when the values fit sixteen bits and the table fits LDS, inside a second table image
   bool mb_in_lds = false;
   SlotTables stab_mb{};
@@ -208,6 +215,7 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
   p->stage_chunk.assign(S, 0);
   p->local_stage.assign((size_t)D * kMaxChunks, -1);
   p->n_chunks.assign(D, 0);
+  p->sync_items.assign(S, m);
   int rc = FPSCHED_OK;
   for (int s = 0; s < S && rc == FPSCHED_OK; ++s) {
     const int d = p->stage_device[s];
@@ -534,7 +542,7 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
 
 void fpsched_problem_destroy(fpsched_problem* p) {
   if (!p) return;
-  if (p->d_ints || p->d_slot_ints) {
+  if (p->d_ints || p->d_slot_ints || p->d_sync_ints) {
     DeviceGuard g(p->device_id);
     if (p->d_ints) (void)hipFree(p->d_ints);
     if (p->d_slot_ints) (void)hipFree(p->d_slot_ints);
@@ -545,6 +553,7 @@ void fpsched_problem_destroy(fpsched_problem* p) {
     if (p->d_links_image) (void)hipFree(p->d_links_image);
     if (p->d_times_links_image) (void)hipFree(p->d_times_links_image);
     if (p->d_combo_image) (void)hipFree(p->d_combo_image);
+    if (p->d_sync_ints) (void)hipFree(p->d_sync_ints);
   }
   delete p;
 }
@@ -597,6 +606,16 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
   if (reinterpret_cast<uintptr_t>(d_ops) & 15) return FPSCHED_EINVAL;
   DeviceGuard g(p->device_id);
   if (!g.ok) return FPSCHED_EHIP;
+  if (p->sync_on) {
+    const int cpw = p->sync_tab.cands_per_wave;
+    const int64_t blocks = (n_cand + cpw - 1) / cpw;
+    if (blocks > 0x7fffffffll) return FPSCHED_EINVAL;
+    hipLaunchKernelGGL(eval_sync_kernel, dim3((unsigned)blocks), dim3(64), (size_t)p->sync_lds_bytes,
+                       static_cast<hipStream_t>(hip_stream), p->sync_tab, d_ops, (long long)n_cand,
+                       (int)stride_words, reinterpret_cast<long long*>(out.makespan),
+                       reinterpret_cast<long long*>(out.idle), out.peak, out.flags);
+    return check_hip(hipGetLastError());
+  }
   if (p->links_on && !p->use_slots) return FPSCHED_EUNSUPPORTED;   // the general kernel has no link form
   if (p->use_slots && (!p->mb_set || p->mb_slots_ok)) {
     // the first 8 bytes of the workspace hold the counter the segments draw candidates from
@@ -706,6 +725,7 @@ int fpsched_problem_set_microbatch_costs(fpsched_problem* p, const int32_t* dur_
     p->mb_set = false;   // the tables stay allocated for the next call
     return FPSCHED_OK;
   }
+  if (p->sync_on) return FPSCHED_EUNSUPPORTED;   // the synchronisation model knows one cost per (type, stage)
   const int D = p->D, S = p->S, m = p->m;
   const size_t n_raw = (size_t)kNKinds * S * m;
   int64_t max_dur = 0;
@@ -841,6 +861,7 @@ int fpsched_problem_set_link_occupancy(fpsched_problem* p, int32_t on) {
     p->links_on = false;   // the table image stays allocated for the next call
     return FPSCHED_OK;
   }
+  if (p->sync_on) return FPSCHED_EUNSUPPORTED;   // the synchronisation model reads transfers as latencies
   const int D = p->D, S = p->S;
   // every finish time is at most the sum of all costs and of all transfers (at most two per op here)
   const int64_t bound = (int64_t)D * p->max_stride * ((p->mb_set ? p->mb_max_dur : p->max_dur) + 2 * p->max_comm);
@@ -992,6 +1013,122 @@ int fpsched_problem_set_link_occupancy(fpsched_problem* p, int32_t on) {
   return FPSCHED_OK;
 }
 
+int fpsched_problem_set_sync(fpsched_problem* p, const int32_t* group, int32_t n_pairs,
+                             const fpsched_dependency* pairs) {
+  if (!p || n_pairs < 0 || (n_pairs > 0 && !pairs)) return FPSCHED_EINVAL;
+  const int D = p->D, S = p->S, m = p->m;
+  bool trivial = n_pairs == 0;
+  for (int s = 0; s < S && group; ++s) {
+    if (group[s] < 1) return FPSCHED_EINVAL;
+    if (group[s] != 1) trivial = false;
+  }
+  if (trivial) {   // back to the plain model; the table stays allocated for the next call
+    p->sync_on = false;
+    p->sync_items.assign(S, m);
+    return FPSCHED_OK;
+  }
+  if (p->mb_set || p->links_on) return FPSCHED_EUNSUPPORTED;
+  int64_t max_lat = p->max_comm;
+  bool wants_w = false;
+  for (int i = 0; i < n_pairs; ++i) {
+    const fpsched_dependency& q = pairs[i];
+    if (q.kind_from != FPSCHED_F && q.kind_from != FPSCHED_B && q.kind_from != FPSCHED_W) return FPSCHED_EINVAL;
+    if (q.kind_to <= FPSCHED_END || q.kind_to >= FPSCHED_NKINDS) return FPSCHED_EINVAL;
+    if ((q.kind_from == FPSCHED_W || q.kind_to == FPSCHED_W) && !p->has_w) return FPSCHED_EINVAL;
+    if (q.stage_from < 0 || q.stage_from >= S || q.stage_to < 0 || q.stage_to >= S || q.latency < 0) return FPSCHED_EINVAL;
+    if (q.stage_from == q.stage_to && (q.kind_from == q.kind_to || (q.kind_from == FPSCHED_F && q.kind_to == FPSCHED_FD)))
+      return FPSCHED_EINVAL;
+    max_lat = std::max<int64_t>(max_lat, q.latency);
+    wants_w = wants_w || q.kind_from == FPSCHED_W;
+  }
+  if ((int64_t)D * p->max_stride * (p->max_dur + max_lat) >= (int64_t)1 << 31) return FPSCHED_EOVERFLOW;
+  std::vector<int32_t> grp(S, 1), items(S, m);
+  for (int s = 0; s < S; ++s) {
+    grp[s] = group ? std::min(group[s], m) : 1;
+    items[s] = (m + grp[s] - 1) / grp[s];
+  }
+  if (p->device_id < 0) {
+    p->sync_items = items;
+    p->sync_on = true;
+    return FPSCHED_OK;
+  }
+  // table image: the plain tables' rows that are needed, the groups, one dependency list per (kind, stage)
+  const std::vector<int32_t>& I = p->host_ints;
+  const DevTables& T = p->tables;
+  std::vector<int32_t> J;
+  SyncTables ST{};
+  ST.D = D; ST.S = S; ST.m = m; ST.has_w = p->has_w;
+  ST.lanes_per_cand = T.lanes_per_cand;
+  ST.n_fin_tables = wants_w ? 3 : 2;
+  auto append = [&](const int32_t* src, size_t n) { const int32_t off = (int32_t)J.size(); J.insert(J.end(), src, src + n); return off; };
+  ST.off_dur = append(&I[T.off_dur], (size_t)kNKinds * S);
+  ST.off_mem_units = append(&I[T.off_mem_units], S);
+  ST.off_group = append(grp.data(), S);
+  ST.off_items = append(items.data(), S);
+  std::vector<int32_t> dep_off((size_t)kNKinds * S + 1, 0), dep;
+  for (int kind = 0; kind < kNKinds; ++kind)
+    for (int s = 0; s < S; ++s) {
+      dep_off[(size_t)kind * S + s] = (int32_t)(dep.size() / 3);
+      if (kind == kF || kind == kFD)
+        for (int e = I[T.off_pred_off + s]; e < I[T.off_pred_off + s + 1]; ++e) {
+          dep.push_back(0); dep.push_back(I[T.off_pred_stage + e]); dep.push_back(I[T.off_pred_comm + e]);
+        }
+      if (kind == kB)
+        for (int e = I[T.off_succ_off + s]; e < I[T.off_succ_off + s + 1]; ++e) {
+          dep.push_back(1); dep.push_back(I[T.off_succ_stage + e]); dep.push_back(I[T.off_succ_comm + e]);
+        }
+      for (int i = 0; i < n_pairs; ++i) {
+        const fpsched_dependency& q = pairs[i];
+        if (q.stage_to != s || !(q.kind_to == kind || (q.kind_to == FPSCHED_F && kind == kFD))) continue;
+        dep.push_back(q.kind_from == FPSCHED_F ? 0 : (q.kind_from == FPSCHED_B ? 1 : 2));
+        dep.push_back(q.stage_from);
+        dep.push_back(p->stage_device[q.stage_from] != p->stage_device[s] ? q.latency : 0);
+      }
+    }
+  dep_off[(size_t)kNKinds * S] = (int32_t)(dep.size() / 3);
+  ST.off_dep_off = append(dep_off.data(), dep_off.size());
+  ST.off_dep = append(dep.data(), dep.size());
+  ST.off_local_stage = append(p->local_stage.data(), (size_t)D * kMaxChunks);
+  ST.off_n_chunks = append(p->n_chunks.data(), D);
+  ST.off_mem_cap = append(&I[T.off_mem_cap], D);
+  ST.n_table_ints = (int32_t)J.size();
+  // candidates per wavefront: whole finish-time tables and state bytes of each in LDS
+  const int64_t SM = (int64_t)S * m;
+  const int64_t per_cand = 4 * (ST.n_fin_tables * SM + ((SM + 3) >> 2));
+  const int64_t table_bytes = 4ll * ST.n_table_ints;
+  int cpw = 64 / ST.lanes_per_cand;
+  while (cpw > 1 && table_bytes + cpw * per_cand > p->max_lds) cpw >>= 1;
+  if (table_bytes + cpw * per_cand > p->max_lds) return FPSCHED_EUNSUPPORTED;
+  ST.cands_per_wave = cpw;
+  DeviceGuard g(p->device_id);
+  if (!g.ok) return FPSCHED_EHIP;
+  if (hipDeviceSynchronize() != hipSuccess) return FPSCHED_EHIP;   // an earlier table may be in use
+  if (J.size() > p->sync_ints_capacity) {
+    int32_t* fresh = nullptr;
+    if (hipMalloc(&fresh, J.size() * sizeof(int32_t)) != hipSuccess) { (void)hipGetLastError(); return FPSCHED_ENOMEM; }
+    if (p->d_sync_ints) (void)hipFree(p->d_sync_ints);
+    p->d_sync_ints = fresh;
+    p->sync_ints_capacity = J.size();
+    if (p->sync_on) {   // the table it ran on is gone
+      p->sync_on = false;
+      p->sync_items.assign(S, m);
+    }
+  }
+  if (hipMemcpy(p->d_sync_ints, J.data(), J.size() * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess ||
+      hipFuncSetAttribute(reinterpret_cast<const void*>(&eval_sync_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          p->max_lds) != hipSuccess) {
+    p->sync_on = false;
+    p->sync_items.assign(S, m);
+    return FPSCHED_EHIP;
+  }
+  ST.ints = p->d_sync_ints;
+  p->sync_tab = ST;
+  p->sync_lds_bytes = (int32_t)(table_bytes + cpw * per_cand);
+  p->sync_items = items;
+  p->sync_on = true;
+  return FPSCHED_OK;
+}
+
 int fpsched_generate(const fpsched_problem* p, const fpsched_actor_policy* d_policy, const int32_t* d_inflight,
                      int64_t n_sets, int32_t stride_words, uint16_t* d_ops, int32_t* d_steps, uint8_t* d_status,
                      void* d_workspace, size_t workspace_bytes, void* hip_stream) {
@@ -999,6 +1136,7 @@ int fpsched_generate(const fpsched_problem* p, const fpsched_actor_policy* d_pol
   if (p->device_id < 0) return FPSCHED_ENODEV;
   if (n_sets == 0) return FPSCHED_OK;
   if (!d_policy || !d_inflight || !d_ops || !d_steps || !d_status) return FPSCHED_EINVAL;
+  if (p->sync_on) return FPSCHED_EUNSUPPORTED;   // the generator schedules one item per micro-batch
   int max_chunks = 0;
   for (int d = 0; d < p->D; ++d) max_chunks = std::max(max_chunks, p->n_chunks[d]);
   const int64_t longest = (int64_t)max_chunks * p->m * (p->has_w ? 3 : 2);
@@ -1159,7 +1297,7 @@ int fpsched_wslide(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_ca
   if (p->device_id < 0) return FPSCHED_ENODEV;
   if (!p->has_w) return FPSCHED_EINVAL;
   // the pass knows one cost per (type, stage)
-  if (!p->slide_ok || p->mb_set || (p->links_on && !p->links_slide_ok)) return FPSCHED_EUNSUPPORTED;
+  if (!p->slide_ok || p->mb_set || p->sync_on || (p->links_on && !p->links_slide_ok)) return FPSCHED_EUNSUPPORTED;
   if (n_cand == 0) return FPSCHED_OK;
   if (!d_ops || !d_ops_out || !out.makespan || !out.idle || !out.peak || !out.flags) return FPSCHED_EINVAL;
   if (stride_words < 8 || (stride_words & 7) || stride_words > p->max_stride) return FPSCHED_EINVAL;
@@ -1268,7 +1406,7 @@ int fpsched_encode(const fpsched_problem* p, const int32_t* ksm, int32_t device,
   if (!p || n < 0 || device < 0 || device >= p->D || (n > 0 && (!ksm || !out_words))) return FPSCHED_EINVAL;
   for (int i = 0; i < n; ++i) {
     const int kind = ksm[3 * i], s = ksm[3 * i + 1], j = ksm[3 * i + 2];
-    if (kind <= FPSCHED_END || kind >= FPSCHED_NKINDS || s < 0 || s >= p->S || j < 0 || j >= p->m)
+    if (kind <= FPSCHED_END || kind >= FPSCHED_NKINDS || s < 0 || s >= p->S || j < 0 || j >= p->sync_items[s])
       return FPSCHED_EINVAL;
     if (p->stage_device[s] != device) return FPSCHED_EINVAL;
     if (kind == FPSCHED_W && !p->has_w) return FPSCHED_EINVAL;
@@ -1289,7 +1427,8 @@ int64_t fpsched_validate(const fpsched_problem* p, const uint16_t* h_ops, int64_
         const unsigned w = row[i];
         const int kind = w >> 13;
         if (kind == FPSCHED_END) break;
-        if ((int)((w >> 11) & 3) >= p->n_chunks[d] || (int)(w & 0x7ff) >= p->m ||
+        const int c = (int)((w >> 11) & 3);
+        if (c >= p->n_chunks[d] || (int)(w & 0x7ff) >= p->sync_items[p->local_stage[(size_t)d * kMaxChunks + c]] ||
             (kind == FPSCHED_W && !p->has_w)) { cand_bad = true; break; }
       }
     }

@@ -19,6 +19,12 @@ __global__ void eval_general_kernel(DevTables T, const uint16_t* ops, long long 
                                     long long* out_makespan, long long* out_idle, int* out_peak,
                                     unsigned char* out_flags, const int32_t* dur_mb);
 
+// Synchronisation stages and dependency pairs (eval_sync.hip): the table form of the evaluator with one
+// dependency list per (kind, stage) and items that stand for groups of micro-batches.
+__global__ void eval_sync_kernel(SyncTables T, const uint16_t* ops, long long n_cand, int stride,
+                                 long long* out_makespan, long long* out_idle, int* out_peak,
+                                 unsigned char* out_flags);
+
 constexpr int kSlotMaxWaves = 16;
 constexpr int kSlotMaxThreads = 64 * kSlotMaxWaves;
 

@@ -150,3 +150,38 @@ def random_sync_lists(problem, group, pairs, rng, p_recompute=0.0, p_offload=0.0
         lists[dev[s]].append((k, chunk[s], g))
         remaining -= 1
     return lists
+
+
+def random_sync_problem(rng, trial):
+    """Random chain or DAG, one to three stages per device, random group sizes and pairs."""
+    D = int(rng.integers(2, 6))
+    S = int(rng.integers(D, min(3 * D, 10) + 1))
+    m = int(rng.integers(2, 9))
+    has_w = int(rng.integers(2))
+    stage_device = list(rng.permutation(D)) + [int(rng.integers(D)) for _ in range(S - D)]
+    while max(np.bincount(stage_device)) > 4:
+        stage_device = list(rng.permutation(D)) + [int(rng.integers(D)) for _ in range(S - D)]
+    order = rng.permutation(S)                     # a random topological order of the stages
+    edges = []
+    for i in range(1, S):
+        for a in rng.choice(order[:i], size=min(i, int(rng.integers(1, 3))), replace=False):
+            edges.append((int(a), int(order[i]), int(rng.integers(0, 4))))
+    dur = {k: rng.integers(0 if k != B else 1, 9, S) for k in (F, B, R, O, L)}
+    dur[FD] = dur[F]
+    if has_w:
+        dur[W] = rng.integers(0, 6, S)
+    prob = make_problem(D, S, m, has_w, stage_device, edges, dur, mem_units=rng.integers(0, 3, S),
+                        mem_cap=rng.integers(m, 4 * m, D))
+    group = [int(rng.choice([1, 1, 2, 3, m])) for _ in range(S)]
+    pos = {int(s): i for i, s in enumerate(order)}
+    pairs = []
+    for _ in range(int(rng.integers(0, 4))):
+        a, b = (int(x) for x in rng.choice(S, 2, replace=False))
+        if pos[a] > pos[b]:
+            a, b = b, a
+        kinds = [(F, F), (F, B), (B, W) if has_w else (F, B), (W, W) if has_w else (B, B), (F, R), (B, L)]
+        k1, k2 = kinds[int(rng.integers(len(kinds)))]
+        if k1 == B and k2 in (B, W):               # backward-to-backward pairs run down the order
+            a, b = b, a
+        pairs.append((k1, a, k2, b, int(rng.integers(0, 4))))
+    return prob, group, pairs

@@ -167,3 +167,24 @@ def test_wslide_full_batch_every_candidate_against_oracle(links):
             if (fl[c] & 3) == 0:
                 assert np.array_equal(keep_a, keep_b)
     h.close()
+
+
+def test_sync_workload_full_batch_every_candidate_against_oracle():
+    """The multimodal workload with a registered synchronisation, in the launch `bench.py --mode sync` times."""
+    spec = workloads.sync_config()
+    words = workloads.generate_sync(spec, threads=16)
+    C = len(words)
+    h = fp.Problem(spec.problem, spec.stride, device=0)
+    h.set_sync(spec.group, spec.pairs)
+    ws = h.alloc_workspace(C, spec.top_k)
+    res = h.evaluate(torch.from_numpy(words.view(np.int16)).cuda(), workspace=ws)
+    top = h.topk(res, spec.top_k, workspace=ws)
+    torch.cuda.synchronize()
+    ref = oracle.evaluate_sync(spec.problem, words, spec.group, spec.pairs, threads=16)
+    for name in ("flags", "makespan", "idle", "peak"):
+        assert np.array_equal(res[name].cpu().numpy(), ref[name]), name
+    r_idx, r_ms, r_cnt = oracle.topk(ref["makespan"], ref["flags"], spec.top_k)
+    assert int(top["count"].item()) == r_cnt and np.array_equal(top["idx"].cpu().numpy(), r_idx)
+    assert np.array_equal(top["makespan"].cpu().numpy(), r_ms)
+    assert (ref["flags"] == 0).mean() > 0.3 and (ref["flags"] & 1).any()
+    h.close()

@@ -10,7 +10,7 @@ import pytest
 import oracle
 import paper_2510_05112_amd as fp
 import workloads
-from workloads.problem import B, F, FD, W, chain_problem, pack_lists, pack_word
+from workloads.problem import B, F, FD, R, W, chain_problem, pack_lists, pack_word
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -106,6 +106,33 @@ def test_host_only_handle_and_errors():
     five = chain_problem(1, 2, v=5)
     with pytest.raises(fp.FpschedError):
         fp.Problem(five, 64, device=None)                  # more than 4 stages on a device
+
+
+def test_sync_setting_on_a_host_only_handle():
+    # groups and pairs are validated on the host; encode and validate then follow the item counts
+    spec = workloads.sync_config(16)
+    words = workloads.generate_sync(spec, threads=2)
+    p = fp.Problem(spec.problem, spec.stride, device=None)
+    assert p.validate(words) == 0            # every item index is below 64 anyway
+    p.set_sync(spec.group, spec.pairs)
+    assert p.validate(words) == 0
+    bad = words.copy()
+    bad[3, 11, 5] = pack_word(F, 1, 16)      # the synchronisation stage has 16 items: 0..15
+    assert p.validate(bad) == 1
+    assert list(p.encode([(F, 12, 15)], device=11)) == [pack_word(F, 1, 15)]
+    with pytest.raises(fp.FpschedError):
+        p.encode([(F, 12, 16)], device=11)
+    for kwargs, code in ((dict(group=[1] * 12 + [0]), -1), (dict(pairs=[(F, 0, F, 0, 0)]), -1),
+                         (dict(pairs=[(R, 0, F, 1, 0)]), -1), (dict(pairs=[(F, 0, F, 1, 1 << 30)]), -4)):
+        with pytest.raises(fp.FpschedError) as e:
+            p.set_sync(**kwargs)
+        assert e.value.code == code
+    with pytest.raises(ValueError):
+        p.set_sync(group=[1, 2])
+    p.set_sync()
+    assert list(p.encode([(F, 12, 16)], device=11)) == [pack_word(F, 1, 16)]
+    assert fp.load_library().fpsched_problem_set_sync(None, None, 0, None) == -1
+    p.close()
 
 
 def test_encode_matches_hand_written_words_and_oracle_decode():

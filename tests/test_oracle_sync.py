@@ -11,7 +11,8 @@ import pytest
 
 import oracle
 import workloads
-from helpers import batch_from_lists, dag_problem, perturb, random_sync_lists, random_valid_lists, two_tower_problem
+from helpers import (batch_from_lists, dag_problem, perturb, random_sync_lists, random_sync_problem,
+                     random_valid_lists, two_tower_problem)
 from sync_checker import check
 from workloads.problem import B, F, FD, L, O, R, W, chain_problem, gpipe_lists, make_problem, pack_lists, pack_word
 
@@ -116,41 +117,6 @@ def test_gpipe_with_one_synchronisation_after_all_forward_passes(p, m, f, b, c, 
     assert out["flags"][0] == 0 and out["makespan"][0] == total
     assert list(out["idle"][0]) == [total - m * (f + b)] * (p - 1) + [total - m * (f + b) - sigma]
     assert list(out["peak"][0]) == [m] * p
-
-
-def random_sync_problem(rng, trial):
-    """Random chain or DAG, one to three stages per device, random group sizes and pairs."""
-    D = int(rng.integers(2, 6))
-    S = int(rng.integers(D, min(3 * D, 10) + 1))
-    m = int(rng.integers(2, 9))
-    has_w = int(rng.integers(2))
-    stage_device = list(rng.permutation(D)) + [int(rng.integers(D)) for _ in range(S - D)]
-    while max(np.bincount(stage_device)) > 4:
-        stage_device = list(rng.permutation(D)) + [int(rng.integers(D)) for _ in range(S - D)]
-    order = rng.permutation(S)                     # a random topological order of the stages
-    edges = []
-    for i in range(1, S):
-        for a in rng.choice(order[:i], size=min(i, int(rng.integers(1, 3))), replace=False):
-            edges.append((int(a), int(order[i]), int(rng.integers(0, 4))))
-    dur = {k: rng.integers(0 if k != B else 1, 9, S) for k in (F, B, R, O, L)}
-    dur[FD] = dur[F]
-    if has_w:
-        dur[W] = rng.integers(0, 6, S)
-    prob = make_problem(D, S, m, has_w, stage_device, edges, dur, mem_units=rng.integers(0, 3, S),
-                        mem_cap=rng.integers(m, 4 * m, D))
-    group = [int(rng.choice([1, 1, 2, 3, m])) for _ in range(S)]
-    pos = {int(s): i for i, s in enumerate(order)}
-    pairs = []
-    for _ in range(int(rng.integers(0, 4))):
-        a, b = (int(x) for x in rng.choice(S, 2, replace=False))
-        if pos[a] > pos[b]:
-            a, b = b, a
-        kinds = [(F, F), (F, B), (B, W) if has_w else (F, B), (W, W) if has_w else (B, B), (F, R), (B, L)]
-        k1, k2 = kinds[int(rng.integers(len(kinds)))]
-        if k1 == B and k2 in (B, W):               # backward-to-backward pairs run down the order
-            a, b = b, a
-        pairs.append((k1, a, k2, b, int(rng.integers(0, 4))))
-    return prob, group, pairs
 
 
 def test_against_the_critical_path_checker_on_random_problems_groups_and_pairs():

@@ -20,14 +20,17 @@ from .problem import (B, F, FD, L, MAX_CHUNKS, NKINDS, NO_CAP, O, R, W, Problem,
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "fpgen.c")
 _LIB = os.path.join(_HERE, "libfpgen.so")
+_SYNC_SRC = os.path.join(_HERE, "fpsyncgen.c")
+_SYNC_LIB = os.path.join(_HERE, "libfpsyncgen.so")
 BASE_SEED = 0xF1E0
 
 
 def build(force: bool = False) -> str:
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
-        tmp = _LIB + ".tmp.%d" % os.getpid()
-        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-pthread", "-o", tmp, _SRC])
-        os.replace(tmp, _LIB)
+    for src, lib in ((_SYNC_SRC, _SYNC_LIB), (_SRC, _LIB)):
+        if force or not os.path.exists(lib) or os.path.getmtime(lib) < os.path.getmtime(src):
+            tmp = lib + ".tmp.%d" % os.getpid()
+            subprocess.check_call(["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-pthread", "-o", tmp, src])
+            os.replace(tmp, lib)
     return _LIB
 
 
@@ -247,3 +250,85 @@ def generator_stride(problem: Problem) -> int:
     per_dev = int(np.bincount(problem.stage_device, minlength=problem.n_devices).max())
     longest = per_dev * problem.n_microbatches * (3 if problem.has_w else 2)
     return max(8, -(-longest // 8) * 8)
+
+
+# ---------------------------------------------------------------------------------------------
+# problems with synchronisation stages and dependency pairs (inputs only)
+
+class _CSyncParams(ctypes.Structure):
+    _fields_ = [
+        ("n_devices", ctypes.c_int32), ("n_stages", ctypes.c_int32),
+        ("n_microbatches", ctypes.c_int32), ("has_w", ctypes.c_int32),
+        ("stage_device", ctypes.c_void_p), ("n_edges", ctypes.c_int32),
+        ("edge_src", ctypes.c_void_p), ("edge_dst", ctypes.c_void_p),
+        ("group", ctypes.c_void_p), ("n_pairs", ctypes.c_int32), ("pairs", ctypes.c_void_p),
+        ("seed", ctypes.c_uint64), ("swap_per_mille", ctypes.c_int32),
+    ]
+
+
+@dataclass
+class SyncSpec:
+    """A problem with synchronisation stages: the plain description plus the group size of every stage
+    and the dependency pairs (rows kind_from, stage_from, kind_to, stage_to, latency)."""
+
+    problem: Problem
+    group: np.ndarray
+    pairs: np.ndarray
+    n_candidates: int
+    stride: int
+    top_k: int
+    seed: int = BASE_SEED + 300
+    swap_per_mille: int = 20
+
+
+def sync_config(n_candidates: int | None = None, sync_every: int = 4) -> SyncSpec:
+    """The multimodal workload with a registered synchronisation (paper Sections 2.2, 4.2 and 7.2: two
+    submodules whose last stages exchange their output states through a synchronisation instruction, once
+    every few micro-batches): a vision tower of 6 stages (F 12, B 24, W 12) on devices 0..5 and a text
+    tower of 6 stages (F 8, B 16, W 8) on devices 6..11, as in configuration 5, both feeding a
+    synchronisation stage on device 11 that gathers every `sync_every` micro-batches (cost 6, its backward
+    item 2, no activation of its own); 64 micro-batches, latency 1, split backward, cap 12 units per
+    device; one user pair: the vision tower's first stage starts a micro-batch after the text tower's
+    first stage has finished it.  65,536 candidates, top-64.  Stands in for the paper's CLIP runs."""
+    m = 64
+    f = [12] * 6 + [8] * 6 + [6]
+    dur = {F: f, B: [24] * 6 + [16] * 6 + [2], W: [12] * 6 + [8] * 6 + [0], FD: list(f), R: list(f), O: 5, L: 5}
+    edges = [(s, s + 1, 1) for s in range(5)] + [(s, s + 1, 1) for s in range(6, 11)] + [(5, 12, 1), (11, 12, 1)]
+    prob = make_problem(12, 13, m, 1, list(range(12)) + [11], edges, dur, mem_units=[1] * 12 + [0], mem_cap=12,
+                        name=f"multimodal_sync_every_{sync_every}")
+    group = np.asarray([1] * 12 + [sync_every], np.int32)
+    pairs = np.asarray([[F, 6, F, 0, 1]], np.int32)
+    # longest row: device 11 holds a tower stage and the synchronisation stage
+    longest = 3 * m + 3 * (-(-m // sync_every))
+    return SyncSpec(prob, group, pairs, n_candidates or 65536, -(-(longest + 1) // 8) * 8, 64)
+
+
+def generate_sync(spec: SyncSpec, n: int | None = None, first: int = 0, threads: int | None = None) -> np.ndarray:
+    """Candidates [first, first + n) of ``spec`` as uint16 [n][D][stride] (fpsyncgen.c: randomised
+    step-wise list scheduling over groups and pairs; orders only)."""
+    from concurrent.futures import ThreadPoolExecutor
+    build()
+    lib = ctypes.CDLL(_SYNC_LIB)
+    lib.fpsyncgen_generate.restype = ctypes.c_int
+    p = spec.problem
+    n = spec.n_candidates - first if n is None else n
+    arrs = [_i32(p.stage_device), _i32(p.edge_src), _i32(p.edge_dst), _i32(spec.group),
+            _i32(spec.pairs).reshape(-1, 5)]
+    cp = _CSyncParams(p.n_devices, p.n_stages, p.n_microbatches, p.has_w, arrs[0].ctypes.data, len(arrs[1]),
+                      arrs[1].ctypes.data, arrs[2].ctypes.data, arrs[3].ctypes.data, len(arrs[4]),
+                      arrs[4].ctypes.data, spec.seed, spec.swap_per_mille)
+    out = np.zeros((n, p.n_devices, spec.stride), np.uint16)
+    threads = max(1, min(threads or min(16, os.cpu_count() or 1), n or 1))
+    bounds = np.linspace(0, n, threads * 4 + 1).astype(np.int64)
+
+    def run(i):
+        lo, hi = int(bounds[i]), int(bounds[i + 1])
+        if hi <= lo:
+            return 0
+        return lib.fpsyncgen_generate(ctypes.byref(cp), ctypes.c_int64(first + lo), ctypes.c_int64(hi - lo),
+                                      ctypes.c_int32(spec.stride), ctypes.c_void_p(out[lo:hi].ctypes.data))
+
+    with ThreadPoolExecutor(threads) as ex:
+        if any(ex.map(run, range(len(bounds) - 1))):
+            raise RuntimeError("fpsyncgen_generate failed")
+    return out
