@@ -27,6 +27,8 @@ _SLIDE_SRC = os.path.join(_HERE, "fpslideoracle.c")
 _SLIDE_LIB = os.path.join(_HERE, "libfpslideoracle.so")
 _SYNC_SRC = os.path.join(_HERE, "fpsyncoracle.c")
 _SYNC_LIB = os.path.join(_HERE, "libfpsyncoracle.so")
+_COPY_SRC = os.path.join(_HERE, "fpcopyoracle.c")
+_COPY_LIB = os.path.join(_HERE, "libfpcopyoracle.so")
 
 FLAG_DEADLOCK = 1
 FLAG_INCOMPLETE = 2
@@ -48,6 +50,7 @@ def build(force: bool = False) -> str:
     _compile(_GEN_SRC, _GEN_LIB, force)
     _compile(_SLIDE_SRC, _SLIDE_LIB, force)
     _compile(_SYNC_SRC, _SYNC_LIB, force)
+    _compile(_COPY_SRC, _COPY_LIB, force)
     return _compile(_SRC, _LIB, force)
 
 
@@ -483,4 +486,72 @@ def evaluate_sync_trace(problem, words_one, group=None, pairs=None):
                              ctypes.c_void_p(st.ctypes.data), ctypes.c_void_p(fi.ctypes.data))
     if rc:
         raise ValueError("fpsyncoracle: invalid problem description")
+    return dict(makespan=int(ms[0]), idle=idle, peak=peak, flags=int(fl[0]), start=st, finish=fi)
+
+
+# ---- a copy engine for offload and reload items (fpcopyoracle.c) ----------------------------------
+
+_copy_lib = None
+
+
+def _load_copy():
+    global _copy_lib
+    if _copy_lib is None:
+        build()
+        _copy_lib = ctypes.CDLL(_COPY_LIB)
+        _copy_lib.fpcopy_eval_one.restype = ctypes.c_int
+        _copy_lib.fpcopy_evaluate.restype = ctypes.c_int
+    return _copy_lib
+
+
+def evaluate_copy(problem, words, depth: int = 4, threads: int = 1):
+    """Evaluate ``words[C][D][stride]`` under the model in which offload and reload items run on a copy
+    engine that holds at most ``depth`` transfers (fpcopyoracle.c).  Returns the dict of ``evaluate``."""
+    lib = _load_copy()
+    mp = _Marshalled(problem)
+    w = np.ascontiguousarray(np.asarray(words, dtype=np.uint16))
+    assert w.ndim == 3 and w.shape[1] == mp.D, w.shape
+    C, _, stride = w.shape
+    out = dict(makespan=np.empty(C, np.int64), idle=np.empty((C, mp.D), np.int64),
+               peak=np.empty((C, mp.D), np.int32), flags=np.empty(C, np.uint8))
+
+    def run(lo, hi):
+        if hi <= lo:
+            return 0
+        return lib.fpcopy_evaluate(ctypes.byref(mp.c), ctypes.c_int32(depth), ctypes.c_void_p(w[lo:hi].ctypes.data),
+                                   ctypes.c_int64(hi - lo), ctypes.c_int32(stride),
+                                   ctypes.c_void_p(out["makespan"][lo:hi].ctypes.data),
+                                   ctypes.c_void_p(out["idle"][lo:hi].ctypes.data),
+                                   ctypes.c_void_p(out["peak"][lo:hi].ctypes.data),
+                                   ctypes.c_void_p(out["flags"][lo:hi].ctypes.data))
+
+    threads = max(1, min(int(threads), C if C else 1))
+    if threads == 1:
+        rcs = [run(0, C)]
+    else:
+        n_slices = min(C, threads * 8)
+        bounds = np.linspace(0, C, n_slices + 1).astype(np.int64)
+        with ThreadPoolExecutor(threads) as ex:
+            rcs = list(ex.map(lambda i: run(int(bounds[i]), int(bounds[i + 1])), range(n_slices)))
+    if any(rcs):
+        raise ValueError("fpcopyoracle: invalid problem description or depth")
+    return out
+
+
+def evaluate_copy_trace(problem, words_one, depth: int = 4):
+    """One candidate ``words[D][stride]`` under the same model; also every op's start and finish."""
+    lib = _load_copy()
+    mp = _Marshalled(problem)
+    w = np.ascontiguousarray(np.asarray(words_one, dtype=np.uint16))
+    assert w.ndim == 2 and w.shape[0] == mp.D
+    stride = w.shape[1]
+    ms, fl = np.empty(1, np.int64), np.empty(1, np.uint8)
+    idle, peak = np.empty(mp.D, np.int64), np.empty(mp.D, np.int32)
+    st, fi = np.empty((mp.D, stride), np.int64), np.empty((mp.D, stride), np.int64)
+    rc = lib.fpcopy_eval_one(ctypes.byref(mp.c), ctypes.c_int32(depth), ctypes.c_void_p(w.ctypes.data),
+                             ctypes.c_int32(stride), ctypes.c_void_p(ms.ctypes.data), ctypes.c_void_p(idle.ctypes.data),
+                             ctypes.c_void_p(peak.ctypes.data), ctypes.c_void_p(fl.ctypes.data),
+                             ctypes.c_void_p(st.ctypes.data), ctypes.c_void_p(fi.ctypes.data))
+    if rc:
+        raise ValueError("fpcopyoracle: invalid problem description or depth")
     return dict(makespan=int(ms[0]), idle=idle, peak=peak, flags=int(fl[0]), start=st, finish=fi)

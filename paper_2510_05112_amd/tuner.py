@@ -131,6 +131,96 @@ def tune(handle, problem, circular: bool, k: int = 8, inflight_options=None, for
                  slid=bool(i >= n)) for i, t in zip(idx, ms)]
 
 
+# ---- shared stages: the weight-gradient synchronisation of the bidirectional placement ----------------
+
+def shared_stage_sync(problem, replica_stage, sync_cost):
+    """A placement that holds every model stage on two actors (the bidirectional strategy, Section 4.1: a
+    stage shared among actors) trains ONE model only if the holders of a stage add up their weight
+    gradients before the optimizer step: where the scheduler meets a shared stage it inserts a
+    synchronisation instruction.  In the library's terms (``Problem.set_sync``) that is, per holder of a
+    shared model stage, a synchronisation stage on the holder's device with ONE item for all micro-batches
+    (group m) whose forward item is the exchange (cost ``sync_cost[model stage]``; its backward and
+    weight-gradient items cost nothing), and dependency pairs that let it start only when the last
+    gradient-producing items (W, or B without split backward) of EVERY holder of that model stage have
+    finished.  replica_stage[s]: the model stage that scheduler stage s is a copy of (``bidirectional``'s
+    third result).  Returns (problem with the synchronisation stages appended, group, pairs); the first
+    stages, their chunk numbers and so every op word of the original problem stay valid."""
+    from types import SimpleNamespace
+    S, D, m = int(problem.n_stages), int(problem.n_devices), int(problem.n_microbatches)
+    dev = [int(x) for x in problem.stage_device]
+    holders = {}
+    for s, model_stage in enumerate(replica_stage):
+        holders.setdefault(int(model_stage), []).append(s)
+    shared = {ms: hs for ms, hs in holders.items() if len(hs) > 1}
+    last = 3 if problem.has_w else 2          # the kind whose items produce the weight gradients
+    new_dev, pairs = [], []
+    dur = np.asarray(problem.dur, np.int32).reshape(8, S)
+    extra = np.zeros((8, sum(len(hs) for hs in shared.values())), np.int32)
+    for ms in sorted(shared):
+        for s in shared[ms]:
+            q = S + len(new_dev)
+            extra[1, len(new_dev)] = extra[7, len(new_dev)] = extra[4, len(new_dev)] = int(sync_cost[ms])
+            new_dev.append(dev[s])
+            pairs += [(last, other, 1, q, 0) for other in shared[ms]]
+    if max(np.bincount(dev + new_dev, minlength=D)) > 4:
+        raise ValueError("more than four stages on a device")
+    out = SimpleNamespace(
+        n_devices=D, n_stages=S + len(new_dev), n_microbatches=m, has_w=int(problem.has_w),
+        stage_device=np.asarray(dev + new_dev, np.int32), edge_src=np.asarray(problem.edge_src, np.int32),
+        edge_dst=np.asarray(problem.edge_dst, np.int32), edge_comm=np.asarray(problem.edge_comm, np.int32),
+        dur=np.concatenate([dur, extra], axis=1),
+        mem_units=np.concatenate([np.asarray(problem.mem_units, np.int32), np.zeros(len(new_dev), np.int32)]),
+        mem_cap=np.asarray(problem.mem_cap, np.int32), name=getattr(problem, "name", "") + "+grad-sync")
+    group = np.asarray([1] * S + [m] * len(new_dev), np.int32)
+    return out, group, np.asarray(pairs, np.int32).reshape(-1, 5)
+
+
+def append_sync_items(ops, problem, shared_problem):
+    """ops: CUDA int16 tensor [n][D][stride] of schedules for `problem`, END-padded in full (what
+    ``Problem.generate`` writes).  Appends, at the end of every device's list, the items of the
+    synchronisation stages that ``shared_stage_sync`` put on that device (forward, backward and, with split
+    backward, weight gradient of item 0, stage by stage).  Returns a new tensor whose stride has room."""
+    import torch
+    S = int(problem.n_stages)
+    dev = np.asarray(shared_problem.stage_device)
+    D = int(problem.n_devices)
+    kinds = (1, 2, 3) if problem.has_w else (1, 2)
+    tails = []
+    for d in range(D):
+        on_d = [s for s in range(int(shared_problem.n_stages)) if dev[s] == d]
+        tails.append([(k << 13) | (on_d.index(q) << 11) for q in on_d if q >= S for k in kinds])
+    width = max(len(t) for t in tails)
+    n, _, stride = ops.shape
+    new_stride = -(-(stride + width) // 8) * 8
+    out = torch.zeros((n, D, new_stride), dtype=ops.dtype, device=ops.device)
+    out[:, :, :stride] = ops
+    length = (ops != 0).sum(dim=2)                                   # [n][D]: items listed per device
+    for d in range(D):
+        for i, word in enumerate(tails[d]):
+            signed = word - 65536 if word >= 32768 and ops.dtype == torch.int16 else word
+            out[:, d, :].scatter_(1, (length[:, d] + i).unsqueeze(1), torch.full((n, 1), signed, dtype=ops.dtype, device=ops.device))
+    return out
+
+
+def tune_shared(gen_handle, sync_handle, problem, shared_problem, k: int = 8, inflight_options=None,
+                forward_first: bool = False):
+    """``tune`` for a placement with shared stages: the schedules are generated for `problem` (two separate
+    chains, ``gen_handle``), the inserted synchronisation items are appended, and the lists are timed and
+    ranked under the synchronisation model (``sync_handle``: a handle of ``shared_problem`` on which
+    ``set_sync`` was called with ``shared_stage_sync``'s group and pairs).  Returns the k best as ``tune``
+    does."""
+    import torch
+    labels, pol, inf = grid(problem, False, inflight_options, forward_first)
+    out = gen_handle.generate(torch.from_numpy(pol).cuda(), torch.from_numpy(inf).cuda(), stride_for(problem))
+    ops = append_sync_items(out["ops"], problem, shared_problem)
+    res = sync_handle.evaluate(ops)
+    top = sync_handle.topk(res, min(k, 1024))
+    torch.cuda.synchronize()
+    cnt = int(top["count"].item())
+    idx, ms = top["idx"].cpu().numpy()[:cnt], top["makespan"].cpu().numpy()[:cnt]
+    return [dict(label=labels[int(i)], makespan=int(t), index=int(i), slid=False) for i, t in zip(idx, ms)]
+
+
 def stride_for(problem) -> int:
     """Row stride (words, multiple of 8) that holds the longest list the generator can emit."""
     per_dev = int(np.bincount(np.asarray(problem.stage_device), minlength=int(problem.n_devices)).max())

@@ -145,3 +145,94 @@ def test_gpu_search_under_the_other_cost_models_matches_the_oracles(variant):
         assert [(b["index"], b["slid"], b["makespan"]) for b in best] == [(int(i) % n, bool(i >= n), int(t)) for i, t in zip(idx[:cnt], top_ms[:cnt])]
         assert any(b["slid"] for b in best)
     h.close()
+
+
+def shared(p, m_per_replica, seed=0):
+    prob = bidirectional_problem(p, m_per_replica, seed)
+    _, _, copy_of = tuner.bidirectional(p)
+    cost = np.arange(5, 5 + p)
+    return (prob, copy_of) + tuner.shared_stage_sync(prob, copy_of, cost)
+
+
+def append_on_host(words, prob, big):
+    """numpy twin of tuner.append_sync_items"""
+    S, D = prob.n_stages, prob.n_devices
+    dev = list(big.stage_device)
+    out = np.zeros(words.shape[:2] + (words.shape[2] + 8,), np.uint16)
+    out[:, :, :words.shape[2]] = words
+    for d in range(D):
+        on_d = [s for s in range(big.n_stages) if dev[s] == d]
+        tail = [(k << 13) | (on_d.index(q) << 11) for q in on_d if q >= S for k in (1, 2, 3)]
+        for c in range(len(words)):
+            n = int((words[c, d] != 0).sum())
+            out[c, d, n:n + len(tail)] = tail
+    return out
+
+
+def test_shared_stages_get_a_synchronisation_after_the_last_weight_gradient_of_every_holder():
+    p, m = 4, 6
+    prob, copy_of, big, group, pairs = shared(p, m)
+    # one synchronisation stage per holder, on the holder's device, one item for all micro-batches
+    assert big.n_stages == 4 * p and list(big.stage_device[2 * p:]) == [0, 3, 1, 2, 2, 1, 3, 0]
+    assert list(group) == [1] * (2 * p) + [m] * (2 * p) and len(pairs) == 4 * p
+    assert all(k1 == W and k2 == F and lat == 0 for k1, _, k2, _, lat in pairs)
+    assert {(int(a), int(q)) for _, a, _, q, _ in pairs if q == 2 * p} == {(0, 2 * p), (p, 2 * p)}
+    assert list(big.dur[F][2 * p:]) == [5, 5, 6, 6, 7, 7, 8, 8] and not big.dur[B][2 * p:].any() and not big.mem_units[2 * p:].any()
+    # the timing: schedules of the two-chain problem keep their times, every synchronisation starts when its
+    # device is free and the last weight gradient of both holders of its model stage is computed
+    labels, pol, inf = tuner.grid(prob, circular=False)
+    st = tuner.stride_for(prob)
+    words = oracle.generate(prob, pol, inf, st)["words"]
+    full = append_on_host(words, prob, big)
+    res = oracle.evaluate_sync(big, full, group, pairs)
+    assert not (res["flags"] & 3).any()
+    for c in (0, 3, len(words) - 1):
+        plain = oracle.evaluate_trace(prob, words[c])
+        tr = oracle.evaluate_sync_trace(big, full[c], group, pairs)
+        k, ch, j = oracle.decode(words[c])
+        dev = list(prob.stage_device)
+        stages_of = [[s for s in range(prob.n_stages) if dev[s] == d] for d in range(p)]
+        last_w = {}
+        for d in range(p):
+            for i in range(st):
+                if k[d, i] == W:
+                    s = stages_of[d][ch[d, i]]
+                    last_w[copy_of[s]] = max(last_w.get(copy_of[s], 0), int(plain["finish"][d, i]))
+        expect = 0
+        for d in range(p):
+            n = int((words[c, d] != 0).sum())
+            assert np.array_equal(tr["finish"][d, :n], plain["finish"][d, :n])
+            t = int(plain["finish"][d, :n].max())
+            for model_stage in sorted([d, p - 1 - d]):  # its two synchronisation stages, in stage order
+                t = max(t, last_w[model_stage]) + 5 + model_stage
+            expect = max(expect, t)
+        assert tr["makespan"] == expect > plain["makespan"]
+    # without the synchronisation items in the lists the model is incomplete, not silently two models
+    short = np.zeros_like(full)
+    short[:, :, :st] = words
+    assert (oracle.evaluate_sync(big, short, group, pairs)["flags"] == oracle.FLAG_INCOMPLETE).all()
+
+
+@pytest.mark.gpu
+def test_gpu_search_with_shared_stages_matches_the_oracles():
+    import paper_2510_05112_amd as fp
+    import torch
+    for p, m in ((4, 6), (3, 5)):
+        prob, copy_of, big, group, pairs = shared(p, m, seed=p)
+        st = tuner.stride_for(prob)
+        gen = fp.Problem(prob, st, device=0)
+        ev = fp.Problem(big, st + 8, device=0)
+        ev.set_sync(group, pairs)
+        best = tuner.tune_shared(gen, ev, prob, big, k=6)
+        labels, pol, inf = tuner.grid(prob, circular=False)
+        words = oracle.generate(prob, pol, inf, st)["words"]
+        ref = oracle.evaluate_sync(big, append_on_host(words, prob, big), group, pairs)
+        idx, ms, cnt = oracle.topk(ref["makespan"], ref["flags"], 6)
+        assert cnt > 0 and [(b["index"], b["makespan"]) for b in best] == [(int(i), int(t)) for i, t in zip(idx[:cnt], ms[:cnt])]
+        # the appended lists on the GPU are the host's
+        out = gen.generate(torch.from_numpy(pol).cuda(), torch.from_numpy(inf).cuda(), st)
+        ops = tuner.append_sync_items(out["ops"], prob, big)
+        torch.cuda.synchronize()
+        assert np.array_equal(ops.cpu().numpy().view(np.uint16), append_on_host(words, prob, big))
+        gen.close()
+        ev.close()
