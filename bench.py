@@ -433,6 +433,9 @@ def main() -> int:
     ap.add_argument("--links", action="store_true",
                     help="evaluate, search and wslide modes: the link-occupancy variant of the cost model (every ordered pair of "
                          "devices carries one value at a time) instead of pure latencies")
+    ap.add_argument("--copy-engine", type=int, default=0, metavar="DEPTH",
+                    help="evaluate mode: offload and reload items run on a copy engine that holds at most DEPTH "
+                         "transfers (1..7) instead of the compute timeline; meant for --config 5")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain elementwise copy of the op batch (a kernel of known HBM "
                          "traffic, used to calibrate rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -478,6 +481,8 @@ def main() -> int:
     if args.mb_costs:
         dur_mb = workloads.microbatch_costs(prob)
         handle.set_microbatch_costs(dur_mb)
+    if args.copy_engine:
+        handle.set_copy_engine(args.copy_engine)
     t0 = time.perf_counter()
     ops = torch.empty((C, D, stride), dtype=torch.int16, device=dev)
     chunk = max(1, (256 << 20) // (D * stride * 2))
@@ -526,8 +531,10 @@ def main() -> int:
     # algorithmic bytes of one evaluation launch: 2 B per op word actually needed, plus the
     # per-candidate outputs (makespan 8 + idle 8D + peak 4D + flags 1)
     alg_bytes = 2 * n_ops + C * (8 + 8 * D + 4 * D + 1)
-    counted = MEASURED_BOTH if args.links and args.mb_costs else MEASURED_LINKS if args.links else MEASURED_MB if args.mb_costs else MEASURED
-    roofline, issue = rooflines(alg_bytes, eval_ms, "fpsched evaluation kernel (eval_slot_kernel)",
+    counted = ({} if args.copy_engine else MEASURED_BOTH if args.links and args.mb_costs else MEASURED_LINKS if args.links
+               else MEASURED_MB if args.mb_costs else MEASURED)
+    roofline, issue = rooflines(alg_bytes, eval_ms, "fpsched evaluation kernel (eval_sync_kernel, copy-engine form)"
+                                if args.copy_engine else "fpsched evaluation kernel (eval_slot_kernel)",
                                 counted.get((f"cfg{spec.index}", C)), units=n_ops)
     flags = res["flags"].cpu().numpy()
     makespan = res["makespan"].cpu().numpy()
@@ -542,7 +549,8 @@ def main() -> int:
         "config": {"workload": f"cfg{spec.index}: {prob.name}, {C} candidates, top-{k}, "
                                f"cap {int(prob.mem_cap[0])} units/device"
                                + (", costs per micro-batch (factors in [1/2, 3/2))" if args.mb_costs else "")
-                               + (", link occupancy" if args.links else ""),
+                               + (", link occupancy" if args.links else "")
+                               + (f", copy engine of depth {args.copy_engine}" if args.copy_engine else ""),
                    "candidates": C, "devices": D, "stages": prob.n_stages,
                    "microbatches": prob.n_microbatches, "ops_per_candidate": n_ops / C,
                    "stride_words": stride, "top_k": k},
@@ -561,10 +569,15 @@ def main() -> int:
 
     if args.check or not args.no_cpu_baseline:
         import oracle  # test infrastructure: parity sample and the reported CPU baseline only
+
+        def oracle_evaluate(w, n_threads):
+            if args.copy_engine:
+                return oracle.evaluate_copy(prob, w, depth=args.copy_engine, threads=n_threads)
+            return oracle.evaluate(prob, w, threads=n_threads, dur_mb=dur_mb, links=args.links)
         if args.check:
             rng = np.random.default_rng(0)
             pick = np.sort(rng.choice(C, min(args.check, C), replace=False))
-            ref = oracle.evaluate(prob, words[pick], threads=threads, dur_mb=dur_mb, links=args.links)
+            ref = oracle_evaluate(words[pick], threads)
             ok = all(np.array_equal(res[n][torch.from_numpy(pick).to(dev)].cpu().numpy(), ref[n])
                      for n in ("makespan", "idle", "peak", "flags"))
             out["parity_sample"] = {"candidates": int(len(pick)), "bit_exact": bool(ok)}
@@ -573,11 +586,11 @@ def main() -> int:
         if not args.no_cpu_baseline:
             n1 = min(C, args.cpu_sample or max(64, int(120e6 // max(1, n_ops // C))))
             t0 = time.perf_counter()
-            oracle.evaluate(prob, words[:n1], threads=1, dur_mb=dur_mb, links=args.links)
+            oracle_evaluate(words[:n1], 1)
             t1 = time.perf_counter() - t0
             nn = min(C, n1 * min(threads, 8))
             t0 = time.perf_counter()
-            oracle.evaluate(prob, words[:nn], threads=threads, dur_mb=dur_mb, links=args.links)
+            oracle_evaluate(words[:nn], threads)
             tn = time.perf_counter() - t0
             out["cpu_baseline"] = {
                 "value": nn / tn, "unit": "schedules/s", "cores": threads, "kind": "oracle",

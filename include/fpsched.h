@@ -202,6 +202,32 @@ typedef struct {
 int fpsched_problem_set_sync(fpsched_problem *p, const int32_t *group, int32_t n_pairs,
                              const fpsched_dependency *pairs);
 
+/* Variant of the cost model: a copy engine for offload and reload items.  The paper names CPU offloading
+ * among the memory optimisations of pipeline schedules (Section 8) and does not say how an offload is
+ * timed; fpsched_evaluate runs O and L items on the device's compute timeline like any other item.
+ * With depth >= 1 they run on a copy timeline of the device, beside the computation:
+ *   - each timeline is serial and keeps the order of the device's list; the walk through the list
+ *     hands a transfer to the copy engine when it reaches it (every compute item in front of it has
+ *     finished) and goes on at once; the engine holds at most `depth` unfinished transfers, and a
+ *     walk that reaches a transfer while `depth` are unfinished waits for the oldest of them;
+ *   - a transfer starts at max(hand-over, finish of the transfer before it) and takes
+ *     dur[kind][stage]; a backward item starts no earlier than the finish of the reload of its
+ *     activation; the activation state machine follows the list order as before;
+ *   - memory is counted over time: +units at the start of F, FD, R, L, -units at the end of FD, O
+ *     and W (B without split backward); peak[d] is the largest running sum over the device's events
+ *     in time order, the compute timeline's events first at equal times;
+ *   - makespan = the latest finish on either timeline; idle[d] = makespan - the costs of d's compute
+ *     items.  Flags, sentinels and ranking are unchanged.  Lists without O and L items are timed
+ *     exactly as before.
+ * depth == 0 switches back; 1 <= depth <= FPSCHED_MAX_COPY_DEPTH.  FPSCHED_EINVAL if depth is out of
+ * range or some stage has dur[O] < 1 or dur[L] < 1 (a transfer takes time); FPSCHED_EUNSUPPORTED if
+ * the tables do not fit LDS or while costs per micro-batch, link occupancy or fpsched_problem_set_sync
+ * are in force (and those setters, fpsched_wslide answer FPSCHED_EUNSUPPORTED while this is): the
+ * handle keeps what it had.  Synchronous; allocates one table of device memory at most; works on a
+ * host-only handle (validation only). */
+#define FPSCHED_MAX_COPY_DEPTH 7
+int fpsched_problem_set_copy_engine(fpsched_problem *p, int32_t depth);
+
 /* DEVICE buffers the caller owns (e.g. torch tensors); all must hold n_cand entries. */
 typedef struct {
   int64_t *makespan; /* [C]     max finish time over all devices                          */

@@ -67,6 +67,8 @@ def load_library():
         lib.fpsched_problem_set_link_occupancy.argtypes = [vp, i32]
         lib.fpsched_problem_set_sync.restype = ctypes.c_int
         lib.fpsched_problem_set_sync.argtypes = [vp, vp, i32, vp]
+        lib.fpsched_problem_set_copy_engine.restype = ctypes.c_int
+        lib.fpsched_problem_set_copy_engine.argtypes = [vp, i32]
         lib.fpsched_problem_select_kernel.restype = ctypes.c_int
         lib.fpsched_problem_select_kernel.argtypes = [vp, ctypes.c_int]
         lib.fpsched_workspace_bytes.restype = ctypes.c_size_t
@@ -203,6 +205,13 @@ class Problem:
                                                      prs.ctypes.data if len(prs) else None)
         if rc != 0:
             raise FpschedError(rc, "fpsched_problem_set_sync")
+
+    def set_copy_engine(self, depth: int = 4):
+        """Offload and reload items run on a copy engine that holds at most ``depth`` transfers
+        (see fpsched_problem_set_copy_engine); 0 switches back."""
+        rc = load_library().fpsched_problem_set_copy_engine(self._h, int(depth))
+        if rc != 0:
+            raise FpschedError(rc, "fpsched_problem_set_copy_engine")
 
     # ---- host helpers -----------------------------------------------------
     def encode(self, items, device: int) -> np.ndarray:

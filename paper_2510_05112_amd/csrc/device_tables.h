@@ -106,6 +106,7 @@ struct SyncTables {
   int32_t lanes_per_cand;   // power of two >= D
   int32_t cands_per_wave;   // limited by LDS
   int32_t n_fin_tables;     // 2, or 3 if some pair waits for a weight-gradient item
+  int32_t copy_depth;       // copy-engine form: transfers the engine holds at most (1..7), else 0
   int32_t n_table_ints;     // length of `ints`
   // offsets (in int32 units) into `ints`
   int32_t off_dur;          // [kNKinds][S]

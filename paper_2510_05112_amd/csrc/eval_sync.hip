@@ -17,6 +17,19 @@
 //
 // Start rule: start = max(device free, finish of every item waited for + latency if it ran on another
 // device); finish = start + dur[kind][stage].
+//
+// COPY = true is the copy-engine form of the cost model (the paper names CPU offloading without saying
+// how an offload is timed; in the plain model offload and reload items run on the compute timeline):
+// offload (O) and reload (L) items run on a copy timeline of their own.  The walk through the list hands
+// such an item to the engine when it reaches it and goes on at once, unless `copy_depth` transfers are
+// still unfinished: then it waits for the oldest of them.  A transfer starts at max(hand-over, finish of
+// the transfer before it); a backward item waits for the reload of its activation (a table of its own);
+// the makespan covers both timelines; the costs of transfers are not busy time.  Memory becomes a sum over
+// events in time order (allocations at the start of F, FD, R, L; releases at the end of FD, O, W or B);
+// at equal times the compute timeline's events come first.  The walk produces compute events in time
+// order and knows every transfer's event time at hand-over, so a lane keeps the transfer events that lie
+// ahead of the walk in a small ring (at most copy_depth + 1: transfers cost at least 1) and applies them
+// as the walk passes their time.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -24,6 +37,7 @@
 
 namespace fpsched {
 
+template <bool COPY>
 __global__ __launch_bounds__(64) void eval_sync_kernel(
     SyncTables T, const uint16_t* __restrict__ ops, long long n_cand, int stride,
     long long* __restrict__ out_makespan, long long* __restrict__ out_idle,
@@ -32,7 +46,8 @@ __global__ __launch_bounds__(64) void eval_sync_kernel(
   const int lane = threadIdx.x;
   const int S = T.S, m = T.m, SM = S * m;
   const int fin_ints = T.n_fin_tables * SM;
-  const int per_cand_ints = fin_ints + ((SM + 3) >> 2);
+  // COPY: behind the finish times, the time each activation became resident again (0 = never reloaded)
+  const int per_cand_ints = fin_ints + (COPY ? SM : 0) + ((SM + 3) >> 2);
   const int cpw = T.cands_per_wave;
   const int lpc = T.lanes_per_cand;
   const int lpc_shift = __ffs(lpc) - 1;
@@ -42,7 +57,7 @@ __global__ __launch_bounds__(64) void eval_sync_kernel(
   for (int c = 0; c < cpw; ++c) {
     int32_t* p = cand_base + c * per_cand_ints;
     for (int i = lane; i < fin_ints; i += 64) p[i] = -1;
-    for (int i = fin_ints + lane; i < per_cand_ints; i += 64) p[i] = 0;
+    for (int i = fin_ints + lane; i < per_cand_ints; i += 64) p[i] = 0;   // reload times, states
   }
   __syncthreads();
 
@@ -52,7 +67,15 @@ __global__ __launch_bounds__(64) void eval_sync_kernel(
   const long long cand = (long long)blockIdx.x * cpw + seg;
   const bool active = (seg < cpw) && (d < T.D) && (cand < n_cand);
   int32_t* fin = cand_base + (seg < cpw ? seg : 0) * per_cand_ints;   // [table][stage][item]
-  unsigned char* state = reinterpret_cast<unsigned char*>(fin + fin_ints);
+  int32_t* resident_at = fin + fin_ints;
+  unsigned char* state = reinterpret_cast<unsigned char*>(fin + fin_ints + (COPY ? SM : 0));
+  // COPY: per lane, behind all candidates' tables: the finish times of the last eight transfers and a ring
+  // of eight pending memory events (time, units), each [entry][lane]
+  int32_t* copy_fin = cand_base + cpw * per_cand_ints + lane;
+  int32_t* ev_time = copy_fin + 8 * 64;
+  int32_t* ev_units = ev_time + 8 * 64;
+  int copy_free = 0, n_copy = 0;
+  unsigned ev_head = 0, ev_tail = 0;
 
   const int dd = active ? d : 0;
   const int nch = tab[T.off_n_chunks + dd];
@@ -80,6 +103,14 @@ __global__ __launch_bounds__(64) void eval_sync_kernel(
   int cursor = 0, free_at = 0, busy = 0, mem = 0, pk = 0, n_term = 0;
   bool done = !active, bad = false, seg_live = true;
   unsigned w = active ? word_at(0) : 0u;
+  // COPY: apply the pending transfer events that come before a compute event at time `limit`
+  auto pass_time = [&](int limit) {
+    while (ev_head != ev_tail && ev_time[(ev_head & 7u) * 64] < limit) {
+      mem += ev_units[(ev_head & 7u) * 64];
+      pk = max(pk, mem);
+      ++ev_head;
+    }
+  };
 
   for (;;) {
     bool progressed = false;
@@ -88,6 +119,7 @@ __global__ __launch_bounds__(64) void eval_sync_kernel(
       if (kind == kEnd) {
         done = true;
         progressed = true;
+        if (COPY) pass_time(0x7fffffff);
       } else {
         const int c = (w >> 11) & 3, g = w & 0x7ff;
         const int s = c < nch ? tab[T.off_local_stage + d * kMaxChunks + c] : 0;
@@ -119,22 +151,47 @@ __global__ __launch_bounds__(64) void eval_sync_kernel(
                 }
               }
             }
-            if (!blocked) {
+            if (COPY && kind == kB) ready = max(ready, resident_at[idx]);
+            if (!blocked && COPY && (kind == kO || kind == kL)) {
+              // a transfer: hand it over (waiting for room in the engine), time it on the copy timeline
+              const int dt = tab[T.off_dur + kind * S + s];
+              const int u = tab[T.off_mem_units + s];
+              int handover = free_at;
+              if (n_copy >= T.copy_depth) handover = max(handover, copy_fin[((unsigned)(n_copy - T.copy_depth) & 7u) * 64]);
+              const int start = max(handover, copy_free);
+              copy_free = start + dt;
+              copy_fin[((unsigned)n_copy & 7u) * 64] = copy_free;
+              ++n_copy;
+              free_at = handover;
+              pass_time(handover);
+              ev_time[(ev_tail & 7u) * 64] = kind == kL ? start : copy_free;
+              ev_units[(ev_tail & 7u) * 64] = kind == kL ? u : -u;
+              ++ev_tail;
+              if (kind == kL) resident_at[idx] = copy_free;
+              state[idx] = (unsigned char)((0x21315410u >> (4 * kind)) & 0xf);
+            } else if (!blocked) {
               const int dt = tab[T.off_dur + kind * S + s];
               const int u = tab[T.off_mem_units + s];
               const int finish = max(free_at, ready) + dt;
               if ((0xD2u >> kind) & 1u) {  // F, R, L, FD allocate at their start
+                if (COPY) pass_time(finish - dt);
                 mem += u;
                 pk = max(pk, mem);
               }
-              if ((free_mask >> kind) & 1u) mem -= u;
+              if ((free_mask >> kind) & 1u) {
+                if (COPY) pass_time(finish);
+                mem -= u;
+              }
               state[idx] = (unsigned char)((0x21315410u >> (4 * kind)) & 0xf);
               if (kind == kF || kind == kFD) fin[idx] = finish;
               else if (kind == kB) fin[SM + idx] = finish;
               else if (kind == kW && T.n_fin_tables > 2) fin[2 * SM + idx] = finish;
-              n_term += (kind == terminal_kind);
               free_at = finish;
               busy += dt;
+              if (COPY) pass_time(finish);
+            }
+            if (!blocked) {
+              n_term += (kind == terminal_kind);
               ++cursor;
               if ((cursor & 7) == 0) {
                 cur = nxt;
@@ -157,7 +214,7 @@ __global__ __launch_bounds__(64) void eval_sync_kernel(
   const unsigned long long stuck_bad = __ballot(active && !done && bad) & seg_mask;
   const unsigned long long unfinished = __ballot(active && n_term != n_expected) & seg_mask;
   const unsigned long long over = __ballot(active && pk > cap) & seg_mask;
-  int ms = active ? free_at : 0;
+  int ms = active ? (COPY ? max(free_at, copy_free) : free_at) : 0;
   for (int off = 1; off < lpc; off <<= 1) ms = max(ms, __shfl_xor(ms, off, 64));
 
   unsigned fl = 0;
@@ -174,5 +231,10 @@ __global__ __launch_bounds__(64) void eval_sync_kernel(
     }
   }
 }
+
+template __global__ void eval_sync_kernel<false>(SyncTables, const uint16_t*, long long, int, long long*, long long*,
+                                                 int*, unsigned char*);
+template __global__ void eval_sync_kernel<true>(SyncTables, const uint16_t*, long long, int, long long*, long long*,
+                                                int*, unsigned char*);
 
 }  // namespace fpsched

@@ -70,6 +70,7 @@ struct fpsched_problem {
   int32_t links_waves = 0, links_grid = 0, links_lds_bytes = 0;
   // synchronisation stages and dependency pairs (fpsched_problem_set_sync)
   bool sync_on = false;
+  int32_t copy_depth = 0;               // copy-engine form (fpsched_problem_set_copy_engine), 0 = off
   std::vector<int32_t> sync_items;      // [S] items per kind of each stage (m while the model is off)
   SyncTables sync_tab{};
   int32_t* d_sync_ints = nullptr;
@@ -606,11 +607,11 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
   if (reinterpret_cast<uintptr_t>(d_ops) & 15) return FPSCHED_EINVAL;
   DeviceGuard g(p->device_id);
   if (!g.ok) return FPSCHED_EHIP;
-  if (p->sync_on) {
+  if (p->sync_on || p->copy_depth > 0) {
     const int cpw = p->sync_tab.cands_per_wave;
     const int64_t blocks = (n_cand + cpw - 1) / cpw;
     if (blocks > 0x7fffffffll) return FPSCHED_EINVAL;
-    hipLaunchKernelGGL(eval_sync_kernel, dim3((unsigned)blocks), dim3(64), (size_t)p->sync_lds_bytes,
+    hipLaunchKernelGGL(p->copy_depth > 0 ? eval_sync_kernel<true> : eval_sync_kernel<false>, dim3((unsigned)blocks), dim3(64), (size_t)p->sync_lds_bytes,
                        static_cast<hipStream_t>(hip_stream), p->sync_tab, d_ops, (long long)n_cand,
                        (int)stride_words, reinterpret_cast<long long*>(out.makespan),
                        reinterpret_cast<long long*>(out.idle), out.peak, out.flags);
@@ -725,7 +726,7 @@ int fpsched_problem_set_microbatch_costs(fpsched_problem* p, const int32_t* dur_
     p->mb_set = false;   // the tables stay allocated for the next call
     return FPSCHED_OK;
   }
-  if (p->sync_on) return FPSCHED_EUNSUPPORTED;   // the synchronisation model knows one cost per (type, stage)
+  if (p->sync_on || p->copy_depth > 0) return FPSCHED_EUNSUPPORTED;   // those models know one cost per (type, stage)
   const int D = p->D, S = p->S, m = p->m;
   const size_t n_raw = (size_t)kNKinds * S * m;
   int64_t max_dur = 0;
@@ -861,7 +862,7 @@ int fpsched_problem_set_link_occupancy(fpsched_problem* p, int32_t on) {
     p->links_on = false;   // the table image stays allocated for the next call
     return FPSCHED_OK;
   }
-  if (p->sync_on) return FPSCHED_EUNSUPPORTED;   // the synchronisation model reads transfers as latencies
+  if (p->sync_on || p->copy_depth > 0) return FPSCHED_EUNSUPPORTED;   // those models read transfers as latencies
   const int D = p->D, S = p->S;
   // every finish time is at most the sum of all costs and of all transfers (at most two per op here)
   const int64_t bound = (int64_t)D * p->max_stride * ((p->mb_set ? p->mb_max_dur : p->max_dur) + 2 * p->max_comm);
@@ -1013,46 +1014,12 @@ int fpsched_problem_set_link_occupancy(fpsched_problem* p, int32_t on) {
   return FPSCHED_OK;
 }
 
-int fpsched_problem_set_sync(fpsched_problem* p, const int32_t* group, int32_t n_pairs,
-                             const fpsched_dependency* pairs) {
-  if (!p || n_pairs < 0 || (n_pairs > 0 && !pairs)) return FPSCHED_EINVAL;
+// The table image and workgroup shape of eval_sync_kernel for one setting of the handle: groups and pairs
+// (fpsched_problem_set_sync) or the copy-engine form (fpsched_problem_set_copy_engine, copy_depth > 0).
+// On success the handle's table is replaced; on failure the handle is back on the plain model.
+static int install_table_model(fpsched_problem* p, const std::vector<int32_t>& grp, const std::vector<int32_t>& items,
+                               int32_t n_pairs, const fpsched_dependency* pairs, bool wants_w, int copy_depth) {
   const int D = p->D, S = p->S, m = p->m;
-  bool trivial = n_pairs == 0;
-  for (int s = 0; s < S && group; ++s) {
-    if (group[s] < 1) return FPSCHED_EINVAL;
-    if (group[s] != 1) trivial = false;
-  }
-  if (trivial) {   // back to the plain model; the table stays allocated for the next call
-    p->sync_on = false;
-    p->sync_items.assign(S, m);
-    return FPSCHED_OK;
-  }
-  if (p->mb_set || p->links_on) return FPSCHED_EUNSUPPORTED;
-  int64_t max_lat = p->max_comm;
-  bool wants_w = false;
-  for (int i = 0; i < n_pairs; ++i) {
-    const fpsched_dependency& q = pairs[i];
-    if (q.kind_from != FPSCHED_F && q.kind_from != FPSCHED_B && q.kind_from != FPSCHED_W) return FPSCHED_EINVAL;
-    if (q.kind_to <= FPSCHED_END || q.kind_to >= FPSCHED_NKINDS) return FPSCHED_EINVAL;
-    if ((q.kind_from == FPSCHED_W || q.kind_to == FPSCHED_W) && !p->has_w) return FPSCHED_EINVAL;
-    if (q.stage_from < 0 || q.stage_from >= S || q.stage_to < 0 || q.stage_to >= S || q.latency < 0) return FPSCHED_EINVAL;
-    if (q.stage_from == q.stage_to && (q.kind_from == q.kind_to || (q.kind_from == FPSCHED_F && q.kind_to == FPSCHED_FD)))
-      return FPSCHED_EINVAL;
-    max_lat = std::max<int64_t>(max_lat, q.latency);
-    wants_w = wants_w || q.kind_from == FPSCHED_W;
-  }
-  if ((int64_t)D * p->max_stride * (p->max_dur + max_lat) >= (int64_t)1 << 31) return FPSCHED_EOVERFLOW;
-  std::vector<int32_t> grp(S, 1), items(S, m);
-  for (int s = 0; s < S; ++s) {
-    grp[s] = group ? std::min(group[s], m) : 1;
-    items[s] = (m + grp[s] - 1) / grp[s];
-  }
-  if (p->device_id < 0) {
-    p->sync_items = items;
-    p->sync_on = true;
-    return FPSCHED_OK;
-  }
-  // table image: the plain tables' rows that are needed, the groups, one dependency list per (kind, stage)
   const std::vector<int32_t>& I = p->host_ints;
   const DevTables& T = p->tables;
   std::vector<int32_t> J;
@@ -1060,11 +1027,13 @@ int fpsched_problem_set_sync(fpsched_problem* p, const int32_t* group, int32_t n
   ST.D = D; ST.S = S; ST.m = m; ST.has_w = p->has_w;
   ST.lanes_per_cand = T.lanes_per_cand;
   ST.n_fin_tables = wants_w ? 3 : 2;
+  ST.copy_depth = copy_depth;
   auto append = [&](const int32_t* src, size_t n) { const int32_t off = (int32_t)J.size(); J.insert(J.end(), src, src + n); return off; };
   ST.off_dur = append(&I[T.off_dur], (size_t)kNKinds * S);
   ST.off_mem_units = append(&I[T.off_mem_units], S);
   ST.off_group = append(grp.data(), S);
   ST.off_items = append(items.data(), S);
+  // one dependency list per (kind, stage): the edges of the stage DAG, then the pairs
   std::vector<int32_t> dep_off((size_t)kNKinds * S + 1, 0), dep;
   for (int kind = 0; kind < kNKinds; ++kind)
     for (int s = 0; s < S; ++s) {
@@ -1092,40 +1061,105 @@ int fpsched_problem_set_sync(fpsched_problem* p, const int32_t* group, int32_t n
   ST.off_n_chunks = append(p->n_chunks.data(), D);
   ST.off_mem_cap = append(&I[T.off_mem_cap], D);
   ST.n_table_ints = (int32_t)J.size();
-  // candidates per wavefront: whole finish-time tables and state bytes of each in LDS
+  // candidates per wavefront: whole finish-time tables (and reload times) and state bytes of each in LDS;
+  // the copy-engine form adds three rings of eight dwords per lane
   const int64_t SM = (int64_t)S * m;
-  const int64_t per_cand = 4 * (ST.n_fin_tables * SM + ((SM + 3) >> 2));
-  const int64_t table_bytes = 4ll * ST.n_table_ints;
+  const int64_t per_cand = 4 * ((ST.n_fin_tables + (copy_depth > 0 ? 1 : 0)) * SM + ((SM + 3) >> 2));
+  const int64_t fixed_bytes = 4ll * ST.n_table_ints + (copy_depth > 0 ? 3 * 8 * 64 * 4 : 0);
   int cpw = 64 / ST.lanes_per_cand;
-  while (cpw > 1 && table_bytes + cpw * per_cand > p->max_lds) cpw >>= 1;
-  if (table_bytes + cpw * per_cand > p->max_lds) return FPSCHED_EUNSUPPORTED;
+  while (cpw > 1 && fixed_bytes + cpw * per_cand > p->max_lds) cpw >>= 1;
+  if (fixed_bytes + cpw * per_cand > p->max_lds) return FPSCHED_EUNSUPPORTED;
   ST.cands_per_wave = cpw;
   DeviceGuard g(p->device_id);
   if (!g.ok) return FPSCHED_EHIP;
   if (hipDeviceSynchronize() != hipSuccess) return FPSCHED_EHIP;   // an earlier table may be in use
+  auto back_to_plain = [&]() {
+    p->sync_on = false;
+    p->copy_depth = 0;
+    p->sync_items.assign(S, m);
+  };
   if (J.size() > p->sync_ints_capacity) {
     int32_t* fresh = nullptr;
     if (hipMalloc(&fresh, J.size() * sizeof(int32_t)) != hipSuccess) { (void)hipGetLastError(); return FPSCHED_ENOMEM; }
     if (p->d_sync_ints) (void)hipFree(p->d_sync_ints);
     p->d_sync_ints = fresh;
     p->sync_ints_capacity = J.size();
-    if (p->sync_on) {   // the table it ran on is gone
-      p->sync_on = false;
-      p->sync_items.assign(S, m);
-    }
+    back_to_plain();   // the table the handle ran on is gone
   }
   if (hipMemcpy(p->d_sync_ints, J.data(), J.size() * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess ||
-      hipFuncSetAttribute(reinterpret_cast<const void*>(&eval_sync_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+      hipFuncSetAttribute(reinterpret_cast<const void*>(&eval_sync_kernel<false>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          p->max_lds) != hipSuccess ||
+      hipFuncSetAttribute(reinterpret_cast<const void*>(&eval_sync_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize,
                           p->max_lds) != hipSuccess) {
-    p->sync_on = false;
-    p->sync_items.assign(S, m);
+    back_to_plain();
     return FPSCHED_EHIP;
   }
   ST.ints = p->d_sync_ints;
   p->sync_tab = ST;
-  p->sync_lds_bytes = (int32_t)(table_bytes + cpw * per_cand);
+  p->sync_lds_bytes = (int32_t)(fixed_bytes + cpw * per_cand);
+  return FPSCHED_OK;
+}
+
+int fpsched_problem_set_sync(fpsched_problem* p, const int32_t* group, int32_t n_pairs,
+                             const fpsched_dependency* pairs) {
+  if (!p || n_pairs < 0 || (n_pairs > 0 && !pairs)) return FPSCHED_EINVAL;
+  const int D = p->D, S = p->S, m = p->m;
+  bool trivial = n_pairs == 0;
+  for (int s = 0; s < S && group; ++s) {
+    if (group[s] < 1) return FPSCHED_EINVAL;
+    if (group[s] != 1) trivial = false;
+  }
+  if (trivial) {   // back to the plain model; the table stays allocated for the next call
+    if (p->sync_on) p->sync_items.assign(S, m);
+    p->sync_on = false;
+    return FPSCHED_OK;
+  }
+  if (p->mb_set || p->links_on || p->copy_depth > 0) return FPSCHED_EUNSUPPORTED;
+  int64_t max_lat = p->max_comm;
+  bool wants_w = false;
+  for (int i = 0; i < n_pairs; ++i) {
+    const fpsched_dependency& q = pairs[i];
+    if (q.kind_from != FPSCHED_F && q.kind_from != FPSCHED_B && q.kind_from != FPSCHED_W) return FPSCHED_EINVAL;
+    if (q.kind_to <= FPSCHED_END || q.kind_to >= FPSCHED_NKINDS) return FPSCHED_EINVAL;
+    if ((q.kind_from == FPSCHED_W || q.kind_to == FPSCHED_W) && !p->has_w) return FPSCHED_EINVAL;
+    if (q.stage_from < 0 || q.stage_from >= S || q.stage_to < 0 || q.stage_to >= S || q.latency < 0) return FPSCHED_EINVAL;
+    if (q.stage_from == q.stage_to && (q.kind_from == q.kind_to || (q.kind_from == FPSCHED_F && q.kind_to == FPSCHED_FD)))
+      return FPSCHED_EINVAL;
+    max_lat = std::max<int64_t>(max_lat, q.latency);
+    wants_w = wants_w || q.kind_from == FPSCHED_W;
+  }
+  if ((int64_t)D * p->max_stride * (p->max_dur + max_lat) >= (int64_t)1 << 31) return FPSCHED_EOVERFLOW;
+  std::vector<int32_t> grp(S, 1), items(S, m);
+  for (int s = 0; s < S; ++s) {
+    grp[s] = group ? std::min(group[s], m) : 1;
+    items[s] = (m + grp[s] - 1) / grp[s];
+  }
+  if (p->device_id >= 0) {
+    const int rc = install_table_model(p, grp, items, n_pairs, pairs, wants_w, 0);
+    if (rc != FPSCHED_OK) return rc;
+  }
   p->sync_items = items;
   p->sync_on = true;
+  return FPSCHED_OK;
+}
+
+int fpsched_problem_set_copy_engine(fpsched_problem* p, int32_t depth) {
+  if (!p || depth < 0 || depth > FPSCHED_MAX_COPY_DEPTH) return FPSCHED_EINVAL;
+  if (depth == 0) {
+    p->copy_depth = 0;
+    return FPSCHED_OK;
+  }
+  if (p->mb_set || p->links_on || p->sync_on) return FPSCHED_EUNSUPPORTED;
+  // a transfer takes time: with a cost of zero any number of them could end at one instant
+  const std::vector<int32_t>& I = p->host_ints;
+  for (int s = 0; s < p->S; ++s)
+    if (I[p->tables.off_dur + kO * p->S + s] < 1 || I[p->tables.off_dur + kL * p->S + s] < 1) return FPSCHED_EINVAL;
+  if (p->device_id >= 0) {
+    const std::vector<int32_t> grp(p->S, 1), items(p->S, p->m);
+    const int rc = install_table_model(p, grp, items, 0, nullptr, false, depth);
+    if (rc != FPSCHED_OK) return rc;
+  }
+  p->copy_depth = depth;
   return FPSCHED_OK;
 }
 
@@ -1297,7 +1331,7 @@ int fpsched_wslide(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_ca
   if (p->device_id < 0) return FPSCHED_ENODEV;
   if (!p->has_w) return FPSCHED_EINVAL;
   // the pass knows one cost per (type, stage)
-  if (!p->slide_ok || p->mb_set || p->sync_on || (p->links_on && !p->links_slide_ok)) return FPSCHED_EUNSUPPORTED;
+  if (!p->slide_ok || p->mb_set || p->sync_on || p->copy_depth > 0 || (p->links_on && !p->links_slide_ok)) return FPSCHED_EUNSUPPORTED;
   if (n_cand == 0) return FPSCHED_OK;
   if (!d_ops || !d_ops_out || !out.makespan || !out.idle || !out.peak || !out.flags) return FPSCHED_EINVAL;
   if (stride_words < 8 || (stride_words & 7) || stride_words > p->max_stride) return FPSCHED_EINVAL;

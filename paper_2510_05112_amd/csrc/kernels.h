@@ -21,6 +21,9 @@ __global__ void eval_general_kernel(DevTables T, const uint16_t* ops, long long 
 
 // Synchronisation stages and dependency pairs (eval_sync.hip): the table form of the evaluator with one
 // dependency list per (kind, stage) and items that stand for groups of micro-batches.
+// COPY: offload and reload items run on a copy engine beside the computation (T.copy_depth transfers at
+// most in the engine); needs 1536 more dwords of LDS per workgroup and one more table per candidate.
+template <bool COPY>
 __global__ void eval_sync_kernel(SyncTables T, const uint16_t* ops, long long n_cand, int stride,
                                  long long* out_makespan, long long* out_idle, int* out_peak,
                                  unsigned char* out_flags);

@@ -188,3 +188,24 @@ def test_sync_workload_full_batch_every_candidate_against_oracle():
     assert np.array_equal(top["makespan"].cpu().numpy(), r_ms)
     assert (ref["flags"] == 0).mean() > 0.3 and (ref["flags"] & 1).any()
     h.close()
+
+
+def test_copy_engine_full_batch_every_candidate_against_oracle():
+    """Configuration 5 (offload / reload items) under the copy-engine form, the launch
+    `bench.py --config 5 --copy-engine 4` times."""
+    spec = workloads.config(5)
+    words = workloads.generate(spec, threads=16)
+    C = len(words)
+    h = fp.Problem(spec.problem, spec.stride, device=0)
+    h.set_copy_engine(4)
+    ws = h.alloc_workspace(C, spec.top_k)
+    res = h.evaluate(torch.from_numpy(words.view(np.int16)).cuda(), workspace=ws)
+    top = h.topk(res, spec.top_k, workspace=ws)
+    torch.cuda.synchronize()
+    ref = oracle.evaluate_copy(spec.problem, words, depth=4, threads=16)
+    for name in ("flags", "makespan", "idle", "peak"):
+        assert np.array_equal(res[name].cpu().numpy(), ref[name]), name
+    r_idx, r_ms, r_cnt = oracle.topk(ref["makespan"], ref["flags"], spec.top_k)
+    assert int(top["count"].item()) == r_cnt and np.array_equal(top["idx"].cpu().numpy(), r_idx)
+    assert np.array_equal(top["makespan"].cpu().numpy(), r_ms)
+    h.close()
