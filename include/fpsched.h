@@ -329,8 +329,9 @@ int fpsched_rank(const fpsched_problem *p, fpsched_results in, int64_t n_cand, i
  * outputs per stage, see fpsched_problem_info), else FPSCHED_EUNSUPPORTED.  Cost model: the
  * handle's latencies as pure latencies or, after fpsched_problem_set_link_occupancy, as links
  * that carry one value at a time; FPSCHED_EUNSUPPORTED while costs per micro-batch are set.
- * Workspace: fpsched_wslide_workspace_bytes (DEVICE, 16-byte aligned; it holds a start time
- * per op word, i.e. about twice the bytes of the input lists).  Asynchronous on hip_stream. */
+ * Workspace: fpsched_wslide_workspace_bytes (DEVICE, 16-byte aligned; it holds sixteen bits
+ * per op word and lane of a candidate plus a short list per row for the ops that wait 2^16 time
+ * units or more, i.e. about the bytes of the input lists).  Asynchronous on hip_stream. */
 size_t fpsched_wslide_workspace_bytes(const fpsched_problem *p, int64_t n_cand, int32_t stride_words);
 int fpsched_wslide(const fpsched_problem *p, const uint16_t *d_ops, int64_t n_cand,
                    int32_t stride_words, uint16_t *d_ops_out, int32_t stride_out_words,

@@ -106,11 +106,15 @@ __global__ void reset_counter_kernel(unsigned long long* counter, unsigned long 
 
 // MODE kSlotTimes (TIMES below) is the first pass of the weight-gradient sliding (wslide.hip): the tables then
 // describe the lists without their W items (a W word is a no-op that always issues at once), and
-// instead of makespan, idle and peak the kernel writes, per op word, the time the op started
-// (<< 8; four positions of a device are 16 bytes, and the 16-byte pieces of a candidate's devices
-// for the same four positions lie side by side, [candidate][stride / 4][lanes per candidate][4]: the
-// lanes of a candidate pass a position at about the same time, so a line fills up quickly) and,
-// per device, the position at which its list stopped.
+// instead of makespan, idle and peak the kernel writes, per op word, the low sixteen bits of the time
+// the op started (eight positions of a device are 16 bytes, and the 16-byte pieces of a candidate's
+// devices for the same eight positions lie side by side, [candidate][stride / 8][lanes per
+// candidate][8]: the lanes of a candidate pass a position at about the same time, so a line fills up
+// quickly) and, per device, the position at which its list stopped.  The second pass rebuilds a start
+// time from the device's free time in front of the op, which it knows: start = free + ((low - free) mod
+// 2^16).  That is exact while the op waits less than 2^16 time units for its inputs; an op that waits
+// longer -- there are at most (largest possible finish time) / 2^16 of them in a row -- leaves an
+// entry (position << 8 | wait >> 16) in the row's escape list, which ends with an all-ones word.
 //
 // MODE kSlotPerMicrobatch: the cost of an item depends on its micro-batch as well (micro-batches of
 // unequal size).  The duration then comes from mb_rows [32 metadata rows][lanes per candidate][m]
@@ -132,7 +136,8 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     long long* __restrict__ out_makespan, long long* __restrict__ out_idle,
     int* __restrict__ out_peak, unsigned char* __restrict__ out_flags,
     unsigned long long* __restrict__ next_candidate, int draw_block,
-    uint32_t* __restrict__ out_start8, int32_t* __restrict__ out_stop, const int32_t* __restrict__ mb_rows) {
+    uint32_t* __restrict__ out_start8, int32_t* __restrict__ out_stop, const int32_t* __restrict__ mb_rows,
+    uint32_t* __restrict__ out_escape, int escape_cap) {
   constexpr bool TIMES = MODE == kSlotTimes || MODE == kSlotTimesLinks;
   constexpr bool MBDUR = MODE == kSlotPerMicrobatch;
   constexpr bool MBLDS = MODE == kSlotPerMicrobatchLds || MODE == kSlotPerMicrobatchLdsLinks;
@@ -235,9 +240,12 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   bool running = false;  // this lane's segment is evaluating a candidate
   unsigned dead = ~0u;   // 0 while this lane carries a device of a running candidate, else all ones
   bool fresh = true;     // (re)start the segment on `cand` at the top of the next round
-  // TIMES: start times of the last four ops, stored 16 bytes at a time at the ops' positions
+  // TIMES: the low halves of the start times of the last eight ops, stored 16 bytes at a time at the
+  // ops' positions; the row's escape list and its length
   unsigned st0 = 0u, st1 = 0u, st2 = 0u, st3 = 0u;
   uint32_t* start_row = out_start8;
+  uint32_t* esc_row = out_escape;
+  int n_esc = 0;
 
   // LDS addresses of everything a round reads for the current word.  They only change when the
   // lane issues, so they are worked out there, once per op, and a round starts with its reads.
@@ -416,8 +424,12 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
         if (running && lane_ok) {
           for (int i = 0; i < lane_words; ++i) stt[i * 64 + lane] = 0u;
           row = ops + ((size_t)cand * T.D + d) * (size_t)stride;
-          // start times: [candidate][group of four positions][lane of the candidate][4]
-          if (TIMES) start_row = out_start8 + (size_t)cand * (size_t)stride * (size_t)lpc + ((size_t)d << 2);
+          // start times: [candidate][group of eight positions][lane of the candidate][8 x 16 bits]
+          if (TIMES) {
+            start_row = out_start8 + (size_t)cand * ((size_t)stride >> 1) * (size_t)lpc + ((size_t)d << 2);
+            esc_row = out_escape + ((size_t)cand * T.D + d) * (size_t)escape_cap;
+            n_esc = 0;
+          }
           prime0 = *reinterpret_cast<const uint2*>(row);
           prime1 = *reinterpret_cast<const uint2*>(row + kChunk);
           if (prime_words > 8) prime2 = *reinterpret_cast<const uint2*>(row + 2 * kChunk);
@@ -476,10 +488,18 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       const unsigned start8 = max(free_at8, ready8);
       const unsigned fin8 = start8 + dur8;
       if (TIMES) {
-        st0 = st1; st1 = st2; st2 = st3; st3 = start8;
-        // npos = (position of this op + 1) << 7: the fourth op of a group completes it
-        if ((npos & (3u << 7)) == 0u)
-          *reinterpret_cast<uint4*>(start_row + ((size_t)((npos >> 9) - 1u) << (lpc_shift + 2))) = make_uint4(st0, st1, st2, st3);
+        // shift bits 8..23 of the start time (its low half in time units) into the 16 bytes
+        st0 = __builtin_amdgcn_alignbit(st1, st0, 16);
+        st1 = __builtin_amdgcn_alignbit(st2, st1, 16);
+        st2 = __builtin_amdgcn_alignbit(st3, st2, 16);
+        st3 = __builtin_amdgcn_perm(start8, st3, 0x06050302u);
+        // npos = (position of this op + 1) << 7: the eighth op of a group completes it
+        if ((npos & (7u << 7)) == 0u)
+          *reinterpret_cast<uint4*>(start_row + ((size_t)((npos >> 10) - 1u) << (lpc_shift + 2))) = make_uint4(st0, st1, st2, st3);
+        // an op that waited 2^16 time units or more for its inputs cannot be rebuilt from the low half
+        const unsigned wait8 = start8 - free_at8;
+        if ((wait8 >> 24) != 0u && n_esc < escape_cap - 1)
+          esc_row[n_esc++] = (((npos >> 7) - 1u) << 8) | (wait8 >> 24);
       }
       mem += (int)(my_ & 0xffu);
       pk = max(pk, mem);
@@ -564,12 +584,19 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
         else if (over) flg = kOverCap;
         if (TIMES) {
           if (lane_ok) {
-            // the start times of an unfinished group of four, and where the list stopped
+            // the start times of an unfinished group of eight, the end of the escape list, and where
+            // the list stopped
             const unsigned stop = (npos >> 7) - 1u;
-            if (stop & 3u) {
-              for (unsigned i = stop & 3u; i < 4u; ++i) { st0 = st1; st1 = st2; st2 = st3; st3 = 0u; }
-              *reinterpret_cast<uint4*>(start_row + ((size_t)(stop >> 2) << (lpc_shift + 2))) = make_uint4(st0, st1, st2, st3);
+            if (stop & 7u) {
+              for (unsigned i = stop & 7u; i < 8u; ++i) {
+                st0 = __builtin_amdgcn_alignbit(st1, st0, 16);
+                st1 = __builtin_amdgcn_alignbit(st2, st1, 16);
+                st2 = __builtin_amdgcn_alignbit(st3, st2, 16);
+                st3 >>= 16;
+              }
+              *reinterpret_cast<uint4*>(start_row + ((size_t)(stop >> 3) << (lpc_shift + 2))) = make_uint4(st0, st1, st2, st3);
             }
+            esc_row[n_esc] = 0xffffffffu;
             out_stop[cand * T.D + d] = (int)stop;
             if (d == 0) out_flags[cand] = (unsigned char)(flg & (kDeadlock | kIncomplete));
           }
@@ -599,7 +626,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
 #define FPSCHED_INSTANTIATE_MODE(V, G, O, MODE)                                                           \
   template __global__ void eval_slot_kernel<V, G, O, MODE>(                                               \
       SlotTables, const uint16_t*, long long, int, long long*, long long*, int*, unsigned char*,          \
-      unsigned long long*, int, uint32_t*, int32_t*, const int32_t*);
+      unsigned long long*, int, uint32_t*, int32_t*, const int32_t*, uint32_t*, int);
 #define FPSCHED_INSTANTIATE(V, G, O)               \
   FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotPlain)    \
   FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotTimes)    \

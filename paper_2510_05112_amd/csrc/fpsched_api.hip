@@ -130,7 +130,7 @@ struct DeviceGuard {
 };
 
 using SlotKernel = void (*)(SlotTables, const uint16_t*, long long, int, long long*, long long*, int*,
-                            unsigned char*, unsigned long long*, int, uint32_t*, int32_t*, const int32_t*);
+                            unsigned char*, unsigned long long*, int, uint32_t*, int32_t*, const int32_t*, uint32_t*, int);
 template <int MODE>   // kSlotPlain, kSlotTimes, ...
 SlotKernel slot_kernel_of(int v, bool deg2, bool one_class) {
   if (deg2)
@@ -653,7 +653,7 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
                        (long long)n_cand, (int)stride_words, reinterpret_cast<long long*>(out.makespan),
                        reinterpret_cast<long long*>(out.idle), out.peak, out.flags, counter, draw_block,
                        (uint32_t*)nullptr, (int32_t*)nullptr,
-                       (const int32_t*)(p->mb_set && !mb_lds && !combo ? p->d_mb_rows : nullptr));
+                       (const int32_t*)(p->mb_set && !mb_lds && !combo ? p->d_mb_rows : nullptr), (uint32_t*)nullptr, 0);
     return check_hip(hipGetLastError());
   }
   const int cpw = p->tables.cands_per_wave;
@@ -1311,17 +1311,27 @@ int fpsched_rank(const fpsched_problem* p, fpsched_results in, int64_t n_cand, i
   return run_topk(keys, excluded, n_cand, k, d_idx, d_key, d_count, static_cast<char*>(d_workspace) + 256, st);
 }
 
-// workspace of the sliding pass: [256 bytes: candidate counter][start times: uint32 per op word]
-// [stop positions: int32 per row][flags of the timing pass: one byte per candidate]
+// workspace of the sliding pass: [256 bytes: candidate counter][low halves of the start times: 16 bits per op
+// word and lane of a candidate][escape lists: escape_cap dwords per row][stop positions: int32 per row]
+// [flags of the timing pass: one byte per candidate]
 static size_t wslide_starts_bytes(const fpsched_problem* p, int64_t n_cand, int32_t stride_words) {
-  return (size_t)n_cand * p->tables.lanes_per_cand * (size_t)stride_words * sizeof(uint32_t);
+  return (size_t)n_cand * p->tables.lanes_per_cand * (size_t)stride_words * sizeof(uint16_t);
+}
+// entries of a row's escape list: an op that waits 2^16 time units or more for its inputs; each such wait
+// uses up 2^16 of the largest possible finish time (links: two transfers per op at most), plus the end mark
+static int wslide_escape_cap(const fpsched_problem* p) {
+  const int64_t bound = (int64_t)p->D * p->max_stride * (p->max_dur + 2 * p->max_comm);
+  return (int)std::min<int64_t>(bound >> 16, 255) + 2;
+}
+static size_t wslide_escape_bytes(const fpsched_problem* p, int64_t n_cand) {
+  return (((size_t)n_cand * p->D * wslide_escape_cap(p) * sizeof(uint32_t)) + 15) & ~(size_t)15;
 }
 
 size_t fpsched_wslide_workspace_bytes(const fpsched_problem* p, int64_t n_cand, int32_t stride_words) {
   if (!p || n_cand < 0 || stride_words < 8) return 0;
   const size_t rows = (size_t)n_cand * p->D;
-  return 256 + wslide_starts_bytes(p, n_cand, stride_words) + ((rows * sizeof(int32_t) + 15) & ~(size_t)15) +
-         (((size_t)n_cand + 15) & ~(size_t)15);
+  return 256 + wslide_starts_bytes(p, n_cand, stride_words) + wslide_escape_bytes(p, n_cand) +
+         ((rows * sizeof(int32_t) + 15) & ~(size_t)15) + (((size_t)n_cand + 15) & ~(size_t)15);
 }
 
 int fpsched_wslide(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_cand, int32_t stride_words,
@@ -1348,7 +1358,9 @@ int fpsched_wslide(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_ca
   char* ws = static_cast<char*>(d_workspace);
   unsigned long long* counter = reinterpret_cast<unsigned long long*>(ws);
   uint32_t* starts = reinterpret_cast<uint32_t*>(ws + 256);
-  int32_t* stops = reinterpret_cast<int32_t*>(ws + 256 + wslide_starts_bytes(p, n_cand, stride_words));
+  uint32_t* escapes = reinterpret_cast<uint32_t*>(ws + 256 + wslide_starts_bytes(p, n_cand, stride_words));
+  const int escape_cap = wslide_escape_cap(p);
+  int32_t* stops = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(escapes) + wslide_escape_bytes(p, n_cand));
   unsigned char* timed_flags = reinterpret_cast<unsigned char*>(stops) + (((size_t)n_cand * p->D * sizeof(int32_t) + 15) & ~(size_t)15);
   // pass 1: the lists without their W items, timed by the evaluation kernel (launched as in fpsched_evaluate)
   // (under the link model: that model's tables and workgroup shape; W items send nothing, so the second
@@ -1368,13 +1380,13 @@ int fpsched_wslide(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_ca
                            : slot_kernel_of<kSlotTimes>(p->slot_v, p->slot_deg2, one_class),
                      dim3((unsigned)blocks), dim3(64 * waves), times_lds, st, times_tab, d_ops, (long long)n_cand,
                      (int)stride_words, (long long*)nullptr, (long long*)nullptr, (int*)nullptr, timed_flags, counter,
-                     draw_block, starts, stops, (const int32_t*)nullptr);
+                     draw_block, starts, stops, (const int32_t*)nullptr, escapes, escape_cap);
   if (hipGetLastError() != hipSuccess) return FPSCHED_EHIP;
   // pass 2: every row places its W items on its own
   hipLaunchKernelGGL(wslide_place_kernel, dim3((unsigned)place_blocks), dim3(kSlideThreads),
                      (size_t)kNKinds * kMaxChunks * lpc * 16 + (kSlideThreads / 64) * kSlideWaveLdsBytes, st, p->stab, d_ops,
                      (long long)n_cand, (int)stride_words,
-                     starts, stops, timed_flags, d_ops_out, (int)stride_out_words,
+                     starts, escapes, escape_cap, stops, timed_flags, d_ops_out, (int)stride_out_words,
                      reinterpret_cast<long long*>(out.makespan), reinterpret_cast<long long*>(out.idle), out.peak,
                      out.flags);
   return check_hip(hipGetLastError());

@@ -35,9 +35,11 @@ constexpr int kSlotMaxThreads = 64 * kSlotMaxWaves;
 // has two inputs or two outputs in the stage DAG.  ONE_CLASS = the DAG is a single chain.
 // next_candidate: a counter in device memory, preset to the number of segments in the grid, from
 // which wavefronts draw their work, draw_block candidates per atomic (1 <= draw_block <= 64).
-// MODE kSlotTimes: first pass of the weight-gradient sliding; writes out_start8 [n_cand][stride / 4][lanes per
-// candidate][4] (start time << 8 of the op at each position), out_stop [n_cand][D] (words issued per device) and out_flags
-// (DEADLOCK / INCOMPLETE only) instead of makespan, idle and peak; needs 16 bytes of LDS more.
+// MODE kSlotTimes: first pass of the weight-gradient sliding; writes out_start8 [n_cand][stride / 8][lanes per
+// candidate][8 x 16 bits] (low half of the start time of the op at each position), out_escape [n_cand][D][escape_cap]
+// (position << 8 | wait >> 16 of the ops that waited 2^16 time units or more, ended by an all-ones word), out_stop
+// [n_cand][D] (words issued per device) and out_flags (DEADLOCK / INCOMPLETE only) instead of makespan, idle and peak;
+// needs 16 bytes of LDS more.
 // MODE kSlotPerMicrobatch: durations from mb_rows [32][lanes per candidate][m] (cost << 8 per metadata
 // row, device and micro-batch) instead of the metadata rows.  MODE kSlotPerMicrobatchLds: from the
 // sixteen-bit table at T.off_mb, which travels to LDS with the metadata.
@@ -51,7 +53,8 @@ template <int V, bool DEG2, bool ONE_CLASS, int MODE>
 __global__ void eval_slot_kernel(SlotTables T, const uint16_t* ops, long long n_cand, int stride,
                                  long long* out_makespan, long long* out_idle, int* out_peak,
                                  unsigned char* out_flags, unsigned long long* next_candidate, int draw_block,
-                                 uint32_t* out_start8, int32_t* out_stop, const int32_t* mb_rows);
+                                 uint32_t* out_start8, int32_t* out_stop, const int32_t* mb_rows,
+                                 uint32_t* out_escape, int escape_cap);
 
 __global__ void reset_counter_kernel(unsigned long long* counter, unsigned long long value);
 
@@ -73,11 +76,12 @@ __global__ void rank_keys_kernel(const long long* makespan, const long long* idl
 
 // Second kernel of the weight-gradient sliding: one lane per (candidate, device) row places the W
 // items into the idle time in front of the ops timed by eval_slot_kernel<..., kSlotTimes>.
-constexpr int kSlideThreads = 512;
-// dynamic LDS of a workgroup: the metadata rows, then 8 KB per wavefront (windows and stash ring)
-constexpr int kSlideWaveLdsBytes = 8192;
+constexpr int kSlideThreads = 384;
+// dynamic LDS of a workgroup: the metadata rows, then 10 KB per wavefront (windows and stash ring)
+constexpr int kSlideWaveLdsBytes = 10240;
 __global__ void wslide_place_kernel(SlotTables T, const uint16_t* ops, long long n_cand, int stride,
-                                    const uint32_t* start8, const int32_t* stop_pos,
+                                    const uint32_t* start_low, const uint32_t* escapes, int escape_cap,
+                                    const int32_t* stop_pos,
                                     const unsigned char* timed_flags, uint16_t* ops_out, int stride_out,
                                     long long* out_makespan, long long* out_idle, int* out_peak,
                                     unsigned char* out_flags);

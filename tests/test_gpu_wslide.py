@@ -149,3 +149,35 @@ def test_largest_sizes_and_long_stashes(links):
         lists += [base, perturb(base, rng, 2)]
     words = batch_from_lists(lists)
     check(prob, words, words.shape[2] + 8, "S=252")
+
+
+@pytest.mark.parametrize("links", [False, True])
+def test_ops_that_wait_longer_than_sixteen_bits_of_time(links):
+    # The hand-off between the two kernels carries the low sixteen bits of every start time; an op that waits
+    # 2^16 time units or more for its inputs goes through the row's escape list.  Costs of up to 70,000 make
+    # such waits common (several per row), next to ordinary ones; strides that are and are not multiples of 16.
+    from helpers import batch_from_lists, perturb, random_valid_lists
+    rng = np.random.default_rng(31)
+    for p, m, v, stride_pad in ((2, 3, 1, 0), (4, 6, 2, 8), (3, 9, 1, 0)):
+        prob = chain_problem(p, m, v=v, f=1, b=1, w=1, comm=3)
+        S = p * v
+        prob.dur[F] = rng.choice([3, 500, 66000, 70000], S)
+        prob.dur[B] = rng.choice([7, 900, 66000, 69999], S)
+        prob.dur[3] = rng.choice([1, 40, 65536, 30000], S)
+        prob.edge_comm[:] = rng.choice([0, 2, 3], S - 1)
+        lists = []
+        for t in range(40):
+            base = random_valid_lists(prob, rng)
+            lists += [base, perturb(base, rng, 1 + t % 2)]
+        words = batch_from_lists(lists)
+        stride = words.shape[2] + stride_pad
+        wide = np.zeros(words.shape[:2] + (stride,), np.uint16)
+        wide[:, :, :words.shape[2]] = words
+        h = fp.Problem(prob, stride, device=0)
+        h.set_link_occupancy(links)
+        _, got = run_gpu(h, wide, stride)
+        ref = oracle.wslide(prob, wide, stride, links=links)
+        assert_same(got, ref, f"p{p} m{m} v{v} links={links}")
+        ok = (ref["flags"] & 3) == 0
+        assert ok.sum() > 20 and ref["makespan"][ok].max() > 6 * 65536
+        h.close()

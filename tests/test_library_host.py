@@ -49,7 +49,7 @@ def test_host_only_handle_and_errors():
     assert lib.fpsched_apply_caps(p._h, 0, 1, 0, 1, 0, 0) == -5
     assert lib.fpsched_wslide(p._h, 0, 1, spec.stride, 0, spec.stride, none, 0, 0, 0) == -5
     # the workspace sizes are host arithmetic and work without a device
-    assert lib.fpsched_wslide_workspace_bytes(p._h, 100, spec.stride) >= 256 + 100 * 8 * spec.stride * 4 + 100 * 8 * 4 + 100
+    assert lib.fpsched_wslide_workspace_bytes(p._h, 100, spec.stride) >= 256 + 100 * 8 * spec.stride * 2 + 100 * 8 * 4 + 100
     assert lib.fpsched_pareto_workspace_bytes(p._h, 5000) >= 3 * 2048 * 20
     assert lib.fpsched_rank_workspace_bytes(p._h, 5000, 16) >= lib.fpsched_workspace_bytes(p._h, 5000, 16) + 5000 * 9
     # null handle and nonsense sizes
