@@ -31,7 +31,7 @@
  * Environment variables, read when the call they belong to runs; none changes a result:
  *   FPSCHED_SLOT_WAVES=n  (fpsched_problem_create, the two cost-model setters) at most n wavefronts
  *                         per workgroup of the main evaluation kernel, one workgroup per compute unit;
- *   FPSCHED_GEN_WAVES=n   (fpsched_generate) n resident wavefronts per compute unit, default 16;
+ *   FPSCHED_GEN_WAVES=n   (fpsched_generate) n resident wavefronts per compute unit, default 24;
  *   FPSCHED_MB_GLOBAL=1   (fpsched_problem_set_microbatch_costs) keep the cost table in device
  *                         memory even where it would fit LDS;
  *   FPSCHED_VERBOSE=1     the two cost-model setters print the kernel form and shape they chose.

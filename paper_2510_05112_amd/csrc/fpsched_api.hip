@@ -1187,7 +1187,7 @@ int fpsched_generate(const fpsched_problem* p, const fpsched_actor_policy* d_pol
   if (lds_bytes > p->max_lds) return FPSCHED_EUNSUPPORTED;
   // persistent grid: as many single-wavefront workgroups as stay resident (tuning knob:
   // FPSCHED_GEN_WAVES = wavefronts per compute unit)
-  int waves_per_cu = 16;
+  int waves_per_cu = 24;
   if (const char* env = getenv("FPSCHED_GEN_WAVES")) {
     const int v = atoi(env);
     if (v >= 1 && v <= 32) waves_per_cu = v;

@@ -79,7 +79,6 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
   const int seg = lane >> lpc_shift;
   const int d = lane & (lpc - 1);
   const bool has_dev = d < D;
-  const unsigned long long seg_mask = (lpc == 64 ? ~0ull : ((1ull << lpc) - 1ull)) << (seg * lpc);
   const int base = seg * 3 * S;   // this segment's counters: counts[base + type * S + stage]
 
   // what depends on the actor only
@@ -114,10 +113,35 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
 #pragma unroll
   for (int c = 0; c < V; ++c) limit[c] = 1;
   int turn_type = kGenF, turn_run = 0, pos_f = 0, pos_b = 0, stepped_f = 0, stepped_b = 0;
+  int first = kGenF;   // the instruction type tried first in a step: fixed, or the interleaved priority's turn
   int left = 0;        // items this actor still has to schedule
   bool live = false;   // the set's process is still running
-  int steps = 0, status = 0, len = 0;
+  int status = 0, len = 0;
+  unsigned long long first_step = 0ull;   // the loop's step counter when the set's process began
+  int steps = 0;
   uint16_t* row = ops;
+  // "does any lane of my segment ..." without vector work: fold a ballot onto the lowest lane of every
+  // segment, then spread those bits over the segments' lanes
+  unsigned long long base_bits = 0ull;
+  for (int sgm = 0; sgm < cpw; ++sgm) base_bits |= 1ull << (sgm * lpc);
+  int fold_shift[6];   // shifts 1, 2, 4, ... below the segment width, then 0 (no-ops)
+#pragma unroll
+  for (int i = 0; i < 6; ++i) fold_shift[i] = (1 << i) < lpc ? (1 << i) : 0;
+  auto any_in_segment = [&](unsigned long long ballot) -> bool {
+    unsigned long long spread;
+    if (lpc == 64) {
+      spread = ballot ? ~0ull : 0ull;
+    } else if (lpc == 32) {   // the two halves of the wavefront on their own
+      spread = ((unsigned)ballot ? 0xffffffffull : 0ull) | ((unsigned)(ballot >> 32) ? 0xffffffff00000000ull : 0ull);
+    } else {
+      unsigned long long x = ballot;
+#pragma unroll
+      for (int i = 0; i < 6; ++i) x |= x >> fold_shift[i];
+      x &= base_bits;
+      spread = (x << lpc) - x;
+    }
+    return __builtin_amdgcn_inverse_ballot_w64(spread);
+  };
 
   // Every step but the last of a set schedules at least one of its 3 S m items, and a segment
   // cannot draw more than all sets: the bound below is never reached, it only makes sure that the
@@ -171,14 +195,16 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
                    b_dir < 0 || b_dir > 1 || b_int < 0 || (cttp != 2 && (unit_f != 1 || unit_b != 1));
 #pragma unroll
         for (int c = 0; c < V; ++c) bad = bad || limit[c] < 1;
-        const bool set_bad = (__ballot(bad && has_row) & seg_mask) != 0ull;
+        const bool set_bad = any_in_segment(__ballot(bad && has_row));
         turn_type = kGenF; turn_run = 0;
+        first = cttp == 0 ? kGenB : kGenF;
         pos_f = f_dir == 0 ? 0 : (nch > 0 ? nch - 1 : 0);
         pos_b = b_dir == 0 ? 0 : (nch > 0 ? nch - 1 : 0);
         stepped_f = 0; stepped_b = 0;
         left = (has_row && !set_bad) ? nch * m * (has_w ? 3 : 2) : 0;
-        live = (__ballot(left > 0) & seg_mask) != 0ull;
-        steps = 0; status = set_bad ? 4 : 0; len = 0;
+        live = any_in_segment(__ballot(left > 0));
+        first_step = step; steps = 0;
+        status = set_bad ? 4 : 0; len = 0;
         row = ops + (size_t)(has_row ? set * D + d : 0) * (size_t)stride;
         fresh = has_set && !live;   // nothing to schedule (a bad set, no stages): written out next time round
       }
@@ -193,8 +219,11 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
       const int nf = counts[own_at[c]], nb = counts[own_at[c] + S], nw = counts[own_at[c] + 2 * S];
       int f_ahead = m, b_ahead = nf;
       if (DEG > 0) {
+        // (no counter exceeds m, and a missing neighbour reads a word that holds m)
+        f_ahead = counts[pred_at[c][0]];
+        b_ahead = min(b_ahead, counts[succ_at[c][0]]);
 #pragma unroll
-        for (int k = 0; k < (DEG > 0 ? DEG : 1); ++k) {
+        for (int k = 1; k < (DEG > 0 ? DEG : 1); ++k) {
           f_ahead = min(f_ahead, counts[pred_at[c][k]]);
           b_ahead = min(b_ahead, counts[succ_at[c][k]]);
         }
@@ -212,7 +241,6 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
     if (!live) { ok_f = 0u; ok_b = 0u; ok_w = 0u; }
     // ---- the step function, without branches: the first instruction type, in priority order, with an
     // eligible item; then the stage, in traversal order
-    const int first = cttp == 0 ? kGenB : (cttp == 1 ? kGenF : turn_type);
     const unsigned ok_first = first == kGenF ? ok_f : ok_b, ok_second = first == kGenF ? ok_b : ok_f;
     const int pick_t = ok_first ? first : (ok_second ? (first ^ 1) : (ok_w ? kGenW : -1));
     const unsigned ok = ok_first ? ok_first : (ok_second ? ok_second : ok_w);
@@ -221,21 +249,31 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
     const int interval = is_f ? f_int : (is_b ? b_int : 0);
     const int p0 = is_f ? pos_f : pos_b;
     const int stepped0 = is_f ? stepped_f : stepped_b;
-    // the next stage after p0, in the traversal direction and cyclically, that has an eligible item:
-    // lay the mask out twice, shift it so that the stage after p0 is at bit 0, take the lowest bit
-    // (depth-first: the same on the mirrored mask)
-    const unsigned mirrored = __brev(ok) >> (32 - nch);   // (nch = 0: ok is 0 and nothing is picked)
-    const unsigned walk = dir == 0 ? ok : mirrored;
-    const int q0 = dir == 0 ? p0 : nch - 1 - p0;
-    const unsigned twice = walk | (walk << nch);
-    int q1 = q0 + 1 + low_bit(twice >> (q0 + 1));
-    q1 = q1 >= nch ? q1 - nch : q1;
-    const int moved_to = dir == 0 ? q1 : nch - 1 - q1;
+    int p1, pick_c;
     const bool move = stepped0 == interval || !((ok >> p0) & 1u);
-    const int p1 = move ? moved_to : p0;
+    if (V <= 2) {
+      // at most two stages: "the next stage with an eligible item" is the other one if it has one, and the
+      // first eligible stage in either direction is the only one, or the first / the last of both
+      const unsigned other = (unsigned)p0 ^ 1u;
+      p1 = (move && ((ok >> other) & 1u)) ? (int)other : p0;
+      const int without_interval = ok == 3u ? dir : (int)(ok >> 1);
+      pick_c = interval > 0 ? p1 : without_interval;
+    } else {
+      // the next stage after p0, in the traversal direction and cyclically, that has an eligible item:
+      // lay the mask out twice, shift it so that the stage after p0 is at bit 0, take the lowest bit
+      // (depth-first: the same on the mirrored mask)
+      const unsigned mirrored = __brev(ok) >> (32 - nch);   // (nch = 0: ok is 0 and nothing is picked)
+      const unsigned walk = dir == 0 ? ok : mirrored;
+      const int q0 = dir == 0 ? p0 : nch - 1 - p0;
+      const unsigned twice = walk | (walk << nch);
+      int q1 = q0 + 1 + low_bit(twice >> (q0 + 1));
+      q1 = q1 >= nch ? q1 - nch : q1;
+      const int moved_to = dir == 0 ? q1 : nch - 1 - q1;
+      p1 = move ? moved_to : p0;
+      const int first_c = low_bit(ok), last_c = high_bit(ok);
+      pick_c = interval > 0 ? p1 : (dir == 0 ? first_c : last_c);
+    }
     const int stepped1 = (move ? 0 : stepped0) + 1;
-    const int first_c = low_bit(ok), last_c = high_bit(ok);
-    const int pick_c = interval > 0 ? p1 : (dir == 0 ? first_c : last_c);
     if (interval > 0 && is_f) { pos_f = p1; stepped_f = stepped1; }
     if (interval > 0 && is_b) { pos_b = p1; stepped_b = stepped1; }
     if (pick_t >= 0) {
@@ -244,7 +282,7 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
       int at = own_at[0];
 #pragma unroll
       for (int c = 1; c < V; ++c) at = pick_c == c ? own_at[c] : at;
-      const int j = atomicAdd(&counts[at + (int)__umul24((unsigned)pick_t, (unsigned)S)], 1);
+      const int j = atomicAdd(&counts[at + (pick_t == kGenF ? 0 : (pick_t == kGenB ? S : 2 * S))], 1);
       left -= 1;
       const unsigned word = ((unsigned)(pick_t + 1) << 13) | ((unsigned)pick_c << 11) | (unsigned)j;
       // sixteen op words are collected in the lane's staging dwords and stored together
@@ -256,16 +294,20 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
       }
       len += 1;
       if (cttp == 2 && pick_t == turn_type) {
-        if (++turn_run >= (is_f ? unit_f : unit_b)) { turn_type = is_f ? kGenB : kGenF; turn_run = 0; }
+        if (++turn_run >= (is_f ? unit_f : unit_b)) { turn_type = is_f ? kGenB : kGenF; turn_run = 0; first = turn_type; }
       }
     }
     __builtin_amdgcn_wave_barrier();
-    const bool any_pick = (__ballot(pick_t >= 0) & seg_mask) != 0ull;
-    const bool any_left = (__ballot(left > 0) & seg_mask) != 0ull;
+    const bool any_pick = any_in_segment(__ballot(pick_t >= 0));
+    const bool any_left = any_in_segment(__ballot(left > 0));
     if (live) {
-      if (!any_pick) { status = 1; live = false; }   // items remain and nothing can move
-      else { steps += 1; live = any_left; }
-      fresh = !live;
+      const bool stuck = !any_pick;   // items remain and nothing can move
+      live = !stuck && any_left;
+      if (!live) {
+        status = stuck ? 1 : status;
+        steps = (int)(step - first_step) + (stuck ? 0 : 1);
+        fresh = true;
+      }
     }
   }
 }
