@@ -48,12 +48,14 @@ MEASURED_BOTH = {}
 # the evaluation with synchronisation stages (--mode sync)
 MEASURED_SYNC = {}
 # one generator launch (--mode generate): WRITE_SIZE x 1024 plus the parameter sets read
-MEASURED_GENERATE = {("cfg4", 65536): {"traffic_bytes": 4.81e9, "valu_wave_instructions": 1.231e10,
-                                       "valu_per_wave_round": None, "profile_kernel_ms": 23.3,
+MEASURED_GENERATE = {("cfg4", 65536): {"traffic_bytes": 4.82e9, "valu_wave_instructions": 1.016e10,
+                                       "valu_per_wave_round": None, "profile_kernel_ms": 21.8,
                                        "profile": "profiles/generate_kernel_cfg4.md"}}
+# generator and evaluator in one kernel (--mode search --fused)
+MEASURED_FUSED = {}
 # the sliding pass (--mode wslide), both of its kernels
-MEASURED_WSLIDE = {("cfg4", 65536): {"traffic_bytes": 8.08e10, "valu_wave_instructions": 5.54e9,
-                                     "valu_per_wave_round": None, "profile_kernel_ms": 20.2,
+MEASURED_WSLIDE = {("cfg4", 65536): {"traffic_bytes": 4.06e10, "valu_wave_instructions": 5.89e9,
+                                     "valu_per_wave_round": None, "profile_kernel_ms": 18.9,
                                      "profile": "profiles/wslide_kernel_cfg4.md"}}
 
 
@@ -113,13 +115,21 @@ def bench_generate(args, spec, threads) -> int:
     if args.links:   # the generator ignores costs; the evaluation (and the sliding pass) of a search step follow
         handle.set_link_occupancy(True)
     d_pol, d_inf = torch.from_numpy(pol).to(dev), torch.from_numpy(inf).to(dev)
-    out = dict(ops=torch.empty((n, prob.n_devices, stride), dtype=torch.int16, device=dev),
-               steps=torch.empty(n, dtype=torch.int32, device=dev),
-               status=torch.empty(n, dtype=torch.uint8, device=dev))
-    print(f"[bench] generate cfg{spec.index}: {n} parameter sets, {prob.n_devices} actors, stride {stride} "
-          f"({out['ops'].numel() * 2 / 1e9:.2f} GB of schedules)", file=sys.stderr, flush=True)
     search = args.mode == "search"
     k = spec.top_k
+    # fused search step: the schedules are timed while they are generated and never written; only the
+    # rows of the k winners are generated afterwards
+    fused = search and args.fused
+    if fused and (args.slide or args.links):
+        print("[bench] --fused knows the plain cost model and no sliding pass", file=sys.stderr)
+        return 2
+    out = dict(ops=torch.empty((k if fused else n, prob.n_devices, stride), dtype=torch.int16, device=dev),
+               steps=torch.empty(n, dtype=torch.int32, device=dev),
+               status=torch.empty(n, dtype=torch.uint8, device=dev))
+    winners = dict(ops=out["ops"], steps=torch.empty(k, dtype=torch.int32, device=dev),
+                   status=torch.empty(k, dtype=torch.uint8, device=dev))
+    print(f"[bench] generate cfg{spec.index}: {n} parameter sets, {prob.n_devices} actors, stride {stride} "
+          f"({out['ops'].numel() * 2 / 1e9:.2f} GB of schedules)", file=sys.stderr, flush=True)
     ws = handle.alloc_workspace(n, k)
     res = handle.alloc_results(n) if search else None
     slide = search and args.slide and bool(prob.has_w)
@@ -134,10 +144,16 @@ def bench_generate(args, spec, threads) -> int:
     def step(e=None):
         if e:
             e[0].record()
-        handle.generate(d_pol, d_inf, stride, out=out, workspace=ws)
+        if fused:
+            handle.generate_evaluate(d_pol, d_inf, results=res, out=out, workspace=ws)
+        else:
+            handle.generate(d_pol, d_inf, stride, out=out, workspace=ws)
         if e:
             e[1].record()
-        if search:
+        if fused:
+            handle.topk(res, k, ws, top)
+            handle.generate_selected(d_pol, d_inf, top["idx"], stride, out=winners, workspace=ws)
+        elif search:
             if slide:
                 handle.wslide(out["ops"], stride, out=slid, workspace=slide_ws)
                 handle.topk(slid, k, ws, top)
@@ -158,12 +174,21 @@ def bench_generate(args, spec, threads) -> int:
     ms_per_step = wall * 1e3 / args.steps
     words = out["ops"].cpu().numpy().view(np.uint16)
     steps = out["steps"].cpu().numpy()
-    n_ops = int(np.count_nonzero(words >> 13))
-    # algorithmic bytes of one launch: the parameter sets in, every row of op words out (the rows are
-    # written in full, END padding included: the evaluator reads them as they are), steps and status
-    alg_bytes = pol.nbytes + inf.nbytes + words.nbytes + 5 * n
-    gen_roofline, gen_issue = rooflines(alg_bytes, gen_ms, "fpsched generator kernel (generate_kernel)",
-                                        MEASURED_GENERATE.get((f"cfg{spec.index}", n)), units=n_ops)
+    if fused:
+        complete = int((out["status"].cpu().numpy() == 0).sum())
+        n_ops = complete * prob.n_stages * prob.n_microbatches * (3 if prob.has_w else 2)
+        # algorithmic bytes of the fused launch: the parameter sets in, the results, steps and status out
+        alg_bytes = pol.nbytes + inf.nbytes + n * (8 + 12 * prob.n_devices + 1 + 5)
+    else:
+        n_ops = int(np.count_nonzero(words >> 13))
+        # algorithmic bytes of one launch: the parameter sets in, every row of op words out (the rows are
+        # written in full, END padding included: the evaluator reads them as they are), steps and status
+        alg_bytes = pol.nbytes + inf.nbytes + words.nbytes + 5 * n
+    gen_roofline, gen_issue = rooflines(alg_bytes, gen_ms,
+                                        "fpsched generator kernel, timed form (generate_kernel<.., true>)" if fused
+                                        else "fpsched generator kernel (generate_kernel)",
+                                        (MEASURED_FUSED if fused else MEASURED_GENERATE).get((f"cfg{spec.index}", n)),
+                                        units=n_ops)
     json_res = {
         "metric": "schedules generated, evaluated and ranked/sec" if search else "schedules generated/sec",
         "value": n / (ms_per_step * 1e-3), "unit": "schedules/s",
@@ -171,7 +196,8 @@ def bench_generate(args, spec, threads) -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
         "config": {"workload": f"{'search loop' if search else 'generator'} on cfg{spec.index}: {prob.name}, "
                                f"{n} seeded parameter sets" + (f", top-{k}" if search else "")
-                               + (", link occupancy" if search and args.links else ""),
+                               + (", link occupancy" if search and args.links else "")
+                               + (", timed while generated (no op words written but the winners')" if fused else ""),
                    "parameter_sets": n, "devices": prob.n_devices, "stages": prob.n_stages,
                    "microbatches": prob.n_microbatches, "ops_per_schedule": n_ops / n, "stride_words": stride},
         "items_scheduled_per_s": n_ops / (ms_per_step * 1e-3),
@@ -193,7 +219,16 @@ def bench_generate(args, spec, threads) -> int:
             rng = np.random.default_rng(0)
             pick = np.sort(rng.choice(n, min(args.check, n), replace=False))
             ref = oracle.generate(prob, pol[pick], inf[pick], stride, threads=threads)
-            ok = (np.array_equal(words[pick], ref["words"]) and np.array_equal(steps[pick], ref["steps"]))
+            if fused:
+                ref_ev = oracle.evaluate(prob, ref["words"], threads=threads)
+                ok = np.array_equal(steps[pick], ref["steps"]) and all(
+                    np.array_equal(res[name].cpu().numpy()[pick], ref_ev[name])
+                    for name in ("makespan", "idle", "peak", "flags"))
+                first = int(top["idx"][0].item())   # the best set's row block, written by generate_selected
+                ok = ok and np.array_equal(words[0], oracle.generate(prob, pol[first:first + 1], inf[first:first + 1],
+                                                                     stride, threads=1)["words"][0])
+            else:
+                ok = (np.array_equal(words[pick], ref["words"]) and np.array_equal(steps[pick], ref["steps"]))
             json_res["parity_sample"] = {"parameter_sets": int(len(pick)), "bit_exact": bool(ok)}
             if not ok:
                 print("[bench] PARITY FAILURE against the generator oracle on the sample", file=sys.stderr)
@@ -425,6 +460,9 @@ def main() -> int:
                          "wslide: the weight-gradient sliding pass + top-k on the resident batch; "
                          "sync: evaluation + top-k on the multimodal workload with a registered "
                          "synchronisation every four micro-batches and a dependency pair")
+    ap.add_argument("--fused", action="store_true",
+                    help="search mode: one kernel generates and times the schedules (fpsched_generate_evaluate); no op "
+                         "words are written except the rows of the k winners")
     ap.add_argument("--slide", action="store_true",
                     help="search mode: rank the generated schedules after the weight-gradient sliding pass")
     ap.add_argument("--mb-costs", action="store_true",

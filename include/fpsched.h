@@ -9,7 +9,8 @@
  * idle (bubble) time, per-device peak activation memory and a deadlock flag,
  * and reduces a batch to its k best candidates under the memory cap.  It also
  * runs the paper's scheduler itself (Section 5: step function, reorder queues,
- * in-flight limits) as a generator of candidates (fpsched_generate), moves the
+ * in-flight limits) as a generator of candidates (fpsched_generate, or fused with the
+ * evaluation: fpsched_generate_evaluate), moves the
  * weight-gradient items of candidate lists into idle time (fpsched_wslide;
  * Section 5.2, bubble optimizations), and ranks evaluated candidates by other
  * keys than the makespan (fpsched_rank, fpsched_pareto, fpsched_apply_caps).
@@ -443,6 +444,35 @@ int fpsched_generate(const fpsched_problem *p, const fpsched_actor_policy *d_pol
                      const int32_t *d_inflight, int64_t n_sets, int32_t stride_words,
                      uint16_t *d_ops, int32_t *d_steps, uint8_t *d_status, void *d_workspace,
                      size_t workspace_bytes, void *hip_stream);
+
+/* Generator and evaluator in one pass (the tuner's loop of Section 6: enumerate schedule types,
+ * let the scheduler of Section 5 produce each schedule, let the estimator time it, rank): for every
+ * parameter set the schedule fpsched_generate would write is timed while it is generated, and
+ * only the results leave the chip -- out gets exactly what fpsched_evaluate gives for the rows
+ * fpsched_generate writes for the same set (a set that ends stuck or has a bad policy leaves items
+ * unscheduled: FPSCHED_FLAG_INCOMPLETE and the sentinels), d_steps and d_status what
+ * fpsched_generate gives.  An item is scheduled only after all it depends on was scheduled in an
+ * earlier step, so its start (Section 5.1, data dependency; start = max(device free, inputs'
+ * finish + cross-device latency)) is known when it is placed.  The plain cost model only:
+ * FPSCHED_EUNSUPPORTED while costs per micro-batch, link occupancy, synchronisation stages or the
+ * copy engine are set, if a stage has more than two inputs or outputs, or if the tables do not
+ * fit LDS; FPSCHED_EOVERFLOW if 3 S m (max dur + max comm) >= 2^30.  Buffers as for
+ * fpsched_generate (no d_ops) and fpsched_evaluate; d_workspace >= 256 bytes.  The schedules of
+ * the sets that fpsched_topk then names are obtained with fpsched_generate_selected. */
+int fpsched_generate_evaluate(const fpsched_problem *p, const fpsched_actor_policy *d_policy,
+                              const int32_t *d_inflight, int64_t n_sets, fpsched_results out,
+                              int32_t *d_steps, uint8_t *d_status, void *d_workspace,
+                              size_t workspace_bytes, void *hip_stream);
+
+/* fpsched_generate for chosen parameter sets: row block i of d_ops (and d_steps[i], d_status[i])
+ * is the schedule of parameter set d_select[i] (DEVICE int64 [n_selected], e.g. the indices
+ * fpsched_topk wrote; each must be below the number of sets d_policy and d_inflight hold).  A
+ * negative entry (an unused top-k slot) selects nothing: empty rows, FPSCHED_GEN_BAD_POLICY. */
+int fpsched_generate_selected(const fpsched_problem *p, const fpsched_actor_policy *d_policy,
+                              const int32_t *d_inflight, const int64_t *d_select,
+                              int64_t n_selected, int32_t stride_words, uint16_t *d_ops,
+                              int32_t *d_steps, uint8_t *d_status, void *d_workspace,
+                              size_t workspace_bytes, void *hip_stream);
 
 const char *fpsched_strerror(int code);
 int fpsched_version(void);

@@ -97,6 +97,10 @@ def load_library():
         lib.fpsched_apply_caps.argtypes = [vp, vp, vp, i32, i64, vp, vp]
         lib.fpsched_generate.restype = ctypes.c_int
         lib.fpsched_generate.argtypes = [vp, vp, vp, i64, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.fpsched_generate_selected.restype = ctypes.c_int
+        lib.fpsched_generate_selected.argtypes = [vp, vp, vp, vp, i64, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.fpsched_generate_evaluate.restype = ctypes.c_int
+        lib.fpsched_generate_evaluate.argtypes = [vp, vp, vp, i64, _Results, vp, vp, vp, ctypes.c_size_t, vp]
         lib.fpsched_encode.restype = ctypes.c_int
         lib.fpsched_encode.argtypes = [vp, vp, i32, i32, vp]
         lib.fpsched_validate.restype = ctypes.c_int64
@@ -341,6 +345,61 @@ class Problem:
         if rc != 0:
             raise FpschedError(rc, "fpsched_generate")
         return out
+
+    def generate_selected(self, policy, inflight, select, stride: int, out=None, workspace=None, stream=None):
+        """fpsched_generate_selected: the schedules of the parameter sets ``select`` names (torch int64
+        CUDA tensor [k], e.g. the indices of a top-k; negative = none).  Returns dict(ops int16
+        [k][D][stride], steps, status).  Asynchronous."""
+        import torch
+        if self.device is None:
+            raise FpschedError(-5, "fpsched_generate_selected")
+        assert policy.is_cuda and policy.is_contiguous() and policy.dtype == torch.int32
+        assert inflight.is_cuda and inflight.is_contiguous() and inflight.dtype == torch.int32
+        assert select.is_cuda and select.is_contiguous() and select.dtype == torch.int64 and select.dim() == 1
+        n = policy.shape[0]
+        assert tuple(policy.shape) == (n, self.D, 8) and tuple(inflight.shape) == (n, self.S)
+        k = select.numel()
+        dev = torch.device("cuda", self.device)
+        if out is None:
+            out = dict(ops=torch.empty((k, self.D, int(stride)), dtype=torch.int16, device=dev),
+                       steps=torch.empty(k, dtype=torch.int32, device=dev),
+                       status=torch.empty(k, dtype=torch.uint8, device=dev))
+        if workspace is None:
+            workspace = self.alloc_workspace(k, 0)
+        rc = load_library().fpsched_generate_selected(
+            self._h, policy.data_ptr(), inflight.data_ptr(), select.data_ptr(), k, int(stride),
+            out["ops"].data_ptr(), out["steps"].data_ptr(), out["status"].data_ptr(), workspace.data_ptr(),
+            workspace.numel(), self._stream(stream))
+        if rc != 0:
+            raise FpschedError(rc, "fpsched_generate_selected")
+        return out
+
+    def generate_evaluate(self, policy, inflight, results=None, out=None, workspace=None, stream=None):
+        """fpsched_generate_evaluate: the schedules of n parameter sets timed while they are generated;
+        no op words are written.  Returns (results as alloc_results gives them, dict(steps, status)).
+        Asynchronous."""
+        import torch
+        if self.device is None:
+            raise FpschedError(-5, "fpsched_generate_evaluate")
+        assert policy.is_cuda and policy.is_contiguous() and policy.dtype == torch.int32
+        assert inflight.is_cuda and inflight.is_contiguous() and inflight.dtype == torch.int32
+        n = policy.shape[0]
+        assert tuple(policy.shape) == (n, self.D, 8) and tuple(inflight.shape) == (n, self.S)
+        dev = torch.device("cuda", self.device)
+        if results is None:
+            results = self.alloc_results(n)
+        if out is None:
+            out = dict(steps=torch.empty(n, dtype=torch.int32, device=dev),
+                       status=torch.empty(n, dtype=torch.uint8, device=dev))
+        if workspace is None:
+            workspace = self.alloc_workspace(n, 0)
+        rc = load_library().fpsched_generate_evaluate(
+            self._h, policy.data_ptr(), inflight.data_ptr(), n, self._res_struct(results),
+            out["steps"].data_ptr(), out["status"].data_ptr(), workspace.data_ptr(), workspace.numel(),
+            self._stream(stream))
+        if rc != 0:
+            raise FpschedError(rc, "fpsched_generate_evaluate")
+        return results, out
 
     RANK_MODES = {"makespan": 0, "makespan_peak": 1, "peak_makespan": 2, "idle": 3}
 

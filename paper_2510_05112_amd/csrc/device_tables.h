@@ -35,6 +35,18 @@ struct DevTables {
   int32_t off_local_stage;  // [D][kMaxChunks], -1 = none
   int32_t off_n_chunks;     // [D]
   int32_t off_mem_cap;      // [D]
+  // Timed form of the generator (generate.hip): one row of eight ints per (instruction type F / B / W,
+  // chunk < gen_row_chunks, device), -1 if the DAG has a stage with more than two inputs or outputs:
+  //   0 duration   1 units allocated at the start   2 units freed at the end
+  //   3 word offset of the first input slot   4 latency of the first input, or -2^30 if there is none
+  //   5, 6 the same for the second input   7 first output slot | second output slot << 16 (degree one:
+  //   the first output slot alone)
+  // Slots of one parameter set: one word per (direction, class, micro-batch) as in the slot kernel
+  // (backward class k at k m, forward class k at (classes + k) m) holding a plain finish time, then m
+  // words that take what items without an out-edge write (and that items without an input read).
+  int32_t off_gen_rows;
+  int32_t gen_row_chunks;   // 1, 2 or 4
+  int32_t gen_slot_words;   // (2 * classes + 1) * m
   const int32_t* ints;      // DEVICE
 };
 

@@ -318,7 +318,56 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
     }
     if (n_classes == 0) n_classes = 1;
   }
-  T.n_table_ints = (int32_t)I.size();
+  T.n_table_ints = (int32_t)I.size();   // what the table-walking kernels copy to LDS ends here
+  // Rows of the timed generator: what an item of (type, chunk) on a device costs, where its inputs'
+  // finish times lie and where its own goes (layout: device_tables.h).
+  T.off_gen_rows = -1;
+  T.gen_row_chunks = 1;
+  T.gen_slot_words = (2 * n_classes + 1) * m;
+  if (p->max_degree <= 2 && (int64_t)(2 * n_classes + 1) * m <= 0xffff) {
+    int max_chunks = 1;
+    for (int d = 0; d < D; ++d) max_chunks = std::max(max_chunks, p->n_chunks[d]);
+    const int V = max_chunks <= 1 ? 1 : (max_chunks <= 2 ? 2 : 4);
+    T.gen_row_chunks = V;
+    std::vector<int32_t> pcl(E), scl(E), pf(S, 0), sf(S, 0);
+    for (int e = 0; e < E; ++e) {
+      const int a = desc->edge_src[e], b = desc->edge_dst[e];
+      pcl[poff[b] + pf[b]++] = edge_cls[e];
+      scl[soff[a] + sf[a]++] = edge_cls[e];
+    }
+    const int32_t dump = 2 * n_classes * m, none = -(1 << 30);
+    std::vector<int32_t> rows((size_t)3 * V * D * 8, 0);
+    for (int t = 0; t < 3; ++t)
+      for (int c = 0; c < V; ++c)
+        for (int d = 0; d < D; ++d) {
+          int32_t* r = &rows[(((size_t)t * V + c) * D + d) * 8];
+          // (a DAG of degree one has no second output: word 7 is then the first output's offset alone)
+          r[3] = dump; r[4] = none; r[5] = dump; r[6] = none; r[7] = p->max_degree <= 1 ? dump : dump | (dump << 16);
+          if (c >= p->n_chunks[d]) continue;
+          const int s = p->local_stage[(size_t)d * kMaxChunks + c];
+          const int kind = t == 0 ? kF : (t == 1 ? kB : kW);
+          r[0] = desc->dur[kind * S + s];
+          r[1] = t == 0 ? desc->mem_units[s] : 0;
+          r[2] = (t == 2 || (t == 1 && !p->has_w)) ? desc->mem_units[s] : 0;
+          if (t == 2) continue;
+          // forward items read the values of their in-edges and write those of their out-edges; backward
+          // items the other way round
+          const std::vector<int32_t>& ioff = t == 0 ? poff : soff;
+          const std::vector<int32_t>& icl = t == 0 ? pcl : scl;
+          const std::vector<int32_t>& ilat = t == 0 ? pcm : scm;
+          const std::vector<int32_t>& ooff = t == 0 ? soff : poff;
+          const std::vector<int32_t>& ocl = t == 0 ? scl : pcl;
+          const int32_t dir_base = t == 0 ? n_classes : 0;
+          for (int k = 0; k < ioff[s + 1] - ioff[s]; ++k) {
+            r[3 + 2 * k] = (dir_base + icl[ioff[s] + k]) * m;
+            r[4 + 2 * k] = ilat[ioff[s] + k];
+          }
+          int32_t out[2] = {dump, dump};
+          for (int k = 0; k < ooff[s + 1] - ooff[s]; ++k) out[k] = (dir_base + ocl[ooff[s] + k]) * m;
+          r[7] = p->max_degree <= 1 ? out[0] : out[0] | (out[1] << 16);
+        }
+    T.off_gen_rows = append(rows.data(), rows.size());
+  }
   T.lanes_per_cand = next_pow2(D);
   T.cands_per_wave = 64 / T.lanes_per_cand;
 
@@ -1163,16 +1212,32 @@ int fpsched_problem_set_copy_engine(fpsched_problem* p, int32_t depth) {
   return FPSCHED_OK;
 }
 
-int fpsched_generate(const fpsched_problem* p, const fpsched_actor_policy* d_policy, const int32_t* d_inflight,
-                     int64_t n_sets, int32_t stride_words, uint16_t* d_ops, int32_t* d_steps, uint8_t* d_status,
-                     void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+using GenKernel = void (*)(DevTables, const int32_t*, const int32_t*, const long long*, long long, int, uint16_t*,
+                           int32_t*, unsigned char*, unsigned long long*, GenResults);
+static int gen_waves_per_cu() {
+  // tuning knob: FPSCHED_GEN_WAVES = resident wavefronts per compute unit
+  int waves_per_cu = 24;
+  if (const char* env = getenv("FPSCHED_GEN_WAVES")) {
+    const int v = atoi(env);
+    if (v >= 1 && v <= 32) waves_per_cu = v;
+  }
+  return waves_per_cu;
+}
+static int gen_max_chunks(const fpsched_problem* p) {
+  int max_chunks = 0;
+  for (int d = 0; d < p->D; ++d) max_chunks = std::max(max_chunks, p->n_chunks[d]);
+  return max_chunks;
+}
+
+static int run_generate(const fpsched_problem* p, const fpsched_actor_policy* d_policy, const int32_t* d_inflight,
+                 const int64_t* d_select, int64_t n_sets, int32_t stride_words, uint16_t* d_ops, int32_t* d_steps,
+                 uint8_t* d_status, void* d_workspace, size_t workspace_bytes, void* hip_stream) {
   if (!p || n_sets < 0) return FPSCHED_EINVAL;
   if (p->device_id < 0) return FPSCHED_ENODEV;
   if (n_sets == 0) return FPSCHED_OK;
   if (!d_policy || !d_inflight || !d_ops || !d_steps || !d_status) return FPSCHED_EINVAL;
   if (p->sync_on) return FPSCHED_EUNSUPPORTED;   // the generator schedules one item per micro-batch
-  int max_chunks = 0;
-  for (int d = 0; d < p->D; ++d) max_chunks = std::max(max_chunks, p->n_chunks[d]);
+  const int max_chunks = gen_max_chunks(p);
   const int64_t longest = (int64_t)max_chunks * p->m * (p->has_w ? 3 : 2);
   if (stride_words < 8 || (stride_words & 7) || stride_words < longest) return FPSCHED_EINVAL;
   if (reinterpret_cast<uintptr_t>(d_ops) & 15) return FPSCHED_EINVAL;
@@ -1182,26 +1247,19 @@ int fpsched_generate(const fpsched_problem* p, const fpsched_actor_policy* d_pol
   const int lpc = p->tables.lanes_per_cand;
   const int cpw = 64 / lpc;
   const int deg = p->max_degree <= 1 ? 1 : (p->max_degree == 2 ? 2 : 0);
-  // tables (if walked), counters, the constant words, 8 staging dwords per lane
-  const int64_t lds_bytes = 4ll * ((deg == 0 ? p->tables.n_table_ints : 0) + (int64_t)cpw * 3 * p->S + 2 * p->S + 1 + 8 * 64);
+  // tables (if walked), counters and the constant words (a multiple of four), 8 staging dwords per lane
+  const int64_t lds_bytes = 4ll * ((deg == 0 ? p->tables.n_table_ints : 0) +
+                                   (((int64_t)cpw * 3 * p->S + 2 * p->S + 1 + 3) & ~3ll) + 8 * 64);
   if (lds_bytes > p->max_lds) return FPSCHED_EUNSUPPORTED;
-  // persistent grid: as many single-wavefront workgroups as stay resident (tuning knob:
-  // FPSCHED_GEN_WAVES = wavefronts per compute unit)
-  int waves_per_cu = 24;
-  if (const char* env = getenv("FPSCHED_GEN_WAVES")) {
-    const int v = atoi(env);
-    if (v >= 1 && v <= 32) waves_per_cu = v;
-  }
-  const int64_t blocks = std::min<int64_t>((n_sets + cpw - 1) / cpw, (int64_t)p->n_cu * waves_per_cu);
+  // persistent grid: as many single-wavefront workgroups as stay resident
+  const int64_t blocks = std::min<int64_t>((n_sets + cpw - 1) / cpw, (int64_t)p->n_cu * gen_waves_per_cu());
   DeviceGuard g(p->device_id);
   if (!g.ok) return FPSCHED_EHIP;
   const int V = max_chunks <= 1 ? 1 : (max_chunks <= 2 ? 2 : 4);
-  using GenKernel = void (*)(DevTables, const int32_t*, const int32_t*, long long, int, uint16_t*, int32_t*,
-                             unsigned char*, unsigned long long*);
   static const GenKernel table[3][3] = {
-      {&generate_kernel<1, 0>, &generate_kernel<1, 1>, &generate_kernel<1, 2>},
-      {&generate_kernel<2, 0>, &generate_kernel<2, 1>, &generate_kernel<2, 2>},
-      {&generate_kernel<4, 0>, &generate_kernel<4, 1>, &generate_kernel<4, 2>}};
+      {&generate_kernel<1, 0, false>, &generate_kernel<1, 1, false>, &generate_kernel<1, 2, false>},
+      {&generate_kernel<2, 0, false>, &generate_kernel<2, 1, false>, &generate_kernel<2, 2, false>},
+      {&generate_kernel<4, 0, false>, &generate_kernel<4, 1, false>, &generate_kernel<4, 2, false>}};
   const GenKernel kernel = table[V == 1 ? 0 : (V == 2 ? 1 : 2)][deg];
   if (lds_bytes > 64 * 1024 &&
       hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -1213,7 +1271,81 @@ int fpsched_generate(const fpsched_problem* p, const fpsched_actor_policy* d_pol
                      (unsigned long long)(blocks * cpw));
   hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(64), (size_t)lds_bytes,
                      static_cast<hipStream_t>(hip_stream), p->tables, reinterpret_cast<const int32_t*>(d_policy),
-                     d_inflight, (long long)n_sets, (int)stride_words, d_ops, d_steps, d_status, counter);
+                     d_inflight, reinterpret_cast<const long long*>(d_select), (long long)n_sets, (int)stride_words,
+                     d_ops, d_steps, d_status, counter, GenResults{nullptr, nullptr, nullptr, nullptr});
+  return check_hip(hipGetLastError());
+}
+
+int fpsched_generate(const fpsched_problem* p, const fpsched_actor_policy* d_policy, const int32_t* d_inflight,
+                     int64_t n_sets, int32_t stride_words, uint16_t* d_ops, int32_t* d_steps, uint8_t* d_status,
+                     void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+  return run_generate(p, d_policy, d_inflight, nullptr, n_sets, stride_words, d_ops, d_steps, d_status, d_workspace,
+                      workspace_bytes, hip_stream);
+}
+
+int fpsched_generate_selected(const fpsched_problem* p, const fpsched_actor_policy* d_policy,
+                              const int32_t* d_inflight, const int64_t* d_select, int64_t n_selected,
+                              int32_t stride_words, uint16_t* d_ops, int32_t* d_steps, uint8_t* d_status,
+                              void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+  if (n_selected > 0 && !d_select) return FPSCHED_EINVAL;
+  return run_generate(p, d_policy, d_inflight, d_select, n_selected, stride_words, d_ops, d_steps, d_status,
+                      d_workspace, workspace_bytes, hip_stream);
+}
+
+int fpsched_generate_evaluate(const fpsched_problem* p, const fpsched_actor_policy* d_policy,
+                              const int32_t* d_inflight, int64_t n_sets, fpsched_results out, int32_t* d_steps,
+                              uint8_t* d_status, void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!p || n_sets < 0) return FPSCHED_EINVAL;
+  if (p->device_id < 0) return FPSCHED_ENODEV;
+  if (n_sets == 0) return FPSCHED_OK;
+  if (!d_policy || !d_inflight || !d_steps || !d_status || !out.makespan || !out.idle || !out.peak || !out.flags)
+    return FPSCHED_EINVAL;
+  // the plain cost model only: one cost per (type, stage), transfers as latencies
+  if (p->sync_on || p->copy_depth > 0 || p->mb_set || p->links_on) return FPSCHED_EUNSUPPORTED;
+  if (p->tables.off_gen_rows < 0) return FPSCHED_EUNSUPPORTED;
+  if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) & 15)) return FPSCHED_EINVAL;
+  if (workspace_bytes < 256) return FPSCHED_ENOMEM;
+  // finish times stay below 2^30: every item starts at most (items before it) * (largest cost + latency) late
+  if (3ll * p->S * p->m * (p->max_dur + p->max_comm) >= (1ll << 30)) return FPSCHED_EOVERFLOW;
+  const int lpc = p->tables.lanes_per_cand;
+  const int cpw = 64 / lpc;
+  const int V = p->tables.gen_row_chunks;
+  // cost rows shared by the workgroup; per wavefront its counters and its sets' slots
+  const int64_t shared_ints = 3ll * V * p->D * 8;
+  const int64_t wave_ints = (((int64_t)cpw * 3 * p->S + 2 * p->S + 1 + 3) & ~3ll) + (int64_t)cpw * p->tables.gen_slot_words;
+  const int64_t lds_ints = p->max_lds / 4;
+  if (shared_ints + wave_ints > lds_ints) return FPSCHED_EUNSUPPORTED;
+  // wavefronts per workgroup and workgroups per compute unit: as many resident wavefronts as asked for
+  // and as LDS holds, in as few workgroups as possible (each keeps a copy of the rows)
+  const int want = gen_waves_per_cu();
+  int best_waves = 1, best_groups = 1;
+  for (int groups = 1; groups <= 8; ++groups) {
+    int wv = (int)std::min<int64_t>((lds_ints / groups - shared_ints - 64) / wave_ints, kGenTimedThreads / 64);
+    wv = std::min(wv, (want + groups - 1) / groups);
+    if (wv >= 1 && wv * groups > best_waves * best_groups) { best_waves = wv; best_groups = groups; }
+  }
+  const int64_t segments = (n_sets + cpw - 1) / cpw;
+  const int64_t blocks = std::min<int64_t>((segments + best_waves - 1) / best_waves, (int64_t)p->n_cu * best_groups);
+  const int64_t lds_bytes = 4 * (shared_ints + best_waves * wave_ints);
+  DeviceGuard g(p->device_id);
+  if (!g.ok) return FPSCHED_EHIP;
+  const int deg = p->max_degree <= 1 ? 1 : 2;
+  static const GenKernel table[3][2] = {{&generate_kernel<1, 1, true>, &generate_kernel<1, 2, true>},
+                                        {&generate_kernel<2, 1, true>, &generate_kernel<2, 2, true>},
+                                        {&generate_kernel<4, 1, true>, &generate_kernel<4, 2, true>}};
+  const GenKernel kernel = table[V == 1 ? 0 : (V == 2 ? 1 : 2)][deg - 1];
+  if (lds_bytes > 64 * 1024 &&
+      hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                          p->max_lds) != hipSuccess)
+    return FPSCHED_EHIP;
+  unsigned long long* counter = static_cast<unsigned long long*>(d_workspace);
+  hipLaunchKernelGGL(reset_counter_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(hip_stream), counter,
+                     (unsigned long long)(blocks * best_waves * cpw));
+  hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(64 * best_waves), (size_t)lds_bytes,
+                     static_cast<hipStream_t>(hip_stream), p->tables, reinterpret_cast<const int32_t*>(d_policy),
+                     d_inflight, nullptr, (long long)n_sets, 0, nullptr, d_steps, d_status, counter,
+                     GenResults{reinterpret_cast<long long*>(out.makespan), reinterpret_cast<long long*>(out.idle),
+                                out.peak, out.flags});
   return check_hip(hipGetLastError());
 }
 

@@ -47,39 +47,61 @@ __device__ __forceinline__ int high_bit(unsigned x) { return 31 - __clz(x); }
 // The grid is persistent: a segment (the lanes of one parameter set) that finishes its schedule
 // writes it out, draws the next set from a global counter and starts over while the other segments
 // of the wavefront keep stepping, so that sets that need few and many steps balance out.
-template <int V, int DEG>
-__global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t* __restrict__ policy,
-                                                      const int32_t* __restrict__ inflight, long long n_sets,
-                                                      int stride, uint16_t* __restrict__ ops,
-                                                      int32_t* __restrict__ out_steps,
-                                                      unsigned char* __restrict__ out_status,
-                                                      unsigned long long* __restrict__ next_set) {
+//
+// TIMED: generator and evaluator in one (fpsched_generate_evaluate).  An item is scheduled only
+// after everything it depends on was scheduled in an earlier step, so its start time is known the
+// moment it is placed: start = max(the actor's free time, the inputs' finish + latency), exactly
+// what fpsched_evaluate computes for the generated lists (Section 5.1 data dependency; the
+// estimator's start / end / cost).  The inputs' finish times travel through the mail slots of the
+// slot kernel, here plain int32 words without tags (the counters already say that the value is
+// there); resident memory is counted as the items are placed.  No op word is formed, nothing but
+// the results is written.  Workgroups hold several wavefronts that share the cost rows; each
+// wavefront keeps its own counters and slots and never looks at another's, so no barrier is needed
+// after the start.
+template <int V, int DEG, bool TIMED>
+__global__ __launch_bounds__(TIMED ? kGenTimedThreads : 64) void generate_kernel(
+    DevTables T, const int32_t* __restrict__ policy, const int32_t* __restrict__ inflight,
+    const long long* __restrict__ select, long long n_sets, int stride, uint16_t* __restrict__ ops,
+    int32_t* __restrict__ out_steps, unsigned char* __restrict__ out_status,
+    unsigned long long* __restrict__ next_set, GenResults R) {
   extern __shared__ int32_t lds[];
-  const int lane = threadIdx.x;
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6, waves_per_block = blockDim.x >> 6;
   const int S = T.S, m = T.m, D = T.D;
   const int lpc = T.lanes_per_cand;
   const int lpc_shift = __ffs(lpc) - 1;
   const int cpw = 64 >> lpc_shift;
   const bool has_w = T.has_w != 0;
-  // LDS: [edge lists, only if DEG == 0][sets of the wavefront: counters [3][S]][one word holding m]
-  // [row staging: 16 op words per lane, as 8 dwords laid out [dword][lane]]
-  const int n_tab = DEG == 0 ? T.n_table_ints : 0;
-  if (DEG == 0)
+  // LDS: [edge lists, only if DEG == 0 | cost rows, only if TIMED] then per wavefront
+  // [sets of the wavefront: counters [3][S]][words holding m]
+  // [row staging: 16 op words per lane, as 8 dwords laid out [dword][lane] | TIMED: the sets' slots]
+  const int n_tab = TIMED ? 3 * V * D * 8 : (DEG == 0 ? T.n_table_ints : 0);
+  if (TIMED) {
+    for (int i = threadIdx.x; i < n_tab; i += blockDim.x) lds[i] = T.ints[T.off_gen_rows + i];
+  } else if (DEG == 0) {
     for (int i = lane; i < n_tab; i += 64) lds[i] = T.ints[i];
-  int32_t* counts = lds + n_tab;
+  }
+  const int n_count_ints = (cpw * 3 * S + 2 * S + 1 + 3) & ~3;
+  const int slot_words = T.gen_slot_words;
+  int32_t* counts = lds + n_tab + wave * (n_count_ints + (TIMED ? cpw * slot_words : 8 * 64));
   // counters that are always "done" (value m): at_m stands in for a missing neighbour, and at_m,
   // at_m + S, at_m + 2 S for the three counters of a chunk the actor does not have
   const int at_m = cpw * 3 * S;
   if (lane < 3) counts[at_m + lane * S] = m;
   // a lane collects 16 op words (32 bytes) of its row before it stores them: HBM is written in
   // 32-byte pieces, not a quarter of that
-  uint32_t* staging = reinterpret_cast<uint32_t*>(counts + at_m + 2 * S + 1) + lane;   // dword i at + i * 64
+  uint32_t* staging = reinterpret_cast<uint32_t*>(counts + n_count_ints) + lane;   // dword i at + i * 64
+  // TIMED: slots never hold anything but finish times (an item without an input reads some word of
+  // them and adds -2^30)
+  if (TIMED)
+    for (int i = lane; i < cpw * slot_words; i += 64) counts[n_count_ints + i] = 0;
   __syncthreads();
 
   const int seg = lane >> lpc_shift;
   const int d = lane & (lpc - 1);
   const bool has_dev = d < D;
   const int base = seg * 3 * S;   // this segment's counters: counts[base + type * S + stage]
+  int32_t* slot = counts + n_count_ints + seg * slot_words;   // TIMED: this segment's slots
 
   // what depends on the actor only
   const int nch = has_dev ? T.ints[T.off_n_chunks + d] : 0;
@@ -103,8 +125,21 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
     }
   }
 
+  // TIMED: what the actor's items cost together, and its memory cap
+  long long busy_total = 0;
+  int cap = 0x7fffffff;
+  if (TIMED && has_dev) {
+    cap = T.ints[T.off_mem_cap + d];
+#pragma unroll
+    for (int c = 0; c < V; ++c)
+      if (c < nch)
+        busy_total += (long long)m * ((long long)T.ints[T.off_dur + kF * S + stage[c]] + T.ints[T.off_dur + kB * S + stage[c]] +
+                                      (has_w ? T.ints[T.off_dur + kW * S + stage[c]] : 0));
+  }
+  int free_at = 0, mem = 0, peak = 0;
+
   // per-set state
-  long long set = (long long)blockIdx.x * cpw + seg;   // the first set of a segment is its global index
+  long long set = ((long long)blockIdx.x * waves_per_block + wave) * cpw + seg;   // the first set of a segment is its global index
   bool first_draw = true;
   bool has_set = false;   // the segment is working on a set (possibly finished and not yet written out)
   bool fresh = true;      // the segment wants its next set
@@ -155,7 +190,27 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
       // ---- segments that finished write their schedule out and start on the next set
       if (fresh) {
         fresh = false;
-        if (has_set && has_dev) {
+        if (TIMED) {
+          if (has_set) {
+            // the segment's results, in the form fpsched_evaluate gives them for the generated lists; a
+            // schedule that is not complete (stuck, bad policy) has items that never ran
+            int makespan = free_at;
+            bool over = peak > cap;
+            for (int off = 1; off < lpc; off <<= 1) makespan = max(makespan, __shfl_xor(makespan, off, 64));
+            over = any_in_segment(__ballot(over));
+            const bool complete = status == 0;
+            if (has_dev) {
+              R.idle[set * D + d] = complete ? (long long)makespan - busy_total : -1ll;
+              R.peak[set * D + d] = complete ? peak : -1;
+            }
+            if (d == 0) {
+              R.makespan[set] = complete ? (long long)makespan : 0x7fffffffffffffffll;
+              R.flags[set] = (unsigned char)(complete ? (over ? kOverCap : 0) : kIncomplete);
+              out_steps[set] = steps;
+              out_status[set] = (unsigned char)status;
+            }
+          }
+        } else if (has_set && has_dev) {
           // rows are END-padded to the stride; words still staged go out with the padding
           int at = len & ~15;
           if (len & 15) {
@@ -183,15 +238,19 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
         if (has_set)
           for (int i = d; i < 3 * S; i += lpc) counts[base + i] = 0;
         cttp = 0; unit_f = 1; unit_b = 1; f_dir = 0; f_int = 0; b_dir = 0; b_int = 0;
-        if (has_row) {
-          const int32_t* pol = policy + (set * D + d) * 8;
+        // (with a selection, output row `set` is the schedule of parameter set select[set]; a negative
+        // entry selects nothing and counts as a bad set)
+        const long long src = (has_set && select) ? select[set] : set;
+        const bool has_src = has_row && src >= 0;
+        if (has_src) {
+          const int32_t* pol = policy + (src * D + d) * 8;
           cttp = pol[0]; unit_f = pol[1]; unit_b = pol[2];
           f_dir = pol[3]; f_int = pol[4]; b_dir = pol[5]; b_int = pol[6];
         }
 #pragma unroll
-        for (int c = 0; c < V; ++c) limit[c] = (has_row && c < nch) ? inflight[set * S + stage[c]] : 1;
+        for (int c = 0; c < V; ++c) limit[c] = (has_src && c < nch) ? inflight[src * S + stage[c]] : 1;
         // a parameter set with a value outside its domain generates nothing (status 4)
-        bool bad = cttp < 0 || cttp > 2 || unit_f < 1 || unit_b < 1 || f_dir < 0 || f_dir > 1 || f_int < 0 ||
+        bool bad = (has_row && src < 0) || cttp < 0 || cttp > 2 || unit_f < 1 || unit_b < 1 || f_dir < 0 || f_dir > 1 || f_int < 0 ||
                    b_dir < 0 || b_dir > 1 || b_int < 0 || (cttp != 2 && (unit_f != 1 || unit_b != 1));
 #pragma unroll
         for (int c = 0; c < V; ++c) bad = bad || limit[c] < 1;
@@ -205,7 +264,8 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
         live = any_in_segment(__ballot(left > 0));
         first_step = step; steps = 0;
         status = set_bad ? 4 : 0; len = 0;
-        row = ops + (size_t)(has_row ? set * D + d : 0) * (size_t)stride;
+        free_at = 0; mem = 0; peak = 0;
+        if (!TIMED) row = ops + (size_t)(has_row ? set * D + d : 0) * (size_t)stride;
         fresh = has_set && !live;   // nothing to schedule (a bad set, no stages): written out next time round
       }
       if (__ballot(has_set) == 0ull) break;   // every segment of the wavefront is out of work
@@ -284,15 +344,29 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
       for (int c = 1; c < V; ++c) at = pick_c == c ? own_at[c] : at;
       const int j = atomicAdd(&counts[at + (pick_t == kGenF ? 0 : (pick_t == kGenB ? S : 2 * S))], 1);
       left -= 1;
-      const unsigned word = ((unsigned)(pick_t + 1) << 13) | ((unsigned)pick_c << 11) | (unsigned)j;
-      // sixteen op words are collected in the lane's staging dwords and stored together
-      reinterpret_cast<uint16_t*>(staging + ((len >> 1) & 7) * 64)[len & 1] = (uint16_t)word;
-      if ((len & 15) == 15) {
-        uint4* dst = reinterpret_cast<uint4*>(row + (len - 15));
-        dst[0] = make_uint4(staging[0], staging[64], staging[128], staging[192]);
-        dst[1] = make_uint4(staging[256], staging[320], staging[384], staging[448]);
+      if (TIMED) {
+        // the item's row: cost, memory, where its inputs' finish times are and where its own goes
+        const int4* r = reinterpret_cast<const int4*>(lds + ((pick_t * V + pick_c) * D + d) * 8);
+        const int4 a = r[0], b = r[1];
+        int ready = slot[a.w + j] + b.x;
+        if (DEG > 1) ready = max(ready, slot[b.y + j] + b.z);
+        free_at = max(free_at, ready) + a.x;
+        slot[(DEG > 1 ? (b.w & 0xffff) : b.w) + j] = free_at;
+        if (DEG > 1) slot[(int)((unsigned)b.w >> 16) + j] = free_at;
+        mem += a.y;
+        peak = max(peak, mem);
+        mem -= a.z;
+      } else {
+        const unsigned word = ((unsigned)(pick_t + 1) << 13) | ((unsigned)pick_c << 11) | (unsigned)j;
+        // sixteen op words are collected in the lane's staging dwords and stored together
+        reinterpret_cast<uint16_t*>(staging + ((len >> 1) & 7) * 64)[len & 1] = (uint16_t)word;
+        if ((len & 15) == 15) {
+          uint4* dst = reinterpret_cast<uint4*>(row + (len - 15));
+          dst[0] = make_uint4(staging[0], staging[64], staging[128], staging[192]);
+          dst[1] = make_uint4(staging[256], staging[320], staging[384], staging[448]);
+        }
+        len += 1;
       }
-      len += 1;
       if (cttp == 2 && pick_t == turn_type) {
         if (++turn_run >= (is_f ? unit_f : unit_b)) { turn_type = is_f ? kGenB : kGenF; turn_run = 0; first = turn_type; }
       }
@@ -312,18 +386,25 @@ __global__ __launch_bounds__(64) void generate_kernel(DevTables T, const int32_t
   }
 }
 
-#define FPSCHED_INSTANTIATE(V, G)                                                                             \
-  template __global__ void generate_kernel<V, G>(DevTables, const int32_t*, const int32_t*, long long, int, \
-                                                 uint16_t*, int32_t*, unsigned char*, unsigned long long*);
-FPSCHED_INSTANTIATE(1, 1)
-FPSCHED_INSTANTIATE(2, 1)
-FPSCHED_INSTANTIATE(4, 1)
-FPSCHED_INSTANTIATE(1, 2)
-FPSCHED_INSTANTIATE(2, 2)
-FPSCHED_INSTANTIATE(4, 2)
-FPSCHED_INSTANTIATE(1, 0)
-FPSCHED_INSTANTIATE(2, 0)
-FPSCHED_INSTANTIATE(4, 0)
+#define FPSCHED_INSTANTIATE(V, G, TIMED)                                                                    \
+  template __global__ void generate_kernel<V, G, TIMED>(DevTables, const int32_t*, const int32_t*,           \
+                                                        const long long*, long long, int, uint16_t*, int32_t*, \
+                                                        unsigned char*, unsigned long long*, GenResults);
+FPSCHED_INSTANTIATE(1, 1, false)
+FPSCHED_INSTANTIATE(2, 1, false)
+FPSCHED_INSTANTIATE(4, 1, false)
+FPSCHED_INSTANTIATE(1, 2, false)
+FPSCHED_INSTANTIATE(2, 2, false)
+FPSCHED_INSTANTIATE(4, 2, false)
+FPSCHED_INSTANTIATE(1, 0, false)
+FPSCHED_INSTANTIATE(2, 0, false)
+FPSCHED_INSTANTIATE(4, 0, false)
+FPSCHED_INSTANTIATE(1, 1, true)
+FPSCHED_INSTANTIATE(2, 1, true)
+FPSCHED_INSTANTIATE(4, 1, true)
+FPSCHED_INSTANTIATE(1, 2, true)
+FPSCHED_INSTANTIATE(2, 2, true)
+FPSCHED_INSTANTIATE(4, 2, true)
 #undef FPSCHED_INSTANTIATE
 
 }  // namespace fpsched

@@ -61,10 +61,20 @@ __global__ void reset_counter_kernel(unsigned long long* counter, unsigned long 
 // V as above; DEG = bound on the in- and out-degree of a stage (1, 2, or 0 = any).  One wavefront per
 // workgroup, 64 / lanes_per_cand parameter sets per wavefront at a time; next_set: a counter in
 // device memory, preset to the number of segments in the grid, from which segments draw their sets.
-template <int V, int DEG>
-__global__ void generate_kernel(DevTables T, const int32_t* policy, const int32_t* inflight, long long n_sets,
-                                int stride, uint16_t* ops, int32_t* out_steps, unsigned char* out_status,
-                                unsigned long long* next_set);
+// select: null, or which parameter set each output row takes (negative: none).
+// TIMED (DEG 1 or 2 only): the schedules are timed as they are generated and only the results R are
+// written (ops and select unused); workgroups of up to kGenTimedThreads threads.
+struct GenResults {
+  long long* makespan;
+  long long* idle;
+  int32_t* peak;
+  unsigned char* flags;
+};
+constexpr int kGenTimedThreads = 512;
+template <int V, int DEG, bool TIMED>
+__global__ void generate_kernel(DevTables T, const int32_t* policy, const int32_t* inflight, const long long* select,
+                                long long n_sets, int stride, uint16_t* ops, int32_t* out_steps,
+                                unsigned char* out_status, unsigned long long* next_set, GenResults R);
 
 __global__ void topk_tile_kernel(const long long* in_makespan, const unsigned char* in_flags,
                                  const Key* in_keys, long long n, int k, Key* out_keys,

@@ -105,19 +105,34 @@ def grid(problem, circular: bool, inflight_options=None, forward_first: bool = F
 
 
 def tune(handle, problem, circular: bool, k: int = 8, inflight_options=None, forward_first: bool = False,
-         slide: bool = False):
+         slide: bool = False, fused: bool = False):
     """Generate, time and rank the grid of one problem on the GPU.  handle: a ``Problem`` created
     with a stride of at least ``stride_for(problem)``.  slide: for problems with split backward,
     also rank every generated schedule after the weight-gradient sliding pass (Section 5.2, bubble
     optimizations); such entries have ``slid`` set.  Returns the k best feasible schedules as a list
     of dicts (label, makespan, index into the grid, slid).  The schedules are timed with whatever cost
     model the handle is set to (``set_microbatch_costs``, ``set_link_occupancy``); the sliding pass
-    follows the link switch and refuses costs per micro-batch."""
+    follows the link switch and refuses costs per micro-batch.  fused: one kernel generates and times the
+    schedules (plain cost model, no sliding pass; ``Problem.generate_evaluate``) and only the winners' rows
+    are written: the entries then carry them as ``ops`` (uint16 [D][stride])."""
     import torch
 
     labels, pol, inf = grid(problem, circular, inflight_options, forward_first)
     n = len(labels)
     stride = stride_for(problem)
+    if fused:
+        if slide:
+            raise ValueError("the fused search has no sliding pass")
+        d_pol, d_inf = torch.from_numpy(pol).cuda(), torch.from_numpy(inf).cuda()
+        res, _ = handle.generate_evaluate(d_pol, d_inf)
+        top = handle.topk(res, min(k, 1024))
+        rows = handle.generate_selected(d_pol, d_inf, top["idx"], stride)
+        torch.cuda.synchronize()
+        cnt = int(top["count"].item())
+        idx, ms = top["idx"].cpu().numpy()[:cnt], top["makespan"].cpu().numpy()[:cnt]
+        ops = rows["ops"].cpu().numpy().view(np.uint16)
+        return [dict(label=labels[int(i)], makespan=int(t), index=int(i), slid=False, ops=ops[r])
+                for r, (i, t) in enumerate(zip(idx, ms))]
     out = handle.generate(torch.from_numpy(pol).cuda(), torch.from_numpy(inf).cuda(), stride)
     res = handle.evaluate(out["ops"])
     if slide and problem.has_w:

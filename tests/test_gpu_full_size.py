@@ -98,10 +98,14 @@ def test_generator_full_batch_8192_sets_against_oracle():
     pol, inf = workloads.policy_sets(prob, n)
     stride = workloads.generator_stride(prob)
     h = fp.Problem(prob, stride, device=0)
-    out = h.generate(torch.from_numpy(pol).cuda(), torch.from_numpy(inf).cuda(), stride)
+    d_pol, d_inf = torch.from_numpy(pol).cuda(), torch.from_numpy(inf).cuda()
+    out = h.generate(d_pol, d_inf, stride)
+    fused, fused_out = h.generate_evaluate(d_pol, d_inf)   # the same sets, timed while generated
     torch.cuda.synchronize()
     steps = out["steps"].cpu().numpy()
     status = out["status"].cpu().numpy()
+    assert np.array_equal(fused_out["steps"].cpu().numpy(), steps) and not fused_out["status"].any()
+    fused = {name: t.cpu().numpy() for name, t in fused.items()}
     rng = np.random.default_rng(4)
     pick = np.unique(np.concatenate([rng.choice(n, 8190, replace=False), [0, n - 1]]))
     for lo in range(0, len(pick), 2048):   # in pieces: the run prints its progress
@@ -110,6 +114,9 @@ def test_generator_full_batch_8192_sets_against_oracle():
         sel = torch.from_numpy(part).cuda()
         assert np.array_equal(out["ops"][sel].cpu().numpy().view(np.uint16), ref["words"])
         assert np.array_equal(steps[part], ref["steps"]) and np.array_equal(status[part], ref["status"])
+        ref_ev = oracle.evaluate(prob, ref["words"], threads=16)
+        for name in ("makespan", "idle", "peak", "flags"):
+            assert np.array_equal(fused[name][part], ref_ev[name]), name
         print(f"generator: {lo + len(part)} of {len(pick)} sets ok", flush=True)
     # properties at full size: every process completes, every actor schedules each of its items once
     assert not status.any()
@@ -121,6 +128,9 @@ def test_generator_full_batch_8192_sets_against_oracle():
     res = h.evaluate(out["ops"])
     torch.cuda.synchronize()
     assert not bool((res["flags"] & 3).any())
+    # ... with the results the fused kernel gave, for every one of the 65,536 sets
+    for name in ("makespan", "idle", "peak", "flags"):
+        assert np.array_equal(fused[name], res[name].cpu().numpy()), name
     h.close()
 
 

@@ -106,6 +106,10 @@ def test_gpu_search_over_the_grid_matches_the_oracles(strategy, p, v):
     idx, ms, cnt = oracle.topk(ref["makespan"], ref["flags"], 5)
     assert [b["index"] for b in best] == list(idx[:cnt]) and [b["makespan"] for b in best] == list(ms[:cnt])
     assert cnt > 0 and best[0]["label"] == labels[idx[0]]
+    # the fused search (timed while generated, only the winners' rows written) finds the same schedules
+    fused = tuner.tune(h, prob, circular, k=5, fused=True)
+    assert [(b["index"], b["makespan"], b["label"]) for b in fused] == [(b["index"], b["makespan"], b["label"]) for b in best]
+    assert all(np.array_equal(b["ops"], words[b["index"]]) for b in fused)
     h.close()
 
 
