@@ -38,7 +38,7 @@ struct DevTables {
   // Timed form of the generator (generate.hip): one row of eight ints per (instruction type F / B / W,
   // chunk < gen_row_chunks, device), -1 if the DAG has a stage with more than two inputs or outputs:
   //   0 duration   1 units allocated at the start   2 units freed at the end
-  //   3 word offset of the first input slot   4 latency of the first input, or -2^30 if there is none
+  //   3 byte offset of the first input slot   4 latency of the first input, or -2^30 if there is none
   //   5, 6 the same for the second input   7 first output slot | second output slot << 16 (degree one:
   //   the first output slot alone)
   // Slots of one parameter set: one word per (direction, class, micro-batch) as in the slot kernel

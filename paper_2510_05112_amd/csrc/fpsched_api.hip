@@ -324,7 +324,7 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
   T.off_gen_rows = -1;
   T.gen_row_chunks = 1;
   T.gen_slot_words = (2 * n_classes + 1) * m;
-  if (p->max_degree <= 2 && (int64_t)(2 * n_classes + 1) * m <= 0xffff) {
+  if (p->max_degree <= 2 && 4ll * (2 * n_classes + 1) * m <= 0xffff) {
     int max_chunks = 1;
     for (int d = 0; d < D; ++d) max_chunks = std::max(max_chunks, p->n_chunks[d]);
     const int V = max_chunks <= 1 ? 1 : (max_chunks <= 2 ? 2 : 4);
@@ -335,7 +335,7 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
       pcl[poff[b] + pf[b]++] = edge_cls[e];
       scl[soff[a] + sf[a]++] = edge_cls[e];
     }
-    const int32_t dump = 2 * n_classes * m, none = -(1 << 30);
+    const int32_t dump = 4 * 2 * n_classes * m, none = -(1 << 30);   // slot offsets in bytes
     std::vector<int32_t> rows((size_t)3 * V * D * 8, 0);
     for (int t = 0; t < 3; ++t)
       for (int c = 0; c < V; ++c)
@@ -359,11 +359,11 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
           const std::vector<int32_t>& ocl = t == 0 ? scl : pcl;
           const int32_t dir_base = t == 0 ? n_classes : 0;
           for (int k = 0; k < ioff[s + 1] - ioff[s]; ++k) {
-            r[3 + 2 * k] = (dir_base + icl[ioff[s] + k]) * m;
+            r[3 + 2 * k] = 4 * (dir_base + icl[ioff[s] + k]) * m;
             r[4 + 2 * k] = ilat[ioff[s] + k];
           }
           int32_t out[2] = {dump, dump};
-          for (int k = 0; k < ooff[s + 1] - ooff[s]; ++k) out[k] = (dir_base + ocl[ooff[s] + k]) * m;
+          for (int k = 0; k < ooff[s + 1] - ooff[s]; ++k) out[k] = 4 * (dir_base + ocl[ooff[s] + k]) * m;
           r[7] = p->max_degree <= 1 ? out[0] : out[0] | (out[1] << 16);
         }
     T.off_gen_rows = append(rows.data(), rows.size());

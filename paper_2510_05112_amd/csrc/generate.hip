@@ -37,6 +37,17 @@ enum GenType : int { kGenF = 0, kGenB = 1, kGenW = 2 };
 // lowest / highest set bit of a non-zero 4-bit mask
 __device__ __forceinline__ int low_bit(unsigned x) { return __ffs(x) - 1; }
 __device__ __forceinline__ int high_bit(unsigned x) { return 31 - __clz(x); }
+// two 16-bit counters side by side: those of an actor's two stages
+typedef short pair16 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ unsigned bits_of(pair16 v) { return __builtin_bit_cast(unsigned, v); }
+constexpr unsigned kBothSigns = 0x80008000u;
+
+// a * b + c for a, b below 2^24, b the same in all lanes: one full-rate instruction
+__device__ __forceinline__ unsigned mad24(unsigned a, unsigned b_uniform, unsigned c) {
+  unsigned r;
+  asm("v_mad_u32_u24 %0, %1, %2, %3" : "=v"(r) : "v"(a), "s"(b_uniform), "v"(c));
+  return r;
+}
 
 }  // namespace
 
@@ -138,6 +149,11 @@ __global__ __launch_bounds__(TIMED ? kGenTimedThreads : 64) void generate_kernel
   }
   int free_at = 0, mem = 0, peak = 0;
 
+  pair16 limit2 = {1, 1};
+  int w_at[V];   // the weight-gradient counters; without split backward, a word that holds m
+#pragma unroll
+  for (int c = 0; c < V; ++c) w_at[c] = has_w ? own_at[c] + 2 * S : at_m;
+
   // per-set state
   long long set = ((long long)blockIdx.x * waves_per_block + wave) * cpw + seg;   // the first set of a segment is its global index
   bool first_draw = true;
@@ -155,27 +171,11 @@ __global__ __launch_bounds__(TIMED ? kGenTimedThreads : 64) void generate_kernel
   unsigned long long first_step = 0ull;   // the loop's step counter when the set's process began
   int steps = 0;
   uint16_t* row = ops;
-  // "does any lane of my segment ..." without vector work: fold a ballot onto the lowest lane of every
-  // segment, then spread those bits over the segments' lanes
-  unsigned long long base_bits = 0ull;
-  for (int sgm = 0; sgm < cpw; ++sgm) base_bits |= 1ull << (sgm * lpc);
-  int fold_shift[6];   // shifts 1, 2, 4, ... below the segment width, then 0 (no-ops)
-#pragma unroll
-  for (int i = 0; i < 6; ++i) fold_shift[i] = (1 << i) < lpc ? (1 << i) : 0;
+  // "does any lane of my segment ...": the ballot against the lanes of the segment
+  const unsigned long long seg_lanes = (lpc == 64 ? ~0ull : ((1ull << lpc) - 1ull)) << (seg * lpc);
+  const unsigned seg_lo = (unsigned)seg_lanes, seg_hi = (unsigned)(seg_lanes >> 32);
   auto any_in_segment = [&](unsigned long long ballot) -> bool {
-    unsigned long long spread;
-    if (lpc == 64) {
-      spread = ballot ? ~0ull : 0ull;
-    } else if (lpc == 32) {   // the two halves of the wavefront on their own
-      spread = ((unsigned)ballot ? 0xffffffffull : 0ull) | ((unsigned)(ballot >> 32) ? 0xffffffff00000000ull : 0ull);
-    } else {
-      unsigned long long x = ballot;
-#pragma unroll
-      for (int i = 0; i < 6; ++i) x |= x >> fold_shift[i];
-      x &= base_bits;
-      spread = (x << lpc) - x;
-    }
-    return __builtin_amdgcn_inverse_ballot_w64(spread);
+    return (((unsigned)ballot & seg_lo) | ((unsigned)(ballot >> 32) & seg_hi)) != 0u;
   };
 
   // Every step but the last of a set schedules at least one of its 3 S m items, and a segment
@@ -249,6 +249,10 @@ __global__ __launch_bounds__(TIMED ? kGenTimedThreads : 64) void generate_kernel
         }
 #pragma unroll
         for (int c = 0; c < V; ++c) limit[c] = (has_src && c < nch) ? inflight[src * S + stage[c]] : 1;
+        if constexpr (V == 2) {   // (no stage has more than m <= 2048 micro-batches in flight)
+          limit2.x = (short)min(limit[0], 0x7fff);
+          limit2.y = (short)min(limit[1], 0x7fff);
+        }
         // a parameter set with a value outside its domain generates nothing (status 4)
         bool bad = (has_row && src < 0) || cttp < 0 || cttp > 2 || unit_f < 1 || unit_b < 1 || f_dir < 0 || f_dir > 1 || f_int < 0 ||
                    b_dir < 0 || b_dir > 1 || b_int < 0 || (cttp != 2 && (unit_f != 1 || unit_b != 1));
@@ -273,6 +277,52 @@ __global__ __launch_bounds__(TIMED ? kGenTimedThreads : 64) void generate_kernel
     // ---- read phase: the counters of this actor's own (type, stage) and of the neighbouring stages;
     // then for which stages the next item of each type is eligible (dependencies resolved, and for
     // forward items the in-flight rule).  A chunk the actor does not have is never eligible.
+    int pick_t, pick_c, p1;
+    bool is_f, is_b, move;
+    int interval, stepped0;
+    if constexpr (V == 2) {
+      // Two stages per actor: their counters side by side in 16-bit halves (no counter exceeds m <= 2048),
+      // every comparison a packed subtraction whose sign bits (bit 15: first stage, bit 31: second) say
+      // "eligible".  A missing stage reads words that hold m and is never eligible.
+      auto both = [&](int at0, int at1) {
+        pair16 v;
+        v.x = *reinterpret_cast<const short*>(&counts[at0]);
+        v.y = *reinterpret_cast<const short*>(&counts[at1]);
+        return v;
+      };
+      const pair16 nf = both(own_at[0], own_at[1]), nb = both(own_at[0] + S, own_at[1] + S);
+      const pair16 nw = both(w_at[0], w_at[1]);
+      pair16 f_ahead = both(pred_at[0][0], pred_at[1][0]), b_ahead = both(succ_at[0][0], succ_at[1][0]);
+      if (DEG > 1) {
+        f_ahead = __builtin_elementwise_min(f_ahead, both(pred_at[0][DEG > 1 ? 1 : 0], pred_at[1][DEG > 1 ? 1 : 0]));
+        b_ahead = __builtin_elementwise_min(b_ahead, both(succ_at[0][DEG > 1 ? 1 : 0], succ_at[1][DEG > 1 ? 1 : 0]));
+      }
+      const unsigned alive = live ? kBothSigns : 0u;
+      const unsigned el_f = bits_of(nf - f_ahead) & bits_of(nf - nb - limit2) & alive;
+      const unsigned el_b = bits_of(nb - __builtin_elementwise_min(nf, b_ahead)) & alive;
+      const unsigned el_w = bits_of(nw - nb) & alive;
+      // the step function: the first instruction type, in priority order, with an eligible item ...
+      const bool f_first = first == kGenF;
+      const unsigned el_first = f_first ? el_f : el_b, el_second = f_first ? el_b : el_f;
+      int type = el_w ? (int)kGenW : -1;
+      type = el_second ? (first ^ 1) : type;
+      type = el_first ? first : type;
+      pick_t = type;
+      unsigned el = el_second ? el_second : el_w;
+      el = el_first ? el_first : el;
+      is_f = pick_t == kGenF; is_b = pick_t == kGenB;
+      const int dir = is_f ? f_dir : (is_b ? b_dir : 0);
+      interval = is_f ? f_int : (is_b ? b_int : 0);
+      const int p0 = is_f ? pos_f : pos_b;
+      stepped0 = is_f ? stepped_f : stepped_b;
+      // ... then the stage: "the next stage with an eligible item" is the other one if it has one, and the
+      // first eligible stage in either direction is the only one, or the first / the last of both
+      const unsigned p0_bit = 15u | ((unsigned)p0 << 4);
+      move = stepped0 == interval || !((el >> p0_bit) & 1u);
+      p1 = (move && ((el >> (p0_bit ^ 16u)) & 1u)) ? (p0 ^ 1) : p0;
+      const int without_interval = el == kBothSigns ? dir : (int)(el >> 31);
+      pick_c = interval > 0 ? p1 : without_interval;
+    } else {
     unsigned ok_f = 0u, ok_b = 0u, ok_w = 0u;
 #pragma unroll
     for (int c = 0; c < V; ++c) {
@@ -302,15 +352,14 @@ __global__ __launch_bounds__(TIMED ? kGenTimedThreads : 64) void generate_kernel
     // ---- the step function, without branches: the first instruction type, in priority order, with an
     // eligible item; then the stage, in traversal order
     const unsigned ok_first = first == kGenF ? ok_f : ok_b, ok_second = first == kGenF ? ok_b : ok_f;
-    const int pick_t = ok_first ? first : (ok_second ? (first ^ 1) : (ok_w ? kGenW : -1));
+    pick_t = ok_first ? first : (ok_second ? (first ^ 1) : (ok_w ? kGenW : -1));
     const unsigned ok = ok_first ? ok_first : (ok_second ? ok_second : ok_w);
-    const bool is_f = pick_t == kGenF, is_b = pick_t == kGenB;
+    is_f = pick_t == kGenF; is_b = pick_t == kGenB;
     const int dir = is_f ? f_dir : (is_b ? b_dir : 0);
-    const int interval = is_f ? f_int : (is_b ? b_int : 0);
+    interval = is_f ? f_int : (is_b ? b_int : 0);
     const int p0 = is_f ? pos_f : pos_b;
-    const int stepped0 = is_f ? stepped_f : stepped_b;
-    int p1, pick_c;
-    const bool move = stepped0 == interval || !((ok >> p0) & 1u);
+    stepped0 = is_f ? stepped_f : stepped_b;
+    move = stepped0 == interval || !((ok >> p0) & 1u);
     if (V <= 2) {
       // at most two stages: "the next stage with an eligible item" is the other one if it has one, and the
       // first eligible stage in either direction is the only one, or the first / the last of both
@@ -333,6 +382,7 @@ __global__ __launch_bounds__(TIMED ? kGenTimedThreads : 64) void generate_kernel
       const int first_c = low_bit(ok), last_c = high_bit(ok);
       pick_c = interval > 0 ? p1 : (dir == 0 ? first_c : last_c);
     }
+    }
     const int stepped1 = (move ? 0 : stepped0) + 1;
     if (interval > 0 && is_f) { pos_f = p1; stepped_f = stepped1; }
     if (interval > 0 && is_b) { pos_b = p1; stepped_b = stepped1; }
@@ -342,17 +392,20 @@ __global__ __launch_bounds__(TIMED ? kGenTimedThreads : 64) void generate_kernel
       int at = own_at[0];
 #pragma unroll
       for (int c = 1; c < V; ++c) at = pick_c == c ? own_at[c] : at;
-      const int j = atomicAdd(&counts[at + (pick_t == kGenF ? 0 : (pick_t == kGenB ? S : 2 * S))], 1);
+      const int j = atomicAdd(&counts[mad24((unsigned)pick_t, (unsigned)S, (unsigned)at)], 1);
       left -= 1;
       if (TIMED) {
         // the item's row: cost, memory, where its inputs' finish times are and where its own goes
-        const int4* r = reinterpret_cast<const int4*>(lds + ((pick_t * V + pick_c) * D + d) * 8);
+        const int4* r = reinterpret_cast<const int4*>(
+            reinterpret_cast<const char*>(lds) + __umul24((unsigned)(pick_t * V + pick_c), (unsigned)D * 32u) + d * 32);
         const int4 a = r[0], b = r[1];
-        int ready = slot[a.w + j] + b.x;
-        if (DEG > 1) ready = max(ready, slot[b.y + j] + b.z);
+        // (slot offsets in the rows are byte offsets)
+        char* my_slot = reinterpret_cast<char*>(slot) + j * 4;
+        int ready = *reinterpret_cast<const int32_t*>(my_slot + a.w) + b.x;
+        if (DEG > 1) ready = max(ready, *reinterpret_cast<const int32_t*>(my_slot + b.y) + b.z);
         free_at = max(free_at, ready) + a.x;
-        slot[(DEG > 1 ? (b.w & 0xffff) : b.w) + j] = free_at;
-        if (DEG > 1) slot[(int)((unsigned)b.w >> 16) + j] = free_at;
+        *reinterpret_cast<int32_t*>(my_slot + (DEG > 1 ? (b.w & 0xffff) : b.w)) = free_at;
+        if (DEG > 1) *reinterpret_cast<int32_t*>(my_slot + ((unsigned)b.w >> 16)) = free_at;
         mem += a.y;
         peak = max(peak, mem);
         mem -= a.z;
