@@ -44,15 +44,21 @@ MEASURED_LINKS = {("cfg4", 65536): {"traffic_bytes": None, "valu_wave_instructio
                                     "valu_per_wave_round": None, "profile_kernel_ms": 6.16,
                                     "profile": "profiles/eval_slot_kernel_cfg4_link_occupancy.md"}}
 # both cost-model variants together (--links --mb-costs)
-MEASURED_BOTH = {}
+MEASURED_BOTH = {("cfg4", 65536): {"traffic_bytes": 3.765e9, "valu_wave_instructions": 3.520e9,
+                                   "valu_per_wave_round": None, "profile_kernel_ms": 8.554,
+                                   "profile": "profiles/eval_slot_kernel_cfg4_links_and_microbatch_costs.md"}}
 # the evaluation with synchronisation stages (--mode sync)
-MEASURED_SYNC = {}
+MEASURED_SYNC = {("sync4", 65536): {"traffic_bytes": None, "valu_wave_instructions": 1.068e9,
+                                   "valu_per_wave_round": None, "profile_kernel_ms": 7.12,
+                                   "profile": "profiles/eval_sync_kernel.md"}}
 # one generator launch (--mode generate): WRITE_SIZE x 1024 plus the parameter sets read
-MEASURED_GENERATE = {("cfg4", 65536): {"traffic_bytes": 4.82e9, "valu_wave_instructions": 1.016e10,
-                                       "valu_per_wave_round": None, "profile_kernel_ms": 21.8,
+MEASURED_GENERATE = {("cfg4", 65536): {"traffic_bytes": 4.82e9, "valu_wave_instructions": 9.509e9,
+                                       "valu_per_wave_round": None, "profile_kernel_ms": 17.49,
                                        "profile": "profiles/generate_kernel_cfg4.md"}}
 # generator and evaluator in one kernel (--mode search --fused)
-MEASURED_FUSED = {}
+MEASURED_FUSED = {("cfg4", 65536): {"traffic_bytes": None, "valu_wave_instructions": 8.916e9,
+                                    "valu_per_wave_round": None, "profile_kernel_ms": 16.77,
+                                    "profile": "profiles/generate_kernel_cfg4.md"}}
 # the sliding pass (--mode wslide), both of its kernels
 MEASURED_WSLIDE = {("cfg4", 65536): {"traffic_bytes": 4.06e10, "valu_wave_instructions": 5.89e9,
                                      "valu_per_wave_round": None, "profile_kernel_ms": 18.9,
