@@ -135,18 +135,21 @@ def _mb_table(mp, dur_mb):
     return t
 
 
-def evaluate(problem, words, threads: int = 1, dur_mb=None, links: bool = False):
+def evaluate(problem, words, threads: int = 1, dur_mb=None, links: bool = False, variant_loop: bool = False):
     """Evaluate a batch ``words[C][D][stride]`` (uint16).
 
     Returns dict(makespan int64[C], idle int64[C][D], peak int32[C][D],
     flags uint8[C]).  ``threads`` > 1 only splits the batch over host threads;
     every candidate is still evaluated by the same single-threaded C routine.
     ``dur_mb[8][S][m]``: per-micro-batch costs in place of ``problem.dur``.  ``links``: every ordered
-    pair of devices is a link that carries one value at a time (see fporacle_evaluate_links).
+    pair of devices is a link that carries one value at a time (see fporacle_evaluate_links).  Without either
+    the plain definition runs (eval_one in fporacle.c); ``variant_loop`` sends such a call through the
+    variants' loop with both switches off instead (for the tests that compare the two loops).
     """
     lib = _load()
     mp = _Marshalled(problem)
     table = _mb_table(mp, dur_mb)
+    plain = table is None and not links and not variant_loop
     table_ptr = ctypes.c_void_p(table.ctypes.data if table is not None else None)
     w = np.ascontiguousarray(np.asarray(words, dtype=np.uint16))
     assert w.ndim == 3 and w.shape[1] == mp.D, w.shape
@@ -157,6 +160,13 @@ def evaluate(problem, words, threads: int = 1, dur_mb=None, links: bool = False)
     def run(lo, hi):
         if hi <= lo:
             return 0
+        if plain:
+            return lib.fporacle_evaluate(
+                ctypes.byref(mp.c), ctypes.c_void_p(w[lo:hi].ctypes.data), ctypes.c_int64(hi - lo),
+                ctypes.c_int32(stride), ctypes.c_void_p(out["makespan"][lo:hi].ctypes.data),
+                ctypes.c_void_p(out["idle"][lo:hi].ctypes.data),
+                ctypes.c_void_p(out["peak"][lo:hi].ctypes.data),
+                ctypes.c_void_p(out["flags"][lo:hi].ctypes.data))
         if links:
             return lib.fporacle_evaluate_links(
                 ctypes.byref(mp.c), table_ptr, ctypes.c_void_p(w[lo:hi].ctypes.data), ctypes.c_int64(hi - lo),
@@ -185,7 +195,7 @@ def evaluate(problem, words, threads: int = 1, dur_mb=None, links: bool = False)
     return out
 
 
-def evaluate_trace(problem, words_one, dur_mb=None, links: bool = False):
+def evaluate_trace(problem, words_one, dur_mb=None, links: bool = False, variant_loop: bool = False):
     """One candidate ``words[D][stride]``; also returns every op's start/finish."""
     lib = _load()
     mp = _Marshalled(problem)
@@ -203,7 +213,10 @@ def evaluate_trace(problem, words_one, dur_mb=None, links: bool = False):
             ctypes.c_void_p(idle.ctypes.data), ctypes.c_void_p(peak.ctypes.data), ctypes.c_void_p(fl.ctypes.data),
             ctypes.c_void_p(st.ctypes.data), ctypes.c_void_p(fi.ctypes.data))
     table_ptr = ctypes.c_void_p(table.ctypes.data if table is not None else None)
-    rc = (lib.fporacle_eval_one_links if links else lib.fporacle_eval_one_mb)(ctypes.byref(mp.c), table_ptr, *tail)
+    if table is None and not links and not variant_loop:
+        rc = lib.fporacle_eval_one(ctypes.byref(mp.c), *tail)
+    else:
+        rc = (lib.fporacle_eval_one_links if links else lib.fporacle_eval_one_mb)(ctypes.byref(mp.c), table_ptr, *tail)
     if rc:
         raise ValueError("fporacle: invalid problem description")
     return dict(makespan=int(ms[0]), idle=idle, peak=peak, flags=int(fl[0]), start=st, finish=fi)

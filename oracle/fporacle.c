@@ -40,6 +40,11 @@
  *   - ranking key is (makespan ascending, candidate index ascending): total
  *     work is fixed per problem, so least bubble ratio == least makespan.
  *
+ * Layout of this file: eval_one is the definition above and nothing else.  The two variants of the
+ * cost model (costs per micro-batch, link occupancy) are a loop of their own further down,
+ * eval_one_variants, which repeats the definition with the two switches; with both off it must give
+ * what eval_one gives, and the tests compare the two loops.
+ *
  * Parity pins (tests/, -m "not gpu"): GPipe and 1F1B closed forms, an
  * independent longest-path + Kahn checker, brute force over all order pairs
  * for p=2, m<=3, order-only memory scan, monotonicity, and the input
@@ -104,7 +109,151 @@ static int build_local_stage(const fporacle_problem *P, int32_t *local_stage, in
  * (-1 where the op never issued or past the end of the list).
  * Returns 0, or -1 for an invalid problem.
  */
-static int eval_one(const fporacle_problem *P, const int32_t *dur_mb, int links, const uint16_t *words, int32_t stride,
+static int eval_one(const fporacle_problem *P, const uint16_t *words, int32_t stride,
+                    int64_t *makespan, int64_t *idle, int32_t *peak, uint8_t *flags,
+                    int64_t *op_start, int64_t *op_finish) {
+  const int D = P->n_devices, S = P->n_stages, m = P->n_microbatches;
+  int32_t *local_stage = malloc(sizeof(int32_t) * D * MAX_CHUNKS);
+  int32_t *n_chunks = malloc(sizeof(int32_t) * D);
+  if (build_local_stage(P, local_stage, n_chunks)) { free(local_stage); free(n_chunks); return -1; }
+
+  int64_t *fin_fwd = malloc(sizeof(int64_t) * S * m);   /* finish of F/FD(s,j), -1 = not yet */
+  int64_t *fin_bwd = malloc(sizeof(int64_t) * S * m);   /* finish of B(s,j) */
+  uint8_t *state = calloc((size_t)S * m, 1);
+  int32_t *cursor = calloc(D, sizeof(int32_t));
+  int32_t *len = calloc(D, sizeof(int32_t));
+  int64_t *free_at = calloc(D, sizeof(int64_t));
+  int64_t *busy = calloc(D, sizeof(int64_t));
+  int64_t *mem = calloc(D, sizeof(int64_t));
+  int64_t *pk = calloc(D, sizeof(int64_t));
+  for (int i = 0; i < S * m; ++i) fin_fwd[i] = fin_bwd[i] = -1;
+  for (int d = 0; d < D; ++d) {
+    int n = 0;
+    while (n < stride && word_kind(words[(size_t)d * stride + n]) != K_END) ++n;
+    len[d] = n;
+  }
+  if (op_start) for (int64_t i = 0; i < (int64_t)D * stride; ++i) op_start[i] = op_finish[i] = -1;
+
+  int malformed_head = 0;
+  for (;;) {
+    int issued_any = 0;
+    malformed_head = 0;
+    for (int d = 0; d < D; ++d) {
+      if (cursor[d] >= len[d]) continue;
+      const uint16_t w = words[(size_t)d * stride + cursor[d]];
+      const int kind = word_kind(w), c = word_chunk(w), j = word_mb(w);
+      if (c >= n_chunks[d] || j >= m || (kind == K_W && !P->has_w)) { malformed_head = 1; continue; }
+      const int s = local_stage[d * MAX_CHUNKS + c];
+      uint8_t *st = &state[(size_t)s * m + j];
+
+      /* same-device rule: required source state */
+      int need;
+      switch (kind) {
+        case K_F: case K_FD: need = ST_ABSENT; break;
+        case K_R: need = ST_DISC; break;
+        case K_O: need = ST_RES; break;
+        case K_L: need = ST_OFF; break;
+        case K_B: need = ST_RES; break;
+        default:  need = ST_BDONE; break; /* K_W */
+      }
+      if (*st != need) continue;
+
+      /* cross-stage rule */
+      int64_t ready = 0;
+      int blocked = 0;
+      if (kind == K_F || kind == K_FD) {
+        for (int e = 0; e < P->n_edges && !blocked; ++e) {
+          if (P->edge_dst[e] != s) continue;
+          const int sp = P->edge_src[e];
+          const int64_t t = fin_fwd[(size_t)sp * m + j];
+          if (t < 0) { blocked = 1; break; }
+          const int64_t r = t + (P->stage_device[sp] != d ? P->edge_comm[e] : 0);
+          if (r > ready) ready = r;
+        }
+      } else if (kind == K_B) {
+        for (int e = 0; e < P->n_edges && !blocked; ++e) {
+          if (P->edge_src[e] != s) continue;
+          const int sn = P->edge_dst[e];
+          const int64_t t = fin_bwd[(size_t)sn * m + j];
+          if (t < 0) { blocked = 1; break; }
+          const int64_t r = t + (P->stage_device[sn] != d ? P->edge_comm[e] : 0);
+          if (r > ready) ready = r;
+        }
+      }
+      if (blocked) continue;
+
+      /* issue */
+      const int64_t dt = P->dur[kind * S + s];
+      const int64_t u = P->mem_units[s];
+      const int64_t start = free_at[d] > ready ? free_at[d] : ready;
+      const int64_t finish = start + dt;
+      if (kind == K_F || kind == K_FD || kind == K_R || kind == K_L) {
+        mem[d] += u;
+        if (mem[d] > pk[d]) pk[d] = mem[d];
+      }
+      if (kind == K_FD || kind == K_O) mem[d] -= u;
+      if (kind == K_W || (kind == K_B && !P->has_w)) mem[d] -= u;
+      switch (kind) {
+        case K_F:  *st = ST_RES;  fin_fwd[(size_t)s * m + j] = finish; break;
+        case K_FD: *st = ST_DISC; fin_fwd[(size_t)s * m + j] = finish; break;
+        case K_R:  *st = ST_RES; break;
+        case K_O:  *st = ST_OFF; break;
+        case K_L:  *st = ST_RES; break;
+        case K_B:  *st = ST_BDONE; fin_bwd[(size_t)s * m + j] = finish; break;
+        default:   *st = ST_DONE; break;
+      }
+      if (op_start) {
+        op_start[(size_t)d * stride + cursor[d]] = start;
+        op_finish[(size_t)d * stride + cursor[d]] = finish;
+      }
+      free_at[d] = finish;
+      busy[d] += dt;
+      cursor[d] += 1;
+      issued_any = 1;
+    }
+    if (!issued_any) break;
+  }
+
+  uint8_t fl = 0;
+  for (int d = 0; d < D; ++d) if (cursor[d] < len[d]) fl |= FLAG_DEADLOCK;
+  if (fl && malformed_head) fl |= FLAG_INCOMPLETE;
+  if (!fl) {
+    const int terminal = P->has_w ? ST_DONE : ST_BDONE;
+    for (int i = 0; i < S * m; ++i) if (state[i] != terminal) { fl |= FLAG_INCOMPLETE; break; }
+  }
+  if (fl) {
+    *makespan = INT64_MAX;
+    for (int d = 0; d < D; ++d) { idle[d] = -1; peak[d] = -1; }
+  } else {
+    int64_t ms = 0;
+    for (int d = 0; d < D; ++d) if (free_at[d] > ms) ms = free_at[d];
+    *makespan = ms;
+    for (int d = 0; d < D; ++d) {
+      idle[d] = ms - busy[d];
+      peak[d] = (int32_t)pk[d];
+      if (pk[d] > P->mem_cap[d]) fl |= FLAG_OVER_CAP;
+    }
+  }
+  *flags = fl;
+
+  free(local_stage); free(n_chunks); free(fin_fwd); free(fin_bwd); free(state);
+  free(cursor); free(len); free(free_at); free(busy); free(mem); free(pk);
+  return 0;
+}
+
+int fporacle_eval_one(const fporacle_problem *P, const uint16_t *words, int32_t stride,
+                      int64_t *makespan, int64_t *idle, int32_t *peak, uint8_t *flags,
+                      int64_t *op_start, int64_t *op_finish) {
+  return eval_one(P, words, stride, makespan, idle, peak, flags, op_start, op_finish);
+}
+
+/*
+ * The variants of the cost model (costs per micro-batch, link occupancy; see the entry points below),
+ * as a loop of their own: the plain definition above, written out again with the two switches.  With
+ * dur_mb == NULL and links == 0 it must give what eval_one gives (tests/test_oracle_mbdur.py,
+ * tests/test_oracle_links.py compare the two loops).
+ */
+static int eval_one_variants(const fporacle_problem *P, const int32_t *dur_mb, int links, const uint16_t *words, int32_t stride,
                     int64_t *makespan, int64_t *idle, int32_t *peak, uint8_t *flags,
                     int64_t *op_start, int64_t *op_finish) {
   const int D = P->n_devices, S = P->n_stages, m = P->n_microbatches, E = P->n_edges;
@@ -266,11 +415,6 @@ static int eval_one(const fporacle_problem *P, const int32_t *dur_mb, int links,
   return 0;
 }
 
-int fporacle_eval_one(const fporacle_problem *P, const uint16_t *words, int32_t stride,
-                      int64_t *makespan, int64_t *idle, int32_t *peak, uint8_t *flags,
-                      int64_t *op_start, int64_t *op_finish) {
-  return eval_one(P, NULL, 0, words, stride, makespan, idle, peak, flags, op_start, op_finish);
-}
 
 /*
  * Variant of the cost model: micro-batches of unequal size.  The paper profiles one cost per
@@ -284,7 +428,7 @@ int fporacle_eval_one(const fporacle_problem *P, const uint16_t *words, int32_t 
 int fporacle_eval_one_mb(const fporacle_problem *P, const int32_t *dur_mb, const uint16_t *words,
                          int32_t stride, int64_t *makespan, int64_t *idle, int32_t *peak, uint8_t *flags,
                          int64_t *op_start, int64_t *op_finish) {
-  return eval_one(P, dur_mb, 0, words, stride, makespan, idle, peak, flags, op_start, op_finish);
+  return eval_one_variants(P, dur_mb, 0, words, stride, makespan, idle, peak, flags, op_start, op_finish);
 }
 
 /* Evaluate candidates [0, n_cand) of a batch laid out [C][D][stride]; dur_mb may be NULL. */
@@ -293,7 +437,7 @@ int fporacle_evaluate_mb(const fporacle_problem *P, const int32_t *dur_mb, const
                          uint8_t *flags) {
   const int D = P->n_devices;
   for (int64_t c = 0; c < n_cand; ++c) {
-    int rc = eval_one(P, dur_mb, 0, words + (size_t)c * D * stride, stride, &makespan[c],
+    int rc = eval_one_variants(P, dur_mb, 0, words + (size_t)c * D * stride, stride, &makespan[c],
                       &idle[c * D], &peak[c * D], &flags[c], NULL, NULL);
     if (rc) return rc;
   }
@@ -315,7 +459,7 @@ int fporacle_evaluate_mb(const fporacle_problem *P, const int32_t *dur_mb, const
 int fporacle_eval_one_links(const fporacle_problem *P, const int32_t *dur_mb, const uint16_t *words, int32_t stride,
                             int64_t *makespan, int64_t *idle, int32_t *peak, uint8_t *flags, int64_t *op_start,
                             int64_t *op_finish) {
-  return eval_one(P, dur_mb, 1, words, stride, makespan, idle, peak, flags, op_start, op_finish);
+  return eval_one_variants(P, dur_mb, 1, words, stride, makespan, idle, peak, flags, op_start, op_finish);
 }
 
 /* dur_mb: NULL, or costs per micro-batch as in fporacle_evaluate_mb (the two variants are independent: one
@@ -324,16 +468,23 @@ int fporacle_evaluate_links(const fporacle_problem *P, const int32_t *dur_mb, co
                             int32_t stride, int64_t *makespan, int64_t *idle, int32_t *peak, uint8_t *flags) {
   const int D = P->n_devices;
   for (int64_t c = 0; c < n_cand; ++c) {
-    int rc = eval_one(P, dur_mb, 1, words + (size_t)c * D * stride, stride, &makespan[c],
+    int rc = eval_one_variants(P, dur_mb, 1, words + (size_t)c * D * stride, stride, &makespan[c],
                       &idle[c * D], &peak[c * D], &flags[c], NULL, NULL);
     if (rc) return rc;
   }
   return 0;
 }
 
+/* The plain model: candidates [0, n_cand) of a batch laid out [C][D][stride], each by eval_one. */
 int fporacle_evaluate(const fporacle_problem *P, const uint16_t *words, int64_t n_cand, int32_t stride,
                       int64_t *makespan, int64_t *idle, int32_t *peak, uint8_t *flags) {
-  return fporacle_evaluate_mb(P, NULL, words, n_cand, stride, makespan, idle, peak, flags);
+  const int D = P->n_devices;
+  for (int64_t c = 0; c < n_cand; ++c) {
+    int rc = eval_one(P, words + (size_t)c * D * stride, stride, &makespan[c], &idle[c * D], &peak[c * D],
+                      &flags[c], NULL, NULL);
+    if (rc) return rc;
+  }
+  return 0;
 }
 
 typedef struct { int64_t makespan, idx; } rank_key;

@@ -7,7 +7,7 @@ import pytest
 import checker
 import oracle
 import workloads
-from helpers import perturb, random_valid_lists, two_tower_problem
+from helpers import batch_from_lists, perturb, random_valid_lists, two_tower_problem
 from workloads.problem import B, F, chain_problem, gpipe_lists, pack_lists
 
 NKINDS = 8
@@ -114,6 +114,34 @@ def test_a_constant_table_is_the_plain_model(index, n):
     same = oracle.evaluate(spec.problem, words, threads=4, dur_mb=constant_table(spec.problem))
     for name in plain:
         assert np.array_equal(plain[name], same[name]), name
+
+
+def test_the_variants_loop_with_both_switches_off_is_the_plain_definition():
+    # fporacle.c holds the plain definition (eval_one) and, written out again with the two switches, the loop
+    # of the cost-model variants: with no cost table and no link occupancy the second must repeat the first,
+    # results and every op's times, also on lists that deadlock, end early or carry malformed words
+    for index, n in ((2, 150), (5, 80)):
+        spec = workloads.config(index, n)
+        words = workloads.generate(spec, threads=4)
+        a = oracle.evaluate(spec.problem, words, threads=4)
+        b = oracle.evaluate(spec.problem, words, threads=4, variant_loop=True)
+        for name in a:
+            assert np.array_equal(a[name], b[name]), name
+    rng = np.random.default_rng(77)
+    prob = chain_problem(3, 4, v=2, f=2, b=3, w=1, comm=2)
+    for trial in range(40):
+        lists = random_valid_lists(prob, rng, 0.3, 0.3)
+        if trial % 3 == 1:
+            lists = perturb(lists, rng, 2)
+        if trial % 3 == 2:
+            lists = [l[:max(0, len(l) - int(rng.integers(0, 3)))] for l in lists]
+        one = batch_from_lists([lists])[0]
+        if trial % 10 == 9:
+            one[0, 0] = np.uint16((3 << 13) | (3 << 11))   # a chunk the device does not have
+        a, b = oracle.evaluate_trace(prob, one), oracle.evaluate_trace(prob, one, variant_loop=True)
+        assert a["makespan"] == b["makespan"] and a["flags"] == b["flags"]
+        for name in ("idle", "peak", "start", "finish"):
+            assert np.array_equal(a[name], b[name]), (trial, name)
 
 
 def test_raising_one_cost_never_shortens_a_schedule_and_busy_time_follows():
