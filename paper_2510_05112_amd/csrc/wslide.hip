@@ -18,7 +18,7 @@
 //      item at the list cursor (or the list is over), else that item.  The new row leaves in
 //      16-byte pieces collected in registers; memory is accounted along the new order.
 // No global load sits on a step's critical path: op words and the low halves of their start times reach a
-// lane through a 32-position LDS window that the whole wavefront tops up every fourth step, sixteen
+// lane through a 32-position LDS window that the whole wavefront tops up every eighth step, sixteen
 // positions (32 bytes of each) at a time, the loads requested at one top-up landing at the next.  (With
 // loads issued by each lane when it needs them the wavefront waited for memory in nearly every step:
 // among 64 lanes at 64 different positions some lane always needs its next piece.)  The first kernel
@@ -37,7 +37,8 @@ namespace {
 
 constexpr int kWin = 32;      // window: positions per lane (op words and the low halves of their start times)
 constexpr int kPiece = 16;    // positions per load: 32 bytes of op words, 32 bytes of start times
-constexpr int kRefillAt = 12; // a lane asks for its next piece when at most this many positions are unread
+constexpr int kRefillAt = 16; // a lane asks for its next piece when at most this many positions are unread
+constexpr unsigned kTopUpMask = 7u;   // the window is topped up every eighth step
 constexpr int kFifo = 16;     // stash ring: B words per lane
 static_assert((2 * kWin + kFifo) * 64 * 2 == kSlideWaveLdsBytes, "LDS of one wavefront");
 
@@ -87,7 +88,7 @@ __global__ __launch_bounds__(kSlideThreads) void wslide_place_kernel(
   const bool at_end = active && (end_word >> 13) == (unsigned)kEnd;
 
   // window: positions [loaded - kWin, loaded) of the row are in the rings; the whole wavefront tops
-  // them up every fourth step, the loads requested at one top-up landing at the next
+  // them up every eighth step, the loads requested at one top-up landing at the next
   int loaded = 0;
   uint4 pend_w0 = make_uint4(0u, 0u, 0u, 0u), pend_w1 = pend_w0, pend_s0 = pend_w0, pend_s1 = pend_w0;
   bool has_pend = false;
@@ -153,7 +154,7 @@ __global__ __launch_bounds__(kSlideThreads) void wslide_place_kernel(
   // stashed item runs if it ends by the start of that item (or the list is over); else the item issues, or
   // a W word of the input is passed over.
   for (unsigned step = 0;; ++step) {
-    if ((step & 3u) == 0u) {
+    if ((step & kTopUpMask) == 0u) {
       if (has_pend) {
         land();
         has_pend = false;
