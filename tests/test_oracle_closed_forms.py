@@ -77,3 +77,28 @@ def test_first_op_times_and_comm_only_across_devices():
     r = _eval(prob, [[(F, 0, 0), (B, 0, 0)], [(F, 0, 0), (B, 0, 0)]])
     assert r["makespan"] == 3 + 100 + 3 + 5 + 100 + 5
     assert r["start"][1][0] == 103 and r["start"][0][1] == 211
+
+
+def test_hand_worked_timeline_with_recompute_offload_and_reload_on_two_devices():
+    # Two stages on two devices, two micro-batches, latency 1, split backward.  Costs F/B/W/R/O/L: stage 0
+    # 2/3/1/2/4/3 (2 units per activation), stage 1 3/2/2/3/1/1 (5 units).  Worked by hand:
+    #  device 0: FD(0,0) 0-2 | F(0,1) 2-4 | O(0,1) 4-8 | R(0,0) 8-10 | B(0,0) waits for B(1,0) (15) + 1: 16-19 |
+    #            L(0,1) 19-22 | W(0,0) 22-23 | B(0,1) (its gradient came at 12 + 1) 23-26 | W(0,1) 26-27
+    #  device 1: F(1,0) waits for FD(0,0) (2) + 1: 3-6 | F(1,1) (input at 4 + 1, device free at 6) 6-9 |
+    #            O(1,0) 9-10 | B(1,1) 10-12 | L(1,0) 12-13 | B(1,0) 13-15 | W(1,1) 15-17 | W(1,0) 17-19
+    #  memory, device 0: +2 -2 (discarding forward), +2 (F), -2 (offload done), +2 (recompute), +2 (reload) = 4
+    #  at most; device 1: 5, 10 (two forward passes), 5 after the offload, 10 again with the reload.
+    from workloads.problem import B, F, FD, L, O, R, W, make_problem
+    dur = {F: [2, 3], FD: [2, 3], B: [3, 2], W: [1, 2], R: [2, 3], O: [4, 1], L: [3, 1]}
+    prob = make_problem(2, 2, 2, 1, [0, 1], [(0, 1, 1)], dur, mem_units=[2, 5])
+    lists = [[(FD, 0, 0), (F, 0, 1), (O, 0, 1), (R, 0, 0), (B, 0, 0), (L, 0, 1), (W, 0, 0), (B, 0, 1), (W, 0, 1)],
+             [(F, 0, 0), (F, 0, 1), (O, 0, 0), (B, 0, 1), (L, 0, 0), (B, 0, 0), (W, 0, 1), (W, 0, 0)]]
+    r = _eval(prob, lists)
+    assert r["flags"] == 0 and r["makespan"] == 27
+    assert list(r["start"][0][:9]) == [0, 2, 4, 8, 16, 19, 22, 23, 26]
+    assert list(r["start"][1][:8]) == [3, 6, 9, 10, 12, 13, 15, 17]
+    assert list(r["finish"][0][:9]) == [2, 4, 8, 10, 19, 22, 23, 26, 27]
+    assert list(r["idle"]) == [27 - 21, 27 - 16] and list(r["peak"]) == [4, 10]
+    # the backward pass of an offloaded activation cannot run before its reload
+    stuck = [list(lists[0]), [(F, 0, 0), (F, 0, 1), (O, 0, 0), (B, 0, 0), (L, 0, 0), (B, 0, 1), (W, 0, 1), (W, 0, 0)]]
+    assert _eval(prob, stuck)["flags"] & 1               # B(1,0) while its activation is offloaded: never runs
