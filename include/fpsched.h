@@ -225,7 +225,9 @@ int fpsched_problem_set_sync(fpsched_problem *p, const int32_t *group, int32_t n
  * the tables do not fit LDS or while costs per micro-batch, link occupancy or fpsched_problem_set_sync
  * are in force (and those setters, fpsched_wslide answer FPSCHED_EUNSUPPORTED while this is): the
  * handle keeps what it had.  Synchronous; allocates one table of device memory at most; works on a
- * host-only handle (validation only). */
+ * host-only handle (validation only).  Both evaluation kernels have a form of this model: the slot
+ * kernel's runs when the problem fits it (fpsched_problem_select_kernel chooses as for the plain
+ * model), and then fpsched_evaluate needs its workspace as in the plain model. */
 #define FPSCHED_MAX_COPY_DEPTH 7
 int fpsched_problem_set_copy_engine(fpsched_problem *p, int32_t depth);
 

@@ -104,6 +104,8 @@ struct SlotTables {
                             // the dev rows then have 4V more ints: per chunk the first forward / first backward /
                             // second forward / second backward out-edge as latency << 16 | byte offset of its
                             // link word (link index * 256)
+  int32_t copy_depth;       // copy-engine form: transfers the engine holds at most (1..7), else 0; link_words is
+                            // then the number of ring dwords per lane behind its state words
   uint32_t mb_kind_map;     // four bits per kind: which block of the table at off_mb holds the kind's costs
                             // (kinds with the same costs share a block)
   const int32_t* ints;      // DEVICE

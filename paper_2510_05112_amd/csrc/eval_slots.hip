@@ -130,6 +130,18 @@ __global__ void reset_counter_kernel(unsigned long long* counter, unsigned long 
 // value leaves, max(finish, link busy until), and keeps the link busy for the edge's latency from then;
 // the consumer adds the latency as before.  The link word of the current op is read when the op is
 // decoded (only the lane itself ever writes it, in program order before that read).
+//
+// MODE kSlotCopy: the copy-engine variant of the cost model (the paper names CPU offloading without saying how
+// an offload is timed).  Offload and reload items run on a copy timeline of the device: the walk through the
+// list hands such an item to the engine when it reaches it and goes on at once, unless T.copy_depth transfers
+// are still unfinished (then it waits for the oldest of them); a transfer starts at max(hand-over, finish of the
+// transfer before it).  A backward item waits for the reload of its activation: a reload sets bit 3 of the
+// activation's state nibble (the decision looks at the low three bits only), and a backward item that finds the
+// bit looks for its (chunk, micro-batch) among the last copy_depth transfers, which a lane keeps in a ring
+// (older ones have finished before the walk got here).  Memory becomes a sum over events in time order: the
+// transfers' events (a reload allocates at its start, an offload releases at its end) wait in a second ring
+// and are applied as the walk passes their time, compute events first at equal times.  Transfers are no busy
+// time; the makespan covers both timelines.
 template <int V, bool DEG2, bool ONE_CLASS, int MODE>
 __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     SlotTables T, const uint16_t* __restrict__ ops, long long n_cand, int stride,
@@ -142,6 +154,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   constexpr bool MBDUR = MODE == kSlotPerMicrobatch;
   constexpr bool MBLDS = MODE == kSlotPerMicrobatchLds || MODE == kSlotPerMicrobatchLdsLinks;
   constexpr bool LINKS = MODE == kSlotLinks || MODE == kSlotTimesLinks || MODE == kSlotPerMicrobatchLdsLinks;
+  constexpr bool COPY = MODE == kSlotCopy;
   extern __shared__ int32_t lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int m = T.m;
@@ -160,7 +173,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   // window: kRing sixteen-bit words per lane, laid out [word][lane]
   uint16_t* win = reinterpret_cast<uint16_t*>(L + shared_bytes + wave * (kRing * 128u));
   uint32_t* stt = reinterpret_cast<uint32_t*>(L + rest_off);              // [state word][lane]
-  const int lane_words = T.state_words + (LINKS ? T.link_words : 0);   // state words, then link words
+  const int lane_words = T.state_words + (LINKS || COPY ? T.link_words : 0);   // state words, then link words / rings
   uint32_t* slots = stt + lane_words * 64;
   const int slots_per_cand = T.slots_per_cand;  // backward, forward, dump; a multiple of 8
   // TIMES: one dword behind the last wavefront's region stays zero; it is the state word of W words
@@ -255,6 +268,24 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   int4 M = make_int4(0, 0, 15, 0);   // metadata row of the current word (an invalid row to begin with)
   int2 M2 = make_int2(0, 0);         // its second-edge row
   unsigned w_next = 0u;              // the word behind the current one
+  // COPY: the copy timeline of this device.  Rings of eight dwords per lane behind its state words (entry i at
+  // + i * 256): finish << 8 of the last transfers, their keys (low 13 bits of a reload's word, all ones for an
+  // offload), time << 8 and units of the transfer events that the walk has not passed yet.
+  const unsigned ring_fin = stt_off + (unsigned)T.state_words * 256u;
+  const unsigned ring_key = ring_fin + 8u * 256u, ring_ev_time = ring_fin + 16u * 256u, ring_ev_units = ring_fin + 24u * 256u;
+  const unsigned copy_depth = (unsigned)T.copy_depth;
+  unsigned copy_free8 = 0u, n_copy = 0u, ev_head = 0u, ev_tail = 0u;
+  unsigned next_ev8 = 0xffffffffu;   // time << 8 of the oldest pending event (all ones: none)
+  unsigned cur_kind = 0u, cur_key = 0u;   // kind and (chunk, micro-batch) bits of the current word
+  // apply the pending transfer events that come before a compute event at `limit8`
+  auto pass_time = [&](unsigned limit8) {
+    while (next_ev8 < limit8) {
+      mem += (int)lds_read<uint32_t>(ring_ev_units + ((ev_head & 7u) << 8));
+      pk = max(pk, mem);
+      ++ev_head;
+      next_ev8 = ev_head != ev_tail ? lds_read<uint32_t>(ring_ev_time + ((ev_head & 7u) << 8)) : 0xffffffffu;
+    }
+  };
   int dur_mb8 = 0;                   // MBDUR: cost << 8 of the current word
   const unsigned mb_lane = (unsigned)d * (unsigned)m;   // this device's part of a row of mb_rows
   const unsigned mb_row_ints = (unsigned)lpc * (unsigned)m;
@@ -277,6 +308,10 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   const unsigned dump_bytes = (unsigned)(2 * T.n_classes * m) * 4u;   // offset of the slots nobody reads
   unsigned out1 = link_dummy, out2 = link_dummy, at_link1 = link_base, lf1 = 0u;
   auto decode = [&](unsigned word) {
+    if (COPY) {
+      cur_kind = word >> 13;
+      cur_key = word & 0x1fffu;
+    }
     const unsigned j = word & 0x7ffu;
     const unsigned jc = min(j, (unsigned)m - 1u);
     const unsigned c5 = word >> 11;
@@ -416,6 +451,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
         priming = running;
         dead = ~0u;
         npos = 128u; free_at8 = 0; busy8 = 0; mem = 0; pk = 0;
+        copy_free8 = 0u; n_copy = 0u; ev_head = 0u; ev_tail = 0u; next_ev8 = 0xffffffffu;
         has_pend = false;
         loaded = 0;
         if (running) {
@@ -423,6 +459,8 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
         }
         if (running && lane_ok) {
           for (int i = 0; i < lane_words; ++i) stt[i * 64 + lane] = 0u;
+          if (COPY)   // no transfer yet: keys that no word has
+            for (unsigned i = 0; i < 8u; ++i) lds_write<uint32_t>(ring_key + (i << 8), 0xffffffffu);
           row = ops + ((size_t)cand * T.D + d) * (size_t)stride;
           // start times: [candidate][group of eight positions][lane of the candidate][8 x 16 bits]
           if (TIMES) {
@@ -468,7 +506,8 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     // state; input slot not tagged with the upstream stage (only if the op has an input: the top
     // byte of the last metadata dword is 0xff then, else 0).  A live lane has dead == 0, any other
     // lane all ones, which the word never equals.
-    const unsigned state = __builtin_amdgcn_ubfe(sx, bj, 4);
+    // (COPY: bit 3 of the nibble only says that the activation was reloaded)
+    const unsigned state = __builtin_amdgcn_ubfe(sx, bj, COPY ? 3 : 4);
     unsigned ready8 = (in1 + lat_tag) & (unsigned)((int)my_ >> 24);
     // (only the low byte counts: the state nibble is clean, byte 0 of the third metadata dword
     // holds nothing but the required state, and the ready time sits above its tag byte)
@@ -484,8 +523,44 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
                  : "=s"(moved) : "v"(veto), "v"(dead));
     const bool ok = __builtin_amdgcn_inverse_ballot_w64(moved);
     // ---- issue
-    if (ok) {
-      const unsigned start8 = max(free_at8, ready8);
+    const bool transfer = COPY && (cur_kind - (unsigned)kO) < 2u;   // kO, kL
+    if (COPY && ok && transfer) {
+      // hand the transfer to the engine (waiting for room), time it on the copy timeline
+      unsigned handover8 = free_at8;
+      if (n_copy >= copy_depth) handover8 = max(handover8, lds_read<uint32_t>(ring_fin + (((n_copy - copy_depth) & 7u) << 8)));
+      const unsigned begin8 = max(handover8, copy_free8);
+      copy_free8 = begin8 + dur8;
+      const bool reload = cur_kind == (unsigned)kL;
+      lds_write<uint32_t>(ring_fin + ((n_copy & 7u) << 8), copy_free8);
+      lds_write<uint32_t>(ring_key + ((n_copy & 7u) << 8), reload ? cur_key : 0xffffffffu);
+      ++n_copy;
+      free_at8 = handover8;
+      pass_time(handover8);
+      // its memory event: a reload allocates when it starts, an offload releases when it ends
+      const unsigned ev8 = reload ? begin8 : copy_free8;
+      lds_write<uint32_t>(ring_ev_time + ((ev_tail & 7u) << 8), ev8);
+      lds_write<uint32_t>(ring_ev_units + ((ev_tail & 7u) << 8),
+                          reload ? (my_ & 0xffu) : 0u - ((my_ >> 8) & 0xffu));
+      next_ev8 = ev_head == ev_tail ? ev8 : next_ev8;
+      ++ev_tail;
+      unsigned flip;
+      asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1"
+          : "=v"(flip) : "v"(bj), "v"(mx_));
+      // (a reload marks the activation: bit 3 of its nibble)
+      lds_write<uint32_t>(at_state, (sx ^ flip) | (reload ? 8u << (bj & 31u) : 0u));
+      decode(w_next);
+      npos += 128u;
+      w_next = lds_read<uint16_t>((npos & ((kRing - 1) << 7)) | win_off);
+    }
+    if (ok && !transfer) {
+      unsigned start8 = max(free_at8, ready8);
+      if (COPY && cur_kind == (unsigned)kB && ((sx >> (bj & 31u)) & 8u) != 0u) {
+        // the activation was reloaded: if that transfer is among the last copy_depth ones it may still run
+        for (unsigned i = 1; i <= copy_depth; ++i) {
+          const unsigned at = ((n_copy - i) & 7u) << 8;
+          if (lds_read<uint32_t>(ring_key + at) == cur_key) start8 = max(start8, lds_read<uint32_t>(ring_fin + at));
+        }
+      }
       const unsigned fin8 = start8 + dur8;
       if (TIMES) {
         // shift bits 8..23 of the start time (its low half in time units) into the 16 bytes
@@ -501,8 +576,10 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
         if ((wait8 >> 24) != 0u && n_esc < escape_cap - 1)
           esc_row[n_esc++] = (((npos >> 7) - 1u) << 8) | (wait8 >> 24);
       }
+      if (COPY) pass_time(start8);
       mem += (int)(my_ & 0xffu);
       pk = max(pk, mem);
+      if (COPY) pass_time(fin8);
       mem -= (int)((my_ >> 8) & 0xffu);
       // state ^= (need ^ next) << nibble position; the shift takes the low five bits of bj
       unsigned flip;
@@ -568,14 +645,16 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
         const int4 Mh = lds_read<int4>(__umul24(w >> 11, row_bytes) + meta_off);
         bad_head = (w >> 13) != 0u && (((unsigned)Mh.z & 15u) == 15u || (int)(w & 0x7ff) >= m);
         // every activation of this device consumed?
-        for (int i = 0; i < T.state_words; ++i) incomplete = incomplete || (stt[i * 64 + lane] != (unsigned)expect[i]);
+        for (int i = 0; i < T.state_words; ++i)
+          incomplete = incomplete || ((stt[i * 64 + lane] & (COPY ? 0x77777777u : ~0u)) != (unsigned)expect[i]);
+        if (COPY) pass_time(0xffffffffu);   // what the copy engine still had to do when the list ended
       }
       // (kind 0 ends a list whatever its low bits are)
       const unsigned long long stuck = __ballot(lane_ok && (w >> 13) != 0u) & seg_mask;
       const unsigned long long stuck_bad = __ballot(bad_head) & seg_mask;
       const unsigned long long unfinished = __ballot(incomplete) & seg_mask;
       const unsigned long long over = __ballot(lane_ok && pk > cap) & seg_mask;
-      int ms = lane_ok ? (int)(free_at8 >> 8) : 0;
+      int ms = lane_ok ? (int)((COPY ? max(free_at8, copy_free8) : free_at8) >> 8) : 0;
       for (int off = 1; off < lpc; off <<= 1) ms = max(ms, __shfl_xor(ms, off, 64));
       if (seg_ended) {
         unsigned flg = 0;
@@ -634,7 +713,8 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotPerMicrobatchLds) \
   FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotLinks)            \
   FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotTimesLinks)       \
-  FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotPerMicrobatchLdsLinks)
+  FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotPerMicrobatchLdsLinks) \
+  FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotCopy)
 FPSCHED_INSTANTIATE(1, false, true)
 FPSCHED_INSTANTIATE(2, false, true)
 FPSCHED_INSTANTIATE(4, false, true)

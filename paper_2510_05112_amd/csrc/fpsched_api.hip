@@ -71,6 +71,9 @@ struct fpsched_problem {
   // synchronisation stages and dependency pairs (fpsched_problem_set_sync)
   bool sync_on = false;
   int32_t copy_depth = 0;               // copy-engine form (fpsched_problem_set_copy_engine), 0 = off
+  bool copy_slots_ok = false;           // ... which the slot kernel can run (its rings fit LDS)
+  SlotTables stab_copy{};
+  int32_t copy_waves = 0, copy_grid = 0, copy_lds_bytes = 0;
   std::vector<int32_t> sync_items;      // [S] items per kind of each stage (m while the model is off)
   SyncTables sync_tab{};
   int32_t* d_sync_ints = nullptr;
@@ -656,7 +659,8 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
   if (reinterpret_cast<uintptr_t>(d_ops) & 15) return FPSCHED_EINVAL;
   DeviceGuard g(p->device_id);
   if (!g.ok) return FPSCHED_EHIP;
-  if (p->sync_on || p->copy_depth > 0) {
+  const bool copy_on_slots = p->copy_depth > 0 && p->use_slots && p->copy_slots_ok;
+  if ((p->sync_on || p->copy_depth > 0) && !copy_on_slots) {
     const int cpw = p->sync_tab.cands_per_wave;
     const int64_t blocks = (n_cand + cpw - 1) / cpw;
     if (blocks > 0x7fffffffll) return FPSCHED_EINVAL;
@@ -667,7 +671,7 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
     return check_hip(hipGetLastError());
   }
   if (p->links_on && !p->use_slots) return FPSCHED_EUNSUPPORTED;   // the general kernel has no link form
-  if (p->use_slots && (!p->mb_set || p->mb_slots_ok)) {
+  if (copy_on_slots || (p->use_slots && (!p->mb_set || p->mb_slots_ok))) {
     // the first 8 bytes of the workspace hold the counter the segments draw candidates from
     if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) & 15)) return FPSCHED_EINVAL;
     if (workspace_bytes < 256) return FPSCHED_ENOMEM;
@@ -677,10 +681,11 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
     const bool combo = p->links_on && p->mb_set;   // both variants: the setters made sure the tables exist
     if (combo && !p->combo_ok) return FPSCHED_EUNSUPPORTED;
     const bool links = p->links_on && !combo;
-    const SlotTables& tab = combo ? p->stab_combo : links ? p->stab_links : (mb_lds ? p->stab_mb : p->stab);
-    const int waves = combo ? p->combo_waves : links ? p->links_waves : (mb_lds ? p->mb_waves : p->slot_waves);
-    const int grid = combo ? p->combo_grid : links ? p->links_grid : (mb_lds ? p->mb_grid : p->slot_grid);
-    const size_t lds_bytes = (size_t)(combo ? p->combo_lds_bytes : links ? p->links_lds_bytes : (mb_lds ? p->mb_lds_bytes : p->slot_lds_bytes));
+    const SlotTables& tab = copy_on_slots ? p->stab_copy : combo ? p->stab_combo : links ? p->stab_links : (mb_lds ? p->stab_mb : p->stab);
+    const int waves = copy_on_slots ? p->copy_waves : combo ? p->combo_waves : links ? p->links_waves : (mb_lds ? p->mb_waves : p->slot_waves);
+    const int grid = copy_on_slots ? p->copy_grid : combo ? p->combo_grid : links ? p->links_grid : (mb_lds ? p->mb_grid : p->slot_grid);
+    const size_t lds_bytes = (size_t)(copy_on_slots ? p->copy_lds_bytes : combo ? p->combo_lds_bytes : links ? p->links_lds_bytes
+                                      : (mb_lds ? p->mb_lds_bytes : p->slot_lds_bytes));
     const int per_block = tab.cands_per_wave * waves;
     const int64_t blocks = std::min<int64_t>((n_cand + per_block - 1) / per_block, grid);
     // Candidates per atomic draw.  Atomics on one address complete at some 8e7 per second; a batch of
@@ -692,7 +697,8 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
     hipLaunchKernelGGL(reset_counter_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(hip_stream), counter,
                        (unsigned long long)(blocks * per_block));
     const bool one_class = p->stab.n_classes == 1;
-    const SlotKernel kernel = combo ? slot_kernel_of<kSlotPerMicrobatchLdsLinks>(p->slot_v, p->slot_deg2, one_class)
+    const SlotKernel kernel = copy_on_slots ? slot_kernel_of<kSlotCopy>(p->slot_v, p->slot_deg2, one_class)
+                              : combo ? slot_kernel_of<kSlotPerMicrobatchLdsLinks>(p->slot_v, p->slot_deg2, one_class)
                               : links ? slot_kernel_of<kSlotLinks>(p->slot_v, p->slot_deg2, one_class)
                               : !p->mb_set ? slot_kernel_ptr(p->slot_v, p->slot_deg2, one_class)
                               : (mb_lds ? slot_kernel_of<kSlotPerMicrobatchLds>(p->slot_v, p->slot_deg2, one_class)
@@ -1207,6 +1213,27 @@ int fpsched_problem_set_copy_engine(fpsched_problem* p, int32_t depth) {
     const std::vector<int32_t> grp(p->S, 1), items(p->S, p->m);
     const int rc = install_table_model(p, grp, items, 0, nullptr, false, depth);
     if (rc != FPSCHED_OK) return rc;
+    // the slot kernel has a form of this model too: the plain tables, 32 more dwords of LDS per lane for
+    // the rings of the copy timeline
+    p->copy_slots_ok = false;
+    if (p->slots_ok) {
+      const SlotTables& PT = p->stab;
+      const SlotGeometry geo = slot_geometry(PT.n_shared_ints, PT.lanes_per_cand, PT.state_words + kSlotCopyWords,
+                                             PT.slots_per_cand, p->max_lds, PT.cands_per_wave);
+      DeviceGuard g(p->device_id);
+      if (g.ok && geo.waves >= 1 && geo.cands_per_wave == PT.cands_per_wave &&
+          hipFuncSetAttribute(reinterpret_cast<const void*>(slot_kernel_of<kSlotCopy>(p->slot_v, p->slot_deg2, PT.n_classes == 1)),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, p->max_lds) == hipSuccess) {
+        p->stab_copy = PT;
+        p->stab_copy.link_words = kSlotCopyWords;
+        p->stab_copy.copy_depth = depth;
+        p->stab_copy.wave_ints = geo.wave_ints;
+        p->copy_waves = geo.waves;
+        p->copy_grid = p->n_cu * geo.groups;
+        p->copy_lds_bytes = (int32_t)(4ll * (PT.n_shared_ints + (int64_t)geo.waves * geo.wave_ints));
+        p->copy_slots_ok = true;
+      }
+    }
   }
   p->copy_depth = depth;
   return FPSCHED_OK;

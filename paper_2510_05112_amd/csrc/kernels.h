@@ -47,8 +47,12 @@ constexpr int kSlotMaxThreads = 64 * kSlotMaxWaves;
 // producer holds its value back until its link is free (T.link_words, the longer dev rows).
 // MODE kSlotTimesLinks: the timing pass of the sliding under the link model (both of the above).
 // MODE kSlotPerMicrobatchLdsLinks: costs per micro-batch from LDS and link occupancy together.
+// MODE kSlotCopy: offload and reload items run on a copy engine beside the computation (T.copy_depth transfers
+// at most in the engine; T.link_words = 32 dwords per lane behind its state words: the finish times and keys of
+// the last eight transfers, and a ring of eight pending memory events).
 constexpr int kSlotPlain = 0, kSlotTimes = 1, kSlotPerMicrobatch = 2, kSlotPerMicrobatchLds = 3, kSlotLinks = 4,
-              kSlotTimesLinks = 5, kSlotPerMicrobatchLdsLinks = 6;
+              kSlotTimesLinks = 5, kSlotPerMicrobatchLdsLinks = 6, kSlotCopy = 7;
+constexpr int kSlotCopyWords = 32;
 template <int V, bool DEG2, bool ONE_CLASS, int MODE>
 __global__ void eval_slot_kernel(SlotTables T, const uint16_t* ops, long long n_cand, int stride,
                                  long long* out_makespan, long long* out_idle, int* out_peak,

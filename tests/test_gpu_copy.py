@@ -14,9 +14,13 @@ from workloads.problem import B, F, FD, L, O, R, W, chain_problem, make_problem,
 pytestmark = pytest.mark.gpu
 
 
-def gpu_copy(problem, words, depth, k=None):
+def gpu_copy(problem, words, depth, k=None, kernel="auto"):
+    """kernel: "auto" = the slot kernel's copy-engine form where the problem fits it, "general" = the table
+    kernel (eval_sync_kernel<true>)."""
     words = np.ascontiguousarray(words, dtype=np.uint16)
     h = fp.Problem(problem, words.shape[2], device=0)
+    if kernel != "auto":
+        h.select_kernel(kernel)
     h.set_copy_engine(depth)
     res = h.evaluate(torch.from_numpy(words.view(np.int16)).cuda())
     top = h.topk(res, k) if k else None
@@ -32,16 +36,18 @@ def test_hand_worked_timelines_on_the_gpu():
     prob = make_problem(1, 1, 3, 0, [0], [], {F: 3, B: 4, O: 5, L: 2})
     ops = [(F, 0, 0), (O, 0, 0), (F, 0, 1), (O, 0, 1), (F, 0, 2), (L, 0, 0), (L, 0, 1), (B, 0, 0), (B, 0, 1), (B, 0, 2)]
     words = pack_lists([ops], 16)[None]
-    for depth in (1, 4, 7):
-        out, _ = gpu_copy(prob, words, depth)
-        assert out["flags"][0] == 0 and out["makespan"][0] == 27 and out["idle"][0, 0] == 6 and out["peak"][0, 0] == 3
-        assert_same(out, oracle.evaluate_copy(prob, words, depth=depth), f"depth {depth}")
+    for kernel in ("auto", "general"):
+        for depth in (1, 4, 7):
+            out, _ = gpu_copy(prob, words, depth, kernel=kernel)
+            assert out["flags"][0] == 0 and out["makespan"][0] == 27 and out["idle"][0, 0] == 6 and out["peak"][0, 0] == 3
+            assert_same(out, oracle.evaluate_copy(prob, words, depth=depth), f"depth {depth} {kernel}")
     # an allocation of the compute timeline counts before a release of the copy engine at the same time
-    for o_cost, expect in ((5, 3), (4, 2)):
-        prob = make_problem(1, 2, 2, 0, [0, 0], [], {F: [3, 5], B: [1, 1], O: o_cost, L: 1})
-        ops = [(F, 0, 0), (O, 0, 0), (F, 1, 0), (F, 1, 1), (B, 1, 0), (B, 1, 1), (L, 0, 0), (B, 0, 0), (F, 0, 1), (B, 0, 1)]
-        out, _ = gpu_copy(prob, pack_lists([ops], 16)[None], 4)
-        assert out["flags"][0] == 0 and out["peak"][0, 0] == expect
+    for kernel in ("auto", "general"):
+        for o_cost, expect in ((5, 3), (4, 2)):
+            prob2 = make_problem(1, 2, 2, 0, [0, 0], [], {F: [3, 5], B: [1, 1], O: o_cost, L: 1})
+            ops = [(F, 0, 0), (O, 0, 0), (F, 1, 0), (F, 1, 1), (B, 1, 0), (B, 1, 1), (L, 0, 0), (B, 0, 0), (F, 0, 1), (B, 0, 1)]
+            out, _ = gpu_copy(prob2, pack_lists([ops], 16)[None], 4, kernel=kernel)
+            assert out["flags"][0] == 0 and out["peak"][0, 0] == expect
 
 
 def transfer_problems():
@@ -53,8 +59,9 @@ def transfer_problems():
             dag_problem([(0, 1), (0, 2), (1, 3), (2, 3)], 4, [0, 1, 2, 0], 3, m=4, has_w=0, seed=3)]
 
 
+@pytest.mark.parametrize("kernel", ["auto", "general"])
 @pytest.mark.parametrize("depth", [1, 2, 4, 7])
-def test_random_lists_with_transfers_against_the_oracle(depth):
+def test_random_lists_with_transfers_against_the_oracle(depth, kernel):
     rng = np.random.default_rng(100 + depth)
     for prob in transfer_problems():
         lists = []
@@ -63,7 +70,7 @@ def test_random_lists_with_transfers_against_the_oracle(depth):
             lists += [base, perturb(base, rng, 1 + t % 3)]
         words = batch_from_lists(lists)
         ref = oracle.evaluate_copy(prob, words, depth=depth, threads=4)
-        out, top = gpu_copy(prob, words, depth, k=9)
+        out, top = gpu_copy(prob, words, depth, k=9, kernel=kernel)
         assert_same(out, ref, f"{prob.name} depth {depth}")
         idx, ms, cnt = oracle.topk(ref["makespan"], ref["flags"], 9)
         assert top[2] == cnt and np.array_equal(top[0], idx) and np.array_equal(top[1], ms)
