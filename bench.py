@@ -480,6 +480,8 @@ def main() -> int:
     ap.add_argument("--copy-engine", type=int, default=0, metavar="DEPTH",
                     help="evaluate mode: offload and reload items run on a copy engine that holds at most DEPTH "
                          "transfers (1..7) instead of the compute timeline; meant for --config 5")
+    ap.add_argument("--table-kernel", action="store_true",
+                    help="evaluate mode: the table form of the evaluation kernel instead of the slot kernel")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain elementwise copy of the op batch (a kernel of known HBM "
                          "traffic, used to calibrate rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
@@ -525,6 +527,8 @@ def main() -> int:
     if args.mb_costs:
         dur_mb = workloads.microbatch_costs(prob)
         handle.set_microbatch_costs(dur_mb)
+    if args.table_kernel:
+        handle.select_kernel("general")
     if args.copy_engine:
         handle.set_copy_engine(args.copy_engine)
     t0 = time.perf_counter()
@@ -575,10 +579,11 @@ def main() -> int:
     # algorithmic bytes of one evaluation launch: 2 B per op word actually needed, plus the
     # per-candidate outputs (makespan 8 + idle 8D + peak 4D + flags 1)
     alg_bytes = 2 * n_ops + C * (8 + 8 * D + 4 * D + 1)
-    counted = ({} if args.copy_engine else MEASURED_BOTH if args.links and args.mb_costs else MEASURED_LINKS if args.links
+    counted = ({} if args.copy_engine or args.table_kernel else MEASURED_BOTH if args.links and args.mb_costs else MEASURED_LINKS if args.links
                else MEASURED_MB if args.mb_costs else MEASURED)
-    roofline, issue = rooflines(alg_bytes, eval_ms, "fpsched evaluation kernel (eval_sync_kernel, copy-engine form)"
-                                if args.copy_engine else "fpsched evaluation kernel (eval_slot_kernel)",
+    roofline, issue = rooflines(alg_bytes, eval_ms,
+                                "fpsched evaluation kernel, table form" + (" (eval_sync_kernel, copy-engine form)" if args.copy_engine else " (eval_general_kernel)")
+                                if args.table_kernel else "fpsched evaluation kernel (eval_slot_kernel" + (", copy-engine mode)" if args.copy_engine else ")"),
                                 counted.get((f"cfg{spec.index}", C)), units=n_ops)
     flags = res["flags"].cpu().numpy()
     makespan = res["makespan"].cpu().numpy()
