@@ -556,10 +556,16 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       unsigned start8 = max(free_at8, ready8);
       if (COPY && cur_kind == (unsigned)kB && ((sx >> (bj & 31u)) & 8u) != 0u) {
         // the activation was reloaded: if that transfer is among the last copy_depth ones it may still run
-        for (unsigned i = 1; i <= copy_depth; ++i) {
-          const unsigned at = ((n_copy - i) & 7u) << 8;
-          if (lds_read<uint32_t>(ring_key + at) == cur_key) start8 = max(start8, lds_read<uint32_t>(ring_fin + at));
+        // (all eight places of the ring are looked at, in one round trip: a transfer further back than
+        // copy_depth has finished before the device got here, so a match there changes nothing)
+        unsigned keys[8], fins[8];
+#pragma unroll
+        for (unsigned i = 0; i < 8u; ++i) {
+          keys[i] = lds_read<uint32_t>(ring_key + (i << 8));
+          fins[i] = lds_read<uint32_t>(ring_fin + (i << 8));
         }
+#pragma unroll
+        for (unsigned i = 0; i < 8u; ++i) start8 = max(start8, keys[i] == cur_key ? fins[i] : 0u);
       }
       const unsigned fin8 = start8 + dur8;
       if (TIMES) {
