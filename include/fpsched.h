@@ -468,10 +468,11 @@ int fpsched_generate_evaluate(const fpsched_problem *p, const fpsched_actor_poli
 
 /* fpsched_generate for chosen parameter sets: row block i of d_ops (and d_steps[i], d_status[i])
  * is the schedule of parameter set d_select[i] (DEVICE int64 [n_selected], e.g. the indices
- * fpsched_topk wrote; each must be below the number of sets d_policy and d_inflight hold).  A
- * negative entry (an unused top-k slot) selects nothing: empty rows, FPSCHED_GEN_BAD_POLICY. */
+ * fpsched_topk wrote) of the n_sets sets that d_policy and d_inflight hold.  An entry outside
+ * 0 .. n_sets - 1 (the -1 of an unused top-k slot) selects nothing: empty rows,
+ * FPSCHED_GEN_BAD_POLICY; no set is ever read that the caller did not say is there. */
 int fpsched_generate_selected(const fpsched_problem *p, const fpsched_actor_policy *d_policy,
-                              const int32_t *d_inflight, const int64_t *d_select,
+                              const int32_t *d_inflight, int64_t n_sets, const int64_t *d_select,
                               int64_t n_selected, int32_t stride_words, uint16_t *d_ops,
                               int32_t *d_steps, uint8_t *d_status, void *d_workspace,
                               size_t workspace_bytes, void *hip_stream);

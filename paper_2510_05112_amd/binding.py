@@ -98,7 +98,7 @@ def load_library():
         lib.fpsched_generate.restype = ctypes.c_int
         lib.fpsched_generate.argtypes = [vp, vp, vp, i64, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.fpsched_generate_selected.restype = ctypes.c_int
-        lib.fpsched_generate_selected.argtypes = [vp, vp, vp, vp, i64, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.fpsched_generate_selected.argtypes = [vp, vp, vp, i64, vp, i64, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.fpsched_generate_evaluate.restype = ctypes.c_int
         lib.fpsched_generate_evaluate.argtypes = [vp, vp, vp, i64, _Results, vp, vp, vp, ctypes.c_size_t, vp]
         lib.fpsched_encode.restype = ctypes.c_int
@@ -367,7 +367,7 @@ class Problem:
         if workspace is None:
             workspace = self.alloc_workspace(k, 0)
         rc = load_library().fpsched_generate_selected(
-            self._h, policy.data_ptr(), inflight.data_ptr(), select.data_ptr(), k, int(stride),
+            self._h, policy.data_ptr(), inflight.data_ptr(), n, select.data_ptr(), k, int(stride),
             out["ops"].data_ptr(), out["steps"].data_ptr(), out["status"].data_ptr(), workspace.data_ptr(),
             workspace.numel(), self._stream(stream))
         if rc != 0:

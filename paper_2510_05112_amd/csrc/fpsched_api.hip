@@ -1239,7 +1239,7 @@ int fpsched_problem_set_copy_engine(fpsched_problem* p, int32_t depth) {
   return FPSCHED_OK;
 }
 
-using GenKernel = void (*)(DevTables, const int32_t*, const int32_t*, const long long*, long long, int, uint16_t*,
+using GenKernel = void (*)(DevTables, const int32_t*, const int32_t*, const long long*, long long, long long, int, uint16_t*,
                            int32_t*, unsigned char*, unsigned long long*, GenResults);
 static int gen_waves_per_cu() {
   // tuning knob: FPSCHED_GEN_WAVES = resident wavefronts per compute unit
@@ -1257,7 +1257,7 @@ static int gen_max_chunks(const fpsched_problem* p) {
 }
 
 static int run_generate(const fpsched_problem* p, const fpsched_actor_policy* d_policy, const int32_t* d_inflight,
-                 const int64_t* d_select, int64_t n_sets, int32_t stride_words, uint16_t* d_ops, int32_t* d_steps,
+                 const int64_t* d_select, int64_t n_src, int64_t n_sets, int32_t stride_words, uint16_t* d_ops, int32_t* d_steps,
                  uint8_t* d_status, void* d_workspace, size_t workspace_bytes, void* hip_stream) {
   if (!p || n_sets < 0) return FPSCHED_EINVAL;
   if (p->device_id < 0) return FPSCHED_ENODEV;
@@ -1298,7 +1298,7 @@ static int run_generate(const fpsched_problem* p, const fpsched_actor_policy* d_
                      (unsigned long long)(blocks * cpw));
   hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(64), (size_t)lds_bytes,
                      static_cast<hipStream_t>(hip_stream), p->tables, reinterpret_cast<const int32_t*>(d_policy),
-                     d_inflight, reinterpret_cast<const long long*>(d_select), (long long)n_sets, (int)stride_words,
+                     d_inflight, reinterpret_cast<const long long*>(d_select), (long long)n_src, (long long)n_sets, (int)stride_words,
                      d_ops, d_steps, d_status, counter, GenResults{nullptr, nullptr, nullptr, nullptr});
   return check_hip(hipGetLastError());
 }
@@ -1306,16 +1306,16 @@ static int run_generate(const fpsched_problem* p, const fpsched_actor_policy* d_
 int fpsched_generate(const fpsched_problem* p, const fpsched_actor_policy* d_policy, const int32_t* d_inflight,
                      int64_t n_sets, int32_t stride_words, uint16_t* d_ops, int32_t* d_steps, uint8_t* d_status,
                      void* d_workspace, size_t workspace_bytes, void* hip_stream) {
-  return run_generate(p, d_policy, d_inflight, nullptr, n_sets, stride_words, d_ops, d_steps, d_status, d_workspace,
+  return run_generate(p, d_policy, d_inflight, nullptr, n_sets, n_sets, stride_words, d_ops, d_steps, d_status, d_workspace,
                       workspace_bytes, hip_stream);
 }
 
 int fpsched_generate_selected(const fpsched_problem* p, const fpsched_actor_policy* d_policy,
-                              const int32_t* d_inflight, const int64_t* d_select, int64_t n_selected,
+                              const int32_t* d_inflight, int64_t n_sets, const int64_t* d_select, int64_t n_selected,
                               int32_t stride_words, uint16_t* d_ops, int32_t* d_steps, uint8_t* d_status,
                               void* d_workspace, size_t workspace_bytes, void* hip_stream) {
-  if (n_selected > 0 && !d_select) return FPSCHED_EINVAL;
-  return run_generate(p, d_policy, d_inflight, d_select, n_selected, stride_words, d_ops, d_steps, d_status,
+  if (n_sets < 0 || (n_selected > 0 && !d_select)) return FPSCHED_EINVAL;
+  return run_generate(p, d_policy, d_inflight, d_select, n_sets, n_selected, stride_words, d_ops, d_steps, d_status,
                       d_workspace, workspace_bytes, hip_stream);
 }
 
@@ -1370,7 +1370,7 @@ int fpsched_generate_evaluate(const fpsched_problem* p, const fpsched_actor_poli
                      (unsigned long long)(blocks * best_waves * cpw));
   hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(64 * best_waves), (size_t)lds_bytes,
                      static_cast<hipStream_t>(hip_stream), p->tables, reinterpret_cast<const int32_t*>(d_policy),
-                     d_inflight, nullptr, (long long)n_sets, 0, nullptr, d_steps, d_status, counter,
+                     d_inflight, nullptr, (long long)n_sets, (long long)n_sets, 0, nullptr, d_steps, d_status, counter,
                      GenResults{reinterpret_cast<long long*>(out.makespan), reinterpret_cast<long long*>(out.idle),
                                 out.peak, out.flags});
   return check_hip(hipGetLastError());

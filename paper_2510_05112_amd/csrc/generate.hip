@@ -72,7 +72,7 @@ __device__ __forceinline__ unsigned mad24(unsigned a, unsigned b_uniform, unsign
 template <int V, int DEG, bool TIMED>
 __global__ __launch_bounds__(TIMED ? kGenTimedThreads : 64) void generate_kernel(
     DevTables T, const int32_t* __restrict__ policy, const int32_t* __restrict__ inflight,
-    const long long* __restrict__ select, long long n_sets, int stride, uint16_t* __restrict__ ops,
+    const long long* __restrict__ select, long long n_src, long long n_sets, int stride, uint16_t* __restrict__ ops,
     int32_t* __restrict__ out_steps, unsigned char* __restrict__ out_status,
     unsigned long long* __restrict__ next_set, GenResults R) {
   extern __shared__ int32_t lds[];
@@ -238,10 +238,10 @@ __global__ __launch_bounds__(TIMED ? kGenTimedThreads : 64) void generate_kernel
         if (has_set)
           for (int i = d; i < 3 * S; i += lpc) counts[base + i] = 0;
         cttp = 0; unit_f = 1; unit_b = 1; f_dir = 0; f_int = 0; b_dir = 0; b_int = 0;
-        // (with a selection, output row `set` is the schedule of parameter set select[set]; a negative
-        // entry selects nothing and counts as a bad set)
+        // (with a selection, output row `set` is the schedule of parameter set select[set]; an entry that
+        // is negative or not below n_src selects nothing and counts as a bad set)
         const long long src = (has_set && select) ? select[set] : set;
-        const bool has_src = has_row && src >= 0;
+        const bool has_src = has_row && src >= 0 && src < n_src;
         if (has_src) {
           const int32_t* pol = policy + (src * D + d) * 8;
           cttp = pol[0]; unit_f = pol[1]; unit_b = pol[2];
@@ -254,7 +254,7 @@ __global__ __launch_bounds__(TIMED ? kGenTimedThreads : 64) void generate_kernel
           limit2.y = (short)min(limit[1], 0x7fff);
         }
         // a parameter set with a value outside its domain generates nothing (status 4)
-        bool bad = (has_row && src < 0) || cttp < 0 || cttp > 2 || unit_f < 1 || unit_b < 1 || f_dir < 0 || f_dir > 1 || f_int < 0 ||
+        bool bad = (has_row && !has_src) || cttp < 0 || cttp > 2 || unit_f < 1 || unit_b < 1 || f_dir < 0 || f_dir > 1 || f_int < 0 ||
                    b_dir < 0 || b_dir > 1 || b_int < 0 || (cttp != 2 && (unit_f != 1 || unit_b != 1));
 #pragma unroll
         for (int c = 0; c < V; ++c) bad = bad || limit[c] < 1;
@@ -441,7 +441,7 @@ __global__ __launch_bounds__(TIMED ? kGenTimedThreads : 64) void generate_kernel
 
 #define FPSCHED_INSTANTIATE(V, G, TIMED)                                                                    \
   template __global__ void generate_kernel<V, G, TIMED>(DevTables, const int32_t*, const int32_t*,           \
-                                                        const long long*, long long, int, uint16_t*, int32_t*, \
+                                                        const long long*, long long, long long, int, uint16_t*, int32_t*, \
                                                         unsigned char*, unsigned long long*, GenResults);
 FPSCHED_INSTANTIATE(1, 1, false)
 FPSCHED_INSTANTIATE(2, 1, false)

@@ -65,7 +65,7 @@ __global__ void reset_counter_kernel(unsigned long long* counter, unsigned long 
 // V as above; DEG = bound on the in- and out-degree of a stage (1, 2, or 0 = any).  One wavefront per
 // workgroup, 64 / lanes_per_cand parameter sets per wavefront at a time; next_set: a counter in
 // device memory, preset to the number of segments in the grid, from which segments draw their sets.
-// select: null, or which parameter set each output row takes (negative: none).
+// select: null, or which of the n_src parameter sets each output row takes (outside 0 .. n_src - 1: none).
 // TIMED (DEG 1 or 2 only): the schedules are timed as they are generated and only the results R are
 // written (ops and select unused); workgroups of up to kGenTimedThreads threads.
 struct GenResults {
@@ -77,7 +77,7 @@ struct GenResults {
 constexpr int kGenTimedThreads = 512;
 template <int V, int DEG, bool TIMED>
 __global__ void generate_kernel(DevTables T, const int32_t* policy, const int32_t* inflight, const long long* select,
-                                long long n_sets, int stride, uint16_t* ops, int32_t* out_steps,
+                                long long n_src, long long n_sets, int stride, uint16_t* ops, int32_t* out_steps,
                                 unsigned char* out_status, unsigned long long* next_set, GenResults R);
 
 __global__ void topk_tile_kernel(const long long* in_makespan, const unsigned char* in_flags,

@@ -149,10 +149,11 @@ def test_search_step_and_the_winners_rows():
     assert np.array_equal(rows["ops"].cpu().numpy().view(np.uint16), ref_gen["words"][idx])
     assert np.array_equal(rows["steps"].cpu().numpy(), ref_gen["steps"][idx])
     # unused top-k slots (-1) select nothing
-    sel = torch.tensor([5, -1, 0, 299], dtype=torch.int64, device="cuda")
+    # ... and so do indices beyond the sets that are there
+    sel = torch.tensor([5, -1, 0, 299, 300, 2 ** 40], dtype=torch.int64, device="cuda")
     rows = h.generate_selected(d_pol, d_inf, sel, st)
     torch.cuda.synchronize()
     words = rows["ops"].cpu().numpy().view(np.uint16)
-    assert np.array_equal(words[[0, 2, 3]], ref_gen["words"][[5, 0, 299]]) and not words[1].any()
-    assert list(rows["status"].cpu().numpy()) == [0, 4, 0, 0]
+    assert np.array_equal(words[[0, 2, 3]], ref_gen["words"][[5, 0, 299]]) and not words[[1, 4, 5]].any()
+    assert list(rows["status"].cpu().numpy()) == [0, 4, 0, 0, 4, 4]
     h.close()
