@@ -176,7 +176,7 @@ __global__ __launch_bounds__(kSlideThreads) void wslide_place_kernel(
     const bool have = pos < stop;
     const bool in_window = pos < loaded;
     // (any 16-bit value indexes a row of the table: the top five bits of the word)
-    const int4 M = meta[(w >> 11) * lpc + d];
+    const int4 M = meta[((w >> 11) << lpc_shift) + d];
     // the start time from its low half and the free time in front of the op, plus what the escape
     // list says for an op that waited 2^16 time units or more
     const bool esc_here = (esc >> 8) == (unsigned)pos;
