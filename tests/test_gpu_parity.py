@@ -344,6 +344,78 @@ def test_generate_slide_and_topk_replayed_from_a_hip_graph(links):
     h.close()
 
 
+def test_fused_search_step_replayed_from_a_hip_graph():
+    # generate-and-time, top-k and the winners' rows, captured once and replayed on new parameter sets;
+    # every replay is checked against the two oracles composed on the CPU
+    import torch
+
+    import paper_2510_05112_amd as fp
+    spec = workloads.config(2, 8)
+    prob, k, n = spec.problem, 5, 160
+    st = workloads.generator_stride(prob)
+    sets = [workloads.policy_sets(prob, n, seed=91 + i) for i in range(3)]
+    h = fp.Problem(prob, st, device=0)
+    d_pol, d_inf = torch.from_numpy(sets[0][0]).cuda(), torch.from_numpy(sets[0][1]).cuda()
+    ws = h.alloc_workspace(n, k)
+    res, out = h.generate_evaluate(d_pol, d_inf, workspace=ws)     # eager once: allocates the outputs
+    top = h.topk(res, k, ws)
+    rows = h.generate_selected(d_pol, d_inf, top["idx"], st, workspace=ws)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        h.generate_evaluate(d_pol, d_inf, results=res, out=out, workspace=ws)
+        h.topk(res, k, ws, top)
+        h.generate_selected(d_pol, d_inf, top["idx"], st, out=rows, workspace=ws)
+    for pol, inf in sets[::-1] + sets:
+        d_pol.copy_(torch.from_numpy(pol))
+        d_inf.copy_(torch.from_numpy(inf))
+        res["flags"].fill_(255)       # eager work between the replays
+        rows["ops"].zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        ref_gen = oracle.generate(prob, pol, inf, st, threads=2)
+        ref = oracle.evaluate(prob, ref_gen["words"], threads=2)
+        for name in ("makespan", "idle", "peak", "flags"):
+            assert np.array_equal(res[name].cpu().numpy(), ref[name]), name
+        assert np.array_equal(out["steps"].cpu().numpy(), ref_gen["steps"])
+        idx, ms, cnt = oracle.topk(ref["makespan"], ref["flags"], k)
+        assert int(top["count"].item()) == cnt == k and np.array_equal(top["idx"].cpu().numpy(), idx)
+        assert np.array_equal(rows["ops"].cpu().numpy().view(np.uint16), ref_gen["words"][idx])
+    h.close()
+
+
+def test_copy_engine_evaluation_replayed_from_a_hip_graph():
+    import torch
+
+    import paper_2510_05112_amd as fp
+    spec = workloads.config(5, 300)
+    prob, k = spec.problem, 9
+    batches = [workloads.generate(spec, n=300, first=300 * i, threads=2) for i in range(3)]
+    h = fp.Problem(prob, spec.stride, device=0)
+    h.set_copy_engine(3)
+    ops = torch.from_numpy(batches[0].view(np.int16)).cuda()
+    res, ws = h.alloc_results(300), h.alloc_workspace(300, k)
+    top = h.topk(h.evaluate(ops, res, ws), k, ws)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        h.evaluate(ops, res, ws)
+        h.topk(res, k, ws, top)
+    for words in batches[::-1] + batches:
+        ops.copy_(torch.from_numpy(words.view(np.int16)))
+        res["flags"].fill_(255)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        ref = oracle.evaluate_copy(prob, words, depth=3, threads=2)
+        for name in ("makespan", "idle", "peak", "flags"):
+            assert np.array_equal(res[name].cpu().numpy(), ref[name]), name
+        idx, ms, cnt = oracle.topk(ref["makespan"], ref["flags"], k)
+        assert int(top["count"].item()) == cnt and np.array_equal(top["idx"].cpu().numpy(), idx)
+    h.close()
+
+
 def test_two_live_handles_with_different_lds_needs():
     # The dynamic-LDS limit of a kernel is one value per process: a handle created later with a smaller
     # need must not take the room of an earlier one (both problems run the same kernel instantiation).
