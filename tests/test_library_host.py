@@ -42,6 +42,11 @@ def test_host_only_handle_and_errors():
     rc = lib.fpsched_evaluate(p._h, 0, 1, spec.stride, fp.binding._Results(0, 0, 0, 0), 0, 0, 0)
     assert rc == -5
     assert lib.fpsched_generate(p._h, 0, 0, 1, 1024, 0, 0, 0, 0, 0, 0) == -5
+    assert lib.fpsched_generate_selected(p._h, 0, 0, 4, 1, 1, 1024, 0, 0, 0, 0, 0, 0) == -5
+    assert lib.fpsched_generate_evaluate(p._h, 0, 0, 1, fp.binding._Results(0, 0, 0, 0), 0, 0, 0, 0, 0) == -5
+    assert lib.fpsched_generate_selected(p._h, 0, 0, -1, 1, 1, 1024, 0, 0, 0, 0, 0, 0) == -1   # a negative number of sets
+    assert lib.fpsched_generate_selected(p._h, 0, 0, 4, 0, 1, 1024, 0, 0, 0, 0, 0, 0) == -1    # no selection given
+    assert lib.fpsched_generate_evaluate(None, 0, 0, 1, fp.binding._Results(0, 0, 0, 0), 0, 0, 0, 0, 0) == -1
     none = fp.binding._Results(0, 0, 0, 0)
     assert lib.fpsched_topk(p._h, none, 1, 1, 1, 1, 1, 0, 0, 0) == -5
     assert lib.fpsched_rank(p._h, none, 1, 1, 0, 0, 1, 1, 1, 0, 0, 0) == -5
