@@ -114,3 +114,35 @@ def test_random_problems_sliding(seed):
                 assert np.array_equal(out[name].cpu().numpy(), ref[name]), (what, name)
         h.close()
         done += 1
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_problems_fused_generator(seed):
+    # generator and evaluator in one kernel against the two oracles composed on the CPU
+    from test_gpu_generate_evaluate import check as check_fused
+    rng = np.random.default_rng(3000 + seed)
+    for i in range(10):
+        prob = random_problem(rng)
+        n = 40
+        pol, inf = random_policies(rng, n, prob, rng.random(n) < 0.5)
+        check_fused(prob, pol, inf, f"seed {seed} problem {i}")
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_problems_copy_engine(seed):
+    # the copy-engine model on both evaluation kernels against its oracle
+    from test_gpu_copy import gpu_copy
+    from gpu_common import assert_same
+    rng = np.random.default_rng(4000 + seed)
+    for i in range(8):
+        prob = random_problem(rng)
+        depth = int(rng.integers(1, 8))
+        lists = []
+        for t in range(16):
+            base = random_valid_lists(prob, rng, 0.3 * (t % 2), 0.2 + 0.3 * ((t // 2) % 2))
+            lists += [base, perturb(base, rng, 1 + t % 3)]
+        words = batch_from_lists(lists)
+        ref = oracle.evaluate_copy(prob, words, depth=depth, threads=4)
+        for kernel in ("auto", "general"):
+            out, _ = gpu_copy(prob, words, depth, kernel=kernel)
+            assert_same(out, ref, f"seed {seed} problem {i} depth {depth} {kernel}")
