@@ -48,9 +48,10 @@ MEASURED_BOTH = {("cfg4", 65536): {"traffic_bytes": 3.765e9, "valu_wave_instruct
                                    "valu_per_wave_round": None, "profile_kernel_ms": 8.554,
                                    "profile": "profiles/eval_slot_kernel_cfg4_links_and_microbatch_costs.md"}}
 # the evaluation with synchronisation stages (--mode sync)
-MEASURED_SYNC = {("sync4", 65536): {"traffic_bytes": None, "valu_wave_instructions": 1.068e9,
-                                   "valu_per_wave_round": None, "profile_kernel_ms": 7.12,
-                                   "profile": "profiles/eval_sync_kernel.md"}}
+MEASURED_SYNC = {}
+MEASURED_SYNC_TABLE = {("sync4", 65536): {"traffic_bytes": None, "valu_wave_instructions": 1.068e9,
+                                         "valu_per_wave_round": None, "profile_kernel_ms": 7.12,
+                                         "profile": "profiles/eval_sync_kernel.md"}}
 # one generator launch (--mode generate): WRITE_SIZE x 1024 plus the parameter sets read
 MEASURED_GENERATE = {("cfg4", 65536): {"traffic_bytes": 4.82e9, "valu_wave_instructions": 9.509e9,
                                        "valu_per_wave_round": None, "profile_kernel_ms": 17.49,
@@ -382,6 +383,8 @@ def bench_sync(args, threads) -> int:
     C, D, stride = words.shape
     n_ops = workloads.count_ops(words)
     handle = fp.Problem(prob, stride, device=0)
+    if args.table_kernel:
+        handle.select_kernel("general")
     handle.set_sync(spec.group, spec.pairs)
     ops = torch.from_numpy(words.view(np.int16)).to(dev)
     res, k = handle.alloc_results(C), spec.top_k
@@ -406,8 +409,11 @@ def bench_sync(args, threads) -> int:
     eval_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
     ms_per_step = wall * 1e3 / args.steps
     alg_bytes = 2 * n_ops + C * (8 + 8 * D + 4 * D + 1)
-    roofline, issue = rooflines(alg_bytes, eval_ms, "fpsched evaluation kernel for synchronisation stages (eval_sync_kernel)",
-                                MEASURED_SYNC.get(("sync4", C)), units=n_ops)
+    on_slots = handle.active_kernel() == "slots"
+    roofline, issue = rooflines(alg_bytes, eval_ms,
+                                "fpsched evaluation kernel (eval_slot_kernel, synchronisation mode)" if on_slots
+                                else "fpsched evaluation kernel for synchronisation stages, table form (eval_sync_kernel)",
+                                (MEASURED_SYNC if on_slots else MEASURED_SYNC_TABLE).get(("sync4", C)), units=n_ops)
     flags = res["flags"].cpu().numpy()
     out = {
         "metric": "candidate schedules evaluated/sec", "value": C / (ms_per_step * 1e-3), "unit": "schedules/s",
@@ -481,7 +487,7 @@ def main() -> int:
                     help="evaluate mode: offload and reload items run on a copy engine that holds at most DEPTH "
                          "transfers (1..7) instead of the compute timeline; meant for --config 5")
     ap.add_argument("--table-kernel", action="store_true",
-                    help="evaluate mode: the table form of the evaluation kernel instead of the slot kernel")
+                    help="evaluate and sync modes: the table form of the evaluation kernel instead of the slot kernel")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain elementwise copy of the op batch (a kernel of known HBM "
                          "traffic, used to calibrate rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")

@@ -392,6 +392,11 @@ int fpsched_problem_info(const fpsched_problem *p, int32_t *lanes_per_candidate,
 #define FPSCHED_KERNEL_GENERAL 1
 #define FPSCHED_KERNEL_SLOTS 2
 int fpsched_problem_select_kernel(fpsched_problem *p, int which);
+/* Which of the two fpsched_evaluate would launch under the handle's present cost model and selection:
+ * FPSCHED_KERNEL_SLOTS or FPSCHED_KERNEL_GENERAL (the table form: eval_general_kernel, or eval_sync_kernel
+ * under the synchronisation or copy-engine model when the setting does not fit the slot kernel); a negative
+ * code for a null or host-only handle. */
+int fpsched_problem_active_kernel(const fpsched_problem *p);
 
 /* ---- schedule generator: the actor-aware schedule of Section 5 -------------------------
  * One actor's scheduling priorities (Section 5.2; table of built-in values): the

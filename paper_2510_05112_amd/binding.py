@@ -69,6 +69,8 @@ def load_library():
         lib.fpsched_problem_set_sync.argtypes = [vp, vp, i32, vp]
         lib.fpsched_problem_set_copy_engine.restype = ctypes.c_int
         lib.fpsched_problem_set_copy_engine.argtypes = [vp, i32]
+        lib.fpsched_problem_active_kernel.restype = ctypes.c_int
+        lib.fpsched_problem_active_kernel.argtypes = [vp]
         lib.fpsched_problem_select_kernel.restype = ctypes.c_int
         lib.fpsched_problem_select_kernel.argtypes = [vp, ctypes.c_int]
         lib.fpsched_workspace_bytes.restype = ctypes.c_size_t
@@ -176,6 +178,13 @@ class Problem:
         rc = load_library().fpsched_problem_select_kernel(self._h, {"auto": 0, "general": 1, "slots": 2}[which])
         if rc != 0:
             raise FpschedError(rc, "fpsched_problem_select_kernel")
+
+    def active_kernel(self) -> str:
+        """'slots' or 'general': the kernel ``evaluate`` launches under the present cost model."""
+        rc = load_library().fpsched_problem_active_kernel(self._h)
+        if rc < 0:
+            raise FpschedError(rc, "fpsched_problem_active_kernel")
+        return {1: "general", 2: "slots"}[rc]
 
     def set_microbatch_costs(self, dur_mb):
         """dur_mb[8][S][m] (host array): per-micro-batch costs that replace dur[kind][stage] in evaluate;

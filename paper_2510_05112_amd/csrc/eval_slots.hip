@@ -142,6 +142,15 @@ __global__ void reset_counter_kernel(unsigned long long* counter, unsigned long 
 // transfers' events (a reload allocates at its start, an offload releases at its end) wait in a second ring
 // and are applied as the walk passes their time, compute events first at equal times.  Transfers are no busy
 // time; the makespan covers both timelines.
+//
+// MODE kSlotSync: stages whose items stand for groups of micro-batches (a synchronisation every n micro-batches,
+// Section 4.2 / 7.2 of the paper) and dependency pairs between items of one direction.  An item of a stage with
+// group n waits for the n values of its micro-batches, one slot per round: the lane keeps how many are still to
+// come and the latest arrival so far, moves its input address on whenever the slot it looks at carries the
+// expected tag, and may issue when the last one does; when it issues it writes its result into the n slots of
+// its micro-batches.  Its state nibble is indexed by the item, its slots by the micro-batches.  (The host only
+// selects this form when the neighbours of such a stage have one item per micro-batch.)  A pair (F, a) -> (F, b) or
+// (B, a) -> (B, b) is an edge of its own slot class in one direction only.
 template <int V, bool DEG2, bool ONE_CLASS, int MODE>
 __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     SlotTables T, const uint16_t* __restrict__ ops, long long n_cand, int stride,
@@ -155,6 +164,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   constexpr bool MBLDS = MODE == kSlotPerMicrobatchLds || MODE == kSlotPerMicrobatchLdsLinks;
   constexpr bool LINKS = MODE == kSlotLinks || MODE == kSlotTimesLinks || MODE == kSlotPerMicrobatchLdsLinks;
   constexpr bool COPY = MODE == kSlotCopy;
+  constexpr bool SYNC = MODE == kSlotSync;
   extern __shared__ int32_t lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int m = T.m;
@@ -214,6 +224,13 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     out_b2[c] = LINKS && DEG2 ? dev[2 + 7 * V + c] : 0;
     if (LINKS) asm volatile("" : "+v"(out_f[c]), "+v"(out_b[c]), "+v"(out_f2[c]), "+v"(out_b2[c]));
   }
+  // SYNC: per chunk the micro-batches per item (1: an ordinary stage) | items << 16
+  int grp[V];
+#pragma unroll
+  for (int c = 0; c < V; ++c) {
+    grp[c] = SYNC ? dev[2 + 4 * V + c] : 0;
+    if (SYNC) asm volatile("" : "+v"(grp[c]));
+  }
   const unsigned long long seg_mask =
       (lpc == 64 ? ~0ull : ((1ull << lpc) - 1ull)) << (seg * lpc);
   // LDS byte offsets of this lane's columns
@@ -268,6 +285,9 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   int4 M = make_int4(0, 0, 15, 0);   // metadata row of the current word (an invalid row to begin with)
   int2 M2 = make_int2(0, 0);         // its second-edge row
   unsigned w_next = 0u;              // the word behind the current one
+  // SYNC: the item under the cursor: position of its state nibble, values of its group still to arrive (1: the
+  // slot the round looks at is the last), the latest arrival so far, slots to write when it issues
+  unsigned at_nib = 0u, gat_left = 1u, acc8 = 0u, n_out = 1u;
   // COPY: the copy timeline of this device.  Rings of eight dwords per lane behind its state words (entry i at
   // + i * 256): finish << 8 of the last transfers, their keys (low 13 bits of a reload's word, all ones for an
   // offload), time << 8 and units of the transfer events that the walk has not passed yet.
@@ -313,8 +333,10 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       cur_key = word & 0x1fffu;
     }
     const unsigned j = word & 0x7ffu;
-    const unsigned jc = min(j, (unsigned)m - 1u);
     const unsigned c5 = word >> 11;
+    // (SYNC: the micro-batch field is the item; an item index beyond the stage's count is malformed)
+    const unsigned group_items = SYNC ? (unsigned)pick<V>(grp, c5 & (unsigned)(V - 1)) : 0u;
+    const unsigned jc = min(j, (SYNC ? max(group_items >> 16, 1u) : (unsigned)m) - 1u);
     // a micro-batch out of range reads row 0 (kind 0), which is invalid and never issues
     M = lds_read<int4>(__umul24(j == jc ? c5 : 0u, row_bytes) + meta_off);
     // (c5 < 32, d < lanes per candidate, jc < m: inside the table whatever the word holds)
@@ -335,7 +357,16 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       else dur_mb16 = lds_read<uint8_t>(at_row + jc);
     }
     if (TIMES) at_state = (word >> 13) == (unsigned)kW ? lds0 + zero_off : at_state;
-    at_slot = (jc << 2) + slot_base;   // slot j of the first class; low five bits = 4 (j & 7)
+    unsigned j_first = jc;
+    if (SYNC) {
+      const unsigned n = max(group_items & 0xffffu, 1u);
+      at_nib = jc << 2;
+      j_first = __umul24(jc, n);
+      n_out = min((unsigned)m - j_first, n);
+      gat_left = n_out;
+      acc8 = 0u;
+    }
+    at_slot = (j_first << 2) + slot_base;   // slot j of the first class; low five bits = 4 (j & 7)
     const bool is_b = (word >> 13) == (unsigned)kB;
     // one class: backward inputs at slot j, forward inputs at slot m + j; bit 13 of the word is set
     // for F and FD and clear for B (other kinds have no input, whatever they read is ignored)
@@ -507,15 +538,34 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     // byte of the last metadata dword is 0xff then, else 0).  A live lane has dead == 0, any other
     // lane all ones, which the word never equals.
     // (COPY: bit 3 of the nibble only says that the activation was reloaded)
-    const unsigned state = __builtin_amdgcn_ubfe(sx, bj, COPY ? 3 : 4);
+    const unsigned state = __builtin_amdgcn_ubfe(sx, SYNC ? at_nib : bj, COPY ? 3 : 4);
     unsigned ready8 = (in1 + lat_tag) & (unsigned)((int)my_ >> 24);
     // (only the low byte counts: the state nibble is clean, byte 0 of the third metadata dword
     // holds nothing but the required state, and the ready time sits above its tag byte)
     unsigned veto = __builtin_amdgcn_bitop3_b32(state, mx_, ready8, 0xbe);   // (state ^ mx_) | ready8
+    unsigned tag_bits = ready8;   // low byte zero iff every input slot carries its expected tag
     if (DEG2) {
       const unsigned ready2 = (in2 + (unsigned)M2.x) & (unsigned)(M2.y >> 31);
       veto |= ready2;
+      if (SYNC) tag_bits |= ready2;
       ready8 = max(ready8, ready2);
+    }
+    unsigned long long gathered = 0ull;
+    if (SYNC) {
+      // an item that still waits for more values of its group takes the one in front of it, if it is there
+      // (the tags say so), and looks at the next slot in the next round
+      // (an item without an input has nothing to gather; nor has a malformed word, whose row says so too)
+      const bool more = gat_left > 1u && (my_ >> 24) != 0u;
+      const bool arrived = ((tag_bits & 0xffu) | dead) == 0u && more;
+      gathered = __ballot(arrived);
+      veto |= more ? 1u : 0u;
+      if (arrived) {
+        acc8 = max(acc8, ready8);
+        at_in += 4u;
+        if (DEG2) at_in2 += 4u;
+        gat_left -= 1u;
+      }
+      ready8 = max(ready8, acc8);
     }
     // one compare of the low byte against `dead` yields the issue mask
     unsigned long long moved;
@@ -589,8 +639,9 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       mem -= (int)((my_ >> 8) & 0xffu);
       // state ^= (need ^ next) << nibble position; the shift takes the low five bits of bj
       unsigned flip;
+      const unsigned nib_at = SYNC ? at_nib : bj;
       asm("v_lshlrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1"
-          : "=v"(flip) : "v"(bj), "v"(mx_));
+          : "=v"(flip) : "v"(nib_at), "v"(mx_));
       lds_write<uint32_t>(at_state, sx ^ flip);
       // LINKS: the value leaves when the link to its consumer's device is free, and keeps it busy for
       // the edge's latency (an op that sends nothing off the device uses the lane's spare link word,
@@ -610,6 +661,12 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       // form's tables have no dump region, its offset only marks such ops)
       if (LINKS) lds_write<uint32_t>((mx_ >> 16) != dump_bytes ? bj + (mx_ >> 16) : spare_at, val);
       else lds_write<uint32_t>(bj + (mx_ >> 16), val);
+      if (SYNC) {
+        // an item of a group is the value of each of its micro-batches
+        for (unsigned k = 1; k < n_out; ++k) lds_write<uint32_t>(bj + (mx_ >> 16) + (k << 2), val);
+        if (DEG2 && ((unsigned)M2.y & kMetaHasProd))
+          for (unsigned k = 1; k < n_out; ++k) lds_write<uint32_t>(bj + ((unsigned)M2.y & 0xffffu) + (k << 2), val);
+      }
       if (DEG2) {
         if ((unsigned)M2.y & kMetaHasProd) {
           unsigned val2 = val;
@@ -634,10 +691,10 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     // the top-up looks.  Cheap scalar pre-test: does the issue mask, with the fields of idle
     // segments filled, contain an all-zero field of lpc bits?  (x - lows) & ~x & highs is non-zero
     // iff some field of x is zero.
-    const unsigned long long x = moved | idle_fields;
+    const unsigned long long x = moved | gathered | idle_fields;
     if (sub == kSyncRounds - 1 && (((x - base_bits) & ~x) & high_bits) != 0ull) {
       // fold the issue mask onto the segments' base bits to find which segments ended
-      unsigned long long any_moved = moved;
+      unsigned long long any_moved = moved | gathered;
 #pragma unroll
       for (int i = 0; i < 6; ++i) any_moved |= any_moved >> fold_shift[i];
       const unsigned long long ended = ~any_moved & run_bases;
@@ -649,7 +706,8 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       if (seg_ended && lane_ok) {
         // a stuck device sits on a malformed word?
         const int4 Mh = lds_read<int4>(__umul24(w >> 11, row_bytes) + meta_off);
-        bad_head = (w >> 13) != 0u && (((unsigned)Mh.z & 15u) == 15u || (int)(w & 0x7ff) >= m);
+        const int n_items = SYNC ? pick<V>(grp, (int)((w >> 11) & (unsigned)(V - 1))) >> 16 : m;
+        bad_head = (w >> 13) != 0u && (((unsigned)Mh.z & 15u) == 15u || (int)(w & 0x7ff) >= n_items);
         // every activation of this device consumed?
         for (int i = 0; i < T.state_words; ++i)
           incomplete = incomplete || ((stt[i * 64 + lane] & (COPY ? 0x77777777u : ~0u)) != (unsigned)expect[i]);
@@ -720,7 +778,8 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotLinks)            \
   FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotTimesLinks)       \
   FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotPerMicrobatchLdsLinks) \
-  FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotCopy)
+  FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotCopy) \
+  FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotSync)
 FPSCHED_INSTANTIATE(1, false, true)
 FPSCHED_INSTANTIATE(2, false, true)
 FPSCHED_INSTANTIATE(4, false, true)

@@ -71,6 +71,12 @@ struct fpsched_problem {
   // synchronisation stages and dependency pairs (fpsched_problem_set_sync)
   bool sync_on = false;
   int32_t copy_depth = 0;               // copy-engine form (fpsched_problem_set_copy_engine), 0 = off
+  bool sync_slots_ok = false;           // the synchronisation model has a slot-kernel form for this setting
+  SlotTables stab_sync{};
+  bool sync_deg2 = false;
+  int32_t* d_sync_slot_image = nullptr;
+  size_t sync_slot_image_ints = 0;
+  int32_t sync_slot_waves = 0, sync_slot_grid = 0, sync_slot_lds_bytes = 0;
   bool copy_slots_ok = false;           // ... which the slot kernel can run (its rings fit LDS)
   SlotTables stab_copy{};
   int32_t copy_waves = 0, copy_grid = 0, copy_lds_bytes = 0;
@@ -583,6 +589,7 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
     if (!ok) {
       (void)hipFree(p->d_ints);
       if (p->d_slot_ints) (void)hipFree(p->d_slot_ints);
+    if (p->d_sync_slot_image) (void)hipFree(p->d_sync_slot_image);
       if (p->d_times_ints) (void)hipFree(p->d_times_ints);
       delete p;
       return FPSCHED_EHIP;
@@ -599,6 +606,7 @@ void fpsched_problem_destroy(fpsched_problem* p) {
     DeviceGuard g(p->device_id);
     if (p->d_ints) (void)hipFree(p->d_ints);
     if (p->d_slot_ints) (void)hipFree(p->d_slot_ints);
+    if (p->d_sync_slot_image) (void)hipFree(p->d_sync_slot_image);
     if (p->d_times_ints) (void)hipFree(p->d_times_ints);
     if (p->d_mb_raw) (void)hipFree(p->d_mb_raw);
     if (p->d_mb_rows) (void)hipFree(p->d_mb_rows);
@@ -631,6 +639,14 @@ int fpsched_problem_select_kernel(fpsched_problem* p, int which) {
   return FPSCHED_OK;
 }
 
+int fpsched_problem_active_kernel(const fpsched_problem* p) {
+  if (!p) return FPSCHED_EINVAL;
+  if (p->device_id < 0) return FPSCHED_ENODEV;
+  if (p->sync_on) return p->use_slots && p->sync_slots_ok ? FPSCHED_KERNEL_SLOTS : FPSCHED_KERNEL_GENERAL;
+  if (p->copy_depth > 0) return p->use_slots && p->copy_slots_ok ? FPSCHED_KERNEL_SLOTS : FPSCHED_KERNEL_GENERAL;
+  return p->use_slots && (!p->mb_set || p->mb_slots_ok) ? FPSCHED_KERNEL_SLOTS : FPSCHED_KERNEL_GENERAL;
+}
+
 static int64_t topk_level_sizes(int64_t n, int32_t k, int64_t* first, int64_t* second) {
   // survivors after level 0 and after level 1 (the two ping-pong buffers)
   const int64_t t0 = std::max<int64_t>(1, (n + kTile - 1) / kTile);
@@ -660,7 +676,8 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
   DeviceGuard g(p->device_id);
   if (!g.ok) return FPSCHED_EHIP;
   const bool copy_on_slots = p->copy_depth > 0 && p->use_slots && p->copy_slots_ok;
-  if ((p->sync_on || p->copy_depth > 0) && !copy_on_slots) {
+  const bool sync_on_slots = p->sync_on && p->use_slots && p->sync_slots_ok;
+  if ((p->sync_on || p->copy_depth > 0) && !copy_on_slots && !sync_on_slots) {
     const int cpw = p->sync_tab.cands_per_wave;
     const int64_t blocks = (n_cand + cpw - 1) / cpw;
     if (blocks > 0x7fffffffll) return FPSCHED_EINVAL;
@@ -671,7 +688,7 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
     return check_hip(hipGetLastError());
   }
   if (p->links_on && !p->use_slots) return FPSCHED_EUNSUPPORTED;   // the general kernel has no link form
-  if (copy_on_slots || (p->use_slots && (!p->mb_set || p->mb_slots_ok))) {
+  if (copy_on_slots || sync_on_slots || (p->use_slots && (!p->mb_set || p->mb_slots_ok))) {
     // the first 8 bytes of the workspace hold the counter the segments draw candidates from
     if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) & 15)) return FPSCHED_EINVAL;
     if (workspace_bytes < 256) return FPSCHED_ENOMEM;
@@ -681,10 +698,10 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
     const bool combo = p->links_on && p->mb_set;   // both variants: the setters made sure the tables exist
     if (combo && !p->combo_ok) return FPSCHED_EUNSUPPORTED;
     const bool links = p->links_on && !combo;
-    const SlotTables& tab = copy_on_slots ? p->stab_copy : combo ? p->stab_combo : links ? p->stab_links : (mb_lds ? p->stab_mb : p->stab);
-    const int waves = copy_on_slots ? p->copy_waves : combo ? p->combo_waves : links ? p->links_waves : (mb_lds ? p->mb_waves : p->slot_waves);
-    const int grid = copy_on_slots ? p->copy_grid : combo ? p->combo_grid : links ? p->links_grid : (mb_lds ? p->mb_grid : p->slot_grid);
-    const size_t lds_bytes = (size_t)(copy_on_slots ? p->copy_lds_bytes : combo ? p->combo_lds_bytes : links ? p->links_lds_bytes
+    const SlotTables& tab = sync_on_slots ? p->stab_sync : copy_on_slots ? p->stab_copy : combo ? p->stab_combo : links ? p->stab_links : (mb_lds ? p->stab_mb : p->stab);
+    const int waves = sync_on_slots ? p->sync_slot_waves : copy_on_slots ? p->copy_waves : combo ? p->combo_waves : links ? p->links_waves : (mb_lds ? p->mb_waves : p->slot_waves);
+    const int grid = sync_on_slots ? p->sync_slot_grid : copy_on_slots ? p->copy_grid : combo ? p->combo_grid : links ? p->links_grid : (mb_lds ? p->mb_grid : p->slot_grid);
+    const size_t lds_bytes = (size_t)(sync_on_slots ? p->sync_slot_lds_bytes : copy_on_slots ? p->copy_lds_bytes : combo ? p->combo_lds_bytes : links ? p->links_lds_bytes
                                       : (mb_lds ? p->mb_lds_bytes : p->slot_lds_bytes));
     const int per_block = tab.cands_per_wave * waves;
     const int64_t blocks = std::min<int64_t>((n_cand + per_block - 1) / per_block, grid);
@@ -696,8 +713,9 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
     // segment g starts on candidate g; the counter hands out the candidates after those
     hipLaunchKernelGGL(reset_counter_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(hip_stream), counter,
                        (unsigned long long)(blocks * per_block));
-    const bool one_class = p->stab.n_classes == 1;
-    const SlotKernel kernel = copy_on_slots ? slot_kernel_of<kSlotCopy>(p->slot_v, p->slot_deg2, one_class)
+    const bool one_class = tab.n_classes == 1;
+    const SlotKernel kernel = sync_on_slots ? slot_kernel_of<kSlotSync>(p->slot_v, p->sync_deg2, one_class)
+                              : copy_on_slots ? slot_kernel_of<kSlotCopy>(p->slot_v, p->slot_deg2, one_class)
                               : combo ? slot_kernel_of<kSlotPerMicrobatchLdsLinks>(p->slot_v, p->slot_deg2, one_class)
                               : links ? slot_kernel_of<kSlotLinks>(p->slot_v, p->slot_deg2, one_class)
                               : !p->mb_set ? slot_kernel_ptr(p->slot_v, p->slot_deg2, one_class)
@@ -1155,6 +1173,178 @@ static int install_table_model(fpsched_problem* p, const std::vector<int32_t>& g
   return FPSCHED_OK;
 }
 
+// The slot kernel's form of the synchronisation model (mode kSlotSync): possible when every dependency pair runs
+// forward-to-forward or backward-to-backward, no stage has more than two inputs or outputs in either direction
+// (pairs included), and the neighbours of a stage with more than one micro-batch per item all have one.  The
+// table image has the plain layout; a pair is an edge of a slot class of its own that exists in one direction.
+// Leaves p->sync_slots_ok false when the setting does not fit.
+static void build_sync_slot_tables(fpsched_problem* p, const std::vector<int32_t>& grp, const std::vector<int32_t>& items,
+                                   int32_t n_pairs, const fpsched_dependency* pairs, int64_t max_lat) {
+  p->sync_slots_ok = false;
+  if (!p->slots_ok) return;   // (units, stage count and word format were checked for the plain tables)
+  const int D = p->D, S = p->S, m = p->m;
+  const std::vector<int32_t>& I = p->host_ints;
+  const DevTables& T = p->tables;
+  if ((int64_t)D * p->max_stride * (p->max_dur + max_lat) >= (1ll << 24) || max_lat >= (1ll << 16)) return;
+  struct In { int from, lat, cls; };
+  std::vector<std::vector<In>> fwd_in(S), bwd_in(S);
+  std::vector<std::vector<int>> fwd_out(S), bwd_out(S), partners(S);
+  // classes of the DAG's edges: chains, as for the plain tables
+  std::vector<std::vector<int>> out_cls(S);
+  int n_classes = 0;
+  {
+    std::vector<int> indeg(S, 0), order;
+    std::vector<std::vector<int>> arriving(S);
+    for (int s = 0; s < S; ++s) indeg[s] = I[T.off_pred_off + s + 1] - I[T.off_pred_off + s];
+    for (int s = 0; s < S; ++s) if (!indeg[s]) order.push_back(s);
+    for (size_t i = 0; i < order.size(); ++i) {
+      const int s = order[i];
+      size_t used = 0;
+      for (int e = I[T.off_succ_off + s]; e < I[T.off_succ_off + s + 1]; ++e) {
+        const int v = I[T.off_succ_stage + e], lat = I[T.off_succ_comm + e];
+        const int cls = used < arriving[s].size() ? arriving[s][used++] : n_classes++;
+        arriving[v].push_back(cls);
+        fwd_out[s].push_back(cls); fwd_in[v].push_back(In{s, lat, cls});
+        bwd_in[s].push_back(In{v, lat, cls}); bwd_out[v].push_back(cls);
+        partners[s].push_back(v); partners[v].push_back(s);
+        if (--indeg[v] == 0) order.push_back(v);
+      }
+    }
+  }
+  for (int i = 0; i < n_pairs; ++i) {
+    const fpsched_dependency& q = pairs[i];
+    const int a = q.stage_from, b = q.stage_to;
+    const int lat = p->stage_device[a] != p->stage_device[b] ? q.latency : 0;
+    const int cls = n_classes++;
+    if (q.kind_from == FPSCHED_F && q.kind_to == FPSCHED_F) {
+      fwd_out[a].push_back(cls); fwd_in[b].push_back(In{a, lat, cls});
+    } else if (q.kind_from == FPSCHED_B && q.kind_to == FPSCHED_B) {
+      bwd_out[a].push_back(cls); bwd_in[b].push_back(In{a, lat, cls});
+    } else {
+      return;   // a pair the mail slots cannot carry
+    }
+    partners[a].push_back(b); partners[b].push_back(a);
+  }
+  if (n_classes == 0) n_classes = 1;
+  bool deg2 = false;
+  for (int s = 0; s < S; ++s) {
+    const size_t most = std::max({fwd_in[s].size(), fwd_out[s].size(), bwd_in[s].size(), bwd_out[s].size()});
+    if (most > 2) return;
+    if (most > 1) deg2 = true;
+    if (grp[s] > 1)
+      for (int t : partners[s]) if (grp[t] != 1) return;
+  }
+  const int V = p->slot_v, lpc = T.lanes_per_cand;
+  const int slot_stride = ((2 * n_classes + 1) * m + 7) & ~7;
+  if (4ll * slot_stride > 0xffff) return;
+  const int64_t unit_scale = p->stab.unit_scale;
+  const int n_meta = kNKinds * kMaxChunks * lpc * 4;
+  const int n_meta2 = deg2 ? (2 * kMaxChunks + 1) * lpc * 2 : 0;
+  const int n_shared = (n_meta + n_meta2 + 511) & ~511;
+  const unsigned dump_bytes = (unsigned)(2 * n_classes * m) * 4u;
+  const int dev_ints = 2 + 5 * V;
+  const int words_per_chunk = (m + 7) / 8;
+  const int state_words = V * words_per_chunk;
+  std::vector<int32_t> J((size_t)n_shared + (size_t)lpc * dev_ints + (size_t)lpc * state_words, 0);
+  static const int need_of[kNKinds] = {15, kAbsent, kRes, kBDone, kDisc, kRes, kOff, kAbsent};
+  static const int next_of[kNKinds] = {0, kRes, kBDone, kDone, kRes, kOff, kRes, kDisc};
+  auto fwd_slot = [&](int cls) { return (unsigned)((n_classes + cls) * m) * 4u; };
+  auto bwd_slot = [&](int cls) { return (unsigned)(cls * m) * 4u; };
+  for (int kind = 0; kind < kNKinds; ++kind)
+    for (int c = 0; c < kMaxChunks; ++c)
+      for (int d = 0; d < lpc; ++d) {
+        int32_t* e = &J[(((size_t)kind * kMaxChunks + c) * lpc + d) * 4];
+        e[2] = (int32_t)(15u | (dump_bytes << 16));
+        if (d >= D || c >= p->n_chunks[d] || kind == kEnd || (kind == kW && !p->has_w)) continue;
+        const int st = p->local_stage[(size_t)d * kMaxChunks + c];
+        const unsigned units = (unsigned)(I[T.off_mem_units + st] / unit_scale);
+        const bool allocs = kind == kF || kind == kFD || kind == kR || kind == kL;
+        const bool frees = kind == kFD || kind == kO || kind == (p->has_w ? kW : kB);
+        unsigned has_in = 0, tag = 0, prod = dump_bytes, comm = 0;
+        if (kind == kF || kind == kFD) {
+          if (!fwd_in[st].empty()) { has_in = 0xffu; tag = (unsigned)fwd_in[st][0].from; comm = (unsigned)fwd_in[st][0].lat; }
+          if (!fwd_out[st].empty()) prod = fwd_slot(fwd_out[st][0]);
+        } else if (kind == kB) {
+          if (!bwd_in[st].empty()) { has_in = 0xffu; tag = (unsigned)bwd_in[st][0].from; comm = (unsigned)bwd_in[st][0].lat; }
+          if (!bwd_out[st].empty()) prod = bwd_slot(bwd_out[st][0]);
+        }
+        e[0] = (int32_t)((unsigned)I[T.off_dur + kind * S + st] << 8);
+        e[1] = (int32_t)((comm << 8) - tag);
+        e[2] = (int32_t)((unsigned)need_of[kind] | ((unsigned)(need_of[kind] ^ next_of[kind]) << 8) | (prod << 16));
+        e[3] = (int32_t)((allocs ? units : 0u) | ((frees ? units : 0u) << 8) | ((unsigned)st << 16) | (has_in << 24));
+      }
+  for (int dir = 0; dir < 2 && deg2; ++dir)
+    for (int c = 0; c < kMaxChunks; ++c)
+      for (int d = 0; d < D; ++d) {
+        if (c >= p->n_chunks[d]) continue;
+        const int st = p->local_stage[(size_t)d * kMaxChunks + c];
+        int32_t* e = &J[(size_t)n_meta + (((size_t)dir * kMaxChunks + c) * lpc + d) * 2];
+        const std::vector<In>& in = dir == 0 ? fwd_in[st] : bwd_in[st];
+        const std::vector<int>& out = dir == 0 ? fwd_out[st] : bwd_out[st];
+        unsigned y = 0;
+        if (in.size() > 1) { y |= kMetaHasCons; e[0] = (int32_t)(((unsigned)in[1].lat << 8) - (unsigned)in[1].from); }
+        if (out.size() > 1) y |= kMetaHasProd | (dir == 0 ? fwd_slot(out[1]) : bwd_slot(out[1]));
+        e[1] = (int32_t)y;
+      }
+  for (int d = 0; d < D; ++d) {
+    // state words of device d once every item placed on it is consumed
+    int32_t* x = &J[(size_t)n_shared + (size_t)lpc * dev_ints + (size_t)d * state_words];
+    const unsigned terminal = p->has_w ? kDone : kBDone;
+    for (int c = 0; c < p->n_chunks[d]; ++c) {
+      const int st = p->local_stage[(size_t)d * kMaxChunks + c];
+      for (int g = 0; g < items[st]; ++g) x[c * words_per_chunk + (g >> 3)] |= (int32_t)(terminal << ((g & 7) * 4));
+    }
+    int32_t* e = &J[(size_t)n_shared + (size_t)d * dev_ints];
+    e[0] = p->n_chunks[d];
+    e[1] = (int32_t)(I[T.off_mem_cap + d] / unit_scale);
+    for (int c = 0; c < p->n_chunks[d]; ++c) {
+      const int st = p->local_stage[(size_t)d * kMaxChunks + c];
+      e[2 + c] = !fwd_in[st].empty() ? (n_classes + fwd_in[st][0].cls) * m : 0;
+      e[2 + V + c] = !bwd_in[st].empty() ? bwd_in[st][0].cls * m : 0;
+      e[2 + 2 * V + c] = fwd_in[st].size() > 1 ? (n_classes + fwd_in[st][1].cls) * m : 0;
+      e[2 + 3 * V + c] = bwd_in[st].size() > 1 ? bwd_in[st][1].cls * m : 0;
+      e[2 + 4 * V + c] = grp[st] | (items[st] << 16);
+    }
+    for (int c = p->n_chunks[d]; c < V; ++c) e[2 + 4 * V + c] = 1;   // (no such chunk: no item is valid)
+  }
+  SlotTables ST = p->stab;
+  ST.n_classes = n_classes;
+  ST.slots_per_cand = slot_stride;
+  ST.state_words = state_words;
+  ST.n_shared_ints = n_shared;
+  ST.off_meta2 = n_meta;
+  ST.off_dev = n_shared;
+  ST.dev_ints = dev_ints;
+  ST.off_expect = n_shared + lpc * dev_ints;
+  ST.off_mb = 0; ST.link_words = 0; ST.mb_kind_map = 0; ST.copy_depth = 0;
+  const SlotGeometry geo = slot_geometry(n_shared, lpc, state_words, slot_stride, p->max_lds);
+  if (geo.waves < 1) return;
+  ST.cands_per_wave = geo.cands_per_wave;
+  ST.wave_ints = geo.wave_ints;
+  DeviceGuard g(p->device_id);
+  if (!g.ok) return;
+  if (J.size() > p->sync_slot_image_ints) {
+    if (p->d_sync_slot_image) (void)hipFree(p->d_sync_slot_image);
+    p->d_sync_slot_image = nullptr;
+    p->sync_slot_image_ints = 0;
+    if (hipMalloc(&p->d_sync_slot_image, J.size() * sizeof(int32_t)) != hipSuccess) { (void)hipGetLastError(); p->d_sync_slot_image = nullptr; return; }
+    p->sync_slot_image_ints = J.size();
+  }
+  if (hipMemcpy(p->d_sync_slot_image, J.data(), J.size() * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess ||
+      hipFuncSetAttribute(reinterpret_cast<const void*>(slot_kernel_of<kSlotSync>(V, deg2, n_classes == 1)),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, p->max_lds) != hipSuccess) {
+    (void)hipGetLastError();
+    return;
+  }
+  ST.ints = p->d_sync_slot_image;
+  p->stab_sync = ST;
+  p->sync_deg2 = deg2;
+  p->sync_slot_waves = geo.waves;
+  p->sync_slot_grid = p->n_cu * geo.groups;
+  p->sync_slot_lds_bytes = (int32_t)(4ll * (n_shared + (int64_t)geo.waves * geo.wave_ints));
+  p->sync_slots_ok = true;
+}
+
 int fpsched_problem_set_sync(fpsched_problem* p, const int32_t* group, int32_t n_pairs,
                              const fpsched_dependency* pairs) {
   if (!p || n_pairs < 0 || (n_pairs > 0 && !pairs)) return FPSCHED_EINVAL;
@@ -1192,6 +1382,7 @@ int fpsched_problem_set_sync(fpsched_problem* p, const int32_t* group, int32_t n
   if (p->device_id >= 0) {
     const int rc = install_table_model(p, grp, items, n_pairs, pairs, wants_w, 0);
     if (rc != FPSCHED_OK) return rc;
+    build_sync_slot_tables(p, grp, items, n_pairs, pairs, max_lat);
   }
   p->sync_items = items;
   p->sync_on = true;

@@ -50,8 +50,11 @@ constexpr int kSlotMaxThreads = 64 * kSlotMaxWaves;
 // MODE kSlotCopy: offload and reload items run on a copy engine beside the computation (T.copy_depth transfers
 // at most in the engine; T.link_words = 32 dwords per lane behind its state words: the finish times and keys of
 // the last eight transfers, and a ring of eight pending memory events).
+// MODE kSlotSync: synchronisation stages (one item per group of micro-batches) and dependency pairs of the
+// forms the mail slots can carry (forward to forward, backward to backward); the dev rows then have V more ints:
+// per chunk the micro-batches per item | items << 16.
 constexpr int kSlotPlain = 0, kSlotTimes = 1, kSlotPerMicrobatch = 2, kSlotPerMicrobatchLds = 3, kSlotLinks = 4,
-              kSlotTimesLinks = 5, kSlotPerMicrobatchLdsLinks = 6, kSlotCopy = 7;
+              kSlotTimesLinks = 5, kSlotPerMicrobatchLdsLinks = 6, kSlotCopy = 7, kSlotSync = 8;
 constexpr int kSlotCopyWords = 32;
 template <int V, bool DEG2, bool ONE_CLASS, int MODE>
 __global__ void eval_slot_kernel(SlotTables T, const uint16_t* ops, long long n_cand, int stride,

@@ -185,3 +185,51 @@ def random_sync_problem(rng, trial):
             a, b = b, a
         pairs.append((k1, a, k2, b, int(rng.integers(0, 4))))
     return prob, group, pairs
+
+
+def random_slot_sync_problem(rng):
+    """A problem with synchronisation stages and pairs of the kind the slot kernel has a form for: a stage DAG
+    with at most two inputs and outputs per stage, pairs that run forward-to-forward or backward-to-backward
+    (and keep those bounds), groups of micro-batches only on stages all of whose neighbours have one item per
+    micro-batch."""
+    D = int(rng.integers(2, 7))
+    S = int(rng.integers(D, min(3 * D, 11) + 1))
+    m = int(rng.integers(2, 10))
+    has_w = int(rng.integers(2))
+    stage_device = [int(x) for x in rng.permutation(D)] + [int(rng.integers(D)) for _ in range(S - D)]
+    while max(np.bincount(stage_device)) > 4:
+        stage_device = [int(x) for x in rng.permutation(D)] + [int(rng.integers(D)) for _ in range(S - D)]
+    # edges a -> b with a < b, in- and out-degree at most two
+    fin, fout, bin_, bout = [0] * S, [0] * S, [0] * S, [0] * S   # degrees per direction
+    edges, nbr = [], [set() for _ in range(S)]
+    for b in range(int(rng.integers(1, min(3, S) + 1)), S):
+        cands = [a for a in range(b) if fout[a] < 2]
+        for a in rng.choice(cands, size=min(len(cands), int(rng.integers(1, 3))), replace=False) if cands else []:
+            a = int(a)
+            edges.append((a, b, int(rng.integers(0, 4))))
+            fout[a] += 1; fin[b] += 1; bin_[a] += 1; bout[b] += 1
+            nbr[a].add(b); nbr[b].add(a)
+    pairs = []
+    for _ in range(int(rng.integers(0, 4))):
+        a, b = sorted(int(x) for x in rng.choice(S, 2, replace=False))
+        if rng.random() < 0.5:
+            if fout[a] < 2 and fin[b] < 2:                 # forward of a before forward of b
+                pairs.append((F, a, F, b, int(rng.integers(0, 4))))
+                fout[a] += 1; fin[b] += 1
+                nbr[a].add(b); nbr[b].add(a)
+        elif bout[b] < 2 and bin_[a] < 2:                  # backward of b before backward of a
+            pairs.append((B, b, B, a, int(rng.integers(0, 4))))
+            bout[b] += 1; bin_[a] += 1
+            nbr[a].add(b); nbr[b].add(a)
+    group = [1] * S
+    for s in rng.permutation(S):
+        s = int(s)
+        if rng.random() < 0.4 and all(group[t] == 1 for t in nbr[s]):
+            group[s] = int(rng.choice([2, 3, m]))
+    dur = {k: rng.integers(0 if k != B else 1, 9, S) for k in (F, B, R, O, L)}
+    dur[FD] = dur[F]
+    if has_w:
+        dur[W] = rng.integers(0, 6, S)
+    prob = make_problem(D, S, m, has_w, stage_device, edges, dur, mem_units=rng.integers(0, 3, S),
+                        mem_cap=rng.integers(m, 4 * m, D))
+    return prob, group, pairs

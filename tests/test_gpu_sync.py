@@ -8,17 +8,23 @@ import oracle
 import paper_2510_05112_amd as fp
 import workloads
 from gpu_common import assert_same
-from helpers import batch_from_lists, perturb, random_sync_lists, random_sync_problem
+from helpers import batch_from_lists, perturb, random_slot_sync_problem, random_sync_lists, random_sync_problem
 from workloads.problem import B, F, FD, W, make_problem, pack_lists, pack_word
 
 pytestmark = pytest.mark.gpu
 
 
-def gpu_sync(problem, words, group, pairs, k=None, max_stride=None):
+def gpu_sync(problem, words, group, pairs, k=None, max_stride=None, kernel="auto", expect_kernel=None):
+    """kernel: "auto" = the slot kernel's form of the model where the setting fits it, "general" = the table
+    kernel (eval_sync_kernel<false>)."""
     words = np.ascontiguousarray(words, dtype=np.uint16)
     C, D, stride = words.shape
     h = fp.Problem(problem, max_stride or stride, device=0)
+    if kernel != "auto":
+        h.select_kernel(kernel)
     h.set_sync(group, pairs)
+    if expect_kernel:
+        assert h.active_kernel() == expect_kernel
     ops = torch.from_numpy(words.view(np.int16)).cuda()
     res = h.evaluate(ops)
     top = h.topk(res, k) if k else None
@@ -38,10 +44,12 @@ def test_hand_worked_timeline_on_the_gpu():
     early = [lists[0], [lists[1][0], lists[1][2], lists[1][1]] + lists[1][3:]]
     bad = [lists[0], lists[1][:2] + [(F, 1, 1)] + lists[1][3:]]
     words = batch_from_lists([lists, early, bad], 8)
-    out, _ = gpu_sync(prob, words, [1, 1, 2], None)
-    assert list(out["flags"]) == [0, 1, 3] and out["makespan"][0] == 18
-    assert list(out["idle"][0]) == [6, 0] and list(out["peak"][0]) == [2, 2]
-    assert_same(out, oracle.evaluate_sync(prob, words, group=[1, 1, 2]), "hand-worked")
+    for kernel in ("slots", "general"):   # the synchronisation stage's neighbours have one item per micro-batch
+        out, _ = gpu_sync(prob, words, [1, 1, 2], None, kernel="auto" if kernel == "slots" else kernel,
+                          expect_kernel=kernel)
+        assert list(out["flags"]) == [0, 1, 3] and out["makespan"][0] == 18
+        assert list(out["idle"][0]) == [6, 0] and list(out["peak"][0]) == [2, 2]
+        assert_same(out, oracle.evaluate_sync(prob, words, group=[1, 1, 2]), f"hand-worked {kernel}")
 
 
 def test_random_problems_groups_and_pairs_against_the_oracle():
@@ -75,12 +83,49 @@ def test_random_problems_groups_and_pairs_against_the_oracle():
     assert n_run > 45 and n_dead > 60 and n_w > 3
 
 
+def test_settings_the_slot_kernel_has_a_form_for():
+    # groups in the middle of chains and at joins, forward and backward pairs, two inputs or outputs per stage:
+    # the slot kernel's form of the model and the table kernel against the oracle
+    rng = np.random.default_rng(91)
+    n_grouped = n_pairs = n_deg2 = n_dead = 0
+    for trial in range(80):
+        prob, group, pairs = random_slot_sync_problem(rng)
+        lists = []
+        for t in range(6):
+            base = random_sync_lists(prob, group, pairs, rng, 0.25 * (t % 2), 0.25 * ((t // 2) % 2))
+            if base is None:
+                break
+            cut = [list(x) for x in base]
+            d = int(rng.integers(prob.n_devices))
+            if cut[d]:
+                cut[d].pop(int(rng.integers(len(cut[d]))))
+            lists += [base, perturb(base, rng, 1 + t % 3), cut]
+        if not lists:
+            continue
+        words = batch_from_lists(lists)
+        words[-1, 0, 0] = pack_word(F, 0, 2047)   # an item index beyond its stage's item count
+        ref = oracle.evaluate_sync(prob, words, group=group, pairs=pairs)
+        out, top = gpu_sync(prob, words, group, pairs, k=5, expect_kernel="slots")
+        assert_same(out, ref, f"trial {trial} slots")
+        idx, ms, cnt = oracle.topk(ref["makespan"], ref["flags"], 5)
+        assert top[2] == cnt and np.array_equal(top[0], idx) and np.array_equal(top[1], ms)
+        out, _ = gpu_sync(prob, words, group, pairs, kernel="general", expect_kernel="general")
+        assert_same(out, ref, f"trial {trial} general")
+        n_grouped += any(g > 1 for g in group)
+        n_pairs += bool(pairs)
+        n_deg2 += max(np.bincount(np.asarray(prob.edge_dst), minlength=1)) > 1
+        n_dead += int((ref["flags"] & 1).sum())
+    assert n_grouped > 30 and n_pairs > 10 and n_deg2 > 20 and n_dead > 40
+
+
+@pytest.mark.parametrize("kernel", ["slots", "general"])
 @pytest.mark.parametrize("every", [1, 4, 7, 64])
-def test_multimodal_workload_reduced_batch(every):
+def test_multimodal_workload_reduced_batch(every, kernel):
     spec = workloads.sync_config(3001, sync_every=every)
     words = workloads.generate_sync(spec, threads=8)
     ref = oracle.evaluate_sync(spec.problem, words, spec.group, spec.pairs, threads=8)
-    out, top = gpu_sync(spec.problem, words, spec.group, spec.pairs, k=spec.top_k)
+    out, top = gpu_sync(spec.problem, words, spec.group, spec.pairs, k=spec.top_k,
+                        kernel="auto" if kernel == "slots" else kernel, expect_kernel=kernel)
     assert_same(out, ref, f"sync every {every}")
     idx, ms, cnt = oracle.topk(ref["makespan"], ref["flags"], spec.top_k)
     assert top[2] == cnt and np.array_equal(top[0], idx) and np.array_equal(top[1], ms)
