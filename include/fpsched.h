@@ -186,8 +186,12 @@ int fpsched_problem_set_link_occupancy(fpsched_problem *p, int32_t on);
  *     kind (FPSCHED_F also constrains FD).  Pairs that close a cycle make candidates deadlock, which
  *     their flags report.
  * From then on fpsched_evaluate (and fpsched_evaluate_topk_static) time the candidates under this
- * model, with a kernel that keeps whole finish-time tables in LDS; fpsched_encode and
- * fpsched_validate check micro-batch fields against the item counts.  (NULL, 0, NULL) switches back.
+ * model -- with the slot kernel when every pair runs forward-to-forward or backward-to-backward, no
+ * stage has more than two inputs or outputs in a direction (pairs included) and the neighbours of a
+ * stage with group > 1 all have group 1, else with a kernel that keeps whole finish-time tables in LDS
+ * (fpsched_problem_active_kernel says which; the slot kernel needs the workspace as in the plain
+ * model); fpsched_encode and fpsched_validate check micro-batch fields against the item counts.
+ * (NULL, 0, NULL) switches back.
  * Copied; synchronous (waits for the device's queued work); allocates one table of device memory
  * (FPSCHED_ENOMEM), freed by fpsched_problem_destroy.  FPSCHED_EINVAL for a group < 1, a stage or
  * kind out of range, a negative latency, W without split backward, or a pair from an item to
