@@ -48,7 +48,9 @@ MEASURED_BOTH = {("cfg4", 65536): {"traffic_bytes": 3.765e9, "valu_wave_instruct
                                    "valu_per_wave_round": None, "profile_kernel_ms": 8.554,
                                    "profile": "profiles/eval_slot_kernel_cfg4_links_and_microbatch_costs.md"}}
 # the evaluation with synchronisation stages (--mode sync)
-MEASURED_SYNC = {}
+MEASURED_SYNC = {("sync4", 65536): {"traffic_bytes": None, "valu_wave_instructions": 5.74e8,
+                                   "valu_per_wave_round": None, "profile_kernel_ms": 1.312,
+                                   "profile": "profiles/eval_sync_kernel.md"}}
 MEASURED_SYNC_TABLE = {("sync4", 65536): {"traffic_bytes": None, "valu_wave_instructions": 1.068e9,
                                          "valu_per_wave_round": None, "profile_kernel_ms": 7.12,
                                          "profile": "profiles/eval_sync_kernel.md"}}
