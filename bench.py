@@ -48,6 +48,10 @@ MEASURED_BOTH = {("cfg4", 65536): {"traffic_bytes": 3.765e9, "valu_wave_instruct
                                    "valu_per_wave_round": None, "profile_kernel_ms": 8.554,
                                    "profile": "profiles/eval_slot_kernel_cfg4_links_and_microbatch_costs.md"}}
 # the evaluation with synchronisation stages (--mode sync)
+# the sliding pass without its lists (--mode wslide --no-lists): one launch of the evaluation kernel's sliding mode
+MEASURED_WSLIDE_EVAL = {("cfg4", 65536): {"traffic_bytes": 4.64e9, "valu_wave_instructions": 5.813e9,
+                                          "valu_per_wave_round": None, "profile_kernel_ms": 10.83,
+                                          "profile": "profiles/wslide_kernel_cfg4.md"}}
 MEASURED_SYNC = {("sync4", 65536): {"traffic_bytes": None, "valu_wave_instructions": 5.74e8,
                                    "valu_per_wave_round": None, "profile_kernel_ms": 1.312,
                                    "profile": "profiles/eval_sync_kernel.md"}}
@@ -142,10 +146,14 @@ def bench_generate(args, spec, threads) -> int:
     ws = handle.alloc_workspace(n, k)
     res = handle.alloc_results(n) if search else None
     slide = search and args.slide and bool(prob.has_w)
-    if slide:   # the generated schedules also go through the sliding pass (Section 5.2, bubble optimizations)
+    if slide and args.links:
+        # the generated schedules also go through the sliding pass (Section 5.2, bubble optimizations)
         slide_ws = torch.empty(int(fp.load_library().fpsched_wslide_workspace_bytes(handle._h, n, stride)),
                                dtype=torch.uint8, device=dev)
         slid = handle.wslide(out["ops"], stride, workspace=slide_ws)
+    elif slide:
+        # (plain cost model: the one-kernel form ranks the slid schedules, and only the winners' lists are written)
+        slid = handle.wslide_evaluate(out["ops"], workspace=ws)
     top = dict(idx=torch.empty(k, dtype=torch.int64, device=dev),
                makespan=torch.empty(k, dtype=torch.int64, device=dev),
                count=torch.empty(1, dtype=torch.int32, device=dev))
@@ -163,9 +171,13 @@ def bench_generate(args, spec, threads) -> int:
             handle.topk(res, k, ws, top)
             handle.generate_selected(d_pol, d_inf, top["idx"], stride, out=winners, workspace=ws)
         elif search:
-            if slide:
+            if slide and args.links:
                 handle.wslide(out["ops"], stride, out=slid, workspace=slide_ws)
                 handle.topk(slid, k, ws, top)
+            elif slide:
+                handle.wslide_evaluate(out["ops"], out=slid, workspace=ws)
+                handle.topk(slid, k, ws, top)
+                handle.wslide(out["ops"].index_select(0, top["idx"].clamp(min=0)), stride)
             else:
                 handle.evaluate(out["ops"], res, ws)
                 handle.topk(res, k, ws, top)
@@ -294,27 +306,49 @@ def bench_wslide(args, spec, threads) -> int:
         del probe
     slide_ws = torch.empty(int(fp.load_library().fpsched_wslide_workspace_bytes(handle._h, C, stride)),
                            dtype=torch.uint8, device=dev)
-    out = handle.wslide(ops, stride, workspace=slide_ws)
+    no_lists = args.no_lists
+    winners = None
+    if no_lists:
+        def step(out):
+            out = handle.wslide_evaluate(ops, out=out, workspace=ws)
+            return out
+
+        def after(out):
+            # the lists of the k winners only
+            top = handle.topk(out, k, ws)
+            rows = ops.index_select(0, top["idx"].clamp_(min=0))
+            return top, handle.wslide(rows, stride)
+        out = step(None)
+    else:
+        def step(out):
+            return handle.wslide(ops, stride, out=out, workspace=slide_ws)
+
+        def after(out):
+            return handle.topk(out, k, ws), None
+        out = step(None)
     for _ in range(args.warmup):
-        handle.wslide(ops, stride, out=out, workspace=slide_ws)
+        step(out)
+        after(out)
     torch.cuda.synchronize()
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
     t0 = time.perf_counter()
     for i in range(args.steps):
         ev[i][0].record()
-        handle.wslide(ops, stride, out=out, workspace=slide_ws)
+        step(out)
         ev[i][1].record()
-        top = handle.topk(out, k, ws)
+        top, winners = after(out)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     kernel_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
     ms_per_step = wall * 1e3 / args.steps
     # algorithmic bytes of one launch: the op words read, the new rows written in full (END padding
     # included: the evaluator reads them as they are), the per-candidate results
-    alg_bytes = 2 * n_ops + words.nbytes + C * (8 + 8 * D + 4 * D + 1)
+    alg_bytes = 2 * n_ops + (0 if no_lists else words.nbytes) + C * (8 + 8 * D + 4 * D + 1)
     ws_roofline, ws_issue = rooflines(
-        alg_bytes, kernel_ms, "fpsched sliding pass: eval_slot_kernel in its timing mode + wslide_place_kernel",
-        None if args.links else MEASURED_WSLIDE.get((f"cfg{spec.index}", C)))
+        alg_bytes, kernel_ms,
+        "fpsched sliding pass without lists: eval_slot_kernel in its sliding mode" if no_lists
+        else "fpsched sliding pass: eval_slot_kernel in its timing mode + wslide_place_kernel",
+        None if args.links else (MEASURED_WSLIDE_EVAL if no_lists else MEASURED_WSLIDE).get((f"cfg{spec.index}", C)))
     fl0, fl1 = before["flags"].cpu().numpy(), out["flags"].cpu().numpy()
     ms0, ms1 = before["makespan"].cpu().numpy(), out["makespan"].cpu().numpy()
     both = ((fl0 & 3) == 0) & ((fl1 & 3) == 0)
@@ -324,7 +358,8 @@ def bench_wslide(args, spec, threads) -> int:
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int32", "data": "synthetic",
         "config": {"workload": f"weight-gradient sliding on cfg{spec.index}: {prob.name}, {C} candidates, top-{k}"
-                               + (", link occupancy" if args.links else ""),
+                               + (", link occupancy" if args.links else "")
+                               + (", results for all candidates and the lists of the winners only" if no_lists else ""),
                    "candidates": C, "devices": D, "stages": prob.n_stages, "microbatches": prob.n_microbatches,
                    "ops_per_candidate": n_ops / C, "stride_words": stride},
         "wslide_kernel_ms": kernel_ms,
@@ -344,8 +379,16 @@ def bench_wslide(args, spec, threads) -> int:
             pick = np.sort(rng.choice(C, min(args.check, C), replace=False))
             ref = oracle.wslide(prob, words[pick], stride, threads=threads, links=args.links)
             sel = torch.from_numpy(pick).to(dev)
-            ok = np.array_equal(out["ops"][sel].cpu().numpy().view(np.uint16), ref["ops"]) and all(
-                np.array_equal(out[n][sel].cpu().numpy(), ref[n]) for n in ("makespan", "idle", "peak", "flags"))
+            ok = all(np.array_equal(out[n][sel].cpu().numpy(), ref[n]) for n in ("makespan", "idle", "peak", "flags"))
+            if no_lists:
+                # the winners' lists against the oracle's lists of the same candidates
+                n_top = int(top["count"].item())
+                idx = top["idx"][:n_top].cpu().numpy()
+                ref_top = oracle.wslide(prob, words[idx], stride, threads=threads)
+                ok = ok and all(np.array_equal(winners[n][:n_top].cpu().numpy().view(ref_top[n].dtype), ref_top[n])
+                                for n in ("ops", "makespan", "idle", "peak", "flags"))
+            else:
+                ok = ok and np.array_equal(out["ops"][sel].cpu().numpy().view(np.uint16), ref["ops"])
             json_res["parity_sample"] = {"candidates": int(len(pick)), "bit_exact": bool(ok)}
             if not ok:
                 print("[bench] PARITY FAILURE against the sliding oracle on the sample", file=sys.stderr)
@@ -477,6 +520,9 @@ def main() -> int:
     ap.add_argument("--fused", action="store_true",
                     help="search mode: one kernel generates and times the schedules (fpsched_generate_evaluate); no op "
                          "words are written except the rows of the k winners")
+    ap.add_argument("--no-lists", action="store_true",
+                    help="wslide mode: the one-kernel form that evaluates the slid lists without writing them "
+                         "(fpsched_wslide_evaluate), top-k, then fpsched_wslide on the k winners only")
     ap.add_argument("--slide", action="store_true",
                     help="search mode: rank the generated schedules after the weight-gradient sliding pass")
     ap.add_argument("--mb-costs", action="store_true",

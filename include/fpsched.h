@@ -345,6 +345,20 @@ int fpsched_wslide(const fpsched_problem *p, const uint16_t *d_ops, int64_t n_ca
                    fpsched_results out, void *d_workspace, size_t workspace_bytes,
                    void *hip_stream);
 
+/* The same pass when only the evaluation of the new lists is wanted (a search that ranks the
+ * slid candidates and then asks fpsched_wslide for the lists of the few it keeps): `out` is
+ * what fpsched_wslide reports with rows long enough for every item, without any list being
+ * written (Section 5.2, bubble optimizations; the rules above).  One kernel: the walk of
+ * fpsched_evaluate over the lists without their W words, in which a device runs its oldest
+ * stashed W items in front of every item they end before.  Same arguments, alignment and
+ * errors as fpsched_evaluate; workspace: fpsched_workspace_bytes(p, n_cand, 0) (DEVICE, 16-byte
+ * aligned).  FPSCHED_EINVAL without split backward; FPSCHED_EUNSUPPORTED without the slot
+ * tables or while costs per micro-batch, link occupancy, synchronisation stages or the copy
+ * engine are set.  Asynchronous on hip_stream. */
+int fpsched_wslide_evaluate(const fpsched_problem *p, const uint16_t *d_ops, int64_t n_cand,
+                            int32_t stride_words, fpsched_results out, void *d_workspace,
+                            size_t workspace_bytes, void *hip_stream);
+
 /* Pareto front of (makespan, largest peak[d]) over the candidates that completed (neither
  * DEADLOCK nor INCOMPLETE; OVER_CAP is ignored: the front takes the place of a fixed cap).
  * The paper gives a schedule two properties, bubble ratio (Section 7.1) and memory footprint

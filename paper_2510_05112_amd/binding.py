@@ -91,6 +91,8 @@ def load_library():
         lib.fpsched_wslide_workspace_bytes.argtypes = [vp, i64, i32]
         lib.fpsched_wslide.restype = ctypes.c_int
         lib.fpsched_wslide.argtypes = [vp, vp, i64, i32, vp, i32, _Results, vp, ctypes.c_size_t, vp]
+        lib.fpsched_wslide_evaluate.restype = ctypes.c_int
+        lib.fpsched_wslide_evaluate.argtypes = [vp, vp, i64, i32, _Results, vp, ctypes.c_size_t, vp]
         lib.fpsched_pareto_workspace_bytes.restype = ctypes.c_size_t
         lib.fpsched_pareto_workspace_bytes.argtypes = [vp, i64]
         lib.fpsched_pareto.restype = ctypes.c_int
@@ -460,6 +462,29 @@ class Problem:
                                            self._stream(stream))
         if rc != 0:
             raise FpschedError(rc, "fpsched_wslide")
+        return out
+
+    def wslide_evaluate(self, ops, out=None, workspace=None, stream=None):
+        """The evaluation of the lists ``wslide`` would write for ``ops``, without the lists (see
+        fpsched_wslide_evaluate).  Returns dict(makespan, idle, peak, flags).  Asynchronous."""
+        import torch
+        if self.device is None:
+            raise FpschedError(-5, "fpsched_wslide_evaluate")
+        assert ops.is_cuda and ops.is_contiguous() and ops.dim() == 3 and ops.shape[1] == self.D
+        assert ops.dtype in (torch.int16, torch.uint16)
+        n, _, stride = ops.shape
+        dev = torch.device("cuda", self.device)
+        if out is None:
+            out = dict(makespan=torch.empty(n, dtype=torch.int64, device=dev),
+                       idle=torch.empty((n, self.D), dtype=torch.int64, device=dev),
+                       peak=torch.empty((n, self.D), dtype=torch.int32, device=dev),
+                       flags=torch.empty(n, dtype=torch.uint8, device=dev))
+        if workspace is None:
+            workspace = torch.empty(256, dtype=torch.uint8, device=dev)
+        rc = load_library().fpsched_wslide_evaluate(self._h, ops.data_ptr(), n, int(stride), self._res_struct(out),
+                                                    workspace.data_ptr(), workspace.numel(), self._stream(stream))
+        if rc != 0:
+            raise FpschedError(rc, "fpsched_wslide_evaluate")
         return out
 
     def pareto(self, results, kmax: int, stream=None):

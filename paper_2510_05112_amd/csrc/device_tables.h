@@ -106,6 +106,8 @@ struct SlotTables {
                             // link word (link index * 256)
   int32_t copy_depth;       // copy-engine form: transfers the engine holds at most (1..7), else 0; link_words is
                             // then the number of ring dwords per lane behind its state words
+  int32_t off_w;            // in ints; sliding form: per device [lanes_per_cand][2 * kMaxChunks + 1]: cost << 8 of the
+                            // W item of each chunk, the units it frees, then (cost << 8 of all W items of the device)
   uint32_t mb_kind_map;     // four bits per kind: which block of the table at off_mb holds the kind's costs
                             // (kinds with the same costs share a block)
   const int32_t* ints;      // DEVICE

@@ -151,6 +151,15 @@ __global__ void reset_counter_kernel(unsigned long long* counter, unsigned long 
 // its micro-batches.  Its state nibble is indexed by the item, its slots by the micro-batches.  (The host only
 // selects this form when the neighbours of such a stage have one item per micro-batch.)  A pair (F, a) -> (F, b) or
 // (B, a) -> (B, b) is an edge of its own slot class in one direction only.
+//
+// MODE kSlotSlide: the weight-gradient sliding pass (Section 5.2, bubble optimizations) when only the results of
+// the new lists are wanted.  The tables are those of kSlotTimes (a W word of the input is a no-op), so every item
+// starts when it would start without any W item; a B item that issues stashes its W item, and in front of every
+// item the lane runs the oldest stashed items that end before the item starts (only the oldest is tried).  Of the
+// stash a lane needs nothing but the chunks of its entries, oldest first: a queue of log2(V) bits per entry in one
+// register (entries that find no room stay in the row and are read back from there, at the next top-up, when the
+// queue has run empty).  What is still stashed when a list ends runs back to back behind it: a device's last finish time is
+// its free time plus the cost of the W items it has not placed.
 template <int V, bool DEG2, bool ONE_CLASS, int MODE>
 __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     SlotTables T, const uint16_t* __restrict__ ops, long long n_cand, int stride,
@@ -165,6 +174,12 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   constexpr bool LINKS = MODE == kSlotLinks || MODE == kSlotTimesLinks || MODE == kSlotPerMicrobatchLdsLinks;
   constexpr bool COPY = MODE == kSlotCopy;
   constexpr bool SYNC = MODE == kSlotSync;
+  constexpr bool SLIDE = MODE == kSlotSlide;
+  constexpr bool W_NOOP = TIMES || SLIDE;   // the tables describe the lists without their W items
+  // SLIDE: bits per queue entry, entries the queue holds
+  constexpr unsigned kQBits = V == 1 ? 0u : (V == 2 ? 1u : 2u);
+  constexpr unsigned kQCap = V == 1 ? 0x7fffffffu : 32u / (kQBits ? kQBits : 1u);
+  constexpr unsigned kRefillStall = 0x100u;   // value of `dead` while a lane waits for its queue to be read back
   extern __shared__ int32_t lds[];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int m = T.m;
@@ -186,9 +201,9 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   const int lane_words = T.state_words + (LINKS || COPY ? T.link_words : 0);   // state words, then link words / rings
   uint32_t* slots = stt + lane_words * 64;
   const int slots_per_cand = T.slots_per_cand;  // backward, forward, dump; a multiple of 8
-  // TIMES: one dword behind the last wavefront's region stays zero; it is the state word of W words
+  // TIMES, SLIDE: one dword behind the last wavefront's region stays zero; it is the state word of W words
   const unsigned zero_off = shared_bytes + (blockDim.x >> 6) * (kRing * 128u + rest_ints * 4u);
-  if (TIMES && tid == 0) *reinterpret_cast<uint32_t*>(L + zero_off) = 0u;
+  if (W_NOOP && tid == 0) *reinterpret_cast<uint32_t*>(L + zero_off) = 0u;
   __syncthreads();
 
   const int seg = lane >> lpc_shift;
@@ -283,6 +298,9 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   // word behind it (a lane that issues the op at position k reads the word at k + 2).
   unsigned at_state = stt_off, at_slot = slot_base, at_in = slot_base, at_in2 = slot_base;
   int4 M = make_int4(0, 0, 15, 0);   // metadata row of the current word (an invalid row to begin with)
+  // (SLIDE: the row as one 16-byte value from its load to the decision, so that it stays in the four registers
+  // it was loaded into and nothing waits for the load before the next round's reads are out)
+  lds_int4 M_row = {0, 0, 15, 0};
   int2 M2 = make_int2(0, 0);         // its second-edge row
   unsigned w_next = 0u;              // the word behind the current one
   // SYNC: the item under the cursor: position of its state nibble, values of its group still to arrive (1: the
@@ -305,6 +323,32 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       ++ev_head;
       next_ev8 = ev_head != ev_tail ? lds_read<uint32_t>(ring_ev_time + ((ev_head & 7u) << 8)) : 0xffffffffu;
     }
+  };
+  // SLIDE: the stash as a queue of chunk indices (oldest entry in the low bits), its length, the cost << 8 of the
+  // W items placed so far; whether B items found no room, and from which row position on they are still in the row;
+  // the chunk of the current word (what a B word stashes when it issues)
+  unsigned q_bits = 0u, q_n = 0u, w_placed8 = 0u, cur_push = 0u;
+  unsigned q_over = 0u;   // 1: B items found no room
+  int q_refill_at = 0;
+  int w_dur8[V], w_free[V];
+  unsigned w_total8 = 0u;
+#pragma unroll
+  for (int c = 0; c < V; ++c) {
+    w_dur8[c] = SLIDE ? T.ints[T.off_w + dd * (2 * kMaxChunks + 1) + c] : 0;
+    w_free[c] = SLIDE ? T.ints[T.off_w + dd * (2 * kMaxChunks + 1) + kMaxChunks + c] : 0;
+    if (SLIDE) asm volatile("" : "+v"(w_dur8[c]), "+v"(w_free[c]));
+  }
+  if (SLIDE) {
+    w_total8 = (unsigned)T.ints[T.off_w + dd * (2 * kMaxChunks + 1) + 2 * kMaxChunks];
+    asm volatile("" : "+v"(w_total8));
+  }
+  // cost << 8 of the oldest stashed item (all ones: the queue is empty) and the units it frees
+  unsigned q_head_dur8 = 0xffffffffu;
+  int q_head_free = 0;
+  auto new_head = [&]() {
+    const unsigned head = V > 1 ? q_bits & (unsigned)(V - 1) : 0u;
+    q_head_dur8 = q_n != 0u ? (unsigned)pick<V>(w_dur8, head) : 0xffffffffu;
+    q_head_free = pick<V>(w_free, head);
   };
   int dur_mb8 = 0;                   // MBDUR: cost << 8 of the current word
   const unsigned mb_lane = (unsigned)d * (unsigned)m;   // this device's part of a row of mb_rows
@@ -338,7 +382,8 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     const unsigned group_items = SYNC ? (unsigned)pick<V>(grp, c5 & (unsigned)(V - 1)) : 0u;
     const unsigned jc = min(j, (SYNC ? max(group_items >> 16, 1u) : (unsigned)m) - 1u);
     // a micro-batch out of range reads row 0 (kind 0), which is invalid and never issues
-    M = lds_read<int4>(__umul24(j == jc ? c5 : 0u, row_bytes) + meta_off);
+    if (SLIDE) M_row = *reinterpret_cast<const FPSCHED_LDS lds_int4*>(__umul24(j == jc ? c5 : 0u, row_bytes) + meta_off);
+    else M = lds_read<int4>(__umul24(j == jc ? c5 : 0u, row_bytes) + meta_off);
     // (c5 < 32, d < lanes per candidate, jc < m: inside the table whatever the word holds)
     if (MBDUR) dur_mb8 = mb_rows[__umul24(c5, mb_row_ints) + mb_lane + jc];
     unsigned c = c5 & (unsigned)(V - 1);
@@ -356,7 +401,8 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       if (mb_wide) dur_mb16 = lds_read<uint16_t>(at_row + (jc << 1));
       else dur_mb16 = lds_read<uint8_t>(at_row + jc);
     }
-    if (TIMES) at_state = (word >> 13) == (unsigned)kW ? lds0 + zero_off : at_state;
+    if (W_NOOP) at_state = (word >> 13) == (unsigned)kW ? lds0 + zero_off : at_state;
+    if (SLIDE) cur_push = c;
     unsigned j_first = jc;
     if (SYNC) {
       const unsigned n = max(group_items & 0xffffu, 1u);
@@ -393,7 +439,8 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   // Every candidate ends after at most D * stride + 2 rounds (each round but its last issues at
   // least one of its at most D * stride ops), so the bound below is never reached; it only makes
   // sure the wavefront leaves the loop whatever happens.
-  const unsigned long long per_cand_rounds = (unsigned long long)T.D * (unsigned)stride + 8ull;
+  // (SLIDE: a lane may wait a few rounds for its queue to be read back, once per kQCap items at most)
+  const unsigned long long per_cand_rounds = (unsigned long long)T.D * (unsigned)stride * (SLIDE ? 2ull : 1ull) + 8ull;
   // (a segment cannot draw more than all candidates; fast segments draw more than their share)
   const unsigned long long my_cands = (unsigned long long)n_cand + 1ull;
   const unsigned long long bound = per_cand_rounds * my_cands;
@@ -411,6 +458,26 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   bool priming = false;      // the segment has requested the head of its rows and waits for the top-up
   const int prime_words = stride < kPrimeChunks * kChunk ? stride : kPrimeChunks * kChunk;
   for (unsigned round = 0; round < max_rounds; round += kSyncRounds) {
+    if (SLIDE) {
+      // ---- queues that ran empty while B items wait in the row are read back from there, up to the cursor
+      const bool stalled = dead == kRefillStall;
+      if (__ballot(stalled) != 0ull && stalled) {
+        int at = q_refill_at;
+        const int cursor = (int)(npos >> 7) - 1;
+        while (at < cursor && q_n < kQCap) {
+          const unsigned b_word = row[at];
+          if ((b_word >> 13) == (unsigned)kB) {
+            q_bits |= ((b_word >> 11) & (unsigned)(V - 1)) << (q_n * kQBits);
+            ++q_n;
+          }
+          ++at;
+        }
+        q_refill_at = at;
+        q_over = at < cursor ? 1u : 0u;
+        new_head();
+        dead = 0u;
+      }
+    }
     // ---- wave-wide top-up of the op windows.  Loads requested at the previous top-up are landed
     // now, four rounds later, so nobody waits for HBM.
     if (has_pend) {
@@ -483,6 +550,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
         dead = ~0u;
         npos = 128u; free_at8 = 0; busy8 = 0; mem = 0; pk = 0;
         copy_free8 = 0u; n_copy = 0u; ev_head = 0u; ev_tail = 0u; next_ev8 = 0xffffffffu;
+        q_bits = 0u; q_n = 0u; w_placed8 = 0u; cur_push = 0u; q_over = 0u; q_refill_at = 0; q_head_dur8 = 0xffffffffu;
         has_pend = false;
         loaded = 0;
         if (running) {
@@ -528,7 +596,12 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     }
     // keep every load of the round in front of the decision (one LDS round trip per round)
     // (the metadata row was requested when the lane last issued; nothing may wait for it earlier)
-    asm volatile("" : "+v"(sx), "+v"(in1), "+v"(M.x), "+v"(M.y), "+v"(M.z), "+v"(M.w));
+    if (SLIDE) {
+      asm volatile("" : "+v"(sx), "+v"(in1), "+v"(M_row));
+      M = make_int4(M_row.x, M_row.y, M_row.z, M_row.w);
+    } else {
+      asm volatile("" : "+v"(sx), "+v"(in1), "+v"(M.x), "+v"(M.y), "+v"(M.z), "+v"(M.w));
+    }
     // ---- decide.  An exhausted lane sits on a word of kind 0, whose metadata row is invalid; invalid
     // rows require state 15, which no activation is ever in.  Lanes without a device (and idle
     // segments) never initialise their LDS words, so they are masked off explicitly.
@@ -602,8 +675,28 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       npos += 128u;
       w_next = lds_read<uint16_t>((npos & ((kRing - 1) << 7)) | win_off);
     }
-    if (ok && !transfer) {
-      unsigned start8 = max(free_at8, ready8);
+    // SLIDE: in front of the item, the oldest stashed W items that end before it starts (the item's start does not
+    // move: it is the later of its inputs and the device's free time without any W item, and the W items end
+    // before it).  A queue that runs empty while B items wait in the row is read back at the next top-up: the
+    // device keeps the time it has reached and does nothing until then.
+    // (the later of the device's free time and the inputs; placing W items in front does not change it)
+    const unsigned first8 = max(free_at8, ready8);
+    if (SLIDE && ok) {
+      if (q_head_dur8 <= first8 - free_at8) {
+        const unsigned before8 = free_at8;
+        do {
+          free_at8 += q_head_dur8;
+          mem -= q_head_free;
+          q_bits >>= kQBits;
+          --q_n;
+          new_head();
+        } while (q_head_dur8 <= first8 - free_at8);
+        w_placed8 += free_at8 - before8;
+        if (q_over > q_n) dead = kRefillStall;   // empty, and B items wait in the row
+      }
+    }
+    if (ok && !transfer && (!SLIDE || dead == 0u)) {
+      unsigned start8 = first8;
       if (COPY && cur_kind == (unsigned)kB && ((sx >> (bj & 31u)) & 8u) != 0u) {
         // the activation was reloaded: if that transfer is among the last copy_depth ones it may still run
         // (all eight places of the ring are looked at, in one round trip: a transfer further back than
@@ -682,6 +775,18 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       }
       free_at8 = fin8;
       busy8 += dur8;
+      // (B is the only kind that takes an activation from resident to backward-done)
+      if (SLIDE && ((mx_ >> 8) & 0xffu) == (unsigned)(kRes ^ kBDone)) {
+        // a B item stashes its W item (once the queue has overflowed, later ones stay in the row)
+        if (q_n + (q_over << 6) < kQCap) {
+          q_bits |= cur_push << (q_n * kQBits);
+          ++q_n;
+          new_head();
+        } else if (q_over == 0u) {
+          q_over = 1u;
+          q_refill_at = (int)(npos >> 7) - 1;
+        }
+      }
       decode(w_next);
       npos += 128u;
       w_next = lds_read<uint16_t>((npos & ((kRing - 1) << 7)) | win_off);
@@ -691,6 +796,8 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     // the top-up looks.  Cheap scalar pre-test: does the issue mask, with the fields of idle
     // segments filled, contain an all-zero field of lpc bits?  (x - lows) & ~x & highs is non-zero
     // iff some field of x is zero.
+    // (SLIDE: a device that waits for its queue to be read back is not finished)
+    if (SLIDE && sub == kSyncRounds - 1) gathered = __ballot(dead == kRefillStall);
     const unsigned long long x = moved | gathered | idle_fields;
     if (sub == kSyncRounds - 1 && (((x - base_bits) & ~x) & high_bits) != 0ull) {
       // fold the issue mask onto the segments' base bits to find which segments ended
@@ -718,7 +825,8 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
       const unsigned long long stuck_bad = __ballot(bad_head) & seg_mask;
       const unsigned long long unfinished = __ballot(incomplete) & seg_mask;
       const unsigned long long over = __ballot(lane_ok && pk > cap) & seg_mask;
-      int ms = lane_ok ? (int)((COPY ? max(free_at8, copy_free8) : free_at8) >> 8) : 0;
+      // (SLIDE: what is still stashed runs back to back behind the list)
+      int ms = lane_ok ? (int)((COPY ? max(free_at8, copy_free8) : SLIDE ? free_at8 + (w_total8 - w_placed8) : free_at8) >> 8) : 0;
       for (int off = 1; off < lpc; off <<= 1) ms = max(ms, __shfl_xor(ms, off, 64));
       if (seg_ended) {
         unsigned flg = 0;
@@ -745,7 +853,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
           }
         } else if (lane_ok) {
           const bool failed = (flg & (kDeadlock | kIncomplete)) != 0;
-          out_idle[cand * T.D + d] = failed ? -1ll : (long long)(ms - (int)(busy8 >> 8));
+          out_idle[cand * T.D + d] = failed ? -1ll : (long long)(ms - (int)((busy8 + (SLIDE ? w_total8 : 0u)) >> 8));
           out_peak[cand * T.D + d] = failed ? -1 : pk * T.unit_scale;
           if (d == 0) {
             out_makespan[cand] = failed ? 0x7fffffffffffffffll : (long long)ms;
@@ -779,7 +887,8 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotTimesLinks)       \
   FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotPerMicrobatchLdsLinks) \
   FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotCopy) \
-  FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotSync)
+  FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotSync) \
+  FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotSlide)
 FPSCHED_INSTANTIATE(1, false, true)
 FPSCHED_INSTANTIATE(2, false, true)
 FPSCHED_INSTANTIATE(4, false, true)

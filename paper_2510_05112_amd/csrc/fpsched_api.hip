@@ -39,6 +39,9 @@ struct fpsched_problem {
   bool slide_ok = false;           // the sliding pass is available (split backward, slot tables)
   SlotTables stab_times{};         // the slot tables of the lists without their W items
   int32_t* d_times_ints = nullptr;
+  bool slide_eval_ok = false;      // the one-kernel form of the sliding pass (results only) is available
+  SlotTables stab_slide{};         // stab_times plus the costs of the W items
+  int32_t* d_slide_ints = nullptr;
   SlotTables stab{};
   std::vector<int32_t> slot_ints;
   int32_t* d_slot_ints = nullptr;
@@ -580,6 +583,34 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
         if (up) {
           p->stab_times.ints = p->d_times_ints;
           p->slide_ok = true;
+          // the one-kernel form: the same image, and behind it per device the cost << 8 of the W item of each
+          // chunk, the units it frees, and the cost << 8 of all W items of the device
+          std::vector<int32_t> JS = J;
+          const int32_t off_w = (int32_t)JS.size();
+          JS.resize(JS.size() + (size_t)lpc * (2 * kMaxChunks + 1), 0);
+          for (int d = 0; d < D; ++d) {
+            int32_t* w = &JS[(size_t)off_w + (size_t)d * (2 * kMaxChunks + 1)];
+            int64_t total = 0;
+            for (int c = 0; c < p->n_chunks[d]; ++c) {
+              const int s = p->local_stage[(size_t)d * kMaxChunks + c];
+              w[c] = (int32_t)((unsigned)desc->dur[kW * S + s] << 8);
+              w[kMaxChunks + c] = (int32_t)(desc->mem_units[s] / p->stab.unit_scale);
+              total += (int64_t)m * desc->dur[kW * S + s];
+            }
+            w[2 * kMaxChunks] = (int32_t)((uint32_t)total << 8);   // (below 2^24: the slot form's bound on all times)
+          }
+          if (hipMalloc(&p->d_slide_ints, JS.size() * sizeof(int32_t)) == hipSuccess &&
+              hipMemcpy(p->d_slide_ints, JS.data(), JS.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess &&
+              hipFuncSetAttribute(reinterpret_cast<const void*>(slot_kernel_of<kSlotSlide>(p->slot_v, p->slot_deg2, p->stab.n_classes == 1)),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, p->max_lds) == hipSuccess) {
+            p->stab_slide = p->stab_times;
+            p->stab_slide.ints = p->d_slide_ints;
+            p->stab_slide.off_w = off_w;
+            p->slide_eval_ok = true;
+          } else {
+            (void)hipGetLastError();
+            if (p->d_slide_ints) { (void)hipFree(p->d_slide_ints); p->d_slide_ints = nullptr; }
+          }
         } else {
           (void)hipGetLastError();
           if (p->d_times_ints) { (void)hipFree(p->d_times_ints); p->d_times_ints = nullptr; }
@@ -591,6 +622,8 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
       if (p->d_slot_ints) (void)hipFree(p->d_slot_ints);
     if (p->d_sync_slot_image) (void)hipFree(p->d_sync_slot_image);
       if (p->d_times_ints) (void)hipFree(p->d_times_ints);
+    if (p->d_slide_ints) (void)hipFree(p->d_slide_ints);
+      if (p->d_slide_ints) (void)hipFree(p->d_slide_ints);
       delete p;
       return FPSCHED_EHIP;
     }
@@ -1739,6 +1772,37 @@ int fpsched_wslide(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_ca
                      starts, escapes, escape_cap, stops, timed_flags, d_ops_out, (int)stride_out_words,
                      reinterpret_cast<long long*>(out.makespan), reinterpret_cast<long long*>(out.idle), out.peak,
                      out.flags);
+  return check_hip(hipGetLastError());
+}
+
+int fpsched_wslide_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_cand, int32_t stride_words,
+                            fpsched_results out, void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!p || n_cand < 0) return FPSCHED_EINVAL;
+  if (p->device_id < 0) return FPSCHED_ENODEV;
+  if (!p->has_w) return FPSCHED_EINVAL;
+  if (!p->slide_eval_ok || p->mb_set || p->sync_on || p->copy_depth > 0 || p->links_on) return FPSCHED_EUNSUPPORTED;
+  if (n_cand == 0) return FPSCHED_OK;
+  if (!d_ops || !out.makespan || !out.idle || !out.peak || !out.flags) return FPSCHED_EINVAL;
+  if (stride_words < 8 || (stride_words & 7) || stride_words > p->max_stride) return FPSCHED_EINVAL;
+  if (reinterpret_cast<uintptr_t>(d_ops) & 15) return FPSCHED_EINVAL;
+  if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) & 15)) return FPSCHED_EINVAL;
+  if (workspace_bytes < 256) return FPSCHED_ENOMEM;
+  DeviceGuard g(p->device_id);
+  if (!g.ok) return FPSCHED_EHIP;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  unsigned long long* counter = static_cast<unsigned long long*>(d_workspace);
+  // launched as fpsched_evaluate launches the plain form (same workgroup shape; 16 bytes of LDS more)
+  const SlotTables& tab = p->stab_slide;
+  const int per_block = tab.cands_per_wave * p->slot_waves;
+  const int64_t blocks = std::min<int64_t>((n_cand + per_block - 1) / per_block, p->slot_grid);
+  const int64_t row_words = (int64_t)p->D * stride_words;
+  const int draw_block = (int)std::clamp<int64_t>((12288 + row_words - 1) / row_words, 1, tab.cands_per_wave);
+  hipLaunchKernelGGL(reset_counter_kernel, dim3(1), dim3(64), 0, st, counter, (unsigned long long)(blocks * per_block));
+  hipLaunchKernelGGL(slot_kernel_of<kSlotSlide>(p->slot_v, p->slot_deg2, tab.n_classes == 1), dim3((unsigned)blocks),
+                     dim3(64 * p->slot_waves), (size_t)p->slot_lds_bytes + 16, st, tab, d_ops, (long long)n_cand,
+                     (int)stride_words, reinterpret_cast<long long*>(out.makespan), reinterpret_cast<long long*>(out.idle),
+                     out.peak, out.flags, counter, draw_block, (uint32_t*)nullptr, (int32_t*)nullptr,
+                     (const int32_t*)nullptr, (uint32_t*)nullptr, 0);
   return check_hip(hipGetLastError());
 }
 

@@ -53,8 +53,10 @@ constexpr int kSlotMaxThreads = 64 * kSlotMaxWaves;
 // MODE kSlotSync: synchronisation stages (one item per group of micro-batches) and dependency pairs of the
 // forms the mail slots can carry (forward to forward, backward to backward); the dev rows then have V more ints:
 // per chunk the micro-batches per item | items << 16.
+// MODE kSlotSlide: the weight-gradient sliding pass without its lists: the results of the lists the two-pass form
+// would write, in one kernel (tables as for kSlotTimes plus the W items' costs at T.off_w; 16 bytes of LDS more).
 constexpr int kSlotPlain = 0, kSlotTimes = 1, kSlotPerMicrobatch = 2, kSlotPerMicrobatchLds = 3, kSlotLinks = 4,
-              kSlotTimesLinks = 5, kSlotPerMicrobatchLdsLinks = 6, kSlotCopy = 7, kSlotSync = 8;
+              kSlotTimesLinks = 5, kSlotPerMicrobatchLdsLinks = 6, kSlotCopy = 7, kSlotSync = 8, kSlotSlide = 9;
 constexpr int kSlotCopyWords = 32;
 template <int V, bool DEG2, bool ONE_CLASS, int MODE>
 __global__ void eval_slot_kernel(SlotTables T, const uint16_t* ops, long long n_cand, int stride,

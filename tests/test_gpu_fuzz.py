@@ -112,6 +112,12 @@ def test_random_problems_sliding(seed):
             assert np.array_equal(out["ops"].cpu().numpy().view(np.uint16), ref["ops"]), what
             for name in ("makespan", "idle", "peak", "flags"):
                 assert np.array_equal(out[name].cpu().numpy(), ref[name]), (what, name)
+        # the one-kernel form without lists
+        only = h.wslide_evaluate(torch.from_numpy(words.view(np.int16)).cuda())
+        torch.cuda.synchronize()
+        ref = oracle.wslide(prob, words, stride + 8, threads=4)
+        for name in ("makespan", "idle", "peak", "flags"):
+            assert np.array_equal(only[name].cpu().numpy(), ref[name]), (f"seed {seed} problem {done} no lists", name)
         h.close()
         done += 1
 

@@ -24,7 +24,8 @@ def test_library_loads_and_exports_every_declared_symbol():
             "fpsched_workspace_bytes", "fpsched_encode", "fpsched_validate", "fpsched_strerror",
             "fpsched_version", "fpsched_problem_info", "fpsched_generate",
             "fpsched_problem_select_kernel", "fpsched_rank", "fpsched_rank_workspace_bytes",
-            "fpsched_pareto", "fpsched_pareto_workspace_bytes", "fpsched_apply_caps", "fpsched_wslide", "fpsched_wslide_workspace_bytes"} <= names
+            "fpsched_pareto", "fpsched_pareto_workspace_bytes", "fpsched_apply_caps", "fpsched_wslide", "fpsched_wslide_workspace_bytes",
+            "fpsched_wslide_evaluate"} <= names
     for n in names:
         assert hasattr(lib, n), n
     assert fp.version() == 100
@@ -53,12 +54,14 @@ def test_host_only_handle_and_errors():
     assert lib.fpsched_pareto(p._h, none, 1, 1, 1, 1, 1, 1, 0, 0, 0) == -5
     assert lib.fpsched_apply_caps(p._h, 0, 1, 0, 1, 0, 0) == -5
     assert lib.fpsched_wslide(p._h, 0, 1, spec.stride, 0, spec.stride, none, 0, 0, 0) == -5
+    assert lib.fpsched_wslide_evaluate(p._h, 0, 1, spec.stride, none, 0, 0, 0) == -5
     # the workspace sizes are host arithmetic and work without a device
     assert lib.fpsched_wslide_workspace_bytes(p._h, 100, spec.stride) >= 256 + 100 * 8 * spec.stride * 2 + 100 * 8 * 4 + 100
     assert lib.fpsched_pareto_workspace_bytes(p._h, 5000) >= 3 * 2048 * 20
     assert lib.fpsched_rank_workspace_bytes(p._h, 5000, 16) >= lib.fpsched_workspace_bytes(p._h, 5000, 16) + 5000 * 9
     # null handle and nonsense sizes
     assert lib.fpsched_wslide(None, 0, 1, 8, 0, 8, none, 0, 0, 0) == -1
+    assert lib.fpsched_wslide_evaluate(None, 0, 1, 8, none, 0, 0, 0) == -1
     assert lib.fpsched_pareto(p._h, none, 1, 0, 1, 1, 1, 1, 0, 0, 0) == -1
     assert lib.fpsched_topk(p._h, none, 1, 2000, 1, 1, 1, 0, 0, 0) == -1
     assert lib.fpsched_pareto(p._h, none, (1 << 24) + 1, 4, 1, 1, 1, 1, 1, 1 << 40, 0) == -1   # more tiles than cursors
