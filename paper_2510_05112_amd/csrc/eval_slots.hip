@@ -298,8 +298,11 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   // word behind it (a lane that issues the op at position k reads the word at k + 2).
   unsigned at_state = stt_off, at_slot = slot_base, at_in = slot_base, at_in2 = slot_base;
   int4 M = make_int4(0, 0, 15, 0);   // metadata row of the current word (an invalid row to begin with)
-  // (SLIDE: the row as one 16-byte value from its load to the decision, so that it stays in the four registers
-  // it was loaded into and nothing waits for the load before the next round's reads are out)
+  // (SLIDE, SYNC: the row as one 16-byte value from its load to the decision, so that it stays in the four
+  // registers it was loaded into; as four separate values the register allocator copies some of them right behind
+  // the load, which puts a wait for that load in front of the next round's reads.  The other modes measured the
+  // same or slightly worse with it.)
+  constexpr bool ROW16 = SLIDE || SYNC;
   lds_int4 M_row = {0, 0, 15, 0};
   int2 M2 = make_int2(0, 0);         // its second-edge row
   unsigned w_next = 0u;              // the word behind the current one
@@ -382,7 +385,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     const unsigned group_items = SYNC ? (unsigned)pick<V>(grp, c5 & (unsigned)(V - 1)) : 0u;
     const unsigned jc = min(j, (SYNC ? max(group_items >> 16, 1u) : (unsigned)m) - 1u);
     // a micro-batch out of range reads row 0 (kind 0), which is invalid and never issues
-    if (SLIDE) M_row = *reinterpret_cast<const FPSCHED_LDS lds_int4*>(__umul24(j == jc ? c5 : 0u, row_bytes) + meta_off);
+    if (ROW16) M_row = *reinterpret_cast<const FPSCHED_LDS lds_int4*>(__umul24(j == jc ? c5 : 0u, row_bytes) + meta_off);
     else M = lds_read<int4>(__umul24(j == jc ? c5 : 0u, row_bytes) + meta_off);
     // (c5 < 32, d < lanes per candidate, jc < m: inside the table whatever the word holds)
     if (MBDUR) dur_mb8 = mb_rows[__umul24(c5, mb_row_ints) + mb_lane + jc];
@@ -596,7 +599,7 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
     }
     // keep every load of the round in front of the decision (one LDS round trip per round)
     // (the metadata row was requested when the lane last issued; nothing may wait for it earlier)
-    if (SLIDE) {
+    if (ROW16) {
       asm volatile("" : "+v"(sx), "+v"(in1), "+v"(M_row));
       M = make_int4(M_row.x, M_row.y, M_row.z, M_row.w);
     } else {
