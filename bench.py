@@ -59,12 +59,12 @@ MEASURED_SYNC_TABLE = {("sync4", 65536): {"traffic_bytes": None, "valu_wave_inst
                                          "valu_per_wave_round": None, "profile_kernel_ms": 7.12,
                                          "profile": "profiles/eval_sync_kernel.md"}}
 # one generator launch (--mode generate): WRITE_SIZE x 1024 plus the parameter sets read
-MEASURED_GENERATE = {("cfg4", 65536): {"traffic_bytes": 4.82e9, "valu_wave_instructions": 9.509e9,
-                                       "valu_per_wave_round": None, "profile_kernel_ms": 17.49,
+MEASURED_GENERATE = {("cfg4", 65536): {"traffic_bytes": 4.83e9, "valu_wave_instructions": 7.945e9,
+                                       "valu_per_wave_round": None, "profile_kernel_ms": 14.67,
                                        "profile": "profiles/generate_kernel_cfg4.md"}}
 # generator and evaluator in one kernel (--mode search --fused)
-MEASURED_FUSED = {("cfg4", 65536): {"traffic_bytes": None, "valu_wave_instructions": 8.916e9,
-                                    "valu_per_wave_round": None, "profile_kernel_ms": 16.77,
+MEASURED_FUSED = {("cfg4", 65536): {"traffic_bytes": None, "valu_wave_instructions": 7.821e9,
+                                    "valu_per_wave_round": None, "profile_kernel_ms": 14.46,
                                     "profile": "profiles/generate_kernel_cfg4.md"}}
 # the sliding pass (--mode wslide), both of its kernels
 MEASURED_WSLIDE = {("cfg4", 65536): {"traffic_bytes": 4.06e10, "valu_wave_instructions": 5.89e9,

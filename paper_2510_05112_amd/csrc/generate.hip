@@ -170,6 +170,8 @@ __global__ __launch_bounds__(TIMED ? kGenTimedThreads : 64) void generate_kernel
   int status = 0, len = 0;
   unsigned long long first_step = 0ull;   // the loop's step counter when the set's process began
   int steps = 0;
+  int last_pick = -1;   // the step, counted from first_step, in which this actor scheduled its last item so far
+  constexpr unsigned long long kEndCheckMask = 7ull;
   uint16_t* row = ops;
   // "does any lane of my segment ...": the ballot against the lanes of the segment
   const unsigned long long seg_lanes = (lpc == 64 ? ~0ull : ((1ull << lpc) - 1ull)) << (seg * lpc);
@@ -183,7 +185,7 @@ __global__ __launch_bounds__(TIMED ? kGenTimedThreads : 64) void generate_kernel
   // wavefront leaves the loop whatever happens.  A workgroup is one wavefront: its LDS instructions
   // execute in program order, so the reads of a step see the counters as the previous step left them
   // and no barrier is needed between the phases.
-  const unsigned long long per_set = 3ull * (unsigned)S * (unsigned)m + 4ull;
+  const unsigned long long per_set = 3ull * (unsigned)S * (unsigned)m + 16ull;
   const unsigned long long bound = per_set * ((unsigned long long)n_sets + 1ull);
   for (unsigned long long step = 0; step < bound; ++step) {
     if (__ballot(fresh) != 0ull) {
@@ -266,7 +268,7 @@ __global__ __launch_bounds__(TIMED ? kGenTimedThreads : 64) void generate_kernel
         stepped_f = 0; stepped_b = 0;
         left = (has_row && !set_bad) ? nch * m * (has_w ? 3 : 2) : 0;
         live = any_in_segment(__ballot(left > 0));
-        first_step = step; steps = 0;
+        first_step = step; steps = 0; last_pick = -1;
         status = set_bad ? 4 : 0; len = 0;
         free_at = 0; mem = 0; peak = 0;
         if (!TIMED) row = ops + (size_t)(has_row ? set * D + d : 0) * (size_t)stride;
@@ -394,6 +396,7 @@ __global__ __launch_bounds__(TIMED ? kGenTimedThreads : 64) void generate_kernel
       for (int c = 1; c < V; ++c) at = pick_c == c ? own_at[c] : at;
       const int j = atomicAdd(&counts[mad24((unsigned)pick_t, (unsigned)S, (unsigned)at)], 1);
       left -= 1;
+      last_pick = (int)(step - first_step);
       if (TIMED) {
         // the item's row: cost, memory, where its inputs' finish times are and where its own goes
         const int4* r = reinterpret_cast<const int4*>(
@@ -425,14 +428,19 @@ __global__ __launch_bounds__(TIMED ? kGenTimedThreads : 64) void generate_kernel
       }
     }
     __builtin_amdgcn_wave_barrier();
-    const bool any_pick = any_in_segment(__ballot(pick_t >= 0));
-    const bool any_left = any_in_segment(__ballot(left > 0));
-    if (live) {
-      const bool stuck = !any_pick;   // items remain and nothing can move
-      live = !stuck && any_left;
-      if (!live) {
-        status = stuck ? 1 : status;
-        steps = (int)(step - first_step) + (stuck ? 0 : 1);
+    // ---- has the set's process ended?  Looked at every eighth step only: a process that has ended stays ended
+    // (when every item is scheduled nothing is eligible any more; when a step schedules nothing although items
+    // remain, no later step can), so the few steps a segment runs on change nothing, and the number of steps the
+    // process took is one more than the step of its last item.
+    if ((step & kEndCheckMask) == kEndCheckMask) {
+      const bool any_pick = any_in_segment(__ballot(pick_t >= 0));
+      const bool any_left = any_in_segment(__ballot(left > 0));
+      if (live && (!any_pick || !any_left)) {
+        int last = last_pick;
+        for (int off = 1; off < lpc; off <<= 1) last = max(last, __shfl_xor(last, off, 64));
+        status = any_left ? 1 : status;   // items remain and nothing can move
+        steps = last + 1;
+        live = false;
         fresh = true;
       }
     }
