@@ -79,8 +79,12 @@ __device__ __forceinline__ void lds_write(unsigned a, T v) {
   *reinterpret_cast<FPSCHED_LDS T*>(a) = v;
 }
 
+// One value per chunk of a device, kept as ONE vector value: as an array of four ints the compiler turns the
+// select chain below into a load with a variable index and puts the array into scratch memory.
 template <int V>
-__device__ __forceinline__ int pick(const int (&a)[V], int c) {
+struct PerChunk { typedef int type __attribute__((ext_vector_type(V))); };
+template <int V>
+__device__ __forceinline__ int pick(typename PerChunk<V>::type a, int c) {
   int r = a[0];
 #pragma unroll
   for (int i = 1; i < V; ++i) r = (c == i) ? a[i] : r;
@@ -217,34 +221,33 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   const int32_t* dev = T.ints + T.off_dev + dd * T.dev_ints;
   const int32_t* expect = T.ints + T.off_expect + dd * T.state_words;
   int cap = dev[1];
-  int cons_f[V], cons_b[V], cons_f2[V], cons_b2[V];
+  typename PerChunk<V>::type cons_f, cons_b, cons_f2, cons_b2;
 #pragma unroll
   for (int c = 0; c < V; ++c) {
-    cons_f[c] = dev[2 + c] << 2;
-    cons_b[c] = dev[2 + V + c] << 2;
-    cons_f2[c] = DEG2 ? dev[2 + 2 * V + c] << 2 : 0;
-    cons_b2[c] = DEG2 ? dev[2 + 3 * V + c] << 2 : 0;
+    int f = dev[2 + c] << 2, b = dev[2 + V + c] << 2;
+    int f2 = DEG2 ? dev[2 + 2 * V + c] << 2 : 0, b2 = DEG2 ? dev[2 + 3 * V + c] << 2 : 0;
     // have the constants in registers before the loop: a wait for them inside the loop would
     // also wait for the op-window prefetch
-    asm volatile("" : "+v"(cons_f[c]), "+v"(cons_b[c]), "+v"(cons_f2[c]), "+v"(cons_b2[c]));
+    asm volatile("" : "+v"(f), "+v"(b), "+v"(f2), "+v"(b2));
+    cons_f[c] = f; cons_b[c] = b; cons_f2[c] = f2; cons_b2[c] = b2;
   }
   asm volatile("" : "+v"(cap));
   // LINKS: per chunk the out-edges as latency << 16 | byte offset of the link word
-  int out_f[V], out_b[V], out_f2[V], out_b2[V];
+  typename PerChunk<V>::type out_f, out_b, out_f2, out_b2;
 #pragma unroll
   for (int c = 0; c < V; ++c) {
-    out_f[c] = LINKS ? dev[2 + 4 * V + c] : 0;
-    out_b[c] = LINKS ? dev[2 + 5 * V + c] : 0;
-    out_f2[c] = LINKS && DEG2 ? dev[2 + 6 * V + c] : 0;
-    out_b2[c] = LINKS && DEG2 ? dev[2 + 7 * V + c] : 0;
-    if (LINKS) asm volatile("" : "+v"(out_f[c]), "+v"(out_b[c]), "+v"(out_f2[c]), "+v"(out_b2[c]));
+    int f = LINKS ? dev[2 + 4 * V + c] : 0, b = LINKS ? dev[2 + 5 * V + c] : 0;
+    int f2 = LINKS && DEG2 ? dev[2 + 6 * V + c] : 0, b2 = LINKS && DEG2 ? dev[2 + 7 * V + c] : 0;
+    if (LINKS) asm volatile("" : "+v"(f), "+v"(b), "+v"(f2), "+v"(b2));
+    out_f[c] = f; out_b[c] = b; out_f2[c] = f2; out_b2[c] = b2;
   }
   // SYNC: per chunk the micro-batches per item (1: an ordinary stage) | items << 16
-  int grp[V];
+  typename PerChunk<V>::type grp;
 #pragma unroll
   for (int c = 0; c < V; ++c) {
-    grp[c] = SYNC ? dev[2 + 4 * V + c] : 0;
-    if (SYNC) asm volatile("" : "+v"(grp[c]));
+    int g = SYNC ? dev[2 + 4 * V + c] : 0;
+    if (SYNC) asm volatile("" : "+v"(g));
+    grp[c] = g;
   }
   const unsigned long long seg_mask =
       (lpc == 64 ? ~0ull : ((1ull << lpc) - 1ull)) << (seg * lpc);
@@ -333,13 +336,14 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   unsigned q_bits = 0u, q_n = 0u, w_placed8 = 0u, cur_push = 0u;
   unsigned q_over = 0u;   // 1: B items found no room
   int q_refill_at = 0;
-  int w_dur8[V], w_free[V];
+  typename PerChunk<V>::type w_dur8, w_free;
   unsigned w_total8 = 0u;
 #pragma unroll
   for (int c = 0; c < V; ++c) {
-    w_dur8[c] = SLIDE ? T.ints[T.off_w + dd * (2 * kMaxChunks + 1) + c] : 0;
-    w_free[c] = SLIDE ? T.ints[T.off_w + dd * (2 * kMaxChunks + 1) + kMaxChunks + c] : 0;
-    if (SLIDE) asm volatile("" : "+v"(w_dur8[c]), "+v"(w_free[c]));
+    int wd = SLIDE ? T.ints[T.off_w + dd * (2 * kMaxChunks + 1) + c] : 0;
+    int wf = SLIDE ? T.ints[T.off_w + dd * (2 * kMaxChunks + 1) + kMaxChunks + c] : 0;
+    if (SLIDE) asm volatile("" : "+v"(wd), "+v"(wf));
+    w_dur8[c] = wd; w_free[c] = wf;
   }
   if (SLIDE) {
     w_total8 = (unsigned)T.ints[T.off_w + dd * (2 * kMaxChunks + 1) + 2 * kMaxChunks];

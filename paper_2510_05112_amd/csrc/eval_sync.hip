@@ -96,8 +96,11 @@ __global__ __launch_bounds__(64) void eval_sync_kernel(
     if (stride > 8) nxt = *reinterpret_cast<const uint4*>(row + 8);
   }
   auto word_at = [&](int k) -> unsigned {   // word k & 7 of `cur`
-    const unsigned pair = (k & 4) ? ((k & 2) ? cur.w : cur.z) : ((k & 2) ? cur.y : cur.x);
-    return (k & 1) ? pair >> 16 : pair & 0xffffu;
+    // (two selects and a 64-bit shift: as a select among the four dwords the compiler moves `cur` to scratch
+    // memory and loads the dword from there)
+    const unsigned lo = (k & 4) ? cur.z : cur.x, hi = (k & 4) ? cur.w : cur.y;
+    const unsigned long long half = ((unsigned long long)hi << 32) | lo;
+    return (unsigned)(half >> ((k & 3) << 4)) & 0xffffu;
   };
 
   int cursor = 0, free_at = 0, busy = 0, mem = 0, pk = 0, n_term = 0;
