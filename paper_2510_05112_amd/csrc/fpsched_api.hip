@@ -156,6 +156,22 @@ SlotKernel slot_kernel_of(int v, bool deg2, bool one_class) {
 }
 SlotKernel slot_kernel_ptr(int v, bool deg2, bool one_class) { return slot_kernel_of<kSlotPlain>(v, deg2, one_class); }
 
+// Launch shape of the slot kernel for a batch: `waves` wavefronts per workgroup and `grid` workgroups fill the
+// chip; a batch too small for that is spread over as many compute units as it has wavefronts' worth of
+// candidates (a wavefront that has a SIMD to itself runs its rounds faster than three that share one), with
+// fewer wavefronts per workgroup and the LDS that goes with them.
+struct SlotLaunch { int waves; int64_t blocks; size_t lds_bytes; };
+static SlotLaunch slot_launch(const SlotTables& tab, int waves, int grid, size_t lds_bytes, int64_t n_cand) {
+  const int64_t cpw = tab.cands_per_wave;
+  const int64_t spread = (n_cand + cpw * grid - 1) / (cpw * grid);   // wavefronts per workgroup that cover the batch
+  const int w = (int)std::clamp<int64_t>(spread, 1, waves);
+  SlotLaunch L;
+  L.waves = w;
+  L.blocks = std::min<int64_t>((n_cand + cpw * w - 1) / (cpw * w), grid);
+  L.lds_bytes = lds_bytes - (size_t)(waves - w) * (size_t)tab.wave_ints * 4u;
+  return L;
+}
+
 // Workgroup shape of the slot kernel for a shared LDS part of n_shared_ints dwords: candidates per
 // wavefront, then the split of a compute unit's LDS into workgroups that keeps the most wavefronts
 // resident (LDS is the only limiter: ~50 VGPRs).  Returns wavefronts per workgroup (0 = does not fit).
@@ -736,8 +752,9 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
     const int grid = sync_on_slots ? p->sync_slot_grid : copy_on_slots ? p->copy_grid : combo ? p->combo_grid : links ? p->links_grid : (mb_lds ? p->mb_grid : p->slot_grid);
     const size_t lds_bytes = (size_t)(sync_on_slots ? p->sync_slot_lds_bytes : copy_on_slots ? p->copy_lds_bytes : combo ? p->combo_lds_bytes : links ? p->links_lds_bytes
                                       : (mb_lds ? p->mb_lds_bytes : p->slot_lds_bytes));
-    const int per_block = tab.cands_per_wave * waves;
-    const int64_t blocks = std::min<int64_t>((n_cand + per_block - 1) / per_block, grid);
+    const SlotLaunch L = slot_launch(tab, waves, grid, lds_bytes, n_cand);
+    const int per_block = tab.cands_per_wave * L.waves;
+    const int64_t blocks = L.blocks;
     // Candidates per atomic draw.  Atomics on one address complete at some 8e7 per second; a batch of
     // long candidates stays far below that and is drawn one by one (best balance at the end of the
     // batch), short rows are drawn several at a time: about one draw per 12 K op words.
@@ -754,7 +771,7 @@ int fpsched_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_
                               : !p->mb_set ? slot_kernel_ptr(p->slot_v, p->slot_deg2, one_class)
                               : (mb_lds ? slot_kernel_of<kSlotPerMicrobatchLds>(p->slot_v, p->slot_deg2, one_class)
                                         : slot_kernel_of<kSlotPerMicrobatch>(p->slot_v, p->slot_deg2, one_class));
-    hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(64 * waves), lds_bytes,
+    hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(64 * L.waves), L.lds_bytes,
                        static_cast<hipStream_t>(hip_stream), tab, d_ops,
                        (long long)n_cand, (int)stride_words, reinterpret_cast<long long*>(out.makespan),
                        reinterpret_cast<long long*>(out.idle), out.peak, out.flags, counter, draw_block,
@@ -1733,7 +1750,11 @@ int fpsched_wslide(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_ca
   if (!d_workspace || (reinterpret_cast<uintptr_t>(d_workspace) & 15)) return FPSCHED_EINVAL;
   if (workspace_bytes < fpsched_wslide_workspace_bytes(p, n_cand, stride_words)) return FPSCHED_ENOMEM;
   const int lpc = p->stab.lanes_per_cand;
-  const int64_t place_blocks = (n_cand * lpc + kSlideThreads - 1) / kSlideThreads;
+  // (a small batch is spread over the compute units: fewer wavefronts per workgroup)
+  const int64_t place_waves_all = (n_cand * lpc + 63) / 64;
+  const int place_threads = 64 * (int)std::clamp<int64_t>((place_waves_all + std::max(p->n_cu, 1) - 1) / std::max(p->n_cu, 1),
+                                                          1, kSlideThreads / 64);
+  const int64_t place_blocks = (n_cand * lpc + place_threads - 1) / place_threads;
   if (place_blocks > 0x7fffffffll) return FPSCHED_EINVAL;
   DeviceGuard g(p->device_id);
   if (!g.ok) return FPSCHED_EHIP;
@@ -1753,21 +1774,22 @@ int fpsched_wslide(const fpsched_problem* p, const uint16_t* d_ops, int64_t n_ca
   const int waves = links ? p->links_waves : p->slot_waves;
   const int grid = links ? p->links_grid : p->slot_grid;
   const size_t times_lds = (size_t)(links ? p->links_lds_bytes : p->slot_lds_bytes) + 16;
-  const int per_block = times_tab.cands_per_wave * waves;
-  const int64_t blocks = std::min<int64_t>((n_cand + per_block - 1) / per_block, grid);
+  const SlotLaunch L = slot_launch(times_tab, waves, grid, times_lds, n_cand);
+  const int per_block = times_tab.cands_per_wave * L.waves;
+  const int64_t blocks = L.blocks;
   const int64_t row_words = (int64_t)p->D * stride_words;
   const int draw_block = (int)std::clamp<int64_t>((12288 + row_words - 1) / row_words, 1, times_tab.cands_per_wave);
   const bool one_class = p->stab.n_classes == 1;
   hipLaunchKernelGGL(reset_counter_kernel, dim3(1), dim3(64), 0, st, counter, (unsigned long long)(blocks * per_block));
   hipLaunchKernelGGL(links ? slot_kernel_of<kSlotTimesLinks>(p->slot_v, p->slot_deg2, one_class)
                            : slot_kernel_of<kSlotTimes>(p->slot_v, p->slot_deg2, one_class),
-                     dim3((unsigned)blocks), dim3(64 * waves), times_lds, st, times_tab, d_ops, (long long)n_cand,
+                     dim3((unsigned)blocks), dim3(64 * L.waves), L.lds_bytes, st, times_tab, d_ops, (long long)n_cand,
                      (int)stride_words, (long long*)nullptr, (long long*)nullptr, (int*)nullptr, timed_flags, counter,
                      draw_block, starts, stops, (const int32_t*)nullptr, escapes, escape_cap);
   if (hipGetLastError() != hipSuccess) return FPSCHED_EHIP;
   // pass 2: every row places its W items on its own
-  hipLaunchKernelGGL(wslide_place_kernel, dim3((unsigned)place_blocks), dim3(kSlideThreads),
-                     (size_t)kNKinds * kMaxChunks * lpc * 16 + (kSlideThreads / 64) * kSlideWaveLdsBytes, st, p->stab, d_ops,
+  hipLaunchKernelGGL(wslide_place_kernel, dim3((unsigned)place_blocks), dim3(place_threads),
+                     (size_t)kNKinds * kMaxChunks * lpc * 16 + (place_threads / 64) * kSlideWaveLdsBytes, st, p->stab, d_ops,
                      (long long)n_cand, (int)stride_words,
                      starts, escapes, escape_cap, stops, timed_flags, d_ops_out, (int)stride_out_words,
                      reinterpret_cast<long long*>(out.makespan), reinterpret_cast<long long*>(out.idle), out.peak,
@@ -1793,13 +1815,14 @@ int fpsched_wslide_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int
   unsigned long long* counter = static_cast<unsigned long long*>(d_workspace);
   // launched as fpsched_evaluate launches the plain form (same workgroup shape; 16 bytes of LDS more)
   const SlotTables& tab = p->stab_slide;
-  const int per_block = tab.cands_per_wave * p->slot_waves;
-  const int64_t blocks = std::min<int64_t>((n_cand + per_block - 1) / per_block, p->slot_grid);
+  const SlotLaunch L = slot_launch(tab, p->slot_waves, p->slot_grid, (size_t)p->slot_lds_bytes + 16, n_cand);
+  const int per_block = tab.cands_per_wave * L.waves;
+  const int64_t blocks = L.blocks;
   const int64_t row_words = (int64_t)p->D * stride_words;
   const int draw_block = (int)std::clamp<int64_t>((12288 + row_words - 1) / row_words, 1, tab.cands_per_wave);
   hipLaunchKernelGGL(reset_counter_kernel, dim3(1), dim3(64), 0, st, counter, (unsigned long long)(blocks * per_block));
   hipLaunchKernelGGL(slot_kernel_of<kSlotSlide>(p->slot_v, p->slot_deg2, tab.n_classes == 1), dim3((unsigned)blocks),
-                     dim3(64 * p->slot_waves), (size_t)p->slot_lds_bytes + 16, st, tab, d_ops, (long long)n_cand,
+                     dim3(64 * L.waves), L.lds_bytes, st, tab, d_ops, (long long)n_cand,
                      (int)stride_words, reinterpret_cast<long long*>(out.makespan), reinterpret_cast<long long*>(out.idle),
                      out.peak, out.flags, counter, draw_block, (uint32_t*)nullptr, (int32_t*)nullptr,
                      (const int32_t*)nullptr, (uint32_t*)nullptr, 0);
