@@ -1593,7 +1593,10 @@ int fpsched_generate_evaluate(const fpsched_problem* p, const fpsched_actor_poli
     if (wv >= 1 && wv * groups > best_waves * best_groups) { best_waves = wv; best_groups = groups; }
   }
   const int64_t segments = (n_sets + cpw - 1) / cpw;
-  const int64_t blocks = std::min<int64_t>((segments + best_waves - 1) / best_waves, (int64_t)p->n_cu * best_groups);
+  // (a small batch is spread over the compute units: fewer wavefronts per workgroup)
+  const int64_t grid = (int64_t)p->n_cu * best_groups;
+  best_waves = (int)std::clamp<int64_t>((segments + grid - 1) / grid, 1, best_waves);
+  const int64_t blocks = std::min<int64_t>((segments + best_waves - 1) / best_waves, grid);
   const int64_t lds_bytes = 4 * (shared_ints + best_waves * wave_ints);
   DeviceGuard g(p->device_id);
   if (!g.ok) return FPSCHED_EHIP;
