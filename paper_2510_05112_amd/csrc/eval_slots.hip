@@ -301,11 +301,11 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   // word behind it (a lane that issues the op at position k reads the word at k + 2).
   unsigned at_state = stt_off, at_slot = slot_base, at_in = slot_base, at_in2 = slot_base;
   int4 M = make_int4(0, 0, 15, 0);   // metadata row of the current word (an invalid row to begin with)
-  // (SLIDE, SYNC: the row as one 16-byte value from its load to the decision, so that it stays in the four
+  // (SLIDE, SYNC, TIMES: the row as one 16-byte value from its load to the decision, so that it stays in the four
   // registers it was loaded into; as four separate values the register allocator copies some of them right behind
   // the load, which puts a wait for that load in front of the next round's reads.  The other modes measured the
   // same or slightly worse with it.)
-  constexpr bool ROW16 = SLIDE || SYNC;
+  constexpr bool ROW16 = SLIDE || SYNC || TIMES;
   lds_int4 M_row = {0, 0, 15, 0};
   int2 M2 = make_int2(0, 0);         // its second-edge row
   unsigned w_next = 0u;              // the word behind the current one
