@@ -52,8 +52,8 @@ MEASURED_BOTH = {("cfg4", 65536): {"traffic_bytes": 3.765e9, "valu_wave_instruct
 MEASURED_WSLIDE_EVAL = {("cfg4", 65536): {"traffic_bytes": 4.64e9, "valu_wave_instructions": 5.813e9,
                                           "valu_per_wave_round": None, "profile_kernel_ms": 10.83,
                                           "profile": "profiles/wslide_kernel_cfg4.md"}}
-MEASURED_SYNC = {("sync4", 65536): {"traffic_bytes": None, "valu_wave_instructions": 5.74e8,
-                                   "valu_per_wave_round": None, "profile_kernel_ms": 1.312,
+MEASURED_SYNC = {("sync4", 65536): {"traffic_bytes": None, "valu_wave_instructions": 5.62e8,
+                                   "valu_per_wave_round": None, "profile_kernel_ms": 1.293,
                                    "profile": "profiles/eval_sync_kernel.md"}}
 MEASURED_SYNC_TABLE = {("sync4", 65536): {"traffic_bytes": None, "valu_wave_instructions": 1.068e9,
                                          "valu_per_wave_round": None, "profile_kernel_ms": 7.12,
