@@ -146,13 +146,9 @@ def bench_generate(args, spec, threads) -> int:
     ws = handle.alloc_workspace(n, k)
     res = handle.alloc_results(n) if search else None
     slide = search and args.slide and bool(prob.has_w)
-    if slide and args.links:
-        # the generated schedules also go through the sliding pass (Section 5.2, bubble optimizations)
-        slide_ws = torch.empty(int(fp.load_library().fpsched_wslide_workspace_bytes(handle._h, n, stride)),
-                               dtype=torch.uint8, device=dev)
-        slid = handle.wslide(out["ops"], stride, workspace=slide_ws)
-    elif slide:
-        # (plain cost model: the one-kernel form ranks the slid schedules, and only the winners' lists are written)
+    if slide:
+        # the generated schedules also go through the sliding pass (Section 5.2, bubble optimizations): its
+        # one-kernel form ranks the slid schedules, and only the winners' lists are written
         slid = handle.wslide_evaluate(out["ops"], workspace=ws)
     top = dict(idx=torch.empty(k, dtype=torch.int64, device=dev),
                makespan=torch.empty(k, dtype=torch.int64, device=dev),
@@ -171,10 +167,7 @@ def bench_generate(args, spec, threads) -> int:
             handle.topk(res, k, ws, top)
             handle.generate_selected(d_pol, d_inf, top["idx"], stride, out=winners, workspace=ws)
         elif search:
-            if slide and args.links:
-                handle.wslide(out["ops"], stride, out=slid, workspace=slide_ws)
-                handle.topk(slid, k, ws, top)
-            elif slide:
+            if slide:
                 handle.wslide_evaluate(out["ops"], out=slid, workspace=ws)
                 handle.topk(slid, k, ws, top)
                 handle.wslide(out["ops"].index_select(0, top["idx"].clamp(min=0)), stride)
@@ -304,8 +297,8 @@ def bench_wslide(args, spec, threads) -> int:
         print(f"[bench] copy probe: {ops.numel() * 2} bytes read, {ops.numel() * 2} bytes written",
               file=sys.stderr, flush=True)
         del probe
-    slide_ws = torch.empty(int(fp.load_library().fpsched_wslide_workspace_bytes(handle._h, C, stride)),
-                           dtype=torch.uint8, device=dev)
+    slide_ws = None if args.no_lists else torch.empty(
+        int(fp.load_library().fpsched_wslide_workspace_bytes(handle._h, C, stride)), dtype=torch.uint8, device=dev)
     no_lists = args.no_lists
     winners = None
     if no_lists:
@@ -384,7 +377,7 @@ def bench_wslide(args, spec, threads) -> int:
                 # the winners' lists against the oracle's lists of the same candidates
                 n_top = int(top["count"].item())
                 idx = top["idx"][:n_top].cpu().numpy()
-                ref_top = oracle.wslide(prob, words[idx], stride, threads=threads)
+                ref_top = oracle.wslide(prob, words[idx], stride, threads=threads, links=args.links)
                 ok = ok and all(np.array_equal(winners[n][:n_top].cpu().numpy().view(ref_top[n].dtype), ref_top[n])
                                 for n in ("ops", "makespan", "idle", "peak", "flags"))
             else:

@@ -352,9 +352,10 @@ int fpsched_wslide(const fpsched_problem *p, const uint16_t *d_ops, int64_t n_ca
  * fpsched_evaluate over the lists without their W words, in which a device runs its oldest
  * stashed W items in front of every item they end before.  Same arguments, alignment and
  * errors as fpsched_evaluate; workspace: fpsched_workspace_bytes(p, n_cand, 0) (DEVICE, 16-byte
- * aligned).  FPSCHED_EINVAL without split backward; FPSCHED_EUNSUPPORTED without the slot
- * tables or while costs per micro-batch, link occupancy, synchronisation stages or the copy
- * engine are set.  Asynchronous on hip_stream. */
+ * aligned).  Cost model: as for fpsched_wslide (pure latencies, or links that carry one value
+ * at a time).  FPSCHED_EINVAL without split backward; FPSCHED_EUNSUPPORTED without the slot
+ * tables or while costs per micro-batch, synchronisation stages or the copy engine are set.
+ * Asynchronous on hip_stream. */
 int fpsched_wslide_evaluate(const fpsched_problem *p, const uint16_t *d_ops, int64_t n_cand,
                             int32_t stride_words, fpsched_results out, void *d_workspace,
                             size_t workspace_bytes, void *hip_stream);

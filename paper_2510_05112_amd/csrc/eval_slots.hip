@@ -175,10 +175,10 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   constexpr bool TIMES = MODE == kSlotTimes || MODE == kSlotTimesLinks;
   constexpr bool MBDUR = MODE == kSlotPerMicrobatch;
   constexpr bool MBLDS = MODE == kSlotPerMicrobatchLds || MODE == kSlotPerMicrobatchLdsLinks;
-  constexpr bool LINKS = MODE == kSlotLinks || MODE == kSlotTimesLinks || MODE == kSlotPerMicrobatchLdsLinks;
+  constexpr bool LINKS = MODE == kSlotLinks || MODE == kSlotTimesLinks || MODE == kSlotPerMicrobatchLdsLinks || MODE == kSlotSlideLinks;
   constexpr bool COPY = MODE == kSlotCopy;
   constexpr bool SYNC = MODE == kSlotSync;
-  constexpr bool SLIDE = MODE == kSlotSlide;
+  constexpr bool SLIDE = MODE == kSlotSlide || MODE == kSlotSlideLinks;
   constexpr bool W_NOOP = TIMES || SLIDE;   // the tables describe the lists without their W items
   // SLIDE: bits per queue entry, entries the queue holds
   constexpr unsigned kQBits = V == 1 ? 0u : (V == 2 ? 1u : 2u);
@@ -895,7 +895,8 @@ __global__ __launch_bounds__(kSlotMaxThreads) void eval_slot_kernel(
   FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotPerMicrobatchLdsLinks) \
   FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotCopy) \
   FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotSync) \
-  FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotSlide)
+  FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotSlide) \
+  FPSCHED_INSTANTIATE_MODE(V, G, O, kSlotSlideLinks)
 FPSCHED_INSTANTIATE(1, false, true)
 FPSCHED_INSTANTIATE(2, false, true)
 FPSCHED_INSTANTIATE(4, false, true)

@@ -42,6 +42,10 @@ struct fpsched_problem {
   bool slide_eval_ok = false;      // the one-kernel form of the sliding pass (results only) is available
   SlotTables stab_slide{};         // stab_times plus the costs of the W items
   int32_t* d_slide_ints = nullptr;
+  std::vector<int32_t> slide_w_table;   // host copy of those costs (layout: SlotTables::off_w)
+  bool links_slide_eval_ok = false;     // ... and its form under the link model
+  SlotTables stab_slide_links{};
+  int32_t* d_slide_links_image = nullptr;
   SlotTables stab{};
   std::vector<int32_t> slot_ints;
   int32_t* d_slot_ints = nullptr;
@@ -615,6 +619,7 @@ int fpsched_problem_create(const fpsched_problem_desc* desc, int device_id, int3
             }
             w[2 * kMaxChunks] = (int32_t)((uint32_t)total << 8);   // (below 2^24: the slot form's bound on all times)
           }
+          p->slide_w_table.assign(JS.begin() + off_w, JS.end());
           if (hipMalloc(&p->d_slide_ints, JS.size() * sizeof(int32_t)) == hipSuccess &&
               hipMemcpy(p->d_slide_ints, JS.data(), JS.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess &&
               hipFuncSetAttribute(reinterpret_cast<const void*>(slot_kernel_of<kSlotSlide>(p->slot_v, p->slot_deg2, p->stab.n_classes == 1)),
@@ -662,6 +667,7 @@ void fpsched_problem_destroy(fpsched_problem* p) {
     if (p->d_mb_image) (void)hipFree(p->d_mb_image);
     if (p->d_links_image) (void)hipFree(p->d_links_image);
     if (p->d_times_links_image) (void)hipFree(p->d_times_links_image);
+    if (p->d_slide_links_image) (void)hipFree(p->d_slide_links_image);
     if (p->d_combo_image) (void)hipFree(p->d_combo_image);
     if (p->d_sync_ints) (void)hipFree(p->d_sync_ints);
   }
@@ -1121,6 +1127,25 @@ int fpsched_problem_set_link_occupancy(fpsched_problem* p, int32_t on) {
       p->stab_times_links = p->stab_links;
       p->stab_times_links.ints = timg;
       p->links_slide_ok = true;
+      // the one-kernel form of the pass under the link model: the same image with the W items' costs behind it
+      if (p->slide_eval_ok && !p->slide_w_table.empty()) {
+        std::vector<int32_t> JS = JT;
+        JS.insert(JS.end(), p->slide_w_table.begin(), p->slide_w_table.end());
+        int32_t* simg = nullptr;
+        if (hipMalloc(&simg, JS.size() * sizeof(int32_t)) == hipSuccess &&
+            hipMemcpy(simg, JS.data(), JS.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess &&
+            hipFuncSetAttribute(reinterpret_cast<const void*>(slot_kernel_of<kSlotSlideLinks>(p->slot_v, p->slot_deg2, ST.n_classes == 1)),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, p->max_lds) == hipSuccess) {
+          p->d_slide_links_image = simg;
+          p->stab_slide_links = p->stab_links;
+          p->stab_slide_links.ints = simg;
+          p->stab_slide_links.off_w = (int32_t)JT.size();
+          p->links_slide_eval_ok = true;
+        } else {
+          (void)hipGetLastError();
+          if (simg) (void)hipFree(simg);
+        }
+      }
     } else {
       (void)hipGetLastError();
       if (timg) (void)hipFree(timg);
@@ -1805,7 +1830,8 @@ int fpsched_wslide_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int
   if (!p || n_cand < 0) return FPSCHED_EINVAL;
   if (p->device_id < 0) return FPSCHED_ENODEV;
   if (!p->has_w) return FPSCHED_EINVAL;
-  if (!p->slide_eval_ok || p->mb_set || p->sync_on || p->copy_depth > 0 || p->links_on) return FPSCHED_EUNSUPPORTED;
+  if (!p->slide_eval_ok || p->mb_set || p->sync_on || p->copy_depth > 0 || (p->links_on && !p->links_slide_eval_ok))
+    return FPSCHED_EUNSUPPORTED;
   if (n_cand == 0) return FPSCHED_OK;
   if (!d_ops || !out.makespan || !out.idle || !out.peak || !out.flags) return FPSCHED_EINVAL;
   if (stride_words < 8 || (stride_words & 7) || stride_words > p->max_stride) return FPSCHED_EINVAL;
@@ -1816,15 +1842,18 @@ int fpsched_wslide_evaluate(const fpsched_problem* p, const uint16_t* d_ops, int
   if (!g.ok) return FPSCHED_EHIP;
   hipStream_t st = static_cast<hipStream_t>(hip_stream);
   unsigned long long* counter = static_cast<unsigned long long*>(d_workspace);
-  // launched as fpsched_evaluate launches the plain form (same workgroup shape; 16 bytes of LDS more)
-  const SlotTables& tab = p->stab_slide;
-  const SlotLaunch L = slot_launch(tab, p->slot_waves, p->slot_grid, (size_t)p->slot_lds_bytes + 16, n_cand);
+  // launched as fpsched_evaluate launches the plain form, or the link form (same workgroup shape; 16 bytes of LDS more)
+  const bool links = p->links_on;
+  const SlotTables& tab = links ? p->stab_slide_links : p->stab_slide;
+  const SlotLaunch L = slot_launch(tab, links ? p->links_waves : p->slot_waves, links ? p->links_grid : p->slot_grid,
+                                   (size_t)(links ? p->links_lds_bytes : p->slot_lds_bytes) + 16, n_cand);
   const int per_block = tab.cands_per_wave * L.waves;
   const int64_t blocks = L.blocks;
   const int64_t row_words = (int64_t)p->D * stride_words;
   const int draw_block = (int)std::clamp<int64_t>((12288 + row_words - 1) / row_words, 1, tab.cands_per_wave);
   hipLaunchKernelGGL(reset_counter_kernel, dim3(1), dim3(64), 0, st, counter, (unsigned long long)(blocks * per_block));
-  hipLaunchKernelGGL(slot_kernel_of<kSlotSlide>(p->slot_v, p->slot_deg2, tab.n_classes == 1), dim3((unsigned)blocks),
+  hipLaunchKernelGGL(links ? slot_kernel_of<kSlotSlideLinks>(p->slot_v, p->slot_deg2, tab.n_classes == 1)
+                           : slot_kernel_of<kSlotSlide>(p->slot_v, p->slot_deg2, tab.n_classes == 1), dim3((unsigned)blocks),
                      dim3(64 * L.waves), L.lds_bytes, st, tab, d_ops, (long long)n_cand,
                      (int)stride_words, reinterpret_cast<long long*>(out.makespan), reinterpret_cast<long long*>(out.idle),
                      out.peak, out.flags, counter, draw_block, (uint32_t*)nullptr, (int32_t*)nullptr,

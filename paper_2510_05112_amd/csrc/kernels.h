@@ -56,7 +56,8 @@ constexpr int kSlotMaxThreads = 64 * kSlotMaxWaves;
 // MODE kSlotSlide: the weight-gradient sliding pass without its lists: the results of the lists the two-pass form
 // would write, in one kernel (tables as for kSlotTimes plus the W items' costs at T.off_w; 16 bytes of LDS more).
 constexpr int kSlotPlain = 0, kSlotTimes = 1, kSlotPerMicrobatch = 2, kSlotPerMicrobatchLds = 3, kSlotLinks = 4,
-              kSlotTimesLinks = 5, kSlotPerMicrobatchLdsLinks = 6, kSlotCopy = 7, kSlotSync = 8, kSlotSlide = 9;
+              kSlotTimesLinks = 5, kSlotPerMicrobatchLdsLinks = 6, kSlotCopy = 7, kSlotSync = 8, kSlotSlide = 9,
+              kSlotSlideLinks = 10;   // kSlotSlide under the link model
 constexpr int kSlotCopyWords = 32;
 template <int V, bool DEG2, bool ONE_CLASS, int MODE>
 __global__ void eval_slot_kernel(SlotTables T, const uint16_t* ops, long long n_cand, int stride,

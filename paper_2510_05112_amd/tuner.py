@@ -15,7 +15,6 @@ from dataclasses import dataclass
 
 import numpy as np
 
-from .binding import FpschedError
 
 CTTP_BWD_FIRST, CTTP_FWD_FIRST, CTTP_INTERLEAVED = 0, 1, 2
 BREADTH_FIRST, DEPTH_FIRST = 0, 1
@@ -138,13 +137,8 @@ def tune(handle, problem, circular: bool, k: int = 8, inflight_options=None, for
     out = handle.generate(torch.from_numpy(pol).cuda(), torch.from_numpy(inf).cuda(), stride)
     res = handle.evaluate(out["ops"])
     if slide and problem.has_w:
-        # only the results of the slid lists are ranked: the one-kernel form where the cost model has one
-        try:
-            slid = handle.wslide_evaluate(out["ops"])
-        except FpschedError as e:
-            if e.code != -6:   # FPSCHED_EUNSUPPORTED (link occupancy is set)
-                raise
-            slid = handle.wslide(out["ops"], stride)
+        # only the results of the slid lists are ranked: the one-kernel form, which writes no list
+        slid = handle.wslide_evaluate(out["ops"])
         res = {name: torch.cat([res[name], slid[name]]) for name in ("makespan", "idle", "peak", "flags")}
     top = handle.topk(res, min(k, 1024))
     torch.cuda.synchronize()

@@ -31,14 +31,16 @@ def assert_same(got, ref, what=""):
         assert bad.size == 0, (what, name, bad[:5].tolist(), got[name][tuple(bad[0])], ref[name][tuple(bad[0])])
 
 
+@pytest.mark.parametrize("links", [False, True])
 @pytest.mark.parametrize("index,n", [(2, 3001), (3, 700), (5, 2000), (4, 130)])
-def test_matches_the_oracle_on_the_configurations(index, n):
+def test_matches_the_oracle_on_the_configurations(index, n, links):
     spec = workloads.config(index, n)
     words = workloads.generate(spec, threads=16)
-    print(f"cfg{index}: {n} candidates", flush=True)
+    print(f"cfg{index}: {n} candidates, links={links}", flush=True)
     h = fp.Problem(spec.problem, spec.stride, device=0)
+    h.set_link_occupancy(links)
     got = run_gpu(h, words)
-    ref = oracle.wslide(spec.problem, words, spec.stride, threads=16)
+    ref = oracle.wslide(spec.problem, words, spec.stride, threads=16, links=links)
     assert_same(got, ref, f"cfg{index}")
     assert ((ref["flags"] & 3) == 0).sum() > n // 2
     # and what the two-pass form reports
@@ -94,6 +96,9 @@ def test_small_cases_and_errors():
     torch.cuda.synchronize()
     assert out["makespan"].numel() == 0
     h.set_link_occupancy(True)
+    assert_same(run_gpu(h, words), oracle.wslide(prob, words, 8, links=True), "small, links")
+    h.set_link_occupancy(False)
+    h.set_microbatch_costs(np.repeat(np.asarray(prob.dur)[:, :, None], 2, axis=2))
     with pytest.raises(fp.FpschedError):
         h.wslide_evaluate(to_gpu(words))
     h.close()
@@ -104,14 +109,16 @@ def test_small_cases_and_errors():
     h.close()
 
 
-def test_largest_sizes_and_long_stashes():
+@pytest.mark.parametrize("links", [False, True])
+def test_largest_sizes_and_long_stashes(links):
     from helpers import batch_from_lists, perturb, random_valid_lists
     from workloads.problem import gpipe_lists, one_f_one_b_lists
 
     def check(prob, words, what):
         h = fp.Problem(prob, words.shape[2], device=0)
+        h.set_link_occupancy(links)
         got = run_gpu(h, words)
-        assert_same(got, oracle.wslide(prob, words, words.shape[2], threads=8), what)
+        assert_same(got, oracle.wslide(prob, words, words.shape[2], threads=8, links=links), what)
         h.close()
         return got
 
