@@ -133,8 +133,8 @@ def bench_generate(args, spec, threads) -> int:
     # fused search step: the schedules are timed while they are generated and never written; only the
     # rows of the k winners are generated afterwards
     fused = search and args.fused
-    if fused and (args.slide or args.links):
-        print("[bench] --fused knows the plain cost model and no sliding pass", file=sys.stderr)
+    if fused and args.links:
+        print("[bench] --fused knows the plain cost model only", file=sys.stderr)
         return 2
     out = dict(ops=torch.empty((k if fused else n, prob.n_devices, stride), dtype=torch.int16, device=dev),
                steps=torch.empty(n, dtype=torch.int32, device=dev),
@@ -146,7 +146,7 @@ def bench_generate(args, spec, threads) -> int:
     ws = handle.alloc_workspace(n, k)
     res = handle.alloc_results(n) if search else None
     slide = search and args.slide and bool(prob.has_w)
-    if slide:
+    if slide and not fused:
         # the generated schedules also go through the sliding pass (Section 5.2, bubble optimizations): its
         # one-kernel form ranks the slid schedules, and only the winners' lists are written
         slid = handle.wslide_evaluate(out["ops"], workspace=ws)
@@ -158,7 +158,7 @@ def bench_generate(args, spec, threads) -> int:
         if e:
             e[0].record()
         if fused:
-            handle.generate_evaluate(d_pol, d_inf, results=res, out=out, workspace=ws)
+            handle.generate_evaluate(d_pol, d_inf, results=res, out=out, workspace=ws, slide=slide)
         else:
             handle.generate(d_pol, d_inf, stride, out=out, workspace=ws)
         if e:
@@ -166,6 +166,8 @@ def bench_generate(args, spec, threads) -> int:
         if fused:
             handle.topk(res, k, ws, top)
             handle.generate_selected(d_pol, d_inf, top["idx"], stride, out=winners, workspace=ws)
+            if slide:   # the winners' lists after the sliding pass
+                handle.wslide(winners["ops"], stride)
         elif search:
             if slide:
                 handle.wslide_evaluate(out["ops"], out=slid, workspace=ws)
@@ -201,6 +203,7 @@ def bench_generate(args, spec, threads) -> int:
     gen_roofline, gen_issue = rooflines(alg_bytes, gen_ms,
                                         "fpsched generator kernel, timed form (generate_kernel<.., true>)" if fused
                                         else "fpsched generator kernel (generate_kernel)",
+                                        None if fused and slide else
                                         (MEASURED_FUSED if fused else MEASURED_GENERATE).get((f"cfg{spec.index}", n)),
                                         units=n_ops)
     json_res = {
@@ -211,7 +214,8 @@ def bench_generate(args, spec, threads) -> int:
         "config": {"workload": f"{'search loop' if search else 'generator'} on cfg{spec.index}: {prob.name}, "
                                f"{n} seeded parameter sets" + (f", top-{k}" if search else "")
                                + (", link occupancy" if search and args.links else "")
-                               + (", timed while generated (no op words written but the winners')" if fused else ""),
+                               + (", timed while generated (no op words written but the winners')" if fused else "")
+                               + (", ranked after the weight-gradient sliding pass" if slide else ""),
                    "parameter_sets": n, "devices": prob.n_devices, "stages": prob.n_stages,
                    "microbatches": prob.n_microbatches, "ops_per_schedule": n_ops / n, "stride_words": stride},
         "items_scheduled_per_s": n_ops / (ms_per_step * 1e-3),
@@ -222,7 +226,7 @@ def bench_generate(args, spec, threads) -> int:
         "host": {"parameter_sets_s": prep_s},
     }
     if search:
-        fl = (slid if slide else res)["flags"].cpu().numpy()
+        fl = (slid if slide and not fused else res)["flags"].cpu().numpy()
         res_out = {"feasible_under_cap": float((fl == 0).mean()), "over_cap": float((fl == 4).mean()),
                    "best_makespan": int(top["makespan"][0].item()) if int(top["count"].item()) else None}
         res_out["sliding_pass"] = bool(slide)
@@ -234,7 +238,8 @@ def bench_generate(args, spec, threads) -> int:
             pick = np.sort(rng.choice(n, min(args.check, n), replace=False))
             ref = oracle.generate(prob, pol[pick], inf[pick], stride, threads=threads)
             if fused:
-                ref_ev = oracle.evaluate(prob, ref["words"], threads=threads)
+                ref_ev = (oracle.wslide(prob, ref["words"], stride, threads=threads) if slide
+                          else oracle.evaluate(prob, ref["words"], threads=threads))
                 ok = np.array_equal(steps[pick], ref["steps"]) and all(
                     np.array_equal(res[name].cpu().numpy()[pick], ref_ev[name])
                     for name in ("makespan", "idle", "peak", "flags"))

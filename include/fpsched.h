@@ -490,6 +490,16 @@ int fpsched_generate_evaluate(const fpsched_problem *p, const fpsched_actor_poli
                               int32_t *d_steps, uint8_t *d_status, void *d_workspace,
                               size_t workspace_bytes, void *hip_stream);
 
+/* fpsched_generate_evaluate with the weight-gradient sliding pass in it (Section 5.2: the scheduler,
+ * then the bubble optimization, then the estimator): `out` is what fpsched_wslide_evaluate reports
+ * for the lists fpsched_generate writes for the same parameter sets, d_steps and d_status are those
+ * of fpsched_generate.  Nothing but the results leaves the chip.  Same arguments, workspace and
+ * errors as fpsched_generate_evaluate; FPSCHED_EINVAL for a problem without split backward. */
+int fpsched_generate_slide_evaluate(const fpsched_problem *p, const fpsched_actor_policy *d_policy,
+                                    const int32_t *d_inflight, int64_t n_sets, fpsched_results out,
+                                    int32_t *d_steps, uint8_t *d_status, void *d_workspace,
+                                    size_t workspace_bytes, void *hip_stream);
+
 /* fpsched_generate for chosen parameter sets: row block i of d_ops (and d_steps[i], d_status[i])
  * is the schedule of parameter set d_select[i] (DEVICE int64 [n_selected], e.g. the indices
  * fpsched_topk wrote) of the n_sets sets that d_policy and d_inflight hold.  An entry outside

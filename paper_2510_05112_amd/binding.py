@@ -105,6 +105,8 @@ def load_library():
         lib.fpsched_generate_selected.argtypes = [vp, vp, vp, i64, vp, i64, i32, vp, vp, vp, vp, ctypes.c_size_t, vp]
         lib.fpsched_generate_evaluate.restype = ctypes.c_int
         lib.fpsched_generate_evaluate.argtypes = [vp, vp, vp, i64, _Results, vp, vp, vp, ctypes.c_size_t, vp]
+        lib.fpsched_generate_slide_evaluate.restype = ctypes.c_int
+        lib.fpsched_generate_slide_evaluate.argtypes = lib.fpsched_generate_evaluate.argtypes
         lib.fpsched_encode.restype = ctypes.c_int
         lib.fpsched_encode.argtypes = [vp, vp, i32, i32, vp]
         lib.fpsched_validate.restype = ctypes.c_int64
@@ -385,13 +387,15 @@ class Problem:
             raise FpschedError(rc, "fpsched_generate_selected")
         return out
 
-    def generate_evaluate(self, policy, inflight, results=None, out=None, workspace=None, stream=None):
+    def generate_evaluate(self, policy, inflight, results=None, out=None, workspace=None, stream=None, slide=False):
         """fpsched_generate_evaluate: the schedules of n parameter sets timed while they are generated;
-        no op words are written.  Returns (results as alloc_results gives them, dict(steps, status)).
+        no op words are written.  slide: fpsched_generate_slide_evaluate, the same with the weight-gradient
+        sliding pass in it.  Returns (results as alloc_results gives them, dict(steps, status)).
         Asynchronous."""
         import torch
+        name = "fpsched_generate_slide_evaluate" if slide else "fpsched_generate_evaluate"
         if self.device is None:
-            raise FpschedError(-5, "fpsched_generate_evaluate")
+            raise FpschedError(-5, name)
         assert policy.is_cuda and policy.is_contiguous() and policy.dtype == torch.int32
         assert inflight.is_cuda and inflight.is_contiguous() and inflight.dtype == torch.int32
         n = policy.shape[0]
@@ -404,12 +408,12 @@ class Problem:
                        status=torch.empty(n, dtype=torch.uint8, device=dev))
         if workspace is None:
             workspace = self.alloc_workspace(n, 0)
-        rc = load_library().fpsched_generate_evaluate(
+        rc = getattr(load_library(), name)(
             self._h, policy.data_ptr(), inflight.data_ptr(), n, self._res_struct(results),
             out["steps"].data_ptr(), out["status"].data_ptr(), workspace.data_ptr(), workspace.numel(),
             self._stream(stream))
         if rc != 0:
-            raise FpschedError(rc, "fpsched_generate_evaluate")
+            raise FpschedError(rc, name)
         return results, out
 
     RANK_MODES = {"makespan": 0, "makespan_peak": 1, "peak_makespan": 2, "idle": 3}

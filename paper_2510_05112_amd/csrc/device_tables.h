@@ -47,6 +47,7 @@ struct DevTables {
   int32_t off_gen_rows;
   int32_t gen_row_chunks;   // 1, 2 or 4
   int32_t gen_slot_words;   // (2 * classes + 1) * m
+  int32_t gen_spill_words;  // sliding form of the timed generator: queue words per lane in LDS (a power of two), set per launch
   const int32_t* ints;      // DEVICE
 };
 

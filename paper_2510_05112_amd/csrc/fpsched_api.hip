@@ -1550,9 +1550,9 @@ static int run_generate(const fpsched_problem* p, const fpsched_actor_policy* d_
   if (!g.ok) return FPSCHED_EHIP;
   const int V = max_chunks <= 1 ? 1 : (max_chunks <= 2 ? 2 : 4);
   static const GenKernel table[3][3] = {
-      {&generate_kernel<1, 0, false>, &generate_kernel<1, 1, false>, &generate_kernel<1, 2, false>},
-      {&generate_kernel<2, 0, false>, &generate_kernel<2, 1, false>, &generate_kernel<2, 2, false>},
-      {&generate_kernel<4, 0, false>, &generate_kernel<4, 1, false>, &generate_kernel<4, 2, false>}};
+      {&generate_kernel<1, 0, kGenPlain>, &generate_kernel<1, 1, kGenPlain>, &generate_kernel<1, 2, kGenPlain>},
+      {&generate_kernel<2, 0, kGenPlain>, &generate_kernel<2, 1, kGenPlain>, &generate_kernel<2, 2, kGenPlain>},
+      {&generate_kernel<4, 0, kGenPlain>, &generate_kernel<4, 1, kGenPlain>, &generate_kernel<4, 2, kGenPlain>}};
   const GenKernel kernel = table[V == 1 ? 0 : (V == 2 ? 1 : 2)][deg];
   if (lds_bytes > 64 * 1024 &&
       hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -1585,11 +1585,14 @@ int fpsched_generate_selected(const fpsched_problem* p, const fpsched_actor_poli
                       d_workspace, workspace_bytes, hip_stream);
 }
 
-int fpsched_generate_evaluate(const fpsched_problem* p, const fpsched_actor_policy* d_policy,
-                              const int32_t* d_inflight, int64_t n_sets, fpsched_results out, int32_t* d_steps,
-                              uint8_t* d_status, void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+// generator and evaluator in one kernel; slide: with the weight-gradient sliding pass in it
+static int run_generate_evaluate(const fpsched_problem* p, const fpsched_actor_policy* d_policy,
+                                 const int32_t* d_inflight, int64_t n_sets, fpsched_results out, int32_t* d_steps,
+                                 uint8_t* d_status, void* d_workspace, size_t workspace_bytes, void* hip_stream,
+                                 bool slide) {
   if (!p || n_sets < 0) return FPSCHED_EINVAL;
   if (p->device_id < 0) return FPSCHED_ENODEV;
+  if (slide && !p->has_w) return FPSCHED_EINVAL;
   if (n_sets == 0) return FPSCHED_OK;
   if (!d_policy || !d_inflight || !d_steps || !d_status || !out.makespan || !out.idle || !out.peak || !out.flags)
     return FPSCHED_EINVAL;
@@ -1605,7 +1608,18 @@ int fpsched_generate_evaluate(const fpsched_problem* p, const fpsched_actor_poli
   const int V = p->tables.gen_row_chunks;
   // cost rows shared by the workgroup; per wavefront its counters and its sets' slots
   const int64_t shared_ints = 3ll * V * p->D * 8;
-  const int64_t wave_ints = (((int64_t)cpw * 3 * p->S + 2 * p->S + 1 + 3) & ~3ll) + (int64_t)cpw * p->tables.gen_slot_words;
+  // (slide: a ring of queue words per lane for stashes deeper than two words: one bit per entry at two stages per
+  // device, two at four, none at one; a power of two that holds every W item of a device)
+  DevTables tables = p->tables;
+  tables.gen_spill_words = 0;
+  if (slide) {
+    const int64_t bits = V == 1 ? 0 : (V == 2 ? 1 : 2);
+    int words = 1;
+    while ((int64_t)words * 32 < (int64_t)V * p->m * bits + 32) words <<= 1;
+    tables.gen_spill_words = words;
+  }
+  const int64_t wave_ints = (((int64_t)cpw * 3 * p->S + 2 * p->S + 1 + 3) & ~3ll) + (int64_t)cpw * p->tables.gen_slot_words +
+                            64ll * tables.gen_spill_words;
   const int64_t lds_ints = p->max_lds / 4;
   if (shared_ints + wave_ints > lds_ints) return FPSCHED_EUNSUPPORTED;
   // wavefronts per workgroup and workgroups per compute unit: as many resident wavefronts as asked for
@@ -1626,10 +1640,14 @@ int fpsched_generate_evaluate(const fpsched_problem* p, const fpsched_actor_poli
   DeviceGuard g(p->device_id);
   if (!g.ok) return FPSCHED_EHIP;
   const int deg = p->max_degree <= 1 ? 1 : 2;
-  static const GenKernel table[3][2] = {{&generate_kernel<1, 1, true>, &generate_kernel<1, 2, true>},
-                                        {&generate_kernel<2, 1, true>, &generate_kernel<2, 2, true>},
-                                        {&generate_kernel<4, 1, true>, &generate_kernel<4, 2, true>}};
-  const GenKernel kernel = table[V == 1 ? 0 : (V == 2 ? 1 : 2)][deg - 1];
+  static const GenKernel table[2][3][2] = {
+      {{&generate_kernel<1, 1, kGenTimed>, &generate_kernel<1, 2, kGenTimed>},
+       {&generate_kernel<2, 1, kGenTimed>, &generate_kernel<2, 2, kGenTimed>},
+       {&generate_kernel<4, 1, kGenTimed>, &generate_kernel<4, 2, kGenTimed>}},
+      {{&generate_kernel<1, 1, kGenSlide>, &generate_kernel<1, 2, kGenSlide>},
+       {&generate_kernel<2, 1, kGenSlide>, &generate_kernel<2, 2, kGenSlide>},
+       {&generate_kernel<4, 1, kGenSlide>, &generate_kernel<4, 2, kGenSlide>}}};
+  const GenKernel kernel = table[slide ? 1 : 0][V == 1 ? 0 : (V == 2 ? 1 : 2)][deg - 1];
   if (lds_bytes > 64 * 1024 &&
       hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                           p->max_lds) != hipSuccess)
@@ -1638,11 +1656,25 @@ int fpsched_generate_evaluate(const fpsched_problem* p, const fpsched_actor_poli
   hipLaunchKernelGGL(reset_counter_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(hip_stream), counter,
                      (unsigned long long)(blocks * best_waves * cpw));
   hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(64 * best_waves), (size_t)lds_bytes,
-                     static_cast<hipStream_t>(hip_stream), p->tables, reinterpret_cast<const int32_t*>(d_policy),
+                     static_cast<hipStream_t>(hip_stream), tables, reinterpret_cast<const int32_t*>(d_policy),
                      d_inflight, nullptr, (long long)n_sets, (long long)n_sets, 0, nullptr, d_steps, d_status, counter,
                      GenResults{reinterpret_cast<long long*>(out.makespan), reinterpret_cast<long long*>(out.idle),
                                 out.peak, out.flags});
   return check_hip(hipGetLastError());
+}
+
+int fpsched_generate_evaluate(const fpsched_problem* p, const fpsched_actor_policy* d_policy,
+                              const int32_t* d_inflight, int64_t n_sets, fpsched_results out, int32_t* d_steps,
+                              uint8_t* d_status, void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+  return run_generate_evaluate(p, d_policy, d_inflight, n_sets, out, d_steps, d_status, d_workspace, workspace_bytes,
+                               hip_stream, false);
+}
+
+int fpsched_generate_slide_evaluate(const fpsched_problem* p, const fpsched_actor_policy* d_policy,
+                                    const int32_t* d_inflight, int64_t n_sets, fpsched_results out, int32_t* d_steps,
+                                    uint8_t* d_status, void* d_workspace, size_t workspace_bytes, void* hip_stream) {
+  return run_generate_evaluate(p, d_policy, d_inflight, n_sets, out, d_steps, d_status, d_workspace, workspace_bytes,
+                               hip_stream, true);
 }
 
 // k smallest (key, index) among the entries whose flag byte is 0: tile sort, then a tree of merges

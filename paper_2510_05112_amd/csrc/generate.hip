@@ -42,6 +42,17 @@ typedef short pair16 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ unsigned bits_of(pair16 v) { return __builtin_bit_cast(unsigned, v); }
 constexpr unsigned kBothSigns = 0x80008000u;
 
+// one value per chunk of an actor, as one vector value (an array would be indexed in memory)
+template <int V>
+struct GenPerChunk { typedef int type __attribute__((ext_vector_type(V))); };
+template <int V>
+__device__ __forceinline__ int gen_pick(typename GenPerChunk<V>::type a, unsigned c) {
+  int r = a[0];
+#pragma unroll
+  for (int i = 1; i < V; ++i) r = (c == (unsigned)i) ? a[i] : r;
+  return r;
+}
+
 // a * b + c for a, b below 2^24, b the same in all lanes: one full-rate instruction
 __device__ __forceinline__ unsigned mad24(unsigned a, unsigned b_uniform, unsigned c) {
   unsigned r;
@@ -69,12 +80,23 @@ __device__ __forceinline__ unsigned mad24(unsigned a, unsigned b_uniform, unsign
 // the results is written.  Workgroups hold several wavefronts that share the cost rows; each
 // wavefront keeps its own counters and slots and never looks at another's, so no barrier is needed
 // after the start.
-template <int V, int DEG, bool TIMED>
-__global__ __launch_bounds__(TIMED ? kGenTimedThreads : 64) void generate_kernel(
+//
+// FORM kGenSlide: the timed form with the weight-gradient sliding pass of Section 5.2 (bubble optimizations) in
+// it: the results fpsched_wslide_evaluate gives for the generated lists.  A W item that the scheduler places is
+// passed over; a B item stashes its W item, and in front of every other item the actor runs the oldest
+// stashed items that end before the item starts.  The stash is a queue of log2(V) bits per entry (the chunk):
+// a head word and a tail word in registers, full words in between in a ring in LDS (kGenSpillWords per lane).
+template <int V, int DEG, int FORM>
+__global__ __launch_bounds__(FORM != kGenPlain ? kGenTimedThreads : 64) void generate_kernel(
     DevTables T, const int32_t* __restrict__ policy, const int32_t* __restrict__ inflight,
     const long long* __restrict__ select, long long n_src, long long n_sets, int stride, uint16_t* __restrict__ ops,
     int32_t* __restrict__ out_steps, unsigned char* __restrict__ out_status,
     unsigned long long* __restrict__ next_set, GenResults R) {
+  constexpr bool TIMED = FORM != kGenPlain;
+  constexpr bool SLIDE = FORM == kGenSlide;
+  // SLIDE: bits per queue entry, entries per queue word
+  constexpr unsigned kQBits = V == 1 ? 0u : (V == 2 ? 1u : 2u);
+  constexpr unsigned kQCap = V == 1 ? 0x7fffffffu : 32u / (kQBits ? kQBits : 1u);
   extern __shared__ int32_t lds[];
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6, waves_per_block = blockDim.x >> 6;
@@ -94,7 +116,8 @@ __global__ __launch_bounds__(TIMED ? kGenTimedThreads : 64) void generate_kernel
   }
   const int n_count_ints = (cpw * 3 * S + 2 * S + 1 + 3) & ~3;
   const int slot_words = T.gen_slot_words;
-  int32_t* counts = lds + n_tab + wave * (n_count_ints + (TIMED ? cpw * slot_words : 8 * 64));
+  const int spill_words = SLIDE ? T.gen_spill_words : 0;   // per lane, a power of two
+  int32_t* counts = lds + n_tab + wave * (n_count_ints + (TIMED ? cpw * slot_words + 64 * spill_words : 8 * 64));
   // counters that are always "done" (value m): at_m stands in for a missing neighbour, and at_m,
   // at_m + S, at_m + 2 S for the three counters of a chunk the actor does not have
   const int at_m = cpw * 3 * S;
@@ -148,6 +171,29 @@ __global__ __launch_bounds__(TIMED ? kGenTimedThreads : 64) void generate_kernel
                                       (has_w ? T.ints[T.off_dur + kW * S + stage[c]] : 0));
   }
   int free_at = 0, mem = 0, peak = 0;
+  // SLIDE: cost and freed units of the W item of each chunk (the W rows), what all of them cost; the queue
+  typename GenPerChunk<V>::type w_dur, w_free;
+  int w_total = 0;
+#pragma unroll
+  for (int c = 0; c < V; ++c) {
+    int wd = 0, wf = 0;
+    if (SLIDE && has_dev && c < nch) {
+      const int32_t* r = lds + ((2 * V + c) * D + d) * 8;   // (read after the barrier above)
+      wd = r[0];
+      wf = r[2];
+    }
+    w_dur[c] = wd; w_free[c] = wf;
+    w_total += m * wd;
+  }
+  uint32_t* spill = reinterpret_cast<uint32_t*>(counts + n_count_ints + cpw * slot_words) + lane;   // word i at + i * 64
+  unsigned q_h = 0u, h_n = 0u, q_t = 0u, t_n = 0u, s_rd = 0u, s_wr = 0u;
+  unsigned q_head_dur = 0xffffffffu;   // cost of the oldest stashed item (all ones: none)
+  int q_head_free = 0, w_placed = 0;
+  auto new_head = [&]() {
+    const unsigned head = V > 1 ? q_h & (unsigned)(V - 1) : 0u;
+    q_head_dur = h_n != 0u ? (unsigned)gen_pick<V>(w_dur, head) : 0xffffffffu;
+    q_head_free = gen_pick<V>(w_free, head);
+  };
 
   pair16 limit2 = {1, 1};
   int w_at[V];   // the weight-gradient counters; without split backward, a word that holds m
@@ -196,7 +242,8 @@ __global__ __launch_bounds__(TIMED ? kGenTimedThreads : 64) void generate_kernel
           if (has_set) {
             // the segment's results, in the form fpsched_evaluate gives them for the generated lists; a
             // schedule that is not complete (stuck, bad policy) has items that never ran
-            int makespan = free_at;
+            // (SLIDE: what is still stashed runs back to back behind the actor's last item)
+            int makespan = SLIDE ? free_at + (w_total - w_placed) : free_at;
             bool over = peak > cap;
             for (int off = 1; off < lpc; off <<= 1) makespan = max(makespan, __shfl_xor(makespan, off, 64));
             over = any_in_segment(__ballot(over));
@@ -271,6 +318,7 @@ __global__ __launch_bounds__(TIMED ? kGenTimedThreads : 64) void generate_kernel
         first_step = step; steps = 0; last_pick = -1;
         status = set_bad ? 4 : 0; len = 0;
         free_at = 0; mem = 0; peak = 0;
+        q_h = 0u; h_n = 0u; q_t = 0u; t_n = 0u; s_rd = 0u; s_wr = 0u; q_head_dur = 0xffffffffu; w_placed = 0;
         if (!TIMED) row = ops + (size_t)(has_row ? set * D + d : 0) * (size_t)stride;
         fresh = has_set && !live;   // nothing to schedule (a bad set, no stages): written out next time round
       }
@@ -397,7 +445,7 @@ __global__ __launch_bounds__(TIMED ? kGenTimedThreads : 64) void generate_kernel
       const int j = atomicAdd(&counts[mad24((unsigned)pick_t, (unsigned)S, (unsigned)at)], 1);
       left -= 1;
       last_pick = (int)(step - first_step);
-      if (TIMED) {
+      if (TIMED && (!SLIDE || pick_t != kGenW)) {
         // the item's row: cost, memory, where its inputs' finish times are and where its own goes
         const int4* r = reinterpret_cast<const int4*>(
             reinterpret_cast<const char*>(lds) + __umul24((unsigned)(pick_t * V + pick_c), (unsigned)D * 32u) + d * 32);
@@ -406,12 +454,54 @@ __global__ __launch_bounds__(TIMED ? kGenTimedThreads : 64) void generate_kernel
         char* my_slot = reinterpret_cast<char*>(slot) + j * 4;
         int ready = *reinterpret_cast<const int32_t*>(my_slot + a.w) + b.x;
         if (DEG > 1) ready = max(ready, *reinterpret_cast<const int32_t*>(my_slot + b.y) + b.z);
-        free_at = max(free_at, ready) + a.x;
+        const int start = max(free_at, ready);
+        if (SLIDE && q_head_dur <= (unsigned)(start - free_at)) {
+          // the oldest stashed W items that end before this item starts run in front of it
+          do {
+            free_at += (int)q_head_dur;
+            w_placed += (int)q_head_dur;
+            mem -= q_head_free;
+            q_h >>= kQBits;
+            --h_n;
+            if (h_n == 0u) {
+              // the head word is used up: the oldest full word of the ring, else what the tail word holds
+              if (s_rd != s_wr) {
+                q_h = spill[(s_rd & (unsigned)(spill_words - 1)) * 64];
+                ++s_rd;
+                h_n = kQCap;
+              } else {
+                q_h = q_t; h_n = t_n;
+                q_t = 0u; t_n = 0u;
+              }
+            }
+            new_head();
+          } while (q_head_dur <= (unsigned)(start - free_at));
+        }
+        free_at = start + a.x;
         *reinterpret_cast<int32_t*>(my_slot + (DEG > 1 ? (b.w & 0xffff) : b.w)) = free_at;
         if (DEG > 1) *reinterpret_cast<int32_t*>(my_slot + ((unsigned)b.w >> 16)) = free_at;
         mem += a.y;
         peak = max(peak, mem);
-        mem -= a.z;
+        if (!SLIDE) mem -= a.z;   // (SLIDE: with split backward only W items free, and they do when they are placed)
+        if (SLIDE && pick_t == kGenB) {
+          // a B item stashes its W item: into the head word while nothing waits behind it, else into the tail
+          // word, which moves to the ring when it is full
+          if (s_rd == s_wr && t_n == 0u && h_n < kQCap) {
+            q_h |= (unsigned)pick_c << (h_n * kQBits);
+            ++h_n;
+            new_head();
+          } else {
+            q_t |= (unsigned)pick_c << (t_n * kQBits);
+            ++t_n;
+            if (t_n == kQCap) {
+              spill[(s_wr & (unsigned)(spill_words - 1)) * 64] = q_t;
+              ++s_wr;
+              q_t = 0u; t_n = 0u;
+            }
+          }
+        }
+      } else if (TIMED) {
+        // (SLIDE: a W item the scheduler placed is passed over)
       } else {
         const unsigned word = ((unsigned)(pick_t + 1) << 13) | ((unsigned)pick_c << 11) | (unsigned)j;
         // sixteen op words are collected in the lane's staging dwords and stored together
@@ -447,8 +537,8 @@ __global__ __launch_bounds__(TIMED ? kGenTimedThreads : 64) void generate_kernel
   }
 }
 
-#define FPSCHED_INSTANTIATE(V, G, TIMED)                                                                    \
-  template __global__ void generate_kernel<V, G, TIMED>(DevTables, const int32_t*, const int32_t*,           \
+#define FPSCHED_INSTANTIATE(V, G, FORM)                                                                     \
+  template __global__ void generate_kernel<V, G, FORM>(DevTables, const int32_t*, const int32_t*,            \
                                                         const long long*, long long, long long, int, uint16_t*, int32_t*, \
                                                         unsigned char*, unsigned long long*, GenResults);
 FPSCHED_INSTANTIATE(1, 1, false)
@@ -466,6 +556,12 @@ FPSCHED_INSTANTIATE(4, 1, true)
 FPSCHED_INSTANTIATE(1, 2, true)
 FPSCHED_INSTANTIATE(2, 2, true)
 FPSCHED_INSTANTIATE(4, 2, true)
+FPSCHED_INSTANTIATE(1, 1, kGenSlide)
+FPSCHED_INSTANTIATE(2, 1, kGenSlide)
+FPSCHED_INSTANTIATE(4, 1, kGenSlide)
+FPSCHED_INSTANTIATE(1, 2, kGenSlide)
+FPSCHED_INSTANTIATE(2, 2, kGenSlide)
+FPSCHED_INSTANTIATE(4, 2, kGenSlide)
 #undef FPSCHED_INSTANTIATE
 
 }  // namespace fpsched

@@ -81,7 +81,10 @@ struct GenResults {
   unsigned char* flags;
 };
 constexpr int kGenTimedThreads = 512;
-template <int V, int DEG, bool TIMED>
+// FORM: kGenPlain writes the lists; kGenTimed times them instead (above); kGenSlide times them after the
+// weight-gradient sliding pass (T.gen_spill_words dwords of LDS more per lane)
+constexpr int kGenPlain = 0, kGenTimed = 1, kGenSlide = 2;
+template <int V, int DEG, int FORM>
 __global__ void generate_kernel(DevTables T, const int32_t* policy, const int32_t* inflight, const long long* select,
                                 long long n_src, long long n_sets, int stride, uint16_t* ops, int32_t* out_steps,
                                 unsigned char* out_status, unsigned long long* next_set, GenResults R);

@@ -114,26 +114,31 @@ def tune(handle, problem, circular: bool, k: int = 8, inflight_options=None, for
     of dicts (label, makespan, index into the grid, slid).  The schedules are timed with whatever cost
     model the handle is set to (``set_microbatch_costs``, ``set_link_occupancy``); the sliding pass
     follows the link switch and refuses costs per micro-batch.  fused: one kernel generates and times the
-    schedules (plain cost model, no sliding pass; ``Problem.generate_evaluate``) and only the winners' rows
-    are written: the entries then carry them as ``ops`` (uint16 [D][stride])."""
+    schedules (plain cost model; ``Problem.generate_evaluate``, with ``slide`` a second launch that has the
+    sliding pass in it) and only the winners' rows are written: the entries then carry them as ``ops``
+    (uint16 [D][stride]; the slid list for entries with ``slid`` set)."""
     import torch
 
     labels, pol, inf = grid(problem, circular, inflight_options, forward_first)
     n = len(labels)
     stride = stride_for(problem)
     if fused:
-        if slide:
-            raise ValueError("the fused search has no sliding pass")
         d_pol, d_inf = torch.from_numpy(pol).cuda(), torch.from_numpy(inf).cuda()
         res, _ = handle.generate_evaluate(d_pol, d_inf)
+        if slide and problem.has_w:
+            slid, _ = handle.generate_evaluate(d_pol, d_inf, slide=True)
+            res = {name: torch.cat([res[name], slid[name]]) for name in ("makespan", "idle", "peak", "flags")}
         top = handle.topk(res, min(k, 1024))
-        rows = handle.generate_selected(d_pol, d_inf, top["idx"], stride)
         torch.cuda.synchronize()
         cnt = int(top["count"].item())
         idx, ms = top["idx"].cpu().numpy()[:cnt], top["makespan"].cpu().numpy()[:cnt]
-        ops = rows["ops"].cpu().numpy().view(np.uint16)
-        return [dict(label=labels[int(i)], makespan=int(t), index=int(i), slid=False, ops=ops[r])
-                for r, (i, t) in enumerate(zip(idx, ms))]
+        # the winners' rows as generated, and for entries ranked after the sliding pass their slid lists
+        rows = handle.generate_selected(d_pol, d_inf, torch.from_numpy(idx % n).cuda(), stride)["ops"]
+        ops = rows.cpu().numpy().view(np.uint16)
+        if (idx >= n).any():
+            ops = np.where((idx >= n)[:, None, None], handle.wslide(rows, stride)["ops"].cpu().numpy().view(np.uint16), ops)
+        return [dict(label=labels[int(i) % n] + (" +slide" if i >= n else ""), makespan=int(t), index=int(i) % n,
+                     slid=bool(i >= n), ops=ops[r]) for r, (i, t) in enumerate(zip(idx, ms))]
     out = handle.generate(torch.from_numpy(pol).cuda(), torch.from_numpy(inf).cuda(), stride)
     res = handle.evaluate(out["ops"])
     if slide and problem.has_w:

@@ -25,7 +25,7 @@ def test_library_loads_and_exports_every_declared_symbol():
             "fpsched_version", "fpsched_problem_info", "fpsched_generate",
             "fpsched_problem_select_kernel", "fpsched_rank", "fpsched_rank_workspace_bytes",
             "fpsched_pareto", "fpsched_pareto_workspace_bytes", "fpsched_apply_caps", "fpsched_wslide", "fpsched_wslide_workspace_bytes",
-            "fpsched_wslide_evaluate"} <= names
+            "fpsched_wslide_evaluate", "fpsched_generate_slide_evaluate"} <= names
     for n in names:
         assert hasattr(lib, n), n
     assert fp.version() == 100
@@ -45,9 +45,11 @@ def test_host_only_handle_and_errors():
     assert lib.fpsched_generate(p._h, 0, 0, 1, 1024, 0, 0, 0, 0, 0, 0) == -5
     assert lib.fpsched_generate_selected(p._h, 0, 0, 4, 1, 1, 1024, 0, 0, 0, 0, 0, 0) == -5
     assert lib.fpsched_generate_evaluate(p._h, 0, 0, 1, fp.binding._Results(0, 0, 0, 0), 0, 0, 0, 0, 0) == -5
+    assert lib.fpsched_generate_slide_evaluate(p._h, 0, 0, 1, fp.binding._Results(0, 0, 0, 0), 0, 0, 0, 0, 0) == -5
     assert lib.fpsched_generate_selected(p._h, 0, 0, -1, 1, 1, 1024, 0, 0, 0, 0, 0, 0) == -1   # a negative number of sets
     assert lib.fpsched_generate_selected(p._h, 0, 0, 4, 0, 1, 1024, 0, 0, 0, 0, 0, 0) == -1    # no selection given
     assert lib.fpsched_generate_evaluate(None, 0, 0, 1, fp.binding._Results(0, 0, 0, 0), 0, 0, 0, 0, 0) == -1
+    assert lib.fpsched_generate_slide_evaluate(None, 0, 0, 1, fp.binding._Results(0, 0, 0, 0), 0, 0, 0, 0, 0) == -1
     none = fp.binding._Results(0, 0, 0, 0)
     assert lib.fpsched_topk(p._h, none, 1, 1, 1, 1, 1, 0, 0, 0) == -5
     assert lib.fpsched_rank(p._h, none, 1, 1, 0, 0, 1, 1, 1, 0, 0, 0) == -5

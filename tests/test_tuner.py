@@ -88,6 +88,12 @@ def test_gpu_search_with_sliding_and_bidirectional_placement_matches_the_oracles
         assert cnt > 0 and [b["makespan"] for b in best] == list(top_ms[:cnt])
         assert [(b["index"], b["slid"]) for b in best] == [(int(i) % n, bool(i >= n)) for i in idx[:cnt]]
         assert all(b["label"].endswith(" +slide") == b["slid"] for b in best)
+        # the fused search with the sliding pass in the kernel finds the same entries and returns their lists
+        fused = tuner.tune(h, prob, circular, k=7, slide=True, fused=True)
+        assert [(b["index"], b["slid"], b["makespan"]) for b in fused] == [(b["index"], b["slid"], b["makespan"]) for b in best]
+        for b in fused:
+            want = slid["ops"][b["index"]] if b["slid"] else words[b["index"]]
+            assert np.array_equal(b["ops"], want), b["label"]
         h.close()
 
 
