@@ -126,12 +126,15 @@ def test_random_problems_sliding(seed):
 def test_random_problems_fused_generator(seed):
     # generator and evaluator in one kernel against the two oracles composed on the CPU
     from test_gpu_generate_evaluate import check as check_fused
+    from test_gpu_generate_slide import check_slide
     rng = np.random.default_rng(3000 + seed)
     for i in range(10):
         prob = random_problem(rng)
         n = 40
         pol, inf = random_policies(rng, n, prob, rng.random(n) < 0.5)
         check_fused(prob, pol, inf, f"seed {seed} problem {i}")
+        if prob.has_w:   # ... and with the sliding pass in the kernel
+            check_slide(prob, pol, inf, f"seed {seed} problem {i}, sliding")
 
 
 @pytest.mark.parametrize("seed", range(6))
