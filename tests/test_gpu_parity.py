@@ -385,6 +385,59 @@ def test_fused_search_step_replayed_from_a_hip_graph():
     h.close()
 
 
+def test_search_steps_with_the_sliding_pass_replayed_from_a_hip_graph():
+    # the one-kernel forms of the sliding pass -- inside the generator kernel, and on generated lists -- with top-k,
+    # the winners' rows and their slid lists, captured once and replayed on new parameter sets; every replay is
+    # checked against the generator oracle and the sliding oracle composed on the CPU
+    import torch
+
+    import paper_2510_05112_amd as fp
+    spec = workloads.config(2, 8)
+    prob, k, n = spec.problem, 5, 160
+    st = workloads.generator_stride(prob)
+    sets = [workloads.policy_sets(prob, n, seed=191 + i) for i in range(3)]
+    h = fp.Problem(prob, st, device=0)
+    d_pol, d_inf = torch.from_numpy(sets[0][0]).cuda(), torch.from_numpy(sets[0][1]).cuda()
+    ws = h.alloc_workspace(n, k)
+    res, out = h.generate_evaluate(d_pol, d_inf, workspace=ws, slide=True)     # eager once: allocates the outputs
+    top = h.topk(res, k, ws)
+    rows = h.generate_selected(d_pol, d_inf, top["idx"], st, workspace=ws)
+    slide_ws = torch.empty(int(fp.load_library().fpsched_wslide_workspace_bytes(h._h, k, st)), dtype=torch.uint8,
+                           device="cuda")
+    slid = h.wslide(rows["ops"], st, workspace=slide_ws)
+    gen = h.generate(d_pol, d_inf, st, workspace=ws)
+    again = h.wslide_evaluate(gen["ops"], workspace=ws)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        h.generate_evaluate(d_pol, d_inf, results=res, out=out, workspace=ws, slide=True)
+        h.topk(res, k, ws, top)
+        h.generate_selected(d_pol, d_inf, top["idx"], st, out=rows, workspace=ws)
+        h.wslide(rows["ops"], st, out=slid, workspace=slide_ws)
+        h.generate(d_pol, d_inf, st, out=gen, workspace=ws)
+        h.wslide_evaluate(gen["ops"], out=again, workspace=ws)
+    for pol, inf in sets[::-1] + sets:
+        d_pol.copy_(torch.from_numpy(pol))
+        d_inf.copy_(torch.from_numpy(inf))
+        res["flags"].fill_(255)       # eager work between the replays
+        again["flags"].fill_(255)
+        slid["ops"].zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        ref_gen = oracle.generate(prob, pol, inf, st, threads=2)
+        ref = oracle.wslide(prob, ref_gen["words"], st, threads=2)
+        for name in ("makespan", "idle", "peak", "flags"):
+            assert np.array_equal(res[name].cpu().numpy(), ref[name]), name
+            assert np.array_equal(again[name].cpu().numpy(), ref[name]), name
+        assert np.array_equal(out["steps"].cpu().numpy(), ref_gen["steps"])
+        idx, ms, cnt = oracle.topk(ref["makespan"], ref["flags"], k)
+        assert int(top["count"].item()) == cnt == k and np.array_equal(top["idx"].cpu().numpy(), idx)
+        assert np.array_equal(slid["ops"].cpu().numpy().view(np.uint16), ref["ops"][idx])
+        assert np.array_equal(slid["makespan"].cpu().numpy(), ref["makespan"][idx])
+    h.close()
+
+
 def test_copy_engine_evaluation_replayed_from_a_hip_graph():
     import torch
 
